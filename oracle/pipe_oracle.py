@@ -1,0 +1,422 @@
+"""CPU checker for the residual-expanded quantized layer (PIPE, arXiv 2311.15806).
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, step-by-step statement
+of what the HIP path must compute.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import it; the product never does, and this
+file imports nothing from the product.  It is written in numpy, in the paper's
+order and notation, with no blocking, fusion or packing.
+
+Arithmetic (fixed, because the method is an encoding whose integer codes depend
+on it): weights, scales and residuals are IEEE fp32 with round-to-nearest-even
+and no fused multiply-add; group scores are fp64; the contraction is exact
+integer arithmetic; the de-quantising epilogue is fp32 with an fp64 twin.
+
+Passages followed
+  * quantizer Q and de-quantizer Q^-1 ............ Sec. 3, Eq. (1)
+  * residual expansion R^1..R^K .................. Sec. 3.1, Eq. (2), (3)
+  * structured mask M^k, sparsity ratio gamma .... Sec. 3.1, masked Eq. after (4)
+  * expanded-layer forward ....................... App. B, Eq. (define_dre)
+  * ensemble members, bias in predictor 1 ........ Sec. 3.2, Fig. 2 caption,
+                                                   App. B "Ensemble of more Layers"
+  * operation head-count ......................... App. H
+
+Readings taken where the paper is silent (each is listed in the design notes):
+scale = row absmax / (2^(b-1)-1) and codes clamped to +-(2^(b-1)-1); ties round
+to even; an all-zero row has scale 0 and codes 0; R^1 is dense and orders k>=2
+keep the ceil(gamma*n_groups) groups of `group` consecutive output channels with
+the largest residual energy (sum of squares, fp64), re-selected at every order,
+ties to the lower group index; activations are per-tensor symmetric int8 with a
+static scale if given, else absmax/127; a member owns a contiguous range of
+orders in every layer and its own activation scale.
+
+Pins: every function here is checked in tests/test_oracle_pins.py against facts
+that do not come from this file (hand-worked example, exhaustive nearest-code
+search, the Lemma's bound, brute-force mask enumeration, torch integer matmul
+and conv2d, closed forms).  Not pinned by the paper (this build's reading only):
+the group-selection criterion and the member-wise treatment of gated MLPs.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+f32 = np.float32
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3, Eq. (1): Q(W) = round(W / s), Q^-1(q) = s * q   (per output channel)
+# ----------------------------------------------------------------------------
+def q_max(bits: int) -> int:
+    """Largest code magnitude 2^(b-1)-1 (the Lemma's constant): 127, 7, 1."""
+    if bits not in (8, 4, 2):
+        raise ValueError("bits must be 8, 4 or 2 (ternary)")
+    return 2 ** (bits - 1) - 1
+
+
+def quantize_rows(E: np.ndarray, bits: int):
+    """Row-wise symmetric quantizer.  E fp32 [R, I] -> (codes int8 [R, I], s fp32 [R]).
+
+    s[o] = max_i |E[o,i]| / q_max (fp32 division); q = clamp(rint(E / s), +-q_max),
+    rint rounds half to even.  A row whose scale is 0 gets codes 0."""
+    E = np.asarray(E, dtype=f32)
+    qm = f32(q_max(bits))
+    amax = np.max(np.abs(E), axis=1) if E.shape[1] else np.zeros(E.shape[0], f32)
+    s = (amax / qm).astype(f32)
+    live = s > 0
+    div = np.where(live, s, f32(1.0)).astype(f32)
+    q = np.rint(E / div[:, None])
+    q = np.clip(q, -qm, qm)
+    q[~live, :] = 0
+    return q.astype(np.int8), s
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1: structured mask M^k over groups of consecutive output channels
+# ----------------------------------------------------------------------------
+def n_keep(gamma: float, n_groups: int) -> int:
+    """Number of groups kept at an order k>=2: ceil(gamma * n_groups).
+
+    gamma is first rounded to fp32 (the boundary passes a C float); the factor
+    (1 - 1e-6) keeps an exactly integral product from being pushed up by that
+    rounding."""
+    g = float(f32(gamma))
+    if not (0.0 < g <= 1.0):
+        raise ValueError("gamma must lie in (0, 1]")
+    return max(1, min(n_groups, math.ceil(g * n_groups * (1.0 - 1e-6))))
+
+
+def group_scores(E: np.ndarray, group: int) -> np.ndarray:
+    """Residual energy per group: sum over the group's rows and all columns of
+    E^2, accumulated in fp64 (each square of an fp32 value is exact in fp64)."""
+    E64 = np.asarray(E, dtype=np.float64)
+    row = np.sum(E64 * E64, axis=1)
+    return row.reshape(-1, group).sum(axis=1)
+
+
+def select_groups(scores: np.ndarray, keep: int) -> np.ndarray:
+    """Indices (ascending) of the `keep` highest scores; ties go to the lower index."""
+    n = scores.shape[0]
+    order = sorted(range(n), key=lambda g: (-float(scores[g]), g))
+    return np.array(sorted(order[:keep]), dtype=np.int32)
+
+
+def selection_gap(scores: np.ndarray, keep: int) -> float:
+    """Relative gap between the last kept and the first dropped score (inf if none
+    is dropped).  Input generators use it to reject near-ties, where the order of
+    an fp64 summation could decide the mask."""
+    n = scores.shape[0]
+    if keep >= n:
+        return math.inf
+    srt = np.sort(scores)[::-1]
+    a, b = float(srt[keep - 1]), float(srt[keep])
+    return (a - b) / a if a > 0 else 0.0
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1, Eq. (2)-(3) and the masked form: R^k = M^k Q^-1(Q(W - sum_{j<k} R^j))
+# ----------------------------------------------------------------------------
+@dataclass
+class Order:
+    """One term R^k of the expansion, stored compactly over its kept groups."""
+    group_ids: np.ndarray    # int32 [n_kept], ascending
+    scales: np.ndarray       # fp32  [n_kept*group]   (lambda_{R^k}, row-wise)
+    codes: np.ndarray        # int8  [n_kept*group, I]
+
+
+@dataclass
+class Expansion:
+    out_features: int
+    in_features: int
+    bits: int
+    K: int
+    gamma: float
+    group: int
+    orders: List[Order]
+
+    def rows(self, k: int) -> np.ndarray:
+        """Output-channel index of every stored row of order k (1-based k)."""
+        o = self.orders[k - 1]
+        return (o.group_ids[:, None].astype(np.int64) * self.group
+                + np.arange(self.group)[None, :]).reshape(-1)
+
+    def dense_codes(self, k: int) -> np.ndarray:
+        """int8 [O, I]; pruned rows are 0."""
+        q = np.zeros((self.out_features, self.in_features), dtype=np.int8)
+        q[self.rows(k)] = self.orders[k - 1].codes
+        return q
+
+    def dense_scales(self, k: int) -> np.ndarray:
+        """fp32 [O]; pruned rows are 0."""
+        s = np.zeros(self.out_features, dtype=f32)
+        s[self.rows(k)] = self.orders[k - 1].scales
+        return s
+
+    def reconstruct(self, upto: Optional[int] = None) -> np.ndarray:
+        """sum_{k<=upto} R^k in fp64 (for error measurements only)."""
+        upto = self.K if upto is None else upto
+        R = np.zeros((self.out_features, self.in_features), dtype=np.float64)
+        for k in range(1, upto + 1):
+            R += self.dense_scales(k).astype(np.float64)[:, None] * self.dense_codes(k)
+        return R
+
+
+def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
+           residuals: Optional[list] = None) -> Expansion:
+    """Residual expansion of W [O, I] to order K.
+
+    E_1 = W.  For k = 1..K: (k>=2 and gamma<1: keep the top n_keep groups of E_k
+    by energy, else all groups); on kept rows s_k, q_k = quantize_rows(E_k) and
+    E_{k+1} = E_k - s_k*q_k (fp32 multiply, then fp32 subtract); pruned rows pass
+    their residual on unchanged.  If `residuals` is a list, E_2..E_{K+1} are
+    appended to it (copies)."""
+    W = np.asarray(W, dtype=f32)
+    if W.ndim != 2:
+        raise ValueError("W must be [out, in]")
+    O, I = W.shape
+    if K < 1 or group < 1 or O % group:
+        raise ValueError("need K >= 1 and out % group == 0")
+    q_max(bits)
+    n_g = O // group
+    keep = n_keep(gamma, n_g)
+    E = W.copy()
+    orders: List[Order] = []
+    for k in range(1, K + 1):
+        if k == 1 or keep == n_g:
+            gids = np.arange(n_g, dtype=np.int32)
+        else:
+            gids = select_groups(group_scores(E, group), keep)
+        rows = (gids[:, None].astype(np.int64) * group + np.arange(group)[None, :]).reshape(-1)
+        q, s = quantize_rows(E[rows], bits)
+        Rk = (s[:, None] * q.astype(f32)).astype(f32)      # Q^-1(Q(.)), one rounding
+        E[rows] = (E[rows] - Rk).astype(f32)               # second rounding, no FMA
+        orders.append(Order(gids, s, q))
+        if residuals is not None:
+            residuals.append(E.copy())
+    return Expansion(O, I, bits, K, float(f32(gamma)), group, orders)
+
+
+# ----------------------------------------------------------------------------
+# App. B, Eq. (define_dre): f(x) = sigma( sum_k R^(k) Q(x) lambda_{R^(k)} lambda_x + b )
+# ----------------------------------------------------------------------------
+def quantize_activations(x: np.ndarray, s_x: Optional[float] = None):
+    """Per-tensor symmetric int8.  s_x > 0: static scale; None or <= 0: max|x|/127.
+    Returns (Qx int8 same shape, s_x fp32).  s_x == 0 (all-zero input) gives Qx = 0."""
+    x = np.asarray(x, dtype=f32)
+    if s_x is None or not (s_x > 0):
+        amax = np.max(np.abs(x)) if x.size else f32(0)
+        s = f32(f32(amax) / f32(127.0))
+    else:
+        s = f32(s_x)
+    if not (s > 0):
+        return np.zeros(x.shape, np.int8), f32(0)
+    q = np.clip(np.rint(x / s), -127, 127)
+    return q.astype(np.int8), s
+
+
+def contract(Qx: np.ndarray, codes: np.ndarray) -> np.ndarray:
+    """acc[t, r] = sum_i Qx[t,i] * codes[r,i], exact, returned as int32.
+
+    The products are formed and summed by an fp64 matmul: every operand is an
+    integer of magnitude <= 127 and every partial sum is an integer below
+    127*127*I < 2^53, so each fp64 operation is exact whatever the order."""
+    I = Qx.shape[1]
+    if 127 * 127 * max(I, 1) >= 2 ** 31:
+        raise ValueError("accumulator would not fit int32")
+    a = Qx.astype(np.float64) @ codes.astype(np.float64).T
+    return a.astype(np.int64).astype(np.int32)
+
+
+def forward_acc(exp: Expansion, Qx: np.ndarray) -> np.ndarray:
+    """int32 [K, T, O]: acc_k[t,o] = sum_i Qx[t,i] q_k[o,i]; pruned rows are 0."""
+    T = Qx.shape[0]
+    acc = np.zeros((exp.K, T, exp.out_features), dtype=np.int32)
+    for k in range(1, exp.K + 1):
+        acc[k - 1][:, exp.rows(k)] = contract(Qx, exp.orders[k - 1].codes)
+    return acc
+
+
+def member_ranges(K: int, split: Optional[Sequence[int]]):
+    """[K_1..K_M] -> list of 1-based inclusive order ranges; None means one member."""
+    if split is None:
+        split = [K]
+    if len(split) < 1 or any(int(s) < 1 for s in split) or sum(int(s) for s in split) != K:
+        raise ValueError("split must be positive and sum to K")
+    out, lo = [], 1
+    for s in split:
+        out.append((lo, lo + int(s) - 1))
+        lo += int(s)
+    return out
+
+
+def dequantize(exp: Expansion, acc: np.ndarray, s_x, split=None, bias=None, dtype=f32):
+    """Members' outputs [M, T, O]: y_m = s_x * sum_{k in m, ascending} s_k[o]*acc_k[t,o]
+    (+ b[o] for the first member only), evaluated in `dtype`."""
+    rngs = member_ranges(exp.K, split)
+    T = acc.shape[1]
+    ys = np.zeros((len(rngs), T, exp.out_features), dtype=dtype)
+    for m, (lo, hi) in enumerate(rngs):
+        tot = np.zeros((T, exp.out_features), dtype=dtype)
+        for k in range(lo, hi + 1):
+            term = exp.dense_scales(k).astype(dtype)[None, :] * acc[k - 1].astype(dtype)
+            tot = (tot + term).astype(dtype)
+        ym = (dtype(s_x) * tot).astype(dtype)
+        if m == 0 and bias is not None:
+            ym = (ym + np.asarray(bias).astype(dtype)[None, :]).astype(dtype)
+        ys[m] = ym
+    return ys
+
+
+def sum_members(ys: np.ndarray) -> np.ndarray:
+    """Ensemble output: members added in ascending order, in the array's dtype."""
+    y = ys[0].copy()
+    for m in range(1, ys.shape[0]):
+        y = (y + ys[m]).astype(ys.dtype)
+    return y
+
+
+def forward(exp: Expansion, x: np.ndarray, s_x: Optional[float] = None, split=None,
+            bias=None, reduce_members: bool = True):
+    """Expanded linear layer on x [T, I].  Returns a dict with Qx, s_x, acc (int32
+    [K,T,O]), y (fp32; [T,O] if reduce_members else [M,T,O]) and y64 (fp64 twin)."""
+    Qx, sx = quantize_activations(x, s_x)
+    acc = forward_acc(exp, Qx)
+    ys = dequantize(exp, acc, sx, split, bias, f32)
+    ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
+    if reduce_members:
+        return dict(Qx=Qx, s_x=sx, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
+    return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
+
+
+# ----------------------------------------------------------------------------
+# Convolution (App. H treats conv and fully-connected layers uniformly)
+# ----------------------------------------------------------------------------
+def conv_out_size(H, W, kh, kw, stride, pad):
+    return (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+
+
+def conv2d_acc_direct(Qx: np.ndarray, codes: np.ndarray, kh: int, kw: int,
+                      stride: int, pad: int) -> np.ndarray:
+    """Direct integer convolution.  Qx int8 [N,C,H,W] (zero padded), codes int8
+    [R, C*kh*kw] with a row flattened as [C, kh, kw].  Returns int32 [N*Ho*Wo, R]
+    with tokens ordered (n, ho, wo).  One accumulation per kernel tap (r, s)."""
+    N, C, H, W = Qx.shape
+    R = codes.shape[0]
+    Ho, Wo = conv_out_size(H, W, kh, kw, stride, pad)
+    xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=np.int64)
+    xp[:, :, pad:pad + H, pad:pad + W] = Qx
+    w = codes.astype(np.int64).reshape(R, C, kh, kw)
+    acc = np.zeros((N, Ho, Wo, R), dtype=np.int64)
+    for r in range(kh):
+        for s in range(kw):
+            patch = xp[:, :, r:r + stride * Ho:stride, s:s + stride * Wo:stride]   # [N,C,Ho,Wo]
+            acc += np.einsum("nchw,oc->nhwo", patch, w[:, :, r, s])
+    return acc.reshape(N * Ho * Wo, R).astype(np.int32)
+
+
+def im2col(Q: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.ndarray:
+    """[N,C,H,W] -> [N*Ho*Wo, C*kh*kw], column index (c, r, s), zero padding."""
+    N, C, H, W = Q.shape
+    Ho, Wo = conv_out_size(H, W, kh, kw, stride, pad)
+    xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=Q.dtype)
+    xp[:, :, pad:pad + H, pad:pad + W] = Q
+    cols = np.zeros((N, Ho, Wo, C, kh, kw), dtype=Q.dtype)
+    for r in range(kh):
+        for s in range(kw):
+            cols[:, :, :, :, r, s] = xp[:, :, r:r + stride * Ho:stride,
+                                        s:s + stride * Wo:stride].transpose(0, 2, 3, 1)
+    return cols.reshape(N * Ho * Wo, C * kh * kw)
+
+
+def forward_conv2d(exp: Expansion, x: np.ndarray, kh, kw, stride, pad,
+                   s_x: Optional[float] = None, split=None, bias=None,
+                   reduce_members: bool = True):
+    """Expanded conv layer on x [N,C,H,W] fp32; output rows are tokens (n, ho, wo),
+    i.e. y is [N*Ho*Wo, O] (channels last)."""
+    Qx, sx = quantize_activations(x, s_x)
+    T = Qx.shape[0] * np.prod(conv_out_size(x.shape[2], x.shape[3], kh, kw, stride, pad))
+    acc = np.zeros((exp.K, int(T), exp.out_features), dtype=np.int32)
+    for k in range(1, exp.K + 1):
+        acc[k - 1][:, exp.rows(k)] = conv2d_acc_direct(Qx, exp.orders[k - 1].codes,
+                                                        kh, kw, stride, pad)
+    ys = dequantize(exp, acc, sx, split, bias, f32)
+    ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
+    if reduce_members:
+        return dict(Qx=Qx, s_x=sx, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
+    return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.2 / App. B: ensemble of M predictors over a two-layer MLP
+# ----------------------------------------------------------------------------
+def gelu(v: np.ndarray) -> np.ndarray:
+    """erf-form GELU of fp32 values, evaluated in fp64 and rounded once to fp32."""
+    from scipy.special import erf
+    v64 = np.asarray(v, dtype=np.float64)
+    return (0.5 * v64 * (1.0 + erf(v64 / math.sqrt(2.0)))).astype(f32)
+
+
+def silu_mul(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """SiLU(gate) * up of fp32 values, evaluated in fp64 and rounded once to fp32."""
+    g = np.asarray(gate, dtype=np.float64)
+    return (g / (1.0 + np.exp(-g)) * np.asarray(up, dtype=np.float64)).astype(f32)
+
+
+def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, split=None,
+                bias1=None, bias2=None, s_x: Optional[float] = None):
+    """Two expanded layers with an activation between, run as an ensemble.
+
+    Member m uses only its own orders in BOTH layers, quantizes its own hidden
+    activation with its own dynamic scale, and carries the biases only if m is the
+    first member; the members' outputs are summed after the last layer.
+    kind = "gelu": h = GELU(layer1(x));  kind = "gated": layer1 has 2H outputs
+    (gate rows first, then up rows) and h = SiLU(gate) * up.
+    Returns dict(y fp32 [T,O2], members [M,T,O2], h [M,T,H], s_h [M])."""
+    if exp1.K != exp2.K:
+        raise ValueError("both layers need the same expansion order")
+    rngs = member_ranges(exp1.K, split)
+    Qx, sx = quantize_activations(x, s_x)
+    acc1 = forward_acc(exp1, Qx)
+    y1 = dequantize(exp1, acc1, sx, split, bias1, f32)          # [M, T, O1]
+    hs, shs, outs = [], [], []
+    for m, (lo, hi) in enumerate(rngs):
+        if kind == "gelu":
+            h = gelu(y1[m])
+        elif kind == "gated":
+            H = exp1.out_features // 2
+            h = silu_mul(y1[m][:, :H], y1[m][:, H:])
+        else:
+            raise ValueError("kind must be 'gelu' or 'gated'")
+        Qh, sh = quantize_activations(h)
+        acc2 = forward_acc(exp2, Qh)
+        # this member's orders only; bias of layer 2 only in the first member
+        y2 = dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m]
+        hs.append(h); shs.append(sh); outs.append(y2)
+    members = np.stack(outs)
+    return dict(y=sum_members(members), members=members, h=np.stack(hs),
+                s_h=np.array(shs, dtype=f32), y1=y1, s_x=sx, Qx=Qx)
+
+
+# ----------------------------------------------------------------------------
+# App. H: operation head-count
+# ----------------------------------------------------------------------------
+def bit_operations(D: int, d: int, n_i: int, n_o: int, s: int, b: int, k: int):
+    """Bit-operation counts (original layer, quantized layer, expansion with k
+    b-bit terms) for a d x d conv on D x D x n_i maps, n_o outputs, stride s; a
+    fully-connected layer has D = d = s = 1.  log is taken base 2."""
+    fp = 32 * math.log2(32)
+    ib = b * math.log2(b)
+    mults = d * d * n_i * n_o / (s * s)
+    original = D * D * mults * fp
+    rescale = (n_i + n_o / (s * s)) * fp
+    quantized = D * D * (rescale + mults * ib)
+    expanded = D * D * (rescale + k * mults * ib)
+    return original, quantized, expanded
+
+
+def expansion_macs(exp: Expansion, T: int) -> int:
+    """Integer multiply-accumulates one forward over T tokens performs: T * I *
+    (number of stored rows over all orders)."""
+    return int(T) * exp.in_features * sum(o.codes.shape[0] for o in exp.orders)

@@ -1,0 +1,368 @@
+"""Pins for the CPU checker: every check here rests on something other than the
+checker's own formulas -- a hand-worked example, an exhaustive search, the
+paper's bounds, brute-force enumeration, or an independent library routine."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pipe_oracle as po
+from paper_2311_15806_amd import workloads as wl
+
+f32 = np.float32
+
+
+def _rand_w(seed, O, I, heavy=False):
+    rng = np.random.default_rng(seed)
+    if heavy:
+        return (rng.standard_t(3, size=(O, I)) * 0.015).astype(f32)
+    return (rng.standard_normal((O, I)) * 0.02).astype(f32)
+
+
+# ---------------------------------------------------------------- hand-worked example
+def test_hand_worked_example(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "hand_worked.json")))
+    for name in ("ternary", "int4"):
+        c = g[name]
+        W = np.array(c["W"], dtype=f32)
+        res = []
+        e = po.expand(W, c["bits"], c["K"], 1.0, 1, residuals=res)
+        for k in range(c["K"]):
+            assert e.orders[k].codes.tolist() == c["codes"][k], (name, k)
+            assert e.orders[k].scales.tolist() == c["scales"][k], (name, k)
+            assert res[k].tolist() == c["residual_after"][k], (name, k)
+    c = g["ternary"]
+    e = po.expand(np.array(c["W"], dtype=f32), 2, 3, 1.0, 1)
+    r = po.forward(e, np.array(c["x"], dtype=f32), s_x=c["s_x_static"])
+    assert r["Qx"].tolist() == c["Qx"]
+    assert r["acc"].tolist() == c["acc"]
+    assert r["y"].tolist() == c["y"]
+    d = g["dynamic_activation"]
+    Qx, sx = po.quantize_activations(np.array(d["x"], dtype=f32))
+    assert Qx.tolist() == d["Qx"]
+    assert sx == f32(2.0) / f32(127.0)
+
+
+# ---------------------------------------------------------------- Eq. (1): K = 1 is plain quantization
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_k1_is_nearest_code_by_exhaustive_search(bits):
+    """For every element the code must be the integer in [-q_max, q_max] whose
+    de-quantized value is nearest (searched exhaustively, no rounding formula),
+    the row's largest element must sit on +-q_max, and the error is <= s/2."""
+    W = _rand_w(bits, 6, 40, heavy=True)
+    e = po.expand(W, bits, 1, 1.0, 1)
+    q, s = e.orders[0].codes, e.orders[0].scales
+    qm = 2 ** (bits - 1) - 1
+    cand = np.arange(-qm, qm + 1)
+    for o in range(W.shape[0]):
+        j = np.argmax(np.abs(W[o]))
+        assert abs(int(q[o, j])) == qm
+        assert math.isclose(float(s[o]) * qm, float(abs(W[o, j])), rel_tol=1e-6)
+        for i in range(W.shape[1]):
+            d = np.abs(float(W[o, i]) - float(s[o]) * cand)
+            best = d.min()
+            got = abs(float(W[o, i]) - float(s[o]) * int(q[o, i]))
+            assert got <= best * (1 + 1e-5) + 1e-12
+            assert got <= float(s[o]) / 2 * (1 + 1e-5)
+
+
+def test_zero_row_and_zero_matrix():
+    W = _rand_w(1, 4, 8)
+    W[2] = 0
+    e = po.expand(W, 4, 3, 1.0, 1)
+    for o in e.orders:
+        assert o.scales[2] == 0 and not o.codes[2].any()
+    e0 = po.expand(np.zeros((4, 8), f32), 2, 2, 0.5, 2)
+    assert all(not o.codes.any() and not o.scales.any() for o in e0.orders)
+    # exact ties in the scores go to the lower group index
+    assert e0.orders[1].group_ids.tolist() == [0]
+
+
+# ---------------------------------------------------------------- Lemma (exponential convergence)
+@pytest.mark.parametrize("bits,K", [(8, 3), (4, 4), (2, 6)])
+def test_lemma_bound_dense(bits, K):
+    """Per element: |w - sum_k w^(k)| <= s_K/2, scales shrink by >= 2*q_max per
+    order, hence the Lemma's bound (1/q_max)^(K-1) * s_1 / 2; the error norm
+    never grows with the order."""
+    W = _rand_w(10 + bits, 32, 96, heavy=True)
+    qm = 2 ** (bits - 1) - 1
+    res = []
+    e = po.expand(W, bits, K, 1.0, 8, residuals=res)
+    eps = 1 + 4 * 2.0 ** -23
+    # the fp32 product s*q rounds once per order: at most 2^-24 of the row's largest weight
+    ulp = np.abs(W.astype(np.float64)).max(axis=1, keepdims=True) * 2.0 ** -23
+    prev_norm = np.linalg.norm(W.astype(np.float64))
+    prev_rowmax = np.abs(W.astype(np.float64)).max(axis=1)
+    for k in range(1, K + 1):
+        s_k = e.orders[k - 1].scales.astype(np.float64)
+        err = np.abs(W.astype(np.float64) - e.reconstruct(k))
+        assert np.all(err <= (s_k[:, None] / 2) * eps + k * ulp)
+        s1 = e.orders[0].scales.astype(np.float64)
+        assert np.all(err <= ((1.0 / qm) ** (k - 1)) * (s1[:, None] / 2) * eps + k * ulp)
+        if k > 1:
+            s_prev = e.orders[k - 2].scales.astype(np.float64)
+            assert np.all(s_k <= s_prev / (2 * qm) * eps)
+        # the tracked fp32 residual is the true error up to fp32 rounding
+        assert np.allclose(res[k - 1], W.astype(np.float64) - e.reconstruct(k),
+                           rtol=0, atol=float(np.abs(W).max()) * 2.0 ** -21)
+        norm = np.linalg.norm(err)
+        assert norm <= prev_norm
+        prev_norm = norm
+        # row-wise infinity norm of the error shrinks by 2*q_max = 2^b - 2 per order
+        rowmax = err.max(axis=1)
+        assert np.all(rowmax <= prev_rowmax / (2 * qm) * (1 + 1e-5) + k * ulp[:, 0])
+        prev_rowmax = rowmax
+
+
+# ---------------------------------------------------------------- masks
+@pytest.mark.parametrize("bits", [4, 2])
+def test_gamma_one_equals_dense(bits):
+    W = _rand_w(20, 48, 64)
+    a = po.expand(W, bits, 3, 1.0, 16)
+    b = po.expand(W, bits, 3, 1.0, 4)        # grouping is irrelevant when nothing is pruned
+    for k in range(3):
+        assert a.orders[k].group_ids.tolist() == list(range(3))
+        assert np.array_equal(a.dense_codes(k + 1), b.dense_codes(k + 1))
+        assert np.array_equal(a.dense_scales(k + 1), b.dense_scales(k + 1))
+    # and order-by-order it is the plain quantizer applied to the running residual
+    E = W.copy()
+    for k in range(3):
+        q, s = po.quantize_rows(E, bits)
+        assert np.array_equal(q, a.orders[k].codes)
+        E = (E - (s[:, None] * q.astype(f32))).astype(f32)
+
+
+def test_sparse_expansion_structure():
+    W = _rand_w(21, 64, 80, heavy=True)
+    G, gamma, K, bits = 8, 0.5, 4, 4
+    res = []
+    e = po.expand(W, bits, K, gamma, G, residuals=res)
+    assert e.orders[0].group_ids.tolist() == list(range(8))        # R^1 is dense
+    prev = res[0]
+    for k in range(2, K + 1):
+        gids = e.orders[k - 1].group_ids
+        assert len(gids) == 4 and len(set(gids.tolist())) == 4
+        assert list(gids) == sorted(gids)
+        kept = e.rows(k)
+        pruned = np.setdiff1d(np.arange(64), kept)
+        # pruned rows hand their residual on bit-for-bit; kept rows obey |e| <= s/2
+        assert np.array_equal(res[k - 1][pruned], prev[pruned])
+        s = e.orders[k - 1].scales
+        assert np.all(np.abs(res[k - 1][kept]) <= s[:, None] / 2 * (1 + 1e-6) + 1e-30)
+        prev = res[k - 1]
+    # the sparse expansion never does worse than stopping at order 1 and never
+    # better than the dense one of the same order
+    d = po.expand(W, bits, K, 1.0, G)
+    err = lambda ex: np.linalg.norm(W - ex.reconstruct())
+    assert err(d) <= err(e) <= np.linalg.norm(W - e.reconstruct(1))
+
+
+def test_mask_is_energy_optimal_by_enumeration():
+    """Tiny layers: enumerate every mask with n_keep groups; the chosen one removes
+    the most residual energy (energy computed here from the residual itself)."""
+    for seed, (O, G, gamma) in enumerate([(8, 2, 0.5), (6, 1, 0.34), (8, 2, 0.25), (10, 2, 0.6)]):
+        W = _rand_w(30 + seed, O, 12, heavy=True)
+        res = []
+        e = po.expand(W, 4, 2, gamma, G, residuals=res)
+        n_g = O // G
+        keep = math.ceil(gamma * n_g - 1e-9)
+        assert len(e.orders[1].group_ids) == keep == po.n_keep(gamma, n_g)
+        E2 = (W.astype(np.float64) - e.reconstruct(1))
+        energy = [float((E2[g * G:(g + 1) * G] ** 2).sum()) for g in range(n_g)]
+        best = max(itertools.combinations(range(n_g), keep), key=lambda c: sum(energy[g] for g in c))
+        assert sorted(best) == e.orders[1].group_ids.tolist()
+
+
+def test_n_keep_rounding():
+    assert po.n_keep(0.25, 172) == 43 and po.n_keep(0.5, 344) == 172
+    assert po.n_keep(0.5, 16) == 8 and po.n_keep(0.5, 96) == 48 and po.n_keep(0.5, 24) == 12
+    assert po.n_keep(0.3, 10) == 3 and po.n_keep(0.31, 10) == 4 and po.n_keep(1.0, 7) == 7
+    assert po.n_keep(0.01, 10) == 1
+
+
+# ---------------------------------------------------------------- integer contraction
+def test_contraction_against_torch_int64_and_loops():
+    rng = np.random.default_rng(40)
+    Qx = rng.integers(-127, 128, size=(7, 333), dtype=np.int8)
+    q = rng.integers(-127, 128, size=(11, 333), dtype=np.int8)
+    got = po.contract(Qx, q)
+    ref = (torch.from_numpy(Qx).to(torch.int64) @ torch.from_numpy(q).to(torch.int64).T).numpy()
+    assert got.dtype == np.int32 and np.array_equal(got, ref)
+    for t, r in [(0, 0), (3, 5), (6, 10)]:
+        assert int(got[t, r]) == sum(int(Qx[t, i]) * int(q[r, i]) for i in range(333))
+    ones = po.contract(np.ones((2, 500), np.int8), np.ones((3, 500), np.int8))
+    assert np.all(ones == 500)
+    # worst case magnitude at the largest in_features of the configs stays exact
+    big = po.contract(np.full((1, 11008), 127, np.int8), np.full((1, 11008), -127, np.int8))
+    assert int(big[0, 0]) == -127 * 127 * 11008
+
+
+def test_k1_forward_is_textbook_quantized_linear():
+    """One int8 order: y = s_x * s_w[o] * sum_i Qx*Qw, recomputed with Python ints."""
+    W = _rand_w(41, 5, 24)
+    x = np.random.default_rng(42).standard_normal((3, 24)).astype(f32)
+    e = po.expand(W, 8, 1, 1.0, 1)
+    r = po.forward(e, x)
+    sx = float(np.abs(x).max() / f32(127))
+    for t in range(3):
+        for o in range(5):
+            sw = float(np.abs(W[o]).max() / f32(127))
+            acc = sum(int(round(float(x[t, i]) / sx)) * int(round(float(W[o, i]) / sw)) for i in range(24))
+            assert int(r["acc"][0, t, o]) == acc
+            assert math.isclose(float(r["y"][t, o]), sx * sw * acc, rel_tol=1e-5, abs_tol=1e-7)
+
+
+def test_forward_converges_to_full_precision_weights():
+    """int8, K = 4, dense: the expansion reproduces W to ~(1/254)^3, so the output
+    equals s_x * Qx W^T (fp64) down to fp32 resolution; lower orders converge at
+    the Lemma's rate."""
+    W = _rand_w(43, 24, 128)
+    x = np.random.default_rng(44).standard_normal((9, 128)).astype(f32)
+    prev = None
+    for K in (1, 2, 3, 4):
+        e = po.expand(W, 8, K, 1.0, 8)
+        r = po.forward(e, x)
+        target = float(r["s_x"]) * (r["Qx"].astype(np.float64) @ W.astype(np.float64).T)
+        err = np.abs(r["y64"] - target).max() / np.abs(target).max()
+        if prev is not None:
+            # geometric decrease until the fp32 rounding of the residuals (~2^-24) is reached
+            assert err < max(prev / 50, 2e-7)
+        prev = err
+    assert prev < 2e-7
+    assert np.abs(r["y"] - target).max() <= 1e-5 * np.abs(target).max()
+
+
+# ---------------------------------------------------------------- ensemble members (Sec. 3.2)
+def test_single_layer_ensemble_is_exact_partition():
+    W = _rand_w(50, 32, 64, heavy=True)
+    x = np.random.default_rng(51).standard_normal((5, 64)).astype(f32)
+    b = np.random.default_rng(52).standard_normal(32).astype(f32)
+    e = po.expand(W, 4, 4, 0.5, 8)
+    full = po.forward(e, x, bias=b)
+    for split in ([2, 2], [1, 3], [1, 1, 2], [1, 1, 1, 1]):
+        ens = po.forward(e, x, split=split, bias=b)
+        assert np.array_equal(ens["acc"], full["acc"])          # accumulators ignore the split
+        assert np.allclose(ens["y64"], full["y64"], rtol=1e-12, atol=1e-12)   # linearity
+        assert np.allclose(ens["y"], full["y"], rtol=1e-5, atol=1e-6)
+        mem = po.forward(e, x, split=split, bias=b, reduce_members=False)
+        assert mem["y"].shape == (len(split), 5, 32)
+    with pytest.raises(ValueError):
+        po.forward(e, x, split=[2, 1])
+
+
+def test_bias_only_in_first_member():
+    W = _rand_w(53, 16, 32)
+    x = np.random.default_rng(54).standard_normal((4, 32)).astype(f32)
+    b = np.arange(16, dtype=f32)
+    e = po.expand(W, 4, 2, 1.0, 4)
+    with_b = po.forward(e, x, split=[1, 1], bias=b, reduce_members=False)["y"]
+    no_b = po.forward(e, x, split=[1, 1], reduce_members=False)["y"]
+    assert np.allclose(with_b[0] - no_b[0], b[None, :], atol=1e-5)
+    assert np.array_equal(with_b[1], no_b[1])
+    # a member whose weights are all zero outputs exactly 0, bias or not
+    z = po.expand(np.zeros((16, 32), f32), 4, 2, 1.0, 4)
+    out = po.forward(z, x, split=[1, 1], bias=b, reduce_members=False)["y"]
+    assert np.array_equal(out[0], np.broadcast_to(b, (4, 16))) and not out[1].any()
+
+
+# ---------------------------------------------------------------- convolution
+def test_conv_direct_equals_im2col_and_torch():
+    rng = np.random.default_rng(60)
+    for (N, C, H, Wd, O, kh, kw, stride, pad) in [(2, 3, 6, 5, 4, 3, 3, 1, 1), (1, 2, 7, 7, 3, 3, 2, 2, 0)]:
+        Qx = rng.integers(-127, 128, size=(N, C, H, Wd), dtype=np.int8)
+        q = rng.integers(-7, 8, size=(O, C * kh * kw), dtype=np.int8)
+        direct = po.conv2d_acc_direct(Qx, q, kh, kw, stride, pad)
+        gemm = po.contract(po.im2col(Qx, kh, kw, stride, pad), q)
+        assert np.array_equal(direct, gemm)
+        ref = torch.nn.functional.conv2d(torch.from_numpy(Qx).double(),
+                                         torch.from_numpy(q).double().reshape(O, C, kh, kw),
+                                         stride=stride, padding=pad)
+        ref = ref.permute(0, 2, 3, 1).reshape(-1, O).numpy()
+        assert np.array_equal(direct.astype(np.float64), ref)
+
+
+def test_conv_forward_matches_linear_on_im2col():
+    w = wl.scaled(wl.C2, out_div=8, in_div=32, tokens=196)
+    spec, c = w.layers[0], w.conv
+    W, x = wl.make_weight(w, 0), wl.make_input(w)
+    e = po.expand(W, spec.bits, spec.K, spec.gamma, spec.group)
+    conv = po.forward_conv2d(e, x, c["kh"], c["kw"], c["stride"], c["pad"], split=list(w.split))
+    cols = po.im2col(x, c["kh"], c["kw"], c["stride"], c["pad"])
+    lin = po.forward(e, cols, split=list(w.split))
+    assert np.array_equal(conv["acc"], lin["acc"]) and np.array_equal(conv["y"], lin["y"])
+
+
+# ---------------------------------------------------------------- MLP ensemble
+def test_mlp_single_member_is_plain_composition():
+    rng = np.random.default_rng(70)
+    W1, W2 = _rand_w(71, 32, 24), _rand_w(72, 8, 32)
+    x = rng.standard_normal((6, 24)).astype(f32)
+    e1, e2 = po.expand(W1, 4, 2, 1.0, 8), po.expand(W2, 4, 2, 1.0, 8)
+    out = po.mlp_forward(e1, e2, "gelu", x)
+    h = po.forward(e1, x)["y"]
+    # GELU pinned to torch's erf form (independent library routine)
+    g = torch.nn.functional.gelu(torch.from_numpy(h).double()).numpy()
+    assert np.allclose(out["h"][0], g, rtol=1e-6, atol=1e-7)
+    y = po.forward(e2, out["h"][0])["y"]
+    assert np.array_equal(out["y"], y)
+    # gated: SiLU pinned to torch
+    W1g = _rand_w(73, 64, 24)
+    e1g = po.expand(W1g, 4, 2, 1.0, 8)
+    og = po.mlp_forward(e1g, e2, "gated", x)
+    y1 = po.forward(e1g, x)["y"]
+    hg = (torch.nn.functional.silu(torch.from_numpy(y1[:, :32]).double())
+          * torch.from_numpy(y1[:, 32:]).double()).numpy()
+    assert np.allclose(og["h"][0], hg, rtol=1e-6, atol=1e-8)
+
+
+def test_mlp_ensemble_members_use_only_their_orders():
+    """Member 2 of split [1,1] must equal a network built from R^2 alone, without
+    biases; with a ReLU-like regime (large positive pre-activations) the ensemble
+    approaches the full expansion as the paper's approximation states."""
+    rng = np.random.default_rng(74)
+    W1, W2 = _rand_w(75, 32, 24), _rand_w(76, 8, 32)
+    x = rng.standard_normal((6, 24)).astype(f32)
+    b1 = rng.standard_normal(32).astype(f32)
+    e1, e2 = po.expand(W1, 4, 2, 1.0, 8), po.expand(W2, 4, 2, 1.0, 8)
+    out = po.mlp_forward(e1, e2, "gelu", x, split=[1, 1], bias1=b1)
+    # rebuild member 2 by hand from the order-2 terms only
+    Qx, sx = po.quantize_activations(x)
+    y1 = f32(sx) * (e1.dense_scales(2)[None, :] * po.contract(Qx, e1.dense_codes(2)).astype(f32))
+    h = po.gelu(y1)
+    Qh, sh = po.quantize_activations(h)
+    y2 = f32(sh) * (e2.dense_scales(2)[None, :] * po.contract(Qh, e2.dense_codes(2)).astype(f32))
+    assert np.allclose(out["members"][1], y2, rtol=1e-6, atol=1e-9)
+    assert np.array_equal(out["y"], (out["members"][0] + out["members"][1]).astype(f32))
+    full = po.mlp_forward(e1, e2, "gelu", x, bias1=b1)["y"]
+    assert np.abs(out["y"] - full).max() < 0.15 * np.abs(full).max()
+
+
+# ---------------------------------------------------------------- App. H
+def test_operation_head_count_closed_form():
+    o, q, e = po.bit_operations(D=1, d=1, n_i=4096, n_o=11008, s=1, b=4, k=3)
+    assert o == 4096 * 11008 * 32 * 5
+    assert q == (4096 + 11008) * 160 + 4096 * 11008 * 8
+    assert e - q == 2 * 4096 * 11008 * 8
+    o2, q2, _ = po.bit_operations(D=14, d=3, n_i=256, n_o=256, s=1, b=8, k=1)
+    assert o2 == 14 * 14 * 9 * 256 * 256 * 160 and q2 == 196 * (512 * 160 + 9 * 65536 * 24)
+    # MAC counter against T*I*O*(1+(K-1)*gamma)
+    ex = po.expand(_rand_w(80, 64, 32), 4, 3, 0.5, 8)
+    assert po.expansion_macs(ex, 10) == 10 * 32 * 64 * 2
+
+
+# ---------------------------------------------------------------- generator sanity for the configs
+def test_workload_shapes_and_seeding():
+    for cfg, w in wl.WORKLOADS.items():
+        for l in w.layers:
+            assert l.out_features % l.group == 0
+            assert sum(w.split) == l.K
+    a = wl.make_weight(wl.C1, 0)
+    b = wl.make_weight(wl.C1, 0)
+    assert a.dtype == f32 and a.shape == (256, 256) and np.array_equal(a, b)
+    assert abs(float(a.std()) - 0.02) < 1e-3
+    x = wl.make_input(wl.scaled(wl.C2, 8, 32, 196))
+    assert x.min() == 0.0 and x.shape == (1, 8, 14, 14)
