@@ -1,0 +1,143 @@
+/*
+ * pipe.h -- C ABI of the residual-expanded quantized layer (PIPE, arXiv 2311.15806)
+ *           for AMD MI355X (gfx950).
+ *
+ * The library computes, for one layer with weights W [out, in],
+ *
+ *      y = lambda_x * sum_{k=1..K} lambda_{R^k} (.) ( R^k Q(x) )  (+ b)
+ *
+ * where R^1 = Q(W), R^k = M^k Q(W - sum_{j<k} R^j) are low-bit integer residual
+ * terms (Sec. 3.1, Eq. (2)-(3) and the masked form), Q is the symmetric
+ * per-output-channel quantizer of Sec. 3 Eq. (1), M^k keeps a fraction gamma of
+ * the groups of consecutive output channels at orders k >= 2 (structured mask,
+ * Sec. 3.1), and the K terms may be clustered into M ensemble members
+ * [K_1..K_M] whose outputs are summed after the last layer (Sec. 3.2, Fig. 2).
+ * The forward formula is App. B, Eq. (define_dre).
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory on the current HIP device, owned
+ *     by the caller; every other pointer is HOST memory owned by the caller.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     forward calls are asynchronous on that stream.  pipe_expand and the
+ *     introspection calls synchronize the stream before they return.
+ *   - Matrices are row-major and dense; no strides.
+ *   - Every function returns PIPE_OK (0) or a negative error code and never
+ *     throws or aborts.  On an error detected before launch (bad argument,
+ *     shape or split) no output is written.
+ *   - The library keeps a per-process device workspace (quantized activations,
+ *     hidden activations of the MLP call) that grows on demand; calls that share
+ *     a device must not overlap in time (one stream at a time).
+ *   - bits: 8 (int8), 4 (int4, codes in [-7,7]) or 2 (ternary, codes in {-1,0,1}).
+ */
+#ifndef PIPE_H_
+#define PIPE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pipe_expansion pipe_expansion; /* opaque, owned by the library */
+
+enum {
+  PIPE_OK = 0,
+  PIPE_EINVAL = -1,  /* NULL pointer, bits/K/gamma/group out of range            */
+  PIPE_ESHAPE = -2,  /* out % group != 0, group % 16 != 0, sizes <= 0, overflow   */
+  PIPE_ENOMEM = -3,  /* device or host allocation failed                         */
+  PIPE_EDEVICE = -4, /* a HIP call failed (see pipe_last_device_error)           */
+  PIPE_ESPLIT = -5   /* split entries not positive or not summing to K            */
+};
+
+enum { PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2 };
+
+/* Build the expansion (R^1..R^K) of W (Sec. 3.1, Eq. (2)-(3); mask: masked Eq.).
+ *   W_dev   [out, in] fp32, read only.
+ *   bits    8, 4 or 2.          K >= 1 (at most 16).
+ *   gamma   in (0,1]: fraction of channel groups KEPT at every order k >= 2
+ *           (n_keep = ceil(gamma * out/group)); R^1 is always dense.
+ *   group   output channels per group; out % group == 0 and group % 16 == 0.
+ * Arithmetic: per row s = max|e| / (2^(bits-1)-1) (fp32 division), code =
+ * clamp(rint(e / s)), rint = round half to even; residual e - s*code with a
+ * rounded product and a rounded difference (no FMA); group score = sum of
+ * squares of the residual in fp64, highest kept, ties to the lower group.
+ * The result owns device memory (packed codes, scales, group indices, tile
+ * schedules) until pipe_expansion_free.  *exp_out is written only on success. */
+int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                int group, void* stream, pipe_expansion** exp_out);
+
+int pipe_expansion_free(pipe_expansion* e);
+
+/* Shape query; any output pointer may be NULL.  packed_bytes = bytes of packed
+ * codes + scales + group indices the forward pass streams from HBM. */
+int pipe_expansion_info(const pipe_expansion* e, int* out, int* in, int* bits, int* K,
+                        int* group, float* gamma, int64_t* packed_bytes);
+
+/* Introspection of order k (1-based): copies to HOST buffers (each may be NULL).
+ *   n_groups_kept  number of groups stored at this order
+ *   group_ids      [n_groups_kept] ascending
+ *   scales         [n_groups_kept*group]      lambda_{R^k}, row-wise (Eq. (1))
+ *   codes_unpacked [n_groups_kept*group, in]  signed codes, one per byte        */
+int pipe_expansion_order(const pipe_expansion* e, int k, int* n_groups_kept,
+                         int32_t* group_ids, float* scales, int8_t* codes_unpacked);
+
+/* Expanded layer forward (App. B, Eq. (define_dre); members: Sec. 3.2).
+ *   x_dev  [T, in] fp32.        T >= 0 (T == 0 is a no-op).
+ *   s_x    > 0: static per-tensor activation scale; <= 0: dynamic max|x|/127.
+ *          Q(x) = clamp(rint(x / s_x), -127, 127).
+ *   split  HOST [M], positive, sum == K; NULL (then M is ignored) = one member.
+ *   bias_dev NULL or [out]; added to the first member only (Fig. 2 caption).
+ *   reduce_members  1: y_dev [T, out] = sum over members (ascending);
+ *                   0: y_dev [M, T, out], one slab per member.
+ * Per member: y_m = s_x * sum_{k in member, ascending} s_k[o] * float(acc_k[t,o]) (+b),
+ * acc_k the exact int32 contraction.                                           */
+int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, float s_x,
+                 const int* split, int M, const float* bias_dev, int reduce_members,
+                 float* y_dev, void* stream);
+
+/* Debug twin of pipe_forward: exports the integer state for bit-exact checks.
+ *   acc_dev     [K, T, out] int32, rows pruned at order k are 0 (may be NULL)
+ *   qx_dev      [T, in] int8 Q(x), row-major                   (may be NULL)
+ *   s_x_out_dev one float: the activation scale used           (may be NULL)  */
+int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
+                     int32_t* acc_dev, int8_t* qx_dev, float* s_x_out_dev, void* stream);
+
+/* Expanded convolution as a GEMM over output pixels (App. H treats conv and FC
+ * alike).  The expansion was built from W [out, C*kh*kw], a row flattened as
+ * [C, kh, kw].  x_dev is [N,C,H,W] (nhwc == 0) or [N,H,W,C] (nhwc != 0), zero
+ * padded by `pad`.  Tokens are output pixels ordered (n, ho, wo):
+ * y_dev is [N*Ho*Wo, out] (channels last), or [M, N*Ho*Wo, out].
+ * Remaining arguments as pipe_forward.                                        */
+int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,
+                        int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
+                        const int* split, int M, const float* bias_dev,
+                        int reduce_members, float* y_dev, void* stream);
+
+/* Two expanded layers with an activation between, run as an ensemble of M
+ * members (Sec. 3.2; App. B "Ensemble of more Layers"): member m uses only its
+ * own orders in both layers, quantizes its own hidden activation with its own
+ * dynamic scale, carries the biases only if it is the first member, and the
+ * members' outputs are summed after the second layer.
+ *   act = PIPE_ACT_GELU:       l1 [H, in],  h = GELU_erf(l1(x))
+ *   act = PIPE_ACT_SILU_GATED: l1 [2H, in] (gate rows, then up rows),
+ *                              h = SiLU(gate) * up
+ *   l2 [out, H]; both layers have the same K.  y_dev [T, out].
+ *   h_dev  NULL, or [M, T, H] fp32 to receive the hidden activations.          */
+int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                     const float* x_dev, int T, float s_x, const int* split, int M,
+                     const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                     float* y_dev, void* stream);
+
+/* Kernel selection for pipe_forward / pipe_mlp_forward (tuning and tests):
+ * 0 = automatic by token count, 1 = tiled MFMA kernel, 2 = weight-streaming
+ * small-batch kernel.  Returns PIPE_EINVAL for other values.                    */
+int pipe_set_kernel(int which);
+
+const char* pipe_strerror(int code);
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char* pipe_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPE_H_ */

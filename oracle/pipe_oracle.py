@@ -164,14 +164,15 @@ class Expansion:
 
 
 def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
-           residuals: Optional[list] = None) -> Expansion:
+           residuals: Optional[list] = None, gaps: Optional[list] = None) -> Expansion:
     """Residual expansion of W [O, I] to order K.
 
     E_1 = W.  For k = 1..K: (k>=2 and gamma<1: keep the top n_keep groups of E_k
     by energy, else all groups); on kept rows s_k, q_k = quantize_rows(E_k) and
     E_{k+1} = E_k - s_k*q_k (fp32 multiply, then fp32 subtract); pruned rows pass
     their residual on unchanged.  If `residuals` is a list, E_2..E_{K+1} are
-    appended to it (copies)."""
+    appended to it (copies); if `gaps` is a list, the selection_gap of every mask
+    that was chosen is appended to it."""
     W = np.asarray(W, dtype=f32)
     if W.ndim != 2:
         raise ValueError("W must be [out, in]")
@@ -187,7 +188,10 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
         if k == 1 or keep == n_g:
             gids = np.arange(n_g, dtype=np.int32)
         else:
-            gids = select_groups(group_scores(E, group), keep)
+            scores = group_scores(E, group)
+            gids = select_groups(scores, keep)
+            if gaps is not None:
+                gaps.append(selection_gap(scores, keep))
         rows = (gids[:, None].astype(np.int64) * group + np.arange(group)[None, :]).reshape(-1)
         q, s = quantize_rows(E[rows], bits)
         Rk = (s[:, None] * q.astype(f32)).astype(f32)      # Q^-1(Q(.)), one rounding

@@ -1,0 +1,20 @@
+"""MI355X-native residual-expanded quantized layer (PIPE, arXiv 2311.15806).
+
+`workloads` (seeded synthetic inputs) imports without the HIP library;
+everything else comes from `binding`, which needs libpipe_hip.so and raises if
+it is missing.
+"""
+from . import workloads  # noqa: F401
+
+_BINDING_NAMES = (
+    "Expansion", "PipeError", "pipe_expand", "pipe_expansion_order", "pipe_forward", "pipe_forward_acc",
+    "pipe_forward_conv2d", "pipe_mlp_forward", "pipe_set_kernel", "PIPE_ACT_GELU", "PIPE_ACT_SILU_GATED",
+)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES or name == "binding":
+        import importlib
+        b = importlib.import_module(__name__ + ".binding")
+        return b if name == "binding" else getattr(b, name)
+    raise AttributeError(name)

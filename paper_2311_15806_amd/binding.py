@@ -1,0 +1,215 @@
+"""Thin ctypes binding over libpipe_hip.so: argument marshalling only.
+
+Function names and argument order follow include/pipe.h.  Tensors are torch CUDA
+(ROCm) tensors used as device memory; every step of the method runs inside the
+library's HIP kernels.  There is no CPU fallback: importing this module without
+the built library raises, and so does any call that returns an error code.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipe_hip.so")
+
+PIPE_ACT_GELU = 1
+PIPE_ACT_SILU_GATED = 2
+
+
+class PipeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib.pipe_strerror(code).decode()
+        dev = _lib.pipe_last_device_error().decode()
+        super().__init__("%s failed: %s (%d)%s" % (where, msg, code, (" [" + dev + "]") if dev and code == -4 else ""))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libpipe_hip.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or python paper_2311_15806_amd/build.py); there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, ci, cf = C.c_void_p, C.c_int, C.c_float
+    pi = C.POINTER(C.c_int)
+    lib.pipe_expand.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
+    lib.pipe_expansion_free.argtypes = [vp]
+    lib.pipe_expansion_info.argtypes = [vp, pi, pi, pi, pi, pi, C.POINTER(cf), C.POINTER(C.c_int64)]
+    lib.pipe_expansion_order.argtypes = [vp, ci, pi, vp, vp, vp]
+    lib.pipe_forward.argtypes = [vp, vp, ci, cf, pi, ci, vp, ci, vp, vp]
+    lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
+    lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
+    lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
+    lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_strerror.argtypes = [ci]
+    lib.pipe_strerror.restype = C.c_char_p
+    lib.pipe_last_device_error.restype = C.c_char_p
+    for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
+              "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
+              "pipe_set_kernel"):
+        getattr(lib, f).restype = ci
+    return lib
+
+
+_lib = _load()
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise PipeError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _split(split: Optional[Sequence[int]]):
+    if split is None:
+        return None, 0
+    arr = (C.c_int * len(split))(*[int(s) for s in split])
+    return arr, len(split)
+
+
+class Expansion:
+    """Owner of a pipe_expansion handle."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+        o, i, b, k, g = (C.c_int() for _ in range(5))
+        gm, pb = C.c_float(), C.c_int64()
+        _check(_lib.pipe_expansion_info(self._h, o, i, b, k, g, gm, pb), "pipe_expansion_info")
+        self.out_features, self.in_features, self.bits, self.K, self.group = o.value, i.value, b.value, k.value, g.value
+        self.gamma, self.packed_bytes = gm.value, pb.value
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("expansion already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            _check(_lib.pipe_expansion_free(self._h), "pipe_expansion_free")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    def order(self, k: int, codes: bool = True):
+        """(group_ids int32 [n], scales fp32 [n*group], codes int8 [n*group, in]) as numpy."""
+        return pipe_expansion_order(self, k, codes)
+
+    def macs_per_token(self) -> int:
+        """Integer multiply-accumulates per token: in * (stored rows over all orders)."""
+        rows = 0
+        for k in range(1, self.K + 1):
+            n = C.c_int()
+            _check(_lib.pipe_expansion_order(self.handle, k, n, None, None, None), "pipe_expansion_order")
+            rows += n.value * self.group
+        return rows * self.in_features
+
+
+def pipe_expand(W: torch.Tensor, bits: int, K: int, gamma: float, group: int) -> Expansion:
+    if W.dim() != 2:
+        raise ValueError("W must be [out, in]")
+    h = C.c_void_p()
+    _check(_lib.pipe_expand(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(bits), int(K),
+                            float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand")
+    return Expansion(h.value)
+
+
+def pipe_expansion_order(e: Expansion, k: int, codes: bool = True):
+    n = C.c_int()
+    _check(_lib.pipe_expansion_order(e.handle, k, n, None, None, None), "pipe_expansion_order")
+    rows = n.value * e.group
+    gids = np.empty(n.value, dtype=np.int32)
+    scales = np.empty(rows, dtype=np.float32)
+    cds = np.empty((rows, e.in_features), dtype=np.int8) if codes else None
+    _check(_lib.pipe_expansion_order(e.handle, k, n, gids.ctypes.data, scales.ctypes.data,
+                                     cds.ctypes.data if codes else None), "pipe_expansion_order")
+    return gids, scales, cds
+
+
+def pipe_forward(e: Expansion, x: torch.Tensor, s_x: float = 0.0, split=None, bias=None,
+                 reduce_members: bool = True, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != e.in_features:
+        raise ValueError("x must be [T, in]")
+    M = 1 if split is None else len(split)
+    shape = (T, e.out_features) if reduce_members else (M, T, e.out_features)
+    y = out if out is not None else torch.empty(shape, dtype=torch.float32, device=x.device)
+    if tuple(y.shape) != shape:
+        raise ValueError("output has the wrong shape")
+    arr, m = _split(split)
+    _check(_lib.pipe_forward(e.handle, _ptr(x, torch.float32), T, float(s_x), arr, m,
+                             _ptr(bias, torch.float32), 1 if reduce_members else 0,
+                             _ptr(y, torch.float32), _stream()), "pipe_forward")
+    return y
+
+
+def pipe_forward_acc(e: Expansion, x: torch.Tensor, s_x: float = 0.0):
+    """Returns (acc int32 [K,T,out], Qx int8 [T,in], s_x fp32 [1]) device tensors."""
+    T = x.shape[0]
+    acc = torch.empty((e.K, T, e.out_features), dtype=torch.int32, device=x.device)
+    qx = torch.empty((T, e.in_features), dtype=torch.int8, device=x.device)
+    sx = torch.zeros(1, dtype=torch.float32, device=x.device)
+    _check(_lib.pipe_forward_acc(e.handle, _ptr(x, torch.float32), T, float(s_x), _ptr(acc), _ptr(qx),
+                                 _ptr(sx), _stream()), "pipe_forward_acc")
+    return acc, qx, sx
+
+
+def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
+                        nhwc: bool = False, s_x: float = 0.0, split=None, bias=None,
+                        reduce_members: bool = True) -> torch.Tensor:
+    if x.dim() != 4:
+        raise ValueError("x must be 4-D")
+    if nhwc:
+        N, H, W, Cc = x.shape
+    else:
+        N, Cc, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    T = N * Ho * Wo
+    M = 1 if split is None else len(split)
+    shape = (T, e.out_features) if reduce_members else (M, T, e.out_features)
+    y = torch.empty(shape, dtype=torch.float32, device=x.device)
+    arr, m = _split(split)
+    _check(_lib.pipe_forward_conv2d(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
+                                    1 if nhwc else 0, float(s_x), arr, m, _ptr(bias, torch.float32),
+                                    1 if reduce_members else 0, _ptr(y), _stream()), "pipe_forward_conv2d")
+    return y
+
+
+def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_x: float = 0.0,
+                     split=None, bias1=None, bias2=None, return_hidden: bool = False,
+                     out: Optional[torch.Tensor] = None):
+    T = x.shape[0]
+    M = 1 if split is None else len(split)
+    y = out if out is not None else torch.empty((T, l2.out_features), dtype=torch.float32, device=x.device)
+    h = torch.empty((M, T, l2.in_features), dtype=torch.float32, device=x.device) if return_hidden else None
+    arr, m = _split(split)
+    _check(_lib.pipe_mlp_forward(l1.handle, l2.handle, int(act), _ptr(x, torch.float32), T, float(s_x),
+                                 arr, m, _ptr(bias1, torch.float32), _ptr(bias2, torch.float32),
+                                 _ptr(h), _ptr(y), _stream()), "pipe_mlp_forward")
+    return (y, h) if return_hidden else y
+
+
+def pipe_set_kernel(which: int) -> None:
+    _check(_lib.pipe_set_kernel(int(which)), "pipe_set_kernel")

@@ -1,0 +1,489 @@
+// C ABI of the PIPE library: argument checks, expansion object life cycle, tile schedule,
+// workspace and the launch sequences of the forward calls.  All arithmetic of the method
+// runs in the kernels of the other files; the host only validates, sizes and schedules.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "pipe_internal.h"
+
+// ------------------------------------------------------------------ errors
+static thread_local std::string g_last_hip_error;
+
+void pipe_note_hip_error(hipError_t e, const char* what) {
+  g_last_hip_error = std::string(hipGetErrorString(e)) + " in " + what;
+}
+
+extern "C" const char* pipe_last_device_error(void) { return g_last_hip_error.c_str(); }
+
+extern "C" const char* pipe_strerror(int code) {
+  switch (code) {
+    case PIPE_OK: return "ok";
+    case PIPE_EINVAL: return "invalid argument (NULL pointer or bits/K/gamma/group out of range)";
+    case PIPE_ESHAPE: return "invalid shape (out % group != 0, group % 16 != 0, size <= 0 or too large)";
+    case PIPE_ENOMEM: return "out of memory";
+    case PIPE_EDEVICE: return "HIP call failed";
+    case PIPE_ESPLIT: return "ensemble split must be positive and sum to K";
+    default: return "unknown error";
+  }
+}
+
+// ------------------------------------------------------------------ workspace
+static PipeWorkspace g_ws[WS_SLOTS];
+
+void* pipe_ws_get(int slot, size_t bytes) {
+  PipeWorkspace& w = g_ws[slot];
+  if (bytes == 0) bytes = 256;
+  if (w.bytes >= bytes) return w.ptr;
+  if (w.ptr) {
+    if (hipDeviceSynchronize() != hipSuccess) return nullptr;
+    (void)hipFree(w.ptr);
+    w.ptr = nullptr;
+    w.bytes = 0;
+  }
+  const size_t want = (size_t)round_up64((int64_t)bytes, 1 << 20);
+  hipError_t e = hipMalloc(&w.ptr, want);
+  if (e != hipSuccess) {
+    pipe_note_hip_error(e, "hipMalloc(workspace)");
+    w.ptr = nullptr;
+    return nullptr;
+  }
+  w.bytes = want;
+  return w.ptr;
+}
+
+static int g_kernel_choice = 0;
+extern "C" int pipe_set_kernel(int which) {
+  if (which < 0 || which > 2) return PIPE_EINVAL;
+  g_kernel_choice = which;
+  return PIPE_OK;
+}
+
+// ------------------------------------------------------------------ helpers
+static int n_keep_of(float gamma, int n_groups) {
+  const double v = (double)gamma * (double)n_groups * (1.0 - 1e-6);
+  int k = (int)std::ceil(v);
+  if (k < 1) k = 1;
+  if (k > n_groups) k = n_groups;
+  return k;
+}
+
+static int parse_split(int K, const int* split, int M, int* lo, int* hi, int* M_out) {
+  if (split == nullptr) {
+    lo[0] = 0;
+    hi[0] = K - 1;
+    *M_out = 1;
+    return PIPE_OK;
+  }
+  if (M < 1 || M > K) return PIPE_ESPLIT;
+  int pos = 0;
+  for (int m = 0; m < M; ++m) {
+    if (split[m] < 1) return PIPE_ESPLIT;
+    lo[m] = pos;
+    pos += split[m];
+    hi[m] = pos - 1;
+    if (pos > K) return PIPE_ESPLIT;
+  }
+  if (pos != K) return PIPE_ESPLIT;
+  *M_out = M;
+  return PIPE_OK;
+}
+
+static void free_expansion(pipe_expansion* e) {
+  if (!e) return;
+  for (auto& o : e->orders) {
+    if (o.gids_dev) (void)hipFree(o.gids_dev);
+    if (o.scales_dev) (void)hipFree(o.scales_dev);
+    if (o.packed_dev) (void)hipFree(o.packed_dev);
+  }
+  if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
+  if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
+  if (e->packed_ptrs_dev) (void)hipFree((void*)e->packed_ptrs_dev);
+  if (e->scale_ptrs_dev) (void)hipFree((void*)e->scale_ptrs_dev);
+  delete e;
+}
+
+// Sort row blocks by the set of orders that hold them (most orders first) and cut the sorted
+// list into column tiles of NRB_TILE row blocks.
+static int build_schedule(pipe_expansion* e) {
+  const int K = e->K, n_rb = e->n_rb, rbpg = e->rbpg;
+  std::vector<std::vector<int32_t>> slot_of(K, std::vector<int32_t>(e->n_groups, -1));
+  for (int k = 0; k < K; ++k)
+    for (int s = 0; s < (int)e->orders[k].gids.size(); ++s) slot_of[k][e->orders[k].gids[s]] = s;
+  struct Item { uint32_t mask; int pop; int rb; };
+  std::vector<Item> items(n_rb);
+  for (int rb = 0; rb < n_rb; ++rb) {
+    const int g = rb / rbpg;
+    uint32_t mask = 0;
+    for (int k = 0; k < K; ++k)
+      if (slot_of[k][g] >= 0) mask |= 1u << k;
+    items[rb] = Item{mask, __builtin_popcount(mask), rb};
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) {
+    if (a.pop != b.pop) return a.pop > b.pop;
+    if (a.mask != b.mask) return a.mask < b.mask;
+    return a.rb < b.rb;
+  });
+  e->n_ct = ceil_div(n_rb, NRB_TILE);
+  std::vector<int32_t> rb_out((size_t)e->n_ct * NRB_TILE, -1);
+  std::vector<int32_t> src((size_t)e->n_ct * K * NRB_TILE, -1);
+  for (int i = 0; i < n_rb; ++i) {
+    const int ct = i / NRB_TILE, r = i % NRB_TILE, rb = items[i].rb;
+    const int g = rb / rbpg, b = rb % rbpg;
+    rb_out[(size_t)ct * NRB_TILE + r] = rb;
+    for (int k = 0; k < K; ++k)
+      if (slot_of[k][g] >= 0) src[((size_t)ct * K + k) * NRB_TILE + r] = slot_of[k][g] * rbpg + b;
+  }
+  PIPE_HIP(hipMalloc(&e->ct_rb_out_dev, rb_out.size() * 4));
+  PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
+  PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));
+  PIPE_HIP(hipMemcpy(e->ct_src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice));
+  std::vector<const uint8_t*> pp(K);
+  std::vector<const float*> sp(K);
+  for (int k = 0; k < K; ++k) { pp[k] = e->orders[k].packed_dev; sp[k] = e->orders[k].scales_dev; }
+  PIPE_HIP(hipMalloc((void**)&e->packed_ptrs_dev, K * sizeof(void*)));
+  PIPE_HIP(hipMalloc((void**)&e->scale_ptrs_dev, K * sizeof(void*)));
+  PIPE_HIP(hipMemcpy((void*)e->packed_ptrs_dev, pp.data(), K * sizeof(void*), hipMemcpyHostToDevice));
+  PIPE_HIP(hipMemcpy((void*)e->scale_ptrs_dev, sp.data(), K * sizeof(void*), hipMemcpyHostToDevice));
+  return PIPE_OK;
+}
+
+static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, float** resid_out,
+                       double** energy_out) {
+  const int out = e->out, in = e->in, K = e->K, group = e->group;
+  const int n_groups = e->n_groups;
+  const int keep = n_keep_of(e->gamma, n_groups);
+  float* E = nullptr;
+  PIPE_HIP(hipMalloc(&E, (size_t)out * in * sizeof(float)));
+  *resid_out = E;
+  PIPE_HIP(hipMemcpyAsync(E, W_dev, (size_t)out * in * sizeof(float), hipMemcpyDeviceToDevice, st));
+  double* energy = nullptr;
+  PIPE_HIP(hipMalloc(&energy, ((size_t)out + n_groups) * sizeof(double) + (size_t)n_groups * sizeof(int32_t)));
+  *energy_out = energy;
+  const int ksup = 512 / e->bits;
+  e->orders.resize(K);
+  std::vector<int32_t> iota(n_groups);
+  for (int g = 0; g < n_groups; ++g) iota[g] = g;
+  for (int k = 0; k < K; ++k) {
+    PipeOrder& o = e->orders[k];
+    const bool dense = (k == 0) || keep == n_groups;
+    o.n_kept = dense ? n_groups : keep;
+    const size_t rows = (size_t)o.n_kept * group;
+    o.packed_bytes = (rows / 16) * (size_t)(e->in_pad / ksup) * 1024;
+    PIPE_HIP(hipMalloc(&o.gids_dev, (size_t)o.n_kept * sizeof(int32_t)));
+    PIPE_HIP(hipMalloc(&o.scales_dev, rows * sizeof(float)));
+    PIPE_HIP(hipMalloc(&o.packed_dev, o.packed_bytes));
+    if (dense) {
+      PIPE_HIP(hipMemcpyAsync(o.gids_dev, iota.data(), (size_t)n_groups * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    } else {
+      int rc = launch_row_energy(E, out, in, energy, st);
+      if (rc) return rc;
+      rc = launch_group_select(energy, n_groups, group, keep, o.gids_dev, st);
+      if (rc) return rc;
+    }
+    int rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, group, o.gids_dev, o.n_kept, o.scales_dev,
+                                  o.packed_dev, st);
+    if (rc) return rc;
+    e->stream_bytes += (int64_t)o.packed_bytes + (int64_t)rows * 4 + (int64_t)o.n_kept * 4;
+  }
+  PIPE_HIP(hipStreamSynchronize(st));
+  for (int k = 0; k < K; ++k) {
+    PipeOrder& o = e->orders[k];
+    o.gids.resize(o.n_kept);
+    PIPE_HIP(hipMemcpy(o.gids.data(), o.gids_dev, (size_t)o.n_kept * sizeof(int32_t), hipMemcpyDeviceToHost));
+  }
+  return build_schedule(e);
+}
+
+extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                           int group, void* stream, pipe_expansion** exp_out) {
+  if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;
+  if (bits != 8 && bits != 4 && bits != 2) return PIPE_EINVAL;
+  if (K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
+  if (!(gamma > 0.f) || !(gamma <= 1.f)) return PIPE_EINVAL;
+  if (out <= 0 || in <= 0 || group <= 0) return PIPE_ESHAPE;
+  if (out % group != 0 || group % 16 != 0) return PIPE_ESHAPE;
+  // int32 accumulator of offset-binary codes: 127 * 15 * in_pad and 127 * 127 * in must fit
+  if ((int64_t)in > (int64_t)130000) return PIPE_ESHAPE;
+  pipe_expansion* e = new (std::nothrow) pipe_expansion();
+  if (!e) return PIPE_ENOMEM;
+  e->out = out; e->in = in; e->bits = bits; e->K = K; e->group = group; e->gamma = gamma;
+  e->n_groups = out / group;
+  e->rbpg = group / 16;
+  e->n_rb = out / 16;
+  e->in_pad = (int)round_up64(in, IN_PAD);
+  e->nks = e->in_pad / 64;
+  if (hipGetDevice(&e->device) != hipSuccess) { delete e; return PIPE_EDEVICE; }
+  float* resid = nullptr;
+  double* energy = nullptr;
+  int rc = expand_impl(e, W_dev, (hipStream_t)stream, &resid, &energy);
+  if (rc != PIPE_OK) (void)hipDeviceSynchronize();
+  if (resid) (void)hipFree(resid);
+  if (energy) (void)hipFree(energy);
+  if (rc != PIPE_OK) {
+    if (rc == PIPE_EDEVICE && g_last_hip_error.find("out of memory") != std::string::npos) rc = PIPE_ENOMEM;
+    free_expansion(e);
+    return rc;
+  }
+  *exp_out = e;
+  return PIPE_OK;
+}
+
+extern "C" int pipe_expansion_free(pipe_expansion* e) {
+  if (!e) return PIPE_OK;
+  (void)hipDeviceSynchronize();
+  free_expansion(e);
+  return PIPE_OK;
+}
+
+extern "C" int pipe_expansion_info(const pipe_expansion* e, int* out, int* in, int* bits, int* K,
+                                   int* group, float* gamma, int64_t* packed_bytes) {
+  if (!e) return PIPE_EINVAL;
+  if (out) *out = e->out;
+  if (in) *in = e->in;
+  if (bits) *bits = e->bits;
+  if (K) *K = e->K;
+  if (group) *group = e->group;
+  if (gamma) *gamma = e->gamma;
+  if (packed_bytes) *packed_bytes = e->stream_bytes;
+  return PIPE_OK;
+}
+
+extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_groups_kept,
+                                    int32_t* group_ids, float* scales, int8_t* codes_unpacked) {
+  if (!e || k < 1 || k > e->K) return PIPE_EINVAL;
+  const PipeOrder& o = e->orders[k - 1];
+  if (n_groups_kept) *n_groups_kept = o.n_kept;
+  if (group_ids) std::memcpy(group_ids, o.gids.data(), (size_t)o.n_kept * sizeof(int32_t));
+  const size_t rows = (size_t)o.n_kept * e->group;
+  PIPE_HIP(hipDeviceSynchronize());
+  if (scales) PIPE_HIP(hipMemcpy(scales, o.scales_dev, rows * sizeof(float), hipMemcpyDeviceToHost));
+  if (codes_unpacked && rows) {
+    int8_t* tmp = nullptr;
+    PIPE_HIP(hipMalloc(&tmp, rows * (size_t)e->in));
+    int rc = launch_unpack_codes(o.packed_dev, e->bits, (int)rows, e->in, e->in_pad, tmp, nullptr);
+    if (rc == PIPE_OK) {
+      hipError_t he = hipMemcpy(codes_unpacked, tmp, rows * (size_t)e->in, hipMemcpyDeviceToHost);
+      if (he != hipSuccess) { pipe_note_hip_error(he, "hipMemcpy(codes)"); rc = PIPE_EDEVICE; }
+    }
+    (void)hipFree(tmp);
+    if (rc) return rc;
+  }
+  return PIPE_OK;
+}
+
+// ------------------------------------------------------------------ forward
+static bool use_stream_kernel(int T) {
+  if (true) return false;  // the streaming kernel is not wired in yet
+  if (g_kernel_choice == 1) return false;
+  if (g_kernel_choice == 2) return T <= 16;
+  return T <= 16;
+}
+
+struct ActBuffers {
+  uint8_t* qx;
+  int32_t* rowsum;
+  uint32_t* amax;   // [PIPE_MAX_K] bit patterns
+  float* scale;     // [PIPE_MAX_K] scales
+  int T_pad;
+};
+
+static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
+  b->T_pad = (int)round_up64(T, small ? 16 : 128);
+  b->qx = (uint8_t*)pipe_ws_get(WS_QX, (size_t)b->T_pad * in_pad);
+  b->rowsum = (int32_t*)pipe_ws_get(WS_ROWSUM, (size_t)b->T_pad * 4);
+  uint8_t* sc = (uint8_t*)pipe_ws_get(WS_SCAL, 4096);
+  if (!b->qx || !b->rowsum || !sc) return PIPE_ENOMEM;
+  b->amax = (uint32_t*)sc;
+  b->scale = (float*)(sc + 1024);
+  return PIPE_OK;
+}
+
+static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
+  return small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
+}
+
+static void fill_members(GemmArgs& a, int M, const int* lo, const int* hi) {
+  a.M = M;
+  for (int m = 0; m < PIPE_MAX_K; ++m) { a.member_lo[m] = 0; a.member_hi[m] = -1; }
+  for (int m = 0; m < M; ++m) { a.member_lo[m] = lo[m]; a.member_hi[m] = hi[m]; }
+}
+
+extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, float s_x,
+                            const int* split, int M, const float* bias_dev, int reduce_members,
+                            float* y_dev, void* stream) {
+  if (!e || T < 0) return PIPE_EINVAL;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(T);
+  ActBuffers b;
+  rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  if (!(s_x > 0.f)) {
+    rc = launch_zero_u32(b.amax, 1, st);
+    if (rc) return rc;
+    rc = launch_absmax(x_dev, (int64_t)T * e->in, b.amax, st);
+    if (rc) return rc;
+  }
+  rc = launch_quantize_act(x_dev, T, e->in, e->in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, nullptr, b.scale, st);
+  if (rc) return rc;
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.qx_mstride = 0; a.rowsum = b.rowsum; a.rowsum_mstride = 0;
+  a.s_x = b.scale; a.sx_mstride = 0; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.act = 0;
+  a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr;
+  fill_members(a, Mm, lo, hi);
+  return run_gemm(a, small, st);
+}
+
+extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
+                                int32_t* acc_dev, int8_t* qx_dev, float* s_x_out_dev, void* stream) {
+  if (!e || T < 0) return PIPE_EINVAL;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(T);
+  ActBuffers b;
+  int rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  if (!(s_x > 0.f)) {
+    rc = launch_zero_u32(b.amax, 1, st);
+    if (rc) return rc;
+    rc = launch_absmax(x_dev, (int64_t)T * e->in, b.amax, st);
+    if (rc) return rc;
+  }
+  rc = launch_quantize_act(x_dev, T, e->in, e->in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, qx_dev,
+                           s_x_out_dev ? s_x_out_dev : b.scale, st);
+  if (rc) return rc;
+  if (!acc_dev) return PIPE_OK;
+  PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
+  a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev;
+  int lo = 0, hi = e->K - 1;
+  fill_members(a, 1, &lo, &hi);
+  return run_gemm(a, small, st);
+}
+
+extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,
+                                   int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
+                                   const int* split, int M, const float* bias_dev,
+                                   int reduce_members, float* y_dev, void* stream) {
+  if (!e) return PIPE_EINVAL;
+  if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
+  if ((int64_t)C * kh * kw != e->in) return PIPE_ESHAPE;
+  const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+  if (H + 2 * pad < kh || W + 2 * pad < kw) return PIPE_ESHAPE;
+  const int64_t T64 = (int64_t)N * Ho * Wo;
+  if (T64 > (int64_t)1 << 30) return PIPE_ESHAPE;
+  const int T = (int)T64;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(T);
+  ActBuffers b;
+  rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  if (!(s_x > 0.f)) {
+    rc = launch_zero_u32(b.amax, 1, st);
+    if (rc) return rc;
+    rc = launch_absmax(x_dev, (int64_t)N * C * H * W, b.amax, st);
+    if (rc) return rc;
+  }
+  rc = launch_quantize_im2col(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, s_x,
+                              b.amax, b.qx, b.rowsum, b.scale, st);
+  if (rc) return rc;
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
+  a.s_x = b.scale; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev;
+  fill_members(a, Mm, lo, hi);
+  return run_gemm(a, small, st);
+}
+
+extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                                const float* x_dev, int T, float s_x, const int* split, int M,
+                                const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                                float* y_dev, void* stream) {
+  if (!l1 || !l2 || T < 0) return PIPE_EINVAL;
+  if (act != PIPE_ACT_GELU && act != PIPE_ACT_SILU_GATED) return PIPE_EINVAL;
+  if (l1->K != l2->K) return PIPE_ESPLIT;
+  const int H = l2->in;
+  if (l1->out != (act == PIPE_ACT_SILU_GATED ? 2 * H : H)) return PIPE_ESHAPE;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(l1->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(T);
+  ActBuffers b;
+  rc = get_act_buffers(T, l1->in_pad, small, &b);
+  if (rc) return rc;
+  // hidden buffers
+  const int T_pad = b.T_pad;
+  float* y1 = nullptr;
+  if (act == PIPE_ACT_SILU_GATED) {
+    y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
+    if (!y1) return PIPE_ENOMEM;
+  }
+  float* h = h_dev ? h_dev : (float*)pipe_ws_get(WS_H, (size_t)Mm * T * H * sizeof(float));
+  uint8_t* qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * l2->in_pad);
+  int32_t* rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+  if (!h || !qh || !rowsum_h) return PIPE_ENOMEM;
+  uint32_t* amax_h = b.amax + 16;
+  float* scale_h = b.scale + 16;
+
+  if (!(s_x > 0.f)) {
+    rc = launch_zero_u32(b.amax, 1, st);
+    if (rc) return rc;
+    rc = launch_absmax(x_dev, (int64_t)T * l1->in, b.amax, st);
+    if (rc) return rc;
+  }
+  rc = launch_quantize_act(x_dev, T, l1->in, l1->in_pad, T_pad, s_x, b.amax, b.qx, b.rowsum, nullptr, b.scale, st);
+  if (rc) return rc;
+  rc = launch_zero_u32(amax_h, Mm, st);
+  if (rc) return rc;
+
+  // layer 1: every member reads the same Q(x); outputs stay separate
+  GemmArgs a{};
+  a.e = l1; a.T = T; a.T_pad = T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
+  a.bias = bias1_dev; a.reduce = 0;
+  fill_members(a, Mm, lo, hi);
+  if (act == PIPE_ACT_GELU) {
+    a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
+  } else {
+    a.act = 0; a.y = y1; a.amax_out = nullptr;
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
+    rc = launch_mlp_act(y1, Mm, T, H, act, h, amax_h, st);
+    if (rc) return rc;
+  }
+  // each member quantizes its own hidden activation with its own scale
+  for (int m = 0; m < Mm; ++m) {
+    rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, 0.f, amax_h + m,
+                             qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, nullptr,
+                             scale_h + m, st);
+    if (rc) return rc;
+  }
+  // layer 2: member m contracts its own input with its own orders; summed in the epilogue
+  GemmArgs a2{};
+  a2.e = l2; a2.T = T; a2.T_pad = T_pad; a2.qx = qh; a2.qx_mstride = (int64_t)T_pad * l2->in_pad;
+  a2.rowsum = rowsum_h; a2.rowsum_mstride = T_pad; a2.s_x = scale_h; a2.sx_mstride = 1;
+  a2.bias = bias2_dev; a2.reduce = 1; a2.act = 0; a2.y = y_dev;
+  fill_members(a2, Mm, lo, hi);
+  return run_gemm(a2, small, st);
+}
+
+// Until the weight-streaming kernel is selected the tiled kernel serves every token count.
+__attribute__((weak)) int launch_gemm_stream(const GemmArgs& a, hipStream_t st) { return launch_gemm_tiled(a, st); }

@@ -1,0 +1,216 @@
+// Residual-expansion builder (Sec. 3.1, Eq. (2)-(3) and the masked form; quantizer: Sec. 3,
+// Eq. (1)).  Row-parallel kernels: residual energy per row (fp64), top-gamma group selection,
+// per-row quantization with in-place residual update and packing into the tile layout.
+//
+// The integer codes depend on the fp32 arithmetic, so every operation that feeds a rounding
+// decision is written with an explicitly rounded intrinsic (IEEE division, separate multiply
+// and subtract) and this file is compiled with floating-point contraction off.
+#include "pipe_internal.h"
+
+namespace {
+
+constexpr int BLK = 256;
+
+// ---- residual energy of every row: sum_i E[o,i]^2 in fp64, fixed reduction tree ----------
+__global__ __launch_bounds__(BLK) void row_energy_kernel(const float* __restrict__ E, int in,
+                                                         double* __restrict__ out) {
+  const int row = blockIdx.x;
+  const float* p = E + (size_t)row * in;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < in; i += BLK) {
+    const double v = (double)p[i];
+    s += v * v;  // the square of an fp32 value is exact in fp64
+  }
+  __shared__ double sm[BLK];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = BLK / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[row] = sm[0];
+}
+
+// ---- group score = sum of its rows' energies, rows ascending ------------------------------
+__global__ void group_score_kernel(const double* __restrict__ row_energy, int n_groups, int group,
+                                   double* __restrict__ score) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  double s = 0.0;
+  for (int r = 0; r < group; ++r) s += row_energy[(size_t)g * group + r];
+  score[g] = s;
+}
+
+// ---- keep flag: a group is kept if fewer than n_keep groups beat it (higher score, or equal
+//      score and lower index) --------------------------------------------------------------
+__global__ void group_rank_kernel(const double* __restrict__ score, int n_groups, int n_keep,
+                                  int32_t* __restrict__ flag) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  const double sg = score[g];
+  int rank = 0;
+  for (int j = 0; j < n_groups; ++j) {
+    const double sj = score[j];
+    rank += (sj > sg) || (sj == sg && j < g);
+  }
+  flag[g] = rank < n_keep ? 1 : 0;
+}
+
+// ---- compaction: kept groups in ascending order -------------------------------------------
+__global__ void group_compact_kernel(const int32_t* __restrict__ flag, int n_groups,
+                                     int32_t* __restrict__ gids) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups || !flag[g]) return;
+  int idx = 0;
+  for (int j = 0; j < g; ++j) idx += flag[j];
+  gids[idx] = g;
+}
+
+// ---- quantize one stored row, update its residual in place, pack its codes ----------------
+template <int BITS>
+__global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ E, int in, int in_pad,
+                                                            int group, const int32_t* __restrict__ gids,
+                                                            float* __restrict__ scales,
+                                                            uint8_t* __restrict__ packed) {
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  constexpr int KSUP = 512 / BITS;       // k-values per tile
+  constexpr int STEPS = KSUP / 64;       // 64-k steps per tile
+  constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
+  const int r = blockIdx.x;              // stored (compact) row
+  const int slot = r / group;
+  const int o = gids[slot] * group + (r - slot * group);
+  float* e = E + (size_t)o * in;
+
+  float amax = 0.f;
+  for (int i = threadIdx.x; i < in; i += BLK) amax = fmaxf(amax, fabsf(e[i]));
+  __shared__ float sm[BLK];
+  sm[threadIdx.x] = amax;
+  __syncthreads();
+  for (int s = BLK / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sm[threadIdx.x] = fmaxf(sm[threadIdx.x], sm[threadIdx.x + s]);
+    __syncthreads();
+  }
+  amax = sm[0];
+  const float s = __fdiv_rn(amax, (float)QMAX);
+  const bool live = s > 0.f;
+  if (threadIdx.x == 0) scales[r] = s;
+
+  const int crb = r >> 4, rr = r & 15;
+  const int nksup = in_pad / KSUP;
+  const int nchunk = in_pad >> 4;
+  for (int c = threadIdx.x; c < nchunk; c += BLK) {
+    int code[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const int k = c * 16 + t;
+      int q = 0;
+      if (live && k < in) {
+        const float v = e[k];
+        float qf = rintf(__fdiv_rn(v, s));                 // round half to even
+        qf = fminf(fmaxf(qf, (float)-QMAX), (float)QMAX);
+        e[k] = __fsub_rn(v, __fmul_rn(s, qf));             // Q^-1 then residual: two roundings
+        q = (int)qf;
+      }
+      code[t] = q;
+    }
+    const int ks = c >> 2, kc = c & 3;
+    const int ksup = ks / STEPS, j = ks - ksup * STEPS;
+    const int lane = kc * 16 + rr;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(packed + ((size_t)crb * nksup + ksup) * 1024 + lane * 16);
+    if (BITS == 8) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        w[i] = (uint32_t)(uint8_t)code[4 * i] | ((uint32_t)(uint8_t)code[4 * i + 1] << 8) |
+               ((uint32_t)(uint8_t)code[4 * i + 2] << 16) | ((uint32_t)(uint8_t)code[4 * i + 3] << 24);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else if (BITS == 4) {
+      uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint32_t v = (uint32_t)(code[4 * i + b] + OFF) << (8 * b + 4 * (i & 1));
+          if (i < 2) w0 |= v; else w1 |= v;
+        }
+      dst[2 * j] = w0;
+      dst[2 * j + 1] = w1;
+    } else {
+      uint32_t w = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) w |= (uint32_t)(code[4 * i + b] + OFF) << (8 * b + 2 * i);
+      dst[j] = w;
+    }
+  }
+}
+
+// ---- introspection: tile layout -> one signed code per byte, [rows, in] -------------------
+__global__ void unpack_codes_kernel(const uint8_t* __restrict__ packed, int bits, int rows, int in,
+                                    int in_pad, int8_t* __restrict__ codes) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)rows * in) return;
+  const int r = (int)(idx / in), k = (int)(idx - (int64_t)r * in);
+  const int ksupw = 512 / bits, steps = ksupw / 64;
+  const int crb = r >> 4, rr = r & 15;
+  const int c = k >> 4, t = k & 15, ks = c >> 2, kc = c & 3;
+  const int ksup = ks / steps, j = ks - ksup * steps;
+  const int nksup = in_pad / ksupw;
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(packed + ((size_t)crb * nksup + ksup) * 1024 +
+                                                          (kc * 16 + rr) * 16);
+  const int i = t >> 2, b = t & 3;
+  int v;
+  if (bits == 8) v = (int8_t)((src[i] >> (8 * b)) & 0xFF);
+  else if (bits == 4) v = (int)((src[2 * j + (i >> 1)] >> (8 * b + 4 * (i & 1))) & 0xF) - 8;
+  else v = (int)((src[j] >> (8 * b + 2 * i)) & 0x3) - 1;
+  codes[idx] = (int8_t)v;
+}
+
+}  // namespace
+
+int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st) {
+  hipLaunchKernelGGL(row_energy_kernel, dim3(out), dim3(BLK), 0, st, E, in, row_energy);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+// row_energy holds [out] doubles followed by scratch for [n_groups] scores (doubles) and
+// [n_groups] flags (int32); the caller sizes it with out + n_groups doubles + n_groups ints.
+int launch_group_select(const double* row_energy, int n_groups, int group, int n_keep,
+                        int32_t* gids_out, hipStream_t st) {
+  double* score = const_cast<double*>(row_energy) + (size_t)n_groups * group;
+  int32_t* flag = reinterpret_cast<int32_t*>(score + n_groups);
+  const int g = ceil_div(n_groups, 128);
+  hipLaunchKernelGGL(group_score_kernel, dim3(g), dim3(128), 0, st, row_energy, n_groups, group, score);
+  hipLaunchKernelGGL(group_rank_kernel, dim3(g), dim3(128), 0, st, score, n_groups, n_keep, flag);
+  hipLaunchKernelGGL(group_compact_kernel, dim3(g), dim3(128), 0, st, flag, n_groups, gids_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int group,
+                         const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
+                         hipStream_t st) {
+  (void)out;
+  const int rows = n_kept * group;
+  if (rows == 0) return PIPE_OK;
+  if (bits == 8)
+    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+  else if (bits == 4)
+    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+  else
+    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_unpack_codes(const uint8_t* packed, int bits, int rows, int in, int in_pad,
+                        int8_t* codes, hipStream_t st) {
+  const int64_t n = (int64_t)rows * in;
+  if (n == 0) return PIPE_OK;
+  hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed,
+                     bits, rows, in, in_pad, codes);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}

@@ -1,0 +1,142 @@
+// Internal declarations shared by the HIP sources of the PIPE library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/pipe.h"
+
+// ---------------------------------------------------------------------------------------
+// Data layout in HBM
+//
+// Quantized activations ("fragment layout"): tokens are padded to a multiple of TOK_PAD and
+// in_features to a multiple of IN_PAD (pad entries are 0).  A fragment holds 16 tokens x 64
+// consecutive k as 64 lanes x 16 bytes: lane = kc*16 + n holds token n, k = 64*ks + 16*kc + e,
+// e = 0..15.  Fragments are stored [token_block][ks], 1 KiB each, so that one wave reads a
+// fragment with a single fully coalesced 16-byte-per-lane load, already in the register
+// layout of the B operand of v_mfma_i32_16x16x64_i8.
+//
+// Packed codes of one order ("tile layout"): stored rows are grouped in row blocks of 16
+// (compact index crb = kept_group_slot * (group/16) + block).  A tile holds 16 rows x KSUP
+// k-values (KSUP = 512/bits) as 64 lanes x 16 bytes; lane = kc*16 + r holds, for row r and
+// each 64-k step j inside the tile, the 16 codes k = KSUP*ksup + 64*j + 16*kc + e.  Tiles are
+// stored [crb][ksup].  Codes are stored offset-binary (code + 2^(bits-1) for 4 bit, code + 1
+// for ternary; int8 is stored as is) so that unpacking is a shift and a mask:
+//   bits = 4: step j uses dwords 2j, 2j+1; code e = 4i + byte sits in dword 2j + (i >> 1) at
+//             bit 8*byte + 4*(i & 1)      =>  out dword i = (w >> 4*(i&1)) & 0x0F0F0F0F
+//   bits = 2: step j uses dword j; code e = 4i + byte sits at bit 8*byte + 2i
+//                                          =>  out dword i = (w >> 2i) & 0x03030303
+// The exact integer accumulator is recovered as acc - offset * rowsum(Qx[t,:]).
+// ---------------------------------------------------------------------------------------
+constexpr int PIPE_MAX_K = 16;
+constexpr int IN_PAD = 256;    // in_features padded to this (largest KSUP)
+constexpr int TOK_PAD = 256;   // tokens padded to this (largest token tile)
+constexpr int RB = 16;         // rows per row block
+constexpr int NRB_TILE = 8;    // row blocks per column tile of the tiled kernel
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+struct PipeOrder {
+  int n_kept = 0;               // groups stored at this order
+  int32_t* gids_dev = nullptr;  // [n_kept] ascending
+  float* scales_dev = nullptr;  // [n_kept*group]
+  uint8_t* packed_dev = nullptr;
+  size_t packed_bytes = 0;
+  std::vector<int32_t> gids;    // host copy
+};
+
+struct pipe_expansion {
+  int out = 0, in = 0, bits = 0, K = 0, group = 0;
+  float gamma = 1.f;
+  int n_groups = 0;
+  int rbpg = 0;       // row blocks per group = group/16
+  int n_rb = 0;       // out/16
+  int in_pad = 0;     // in rounded up to IN_PAD
+  int nks = 0;        // in_pad/64
+  int device = 0;
+  std::vector<PipeOrder> orders;
+  // Tile schedule.  Row blocks are sorted by the set of orders that hold them so that the
+  // NRB_TILE row blocks of a column tile do the same work.
+  int n_ct = 0;                     // column tiles
+  int32_t* ct_rb_out_dev = nullptr; // [n_ct][NRB_TILE] output row block (channel/16) or -1
+  int32_t* ct_src_dev = nullptr;    // [n_ct][K][NRB_TILE] compact row block in order k or -1
+  // per order device pointers for kernels
+  const uint8_t** packed_ptrs_dev = nullptr;  // [K]
+  const float** scale_ptrs_dev = nullptr;     // [K]
+  int64_t stream_bytes = 0;  // packed codes + scales + indices
+};
+
+// ------------------------------------------------------------------ error plumbing
+void pipe_note_hip_error(hipError_t e, const char* what);
+#define PIPE_HIP(call)                                   \
+  do {                                                   \
+    hipError_t _e = (call);                              \
+    if (_e != hipSuccess) {                              \
+      pipe_note_hip_error(_e, #call);                    \
+      return PIPE_EDEVICE;                               \
+    }                                                    \
+  } while (0)
+
+// ------------------------------------------------------------------ workspace
+struct PipeWorkspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+// Returns a device buffer of at least `bytes` from slot `slot` (grow-only; growing
+// synchronizes the device first).  nullptr on failure.
+void* pipe_ws_get(int slot, size_t bytes);
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_SLOTS };
+
+// ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
+int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
+int launch_group_select(const double* row_energy, int n_groups, int group, int n_keep,
+                        int32_t* gids_out, hipStream_t st);
+int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int group,
+                         const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
+                         hipStream_t st);
+int launch_unpack_codes(const uint8_t* packed, int bits, int rows, int in, int in_pad,
+                        int8_t* codes, hipStream_t st);
+
+// ------------------------------------------------------------------ activation kernels (pipe_quant.hip)
+// amax_bits: device uint32 holding the bit pattern of max|x| (must be zeroed first).
+int launch_zero_u32(uint32_t* p, int n, hipStream_t st);
+int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, hipStream_t st);
+// Quantize x [T, in] into the fragment layout (padded region written as zero), row sums and
+// optionally row-major int8.  scale: if s_static > 0 use it, else amax/127 from amax_bits.
+// Writes the scale used to *scale_out (device).
+int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
+                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum,
+                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
+// Same for the virtual im2col matrix of a convolution.
+int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
+                           int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
+                           float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
+                           int32_t* rowsum, float* scale_out, hipStream_t st);
+// Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h|.
+int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
+                   hipStream_t st);
+
+// ------------------------------------------------------------------ contraction kernels
+struct GemmArgs {
+  const pipe_expansion* e;
+  int T;                 // valid tokens
+  int T_pad;             // padded tokens of the fragment buffers
+  const uint8_t* qx;     // fragment layout, member stride below
+  int64_t qx_mstride;    // bytes between members' activations (0 = shared input)
+  const int32_t* rowsum; // [T_pad] per member
+  int64_t rowsum_mstride;
+  const float* s_x;      // device: activation scale per member
+  int sx_mstride;        // 0 = shared
+  int M;                 // members
+  int member_lo[PIPE_MAX_K];  // 0-based first order of member m
+  int member_hi[PIPE_MAX_K];  // 0-based last order (inclusive)
+  const float* bias;     // or nullptr
+  int reduce;            // 1: y[T,out]; 0: y[M,T,out]
+  int act;               // 0 none, PIPE_ACT_GELU fused in the epilogue
+  float* y;
+  int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
+  uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
+};
+int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
+int launch_gemm_stream(const GemmArgs& a, hipStream_t st);

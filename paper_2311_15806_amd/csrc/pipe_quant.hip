@@ -1,0 +1,237 @@
+// Activation quantization (App. B, Eq. (define_dre): Q(x) with a per-tensor scale lambda_x):
+// absmax reduction, fp32 -> int8 into the fragment layout with per-token code sums, the
+// im2col variant for convolutions, and the element-wise hidden activation of the MLP call.
+//
+// Q(x) = clamp(rint(x / s_x), -127, 127) with an IEEE fp32 division and round-half-to-even;
+// this file is compiled with floating-point contraction off.
+#include "pipe_internal.h"
+
+namespace {
+
+constexpr int BLK = 256;
+
+__global__ void zero_u32_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+__device__ __forceinline__ float block_max(float v) {
+  __shared__ float sm[BLK / 64];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+#pragma unroll
+  for (int i = 1; i < BLK / 64; ++i) r = fmaxf(r, sm[i]);
+  __syncthreads();
+  return r;
+}
+
+// max|x| over n elements; the maximum is order independent, so the result is exact.
+__global__ __launch_bounds__(BLK) void absmax_kernel(const float* __restrict__ x, int64_t n,
+                                                     uint32_t* __restrict__ amax_bits) {
+  float m = 0.f;
+  const int64_t stride = (int64_t)gridDim.x * BLK;
+  const int64_t i0 = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+    const int64_t n4 = n >> 2;
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    for (int64_t i = i0; i < n4; i += stride) {
+      const float4 v = x4[i];
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    for (int64_t i = (n4 << 2) + i0; i < n; i += stride) m = fmaxf(m, fabsf(x[i]));
+  } else {
+    for (int64_t i = i0; i < n; i += stride) m = fmaxf(m, fabsf(x[i]));
+  }
+  m = block_max(m);
+  if (threadIdx.x == 0) atomicMax(amax_bits, __float_as_uint(m));
+}
+
+__device__ __forceinline__ float act_scale(float s_static, const uint32_t* amax_bits) {
+  if (s_static > 0.f) return s_static;
+  return __fdiv_rn(__uint_as_float(*amax_bits), 127.f);
+}
+
+__device__ __forceinline__ int quant1(float v, float s) {
+  float q = rintf(__fdiv_rn(v, s));
+  q = fminf(fmaxf(q, -127.f), 127.f);
+  return (int)q;
+}
+
+__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
+  return (uint32_t)(uint8_t)a | ((uint32_t)(uint8_t)b << 8) | ((uint32_t)(uint8_t)c << 16) |
+         ((uint32_t)(uint8_t)d << 24);
+}
+
+// One block: token block blockIdx.x (16 tokens), a range of 16-wide k-chunks given by
+// blockIdx.y.  Thread = (token n = tid & 15, chunk slot tid >> 4).  FETCH(t, k) returns the
+// fp32 activation (0 outside the valid region).
+template <class Fetch>
+__device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int in_pad, float s,
+                                               uint8_t* __restrict__ qx_frag, int32_t* __restrict__ rowsum,
+                                               int8_t* __restrict__ qx_rowmajor) {
+  const int tb = blockIdx.x;
+  const int n = threadIdx.x & 15;
+  const int t = tb * 16 + n;
+  const int nks = in_pad >> 6;
+  const int nchunk = in_pad >> 4;
+  const int per = (nchunk + gridDim.y - 1) / gridDim.y;
+  const int c_lo = blockIdx.y * per;
+  const int c_hi = min(nchunk, c_lo + per);
+  const bool live = s > 0.f;
+  int sum = 0;
+  for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
+    int q[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int k = c * 16 + e;
+      int v = 0;
+      if (live && t < T && k < in) v = quant1(fetch(t, k), s);
+      q[e] = v;
+      sum += v;
+    }
+    const int ks = c >> 2, kc = c & 3;
+    uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
+                         pack4(q[8], q[9], q[10], q[11]), pack4(q[12], q[13], q[14], q[15]));
+    *reinterpret_cast<uint4*>(qx_frag + (((size_t)tb * nks + ks) * 64 + kc * 16 + n) * 16) = w;
+    if (qx_rowmajor != nullptr && t < T) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (c * 16 + e < in) qx_rowmajor[(size_t)t * in + c * 16 + e] = (int8_t)q[e];
+    }
+  }
+  if (t < T && sum != 0) atomicAdd(&rowsum[t], sum);
+}
+
+__global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restrict__ x, int T, int in,
+                                                           int in_pad, float s_static,
+                                                           const uint32_t* __restrict__ amax_bits,
+                                                           uint8_t* __restrict__ qx_frag,
+                                                           int32_t* __restrict__ rowsum,
+                                                           int8_t* __restrict__ qx_rowmajor,
+                                                           float* __restrict__ scale_out) {
+  const float s = act_scale(s_static, amax_bits);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  auto fetch = [=](int t, int k) { return x[(size_t)t * in + k]; };
+  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor);
+}
+
+struct ConvGeom {
+  int N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo;
+};
+
+__global__ __launch_bounds__(BLK) void quantize_im2col_kernel(const float* __restrict__ x, ConvGeom g, int T,
+                                                              int in, int in_pad, float s_static,
+                                                              const uint32_t* __restrict__ amax_bits,
+                                                              uint8_t* __restrict__ qx_frag,
+                                                              int32_t* __restrict__ rowsum,
+                                                              float* __restrict__ scale_out) {
+  const float s = act_scale(s_static, amax_bits);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  // token t = (n, ho, wo); column k = (c, r, q) as in a weight row flattened [C, kh, kw]
+  auto fetch = [=](int t, int k) {
+    const int wo = t % g.Wo, ho = (t / g.Wo) % g.Ho, n = t / (g.Wo * g.Ho);
+    const int q = k % g.kw, r = (k / g.kw) % g.kh, c = k / (g.kw * g.kh);
+    const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + q;
+    if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) return 0.f;
+    const size_t off = g.nhwc ? (((size_t)n * g.H + hi) * g.W + wi) * g.C + c
+                              : (((size_t)n * g.C + c) * g.H + hi) * g.W + wi;
+    return x[off];
+  };
+  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, nullptr);
+}
+
+// h = act(y1) for every member, and max|h| per member.
+__global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ y1, int T, int H, int act,
+                                                      float* __restrict__ h, uint32_t* __restrict__ amax_bits) {
+  const int m = blockIdx.y;
+  const int64_t n = (int64_t)T * H;
+  const int O1 = act == PIPE_ACT_SILU_GATED ? 2 * H : H;
+  const float* src = y1 + (size_t)m * T * O1;
+  float* dst = h + (size_t)m * n;
+  float mx = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x; i < n; i += (int64_t)gridDim.x * BLK) {
+    float v;
+    if (act == PIPE_ACT_SILU_GATED) {
+      const int64_t t = i / H;
+      const int c = (int)(i - t * H);
+      const float gte = src[t * O1 + c], up = src[t * O1 + H + c];
+      v = gte / (1.f + expf(-gte)) * up;
+    } else {
+      const float a = src[i];
+      v = 0.5f * a * (1.f + erff(a * 0.70710678118654752440f));
+    }
+    dst[i] = v;
+    mx = fmaxf(mx, fabsf(v));
+  }
+  mx = block_max(mx);
+  if (threadIdx.x == 0) atomicMax(&amax_bits[m], __float_as_uint(mx));
+}
+
+}  // namespace
+
+int launch_zero_u32(uint32_t* p, int n, hipStream_t st) {
+  if (n <= 0) return PIPE_OK;
+  hipLaunchKernelGGL(zero_u32_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, p, n);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, hipStream_t st) {
+  if (n <= 0) return PIPE_OK;
+  int64_t blocks = (n / 4 + BLK - 1) / BLK;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+static int ksplit_for(int T_pad, int in_pad) {
+  // enough blocks to fill the chip when there are few token blocks
+  const int tbs = T_pad / 16;
+  int ks = 1;
+  const int nchunk = in_pad / 16;
+  while (tbs * ks < 1024 && ks * 2 * 16 <= nchunk) ks *= 2;
+  return ks;
+}
+
+int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
+                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum,
+                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
+  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
+  if (rc) return rc;
+  dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
+  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, s_static, amax_bits,
+                     qx_frag, rowsum, qx_rowmajor, scale_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
+                           int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
+                           float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
+                           int32_t* rowsum, float* scale_out, hipStream_t st) {
+  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
+  if (rc) return rc;
+  ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
+  const int T = N * Ho * Wo, in = C * kh * kw;
+  dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
+  hipLaunchKernelGGL(quantize_im2col_kernel, grid, dim3(BLK), 0, st, x, g, T, in, in_pad, s_static,
+                     amax_bits, qx_frag, rowsum, scale_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
+                   hipStream_t st) {
+  const int64_t n = (int64_t)T * H;
+  if (n <= 0) return PIPE_OK;
+  int64_t blocks = (n + BLK * 4 - 1) / (BLK * 4);
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}

@@ -1,0 +1,164 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU checker on the same
+seeded inputs.  Integer state (kept groups, codes, Q(x), int32 accumulators) must be
+bit-exact; scales are compared as fp32 bit patterns; the fp32 output within 1e-3 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pipe_oracle as po
+from paper_2311_15806_amd import workloads as wl
+from paper_2311_15806_amd.workloads import LayerSpec
+from _parity import assert_close_fp32, assert_expansion_equal, dev, oracle_expand
+
+pytestmark = pytest.mark.gpu
+
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def pipe():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2311_15806_amd.binding as b
+    return b
+
+
+def _w(seed, O, I, heavy=True):
+    rng = np.random.default_rng(seed)
+    if heavy:
+        return (rng.standard_t(3, size=(O, I)) * 0.015).astype(f32)
+    return (rng.standard_normal((O, I)) * 0.02).astype(f32)
+
+
+def _x(seed, T, I):
+    return np.random.default_rng(seed).standard_normal((T, I)).astype(f32)
+
+
+EXPAND_CASES = [
+    # bits, K, gamma, group, out, in
+    (8, 2, 1.0, 16, 64, 256),
+    (4, 3, 0.5, 16, 128, 200),      # ragged in (pads to 256)
+    (2, 4, 0.25, 64, 512, 333),     # ragged in, several tiles
+    (4, 4, 0.5, 32, 416, 768),      # 13 groups: ragged column tile
+    (2, 3, 0.34, 16, 144, 1040),    # n_keep = ceil(0.34*9) = 4
+    (8, 1, 1.0, 48, 48, 64),
+]
+
+
+@pytest.mark.parametrize("bits,K,gamma,group,O,I", EXPAND_CASES)
+def test_expand_bit_exact(pipe, bits, K, gamma, group, O, I):
+    W = _w(100 + bits + K + O, O, I)
+    W[3] = 0.0                       # an all-zero row: scale 0, codes 0
+    spec = LayerSpec(O, I, bits, K, gamma, group)
+    ora = oracle_expand(W, spec)
+    g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+    assert (g.out_features, g.in_features, g.bits, g.K, g.group) == (O, I, bits, K, group)
+    assert_expansion_equal(g, ora)
+    g.free()
+
+
+@pytest.mark.parametrize("bits,K,gamma,group,O,I", EXPAND_CASES)
+@pytest.mark.parametrize("T", [1, 16, 37, 300])
+def test_forward_acc_bit_exact_and_output(pipe, bits, K, gamma, group, O, I, T):
+    W = _w(200 + bits + K + O, O, I)
+    x = _x(300 + T, T, I)
+    x[:, 5] *= 20.0                  # an outlier channel
+    spec = LayerSpec(O, I, bits, K, gamma, group)
+    ora = oracle_expand(W, spec)
+    ref = po.forward(ora, x)
+    g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+    acc, qx, sx = pipe.pipe_forward_acc(g, dev(x))
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), np.array([ref["s_x"]], f32).view(np.uint32))
+    assert np.array_equal(qx.cpu().numpy(), ref["Qx"])
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    y = pipe.pipe_forward(g, dev(x)).cpu().numpy()
+    assert_close_fp32(y, ref["y"])
+    # run twice: bit-identical (no atomics in the accumulation)
+    y2 = pipe.pipe_forward(g, dev(x)).cpu().numpy()
+    assert np.array_equal(y, y2)
+    g.free()
+
+
+def test_static_scale_split_bias_members(pipe):
+    O, I, T = 256, 512, 70
+    W, x = _w(400, O, I), _x(401, T, I)
+    b = np.random.default_rng(402).standard_normal(O).astype(f32)
+    spec = LayerSpec(O, I, 4, 4, 0.5, 32)
+    ora = oracle_expand(W, spec)
+    g = pipe.pipe_expand(dev(W), 4, 4, 0.5, 32)
+    for split in (None, [2, 2], [1, 3], [1, 1, 1, 1]):
+        for s_x in (0.0, 0.05):
+            ref = po.forward(ora, x, s_x=s_x if s_x > 0 else None, split=split, bias=b)
+            y = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+            assert_close_fp32(y, ref["y"])
+            refm = po.forward(ora, x, s_x=s_x if s_x > 0 else None, split=split, bias=b, reduce_members=False)
+            ym = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b), reduce_members=False).cpu().numpy()
+            assert ym.shape == refm["y"].shape
+            assert_close_fp32(ym, refm["y"])
+    acc, qx, sx = pipe.pipe_forward_acc(g, dev(x), s_x=0.05)
+    ref = po.forward(ora, x, s_x=0.05)
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"]) and np.array_equal(qx.cpu().numpy(), ref["Qx"])
+    g.free()
+
+
+def test_degenerate_inputs(pipe):
+    O, I = 32, 64
+    W = _w(410, O, I)
+    g = pipe.pipe_expand(dev(W), 2, 2, 0.5, 16)
+    # zero tokens: a no-op
+    y = pipe.pipe_forward(g, torch.empty((0, I), device="cuda:0"))
+    assert y.shape == (0, O)
+    # all-zero input: scale 0, output exactly 0
+    y0 = pipe.pipe_forward(g, torch.zeros((5, I), device="cuda:0")).cpu().numpy()
+    assert not y0.any()
+    g.free()
+    # all-zero weights
+    gz = pipe.pipe_expand(torch.zeros((O, I), device="cuda:0"), 4, 3, 0.5, 16)
+    ora = po.expand(np.zeros((O, I), f32), 4, 3, 0.5, 16)
+    assert_expansion_equal(gz, ora)
+    yz = pipe.pipe_forward(gz, dev(_x(411, 3, I))).cpu().numpy()
+    assert not yz.any()
+    gz.free()
+
+
+def test_conv2d_parity(pipe):
+    w = wl.scaled(wl.C2, out_div=4, in_div=8, tokens=2 * 196)
+    spec, c = w.layers[0], w.conv
+    W, x = wl.make_weight(w, 0), wl.make_input(w)
+    ora = oracle_expand(W, spec)
+    ref = po.forward_conv2d(ora, x, c["kh"], c["kw"], c["stride"], c["pad"], split=list(w.split))
+    g = pipe.pipe_expand(dev(W), spec.bits, spec.K, spec.gamma, spec.group)
+    assert_expansion_equal(g, ora)
+    y = pipe.pipe_forward_conv2d(g, dev(x), c["kh"], c["kw"], c["stride"], c["pad"], split=list(w.split)).cpu().numpy()
+    assert_close_fp32(y, ref["y"])
+    # channels-last input gives the same result
+    xl = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    yl = pipe.pipe_forward_conv2d(g, dev(xl), c["kh"], c["kw"], c["stride"], c["pad"], nhwc=True,
+                                  split=list(w.split)).cpu().numpy()
+    assert np.array_equal(y, yl)
+    # stride 2, no padding
+    ref2 = po.forward_conv2d(ora, x, 3, 3, 2, 0)
+    y2 = pipe.pipe_forward_conv2d(g, dev(x), 3, 3, 2, 0).cpu().numpy()
+    assert_close_fp32(y2, ref2["y"])
+    g.free()
+
+
+@pytest.mark.parametrize("kind", ["gelu", "gated"])
+def test_mlp_parity(pipe, kind):
+    base = wl.C3 if kind == "gelu" else wl.C5
+    w = wl.scaled(base, out_div=8, in_div=8, tokens=150)
+    l1, l2 = w.layers
+    W1, W2, x = wl.make_weight(w, 0), wl.make_weight(w, 1), wl.make_input(w)
+    o1, o2 = oracle_expand(W1, l1), oracle_expand(W2, l2)
+    g1 = pipe.pipe_expand(dev(W1), l1.bits, l1.K, l1.gamma, l1.group)
+    g2 = pipe.pipe_expand(dev(W2), l2.bits, l2.K, l2.gamma, l2.group)
+    assert_expansion_equal(g1, o1)
+    assert_expansion_equal(g2, o2)
+    act = pipe.PIPE_ACT_GELU if kind == "gelu" else pipe.PIPE_ACT_SILU_GATED
+    for split in (list(w.split), None, [1] * l1.K):
+        ref = po.mlp_forward(o1, o2, kind, x, split=split)
+        y, h = pipe.pipe_mlp_forward(g1, g2, act, dev(x), split=split, return_hidden=True)
+        # layer 1 + activation: same integer state, device libm within a few ulp
+        assert_close_fp32(h.cpu().numpy(), ref["h"], tol=1e-5)
+        # chained output: a hidden value a few ulp off may flip a code of Q(h)
+        assert_close_fp32(y.cpu().numpy(), ref["y"])
+    g1.free(); g2.free()
