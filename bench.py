@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the residual-expanded quantized layer on one MI355X.
+
+A step is one pass of the whole hot path -- activation quantization, integer
+contraction over all kept rows of all K orders, de-quantizing epilogue, member
+sum -- over one batch of synthetic input that is already resident in HBM (the
+expansion itself is built once, offline, before the timed region).
+
+Prints ONE JSON line.  `value` is effective integer TOPS of the headline
+workload (2*T*in*(stored rows) / step time); `sweep` adds the other token counts
+of the same layer and the decode-sized HBM roofline; `cpu_baseline` is the CPU
+checker timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8, vendor figure (5.0 POP/s)
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, vendor figure (8 TB/s)
+LLC_BYTES = 256 << 20           # Infinity Cache: rotate over more expansion bytes than this
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4",
+                    help="c4 (LLM-7B linear, ternary K=4) | c5 (gated MLP, int4 K=4) | c3 | c2 | c1")
+    ap.add_argument("--tokens", type=int, default=0, help="override the headline token count")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 tiled MFMA, 2 weight streaming")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+              "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2311_15806_amd import workloads as wl
+    import paper_2311_15806_amd.binding as pipe   # raises if the HIP library is missing
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    pipe.pipe_set_kernel(args.kernel)
+
+    cfg = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
+    T_head = args.tokens or cfg.tokens
+
+    # ---- build the expansion(s) once (offline step a0) ------------------------------------
+    t0 = time.time()
+    Ws = [torch.from_numpy(wl.make_weight(cfg, i)).to(dev) for i in range(len(cfg.layers))]
+
+    def build():
+        return [pipe.pipe_expand(Ws[i], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
+
+    torch.cuda.synchronize()
+    t1 = time.time()
+    exps = [build()]
+    torch.cuda.synchronize()
+    expand_s = time.time() - t1
+    stream_bytes = sum(e.packed_bytes for e in exps[0])
+    macs_per_token = sum(e.macs_per_token() for e in exps[0])
+    gen_s = t1 - t0
+
+    x_full = wl.make_input(cfg if cfg.kind == "conv2d" else wl.with_tokens(cfg, max(T_head, 4096)))
+    xd_full = torch.from_numpy(x_full).to(dev)
+    split = list(cfg.split) if len(cfg.split) > 1 else None
+
+    def step_fn(e, xd):
+        if cfg.kind == "linear":
+            return pipe.pipe_forward(e[0], xd, split=split)
+        if cfg.kind == "conv2d":
+            c = cfg.conv
+            return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split)
+        act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
+        return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split)
+
+    def io_bytes(T):
+        b = 0
+        for l in cfg.layers:
+            b += 4 * T * l.in_features if l is cfg.layers[0] else 0
+        b += 4 * T * cfg.layers[-1].out_features
+        return b
+
+    def measure(T, steps, warmup, rotate):
+        """Times `steps` passes; returns dict with step time and contraction-kernel time."""
+        xd = xd_full if cfg.kind == "conv2d" else xd_full[:T].contiguous()
+        copies = 1
+        if rotate:
+            copies = max(2, -(-int(1.25 * LLC_BYTES) // max(stream_bytes, 1)))
+            while len(exps) < copies:
+                exps.append(build())
+        for i in range(warmup):
+            step_fn(exps[i % copies], xd)
+        torch.cuda.synchronize()
+        pipe.pipe_timing_read()
+        pipe.pipe_timing_enable(True)
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        for i in range(steps):
+            step_fn(exps[i % copies], xd)
+        torch.cuda.synchronize()
+        t_b = time.perf_counter()
+        pipe.pipe_timing_enable(False)
+        k_ms, k_n = pipe.pipe_timing_read()
+        step_ms = (t_b - t_a) * 1e3 / steps
+        per_step_kernel_ms = k_ms / steps
+        ops = 2.0 * T * macs_per_token
+        alg_bytes = stream_bytes + io_bytes(T)
+        return dict(tokens=T, ms_per_step=step_ms, kernel_ms_per_step=per_step_kernel_ms,
+                    kernel_launches_per_step=k_n / steps,
+                    eff_tops=ops / (step_ms * 1e-3) / 1e12,
+                    kernel_eff_tops=ops / (per_step_kernel_ms * 1e-3) / 1e12 if k_ms > 0 else None,
+                    tokens_per_s=T / (step_ms * 1e-3),
+                    kernel_gbs=alg_bytes / (per_step_kernel_ms * 1e-3) / 1e9 if k_ms > 0 else None,
+                    alg_bytes=alg_bytes, expansion_copies=copies)
+
+    T0 = cfg.tokens if cfg.kind == "conv2d" else T_head
+    head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 16))
+
+    mfma_bound = T0 > 64
+    if mfma_bound:
+        roofline = dict(bound="mfma", achieved=head["kernel_eff_tops"], peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
+                        frac=(head["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS, traffic=None,
+                        kernel="gemm_tiled_kernel", kernel_ms=head["kernel_ms_per_step"])
+    else:
+        roofline = dict(bound="hbm", achieved=head["kernel_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=(head["kernel_gbs"] or 0) / HBM_PEAK_GBS, traffic=None,
+                        kernel="gemm_stream_kernel", kernel_ms=head["kernel_ms_per_step"])
+
+    sweep = []
+    if not args.no_sweep and cfg.kind != "conv2d":
+        for T in (1, 16, 256, 2048, 4096):
+            if T == T0:
+                r = dict(head)
+            else:
+                r = measure(T, max(10, args.steps // 2), 3, rotate=(T <= 16))
+            r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
+            r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
+            sweep.append({k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()})
+
+    # ---- CPU checker on a bounded sample of the same workload ------------------------------
+    cpu = None
+    if not args.no_cpu:
+        from oracle import pipe_oracle as po
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        O_s = min(cfg.layers[0].out_features, 1024 if cfg.kind == "linear" else cfg.layers[0].out_features)
+        l0 = cfg.layers[0]
+        if cfg.kind == "linear":
+            T_s = min(T0, 512)
+            Wn = Ws[0][:O_s].cpu().numpy()
+            ex = po.expand(Wn, l0.bits, l0.K, l0.gamma, l0.group)
+            xs = x_full[:T_s]
+            tc = time.perf_counter()
+            po.forward(ex, xs, split=split)
+            dt = time.perf_counter() - tc
+            macs = po.expansion_macs(ex, T_s)
+            sample = "forward on the first %d output channels x %d tokens (expansion built outside the timer)" % (O_s, T_s)
+        else:
+            small = wl.scaled(cfg, out_div=4, in_div=2, tokens=256 if cfg.kind != "conv2d" else 392)
+            Wsm = [wl.make_weight(small, i) for i in range(len(small.layers))]
+            exs = [po.expand(Wsm[i], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(small.layers)]
+            xs = wl.make_input(small)
+            tc = time.perf_counter()
+            if cfg.kind == "conv2d":
+                c = small.conv
+                po.forward_conv2d(exs[0], xs, c["kh"], c["kw"], c["stride"], c["pad"], split=split)
+            else:
+                po.mlp_forward(exs[0], exs[1], "gelu" if cfg.kind == "mlp_gelu" else "gated", xs, split=split)
+            dt = time.perf_counter() - tc
+            macs = sum(po.expansion_macs(e, small.tokens) for e in exs)
+            sample = "reduced copy %s, %d tokens" % (small.name, small.tokens)
+        cpu = dict(value=2.0 * macs / dt / 1e12, unit="TOPS", cores=int(cores), kind="oracle",
+                   sample=sample, seconds=dt)
+
+    out = {
+        "metric": "effective int TOPS of the residual-expanded layer (2*T*in*stored_rows / step time)",
+        "value": head["eff_tops"],
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "tokens_per_s": head["tokens_per_s"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": T0, "layers": [[l.out_features, l.in_features] for l in cfg.layers],
+                   "bits": cfg.layers[0].bits, "K": cfg.layers[0].K, "gamma": cfg.layers[0].gamma,
+                   "group": cfg.layers[0].group, "split": list(cfg.split),
+                   "macs_per_token": macs_per_token, "expansion_bytes": stream_bytes},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "sweep": sweep,
+        "expand_seconds": expand_s,
+        "input_generation_seconds": gen_s,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,14 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
  * small-batch kernel.  Returns PIPE_EINVAL for other values.                    */
 int pipe_set_kernel(int which);
 
+/* Kernel timing for benchmarks.  While enabled, every forward call brackets its
+ * contraction kernel (the dominant kernel of the path) with a pair of HIP events
+ * recorded on the call's stream.  pipe_timing_read waits for the recorded events,
+ * returns the summed elapsed time and the number of bracketed launches since the
+ * last read, and resets both.  At most 4096 launches are kept between reads.   */
+int pipe_timing_enable(int on);
+int pipe_timing_read(double* total_ms, int* launches);
+
 const char* pipe_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char* pipe_last_device_error(void);

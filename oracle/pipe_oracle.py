@@ -384,8 +384,8 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
     Qx, sx = quantize_activations(x, s_x)
     acc1 = forward_acc(exp1, Qx)
     y1 = dequantize(exp1, acc1, sx, split, bias1, f32)          # [M, T, O1]
-    hs, shs, outs = [], [], []
-    for m, (lo, hi) in enumerate(rngs):
+    hs = []
+    for m in range(len(rngs)):
         if kind == "gelu":
             h = gelu(y1[m])
         elif kind == "gated":
@@ -393,14 +393,31 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
             h = silu_mul(y1[m][:, :H], y1[m][:, H:])
         else:
             raise ValueError("kind must be 'gelu' or 'gated'")
-        Qh, sh = quantize_activations(h)
+        hs.append(h)
+    hs = np.stack(hs)
+    second = mlp_second_layer(exp2, hs, split, bias2)
+    second.update(h=hs, y1=y1, s_x=sx, Qx=Qx)
+    return second
+
+
+def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None):
+    """Last layer of the ensemble on given hidden activations hs [M, T, H]: member m
+    quantizes hs[m] with its own dynamic scale, uses its own orders of exp2 (bias in
+    the first member only), and the members are summed in ascending order.
+    Returns dict(y [T,O2], members [M,T,O2], s_h [M], Qh [M,T,H])."""
+    rngs = member_ranges(exp2.K, split)
+    if hs.shape[0] != len(rngs):
+        raise ValueError("one hidden activation per member")
+    outs, shs, Qhs = [], [], []
+    for m in range(len(rngs)):
+        Qh, sh = quantize_activations(hs[m])
         acc2 = forward_acc(exp2, Qh)
-        # this member's orders only; bias of layer 2 only in the first member
-        y2 = dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m]
-        hs.append(h); shs.append(sh); outs.append(y2)
+        outs.append(dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m])
+        shs.append(sh)
+        Qhs.append(Qh)
     members = np.stack(outs)
-    return dict(y=sum_members(members), members=members, h=np.stack(hs),
-                s_h=np.array(shs, dtype=f32), y1=y1, s_x=sx, Qx=Qx)
+    return dict(y=sum_members(members), members=members, s_h=np.array(shs, dtype=f32),
+                Qh=np.stack(Qhs))
 
 
 # ----------------------------------------------------------------------------

@@ -46,12 +46,14 @@ def _load():
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_timing_enable.argtypes = [ci]
+    lib.pipe_timing_read.argtypes = [C.POINTER(C.c_double), pi]
     lib.pipe_strerror.argtypes = [ci]
     lib.pipe_strerror.restype = C.c_char_p
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
-              "pipe_set_kernel"):
+              "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read"):
         getattr(lib, f).restype = ci
     return lib
 
@@ -213,3 +215,14 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
 
 def pipe_set_kernel(which: int) -> None:
     _check(_lib.pipe_set_kernel(int(which)), "pipe_set_kernel")
+
+
+def pipe_timing_enable(on: bool) -> None:
+    _check(_lib.pipe_timing_enable(1 if on else 0), "pipe_timing_enable")
+
+
+def pipe_timing_read():
+    """(total milliseconds, launches) of the contraction kernels bracketed since the last read."""
+    ms, n = C.c_double(), C.c_int()
+    _check(_lib.pipe_timing_read(C.byref(ms), C.byref(n)), "pipe_timing_read")
+    return ms.value, n.value

@@ -302,8 +302,47 @@ static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
   return PIPE_OK;
 }
 
+// ------------------------------------------------------------------ kernel timing
+static bool g_timing_on = false;
+static std::vector<hipEvent_t> g_events;   // pairs: start, stop
+static size_t g_events_used = 0;
+constexpr size_t MAX_TIMED = 4096;
+
+extern "C" int pipe_timing_enable(int on) {
+  g_timing_on = on != 0;
+  return PIPE_OK;
+}
+
+extern "C" int pipe_timing_read(double* total_ms, int* launches) {
+  double tot = 0.0;
+  for (size_t i = 0; i + 1 < g_events_used; i += 2) {
+    PIPE_HIP(hipEventSynchronize(g_events[i + 1]));
+    float ms = 0.f;
+    PIPE_HIP(hipEventElapsedTime(&ms, g_events[i], g_events[i + 1]));
+    tot += ms;
+  }
+  if (total_ms) *total_ms = tot;
+  if (launches) *launches = (int)(g_events_used / 2);
+  g_events_used = 0;
+  return PIPE_OK;
+}
+
 static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
-  return small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
+  const bool timed = g_timing_on && g_events_used / 2 < MAX_TIMED;
+  if (timed) {
+    while (g_events.size() < g_events_used + 2) {
+      hipEvent_t ev;
+      PIPE_HIP(hipEventCreate(&ev));
+      g_events.push_back(ev);
+    }
+    PIPE_HIP(hipEventRecord(g_events[g_events_used], st));
+  }
+  const int rc = small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
+  if (timed) {
+    PIPE_HIP(hipEventRecord(g_events[g_events_used + 1], st));
+    g_events_used += 2;
+  }
+  return rc;
 }
 
 static void fill_members(GemmArgs& a, int M, const int* lo, const int* hi) {

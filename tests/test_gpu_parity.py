@@ -158,7 +158,19 @@ def test_mlp_parity(pipe, kind):
         ref = po.mlp_forward(o1, o2, kind, x, split=split)
         y, h = pipe.pipe_mlp_forward(g1, g2, act, dev(x), split=split, return_hidden=True)
         # layer 1 + activation: same integer state, device libm within a few ulp
-        assert_close_fp32(h.cpu().numpy(), ref["h"], tol=1e-5)
-        # chained output: a hidden value a few ulp off may flip a code of Q(h)
-        assert_close_fp32(y.cpu().numpy(), ref["y"])
+        hg = h.cpu().numpy()
+        assert_close_fp32(hg, ref["h"], tol=1e-5)
+        # layer 2 inside the chain, on identical input: the checker's last layer fed the
+        # GPU's own hidden activations
+        ref2 = po.mlp_second_layer(o2, hg, split=split)
+        assert_close_fp32(y.cpu().numpy(), ref2["y"])
+        # end to end: a hidden value a few ulp off can flip a code of Q(h); with heavy-tailed
+        # hidden activations one flip is worth s_h * |w|, so the 1e-3 bar applies when no
+        # code flipped and a loose bar otherwise
+        flips = int((ref2["Qh"] != ref["Qh"]).sum())
+        assert flips <= 1e-4 * ref["Qh"].size
+        if flips == 0:
+            assert_close_fp32(y.cpu().numpy(), ref["y"])
+        else:
+            assert_close_fp32(y.cpu().numpy(), ref["y"], tol=3e-2, elementwise=False)
     g1.free(); g2.free()
