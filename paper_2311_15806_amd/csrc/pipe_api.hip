@@ -101,6 +101,7 @@ static void free_expansion(pipe_expansion* e) {
   }
   if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
   if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
+  if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->packed_ptrs_dev) (void)hipFree((void*)e->packed_ptrs_dev);
   if (e->scale_ptrs_dev) (void)hipFree((void*)e->scale_ptrs_dev);
   delete e;
@@ -141,6 +142,41 @@ static int build_schedule(pipe_expansion* e) {
   PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
   PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));
   PIPE_HIP(hipMemcpy(e->ct_src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice));
+  // Bins of the weight-streaming kernel: output row blocks, most orders first, packed
+  // first-fit into bins of `cap` stored row blocks.
+  {
+    const int cap = std::min(STREAM_BIN_CAP, std::max(4, K));
+    std::vector<StreamBin> bins;
+    std::vector<int> room;
+    for (int i = 0; i < n_rb; ++i) {
+      const int rb = items[i].rb, pop = items[i].pop;
+      const int g = rb / rbpg, b = rb % rbpg;
+      int which = -1;
+      for (int j = (int)bins.size() - 1; j >= 0 && j >= (int)bins.size() - 64; --j)
+        if (room[j] >= pop) { which = j; break; }
+      if (which < 0) {
+        StreamBin nb;
+        std::memset(&nb, 0, sizeof(nb));
+        bins.push_back(nb);
+        room.push_back(cap);
+        which = (int)bins.size() - 1;
+      }
+      StreamBin& bn = bins[which];
+      const int slot = bn.n_out++;
+      bn.out_rb[slot] = rb;
+      for (int k = 0; k < K; ++k) {
+        if (slot_of[k][g] < 0) continue;
+        const int it = bn.n_items++;
+        bn.k[it] = k;
+        bn.crb[it] = slot_of[k][g] * rbpg + b;
+        bn.slot[it] = slot;
+      }
+      room[which] -= pop;
+    }
+    e->n_bins = (int)bins.size();
+    PIPE_HIP(hipMalloc(&e->bins_dev, bins.size() * sizeof(StreamBin)));
+    PIPE_HIP(hipMemcpy(e->bins_dev, bins.data(), bins.size() * sizeof(StreamBin), hipMemcpyHostToDevice));
+  }
   std::vector<const uint8_t*> pp(K);
   std::vector<const float*> sp(K);
   for (int k = 0; k < K; ++k) { pp[k] = e->orders[k].packed_dev; sp[k] = e->orders[k].scales_dev; }
@@ -277,7 +313,6 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
 
 // ------------------------------------------------------------------ forward
 static bool use_stream_kernel(int T) {
-  if (true) return false;  // the streaming kernel is not wired in yet
   if (g_kernel_choice == 1) return false;
   if (g_kernel_choice == 2) return T <= 16;
   return T <= 16;
@@ -523,6 +558,3 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   fill_members(a2, Mm, lo, hi);
   return run_gemm(a2, small, st);
 }
-
-// Until the weight-streaming kernel is selected the tiled kernel serves every token count.
-__attribute__((weak)) int launch_gemm_stream(const GemmArgs& a, hipStream_t st) { return launch_gemm_tiled(a, st); }

@@ -37,6 +37,18 @@ constexpr int NRB_TILE = 8;    // row blocks per column tile of the tiled kernel
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
+// A bin of the weight-streaming kernel: up to STREAM_BIN_CAP stored row blocks that together
+// hold every order of n_out output row blocks (items of one output row block are adjacent and
+// in ascending order k).
+constexpr int STREAM_BIN_CAP = 16;
+struct StreamBin {
+  int32_t n_items, n_out;
+  int32_t k[STREAM_BIN_CAP];       // 0-based order of the item
+  int32_t crb[STREAM_BIN_CAP];     // compact row block inside that order
+  int32_t slot[STREAM_BIN_CAP];    // index into out_rb
+  int32_t out_rb[STREAM_BIN_CAP];  // output row block (channel / 16)
+};
+
 struct PipeOrder {
   int n_kept = 0;               // groups stored at this order
   int32_t* gids_dev = nullptr;  // [n_kept] ascending
@@ -64,6 +76,9 @@ struct pipe_expansion {
   // per order device pointers for kernels
   const uint8_t** packed_ptrs_dev = nullptr;  // [K]
   const float** scale_ptrs_dev = nullptr;     // [K]
+  // bins of the weight-streaming kernel
+  int n_bins = 0;
+  StreamBin* bins_dev = nullptr;
   int64_t stream_bytes = 0;  // packed codes + scales + indices
 };
 

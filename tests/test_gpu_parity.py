@@ -142,10 +142,35 @@ def test_conv2d_parity(pipe):
     g.free()
 
 
+def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
+    """Both kernels fold the orders in the same fixed order, so on a decode-sized batch their
+    fp32 outputs are bit-identical."""
+    O, I, T = 384, 1024, 13
+    W, x = _w(500, O, I), _x(501, T, I)
+    b = np.random.default_rng(502).standard_normal(O).astype(f32)
+    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16)]:
+        g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+        outs = []
+        for which in (1, 2):
+            pipe.pipe_set_kernel(which)
+            try:
+                split = [1] * K
+                y = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b)).cpu().numpy()
+                ym = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b), reduce_members=False).cpu().numpy()
+                acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+                outs.append((y, ym, acc.cpu().numpy()))
+            finally:
+                pipe.pipe_set_kernel(0)
+        for a, c in zip(outs[0], outs[1]):
+            assert np.array_equal(a, c)
+        g.free()
+
+
+@pytest.mark.parametrize("tokens", [150, 9])
 @pytest.mark.parametrize("kind", ["gelu", "gated"])
-def test_mlp_parity(pipe, kind):
+def test_mlp_parity(pipe, kind, tokens):
     base = wl.C3 if kind == "gelu" else wl.C5
-    w = wl.scaled(base, out_div=8, in_div=8, tokens=150)
+    w = wl.scaled(base, out_div=8, in_div=8, tokens=tokens)
     l1, l2 = w.layers
     W1, W2, x = wl.make_weight(w, 0), wl.make_weight(w, 1), wl.make_input(w)
     o1, o2 = oracle_expand(W1, l1), oracle_expand(W2, l2)
