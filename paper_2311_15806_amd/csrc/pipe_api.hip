@@ -129,14 +129,15 @@ static int build_schedule(pipe_expansion* e) {
     return a.rb < b.rb;
   });
   e->n_ct = ceil_div(n_rb, NRB_TILE);
-  std::vector<int32_t> rb_out((size_t)e->n_ct * NRB_TILE, -1);
-  std::vector<int32_t> src((size_t)e->n_ct * K * NRB_TILE, -1);
+  e->n_sorted = (int)round_up64(n_rb, 64);
+  std::vector<int32_t> rb_out((size_t)e->n_sorted, -1);
+  std::vector<int32_t> src((size_t)K * e->n_sorted, -1);
   for (int i = 0; i < n_rb; ++i) {
-    const int ct = i / NRB_TILE, r = i % NRB_TILE, rb = items[i].rb;
+    const int rb = items[i].rb;
     const int g = rb / rbpg, b = rb % rbpg;
-    rb_out[(size_t)ct * NRB_TILE + r] = rb;
+    rb_out[i] = rb;
     for (int k = 0; k < K; ++k)
-      if (slot_of[k][g] >= 0) src[((size_t)ct * K + k) * NRB_TILE + r] = slot_of[k][g] * rbpg + b;
+      if (slot_of[k][g] >= 0) src[(size_t)k * e->n_sorted + i] = slot_of[k][g] * rbpg + b;
   }
   PIPE_HIP(hipMalloc(&e->ct_rb_out_dev, rb_out.size() * 4));
   PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
@@ -327,7 +328,7 @@ struct ActBuffers {
 };
 
 static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
-  b->T_pad = (int)round_up64(T, small ? 16 : 128);
+  b->T_pad = (int)round_up64(T, small ? 16 : TOK_TILE);
   b->qx = (uint8_t*)pipe_ws_get(WS_QX, (size_t)b->T_pad * in_pad);
   b->rowsum = (int32_t*)pipe_ws_get(WS_ROWSUM, (size_t)b->T_pad * 4);
   uint8_t* sc = (uint8_t*)pipe_ws_get(WS_SCAL, 4096);

@@ -2,26 +2,32 @@
 //   y[t,o] = sum_m ( s_x,m * sum_{k in member m} s_k[o] * acc_k[t,o]  (+ b[o] if m = 0) )
 //   acc_k[t,o] = sum_i Qx[t,i] * q_k[o,i]          (exact, int32)
 //
-// One workgroup (4 waves) owns 128 tokens x 8 row blocks (128 stored channels).  The row
-// blocks of a column tile were sorted at expansion time by the set of orders that hold them,
-// so the loop over orders does uniform work; a row block that an order pruned is skipped
-// (no load, no MFMA).  Packed 4-bit / ternary codes are streamed from HBM with 16-byte
-// coalesced loads, widened to int8 with a shift and a mask, and staged in LDS in the
-// register layout of v_mfma_i32_16x16x64_i8 (A operand = 16 channels x 64 k, B operand = 16
-// tokens x 64 k, D = 4 consecutive channels x 1 token per lane).  Codes are stored
-// offset-binary; the offset is removed exactly in the epilogue with the token's code sum.
-// Per order the int32 accumulators are folded into an fp32 running sum with the row-wise
-// scale; the activation scale, the bias, the optional GELU and the member sum are applied once.
+// One workgroup (4 waves) owns MT = 16*MTB tokens x 4*NRW row blocks (16 stored channels
+// each).  Every wave multiplies ALL MT tokens with its OWN NRW row blocks, so
+//   - packed 4-bit / ternary codes never pass through LDS: each wave streams the 1-KiB tiles
+//     of its row blocks from L2/HBM with one coalesced 16-byte load per lane, keeps them
+//     packed in registers and widens them to int8 (shift + mask, offset-binary codes) right
+//     before the MFMA that consumes them;
+//   - only the int8 activation tile is staged in LDS (double buffered, one barrier per 256 k),
+//     already in the register layout of the B operand of v_mfma_i32_16x16x64_i8, so LDS reads
+//     are lane-linear 16-byte reads without bank conflicts.
+// The row blocks of a column tile were sorted at expansion time by the set of orders that
+// hold them, so the loop over orders does uniform work; a row block that an order pruned is
+// skipped (no load, no MFMA).  Per order the int32 accumulators (minus offset * token code
+// sum, exact) are folded into an fp32 running sum with the row-wise scale; activation scale,
+// bias, optional GELU and the member sum are applied once in the epilogue.
+// Workgroups are mapped to (column tile, token tile) in 8x8 super-tiles per XCD so that the
+// 64 workgroups resident on one XCD share 8 weight strips and 8 activation strips in its L2.
+#include <cstdlib>
+
 #include "pipe_internal.h"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int TT = 128;               // tokens per tile
-constexpr int NTB = TT / 16;          // token blocks per tile
-constexpr int STAGE_STEPS = 2;        // 64-k steps per LDS stage
-constexpr int FRAG = 64;              // uint4 per fragment
+constexpr int S = 4;       // 64-k steps per LDS stage (256 k)
+constexpr int FRAG = 64;   // uint4 per fragment
 
 struct TiledParams {
   const uint8_t* qx;
@@ -30,15 +36,17 @@ struct TiledParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* const* packed;   // [K]
-  const float* const* scales;     // [K]
-  const int32_t* ct_rb_out;       // [n_ct][NRB_TILE]
-  const int32_t* ct_src;          // [n_ct][K][NRB_TILE]
+  const uint8_t* packed[PIPE_MAX_K];
+  const float* scales[PIPE_MAX_K];
+  const int32_t* rb_out;          // [n_sorted] output row block of sorted position i, or -1
+  const int32_t* rb_src;          // [K][n_sorted] compact row block in order k, or -1
+  int n_sorted;                   // padded to a multiple of 64
   const float* bias;
   float* y;
   int32_t* acc_out;
   uint32_t* amax_out;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
+  int n_st_t;                     // super-tiles along tokens
   int member_lo[PIPE_MAX_K];
   int member_hi[PIPE_MAX_K];
 };
@@ -47,160 +55,196 @@ __device__ __forceinline__ float gelu_erf(float a) {
   return 0.5f * a * (1.f + erff(a * 0.70710678118654752440f));
 }
 
-template <int BITS, bool ACC_OUT>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(const TiledParams p) {
+template <int BITS>
+struct WRegs {
+  static constexpr int N = BITS == 2 ? 1 : (BITS == 4 ? 2 : 4);   // uint4 per row block per stage
+  uint4 v[N];
+};
+
+template <int N>
+struct XRegs {
+  uint4 v[N];
+};
+
+template <int BITS>
+__device__ __forceinline__ v4i widen(const WRegs<BITS>& w, int j) {
+  if (BITS == 8) {
+    const uint4 a = w.v[j & (WRegs<BITS>::N - 1)];
+    return v4i{(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+  } else if (BITS == 4) {
+    const uint4 q = w.v[(j >> 1) & (WRegs<BITS>::N - 1)];
+    const uint32_t a = (j & 1) ? q.z : q.x, b = (j & 1) ? q.w : q.y;
+    return v4i{(int)(a & 0x0F0F0F0Fu), (int)((a >> 4) & 0x0F0F0F0Fu), (int)(b & 0x0F0F0F0Fu), (int)((b >> 4) & 0x0F0F0F0Fu)};
+  } else {
+    const uint4 q = w.v[0];
+    const uint32_t a = j == 0 ? q.x : (j == 1 ? q.y : (j == 2 ? q.z : q.w));
+    return v4i{(int)(a & 0x03030303u), (int)((a >> 2) & 0x03030303u), (int)((a >> 4) & 0x03030303u), (int)((a >> 6) & 0x03030303u)};
+  }
+}
+
+// uniform dynamic index into a kernel-argument array without forcing it into scratch memory
+template <class T>
+__device__ __forceinline__ T pick(const T (&a)[PIPE_MAX_K], int k) {
+  T v = a[0];
+#pragma unroll
+  for (int i = 1; i < PIPE_MAX_K; ++i) v = (i == k) ? a[i] : v;
+  return v;
+}
+
+enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2 };
+
+template <int BITS, int MTB, int NRW, int MINW, int MODE>
+__global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams p) {
+  constexpr bool ACC_OUT = MODE == MODE_ACC_OUT;
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
-  __shared__ uint4 Xs[2][NTB * STAGE_STEPS * FRAG];       // 2 x 16 KiB
-  __shared__ uint4 Ws[2][NRB_TILE * STAGE_STEPS * FRAG];  // 2 x 16 KiB
+  constexpr int WN = WRegs<BITS>::N;
+  constexpr int NRB_WG = 4 * NRW;
+  constexpr int XCOPY = MTB * S / 4;              // activation fragments per wave per stage
+  static_assert(TOK_TILE % (16 * MTB) == 0 || (16 * MTB) % TOK_TILE == 0, "token tile");
+  __shared__ uint4 Xs[2][MTB * S * FRAG];
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int wm = wave & 1;   // token half: token blocks 4*wm .. 4*wm+3
-  const int wn = wave >> 1;  // row-block half: row blocks 4*wn .. 4*wn+3
-  const int ct = blockIdx.x / p.n_tt;
-  const int tt = blockIdx.x - ct * p.n_tt;
-  const int t0 = tt * TT;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+
+  // ---- (column tile, token tile) from blockIdx: 8x8 super-tiles, one per XCD at a time ----
+  int ct, tt;
+  {
+    const int i = blockIdx.x;
+    const int xcd = i & 7, j = i >> 3;
+    const int sidx = (j >> 6) * 8 + xcd, local = j & 63;
+    const int sc = sidx / p.n_st_t, st = sidx - sc * p.n_st_t;
+    ct = sc * 8 + (local >> 3);
+    tt = st * 8 + (local & 7);
+    if (ct >= p.n_ct || tt >= p.n_tt) return;
+  }
+  const int t0 = tt * (16 * MTB);
   const int nksup = (p.nks * 64) / KSUP;
-  const int n_stage = p.nks / STAGE_STEPS;
+  const int n_stage = p.nks / S;
 
-  int rb_out[4];
+  int rb_out[NRW];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) rb_out[r] = p.ct_rb_out[ct * NRB_TILE + 4 * wn + r];
+  for (int r = 0; r < NRW; ++r) rb_out[r] = __builtin_amdgcn_readfirstlane(p.rb_out[ct * NRB_WG + wave * NRW + r]);
 
-  float ytot[4][4][4];
+  const bool fold_sx = p.reduce && p.M > 1;   // multi-member sum: fold s_x into the row scale
+  float yacc[NRW][MTB][4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+  for (int r = 0; r < NRW; ++r)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < MTB; ++b)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ytot[r][b][i] = 0.f;
+      for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
 
   for (int m = 0; m < p.M; ++m) {
-    const uint8_t* qx = p.qx + (size_t)m * p.qx_mstride;
+    const uint4* qx = reinterpret_cast<const uint4*>(p.qx + (size_t)m * p.qx_mstride);
     const int32_t* rowsum = p.rowsum + (size_t)m * p.rowsum_mstride;
-    float yacc[4][4][4];
+    const float sx = p.s_x[m * p.sx_mstride];
+    int rs[MTB];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-      for (int b = 0; b < 4; ++b)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
-    int rs[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) rs[b] = OFF ? rowsum[t0 + (4 * wm + b) * 16 + (lane & 15)] : 0;
+    for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
 
-    for (int k = p.member_lo[m]; k <= p.member_hi[m]; ++k) {
-      // which row blocks of this column tile does order k hold?
-      const int32_t* srcp = p.ct_src + ((size_t)ct * p.K + k) * NRB_TILE;
-      int src_ld[2];   // the two row blocks this wave loads: 2*wave, 2*wave+1
-      src_ld[0] = srcp[2 * wave];
-      src_ld[1] = srcp[2 * wave + 1];
-      int src_mm[4];   // the four row blocks this wave multiplies
-      bool any = false;
+    const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
+    for (int k = k_lo; k <= k_hi; ++k) {
+      const int32_t* srcp = p.rb_src + (size_t)k * p.n_sorted + ct * NRB_WG;
+      int any = 0;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) src_mm[r] = srcp[4 * wn + r];
+      for (int r = 0; r < NRB_WG; ++r) any |= srcp[r] >= 0 ? 1 : 0;
+      if (!__builtin_amdgcn_readfirstlane(any)) continue;   // uniform over the workgroup
+      const uint8_t* pk = pick(p.packed, k);
+      const float* sck = pick(p.scales, k);
+      int src[NRW];
+      const uint4* wp[NRW];
 #pragma unroll
-      for (int r = 0; r < NRB_TILE; ++r) any |= srcp[r] >= 0;
-      if (!any) continue;   // uniform over the workgroup
-      const uint8_t* pk = p.packed[k];
-
-      v4i acc[4][4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[r][b] = v4i{0, 0, 0, 0};
-
-      uint4 xr[4];
-      uint4 wr[2][2];
-      auto gload = [&](int s) {
-        // activations: 16 fragments per stage, 4 per wave
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-          const int idx = wave * 4 + f;             // = tb*2 + j
-          const int tb = idx >> 1, j = idx & 1;
-          const uint4* g = reinterpret_cast<const uint4*>(
-              qx + ((size_t)(t0 / 16 + tb) * p.nks + (s * STAGE_STEPS + j)) * 1024);
-          xr[f] = g[lane];
-        }
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          if (src_ld[q] < 0) continue;
-          if (BITS == 8) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-              wr[q][j] = reinterpret_cast<const uint4*>(pk + ((size_t)src_ld[q] * nksup + (s * 2 + j)) * 1024)[lane];
-          } else if (BITS == 4) {
-            wr[q][0] = reinterpret_cast<const uint4*>(pk + ((size_t)src_ld[q] * nksup + s) * 1024)[lane];
-          } else {
-            const uint2 v = reinterpret_cast<const uint2*>(pk + ((size_t)src_ld[q] * nksup + (s >> 1)) * 1024)[lane * 2 + (s & 1)];
-            wr[q][0].x = v.x;
-            wr[q][0].y = v.y;
-          }
-        }
-      };
-      auto lstore = [&](int buf) {
-#pragma unroll
-        for (int f = 0; f < 4; ++f) Xs[buf][(wave * 4 + f) * FRAG + lane] = xr[f];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          if (src_ld[q] < 0) continue;
-          const int rb = 2 * wave + q;
-          uint4 o0, o1;
-          if (BITS == 8) {
-            o0 = wr[q][0];
-            o1 = wr[q][1];
-          } else if (BITS == 4) {
-            const uint4 w = wr[q][0];
-            o0 = make_uint4(w.x & 0x0F0F0F0Fu, (w.x >> 4) & 0x0F0F0F0Fu, w.y & 0x0F0F0F0Fu, (w.y >> 4) & 0x0F0F0F0Fu);
-            o1 = make_uint4(w.z & 0x0F0F0F0Fu, (w.z >> 4) & 0x0F0F0F0Fu, w.w & 0x0F0F0F0Fu, (w.w >> 4) & 0x0F0F0F0Fu);
-          } else {
-            const uint32_t a = wr[q][0].x, b = wr[q][0].y;
-            o0 = make_uint4(a & 0x03030303u, (a >> 2) & 0x03030303u, (a >> 4) & 0x03030303u, (a >> 6) & 0x03030303u);
-            o1 = make_uint4(b & 0x03030303u, (b >> 2) & 0x03030303u, (b >> 4) & 0x03030303u, (b >> 6) & 0x03030303u);
-          }
-          Ws[buf][(rb * 2 + 0) * FRAG + lane] = o0;
-          Ws[buf][(rb * 2 + 1) * FRAG + lane] = o1;
-        }
-      };
-
-      gload(0);
-      for (int s = 0; s < n_stage; ++s) {
-        const int buf = s & 1;
-        lstore(buf);
-        __syncthreads();
-        if (s + 1 < n_stage) gload(s + 1);
-#pragma unroll
-        for (int j = 0; j < STAGE_STEPS; ++j) {
-          v4i xf[4];
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const uint4 v = Xs[buf][((4 * wm + b) * 2 + j) * FRAG + lane];
-            xf[b] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (src_mm[r] < 0) continue;
-            const uint4 v = Ws[buf][((4 * wn + r) * 2 + j) * FRAG + lane];
-            const v4i wf = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[b], acc[r][b], 0, 0, 0);
-          }
-        }
+      for (int r = 0; r < NRW; ++r) {
+        src[r] = __builtin_amdgcn_readfirstlane(srcp[wave * NRW + r]);
+        wp[r] = reinterpret_cast<const uint4*>(pk + (size_t)(src[r] < 0 ? 0 : src[r]) * nksup * 1024) + lane;
       }
+
+      v4i acc[NRW][MTB];
+#pragma unroll
+      for (int r = 0; r < NRW; ++r)
+#pragma unroll
+        for (int b = 0; b < MTB; ++b) acc[r][b] = v4i{0, 0, 0, 0};
+
+      // A wave whose row blocks are all pruned at this order only helps staging the
+      // activations; otherwise it multiplies all its row blocks (a pruned one among them reads
+      // row block 0 and its result is dropped).
+      bool active = false;
+#pragma unroll
+      for (int r = 0; r < NRW; ++r) active |= src[r] >= 0;
+
+      WRegs<BITS> w0[NRW], w1[NRW];
+      // activations: global -> LDS without passing through registers; one 1-KiB fragment per
+      // wave-wide load, XCOPY fragments per wave and stage
+      auto xload = [&](int s, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int f = 0; f < XCOPY; ++f) {
+          const int idx = wave * XCOPY + f;          // fragment (b, j) = (idx / S, idx % S)
+          const int b = idx / S, j = idx - b * S;
+          const uint4* g = qx + ((size_t)(t0 / 16 + b) * p.nks + (size_t)s * S + j) * FRAG + lane;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                           (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
+        }
+      };
+      auto gload_w = [&](int s, WRegs<BITS>(&w)[NRW]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NRW; ++r)
+#pragma unroll
+          for (int q = 0; q < WN; ++q) w[r].v[q] = wp[r][(size_t)(s * WN + q) * FRAG];
+      };
+      // one stage: wait for this stage's tiles, prefetch the next stage, multiply this one
+      auto stage = [&](int s, WRegs<BITS>(&cur)[NRW], WRegs<BITS>(&nxt)[NRW]) __attribute__((always_inline)) {
+        const int buf = s & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-direct loads have landed
+        __syncthreads();                      // everyone's have, and buffer buf^1 is free again
+        if (s + 1 < n_stage) {
+          xload(s + 1, buf ^ 1);
+          if (active) gload_w(s + 1, nxt);
+        }
+        if (active) {
+#pragma unroll
+          for (int j = 0; j < S; ++j) {
+            v4i xf[MTB];
+#pragma unroll
+            for (int b = 0; b < MTB; ++b) {
+              const uint4 v = Xs[buf][(b * S + j) * FRAG + lane];
+              xf[b] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+            }
+#pragma unroll
+            for (int r = 0; r < NRW; ++r) {
+              const v4i wf = widen<BITS>(cur[r], j);
+#pragma unroll
+              for (int b = 0; b < MTB; ++b)
+                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[b], acc[r][b], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the 64-k steps apart: bounds live registers
+          }
+        }
+      };
+
+      xload(0, 0);
+      if (active) gload_w(0, w0);
+      int s = 0;
+      for (; s + 1 < n_stage; s += 2) {
+        stage(s, w0, w1);
+        stage(s + 1, w1, w0);
+      }
+      if (s < n_stage) stage(s, w0, w1);
       __syncthreads();
 
       // fold this order: yacc += s_k[o] * float(acc - OFF * rowsum)
-      const float* sck = p.scales[k];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (src_mm[r] < 0) continue;
-        const float4 sc = *reinterpret_cast<const float4*>(sck + (size_t)src_mm[r] * 16 + 4 * (lane >> 4));
-        const float scv[4] = {sc.x, sc.y, sc.z, sc.w};
+      for (int r = 0; r < NRW; ++r) {
+        if (src[r] < 0) continue;
+        const float4 sc = *reinterpret_cast<const float4*>(sck + (size_t)src[r] * 16 + 4 * (lane >> 4));
+        float scv[4] = {sc.x, sc.y, sc.z, sc.w};
+        if (fold_sx) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int t = t0 + (4 * wm + b) * 16 + (lane & 15);
+          for (int i = 0; i < 4; ++i) scv[i] *= sx;
+        }
+#pragma unroll
+        for (int b = 0; b < MTB; ++b) {
+          const int t = t0 + b * 16 + (lane & 15);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int a = acc[r][b][i] - OFF * rs[b];
@@ -215,33 +259,32 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const TiledParams p) {
     }  // orders of the member
 
     if (ACC_OUT) continue;
-    // member epilogue
-    const float sx = p.s_x[m * p.sx_mstride];
+    if (fold_sx && m + 1 < p.M) continue;   // keep accumulating into the same running sum
+    // member (or final) epilogue
     float mx = 0.f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < NRW; ++r) {
       if (rb_out[r] < 0) continue;
       const int ch = rb_out[r] * 16 + 4 * (lane >> 4);
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (m == 0 && p.bias != nullptr) {
+      if ((m == 0 || fold_sx) && p.bias != nullptr) {
         const float4 b4 = *reinterpret_cast<const float4*>(p.bias + ch);
         bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
       }
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const int t = t0 + (4 * wm + b) * 16 + (lane & 15);
+      for (int b = 0; b < MTB; ++b) {
+        const int t = t0 + b * 16 + (lane & 15);
         float v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          v[i] = sx * yacc[r][b][i] + bv[i];
-          if (p.act == PIPE_ACT_GELU) v[i] = gelu_erf(v[i]);
+          v[i] = (fold_sx ? yacc[r][b][i] : sx * yacc[r][b][i]) + bv[i];
+          if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
           if (t < p.T) mx = fmaxf(mx, fabsf(v[i]));
+          yacc[r][b][i] = 0.f;
         }
-        if (p.reduce) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) ytot[r][b][i] = (m == 0) ? v[i] : ytot[r][b][i] + v[i];
-        } else if (t < p.T) {
-          *reinterpret_cast<float4*>(p.y + ((size_t)m * p.T + t) * p.out + ch) = make_float4(v[0], v[1], v[2], v[3]);
+        if (t < p.T) {
+          float* dst = p.y + ((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + ch;
+          *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         }
       }
     }
@@ -251,30 +294,22 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const TiledParams p) {
       if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
     }
   }  // members
-
-  if (!ACC_OUT && p.reduce) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      if (rb_out[r] < 0) continue;
-      const int ch = rb_out[r] * 16 + 4 * (lane >> 4);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const int t = t0 + (4 * wm + b) * 16 + (lane & 15);
-        if (t < p.T)
-          *reinterpret_cast<float4*>(p.y + (size_t)t * p.out + ch) =
-              make_float4(ytot[r][b][0], ytot[r][b][1], ytot[r][b][2], ytot[r][b][3]);
-      }
-    }
-  }
 }
 
-template <int BITS>
-int launch_bits(const TiledParams& p, bool acc_out, hipStream_t st) {
-  const dim3 grid((unsigned)(p.n_ct * p.n_tt));
+template <int BITS, int MTB, int NRW, int MINW>
+int launch_cfg(TiledParams& p, bool acc_out, hipStream_t st) {
+  p.n_tt = ceil_div(p.T, 16 * MTB);
+  p.n_ct = ceil_div(p.n_ct * NRB_TILE, 4 * NRW);   // column tiles of this variant's width
+  p.n_st_t = ceil_div(p.n_tt, 8);
+  const int n_st_c = ceil_div(p.n_ct, 8);
+  // super-tile sidx runs on XCD sidx % 8 as blocks xcd + 8*(64*(sidx/8) + local), local = 0..63
+  const dim3 grid((unsigned)(ceil_div(p.n_st_t * n_st_c, 8) * 8 * 64));
   if (acc_out)
-    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, true>), grid, dim3(256), 0, st, p);
+    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), 0, st, p);
+  else if (p.act == PIPE_ACT_GELU)
+    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GELU>), grid, dim3(256), 0, st, p);
   else
-    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, false>), grid, dim3(256), 0, st, p);
+    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_PLAIN>), grid, dim3(256), 0, st, p);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -284,23 +319,31 @@ int launch_bits(const TiledParams& p, bool acc_out, hipStream_t st) {
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   const pipe_expansion* e = a.e;
   if (a.T <= 0) return PIPE_OK;
-  if (a.T_pad % TT != 0) return PIPE_ESHAPE;
+  if (a.T_pad % TOK_TILE != 0 || a.T_pad < a.T) return PIPE_ESHAPE;
   TiledParams p;
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
-  p.packed = e->packed_ptrs_dev; p.scales = e->scale_ptrs_dev;
-  p.ct_rb_out = e->ct_rb_out_dev; p.ct_src = e->ct_src_dev;
+  for (int k = 0; k < PIPE_MAX_K; ++k) {
+    p.packed[k] = k < e->K ? e->orders[k].packed_dev : nullptr;
+    p.scales[k] = k < e->K ? e->orders[k].scales_dev : nullptr;
+  }
+  p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.n_sorted = e->n_sorted;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
-  p.n_tt = ceil_div(a.T, TT); p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
+  p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   for (int m = 0; m < PIPE_MAX_K; ++m) { p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m]; }
   const bool acc_out = a.acc_out != nullptr;
-  switch (e->bits) {
-    case 8: return launch_bits<8>(p, acc_out, st);
-    case 4: return launch_bits<4>(p, acc_out, st);
-    default: return launch_bits<2>(p, acc_out, st);
+  static const int variant = [] { const char* v = getenv("PIPE_TILE_VARIANT"); return v ? atoi(v) : 0; }();
+  if (a.T_pad % 128 != 0 && variant == 2) return PIPE_ESHAPE;
+  switch (e->bits * 10 + variant) {
+    case 80: case 81: case 82: return launch_cfg<8, 4, 4, 1>(p, acc_out, st);
+    case 40: return launch_cfg<4, 4, 4, 2>(p, acc_out, st);
+    case 41: return launch_cfg<4, 4, 8, 1>(p, acc_out, st);
+    case 42: return launch_cfg<4, 8, 4, 1>(p, acc_out, st);
+    case 20: return launch_cfg<2, 4, 4, 2>(p, acc_out, st);
+    case 21: return launch_cfg<2, 4, 8, 1>(p, acc_out, st);
+    case 22: return launch_cfg<2, 8, 4, 1>(p, acc_out, st);
+    default: return PIPE_EINVAL;
   }
 }
-
-// The weight-streaming small-batch kernel lives in pipe_gemv.hip.

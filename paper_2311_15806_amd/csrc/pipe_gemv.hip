@@ -27,8 +27,8 @@ struct StreamParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* const* packed;
-  const float* const* scales;
+  const uint8_t* packed[PIPE_MAX_K];
+  const float* scales[PIPE_MAX_K];
   const StreamBin* bins;
   const float* bias;
   float* y;
@@ -140,21 +140,28 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
   for (int o = threadIdx.x >> 8; o < bin.n_out; o += (NW * 64) / 256) {
     const int orb = bin.out_rb[o];
     const int col = orb * 16 + ch;
-    float ytot = 0.f;
+    // Evaluation order (same as the tiled kernel): one member, or members kept apart:
+    // y_m = s_x,m * (sum_k s_k * a_k) + b;  members summed: y = sum_m sum_k (s_k * s_x,m) * a_k + b.
+    const bool fold_sx = p.reduce && p.M > 1;
+    float yacc = 0.f;
     for (int m = 0; m < p.M; ++m) {
       const int rs = OFF ? p.rowsum[(size_t)m * p.rowsum_mstride + t] : 0;
-      float yacc = 0.f;
+      const float sx = p.s_x[m * p.sx_mstride];
       for (int it = 0; it < n_items; ++it) {      // items of a row block are stored in ascending order k
         const int k = bin.k[it];
         if (bin.slot[it] != o || k < p.member_lo[m] || k > p.member_hi[m]) continue;
         const int a = fin[it][fidx] - OFF * rs;
-        yacc = fmaf(p.scales[k][(size_t)bin.crb[it] * 16 + ch], (float)a, yacc);
+        float sc = p.scales[k][(size_t)bin.crb[it] * 16 + ch];
+        if (fold_sx) sc *= sx;
+        yacc = fmaf(sc, (float)a, yacc);
         if (ACC_OUT) {
           if (t < p.T) p.acc_out[((size_t)k * p.T + t) * p.out + col] = a;
         }
       }
       if (ACC_OUT) continue;
-      float v = p.s_x[m * p.sx_mstride] * yacc + ((m == 0 && p.bias != nullptr) ? p.bias[col] : 0.f);
+      if (fold_sx && m + 1 < p.M) continue;
+      float v = (fold_sx ? yacc : sx * yacc) + (((m == 0 || fold_sx) && p.bias != nullptr) ? p.bias[col] : 0.f);
+      yacc = 0.f;
       if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
       if (p.amax_out != nullptr) {
         float mx = t < p.T ? fabsf(v) : 0.f;
@@ -162,10 +169,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
         for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
         if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
       }
-      if (p.reduce) ytot = (m == 0) ? v : ytot + v;
-      else if (t < p.T) p.y[((size_t)m * p.T + t) * p.out + col] = v;
+      if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
     }
-    if (!ACC_OUT && p.reduce && t < p.T) p.y[(size_t)t * p.out + col] = ytot;
   }
 }
 
@@ -193,7 +198,10 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
-  p.packed = e->packed_ptrs_dev; p.scales = e->scale_ptrs_dev;
+  for (int k = 0; k < PIPE_MAX_K; ++k) {
+    p.packed[k] = k < e->K ? e->orders[k].packed_dev : nullptr;
+    p.scales[k] = k < e->K ? e->orders[k].scales_dev : nullptr;
+  }
   p.bins = e->bins_dev;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;

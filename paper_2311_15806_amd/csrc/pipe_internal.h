@@ -9,7 +9,7 @@
 // ---------------------------------------------------------------------------------------
 // Data layout in HBM
 //
-// Quantized activations ("fragment layout"): tokens are padded to a multiple of TOK_PAD and
+// Quantized activations ("fragment layout"): tokens are padded to a multiple of TOK_TILE (16 for the streaming kernel) and
 // in_features to a multiple of IN_PAD (pad entries are 0).  A fragment holds 16 tokens x 64
 // consecutive k as 64 lanes x 16 bytes: lane = kc*16 + n holds token n, k = 64*ks + 16*kc + e,
 // e = 0..15.  Fragments are stored [token_block][ks], 1 KiB each, so that one wave reads a
@@ -30,9 +30,9 @@
 // ---------------------------------------------------------------------------------------
 constexpr int PIPE_MAX_K = 16;
 constexpr int IN_PAD = 256;    // in_features padded to this (largest KSUP)
-constexpr int TOK_PAD = 256;   // tokens padded to this (largest token tile)
+constexpr int TOK_TILE = 128;  // token padding of the tiled kernel's buffers (largest token tile)
 constexpr int RB = 16;         // rows per row block
-constexpr int NRB_TILE = 8;    // row blocks per column tile of the tiled kernel
+constexpr int NRB_TILE = 16;   // row blocks per column tile of the tiled kernel
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -70,9 +70,10 @@ struct pipe_expansion {
   std::vector<PipeOrder> orders;
   // Tile schedule.  Row blocks are sorted by the set of orders that hold them so that the
   // NRB_TILE row blocks of a column tile do the same work.
-  int n_ct = 0;                     // column tiles
-  int32_t* ct_rb_out_dev = nullptr; // [n_ct][NRB_TILE] output row block (channel/16) or -1
-  int32_t* ct_src_dev = nullptr;    // [n_ct][K][NRB_TILE] compact row block in order k or -1
+  int n_ct = 0;                     // column tiles of NRB_TILE row blocks
+  int n_sorted = 0;                 // sorted row-block list length, padded to a multiple of 64
+  int32_t* ct_rb_out_dev = nullptr; // [n_sorted] output row block (channel/16) or -1
+  int32_t* ct_src_dev = nullptr;    // [K][n_sorted] compact row block in order k or -1
   // per order device pointers for kernels
   const uint8_t** packed_ptrs_dev = nullptr;  // [K]
   const float** scale_ptrs_dev = nullptr;     // [K]
