@@ -19,6 +19,7 @@
 // Workgroups are mapped to (column tile, token tile) in 8x8 super-tiles per XCD so that the
 // 64 workgroups resident on one XCD share 8 weight strips and 8 activation strips in its L2.
 #include <cstdlib>
+#include <type_traits>
 
 #include "pipe_internal.h"
 
@@ -61,10 +62,24 @@ struct WRegs {
   uint4 v[N];
 };
 
+// Hand-issued LDS reads: N fragments (16 bytes per lane each) at byte offsets BASE + b*STRIDE
+// from `addr` (LDS byte address of this lane's slot in fragment 0).  The results may be used
+// only after lds_wait on the same registers.
+template <int N, int BASE, int STRIDE>
+__device__ __forceinline__ void lds_read_frags(unsigned addr, v4i (&x)[N]) {
+#pragma unroll
+  for (int b = 0; b < N; ++b)
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(x[b]) : "v"(addr), "n"(BASE + b * STRIDE) : "memory");
+}
 template <int N>
-struct XRegs {
-  uint4 v[N];
-};
+__device__ __forceinline__ void lds_wait(v4i (&x)[N]) {
+  static_assert(N == 4 || N == 8, "token blocks per tile");
+  if constexpr (N == 4)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])::"memory");
+}
 
 template <int BITS>
 __device__ __forceinline__ v4i widen(const WRegs<BITS>& w, int j) {
@@ -119,6 +134,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     if (ct >= p.n_ct || tt >= p.n_tt) return;
   }
   const int t0 = tt * (16 * MTB);
+  // LDS byte address of this lane's 16 bytes inside fragment 0 of buffer 0
+  const unsigned xs_lane = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)&Xs[0][0] + lane * 16;
   const int nksup = (p.nks * 64) / KSUP;
   const int n_stage = p.nks / S;
 
@@ -192,9 +209,12 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
           for (int q = 0; q < WN; ++q) w[r].v[q] = wp[r][(size_t)(s * WN + q) * FRAG];
       };
-      // one stage: wait for this stage's tiles, prefetch the next stage, multiply this one
-      auto stage = [&](int s, WRegs<BITS>(&cur)[NRW], WRegs<BITS>(&nxt)[NRW]) __attribute__((always_inline)) {
-        const int buf = s & 1;
+      // One stage: wait for this stage's tiles, prefetch the next stage, multiply this one.
+      // The LDS reads are issued by hand (the compiler cannot tell the two LDS buffers apart and
+      // would otherwise wait for the just-issued prefetch before every read); each 64-k step
+      // reads the next step's fragments while the MFMAs of the current one run.
+      auto stage = [&](int s, auto bufc, WRegs<BITS>(&cur)[NRW], WRegs<BITS>(&nxt)[NRW]) __attribute__((always_inline)) {
+        constexpr int buf = decltype(bufc)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-direct loads have landed
         __syncthreads();                      // everyone's have, and buffer buf^1 is free again
         if (s + 1 < n_stage) {
@@ -202,20 +222,18 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           if (active) gload_w(s + 1, nxt);
         }
         if (active) {
+          v4i xf[2][MTB];
+          lds_read_frags<MTB, (buf * MTB * S + 0) * 1024, S * 1024>(xs_lane, xf[0]);
 #pragma unroll
           for (int j = 0; j < S; ++j) {
-            v4i xf[MTB];
-#pragma unroll
-            for (int b = 0; b < MTB; ++b) {
-              const uint4 v = Xs[buf][(b * S + j) * FRAG + lane];
-              xf[b] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
-            }
+            lds_wait<MTB>(xf[j & 1]);
+            if (j + 1 < S) lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf[(j + 1) & 1]);
 #pragma unroll
             for (int r = 0; r < NRW; ++r) {
               const v4i wf = widen<BITS>(cur[r], j);
 #pragma unroll
               for (int b = 0; b < MTB; ++b)
-                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[b], acc[r][b], 0, 0, 0);
+                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[j & 1][b], acc[r][b], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);   // keep the 64-k steps apart: bounds live registers
           }
@@ -226,10 +244,10 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       if (active) gload_w(0, w0);
       int s = 0;
       for (; s + 1 < n_stage; s += 2) {
-        stage(s, w0, w1);
-        stage(s + 1, w1, w0);
+        stage(s, std::integral_constant<int, 0>{}, w0, w1);
+        stage(s + 1, std::integral_constant<int, 1>{}, w1, w0);
       }
-      if (s < n_stage) stage(s, w0, w1);
+      if (s < n_stage) stage(s, std::integral_constant<int, 0>{}, w0, w1);
       __syncthreads();
 
       // fold this order: yacc += s_k[o] * float(acc - OFF * rowsum)
