@@ -141,6 +141,12 @@ int pipe_set_kernel(int which);
 int pipe_timing_enable(int on);
 int pipe_timing_read(double* total_ms, int* launches);
 
+/* Diagnostic for reports: runs an MFMA-only kernel (back-to-back independent
+ * v_mfma_i32_16x16x64_i8 on registers, no memory traffic) for `iters` rounds of 16
+ * instructions per wave and writes the int8 rate it sustained, in TOP/s, to
+ * *tops_out (HOST).  Synchronizes the stream.                                   */
+int pipe_mfma_probe(int iters, double* tops_out, void* stream);
+
 const char* pipe_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char* pipe_last_device_error(void);

@@ -46,6 +46,7 @@ def _load():
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_mfma_probe.argtypes = [ci, C.POINTER(C.c_double), vp]
     lib.pipe_timing_enable.argtypes = [ci]
     lib.pipe_timing_read.argtypes = [C.POINTER(C.c_double), pi]
     lib.pipe_strerror.argtypes = [ci]
@@ -53,7 +54,7 @@ def _load():
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
-              "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read"):
+              "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe"):
         getattr(lib, f).restype = ci
     return lib
 
@@ -226,3 +227,10 @@ def pipe_timing_read():
     ms, n = C.c_double(), C.c_int()
     _check(_lib.pipe_timing_read(C.byref(ms), C.byref(n)), "pipe_timing_read")
     return ms.value, n.value
+
+
+def pipe_mfma_probe(iters: int = 20000) -> float:
+    """int8 TOP/s an MFMA-only kernel sustains on this chip (diagnostic for reports)."""
+    t = C.c_double()
+    _check(_lib.pipe_mfma_probe(int(iters), C.byref(t), _stream()), "pipe_mfma_probe")
+    return t.value

@@ -18,7 +18,6 @@
 // bias, optional GELU and the member sum are applied once in the epilogue.
 // Workgroups are mapped to (column tile, token tile) in 8x8 super-tiles per XCD so that the
 // 64 workgroups resident on one XCD share 8 weight strips and 8 activation strips in its L2.
-#include <cstdlib>
 #include <type_traits>
 
 #include "pipe_internal.h"
@@ -37,8 +36,8 @@ struct TiledParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* packed[PIPE_MAX_K];
-  const float* scales[PIPE_MAX_K];
+  const uint8_t* const* packed;   // device [K]: packed codes of every order
+  const float* const* scales;     // device [K]: row scales of every order
   const int32_t* rb_out;          // [n_sorted] output row block of sorted position i, or -1
   const int32_t* rb_src;          // [K][n_sorted] compact row block in order k, or -1
   int n_sorted;                   // padded to a multiple of 64
@@ -48,8 +47,7 @@ struct TiledParams {
   uint32_t* amax_out;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
   int n_st_t;                     // super-tiles along tokens
-  int member_lo[PIPE_MAX_K];
-  int member_hi[PIPE_MAX_K];
+  unsigned long long member_nib;  // member of order k in bits [4k, 4k+4)
 };
 
 __device__ __forceinline__ float gelu_erf(float a) {
@@ -97,13 +95,12 @@ __device__ __forceinline__ v4i widen(const WRegs<BITS>& w, int j) {
   }
 }
 
-// uniform dynamic index into a kernel-argument array without forcing it into scratch memory
+// a wave-uniform 64-bit pointer loaded through a vector load, moved to scalar registers
 template <class T>
-__device__ __forceinline__ T pick(const T (&a)[PIPE_MAX_K], int k) {
-  T v = a[0];
-#pragma unroll
-  for (int i = 1; i < PIPE_MAX_K; ++i) v = (i == k) ? a[i] : v;
-  return v;
+__device__ __forceinline__ T* uniform_ptr(T* v) {
+  const unsigned long long a = (unsigned long long)v;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  return (T*)(((unsigned long long)hi << 32) | lo);
 }
 
 enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2 };
@@ -118,6 +115,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   constexpr int XCOPY = MTB * S / 4;              // activation fragments per wave per stage
   static_assert(TOK_TILE % (16 * MTB) == 0 || (16 * MTB) % TOK_TILE == 0, "token tile");
   __shared__ uint4 Xs[2][MTB * S * FRAG];
+  __shared__ float Scl[4][16 * NRW];   // per wave: row scales of the current order
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
@@ -139,11 +137,42 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   const int nksup = (p.nks * 64) / KSUP;
   const int n_stage = p.nks / S;
 
+  // ---- tile descriptors, fetched once (one memory round trip) -------------------------------
+  // the first activation stage does not depend on them: request it first
+  auto xload = [&](const uint8_t* qx, int s, int buf) __attribute__((always_inline)) {
+    // activations: global -> LDS without passing through registers; one 1-KiB fragment per
+    // wave-wide load, XCOPY fragments per wave and stage
+#pragma unroll
+    for (int f = 0; f < XCOPY; ++f) {
+      const int idx = wave * XCOPY + f;          // fragment (b, j) = (idx / S, idx % S)
+      const int b = idx / S, j = idx - b * S;
+      const uint4* g = reinterpret_cast<const uint4*>(qx + ((size_t)(t0 / 16 + b) * p.nks + (size_t)s * S + j) * 1024) + lane;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                       (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
+    }
+  };
+  xload(p.qx, 0, 0);   // member 0 owns order 1, which every tile holds
+  // tile_mask: orders that hold at least one row block of this column tile (uniform);
+  // src_tab: lane k*NRW + r = compact row block of this wave's r-th row block in order k
+  int v_any[PIPE_MAX_K];
+#pragma unroll
+  for (int k = 0; k < PIPE_MAX_K; ++k)
+    v_any[k] = (k < p.K && lane < NRB_WG) ? p.rb_src[(size_t)k * p.n_sorted + ct * NRB_WG + lane] : -1;
+  int src_tab = -1;
+  if (lane < p.K * NRW)
+    src_tab = p.rb_src[(size_t)(lane / NRW) * p.n_sorted + ct * NRB_WG + wave * NRW + (lane % NRW)];
+  int rb_out_v = lane < NRW ? p.rb_out[ct * NRB_WG + wave * NRW + lane] : -1;
+  unsigned tile_mask = 0;
+#pragma unroll
+  for (int k = 0; k < PIPE_MAX_K; ++k)
+    if (__builtin_amdgcn_ballot_w64(v_any[k] >= 0) != 0) tile_mask |= 1u << k;
+  tile_mask = __builtin_amdgcn_readfirstlane(tile_mask);
   int rb_out[NRW];
 #pragma unroll
-  for (int r = 0; r < NRW; ++r) rb_out[r] = __builtin_amdgcn_readfirstlane(p.rb_out[ct * NRB_WG + wave * NRW + r]);
+  for (int r = 0; r < NRW; ++r) rb_out[r] = __builtin_amdgcn_readlane(rb_out_v, r);
 
   const bool fold_sx = p.reduce && p.M > 1;   // multi-member sum: fold s_x into the row scale
+  const unsigned scl_lane = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)&Scl[wave][0] + (lane >> 4) * 16;
   float yacc[NRW][MTB][4];
 #pragma unroll
   for (int r = 0; r < NRW; ++r)
@@ -152,29 +181,29 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
       for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
 
+  bool x0_requested = true;    // stage 0 of the next order to run is already on its way to LDS buffer 0
   for (int m = 0; m < p.M; ++m) {
-    const uint4* qx = reinterpret_cast<const uint4*>(p.qx + (size_t)m * p.qx_mstride);
+    const uint8_t* qx = p.qx + (size_t)m * p.qx_mstride;
     const int32_t* rowsum = p.rowsum + (size_t)m * p.rowsum_mstride;
     const float sx = p.s_x[m * p.sx_mstride];
     int rs[MTB];
 #pragma unroll
     for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
 
-    const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
-    for (int k = k_lo; k <= k_hi; ++k) {
-      const int32_t* srcp = p.rb_src + (size_t)k * p.n_sorted + ct * NRB_WG;
-      int any = 0;
-#pragma unroll
-      for (int r = 0; r < NRB_WG; ++r) any |= srcp[r] >= 0 ? 1 : 0;
-      if (!__builtin_amdgcn_readfirstlane(any)) continue;   // uniform over the workgroup
-      const uint8_t* pk = pick(p.packed, k);
-      const float* sck = pick(p.scales, k);
+    for (int k = 0; k < p.K; ++k) {
+      if ((int)((p.member_nib >> (4 * k)) & 15ull) != m) continue;
+      if (!((tile_mask >> k) & 1u)) continue;   // uniform over the workgroup
+      const uint8_t* pk = uniform_ptr(p.packed[k]);
+      const float* sck = uniform_ptr(p.scales[k]);
       int src[NRW];
-      const uint4* wp[NRW];
+      const uint8_t* wb[NRW];
+      bool active = false;
 #pragma unroll
       for (int r = 0; r < NRW; ++r) {
-        src[r] = __builtin_amdgcn_readfirstlane(srcp[wave * NRW + r]);
-        wp[r] = reinterpret_cast<const uint4*>(pk + (size_t)(src[r] < 0 ? 0 : src[r]) * nksup * 1024) + lane;
+        src[r] = __builtin_amdgcn_readlane(src_tab, k * NRW + r);
+        active |= src[r] >= 0;
+        // a pruned row block among live ones reads row block 0; its result is dropped
+        wb[r] = pk + (size_t)(src[r] < 0 ? 0 : src[r]) * nksup * 1024;
       }
 
       v4i acc[NRW][MTB];
@@ -183,31 +212,12 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
         for (int b = 0; b < MTB; ++b) acc[r][b] = v4i{0, 0, 0, 0};
 
-      // A wave whose row blocks are all pruned at this order only helps staging the
-      // activations; otherwise it multiplies all its row blocks (a pruned one among them reads
-      // row block 0 and its result is dropped).
-      bool active = false;
-#pragma unroll
-      for (int r = 0; r < NRW; ++r) active |= src[r] >= 0;
-
       WRegs<BITS> w0[NRW], w1[NRW];
-      // activations: global -> LDS without passing through registers; one 1-KiB fragment per
-      // wave-wide load, XCOPY fragments per wave and stage
-      auto xload = [&](int s, int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int f = 0; f < XCOPY; ++f) {
-          const int idx = wave * XCOPY + f;          // fragment (b, j) = (idx / S, idx % S)
-          const int b = idx / S, j = idx - b * S;
-          const uint4* g = qx + ((size_t)(t0 / 16 + b) * p.nks + (size_t)s * S + j) * FRAG + lane;
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                           (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
-        }
-      };
       auto gload_w = [&](int s, WRegs<BITS>(&w)[NRW]) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < NRW; ++r)
 #pragma unroll
-          for (int q = 0; q < WN; ++q) w[r].v[q] = wp[r][(size_t)(s * WN + q) * FRAG];
+          for (int q = 0; q < WN; ++q) w[r].v[q] = reinterpret_cast<const uint4*>(wb[r] + (size_t)(s * WN + q) * 1024)[lane];
       };
       // One stage: wait for this stage's tiles, prefetch the next stage, multiply this one.
       // The LDS reads are issued by hand (the compiler cannot tell the two LDS buffers apart and
@@ -218,29 +228,45 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-direct loads have landed
         __syncthreads();                      // everyone's have, and buffer buf^1 is free again
         if (s + 1 < n_stage) {
-          xload(s + 1, buf ^ 1);
+          xload(qx, s + 1, buf ^ 1);
           if (active) gload_w(s + 1, nxt);
         }
+        if (s == 0 && active) {
+          // row scales of this order -> LDS (one 4-byte LDS-direct load per lane), read at the fold
+#pragma unroll
+          for (int g = 0; g < (16 * NRW + 63) / 64; ++g) {
+            const int e = g * 64 + lane, r = e >> 4;
+            int sr = src[0];
+#pragma unroll
+            for (int q = 1; q < NRW; ++q) sr = (r == q) ? src[q] : sr;
+            const float* gp = sck + (size_t)(sr < 0 ? 0 : sr) * 16 + (e & 15);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                             (__attribute__((address_space(3))) void*)&Scl[wave][g * 64], 4, 0, 0);
+          }
+        }
         if (active) {
-          v4i xf[2][MTB];
-          lds_read_frags<MTB, (buf * MTB * S + 0) * 1024, S * 1024>(xs_lane, xf[0]);
+          v4i xf[MTB];
+          lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane, xf);
 #pragma unroll
           for (int j = 0; j < S; ++j) {
-            lds_wait<MTB>(xf[j & 1]);
-            if (j + 1 < S) lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf[(j + 1) & 1]);
+            lds_wait<MTB>(xf);
 #pragma unroll
             for (int r = 0; r < NRW; ++r) {
               const v4i wf = widen<BITS>(cur[r], j);
 #pragma unroll
               for (int b = 0; b < MTB; ++b)
-                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[j & 1][b], acc[r][b], 0, 0, 0);
+                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[b], acc[r][b], 0, 0, 0);
             }
+            // the next step's fragments are requested once this step's MFMAs are issued; the
+            // other wave of the SIMD covers the LDS latency
+            if (j + 1 < S) lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf);
             __builtin_amdgcn_sched_barrier(0);   // keep the 64-k steps apart: bounds live registers
           }
         }
       };
 
-      xload(0, 0);
+      if (!x0_requested) xload(qx, 0, 0);
+      x0_requested = false;
       if (active) gload_w(0, w0);
       int s = 0;
       for (; s + 1 < n_stage; s += 2) {
@@ -248,13 +274,15 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
         stage(s + 1, std::integral_constant<int, 1>{}, w1, w0);
       }
       if (s < n_stage) stage(s, std::integral_constant<int, 0>{}, w0, w1);
+      if (n_stage == 1) __builtin_amdgcn_s_waitcnt(0x0F70);   // the scales were requested in this very stage
       __syncthreads();
 
       // fold this order: yacc += s_k[o] * float(acc - OFF * rowsum)
 #pragma unroll
       for (int r = 0; r < NRW; ++r) {
         if (src[r] < 0) continue;
-        const float4 sc = *reinterpret_cast<const float4*>(sck + (size_t)src[r] * 16 + 4 * (lane >> 4));
+        float4 sc;
+        asm volatile("ds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)" : "=v"(sc) : "v"(scl_lane), "n"(r * 64) : "memory");
         float scv[4] = {sc.x, sc.y, sc.z, sc.w};
         if (fold_sx) {
 #pragma unroll
@@ -342,26 +370,64 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
-  for (int k = 0; k < PIPE_MAX_K; ++k) {
-    p.packed[k] = k < e->K ? e->orders[k].packed_dev : nullptr;
-    p.scales[k] = k < e->K ? e->orders[k].scales_dev : nullptr;
-  }
+  p.packed = e->packed_ptrs_dev; p.scales = e->scale_ptrs_dev;
   p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.n_sorted = e->n_sorted;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
-  for (int m = 0; m < PIPE_MAX_K; ++m) { p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m]; }
+  p.member_nib = 0;
+  for (int m = 0; m < a.M; ++m)
+    for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_nib |= (unsigned long long)m << (4 * k);
   const bool acc_out = a.acc_out != nullptr;
-  static const int variant = [] { const char* v = getenv("PIPE_TILE_VARIANT"); return v ? atoi(v) : 0; }();
-  if (a.T_pad % 128 != 0 && variant == 2) return PIPE_ESHAPE;
-  switch (e->bits * 10 + variant) {
-    case 80: case 81: case 82: return launch_cfg<8, 4, 4, 1>(p, acc_out, st);
-    case 40: return launch_cfg<4, 4, 4, 2>(p, acc_out, st);
-    case 41: return launch_cfg<4, 4, 8, 1>(p, acc_out, st);
-    case 42: return launch_cfg<4, 8, 4, 1>(p, acc_out, st);
-    case 20: return launch_cfg<2, 4, 4, 2>(p, acc_out, st);
-    case 21: return launch_cfg<2, 4, 8, 1>(p, acc_out, st);
-    case 22: return launch_cfg<2, 8, 4, 1>(p, acc_out, st);
+  switch (e->bits) {
+    case 8: return launch_cfg<8, 4, 4, 1>(p, acc_out, st);
+    case 4: return launch_cfg<4, 4, 4, 2>(p, acc_out, st);
+    case 2: return launch_cfg<2, 4, 4, 2>(p, acc_out, st);
     default: return PIPE_EINVAL;
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// MFMA-only probe: every wave issues back-to-back independent v_mfma_i32_16x16x64_i8 on
+// registers (no memory traffic).  Gives the int8 rate the chip sustains at its own clocks,
+// to put next to the vendor peak in reports.
+// ---------------------------------------------------------------------------------------
+namespace {
+__global__ __launch_bounds__(256, 2) void mfma_probe_kernel(int iters, int* sink) {
+  v4i a = v4i{(int)threadIdx.x, 1, 2, 3}, b = v4i{3, 2, 1, (int)blockIdx.x};
+  v4i c[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) c[i] = v4i{0, 0, 0, 0};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c[i], 0, 0, 0);
+  }
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += c[i][0] + c[i][1] + c[i][2] + c[i][3];
+  if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never true
+}
+}  // namespace
+
+extern "C" int pipe_mfma_probe(int iters, double* tops_out, void* stream) {
+  if (iters <= 0 || !tops_out) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  int* sink = (int*)pipe_ws_get(WS_MISC, 256);
+  if (!sink) return PIPE_ENOMEM;
+  hipEvent_t e0, e1;
+  PIPE_HIP(hipEventCreate(&e0));
+  PIPE_HIP(hipEventCreate(&e1));
+  const int blocks = 256 * 2 * 4;   // 2 workgroups per CU resident, 4 rounds
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, sink);   // warm-up
+  PIPE_HIP(hipEventRecord(e0, st));
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, sink);
+  PIPE_HIP(hipEventRecord(e1, st));
+  PIPE_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  PIPE_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  const double ops = (double)blocks * 4.0 * iters * 16.0 * (2.0 * 16 * 16 * 64);
+  *tops_out = ops / (ms * 1e-3) / 1e12;
+  return PIPE_OK;
 }

@@ -30,7 +30,7 @@
 // ---------------------------------------------------------------------------------------
 constexpr int PIPE_MAX_K = 16;
 constexpr int IN_PAD = 256;    // in_features padded to this (largest KSUP)
-constexpr int TOK_TILE = 128;  // token padding of the tiled kernel's buffers (largest token tile)
+constexpr int TOK_TILE = 64;   // tokens per tile of the tiled kernel; token padding of its buffers
 constexpr int RB = 16;         // rows per row block
 constexpr int NRB_TILE = 16;   // row blocks per column tile of the tiled kernel
 
