@@ -313,17 +313,17 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
 }
 
 // ------------------------------------------------------------------ forward
-static bool use_stream_kernel(int T) {
-  if (g_kernel_choice == 1) return false;
-  if (g_kernel_choice == 2) return T <= 16;
+static bool use_stream_kernel(const pipe_expansion* e, int T) {
+  if (g_kernel_choice == 1 || e->K > 4) return false;   // the streaming kernel holds at most 4 orders per bin
   return T <= 16;
 }
 
 struct ActBuffers {
   uint8_t* qx;
   int32_t* rowsum;
-  uint32_t* amax;   // [PIPE_MAX_K] bit patterns
-  float* scale;     // [PIPE_MAX_K] scales
+  uint32_t* amax;        // max|x| bit pattern of this call (zero on entry)
+  uint32_t* amax_next;   // slot of the next call, zeroed by this call's quantizer
+  float* scale;          // [PIPE_MAX_K] scales
   int T_pad;
 };
 
@@ -331,9 +331,14 @@ static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
   b->T_pad = (int)round_up64(T, small ? 16 : TOK_TILE);
   b->qx = (uint8_t*)pipe_ws_get(WS_QX, (size_t)b->T_pad * in_pad);
   b->rowsum = (int32_t*)pipe_ws_get(WS_ROWSUM, (size_t)b->T_pad * 4);
+  const bool fresh = g_ws[WS_SCAL].ptr == nullptr;
   uint8_t* sc = (uint8_t*)pipe_ws_get(WS_SCAL, 4096);
   if (!b->qx || !b->rowsum || !sc) return PIPE_ENOMEM;
-  b->amax = (uint32_t*)sc;
+  if (fresh) PIPE_HIP(hipMemset(sc, 0, 4096));
+  static int parity = 0;
+  parity ^= 1;
+  b->amax = (uint32_t*)sc + parity;          // two slots used alternately: [0], [1]
+  b->amax_next = (uint32_t*)sc + (parity ^ 1);
   b->scale = (float*)(sc + 1024);
   return PIPE_OK;
 }
@@ -361,6 +366,23 @@ extern "C" int pipe_timing_read(double* total_ms, int* launches) {
   if (launches) *launches = (int)(g_events_used / 2);
   g_events_used = 0;
   return PIPE_OK;
+}
+
+// Activation quantization of a [T, in] input into the buffers of `b`; small batches take the
+// single-launch path.
+static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s_x, const ActBuffers& b, bool small,
+                          int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
+  if (small)
+    return launch_quantize_small(x_dev, 0, 1, T, in, in_pad, s_x, b.qx, 0, b.rowsum, qx_rowmajor, scale_out, st);
+  // The reduction slot was left at zero by the previous call (or by the workspace allocation);
+  // the reduction kernel also clears the code sums, so a dynamic scale costs two launches.
+  const bool dynamic = !(s_x > 0.f);
+  if (dynamic) {
+    int rc = launch_absmax(x_dev, (int64_t)T * in, b.amax, b.rowsum, b.T_pad, st);
+    if (rc) return rc;
+  }
+  return launch_quantize_act(x_dev, T, in, in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, dynamic, qx_rowmajor, scale_out,
+                             b.amax_next, st);
 }
 
 static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
@@ -397,17 +419,11 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(T);
+  const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  if (!(s_x > 0.f)) {
-    rc = launch_zero_u32(b.amax, 1, st);
-    if (rc) return rc;
-    rc = launch_absmax(x_dev, (int64_t)T * e->in, b.amax, st);
-    if (rc) return rc;
-  }
-  rc = launch_quantize_act(x_dev, T, e->in, e->in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, nullptr, b.scale, st);
+  rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
   if (rc) return rc;
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.qx_mstride = 0; a.rowsum = b.rowsum; a.rowsum_mstride = 0;
@@ -423,19 +439,13 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   if (T == 0) return PIPE_OK;
   if (!x_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(T);
+  const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   int rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  if (!(s_x > 0.f)) {
-    rc = launch_zero_u32(b.amax, 1, st);
-    if (rc) return rc;
-    rc = launch_absmax(x_dev, (int64_t)T * e->in, b.amax, st);
-    if (rc) return rc;
-  }
-  rc = launch_quantize_act(x_dev, T, e->in, e->in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, qx_dev,
-                           s_x_out_dev ? s_x_out_dev : b.scale, st);
+  rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, qx_dev, b.scale, st);
   if (rc) return rc;
+  if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
   if (!acc_dev) return PIPE_OK;
   PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
   GemmArgs a{};
@@ -464,18 +474,16 @@ extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, 
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(T);
+  const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
   if (!(s_x > 0.f)) {
-    rc = launch_zero_u32(b.amax, 1, st);
-    if (rc) return rc;
-    rc = launch_absmax(x_dev, (int64_t)N * C * H * W, b.amax, st);
+    rc = launch_absmax(x_dev, (int64_t)N * C * H * W, b.amax, nullptr, 0, st);
     if (rc) return rc;
   }
   rc = launch_quantize_im2col(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, s_x,
-                              b.amax, b.qx, b.rowsum, b.scale, st);
+                              b.amax, b.qx, b.rowsum, b.scale, b.amax_next, st);
   if (rc) return rc;
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
@@ -499,7 +507,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(T);
+  const bool small = use_stream_kernel(l1, T);   // both layers have the same K
   ActBuffers b;
   rc = get_act_buffers(T, l1->in_pad, small, &b);
   if (rc) return rc;
@@ -517,16 +525,12 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   uint32_t* amax_h = b.amax + 16;
   float* scale_h = b.scale + 16;
 
-  if (!(s_x > 0.f)) {
-    rc = launch_zero_u32(b.amax, 1, st);
-    if (rc) return rc;
-    rc = launch_absmax(x_dev, (int64_t)T * l1->in, b.amax, st);
+  rc = quantize_input(x_dev, T, l1->in, l1->in_pad, s_x, b, small, nullptr, b.scale, st);
+  if (rc) return rc;
+  if (!small) {
+    rc = launch_zero_u32(amax_h, Mm, st);
     if (rc) return rc;
   }
-  rc = launch_quantize_act(x_dev, T, l1->in, l1->in_pad, T_pad, s_x, b.amax, b.qx, b.rowsum, nullptr, b.scale, st);
-  if (rc) return rc;
-  rc = launch_zero_u32(amax_h, Mm, st);
-  if (rc) return rc;
 
   // layer 1: every member reads the same Q(x); outputs stay separate
   GemmArgs a{};
@@ -534,7 +538,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   a.bias = bias1_dev; a.reduce = 0;
   fill_members(a, Mm, lo, hi);
   if (act == PIPE_ACT_GELU) {
-    a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
+    a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = small ? nullptr : amax_h;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
   } else {
@@ -545,10 +549,15 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     if (rc) return rc;
   }
   // each member quantizes its own hidden activation with its own scale
-  for (int m = 0; m < Mm; ++m) {
+  if (small) {
+    rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, qh, (int64_t)T_pad * l2->in_pad, rowsum_h,
+                               nullptr, scale_h, st);
+    if (rc) return rc;
+  }
+  for (int m = 0; m < Mm && !small; ++m) {
     rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, 0.f, amax_h + m,
-                             qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, nullptr,
-                             scale_h + m, st);
+                             qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
+                             scale_h + m, nullptr, st);
     if (rc) return rc;
   }
   // layer 2: member m contracts its own input with its own orders; summed in the epilogue

@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
         float v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          v[i] = (fold_sx ? yacc[r][b][i] : sx * yacc[r][b][i]) + bv[i];
+          v[i] = fold_sx ? yacc[r][b][i] + bv[i] : fmaf(sx, yacc[r][b][i], bv[i]);   // same rounding as the streaming kernel
           if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
           if (t < p.T) mx = fmaxf(mx, fabsf(v[i]));
           yacc[r][b][i] = 0.f;

@@ -8,10 +8,10 @@
 // own 1-KiB tiles straight from HBM into registers with fully coalesced 16-byte loads, widens
 // them with a shift and a mask and feeds v_mfma_i32_16x16x64_i8 against the 16-token
 // activation fragments (also read straight from L2: waves use disjoint k, nothing is shared,
-// so the k loop has no LDS traffic and no barrier).  The waves' partial int32 tiles are summed
-// with LDS integer adds (exact, order independent); the epilogue then applies offsets, row
-// scales, activation scale, bias and the member sum in a fixed order, so results are
-// bit-reproducible.
+// so the k loop has no LDS traffic and no barrier).  The waves' partial int32 tiles meet in
+// LDS and are summed exactly; the epilogue then applies offsets, row scales, activation scale,
+// bias and the member sum in a fixed order, so results are bit-reproducible.  Expansions with
+// more than 4 orders take the tiled kernel at every batch size.
 #include "pipe_internal.h"
 
 namespace {
@@ -40,6 +40,15 @@ struct StreamParams {
   int member_of[PIPE_MAX_K];
 };
 
+// uniform dynamic index into a kernel-argument array without forcing it into scratch memory
+template <class T>
+__device__ __forceinline__ T pick(const T (&a)[PIPE_MAX_K], int k) {
+  T v = a[0];
+#pragma unroll
+  for (int i = 1; i < PIPE_MAX_K; ++i) v = (i == k) ? a[i] : v;
+  return v;
+}
+
 __device__ __forceinline__ float gelu_erf(float a) {
   return 0.5f * a * (1.f + erff(a * 0.70710678118654752440f));
 }
@@ -62,114 +71,161 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
   constexpr int STEPS = KSUP / 64;      // 64-k steps per packed tile
-  __shared__ int fin[STREAM_BIN_CAP][256];
+  constexpr int BIN_WORDS = sizeof(StreamBin) / 4;
+  static_assert(BIN_WORDS <= 128, "bin descriptor is fetched with two loads per lane");
+  __shared__ int part[NW][R][256];   // each wave's partial tiles of the items in flight
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const StreamBin& bin = p.bins[blockIdx.x];
-  const int n_items = bin.n_items;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_tiles = (p.nks * 64) / KSUP;
 
-  for (int i = threadIdx.x; i < STREAM_BIN_CAP * 256; i += NW * 64) (&fin[0][0])[i] = 0;
-  __syncthreads();
+  // bin descriptor: one memory round trip, then scalar reads out of two vector registers
+  const int32_t* bw = reinterpret_cast<const int32_t*>(p.bins + blockIdx.x);
+  const int d0 = lane < BIN_WORDS ? bw[lane] : 0;
+  const int d1 = lane + 64 < BIN_WORDS ? bw[lane + 64] : 0;
+  // a shared input does not depend on the descriptor: its first tile is requested alongside
+  uint4 x0[SHARED_X ? STEPS : R * STEPS];
+  if (SHARED_X && wave < n_tiles) {
+#pragma unroll
+    for (int j = 0; j < STEPS; ++j) x0[j] = reinterpret_cast<const uint4*>(p.qx + (size_t)(wave * STEPS + j) * 1024)[lane];
+  }
+  auto word = [&](int i) __attribute__((always_inline)) {
+    return i < 64 ? __builtin_amdgcn_readlane(d0, i) : __builtin_amdgcn_readlane(d1, i - 64);
+  };
+  const int n_items = word(0), n_out = word(1);
+  auto item_k = [&](int it) __attribute__((always_inline)) { return word(2 + it); };
+  auto item_crb = [&](int it) __attribute__((always_inline)) { return word(2 + STREAM_BIN_CAP + it); };
+  auto item_slot = [&](int it) __attribute__((always_inline)) { return word(2 + 2 * STREAM_BIN_CAP + it); };
+  auto out_rb = [&](int o) __attribute__((always_inline)) { return word(2 + 3 * STREAM_BIN_CAP + o); };
+
+  // epilogue role of this thread: 256 threads per output row block, thread = (token t, channel ch)
+  const int e = threadIdx.x & 255;
+  const int t = e >> 4, ch = e & 15;
+  const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);   // lane*4 + i of the MFMA result layout
+  const int o_first = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+  constexpr int O_STEP = (NW * 64) / 256;
+  const bool fold_sx = p.reduce && p.M > 1;
 
   for (int c0 = 0; c0 < n_items; c0 += R) {
-    const uint4* wp[R];
-    const uint4* xp[R];
+    const uint8_t* wb[R];
+    const uint8_t* xb[R];
     bool on[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       on[r] = c0 + r < n_items;
       const int it = on[r] ? c0 + r : c0;
-      const int k = bin.k[it];
-      wp[r] = reinterpret_cast<const uint4*>(p.packed[k] + (size_t)bin.crb[it] * n_tiles * 1024) + lane;
-      xp[r] = reinterpret_cast<const uint4*>(p.qx + (SHARED_X ? (size_t)0 : (size_t)p.member_of[k] * p.qx_mstride)) + lane;
+      const int k = item_k(it);
+      wb[r] = pick(p.packed, k) + (size_t)item_crb(it) * n_tiles * 1024;
+      xb[r] = p.qx + (SHARED_X ? (size_t)0 : (size_t)pick(p.member_of, k) * p.qx_mstride);
     }
+    // what the epilogue of this chunk needs is requested now, so that it arrives during the k loop
+    float scv[R];
+    int itk[R], its[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int it = on[r] ? c0 + r : c0;
+      itk[r] = item_k(it);
+      its[r] = on[r] ? item_slot(it) : -1;
+      scv[r] = pick(p.scales, itk[r])[(size_t)item_crb(it) * 16 + ch];
+    }
+
     v4i acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = v4i{0, 0, 0, 0};
 
-    for (int t = wave; t < n_tiles; t += NW) {
-      uint4 w[R];
+    // wave w streams tiles w, w+NW, ...; two tiles are in flight (the loads of tile t+NW are
+    // issued before the MFMAs of tile t)
+    uint4 w0[R], w1[R];
+    uint4 x1[SHARED_X ? STEPS : R * STEPS];
+    if (!(SHARED_X && c0 == 0)) {
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-        if (on[r]) w[r] = wp[r][(size_t)t * 64];
+      for (int j = 0; j < (SHARED_X ? STEPS : R * STEPS); ++j) x0[j] = make_uint4(0, 0, 0, 0);
+    }
+    auto load_tile = [&](int tl, uint4 (&w)[R], uint4 (&x)[SHARED_X ? STEPS : R * STEPS], bool have_x = false) __attribute__((always_inline)) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) w[r] = reinterpret_cast<const uint4*>(wb[r] + (size_t)tl * 1024)[lane];
+      if (have_x) return;
       if (SHARED_X) {
-        uint4 x[STEPS];
 #pragma unroll
-        for (int j = 0; j < STEPS; ++j) x[j] = xp[0][(size_t)(t * STEPS + j) * 64];
-#pragma unroll
-        for (int j = 0; j < STEPS; ++j) {
-          const v4i xf = v4i{(int)x[j].x, (int)x[j].y, (int)x[j].z, (int)x[j].w};
-#pragma unroll
-          for (int r = 0; r < R; ++r) {
-            if (!on[r]) continue;
-            v4i wf;
-            unpack_step<BITS>(w[r], j, wf);
-            acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
-          }
-        }
+        for (int j = 0; j < STEPS; ++j) x[j] = reinterpret_cast<const uint4*>(xb[0] + (size_t)(tl * STEPS + j) * 1024)[lane];
       } else {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-          if (!on[r]) continue;
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int j = 0; j < STEPS; ++j) {
-            const uint4 x = xp[r][(size_t)(t * STEPS + j) * 64];
-            const v4i xf = v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w};
-            v4i wf;
-            unpack_step<BITS>(w[r], j, wf);
-            acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
+          for (int j = 0; j < STEPS; ++j) x[r * STEPS + j] = reinterpret_cast<const uint4*>(xb[r] + (size_t)(tl * STEPS + j) * 1024)[lane];
+      }
+    };
+    auto mul_tile = [&](uint4 (&w)[R], uint4 (&x)[SHARED_X ? STEPS : R * STEPS]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < STEPS; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const uint4 xv = x[SHARED_X ? j : r * STEPS + j];
+          const v4i xf = v4i{(int)xv.x, (int)xv.y, (int)xv.z, (int)xv.w};
+          v4i wf;
+          unpack_step<BITS>(w[r], j, wf);
+          acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
+        }
+      }
+    };
+    int tl = wave;
+    if (tl < n_tiles) load_tile(tl, w0, x0, SHARED_X && c0 == 0);
+    for (; tl < n_tiles; tl += 2 * NW) {
+      if (tl + NW < n_tiles) load_tile(tl + NW, w1, x1);
+      mul_tile(w0, x0);
+      if (tl + NW < n_tiles) {
+        if (tl + 2 * NW < n_tiles) load_tile(tl + 2 * NW, w0, x0);
+        mul_tile(w1, x1);
+      }
+    }
+    if (c0 > 0) __syncthreads();   // the previous chunk's partial tiles have been consumed
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      *reinterpret_cast<v4i*>(&part[wave][r][lane * 4]) = acc[r];
+    __syncthreads();
+
+    // epilogue of this chunk: exact integer sum over the waves, then the fixed-order fp32 sum
+    // (same evaluation order as the tiled kernel): one member, or members kept apart:
+    //   y_m = s_x,m * (sum_k s_k * a_k) + b;  members summed: y = sum_m sum_k (s_k * s_x,m) * a_k + b.
+    for (int o = o_first; o < n_out; o += O_STEP) {
+      bool mine = false;
+#pragma unroll
+      for (int r = 0; r < R; ++r) mine |= its[r] == o;
+      if (!mine) continue;
+      // a row block's items are adjacent and, with K <= R, never split across chunks
+      const int col = out_rb(o) * 16 + ch;
+      float yacc = 0.f;
+      for (int m = 0; m < p.M; ++m) {
+        const int rs = OFF ? p.rowsum[(size_t)m * p.rowsum_mstride + t] : 0;
+        const float sx = p.s_x[m * p.sx_mstride];
+        const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {      // items of a row block are stored in ascending order k
+          if (its[r] != o || itk[r] < k_lo || itk[r] > k_hi) continue;
+          int a = 0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) a += part[w][r][fidx];
+          a -= OFF * rs;
+          const float sc = fold_sx ? scv[r] * sx : scv[r];
+          yacc = fmaf(sc, (float)a, yacc);
+          if (ACC_OUT) {
+            if (t < p.T) p.acc_out[((size_t)itk[r] * p.T + t) * p.out + col] = a;
           }
         }
-      }
-    }
+        if (ACC_OUT) continue;
+        if (fold_sx && m + 1 < p.M) continue;
+        const float bm = ((m == 0 || fold_sx) && p.bias != nullptr) ? p.bias[col] : 0.f;
+        float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the tiled kernel
+        yacc = 0.f;
+        if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
+        if (p.amax_out != nullptr) {
+          float mx = t < p.T ? fabsf(v) : 0.f;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (!on[r]) continue;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) atomicAdd(&fin[c0 + r][lane * 4 + i], acc[r][i]);
-    }
-  }
-  __syncthreads();
-
-  // epilogue: 256 threads per output row block, thread = (token t, channel ch)
-  const int e = threadIdx.x & 255;
-  const int t = e >> 4, ch = e & 15;
-  const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);   // lane*4 + i of the MFMA result layout
-  for (int o = threadIdx.x >> 8; o < bin.n_out; o += (NW * 64) / 256) {
-    const int orb = bin.out_rb[o];
-    const int col = orb * 16 + ch;
-    // Evaluation order (same as the tiled kernel): one member, or members kept apart:
-    // y_m = s_x,m * (sum_k s_k * a_k) + b;  members summed: y = sum_m sum_k (s_k * s_x,m) * a_k + b.
-    const bool fold_sx = p.reduce && p.M > 1;
-    float yacc = 0.f;
-    for (int m = 0; m < p.M; ++m) {
-      const int rs = OFF ? p.rowsum[(size_t)m * p.rowsum_mstride + t] : 0;
-      const float sx = p.s_x[m * p.sx_mstride];
-      for (int it = 0; it < n_items; ++it) {      // items of a row block are stored in ascending order k
-        const int k = bin.k[it];
-        if (bin.slot[it] != o || k < p.member_lo[m] || k > p.member_hi[m]) continue;
-        const int a = fin[it][fidx] - OFF * rs;
-        float sc = p.scales[k][(size_t)bin.crb[it] * 16 + ch];
-        if (fold_sx) sc *= sx;
-        yacc = fmaf(sc, (float)a, yacc);
-        if (ACC_OUT) {
-          if (t < p.T) p.acc_out[((size_t)k * p.T + t) * p.out + col] = a;
+          for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
+          if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
         }
+        if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
       }
-      if (ACC_OUT) continue;
-      if (fold_sx && m + 1 < p.M) continue;
-      float v = (fold_sx ? yacc : sx * yacc) + (((m == 0 || fold_sx) && p.bias != nullptr) ? p.bias[col] : 0.f);
-      yacc = 0.f;
-      if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
-      if (p.amax_out != nullptr) {
-        float mx = t < p.T ? fabsf(v) : 0.f;
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
-        if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
-      }
-      if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
     }
   }
 }
@@ -193,7 +249,7 @@ int launch_nw(const StreamParams& p, int n_bins, bool shared_x, bool acc_out, hi
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   const pipe_expansion* e = a.e;
   if (a.T <= 0) return PIPE_OK;
-  if (a.T > 16 || a.T_pad != 16) return PIPE_ESHAPE;
+  if (a.T > 16 || a.T_pad != 16 || e->K > R) return PIPE_ESHAPE;
   StreamParams p;
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;

@@ -117,18 +117,24 @@ int launch_unpack_codes(const uint8_t* packed, int bits, int rows, int in, int i
 // ------------------------------------------------------------------ activation kernels (pipe_quant.hip)
 // amax_bits: device uint32 holding the bit pattern of max|x| (must be zeroed first).
 int launch_zero_u32(uint32_t* p, int n, hipStream_t st);
-int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, hipStream_t st);
+// launch_absmax also zeroes n_zero ints at zero_me (the code sums of the quantizer that follows).
+int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_me, int n_zero, hipStream_t st);
 // Quantize x [T, in] into the fragment layout (padded region written as zero), row sums and
 // optionally row-major int8.  scale: if s_static > 0 use it, else amax/127 from amax_bits.
 // Writes the scale used to *scale_out (device).
 int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
-                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum,
-                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
+                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum, bool rowsum_is_zero,
+                        int8_t* qx_rowmajor, float* scale_out, uint32_t* amax_next, hipStream_t st);
+// Decode-sized batches (T <= 16, T_pad == 16): max|x|, scale, codes and code sums in ONE launch,
+// one workgroup per member (x, qx_frag, rowsum [16 per member], scale_out [M] with member strides).
+int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
+                          uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum, int8_t* qx_rowmajor,
+                          float* scale_out, hipStream_t st);
 // Same for the virtual im2col matrix of a convolution.
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
-                           int32_t* rowsum, float* scale_out, hipStream_t st);
+                           int32_t* rowsum, float* scale_out, uint32_t* amax_next, hipStream_t st);
 // Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h|.
 int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
                    hipStream_t st);

@@ -29,15 +29,26 @@ __device__ __forceinline__ float block_max(float v) {
 }
 
 // max|x| over n elements; the maximum is order independent, so the result is exact.
+// Also clears the per-token code sums the quantizer that follows accumulates into.
 __global__ __launch_bounds__(BLK) void absmax_kernel(const float* __restrict__ x, int64_t n,
-                                                     uint32_t* __restrict__ amax_bits) {
+                                                     uint32_t* __restrict__ amax_bits,
+                                                     int32_t* __restrict__ zero_me, int n_zero) {
+  for (int i = blockIdx.x * BLK + threadIdx.x; i < n_zero; i += gridDim.x * BLK) zero_me[i] = 0;
   float m = 0.f;
   const int64_t stride = (int64_t)gridDim.x * BLK;
   const int64_t i0 = (int64_t)blockIdx.x * BLK + threadIdx.x;
   if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
     const int64_t n4 = n >> 2;
     const float4* x4 = reinterpret_cast<const float4*>(x);
-    for (int64_t i = i0; i < n4; i += stride) {
+    int64_t i = i0;
+    for (; i + 3 * stride < n4; i += 4 * stride) {   // four independent 16-byte loads in flight
+      const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+    }
+    for (; i < n4; i += stride) {
       const float4 v = x4[i];
       m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
     }
@@ -71,7 +82,7 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
 template <class Fetch>
 __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int in_pad, float s,
                                                uint8_t* __restrict__ qx_frag, int32_t* __restrict__ rowsum,
-                                               int8_t* __restrict__ qx_rowmajor) {
+                                               int8_t* __restrict__ qx_rowmajor, const float* __restrict__ xvec = nullptr) {
   const int tb = blockIdx.x;
   const int n = threadIdx.x & 15;
   const int t = tb * 16 + n;
@@ -84,13 +95,30 @@ __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int i
   int sum = 0;
   for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
     int q[16];
+    if (xvec != nullptr && t < T && c * 16 + 15 < in) {
+      // rows are 16-byte aligned: four 16-byte loads per chunk
+      const float4* row = reinterpret_cast<const float4*>(xvec + (size_t)t * in + c * 16);
+      float f[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int k = c * 16 + e;
-      int v = 0;
-      if (live && t < T && k < in) v = quant1(fetch(t, k), s);
-      q[e] = v;
-      sum += v;
+      for (int e = 0; e < 4; ++e) {
+        const float4 v4 = row[e];
+        f[4 * e] = v4.x; f[4 * e + 1] = v4.y; f[4 * e + 2] = v4.z; f[4 * e + 3] = v4.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int v = live ? quant1(f[e], s) : 0;
+        q[e] = v;
+        sum += v;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = c * 16 + e;
+        int v = 0;
+        if (live && t < T && k < in) v = quant1(fetch(t, k), s);
+        q[e] = v;
+        sum += v;
+      }
     }
     const int ks = c >> 2, kc = c & 3;
     uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
@@ -111,11 +139,109 @@ __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restri
                                                            uint8_t* __restrict__ qx_frag,
                                                            int32_t* __restrict__ rowsum,
                                                            int8_t* __restrict__ qx_rowmajor,
-                                                           float* __restrict__ scale_out) {
+                                                           float* __restrict__ scale_out,
+                                                           uint32_t* __restrict__ amax_next) {
   const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    if (scale_out) *scale_out = s;
+    if (amax_next) *amax_next = 0u;   // the slot the next call's reduction starts from
+  }
   auto fetch = [=](int t, int k) { return x[(size_t)t * in + k]; };
-  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor);
+  const bool vec = (in & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor, vec ? x : nullptr);
+}
+
+// Decode-sized batches (T <= 16): ONE launch does max|x|, scale, codes and code sums, so the
+// forward path is two launches (this one and the contraction).  Workgroup (n, m) owns token n
+// of member m: it first reduces max|x| over the member's whole input (every workgroup does,
+// redundantly -- the input is a few hundred KiB and L2 resident, and it spares a grid-wide
+// synchronization), then quantizes its own token and sums its codes without atomics.
+constexpr int SBLK = 256;
+__global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __restrict__ x_all, int64_t x_mstride,
+                                                              int T, int in, int in_pad, float s_static,
+                                                              uint8_t* __restrict__ qx_all, int64_t qx_mstride,
+                                                              int32_t* __restrict__ rowsum_all,
+                                                              int8_t* __restrict__ qx_rowmajor,
+                                                              float* __restrict__ scale_out) {
+  const int n = blockIdx.x;      // token 0..15
+  const int m = blockIdx.y;
+  const float* x = x_all + (size_t)m * x_mstride;
+  uint8_t* qx_frag = qx_all + (size_t)m * qx_mstride;
+  __shared__ float smax[SBLK / 64];
+  __shared__ int ssum[SBLK / 64];
+  float s = s_static;
+  if (!(s_static > 0.f)) {
+    float mx = 0.f;
+    const int64_t cnt = (int64_t)T * in;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+      const float4* x4 = reinterpret_cast<const float4*>(x);
+      const int64_t n4 = cnt >> 2;
+      int64_t i = threadIdx.x;
+      for (; i + 7 * SBLK < n4; i += 8 * SBLK) {   // eight independent 16-byte loads in flight
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = x4[i + u * SBLK];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
+      }
+      for (; i < n4; i += SBLK) {
+        const float4 v = x4[i];
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+      }
+      for (int64_t j = (n4 << 2) + threadIdx.x; j < cnt; j += SBLK) mx = fmaxf(mx, fabsf(x[j]));
+    } else {
+      for (int64_t j = threadIdx.x; j < cnt; j += SBLK) mx = fmaxf(mx, fabsf(x[j]));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = smax[0];
+#pragma unroll
+    for (int i = 1; i < SBLK / 64; ++i) mx = fmaxf(mx, smax[i]);
+    s = __fdiv_rn(mx, 127.f);
+  }
+  if (n == 0 && threadIdx.x == 0 && scale_out) scale_out[m] = s;
+  const bool live = s > 0.f && n < T;
+  const int nchunk = in_pad >> 4;
+  const bool vec = (in & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+  int sum = 0;
+  for (int c = threadIdx.x; c < nchunk; c += SBLK) {
+    int q[16];
+    if (live && vec && c * 16 + 15 < in) {
+      const float4* row = reinterpret_cast<const float4*>(x + (size_t)n * in + c * 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float4 v = row[e];
+        q[4 * e] = quant1(v.x, s); q[4 * e + 1] = quant1(v.y, s); q[4 * e + 2] = quant1(v.z, s); q[4 * e + 3] = quant1(v.w, s);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) q[e] = (live && c * 16 + e < in) ? quant1(x[(size_t)n * in + c * 16 + e], s) : 0;
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += q[e];
+    const int ks = c >> 2, kc = c & 3;
+    const uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
+                               pack4(q[8], q[9], q[10], q[11]), pack4(q[12], q[13], q[14], q[15]));
+    *reinterpret_cast<uint4*>(qx_frag + (((size_t)ks) * 64 + kc * 16 + n) * 16) = w;
+    if (qx_rowmajor != nullptr && n < T) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (c * 16 + e < in) qx_rowmajor[(size_t)n * in + c * 16 + e] = (int8_t)q[e];
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+  if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < SBLK / 64; ++i) tot += ssum[i];
+    rowsum_all[(size_t)m * 16 + n] = tot;
+  }
 }
 
 struct ConvGeom {
@@ -127,9 +253,13 @@ __global__ __launch_bounds__(BLK) void quantize_im2col_kernel(const float* __res
                                                               const uint32_t* __restrict__ amax_bits,
                                                               uint8_t* __restrict__ qx_frag,
                                                               int32_t* __restrict__ rowsum,
-                                                              float* __restrict__ scale_out) {
+                                                              float* __restrict__ scale_out,
+                                                              uint32_t* __restrict__ amax_next) {
   const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    if (scale_out) *scale_out = s;
+    if (amax_next) *amax_next = 0u;
+  }
   // token t = (n, ho, wo); column k = (c, r, q) as in a weight row flattened [C, kh, kw]
   auto fetch = [=](int t, int k) {
     const int wo = t % g.Wo, ho = (t / g.Wo) % g.Ho, n = t / (g.Wo * g.Ho);
@@ -179,12 +309,12 @@ int launch_zero_u32(uint32_t* p, int n, hipStream_t st) {
   return PIPE_OK;
 }
 
-int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, hipStream_t st) {
+int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_me, int n_zero, hipStream_t st) {
   if (n <= 0) return PIPE_OK;
   int64_t blocks = (n / 4 + BLK - 1) / BLK;
   if (blocks < 1) blocks = 1;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits);
+  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits, zero_me, n_zero);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -199,13 +329,24 @@ static int ksplit_for(int T_pad, int in_pad) {
 }
 
 int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
-                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum,
-                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
-  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
-  if (rc) return rc;
+                        const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum, bool rowsum_is_zero,
+                        int8_t* qx_rowmajor, float* scale_out, uint32_t* amax_next, hipStream_t st) {
+  if (!rowsum_is_zero) {
+    int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
+    if (rc) return rc;
+  }
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
   hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, s_static, amax_bits,
-                     qx_frag, rowsum, qx_rowmajor, scale_out);
+                     qx_frag, rowsum, qx_rowmajor, scale_out, amax_next);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
+                          uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum, int8_t* qx_rowmajor,
+                          float* scale_out, hipStream_t st) {
+  hipLaunchKernelGGL(quantize_small_kernel, dim3(16, M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
+                     qx_frag, qx_mstride, rowsum, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -213,14 +354,14 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
-                           int32_t* rowsum, float* scale_out, hipStream_t st) {
+                           int32_t* rowsum, float* scale_out, uint32_t* amax_next, hipStream_t st) {
   int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
   if (rc) return rc;
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
   hipLaunchKernelGGL(quantize_im2col_kernel, grid, dim3(BLK), 0, st, x, g, T, in, in_pad, s_static,
-                     amax_bits, qx_frag, rowsum, scale_out);
+                     amax_bits, qx_frag, rowsum, scale_out, amax_next);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
