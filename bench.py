@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 tiled MFMA, 2 weight streaming")
+    ap.add_argument("--no-graph", action="store_true", help="time decode steps eagerly instead of as one HIP graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a 1 GiB device copy 5 times (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -58,6 +61,15 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     pipe.pipe_set_kernel(args.kernel)
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "calibrate_copy_bytes_written": a.numel() * 4}))
+        return
 
     cfg = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
     T_head = args.tokens or cfg.tokens
@@ -82,49 +94,72 @@ def main():
     xd_full = torch.from_numpy(x_full).to(dev)
     split = list(cfg.split) if len(cfg.split) > 1 else None
 
-    def step_fn(e, xd):
+    def step_fn(e, xd, out=None):
         if cfg.kind == "linear":
-            return pipe.pipe_forward(e[0], xd, split=split)
+            return pipe.pipe_forward(e[0], xd, split=split, out=out)
         if cfg.kind == "conv2d":
             c = cfg.conv
             return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split)
         act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
-        return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split)
+        return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split, out=out)
 
     def io_bytes(T):
-        b = 0
-        for l in cfg.layers:
-            b += 4 * T * l.in_features if l is cfg.layers[0] else 0
-        b += 4 * T * cfg.layers[-1].out_features
-        return b
+        return 4 * T * cfg.layers[0].in_features + 4 * T * cfg.layers[-1].out_features
 
     def measure(T, steps, warmup, rotate):
         """Times `steps` passes; returns dict with step time and contraction-kernel time."""
         xd = xd_full if cfg.kind == "conv2d" else xd_full[:T].contiguous()
+        out = None if cfg.kind == "conv2d" else torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
         copies = 1
         if rotate:
             copies = max(2, -(-int(1.25 * LLC_BYTES) // max(stream_bytes, 1)))
             while len(exps) < copies:
                 exps.append(build())
         for i in range(warmup):
-            step_fn(exps[i % copies], xd)
+            step_fn(exps[i % copies], xd, out)
         torch.cuda.synchronize()
+        # ---- K steps, eager, contraction kernels bracketed by events on the launch stream ----
         pipe.pipe_timing_read()
         pipe.pipe_timing_enable(True)
         torch.cuda.synchronize()
         t_a = time.perf_counter()
         for i in range(steps):
-            step_fn(exps[i % copies], xd)
+            step_fn(exps[i % copies], xd, out)
         torch.cuda.synchronize()
         t_b = time.perf_counter()
         pipe.pipe_timing_enable(False)
         k_ms, k_n = pipe.pipe_timing_read()
         step_ms = (t_b - t_a) * 1e3 / steps
+        mode = "eager"
+        # ---- decode-sized steps are launch bound: the same K steps as ONE HIP graph ----------
+        if T <= 16 and not args.no_graph and cfg.kind != "conv2d":
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    for i in range(2):
+                        step_fn(exps[i % copies], xd, out)
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for i in range(steps):
+                        step_fn(exps[i % copies], xd, out)
+                g.replay()
+                torch.cuda.synchronize()
+                t_a = time.perf_counter()
+                g.replay()
+                torch.cuda.synchronize()
+                t_b = time.perf_counter()
+                step_ms = (t_b - t_a) * 1e3 / steps
+                mode = "hipgraph"
+            except Exception as ex:      # keep the eager number
+                mode = "eager (graph capture failed: %s)" % type(ex).__name__
         per_step_kernel_ms = k_ms / steps
         ops = 2.0 * T * macs_per_token
         alg_bytes = stream_bytes + io_bytes(T)
         return dict(tokens=T, ms_per_step=step_ms, kernel_ms_per_step=per_step_kernel_ms,
-                    kernel_launches_per_step=k_n / steps,
+                    kernel_launches_per_step=k_n / steps, step_mode=mode,
                     eff_tops=ops / (step_ms * 1e-3) / 1e12,
                     kernel_eff_tops=ops / (per_step_kernel_ms * 1e-3) / 1e12 if k_ms > 0 else None,
                     tokens_per_s=T / (step_ms * 1e-3),
@@ -164,10 +199,10 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        O_s = min(cfg.layers[0].out_features, 1024 if cfg.kind == "linear" else cfg.layers[0].out_features)
+        O_s = cfg.layers[0].out_features
         l0 = cfg.layers[0]
         if cfg.kind == "linear":
-            T_s = min(T0, 512)
+            T_s = min(T0, 1024)
             Wn = Ws[0][:O_s].cpu().numpy()
             ex = po.expand(Wn, l0.bits, l0.K, l0.gamma, l0.group)
             xs = x_full[:T_s]
@@ -175,9 +210,9 @@ def main():
             po.forward(ex, xs, split=split)
             dt = time.perf_counter() - tc
             macs = po.expansion_macs(ex, T_s)
-            sample = "forward on the first %d output channels x %d tokens (expansion built outside the timer)" % (O_s, T_s)
+            sample = "forward (quantize, contract, de-quantize) of all %d output channels on the first %d tokens; expansion built outside the timer" % (O_s, T_s)
         else:
-            small = wl.scaled(cfg, out_div=4, in_div=2, tokens=256 if cfg.kind != "conv2d" else 392)
+            small = wl.scaled(cfg, out_div=2, in_div=1, tokens=512) if cfg.kind != "conv2d" else cfg
             Wsm = [wl.make_weight(small, i) for i in range(len(small.layers))]
             exs = [po.expand(Wsm[i], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(small.layers)]
             xs = wl.make_input(small)
@@ -214,6 +249,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "sweep": sweep,
+        "mfma_probe_tops": pipe.pipe_mfma_probe(20000),
         "expand_seconds": expand_s,
         "input_generation_seconds": gen_s,
     }

@@ -321,8 +321,7 @@ static bool use_stream_kernel(const pipe_expansion* e, int T) {
 struct ActBuffers {
   uint8_t* qx;
   int32_t* rowsum;
-  uint32_t* amax;        // max|x| bit pattern of this call (zero on entry)
-  uint32_t* amax_next;   // slot of the next call, zeroed by this call's quantizer
+  uint32_t* amax;        // max|x| bit pattern: zero on entry, cleared again by the contraction kernel
   float* scale;          // [PIPE_MAX_K] scales
   int T_pad;
 };
@@ -335,10 +334,7 @@ static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
   uint8_t* sc = (uint8_t*)pipe_ws_get(WS_SCAL, 4096);
   if (!b->qx || !b->rowsum || !sc) return PIPE_ENOMEM;
   if (fresh) PIPE_HIP(hipMemset(sc, 0, 4096));
-  static int parity = 0;
-  parity ^= 1;
-  b->amax = (uint32_t*)sc + parity;          // two slots used alternately: [0], [1]
-  b->amax_next = (uint32_t*)sc + (parity ^ 1);
+  b->amax = (uint32_t*)sc;
   b->scale = (float*)(sc + 1024);
   return PIPE_OK;
 }
@@ -374,15 +370,15 @@ static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
   if (small)
     return launch_quantize_small(x_dev, 0, 1, T, in, in_pad, s_x, b.qx, 0, b.rowsum, qx_rowmajor, scale_out, st);
-  // The reduction slot was left at zero by the previous call (or by the workspace allocation);
-  // the reduction kernel also clears the code sums, so a dynamic scale costs two launches.
+  // The reduction slot is zero on entry (workspace allocation, then every contraction kernel
+  // clears it again); the reduction kernel also clears the code sums, so a dynamic scale costs
+  // two launches and no memset.
   const bool dynamic = !(s_x > 0.f);
   if (dynamic) {
     int rc = launch_absmax(x_dev, (int64_t)T * in, b.amax, b.rowsum, b.T_pad, st);
     if (rc) return rc;
   }
-  return launch_quantize_act(x_dev, T, in, in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, dynamic, qx_rowmajor, scale_out,
-                             b.amax_next, st);
+  return launch_quantize_act(x_dev, T, in, in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, dynamic, qx_rowmajor, scale_out, st);
 }
 
 static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
@@ -428,7 +424,7 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.qx_mstride = 0; a.rowsum = b.rowsum; a.rowsum_mstride = 0;
   a.s_x = b.scale; a.sx_mstride = 0; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.act = 0;
-  a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr;
+  a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr; a.zero_after = b.amax;
   fill_members(a, Mm, lo, hi);
   return run_gemm(a, small, st);
 }
@@ -446,11 +442,11 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, qx_dev, b.scale, st);
   if (rc) return rc;
   if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
-  if (!acc_dev) return PIPE_OK;
+  if (!acc_dev) return launch_zero_u32(b.amax, 1, st);   // no contraction kernel follows to clear it
   PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
-  a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev;
+  a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev; a.zero_after = b.amax;
   int lo = 0, hi = e->K - 1;
   fill_members(a, 1, &lo, &hi);
   return run_gemm(a, small, st);
@@ -483,11 +479,11 @@ extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, 
     if (rc) return rc;
   }
   rc = launch_quantize_im2col(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, s_x,
-                              b.amax, b.qx, b.rowsum, b.scale, b.amax_next, st);
+                              b.amax, b.qx, b.rowsum, b.scale, st);
   if (rc) return rc;
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
-  a.s_x = b.scale; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev;
+  a.s_x = b.scale; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev; a.zero_after = b.amax;
   fill_members(a, Mm, lo, hi);
   return run_gemm(a, small, st);
 }
@@ -535,7 +531,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   // layer 1: every member reads the same Q(x); outputs stay separate
   GemmArgs a{};
   a.e = l1; a.T = T; a.T_pad = T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
-  a.bias = bias1_dev; a.reduce = 0;
+  a.bias = bias1_dev; a.reduce = 0; a.zero_after = b.amax;
   fill_members(a, Mm, lo, hi);
   if (act == PIPE_ACT_GELU) {
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = small ? nullptr : amax_h;
@@ -557,7 +553,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   for (int m = 0; m < Mm && !small; ++m) {
     rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, 0.f, amax_h + m,
                              qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
-                             scale_h + m, nullptr, st);
+                             scale_h + m, st);
     if (rc) return rc;
   }
   // layer 2: member m contracts its own input with its own orders; summed in the epilogue

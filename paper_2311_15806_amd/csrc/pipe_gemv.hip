@@ -34,6 +34,7 @@ struct StreamParams {
   float* y;
   int32_t* acc_out;
   uint32_t* amax_out;
+  uint32_t* zero_after;
   int T, out, K, nks, M, reduce, act;
   int member_lo[PIPE_MAX_K];
   int member_hi[PIPE_MAX_K];
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_tiles = (p.nks * 64) / KSUP;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && p.zero_after != nullptr) *p.zero_after = 0u;
 
   // bin descriptor: one memory round trip, then scalar reads out of two vector registers
   const int32_t* bw = reinterpret_cast<const int32_t*>(p.bins + blockIdx.x);
@@ -259,7 +261,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
     p.scales[k] = k < e->K ? e->orders[k].scales_dev : nullptr;
   }
   p.bins = e->bins_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   for (int m = 0; m < PIPE_MAX_K; ++m) { p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m]; p.member_of[m] = 0; }
   for (int m = 0; m < a.M; ++m)

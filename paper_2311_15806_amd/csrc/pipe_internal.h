@@ -124,7 +124,7 @@ int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_
 // Writes the scale used to *scale_out (device).
 int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
                         const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum, bool rowsum_is_zero,
-                        int8_t* qx_rowmajor, float* scale_out, uint32_t* amax_next, hipStream_t st);
+                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
 // Decode-sized batches (T <= 16, T_pad == 16): max|x|, scale, codes and code sums in ONE launch,
 // one workgroup per member (x, qx_frag, rowsum [16 per member], scale_out [M] with member strides).
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
@@ -134,7 +134,7 @@ int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int i
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
-                           int32_t* rowsum, float* scale_out, uint32_t* amax_next, hipStream_t st);
+                           int32_t* rowsum, float* scale_out, hipStream_t st);
 // Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h|.
 int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
                    hipStream_t st);
@@ -159,6 +159,7 @@ struct GemmArgs {
   float* y;
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
+  uint32_t* zero_after;  // a word the kernel clears (the max|x| slot this call consumed), or nullptr
 };
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);

@@ -139,13 +139,9 @@ __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restri
                                                            uint8_t* __restrict__ qx_frag,
                                                            int32_t* __restrict__ rowsum,
                                                            int8_t* __restrict__ qx_rowmajor,
-                                                           float* __restrict__ scale_out,
-                                                           uint32_t* __restrict__ amax_next) {
+                                                           float* __restrict__ scale_out) {
   const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    if (scale_out) *scale_out = s;
-    if (amax_next) *amax_next = 0u;   // the slot the next call's reduction starts from
-  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
   auto fetch = [=](int t, int k) { return x[(size_t)t * in + k]; };
   const bool vec = (in & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
   quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor, vec ? x : nullptr);
@@ -253,13 +249,9 @@ __global__ __launch_bounds__(BLK) void quantize_im2col_kernel(const float* __res
                                                               const uint32_t* __restrict__ amax_bits,
                                                               uint8_t* __restrict__ qx_frag,
                                                               int32_t* __restrict__ rowsum,
-                                                              float* __restrict__ scale_out,
-                                                              uint32_t* __restrict__ amax_next) {
+                                                              float* __restrict__ scale_out) {
   const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    if (scale_out) *scale_out = s;
-    if (amax_next) *amax_next = 0u;
-  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
   // token t = (n, ho, wo); column k = (c, r, q) as in a weight row flattened [C, kh, kw]
   auto fetch = [=](int t, int k) {
     const int wo = t % g.Wo, ho = (t / g.Wo) % g.Ho, n = t / (g.Wo * g.Ho);
@@ -330,14 +322,14 @@ static int ksplit_for(int T_pad, int in_pad) {
 
 int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, float s_static,
                         const uint32_t* amax_bits, uint8_t* qx_frag, int32_t* rowsum, bool rowsum_is_zero,
-                        int8_t* qx_rowmajor, float* scale_out, uint32_t* amax_next, hipStream_t st) {
+                        int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
   if (!rowsum_is_zero) {
     int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
     if (rc) return rc;
   }
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
   hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, s_static, amax_bits,
-                     qx_frag, rowsum, qx_rowmajor, scale_out, amax_next);
+                     qx_frag, rowsum, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -354,14 +346,14 @@ int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int i
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
-                           int32_t* rowsum, float* scale_out, uint32_t* amax_next, hipStream_t st) {
+                           int32_t* rowsum, float* scale_out, hipStream_t st) {
   int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
   if (rc) return rc;
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
   hipLaunchKernelGGL(quantize_im2col_kernel, grid, dim3(BLK), 0, st, x, g, T, in, in_pad, s_static,
-                     amax_bits, qx_frag, rowsum, scale_out, amax_next);
+                     amax_bits, qx_frag, rowsum, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
