@@ -96,6 +96,17 @@ __device__ __forceinline__ v4i widen(const WRegs<BITS>& w, int j) {
   }
 }
 
+// A load known to hit global memory.  Pointers rebuilt from integers are "generic" to the
+// compiler, which would emit FLAT loads: those also count as LDS operations (every wait on the
+// LDS fragment reads would then wait for the weight prefetch as well) and are ordered against
+// the LDS-direct loads.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 gload16(const void* p) {
+  typedef const __attribute__((address_space(1))) v4u* gptr;
+  const v4u v = *(gptr)(unsigned long long)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // a wave-uniform 64-bit pointer loaded through a vector load, moved to scalar registers
 template <class T>
 __device__ __forceinline__ T* uniform_ptr(T* v) {
@@ -219,7 +230,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
         for (int r = 0; r < NRW; ++r)
 #pragma unroll
-          for (int q = 0; q < WN; ++q) w[r].v[q] = reinterpret_cast<const uint4*>(wb[r] + (size_t)(s * WN + q) * 1024)[lane];
+          for (int q = 0; q < WN; ++q) w[r].v[q] = gload16(wb[r] + (size_t)(s * WN + q) * 1024 + lane * 16);
       };
       // One stage: wait for this stage's tiles, prefetch the next stage, multiply this one.
       // The LDS reads are issued by hand (the compiler cannot tell the two LDS buffers apart and
