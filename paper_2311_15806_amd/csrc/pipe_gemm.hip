@@ -70,14 +70,15 @@ __device__ __forceinline__ void lds_read_frags(unsigned addr, v4i (&x)[N]) {
   for (int b = 0; b < N; ++b)
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(x[b]) : "v"(addr), "n"(BASE + b * STRIDE) : "memory");
 }
-template <int N>
+// Waits until at most PENDING later LDS reads are outstanding (LDS reads return in order), i.e.
+// until the N fragments of x, issued before them, have arrived.
+template <int N, int PENDING>
 __device__ __forceinline__ void lds_wait(v4i (&x)[N]) {
-  static_assert(N == 4 || N == 8, "token blocks per tile");
-  if constexpr (N == 4)
+  static_assert(N == 4 && (PENDING == 0 || PENDING == 4), "token blocks per tile");
+  if constexpr (PENDING == 0)
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
   else
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])::"memory");
+    asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
 }
 
 template <int BITS>
@@ -258,22 +259,42 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           }
         }
         if (active) {
-          v4i xf[MTB];
-          lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane, xf);
+          // Software pipeline of the S 64-k steps.  A wave issues in order, so everything that is
+          // not an MFMA has to sit in the shadow of one: the fragments of step j+1 are requested
+          // before step j's MFMAs start (two register sets), and the codes of row block r+1 are
+          // widened between the MFMAs of row block r (two register sets).
+          constexpr int XB = BITS == 4 ? 1 : 2;   // the 4-bit variant has no registers for a second set
+          v4i xf[XB][MTB];
+          v4i wf[2];
+          lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane, xf[0]);
+          wf[0] = widen<BITS>(cur[0], 0);
 #pragma unroll
           for (int j = 0; j < S; ++j) {
-            lds_wait<MTB>(xf);
+            if (XB == 2 && j + 1 < S) {
+              lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf[(j + 1) % XB]);
+              lds_wait<MTB, MTB>(xf[j % XB]);
+            } else {
+              lds_wait<MTB, 0>(xf[j % XB]);
+            }
 #pragma unroll
             for (int r = 0; r < NRW; ++r) {
-              const v4i wf = widen<BITS>(cur[r], j);
+              if (r + 1 < NRW) wf[(r + 1) & 1] = widen<BITS>(cur[r + 1], j);
+              else if (j + 1 < S) wf[(r + 1) & 1] = widen<BITS>(cur[0], j + 1);
 #pragma unroll
               for (int b = 0; b < MTB; ++b)
-                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf[b], acc[r][b], 0, 0, 0);
+                acc[r][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[r & 1], xf[j % XB][b], acc[r][b], 0, 0, 0);
+              if (BITS != 8) {
+                // one MFMA, then two of the unpack instructions, and so on
+#pragma unroll
+                for (int b = 0; b < MTB; ++b) {
+                  __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                  __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                }
+              }
+              __builtin_amdgcn_sched_barrier(0);   // keep the row blocks apart: bounds live registers
             }
-            // the next step's fragments are requested once this step's MFMAs are issued; the
-            // other wave of the SIMD covers the LDS latency
-            if (j + 1 < S) lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf);
-            __builtin_amdgcn_sched_barrier(0);   // keep the 64-k steps apart: bounds live registers
+            // single set: the next step's fragments follow the last MFMAs that read this one's
+            if (XB == 1 && j + 1 < S) lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane + (j + 1) * 1024, xf[0]);
           }
         }
       };
@@ -319,31 +340,45 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 
     if (ACC_OUT) continue;
     if (fold_sx && m + 1 < p.M) continue;   // keep accumulating into the same running sum
-    // member (or final) epilogue
+    // member (or final) epilogue.  The MFMA result layout gives a lane 4 channels of one token, so
+    // a direct store would touch 16 tokens x 64 B per instruction.  Each 16-token block is instead
+    // turned through this wave's 4 KiB of the idle LDS buffer 1 (XOR-swizzled, conflict free) so
+    // that one store instruction writes 4 tokens x 256 contiguous bytes: whole cache lines.
     float mx = 0.f;
-#pragma unroll
-    for (int r = 0; r < NRW; ++r) {
-      if (rb_out[r] < 0) continue;
-      const int ch = rb_out[r] * 16 + 4 * (lane >> 4);
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if ((m == 0 || fold_sx) && p.bias != nullptr) {
-        const float4 b4 = *reinterpret_cast<const float4*>(p.bias + ch);
-        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
-      }
+    {
+      float4* stg = reinterpret_cast<float4*>(&Xs[1][wave * 256]);
+      int lane_e = lane;
+      asm volatile("" : "+v"(lane_e));   // keeps the epilogue's address arithmetic out of the main loop's live range
+      const int tl = lane_e & 15, g = lane_e >> 4;
+      const int rb_l = __shfl(rb_out_v, tl >> 2, 64);            // row block of the channels this lane stores
+      const int ch = rb_l * 16 + 4 * (tl & 3);
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (rb_l >= 0 && (m == 0 || fold_sx) && p.bias != nullptr) bv = *reinterpret_cast<const float4*>(p.bias + ch);
 #pragma unroll
       for (int b = 0; b < MTB; ++b) {
-        const int t = t0 + b * 16 + (lane & 15);
-        float v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v[i] = fold_sx ? yacc[r][b][i] + bv[i] : fmaf(sx, yacc[r][b][i], bv[i]);   // same rounding as the streaming kernel
-          if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
-          if (t < p.T) mx = fmaxf(mx, fabsf(v[i]));
-          yacc[r][b][i] = 0.f;
+        for (int r = 0; r < NRW; ++r) {
+          stg[tl * 16 + ((r * 4 + g) ^ tl)] = make_float4(yacc[r][b][0], yacc[r][b][1], yacc[r][b][2], yacc[r][b][3]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
         }
-        if (t < p.T) {
-          float* dst = p.y + ((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + ch;
-          *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int tq = 4 * q + g, t = t0 + b * 16 + tq;
+          const float4 a = stg[tq * 16 + (tl ^ tq)];
+          float v[4] = {a.x, a.y, a.z, a.w};
+          const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v[i] = fold_sx ? v[i] + bb[i] : fmaf(sx, v[i], bb[i]);   // same rounding as the streaming kernel
+            if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
+          }
+          if (t < p.T && rb_l >= 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fabsf(v[i]));
+            float* dst = p.y + ((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + ch;
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+          }
         }
       }
     }
