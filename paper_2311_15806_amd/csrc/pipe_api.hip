@@ -381,7 +381,8 @@ static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s
   return launch_quantize_act(x_dev, T, in, in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, dynamic, qx_rowmajor, scale_out, st);
 }
 
-static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
+static int run_gemm(const GemmArgs& a0, bool small, hipStream_t st) {
+  GemmArgs a = a0;
   const bool timed = g_timing_on && g_events_used / 2 < MAX_TIMED;
   if (timed) {
     while (g_events.size() < g_events_used + 2) {
@@ -389,13 +390,11 @@ static int run_gemm(const GemmArgs& a, bool small, hipStream_t st) {
       PIPE_HIP(hipEventCreate(&ev));
       g_events.push_back(ev);
     }
-    PIPE_HIP(hipEventRecord(g_events[g_events_used], st));
+    a.ev_start = g_events[g_events_used];
+    a.ev_stop = g_events[g_events_used + 1];
   }
   const int rc = small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
-  if (timed) {
-    PIPE_HIP(hipEventRecord(g_events[g_events_used + 1], st));
-    g_events_used += 2;
-  }
+  if (timed && rc == PIPE_OK) g_events_used += 2;
   return rc;
 }
 

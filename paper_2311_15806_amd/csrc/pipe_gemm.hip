@@ -391,7 +391,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 }
 
 template <int BITS, int MTB, int NRW, int MINW>
-int launch_cfg(TiledParams& p, bool acc_out, hipStream_t st) {
+int launch_cfg(TiledParams& p, bool acc_out, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
   p.n_tt = ceil_div(p.T, 16 * MTB);
   p.n_ct = ceil_div(p.n_ct * NRB_TILE, 4 * NRW);   // column tiles of this variant's width
   p.n_st_t = ceil_div(p.n_tt, 8);
@@ -399,11 +399,11 @@ int launch_cfg(TiledParams& p, bool acc_out, hipStream_t st) {
   // super-tile sidx runs on XCD sidx % 8 as blocks xcd + 8*(64*(sidx/8) + local), local = 0..63
   const dim3 grid((unsigned)(ceil_div(p.n_st_t * n_st_c, 8) * 8 * 64));
   if (acc_out)
-    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), 0, st, p);
+    PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), st, ev0, ev1, p);
   else if (p.act == PIPE_ACT_GELU)
-    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GELU>), grid, dim3(256), 0, st, p);
+    PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GELU>), grid, dim3(256), st, ev0, ev1, p);
   else
-    hipLaunchKernelGGL((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_PLAIN>), grid, dim3(256), 0, st, p);
+    PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_PLAIN>), grid, dim3(256), st, ev0, ev1, p);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -428,9 +428,9 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
     for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_nib |= (unsigned long long)m << (4 * k);
   const bool acc_out = a.acc_out != nullptr;
   switch (e->bits) {
-    case 8: return launch_cfg<8, 4, 4, 1>(p, acc_out, st);
-    case 4: return launch_cfg<4, 4, 4, 2>(p, acc_out, st);
-    case 2: return launch_cfg<2, 4, 4, 2>(p, acc_out, st);
+    case 8: return launch_cfg<8, 4, 4, 1>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 4: return launch_cfg<4, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 2: return launch_cfg<2, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
     default: return PIPE_EINVAL;
   }
 }

@@ -233,14 +233,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
 }
 
 template <int BITS, int NW>
-int launch_nw(const StreamParams& p, int n_bins, bool shared_x, bool acc_out, hipStream_t st) {
+int launch_nw(const StreamParams& p, int n_bins, bool shared_x, bool acc_out, const GemmArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)n_bins), blk(NW * 64);
   if (acc_out) {
-    if (shared_x) hipLaunchKernelGGL((gemm_stream_kernel<BITS, NW, true, true>), grid, blk, 0, st, p);
-    else hipLaunchKernelGGL((gemm_stream_kernel<BITS, NW, false, true>), grid, blk, 0, st, p);
+    if (shared_x) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, true, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, false, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
   } else {
-    if (shared_x) hipLaunchKernelGGL((gemm_stream_kernel<BITS, NW, true, false>), grid, blk, 0, st, p);
-    else hipLaunchKernelGGL((gemm_stream_kernel<BITS, NW, false, false>), grid, blk, 0, st, p);
+    if (shared_x) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, true, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, false, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
   }
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -269,8 +269,8 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   const bool shared_x = a.qx_mstride == 0;
   const bool acc_out = a.acc_out != nullptr;
   switch (e->bits) {
-    case 8: return launch_nw<8, 8>(p, e->n_bins, shared_x, acc_out, st);
-    case 4: return launch_nw<4, 8>(p, e->n_bins, shared_x, acc_out, st);
-    default: return launch_nw<2, 8>(p, e->n_bins, shared_x, acc_out, st);
+    case 8: return launch_nw<8, 8>(p, e->n_bins, shared_x, acc_out, a, st);
+    case 4: return launch_nw<4, 8>(p, e->n_bins, shared_x, acc_out, a, st);
+    default: return launch_nw<2, 8>(p, e->n_bins, shared_x, acc_out, a, st);
   }
 }

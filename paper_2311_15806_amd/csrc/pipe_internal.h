@@ -1,6 +1,7 @@
 // Internal declarations shared by the HIP sources of the PIPE library (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <vector>
 
@@ -160,6 +161,14 @@ struct GemmArgs {
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
   uint32_t* zero_after;  // a word the kernel clears (the max|x| slot this call consumed), or nullptr
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // if set: the dispatch's own begin/end timestamps
 };
+// Launches with the dispatch's begin/end timestamps recorded into the two events when they are set
+// (the kernel alone: no event-record packets on the stream in between).
+#define PIPE_LAUNCH(kernel, grid, block, st, ev0, ev1, ...)                                   \
+  do {                                                                                       \
+    if ((ev0) != nullptr) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__); \
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                         \
+  } while (0)
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
