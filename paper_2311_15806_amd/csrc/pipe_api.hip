@@ -101,6 +101,7 @@ static void free_expansion(pipe_expansion* e) {
   }
   if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
   if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
+  if (e->ct_mask_dev) (void)hipFree(e->ct_mask_dev);
   if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->packed_ptrs_dev) (void)hipFree((void*)e->packed_ptrs_dev);
   if (e->scale_ptrs_dev) (void)hipFree((void*)e->scale_ptrs_dev);
@@ -139,6 +140,10 @@ static int build_schedule(pipe_expansion* e) {
     for (int k = 0; k < K; ++k)
       if (slot_of[k][g] >= 0) src[(size_t)k * e->n_sorted + i] = slot_of[k][g] * rbpg + b;
   }
+  std::vector<uint32_t> ct_mask((size_t)e->n_ct, 0u);
+  for (int i = 0; i < n_rb; ++i) ct_mask[i / NRB_TILE] |= items[i].mask;
+  PIPE_HIP(hipMalloc(&e->ct_mask_dev, ct_mask.size() * 4));
+  PIPE_HIP(hipMemcpy(e->ct_mask_dev, ct_mask.data(), ct_mask.size() * 4, hipMemcpyHostToDevice));
   PIPE_HIP(hipMalloc(&e->ct_rb_out_dev, rb_out.size() * 4));
   PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
   PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));

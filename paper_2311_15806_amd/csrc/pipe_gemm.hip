@@ -40,6 +40,7 @@ struct TiledParams {
   const float* const* scales;     // device [K]: row scales of every order
   const int32_t* rb_out;          // [n_sorted] output row block of sorted position i, or -1
   const int32_t* rb_src;          // [K][n_sorted] compact row block in order k, or -1
+  const uint32_t* ct_mask;        // [n_ct] orders present in the column tile
   int n_sorted;                   // padded to a multiple of 64
   const float* bias;
   float* y;
@@ -102,18 +103,20 @@ __device__ __forceinline__ v4i widen(const WRegs<BITS>& w, int j) {
 // LDS fragment reads would then wait for the weight prefetch as well) and are ordered against
 // the LDS-direct loads.
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 gload16(const void* p) {
   typedef const __attribute__((address_space(1))) v4u* gptr;
   const v4u v = *(gptr)(unsigned long long)p;
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// a wave-uniform 64-bit pointer loaded through a vector load, moved to scalar registers
+// Loads of schedule tables at wave-uniform addresses through the constant address space: the
+// compiler then uses scalar loads (the tables are written once, by the host, when the expansion
+// is built; no kernel ever stores to them), which cost no vector registers and no vector wait.
 template <class T>
-__device__ __forceinline__ T* uniform_ptr(T* v) {
-  const unsigned long long a = (unsigned long long)v;
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
-  return (T*)(((unsigned long long)hi << 32) | lo);
+__device__ __forceinline__ T cload(const T* base, size_t idx) {
+  typedef const __attribute__((address_space(4))) T* cptr;
+  return ((cptr)(unsigned long long)base)[idx];
 }
 
 enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2 };
@@ -166,24 +169,17 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     }
   };
   xload(p.qx, 0, 0);   // member 0 owns order 1, which every tile holds
-  // tile_mask: orders that hold at least one row block of this column tile (uniform);
-  // src_tab: lane k*NRW + r = compact row block of this wave's r-th row block in order k
-  int v_any[PIPE_MAX_K];
+  // tile_mask: orders that hold at least one row block of this column tile; rb_out: output row
+  // blocks of this wave's NRW sorted positions.  Scalar loads; member 0's activation scale and
+  // code sums (vector loads) travel at the same time.
+  static_assert(NRW == 4, "descriptor loads are 4 wide");
+  const unsigned tile_mask = cload(p.ct_mask, (size_t)ct);
+  const v4i rb_out4 = cload(reinterpret_cast<const v4i*>(p.rb_out), (size_t)(ct * NRB_WG + wave * NRW) / 4);
+  const int rb_out[NRW] = {rb_out4[0], rb_out4[1], rb_out4[2], rb_out4[3]};
+  float sx = p.s_x[0];
+  int rs[MTB];
 #pragma unroll
-  for (int k = 0; k < PIPE_MAX_K; ++k)
-    v_any[k] = (k < p.K && lane < NRB_WG) ? p.rb_src[(size_t)k * p.n_sorted + ct * NRB_WG + lane] : -1;
-  int src_tab = -1;
-  if (lane < p.K * NRW)
-    src_tab = p.rb_src[(size_t)(lane / NRW) * p.n_sorted + ct * NRB_WG + wave * NRW + (lane % NRW)];
-  int rb_out_v = lane < NRW ? p.rb_out[ct * NRB_WG + wave * NRW + lane] : -1;
-  unsigned tile_mask = 0;
-#pragma unroll
-  for (int k = 0; k < PIPE_MAX_K; ++k)
-    if (__builtin_amdgcn_ballot_w64(v_any[k] >= 0) != 0) tile_mask |= 1u << k;
-  tile_mask = __builtin_amdgcn_readfirstlane(tile_mask);
-  int rb_out[NRW];
-#pragma unroll
-  for (int r = 0; r < NRW; ++r) rb_out[r] = __builtin_amdgcn_readlane(rb_out_v, r);
+  for (int b = 0; b < MTB; ++b) rs[b] = OFF ? p.rowsum[t0 + b * 16 + (lane & 15)] : 0;
 
   const bool fold_sx = p.reduce && p.M > 1;   // multi-member sum: fold s_x into the row scale
   const unsigned scl_lane = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)&Scl[wave][0] + (lane >> 4) * 16;
@@ -199,22 +195,23 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   for (int m = 0; m < p.M; ++m) {
     const uint8_t* qx = p.qx + (size_t)m * p.qx_mstride;
     const int32_t* rowsum = p.rowsum + (size_t)m * p.rowsum_mstride;
-    const float sx = p.s_x[m * p.sx_mstride];
-    int rs[MTB];
+    if (m > 0) {
+      sx = p.s_x[m * p.sx_mstride];
 #pragma unroll
-    for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
+      for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
+    }
 
     for (int k = 0; k < p.K; ++k) {
       if ((int)((p.member_nib >> (4 * k)) & 15ull) != m) continue;
       if (!((tile_mask >> k) & 1u)) continue;   // uniform over the workgroup
-      const uint8_t* pk = uniform_ptr(p.packed[k]);
-      const float* sck = uniform_ptr(p.scales[k]);
-      int src[NRW];
+      const uint8_t* pk = cload(p.packed, (size_t)k);
+      const float* sck = cload(p.scales, (size_t)k);
+      const v4i src4 = cload(reinterpret_cast<const v4i*>(p.rb_src), ((size_t)k * p.n_sorted + ct * NRB_WG + wave * NRW) / 4);
+      const int src[NRW] = {src4[0], src4[1], src4[2], src4[3]};
       const uint8_t* wb[NRW];
       bool active = false;
 #pragma unroll
       for (int r = 0; r < NRW; ++r) {
-        src[r] = __builtin_amdgcn_readlane(src_tab, k * NRW + r);
         active |= src[r] >= 0;
         // a pruned row block among live ones reads row block 0; its result is dropped
         wb[r] = pk + (size_t)(src[r] < 0 ? 0 : src[r]) * nksup * 1024;
@@ -344,30 +341,47 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     // a direct store would touch 16 tokens x 64 B per instruction.  Each 16-token block is instead
     // turned through this wave's 4 KiB of the idle LDS buffer 1 (XOR-swizzled, conflict free) so
     // that one store instruction writes 4 tokens x 256 contiguous bytes: whole cache lines.
+    // The LDS accesses are issued by hand: left to the compiler, every read would first wait
+    // for the previous global store to complete (it orders LDS accesses against all outstanding
+    // vector-memory operations of a kernel that uses LDS-direct loads), serializing the stores.
     float mx = 0.f;
     {
-      float4* stg = reinterpret_cast<float4*>(&Xs[1][wave * 256]);
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));   // keeps the epilogue's address arithmetic out of the main loop's live range
       const int tl = lane_e & 15, g = lane_e >> 4;
-      const int rb_l = __shfl(rb_out_v, tl >> 2, 64);            // row block of the channels this lane stores
+      const unsigned stg = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)&Xs[1][wave * 256];
+      const unsigned wr_row = stg + tl * 256;                    // this lane's token row when writing
+      int rb_l = rb_out[0];                                      // row block of the channels this lane stores
+#pragma unroll
+      for (int q = 1; q < NRW; ++q) rb_l = (tl >> 2) == q ? rb_out[q] : rb_l;
       const int ch = rb_l * 16 + 4 * (tl & 3);
       float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
       if (rb_l >= 0 && (m == 0 || fold_sx) && p.bias != nullptr) bv = *reinterpret_cast<const float4*>(p.bias + ch);
+      const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+      // the bias has to have arrived before the first (conditional) store block: a wait placed
+      // inside those blocks would be repeated in each and then also wait for the stores before it
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      float* ycol = p.y + (size_t)(p.reduce ? 0 : m) * p.T * p.out + ch;
 #pragma unroll
       for (int b = 0; b < MTB; ++b) {
 #pragma unroll
         for (int r = 0; r < NRW; ++r) {
-          stg[tl * 16 + ((r * 4 + g) ^ tl)] = make_float4(yacc[r][b][0], yacc[r][b][1], yacc[r][b][2], yacc[r][b][3]);
+          const v4f val = v4f{yacc[r][b][0], yacc[r][b][1], yacc[r][b][2], yacc[r][b][3]};
+          asm volatile("ds_write_b128 %0, %1" ::"v"(wr_row + (((r * 4 + g) ^ tl) << 4)), "v"(val) : "memory");
 #pragma unroll
           for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
         }
+        v4f a[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int tq = 4 * q + g, t = t0 + b * 16 + tq;
-          const float4 a = stg[tq * 16 + (tl ^ tq)];
-          float v[4] = {a.x, a.y, a.z, a.w};
-          const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+          const int tq = 4 * q + g;
+          asm volatile("ds_read_b128 %0, %1" : "=v"(a[q]) : "v"(stg + tq * 256 + ((tl ^ tq) << 4)) : "memory");
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])::"memory");
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int t = t0 + b * 16 + 4 * q + g;
+          float v[4] = {a[q][0], a[q][1], a[q][2], a[q][3]};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             v[i] = fold_sx ? v[i] + bb[i] : fmaf(sx, v[i], bb[i]);   // same rounding as the streaming kernel
@@ -376,8 +390,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           if (t < p.T && rb_l >= 0) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fabsf(v[i]));
-            float* dst = p.y + ((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + ch;
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4*>(ycol + (size_t)t * p.out) = make_float4(v[0], v[1], v[2], v[3]);
           }
         }
       }
@@ -419,7 +432,7 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.packed = e->packed_ptrs_dev; p.scales = e->scale_ptrs_dev;
-  p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.n_sorted = e->n_sorted;
+  p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.ct_mask = e->ct_mask_dev; p.n_sorted = e->n_sorted;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;

@@ -75,6 +75,7 @@ struct pipe_expansion {
   int n_sorted = 0;                 // sorted row-block list length, padded to a multiple of 64
   int32_t* ct_rb_out_dev = nullptr; // [n_sorted] output row block (channel/16) or -1
   int32_t* ct_src_dev = nullptr;    // [K][n_sorted] compact row block in order k or -1
+  uint32_t* ct_mask_dev = nullptr;  // [n_ct] orders (bit k) that hold at least one row block of the column tile
   // per order device pointers for kernels
   const uint8_t** packed_ptrs_dev = nullptr;  // [K]
   const float** scale_ptrs_dev = nullptr;     // [K]

@@ -41,12 +41,13 @@ __global__ __launch_bounds__(BLK) void absmax_kernel(const float* __restrict__ x
     const int64_t n4 = n >> 2;
     const float4* x4 = reinterpret_cast<const float4*>(x);
     int64_t i = i0;
-    for (; i + 3 * stride < n4; i += 4 * stride) {   // four independent 16-byte loads in flight
-      const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+    for (; i + 7 * stride < n4; i += 8 * stride) {   // eight independent 16-byte loads in flight
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = x4[i + u * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
     }
     for (; i < n4; i += stride) {
       const float4 v = x4[i];
@@ -305,7 +306,7 @@ int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_
   if (n <= 0) return PIPE_OK;
   int64_t blocks = (n / 4 + BLK - 1) / BLK;
   if (blocks < 1) blocks = 1;
-  if (blocks > 2048) blocks = 2048;
+  if (blocks > 256) blocks = 256;   // 1 per CU: every thread keeps 8 loads (128 B) in flight
   hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits, zero_me, n_zero);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
