@@ -98,19 +98,20 @@ static void free_expansion(pipe_expansion* e) {
     if (o.gids_dev) (void)hipFree(o.gids_dev);
     if (o.scales_dev) (void)hipFree(o.scales_dev);
     if (o.packed_dev) (void)hipFree(o.packed_dev);
+    if (o.pos_dev) (void)hipFree(o.pos_dev);
   }
   if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
   if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
   if (e->ct_mask_dev) (void)hipFree(e->ct_mask_dev);
   if (e->bins_dev) (void)hipFree(e->bins_dev);
-  if (e->packed_ptrs_dev) (void)hipFree((void*)e->packed_ptrs_dev);
-  if (e->scale_ptrs_dev) (void)hipFree((void*)e->scale_ptrs_dev);
+  if (e->codes_dev) (void)hipFree(e->codes_dev);
+  if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
   delete e;
 }
 
 // Sort row blocks by the set of orders that hold them (most orders first) and cut the sorted
 // list into column tiles of NRB_TILE row blocks.
-static int build_schedule(pipe_expansion* e) {
+static int build_schedule(pipe_expansion* e, hipStream_t st) {
   const int K = e->K, n_rb = e->n_rb, rbpg = e->rbpg;
   std::vector<std::vector<int32_t>> slot_of(K, std::vector<int32_t>(e->n_groups, -1));
   for (int k = 0; k < K; ++k)
@@ -129,6 +130,44 @@ static int build_schedule(pipe_expansion* e) {
     if (a.mask != b.mask) return a.mask < b.mask;
     return a.rb < b.rb;
   });
+  // Bins of the weight-streaming kernel: output row blocks, most orders first, packed first-fit
+  // into bins of `cap` stored row blocks.  A stored row block's position in the schedule-ordered
+  // buffers is bin * cap + index inside the bin.
+  const int cap = std::min(STREAM_BIN_CAP, std::max(4, K));
+  std::vector<StreamBin> bins;
+  std::vector<int> room;
+  for (int k = 0; k < K; ++k) e->orders[k].pos.assign((size_t)e->orders[k].n_kept * rbpg, -1);
+  for (int i = 0; i < n_rb; ++i) {
+    const int rb = items[i].rb, pop = items[i].pop;
+    const int g = rb / rbpg, b = rb % rbpg;
+    int which = -1;
+    for (int j = (int)bins.size() - 1; j >= 0 && j >= (int)bins.size() - 64; --j)
+      if (room[j] >= pop) { which = j; break; }
+    if (which < 0) {
+      StreamBin nb;
+      std::memset(&nb, 0, sizeof(nb));
+      bins.push_back(nb);
+      room.push_back(cap);
+      which = (int)bins.size() - 1;
+    }
+    StreamBin& bn = bins[which];
+    const int slot = bn.n_out++;
+    bn.out_rb[slot] = rb;
+    for (int k = 0; k < K; ++k) {
+      if (slot_of[k][g] < 0) continue;
+      const int it = bn.n_items++;
+      bn.k[it] = k;
+      bn.slot[it] = slot;
+      e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b] = which * cap + it;
+    }
+    room[which] -= pop;
+  }
+  e->n_bins = (int)bins.size();
+  e->bin_cap = cap;
+  PIPE_HIP(hipMalloc(&e->bins_dev, bins.size() * sizeof(StreamBin)));
+  PIPE_HIP(hipMemcpy(e->bins_dev, bins.data(), bins.size() * sizeof(StreamBin), hipMemcpyHostToDevice));
+
+  // Tile schedule of the tiled kernel over the same sorted row blocks.
   e->n_ct = ceil_div(n_rb, NRB_TILE);
   e->n_sorted = (int)round_up64(n_rb, 64);
   std::vector<int32_t> rb_out((size_t)e->n_sorted, -1);
@@ -138,7 +177,7 @@ static int build_schedule(pipe_expansion* e) {
     const int g = rb / rbpg, b = rb % rbpg;
     rb_out[i] = rb;
     for (int k = 0; k < K; ++k)
-      if (slot_of[k][g] >= 0) src[(size_t)k * e->n_sorted + i] = slot_of[k][g] * rbpg + b;
+      if (slot_of[k][g] >= 0) src[(size_t)k * e->n_sorted + i] = e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b];
   }
   std::vector<uint32_t> ct_mask((size_t)e->n_ct, 0u);
   for (int i = 0; i < n_rb; ++i) ct_mask[i / NRB_TILE] |= items[i].mask;
@@ -148,48 +187,28 @@ static int build_schedule(pipe_expansion* e) {
   PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
   PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));
   PIPE_HIP(hipMemcpy(e->ct_src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice));
-  // Bins of the weight-streaming kernel: output row blocks, most orders first, packed
-  // first-fit into bins of `cap` stored row blocks.
-  {
-    const int cap = std::min(STREAM_BIN_CAP, std::max(4, K));
-    std::vector<StreamBin> bins;
-    std::vector<int> room;
-    for (int i = 0; i < n_rb; ++i) {
-      const int rb = items[i].rb, pop = items[i].pop;
-      const int g = rb / rbpg, b = rb % rbpg;
-      int which = -1;
-      for (int j = (int)bins.size() - 1; j >= 0 && j >= (int)bins.size() - 64; --j)
-        if (room[j] >= pop) { which = j; break; }
-      if (which < 0) {
-        StreamBin nb;
-        std::memset(&nb, 0, sizeof(nb));
-        bins.push_back(nb);
-        room.push_back(cap);
-        which = (int)bins.size() - 1;
-      }
-      StreamBin& bn = bins[which];
-      const int slot = bn.n_out++;
-      bn.out_rb[slot] = rb;
-      for (int k = 0; k < K; ++k) {
-        if (slot_of[k][g] < 0) continue;
-        const int it = bn.n_items++;
-        bn.k[it] = k;
-        bn.crb[it] = slot_of[k][g] * rbpg + b;
-        bn.slot[it] = slot;
-      }
-      room[which] -= pop;
-    }
-    e->n_bins = (int)bins.size();
-    PIPE_HIP(hipMalloc(&e->bins_dev, bins.size() * sizeof(StreamBin)));
-    PIPE_HIP(hipMemcpy(e->bins_dev, bins.data(), bins.size() * sizeof(StreamBin), hipMemcpyHostToDevice));
+
+  // Move the stored row blocks to their positions and drop the per-order buffers.
+  const int64_t rb_bytes = (int64_t)(e->in_pad / (512 / e->bits)) * 1024;
+  const size_t n_pos = (size_t)e->n_bins * cap;
+  PIPE_HIP(hipMalloc(&e->codes_dev, n_pos * (size_t)rb_bytes));
+  PIPE_HIP(hipMalloc(&e->scales_all_dev, n_pos * 16 * sizeof(float)));
+  PIPE_HIP(hipMemsetAsync(e->codes_dev, 0, n_pos * (size_t)rb_bytes, st));
+  PIPE_HIP(hipMemsetAsync(e->scales_all_dev, 0, n_pos * 16 * sizeof(float), st));
+  for (int k = 0; k < K; ++k) {
+    PipeOrder& o = e->orders[k];
+    PIPE_HIP(hipMalloc(&o.pos_dev, o.pos.size() * sizeof(int32_t)));
+    PIPE_HIP(hipMemcpyAsync(o.pos_dev, o.pos.data(), o.pos.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    int rc = launch_gather_row_blocks(o.packed_dev, o.scales_dev, o.pos_dev, (int)o.pos.size(), rb_bytes, e->codes_dev,
+                                      e->scales_all_dev, st);
+    if (rc) return rc;
   }
-  std::vector<const uint8_t*> pp(K);
-  std::vector<const float*> sp(K);
-  for (int k = 0; k < K; ++k) { pp[k] = e->orders[k].packed_dev; sp[k] = e->orders[k].scales_dev; }
-  PIPE_HIP(hipMalloc((void**)&e->packed_ptrs_dev, K * sizeof(void*)));
-  PIPE_HIP(hipMalloc((void**)&e->scale_ptrs_dev, K * sizeof(void*)));
-  PIPE_HIP(hipMemcpy((void*)e->packed_ptrs_dev, pp.data(), K * sizeof(void*), hipMemcpyHostToDevice));
-  PIPE_HIP(hipMemcpy((void*)e->scale_ptrs_dev, sp.data(), K * sizeof(void*), hipMemcpyHostToDevice));
+  PIPE_HIP(hipStreamSynchronize(st));
+  for (int k = 0; k < K; ++k) {
+    PipeOrder& o = e->orders[k];
+    (void)hipFree(o.packed_dev); o.packed_dev = nullptr;
+    (void)hipFree(o.scales_dev); o.scales_dev = nullptr;
+  }
   return PIPE_OK;
 }
 
@@ -237,7 +256,7 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
     o.gids.resize(o.n_kept);
     PIPE_HIP(hipMemcpy(o.gids.data(), o.gids_dev, (size_t)o.n_kept * sizeof(int32_t), hipMemcpyDeviceToHost));
   }
-  return build_schedule(e);
+  return build_schedule(e, st);
 }
 
 extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
@@ -302,11 +321,17 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
   if (group_ids) std::memcpy(group_ids, o.gids.data(), (size_t)o.n_kept * sizeof(int32_t));
   const size_t rows = (size_t)o.n_kept * e->group;
   PIPE_HIP(hipDeviceSynchronize());
-  if (scales) PIPE_HIP(hipMemcpy(scales, o.scales_dev, rows * sizeof(float), hipMemcpyDeviceToHost));
+  if (scales && rows) {
+    // row scales sit at the row blocks' schedule positions
+    const size_t n_pos = (size_t)e->n_bins * e->bin_cap;
+    std::vector<float> all(n_pos * 16);
+    PIPE_HIP(hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost));
+    for (size_t c = 0; c < o.pos.size(); ++c) std::memcpy(scales + c * 16, &all[(size_t)o.pos[c] * 16], 16 * sizeof(float));
+  }
   if (codes_unpacked && rows) {
     int8_t* tmp = nullptr;
     PIPE_HIP(hipMalloc(&tmp, rows * (size_t)e->in));
-    int rc = launch_unpack_codes(o.packed_dev, e->bits, (int)rows, e->in, e->in_pad, tmp, nullptr);
+    int rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, (int)rows, e->in, e->in_pad, tmp, nullptr);
     if (rc == PIPE_OK) {
       hipError_t he = hipMemcpy(codes_unpacked, tmp, rows * (size_t)e->in, hipMemcpyDeviceToHost);
       if (he != hipSuccess) { pipe_note_hip_error(he, "hipMemcpy(codes)"); rc = PIPE_EDEVICE; }

@@ -147,8 +147,9 @@ __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ 
 }
 
 // ---- introspection: tile layout -> one signed code per byte, [rows, in] -------------------
-__global__ void unpack_codes_kernel(const uint8_t* __restrict__ packed, int bits, int rows, int in,
-                                    int in_pad, int8_t* __restrict__ codes) {
+// rb_map (optional): stored position of compact row block crb inside `packed`.
+__global__ void unpack_codes_kernel(const uint8_t* __restrict__ packed, const int32_t* __restrict__ rb_map, int bits,
+                                    int rows, int in, int in_pad, int8_t* __restrict__ codes) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)rows * in) return;
   const int r = (int)(idx / in), k = (int)(idx - (int64_t)r * in);
@@ -157,7 +158,8 @@ __global__ void unpack_codes_kernel(const uint8_t* __restrict__ packed, int bits
   const int c = k >> 4, t = k & 15, ks = c >> 2, kc = c & 3;
   const int ksup = ks / steps, j = ks - ksup * steps;
   const int nksup = in_pad / ksupw;
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(packed + ((size_t)crb * nksup + ksup) * 1024 +
+  const int pos = rb_map ? rb_map[crb] : crb;
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(packed + ((size_t)pos * nksup + ksup) * 1024 +
                                                           (kc * 16 + rr) * 16);
   const int i = t >> 2, b = t & 3;
   int v;
@@ -167,7 +169,31 @@ __global__ void unpack_codes_kernel(const uint8_t* __restrict__ packed, int bits
   codes[idx] = (int8_t)v;
 }
 
+// ---- stored row blocks of one order -> their positions in the schedule-ordered buffers --------
+// One workgroup per row block: rb_bytes of codes (16-byte units) and 16 row scales.
+__global__ __launch_bounds__(256) void gather_row_blocks_kernel(const uint8_t* __restrict__ codes_k,
+                                                                const float* __restrict__ scales_k,
+                                                                const int32_t* __restrict__ pos_of, int64_t rb_bytes,
+                                                                uint8_t* __restrict__ codes_all,
+                                                                float* __restrict__ scales_all) {
+  const int crb = blockIdx.x;
+  const int64_t pos = pos_of[crb];
+  const uint4* s = reinterpret_cast<const uint4*>(codes_k + (size_t)crb * rb_bytes);
+  uint4* d = reinterpret_cast<uint4*>(codes_all + (size_t)pos * rb_bytes);
+  for (int64_t i = threadIdx.x; i < rb_bytes / 16; i += 256) d[i] = s[i];
+  if (threadIdx.x < 16) scales_all[pos * 16 + threadIdx.x] = scales_k[(size_t)crb * 16 + threadIdx.x];
+}
+
 }  // namespace
+
+int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, const int32_t* pos_of_dev, int n_crb,
+                             int64_t rb_bytes, uint8_t* codes_all, float* scales_all, hipStream_t st) {
+  if (n_crb <= 0) return PIPE_OK;
+  hipLaunchKernelGGL(gather_row_blocks_kernel, dim3((unsigned)n_crb), dim3(256), 0, st, codes_k, scales_k, pos_of_dev,
+                     rb_bytes, codes_all, scales_all);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
 
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st) {
   hipLaunchKernelGGL(row_energy_kernel, dim3(out), dim3(BLK), 0, st, E, in, row_energy);
@@ -205,11 +231,11 @@ int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int gr
   return PIPE_OK;
 }
 
-int launch_unpack_codes(const uint8_t* packed, int bits, int rows, int in, int in_pad,
+int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bits, int rows, int in, int in_pad,
                         int8_t* codes, hipStream_t st) {
   const int64_t n = (int64_t)rows * in;
   if (n == 0) return PIPE_OK;
-  hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed,
+  hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, rb_map_dev,
                      bits, rows, in, in_pad, codes);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;

@@ -36,10 +36,10 @@ struct TiledParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* const* packed;   // device [K]: packed codes of every order
-  const float* const* scales;     // device [K]: row scales of every order
+  const uint8_t* codes;           // stored row blocks of all orders, schedule order
+  const float* scales;            // their row scales, 16 per position
   const int32_t* rb_out;          // [n_sorted] output row block of sorted position i, or -1
-  const int32_t* rb_src;          // [K][n_sorted] compact row block in order k, or -1
+  const int32_t* rb_src;          // [K][n_sorted] position of the row block of order k, or -1
   const uint32_t* ct_mask;        // [n_ct] orders present in the column tile
   int n_sorted;                   // padded to a multiple of 64
   const float* bias;
@@ -204,8 +204,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     for (int k = 0; k < p.K; ++k) {
       if ((int)((p.member_nib >> (4 * k)) & 15ull) != m) continue;
       if (!((tile_mask >> k) & 1u)) continue;   // uniform over the workgroup
-      const uint8_t* pk = cload(p.packed, (size_t)k);
-      const float* sck = cload(p.scales, (size_t)k);
+      const uint8_t* pk = p.codes;
+      const float* sck = p.scales;
       const v4i src4 = cload(reinterpret_cast<const v4i*>(p.rb_src), ((size_t)k * p.n_sorted + ct * NRB_WG + wave * NRW) / 4);
       const int src[NRW] = {src4[0], src4[1], src4[2], src4[3]};
       const uint8_t* wb[NRW];
@@ -431,7 +431,7 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
-  p.packed = e->packed_ptrs_dev; p.scales = e->scale_ptrs_dev;
+  p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.ct_mask = e->ct_mask_dev; p.n_sorted = e->n_sorted;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;

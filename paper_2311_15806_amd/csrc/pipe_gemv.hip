@@ -27,8 +27,8 @@ struct StreamParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* packed[PIPE_MAX_K];
-  const float* scales[PIPE_MAX_K];
+  const uint8_t* codes;    // stored row blocks in schedule order: bin b owns positions [b*R, (b+1)*R)
+  const float* scales;     // 16 row scales per position
   const StreamBin* bins;
   const float* bias;
   float* y;
@@ -68,37 +68,19 @@ __device__ __forceinline__ void unpack_step(const uint4& w, int j, v4i& o) {
 }
 
 template <int BITS, int NW, bool SHARED_X, bool ACC_OUT>
-__global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams p) {
+__global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(const StreamParams p) {
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
   constexpr int STEPS = KSUP / 64;      // 64-k steps per packed tile
+  constexpr int NX = SHARED_X ? STEPS : R * STEPS;
   constexpr int BIN_WORDS = sizeof(StreamBin) / 4;
-  static_assert(BIN_WORDS <= 128, "bin descriptor is fetched with two loads per lane");
-  __shared__ int part[NW][R][256];   // each wave's partial tiles of the items in flight
+  static_assert(BIN_WORDS <= 64, "bin descriptor is fetched with one load per lane");
+  __shared__ int part[NW][R][256];   // each wave's partial tiles
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_tiles = (p.nks * 64) / KSUP;
   if (blockIdx.x == 0 && threadIdx.x == 0 && p.zero_after != nullptr) *p.zero_after = 0u;
-
-  // bin descriptor: one memory round trip, then scalar reads out of two vector registers
-  const int32_t* bw = reinterpret_cast<const int32_t*>(p.bins + blockIdx.x);
-  const int d0 = lane < BIN_WORDS ? bw[lane] : 0;
-  const int d1 = lane + 64 < BIN_WORDS ? bw[lane + 64] : 0;
-  // a shared input does not depend on the descriptor: its first tile is requested alongside
-  uint4 x0[SHARED_X ? STEPS : R * STEPS];
-  if (SHARED_X && wave < n_tiles) {
-#pragma unroll
-    for (int j = 0; j < STEPS; ++j) x0[j] = reinterpret_cast<const uint4*>(p.qx + (size_t)(wave * STEPS + j) * 1024)[lane];
-  }
-  auto word = [&](int i) __attribute__((always_inline)) {
-    return i < 64 ? __builtin_amdgcn_readlane(d0, i) : __builtin_amdgcn_readlane(d1, i - 64);
-  };
-  const int n_items = word(0), n_out = word(1);
-  auto item_k = [&](int it) __attribute__((always_inline)) { return word(2 + it); };
-  auto item_crb = [&](int it) __attribute__((always_inline)) { return word(2 + STREAM_BIN_CAP + it); };
-  auto item_slot = [&](int it) __attribute__((always_inline)) { return word(2 + 2 * STREAM_BIN_CAP + it); };
-  auto out_rb = [&](int o) __attribute__((always_inline)) { return word(2 + 3 * STREAM_BIN_CAP + o); };
 
   // epilogue role of this thread: 256 threads per output row block, thread = (token t, channel ch)
   const int e = threadIdx.x & 255;
@@ -108,126 +90,140 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(const StreamParams
   constexpr int O_STEP = (NW * 64) / 256;
   const bool fold_sx = p.reduce && p.M > 1;
 
-  for (int c0 = 0; c0 < n_items; c0 += R) {
-    const uint8_t* wb[R];
-    const uint8_t* xb[R];
-    bool on[R];
+  // ---- everything that does not depend on the bin descriptor is requested first: the bin's R
+  // stored row blocks sit at positions blockIdx.x * R + r of the schedule-ordered buffers, so
+  // the code stream (the HBM traffic that bounds this kernel) starts at once.  Wave w streams
+  // tiles w, w+NW, ...; two tiles per item are in flight.
+  const size_t pos0 = (size_t)blockIdx.x * R;
+  const uint8_t* wb[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      on[r] = c0 + r < n_items;
-      const int it = on[r] ? c0 + r : c0;
-      const int k = item_k(it);
-      wb[r] = pick(p.packed, k) + (size_t)item_crb(it) * n_tiles * 1024;
-      xb[r] = p.qx + (SHARED_X ? (size_t)0 : (size_t)pick(p.member_of, k) * p.qx_mstride);
-    }
-    // what the epilogue of this chunk needs is requested now, so that it arrives during the k loop
-    float scv[R];
-    int itk[R], its[R];
+  for (int r = 0; r < R; ++r) wb[r] = p.codes + (pos0 + r) * (size_t)n_tiles * 1024;
+  const int d0 = lane < BIN_WORDS ? reinterpret_cast<const int32_t*>(p.bins + blockIdx.x)[lane] : 0;
+  uint4 w0[R], w1[R], x0[NX], x1[NX];
+  auto load_w = [&](int tl, uint4 (&w)[R]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int it = on[r] ? c0 + r : c0;
-      itk[r] = item_k(it);
-      its[r] = on[r] ? item_slot(it) : -1;
-      scv[r] = pick(p.scales, itk[r])[(size_t)item_crb(it) * 16 + ch];
+    for (int r = 0; r < R; ++r) w[r] = reinterpret_cast<const uint4*>(wb[r] + (size_t)tl * 1024)[lane];
+  };
+  const uint8_t* xb[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) xb[r] = p.qx;
+  auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
+    if (SHARED_X) {
+#pragma unroll
+      for (int j = 0; j < STEPS; ++j) x[j] = reinterpret_cast<const uint4*>(xb[0] + (size_t)(tl * STEPS + j) * 1024)[lane];
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) x[r * STEPS + j] = reinterpret_cast<const uint4*>(xb[r] + (size_t)(tl * STEPS + j) * 1024)[lane];
     }
+  };
+#pragma unroll
+  for (int j = 0; j < NX; ++j) { x0[j] = make_uint4(0, 0, 0, 0); x1[j] = make_uint4(0, 0, 0, 0); }
+  int tl = wave;
+  if (tl < n_tiles) { load_w(tl, w0); if (SHARED_X) load_x(tl, x0); }
+  if (tl + NW < n_tiles) { load_w(tl + NW, w1); if (SHARED_X) load_x(tl + NW, x1); }
+  // epilogue operands that need no descriptor: row scales (same positions), and per member the
+  // activation scale and this thread's token code sum
+  float scv[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) scv[r] = p.scales[(pos0 + r) * 16 + ch];
+  float sxm[R];
+  int rsm[R];
+#pragma unroll
+  for (int m = 0; m < R; ++m) {       // at most R members (K <= R)
+    const int mm = m < p.M ? m : p.M - 1;
+    sxm[m] = p.s_x[mm * p.sx_mstride];
+    rsm[m] = OFF ? p.rowsum[(size_t)mm * p.rowsum_mstride + t] : 0;
+  }
 
-    v4i acc[R];
+  // ---- the descriptor: scalar reads out of one vector register
+  auto word = [&](int i) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(d0, i); };
+  const int n_items = word(0), n_out = word(1);
+  int itk[R], its[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = v4i{0, 0, 0, 0};
+  for (int r = 0; r < R; ++r) {
+    const bool on = r < n_items;
+    itk[r] = word(2 + (on ? r : 0));
+    its[r] = on ? word(2 + STREAM_BIN_CAP + r) : -1;
+  }
+  auto out_rb = [&](int o) __attribute__((always_inline)) { return word(2 + 2 * STREAM_BIN_CAP + o); };
+  if (!SHARED_X) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) xb[r] = p.qx + (size_t)pick(p.member_of, itk[r]) * p.qx_mstride;
+    if (tl < n_tiles) load_x(tl, x0);
+    if (tl + NW < n_tiles) load_x(tl + NW, x1);
+  }
 
-    // wave w streams tiles w, w+NW, ...; two tiles are in flight (the loads of tile t+NW are
-    // issued before the MFMAs of tile t)
-    uint4 w0[R], w1[R];
-    uint4 x1[SHARED_X ? STEPS : R * STEPS];
-    if (!(SHARED_X && c0 == 0)) {
+  v4i acc[R];
 #pragma unroll
-      for (int j = 0; j < (SHARED_X ? STEPS : R * STEPS); ++j) x0[j] = make_uint4(0, 0, 0, 0);
-    }
-    auto load_tile = [&](int tl, uint4 (&w)[R], uint4 (&x)[SHARED_X ? STEPS : R * STEPS], bool have_x = false) __attribute__((always_inline)) {
+  for (int r = 0; r < R; ++r) acc[r] = v4i{0, 0, 0, 0};
+  auto mul_tile = [&](uint4 (&w)[R], uint4 (&x)[NX]) __attribute__((always_inline)) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) w[r] = reinterpret_cast<const uint4*>(wb[r] + (size_t)tl * 1024)[lane];
-      if (have_x) return;
-      if (SHARED_X) {
+    for (int j = 0; j < STEPS; ++j) {
 #pragma unroll
-        for (int j = 0; j < STEPS; ++j) x[j] = reinterpret_cast<const uint4*>(xb[0] + (size_t)(tl * STEPS + j) * 1024)[lane];
-      } else {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-          for (int j = 0; j < STEPS; ++j) x[r * STEPS + j] = reinterpret_cast<const uint4*>(xb[r] + (size_t)(tl * STEPS + j) * 1024)[lane];
+      for (int r = 0; r < R; ++r) {
+        const uint4 xv = x[SHARED_X ? j : r * STEPS + j];
+        const v4i xf = v4i{(int)xv.x, (int)xv.y, (int)xv.z, (int)xv.w};
+        v4i wf;
+        unpack_step<BITS>(w[r], j, wf);
+        acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
       }
-    };
-    auto mul_tile = [&](uint4 (&w)[R], uint4 (&x)[SHARED_X ? STEPS : R * STEPS]) __attribute__((always_inline)) {
+    }
+  };
+  for (; tl < n_tiles; tl += 2 * NW) {
+    mul_tile(w0, x0);
+    if (tl + 2 * NW < n_tiles) { load_w(tl + 2 * NW, w0); load_x(tl + 2 * NW, x0); }
+    if (tl + NW < n_tiles) {
+      mul_tile(w1, x1);
+      if (tl + 3 * NW < n_tiles) { load_w(tl + 3 * NW, w1); load_x(tl + 3 * NW, x1); }
+    }
+  }
 #pragma unroll
-      for (int j = 0; j < STEPS; ++j) {
+  for (int r = 0; r < R; ++r)
+    *reinterpret_cast<v4i*>(&part[wave][r][lane * 4]) = acc[r];
+  __syncthreads();
+
+  // epilogue: exact integer sum over the waves, then the fixed-order fp32 sum (same evaluation
+  // order as the tiled kernel): one member, or members kept apart:
+  //   y_m = s_x,m * (sum_k s_k * a_k) + b;  members summed: y = sum_m sum_k (s_k * s_x,m) * a_k + b.
+  for (int o = o_first; o < n_out; o += O_STEP) {
+    // a row block's items are adjacent, in ascending order k
+    const int col = out_rb(o) * 16 + ch;
+    const float bias = p.bias != nullptr ? p.bias[col] : 0.f;
+    float yacc = 0.f;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-          const uint4 xv = x[SHARED_X ? j : r * STEPS + j];
-          const v4i xf = v4i{(int)xv.x, (int)xv.y, (int)xv.z, (int)xv.w};
-          v4i wf;
-          unpack_step<BITS>(w[r], j, wf);
-          acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
+    for (int m = 0; m < R; ++m) {
+      if (m >= p.M) break;
+      const int rs = rsm[m];
+      const float sx = sxm[m];
+      const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (its[r] != o || itk[r] < k_lo || itk[r] > k_hi) continue;
+        int a = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) a += part[w][r][fidx];
+        a -= OFF * rs;
+        const float sc = fold_sx ? scv[r] * sx : scv[r];
+        yacc = fmaf(sc, (float)a, yacc);
+        if (ACC_OUT) {
+          if (t < p.T) p.acc_out[((size_t)itk[r] * p.T + t) * p.out + col] = a;
         }
       }
-    };
-    int tl = wave;
-    if (tl < n_tiles) load_tile(tl, w0, x0, SHARED_X && c0 == 0);
-    for (; tl < n_tiles; tl += 2 * NW) {
-      if (tl + NW < n_tiles) load_tile(tl + NW, w1, x1);
-      mul_tile(w0, x0);
-      if (tl + NW < n_tiles) {
-        if (tl + 2 * NW < n_tiles) load_tile(tl + 2 * NW, w0, x0);
-        mul_tile(w1, x1);
+      if (ACC_OUT) continue;
+      if (fold_sx && m + 1 < p.M) continue;
+      const float bm = (m == 0 || fold_sx) ? bias : 0.f;
+      float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the tiled kernel
+      yacc = 0.f;
+      if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
+      if (p.amax_out != nullptr) {
+        float mx = t < p.T ? fabsf(v) : 0.f;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
+        if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
       }
-    }
-    if (c0 > 0) __syncthreads();   // the previous chunk's partial tiles have been consumed
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-      *reinterpret_cast<v4i*>(&part[wave][r][lane * 4]) = acc[r];
-    __syncthreads();
-
-    // epilogue of this chunk: exact integer sum over the waves, then the fixed-order fp32 sum
-    // (same evaluation order as the tiled kernel): one member, or members kept apart:
-    //   y_m = s_x,m * (sum_k s_k * a_k) + b;  members summed: y = sum_m sum_k (s_k * s_x,m) * a_k + b.
-    for (int o = o_first; o < n_out; o += O_STEP) {
-      bool mine = false;
-#pragma unroll
-      for (int r = 0; r < R; ++r) mine |= its[r] == o;
-      if (!mine) continue;
-      // a row block's items are adjacent and, with K <= R, never split across chunks
-      const int col = out_rb(o) * 16 + ch;
-      float yacc = 0.f;
-      for (int m = 0; m < p.M; ++m) {
-        const int rs = OFF ? p.rowsum[(size_t)m * p.rowsum_mstride + t] : 0;
-        const float sx = p.s_x[m * p.sx_mstride];
-        const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {      // items of a row block are stored in ascending order k
-          if (its[r] != o || itk[r] < k_lo || itk[r] > k_hi) continue;
-          int a = 0;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) a += part[w][r][fidx];
-          a -= OFF * rs;
-          const float sc = fold_sx ? scv[r] * sx : scv[r];
-          yacc = fmaf(sc, (float)a, yacc);
-          if (ACC_OUT) {
-            if (t < p.T) p.acc_out[((size_t)itk[r] * p.T + t) * p.out + col] = a;
-          }
-        }
-        if (ACC_OUT) continue;
-        if (fold_sx && m + 1 < p.M) continue;
-        const float bm = ((m == 0 || fold_sx) && p.bias != nullptr) ? p.bias[col] : 0.f;
-        float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the tiled kernel
-        yacc = 0.f;
-        if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
-        if (p.amax_out != nullptr) {
-          float mx = t < p.T ? fabsf(v) : 0.f;
-#pragma unroll
-          for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
-          if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
-        }
-        if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
-      }
+      if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
     }
   }
 }
@@ -251,15 +247,12 @@ int launch_nw(const StreamParams& p, int n_bins, bool shared_x, bool acc_out, co
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   const pipe_expansion* e = a.e;
   if (a.T <= 0) return PIPE_OK;
-  if (a.T > 16 || a.T_pad != 16 || e->K > R) return PIPE_ESHAPE;
+  if (a.T > 16 || a.T_pad != 16 || e->K > R || e->bin_cap != R) return PIPE_ESHAPE;
   StreamParams p;
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
-  for (int k = 0; k < PIPE_MAX_K; ++k) {
-    p.packed[k] = k < e->K ? e->orders[k].packed_dev : nullptr;
-    p.scales[k] = k < e->K ? e->orders[k].scales_dev : nullptr;
-  }
+  p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.bins = e->bins_dev;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;

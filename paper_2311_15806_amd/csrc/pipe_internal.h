@@ -45,7 +45,6 @@ constexpr int STREAM_BIN_CAP = 16;
 struct StreamBin {
   int32_t n_items, n_out;
   int32_t k[STREAM_BIN_CAP];       // 0-based order of the item
-  int32_t crb[STREAM_BIN_CAP];     // compact row block inside that order
   int32_t slot[STREAM_BIN_CAP];    // index into out_rb
   int32_t out_rb[STREAM_BIN_CAP];  // output row block (channel / 16)
 };
@@ -53,10 +52,12 @@ struct StreamBin {
 struct PipeOrder {
   int n_kept = 0;               // groups stored at this order
   int32_t* gids_dev = nullptr;  // [n_kept] ascending
-  float* scales_dev = nullptr;  // [n_kept*group]
-  uint8_t* packed_dev = nullptr;
+  float* scales_dev = nullptr;  // [n_kept*group]: while the expansion is built, then freed
+  uint8_t* packed_dev = nullptr;  // tile layout in compact row order: while the expansion is built, then freed
   size_t packed_bytes = 0;
   std::vector<int32_t> gids;    // host copy
+  int32_t* pos_dev = nullptr;   // [n_kept*group/16] position of compact row block c in codes_dev / scales_all_dev
+  std::vector<int32_t> pos;     // host copy
 };
 
 struct pipe_expansion {
@@ -74,13 +75,14 @@ struct pipe_expansion {
   int n_ct = 0;                     // column tiles of NRB_TILE row blocks
   int n_sorted = 0;                 // sorted row-block list length, padded to a multiple of 64
   int32_t* ct_rb_out_dev = nullptr; // [n_sorted] output row block (channel/16) or -1
-  int32_t* ct_src_dev = nullptr;    // [K][n_sorted] compact row block in order k or -1
+  int32_t* ct_src_dev = nullptr;    // [K][n_sorted] position (in codes_dev) of the row block in order k, or -1
   uint32_t* ct_mask_dev = nullptr;  // [n_ct] orders (bit k) that hold at least one row block of the column tile
-  // per order device pointers for kernels
-  const uint8_t** packed_ptrs_dev = nullptr;  // [K]
-  const float** scale_ptrs_dev = nullptr;     // [K]
-  // bins of the weight-streaming kernel
-  int n_bins = 0;
+  // Stored row blocks of all orders in schedule order: bin b of the weight-streaming kernel owns
+  // positions [b*bin_cap, (b+1)*bin_cap), so that kernel addresses its codes from its block index
+  // alone; the tiled kernel reaches them through ct_src_dev.  Unused positions are zero.
+  uint8_t* codes_dev = nullptr;       // [n_bins*bin_cap][in_pad/KSUP][1 KiB]
+  float* scales_all_dev = nullptr;    // [n_bins*bin_cap][16]
+  int n_bins = 0, bin_cap = 0;
   StreamBin* bins_dev = nullptr;
   int64_t stream_bytes = 0;  // packed codes + scales + indices
 };
@@ -113,8 +115,10 @@ int launch_group_select(const double* row_energy, int n_groups, int group, int n
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
                          hipStream_t st);
-int launch_unpack_codes(const uint8_t* packed, int bits, int rows, int in, int in_pad,
+int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bits, int rows, int in, int in_pad,
                         int8_t* codes, hipStream_t st);
+int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, const int32_t* pos_of_dev, int n_crb,
+                             int64_t rb_bytes, uint8_t* codes_all, float* scales_all, hipStream_t st);
 
 // ------------------------------------------------------------------ activation kernels (pipe_quant.hip)
 // amax_bits: device uint32 holding the bit pattern of max|x| (must be zeroed first).
