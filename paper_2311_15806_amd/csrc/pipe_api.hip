@@ -370,6 +370,7 @@ static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
 }
 
 // ------------------------------------------------------------------ kernel timing
+static bool g_amax_h_dirty = false;   // the members' max|h| slots hold a value no kernel will clear
 static bool g_timing_on = false;
 static std::vector<hipEvent_t> g_events;   // pairs: start, stop
 static size_t g_events_used = 0;
@@ -399,7 +400,7 @@ extern "C" int pipe_timing_read(double* total_ms, int* launches) {
 static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s_x, const ActBuffers& b, bool small,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
   if (small)
-    return launch_quantize_small(x_dev, 0, 1, T, in, in_pad, s_x, b.qx, 0, b.rowsum, qx_rowmajor, scale_out, st);
+    return launch_quantize_small(x_dev, 0, 1, T, in, in_pad, s_x, nullptr, b.qx, 0, b.rowsum, qx_rowmajor, scale_out, st);
   // The reduction slot is zero on entry (workspace allocation, then every contraction kernel
   // clears it again); the reduction kernel also clears the code sums, so a dynamic scale costs
   // two launches and no memset.
@@ -552,10 +553,14 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
 
   rc = quantize_input(x_dev, T, l1->in, l1->in_pad, s_x, b, small, nullptr, b.scale, st);
   if (rc) return rc;
-  if (!small) {
-    rc = launch_zero_u32(amax_h, Mm, st);
+  // The members' max|h| slots are zero on entry: cleared when the workspace is allocated and,
+  // after each use, by the layer-2 kernel that follows their last reader.  A call that failed
+  // between the two leaves them dirty; then they are cleared by a launch of their own.
+  if (g_amax_h_dirty) {
+    rc = launch_zero_u32(amax_h, PIPE_MAX_K, st);
     if (rc) return rc;
   }
+  g_amax_h_dirty = true;
 
   // layer 1: every member reads the same Q(x); outputs stay separate
   GemmArgs a{};
@@ -563,7 +568,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   a.bias = bias1_dev; a.reduce = 0; a.zero_after = b.amax;
   fill_members(a, Mm, lo, hi);
   if (act == PIPE_ACT_GELU) {
-    a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = small ? nullptr : amax_h;
+    a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
   } else {
@@ -575,8 +580,8 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   }
   // each member quantizes its own hidden activation with its own scale
   if (small) {
-    rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, qh, (int64_t)T_pad * l2->in_pad, rowsum_h,
-                               nullptr, scale_h, st);
+    rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, amax_h, qh, (int64_t)T_pad * l2->in_pad,
+                               rowsum_h, nullptr, scale_h, st);
     if (rc) return rc;
   }
   for (int m = 0; m < Mm && !small; ++m) {
@@ -590,6 +595,9 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   a2.e = l2; a2.T = T; a2.T_pad = T_pad; a2.qx = qh; a2.qx_mstride = (int64_t)T_pad * l2->in_pad;
   a2.rowsum = rowsum_h; a2.rowsum_mstride = T_pad; a2.s_x = scale_h; a2.sx_mstride = 1;
   a2.bias = bias2_dev; a2.reduce = 1; a2.act = 0; a2.y = y_dev;
+  a2.zero_after = amax_h; a2.zero_n = Mm;
   fill_members(a2, Mm, lo, hi);
-  return run_gemm(a2, small, st);
+  rc = run_gemm(a2, small, st);
+  if (rc == PIPE_OK) g_amax_h_dirty = false;
+  return rc;
 }

@@ -47,6 +47,7 @@ struct TiledParams {
   int32_t* acc_out;
   uint32_t* amax_out;
   uint32_t* zero_after;
+  int zero_n;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
   int n_st_t;                     // super-tiles along tokens
   unsigned long long member_nib;  // member of order k in bits [4k, 4k+4)
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     tt = st * 8 + (local & 7);
     if (ct >= p.n_ct || tt >= p.n_tt) return;
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0 && p.zero_after != nullptr) *p.zero_after = 0u;
+  if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
   const int t0 = tt * (16 * MTB);
   // LDS byte address of this lane's 16 bytes inside fragment 0 of buffer 0
   const unsigned xs_lane = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)&Xs[0][0] + lane * 16;
@@ -433,7 +434,7 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.ct_mask = e->ct_mask_dev; p.n_sorted = e->n_sorted;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.member_nib = 0;

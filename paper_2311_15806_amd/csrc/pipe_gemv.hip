@@ -35,6 +35,7 @@ struct StreamParams {
   int32_t* acc_out;
   uint32_t* amax_out;
   uint32_t* zero_after;
+  int zero_n;
   int T, out, K, nks, M, reduce, act;
   int member_lo[PIPE_MAX_K];
   int member_hi[PIPE_MAX_K];
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_tiles = (p.nks * 64) / KSUP;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && p.zero_after != nullptr) *p.zero_after = 0u;
+  if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
 
   // epilogue role of this thread: 256 threads per output row block, thread = (token t, channel ch)
   const int e = threadIdx.x & 255;
@@ -254,7 +255,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.bins = e->bins_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   for (int m = 0; m < PIPE_MAX_K; ++m) { p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m]; p.member_of[m] = 0; }
   for (int m = 0; m < a.M; ++m)

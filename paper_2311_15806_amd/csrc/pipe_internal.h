@@ -134,8 +134,8 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
 // Decode-sized batches (T <= 16, T_pad == 16): max|x|, scale, codes and code sums in ONE launch,
 // one workgroup per member (x, qx_frag, rowsum [16 per member], scale_out [M] with member strides).
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
-                          uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum, int8_t* qx_rowmajor,
-                          float* scale_out, hipStream_t st);
+                          const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
+                          int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
 // Same for the virtual im2col matrix of a convolution.
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
@@ -165,7 +165,8 @@ struct GemmArgs {
   float* y;
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
-  uint32_t* zero_after;  // a word the kernel clears (the max|x| slot this call consumed), or nullptr
+  uint32_t* zero_after;  // words the kernel clears (the max|x| slots this call consumed), or nullptr
+  int zero_n = 1;        // how many (at most 64)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // if set: the dispatch's own begin/end timestamps
 };
 // Launches with the dispatch's begin/end timestamps recorded into the two events when they are set

@@ -156,6 +156,7 @@ __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restri
 constexpr int SBLK = 256;
 __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __restrict__ x_all, int64_t x_mstride,
                                                               int T, int in, int in_pad, float s_static,
+                                                              const uint32_t* __restrict__ amax_bits,
                                                               uint8_t* __restrict__ qx_all, int64_t qx_mstride,
                                                               int32_t* __restrict__ rowsum_all,
                                                               int8_t* __restrict__ qx_rowmajor,
@@ -167,7 +168,10 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
   __shared__ float smax[SBLK / 64];
   __shared__ int ssum[SBLK / 64];
   float s = s_static;
-  if (!(s_static > 0.f)) {
+  if (!(s_static > 0.f) && amax_bits != nullptr) {
+    // the producer of x already reduced max|x| of member m
+    s = __fdiv_rn(__uint_as_float(amax_bits[m]), 127.f);
+  } else if (!(s_static > 0.f)) {
     float mx = 0.f;
     const int64_t cnt = (int64_t)T * in;
     if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
@@ -336,10 +340,10 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
 }
 
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
-                          uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum, int8_t* qx_rowmajor,
-                          float* scale_out, hipStream_t st) {
+                          const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
+                          int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
   hipLaunchKernelGGL(quantize_small_kernel, dim3(16, M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
-                     qx_frag, qx_mstride, rowsum, qx_rowmajor, scale_out);
+                     amax_bits, qx_frag, qx_mstride, rowsum, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
