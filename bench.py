@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 tiled MFMA, 2 weight streaming")
+    ap.add_argument("--stream-split", type=int, default=0,
+                    help="workgroups per bin of the weight-streaming kernel (0 = automatic)")
     ap.add_argument("--no-graph", action="store_true", help="time decode steps eagerly instead of as one HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy 5 times (reference for the FETCH_SIZE/WRITE_SIZE counters)")
@@ -71,6 +73,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     pipe.pipe_set_kernel(args.kernel)
+    pipe.pipe_set_stream_split(args.stream_split)
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
         b = torch.empty_like(a)

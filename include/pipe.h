@@ -133,6 +133,16 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
  * small-batch kernel.  Returns PIPE_EINVAL for other values.                    */
 int pipe_set_kernel(int which);
 
+/* Split of the weight-streaming kernel's bins along in_features (tuning and tests).
+ * A bin (up to 4 stored row blocks holding every order of a few output row blocks)
+ * is normally streamed by one workgroup; layers with few output channels and a long
+ * in_features are split over several workgroups per bin, whose exact integer
+ * partial sums meet in a workspace owned by the expansion (so two forward calls on
+ * the same expansion must not overlap in time).  0 = automatic (default), n >= 1 =
+ * that many workgroups per bin (capped by the number of packed k tiles).  Results
+ * do not depend on the setting.  Returns PIPE_EINVAL outside 0..8.                */
+int pipe_set_stream_split(int workgroups_per_bin);
+
 /* Kernel timing for benchmarks.  While enabled, every forward call brackets its
  * contraction kernel (the dominant kernel of the path) with a pair of HIP events
  * recorded on the call's stream.  pipe_timing_read waits for the recorded events,

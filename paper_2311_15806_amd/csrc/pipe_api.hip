@@ -62,6 +62,12 @@ extern "C" int pipe_set_kernel(int which) {
   return PIPE_OK;
 }
 
+extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
+  if (workgroups_per_bin < 0 || workgroups_per_bin > PIPE_MAX_SPLIT) return PIPE_EINVAL;
+  g_stream_ksplit = workgroups_per_bin;
+  return PIPE_OK;
+}
+
 // ------------------------------------------------------------------ helpers
 static int n_keep_of(float gamma, int n_groups) {
   const double v = (double)gamma * (double)n_groups * (1.0 - 1e-6);
@@ -106,6 +112,8 @@ static void free_expansion(pipe_expansion* e) {
   if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->codes_dev) (void)hipFree(e->codes_dev);
   if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
+  if (e->split_sum_dev) (void)hipFree(e->split_sum_dev);
+  if (e->split_cnt_dev) (void)hipFree(e->split_cnt_dev);
   delete e;
 }
 
@@ -195,6 +203,9 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
   PIPE_HIP(hipMalloc(&e->scales_all_dev, n_pos * 16 * sizeof(float)));
   PIPE_HIP(hipMemsetAsync(e->codes_dev, 0, n_pos * (size_t)rb_bytes, st));
   PIPE_HIP(hipMemsetAsync(e->scales_all_dev, 0, n_pos * 16 * sizeof(float), st));
+  PIPE_HIP(hipMalloc(&e->split_sum_dev, n_pos * PIPE_MAX_SPLIT * 256 * sizeof(int32_t)));
+  PIPE_HIP(hipMalloc(&e->split_cnt_dev, (size_t)e->n_bins * sizeof(uint32_t)));
+  PIPE_HIP(hipMemsetAsync(e->split_cnt_dev, 0, (size_t)e->n_bins * sizeof(uint32_t), st));
   for (int k = 0; k < K; ++k) {
     PipeOrder& o = e->orders[k];
     PIPE_HIP(hipMalloc(&o.pos_dev, o.pos.size() * sizeof(int32_t)));

@@ -14,6 +14,10 @@
 // more than 4 orders take the tiled kernel at every batch size.
 #include "pipe_internal.h"
 
+#include <algorithm>
+
+int g_stream_ksplit = 0;   // 0: automatic
+
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -37,6 +41,9 @@ struct StreamParams {
   uint32_t* zero_after;
   int zero_n;
   int T, out, K, nks, M, reduce, act;
+  int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
+  int32_t* ws_sum;         // [n_bins][ksplit][R][256] partial tiles of split bins
+  uint32_t* ws_cnt;        // [n_bins] arrival counters, zero between launches
   int member_lo[PIPE_MAX_K];
   int member_hi[PIPE_MAX_K];
   int member_of[PIPE_MAX_K];
@@ -68,15 +75,18 @@ __device__ __forceinline__ void unpack_step(const uint4& w, int j, v4i& o) {
   }
 }
 
-template <int BITS, int NW, bool SHARED_X, bool ACC_OUT>
-__global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(const StreamParams p) {
+// XM = number of distinct activation tensors the items of a bin can read: 1 (one input for all
+// orders), or 2 / 4 (one input per ensemble member, at most XM members).
+template <int BITS, int NW, int XM, bool ACC_OUT>
+__global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)) <= 4) ? 4 : 2) void gemm_stream_kernel(const StreamParams p) {
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
   constexpr int STEPS = KSUP / 64;      // 64-k steps per packed tile
-  constexpr int NX = SHARED_X ? STEPS : R * STEPS;
+  constexpr int NX = XM * STEPS;
   constexpr int BIN_WORDS = sizeof(StreamBin) / 4;
   static_assert(BIN_WORDS <= 64, "bin descriptor is fetched with one load per lane");
   __shared__ int part[NW][R][256];   // each wave's partial tiles
+  __shared__ int s_last;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -95,35 +105,35 @@ __global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(
   // stored row blocks sit at positions blockIdx.x * R + r of the schedule-ordered buffers, so
   // the code stream (the HBM traffic that bounds this kernel) starts at once.  Wave w streams
   // tiles w, w+NW, ...; two tiles per item are in flight.
-  const size_t pos0 = (size_t)blockIdx.x * R;
+  const int bin = p.ksplit > 1 ? (int)blockIdx.x / p.ksplit : (int)blockIdx.x;
+  const int ksp = p.ksplit > 1 ? (int)blockIdx.x - bin * p.ksplit : 0;
+  // this workgroup's share of the k tiles
+  const int tile_lo = (int)((long long)n_tiles * ksp / p.ksplit), tile_hi = (int)((long long)n_tiles * (ksp + 1) / p.ksplit);
+  const size_t pos0 = (size_t)bin * R;
   const uint8_t* wb[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) wb[r] = p.codes + (pos0 + r) * (size_t)n_tiles * 1024;
-  const int d0 = lane < BIN_WORDS ? reinterpret_cast<const int32_t*>(p.bins + blockIdx.x)[lane] : 0;
+  const int d0 = lane < BIN_WORDS ? reinterpret_cast<const int32_t*>(p.bins + bin)[lane] : 0;
   uint4 w0[R], w1[R], x0[NX], x1[NX];
   auto load_w = [&](int tl, uint4 (&w)[R]) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < R; ++r) w[r] = reinterpret_cast<const uint4*>(wb[r] + (size_t)tl * 1024)[lane];
   };
-  const uint8_t* xb[R];
+  // member m's activations (members beyond M repeat the last one; never used)
+  const uint8_t* xb[XM];
 #pragma unroll
-  for (int r = 0; r < R; ++r) xb[r] = p.qx;
+  for (int m = 0; m < XM; ++m) xb[m] = p.qx + (size_t)(m < p.M ? m : p.M - 1) * p.qx_mstride;
   auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
-    if (SHARED_X) {
 #pragma unroll
-      for (int j = 0; j < STEPS; ++j) x[j] = reinterpret_cast<const uint4*>(xb[0] + (size_t)(tl * STEPS + j) * 1024)[lane];
-    } else {
+    for (int m = 0; m < XM; ++m)
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < STEPS; ++j) x[r * STEPS + j] = reinterpret_cast<const uint4*>(xb[r] + (size_t)(tl * STEPS + j) * 1024)[lane];
-    }
+      for (int j = 0; j < STEPS; ++j) x[m * STEPS + j] = reinterpret_cast<const uint4*>(xb[m] + (size_t)(tl * STEPS + j) * 1024)[lane];
   };
 #pragma unroll
   for (int j = 0; j < NX; ++j) { x0[j] = make_uint4(0, 0, 0, 0); x1[j] = make_uint4(0, 0, 0, 0); }
-  int tl = wave;
-  if (tl < n_tiles) { load_w(tl, w0); if (SHARED_X) load_x(tl, x0); }
-  if (tl + NW < n_tiles) { load_w(tl + NW, w1); if (SHARED_X) load_x(tl + NW, x1); }
+  int tl = tile_lo + wave;
+  if (tl < tile_hi) { load_w(tl, w0); load_x(tl, x0); }
+  if (tl + NW < tile_hi) { load_w(tl + NW, w1); load_x(tl + NW, x1); }
   // epilogue operands that need no descriptor: row scales (same positions), and per member the
   // activation scale and this thread's token code sum
   float scv[R];
@@ -149,12 +159,9 @@ __global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(
     its[r] = on ? word(2 + STREAM_BIN_CAP + r) : -1;
   }
   auto out_rb = [&](int o) __attribute__((always_inline)) { return word(2 + 2 * STREAM_BIN_CAP + o); };
-  if (!SHARED_X) {
+  int itm[R];   // which activation tensor item r reads
 #pragma unroll
-    for (int r = 0; r < R; ++r) xb[r] = p.qx + (size_t)pick(p.member_of, itk[r]) * p.qx_mstride;
-    if (tl < n_tiles) load_x(tl, x0);
-    if (tl + NW < n_tiles) load_x(tl + NW, x1);
-  }
+  for (int r = 0; r < R; ++r) itm[r] = XM == 1 ? 0 : pick(p.member_of, itk[r]);
 
   v4i acc[R];
 #pragma unroll
@@ -164,26 +171,63 @@ __global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(
     for (int j = 0; j < STEPS; ++j) {
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        const uint4 xv = x[SHARED_X ? j : r * STEPS + j];
-        const v4i xf = v4i{(int)xv.x, (int)xv.y, (int)xv.z, (int)xv.w};
+        v4i xf = v4i{(int)x[j].x, (int)x[j].y, (int)x[j].z, (int)x[j].w};
+#pragma unroll
+        for (int m = 1; m < XM; ++m) {   // uniform select, component by component
+          const bool pickm = itm[r] == m;
+          xf[0] = pickm ? (int)x[m * STEPS + j].x : xf[0];
+          xf[1] = pickm ? (int)x[m * STEPS + j].y : xf[1];
+          xf[2] = pickm ? (int)x[m * STEPS + j].z : xf[2];
+          xf[3] = pickm ? (int)x[m * STEPS + j].w : xf[3];
+        }
         v4i wf;
         unpack_step<BITS>(w[r], j, wf);
         acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
       }
     }
   };
-  for (; tl < n_tiles; tl += 2 * NW) {
+  for (; tl < tile_hi; tl += 2 * NW) {
     mul_tile(w0, x0);
-    if (tl + 2 * NW < n_tiles) { load_w(tl + 2 * NW, w0); load_x(tl + 2 * NW, x0); }
-    if (tl + NW < n_tiles) {
+    if (tl + 2 * NW < tile_hi) { load_w(tl + 2 * NW, w0); load_x(tl + 2 * NW, x0); }
+    if (tl + NW < tile_hi) {
       mul_tile(w1, x1);
-      if (tl + 3 * NW < n_tiles) { load_w(tl + 3 * NW, w1); load_x(tl + 3 * NW, x1); }
+      if (tl + 3 * NW < tile_hi) { load_w(tl + 3 * NW, w1); load_x(tl + 3 * NW, x1); }
     }
   }
 #pragma unroll
   for (int r = 0; r < R; ++r)
     *reinterpret_cast<v4i*>(&part[wave][r][lane * 4]) = acc[r];
   __syncthreads();
+
+  // A split bin: every workgroup writes its integer partial tiles to its own slice of the bin's
+  // workspace with device-scope stores (written through to memory, no cache maintenance), waits
+  // for them to complete (vmcnt counts stores) and then counts its arrival; the one that arrives
+  // last reads all slices with device-scope loads, sums them (exact, order independent), resets
+  // the counter and runs the epilogue.  Nobody waits for anybody.
+  if (p.ksplit > 1) {
+    int32_t* ws = p.ws_sum + ((size_t)bin * p.ksplit + ksp) * (R * 256);
+    for (int i = threadIdx.x; i < R * 256; i += NW * 64) {
+      int a = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) a += (&part[w][0][0])[i];
+      __hip_atomic_store(&ws[i], a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&p.ws_cnt[bin], 1u) == (unsigned)(p.ksplit - 1);
+    __syncthreads();
+    if (!s_last) return;
+    const int32_t* wsb = p.ws_sum + (size_t)bin * p.ksplit * (R * 256);
+    for (int i = threadIdx.x; i < R * 256; i += NW * 64) {
+      int a = 0;
+      for (int q = 0; q < p.ksplit; ++q) a += __hip_atomic_load(&wsb[(size_t)q * (R * 256) + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      (&part[0][0][0])[i] = a;
+#pragma unroll
+      for (int w = 1; w < NW; ++w) (&part[w][0][0])[i] = 0;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(&p.ws_cnt[bin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+  }
 
   // epilogue: exact integer sum over the waves, then the fixed-order fp32 sum (same evaluation
   // order as the tiled kernel): one member, or members kept apart:
@@ -230,14 +274,16 @@ __global__ __launch_bounds__(NW * 64, SHARED_X ? 4 : 2) void gemm_stream_kernel(
 }
 
 template <int BITS, int NW>
-int launch_nw(const StreamParams& p, int n_bins, bool shared_x, bool acc_out, const GemmArgs& a, hipStream_t st) {
-  const dim3 grid((unsigned)n_bins), blk(NW * 64);
+int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const GemmArgs& a, hipStream_t st) {
+  const dim3 grid((unsigned)(n_bins * p.ksplit)), blk(NW * 64);
   if (acc_out) {
-    if (shared_x) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, true, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, false, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    if (xm == 1) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else if (xm == 2) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 2, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 4, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
   } else {
-    if (shared_x) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, true, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, false, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    if (xm == 1) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else if (xm == 2) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 2, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 4, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
   }
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -257,14 +303,27 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.bins = e->bins_dev;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
+  // Fewer bins than half the CUs and a long k: split each bin over several workgroups (each still
+  // with at least two tiles per wave).  With more bins a split only adds the exchange through
+  // the workspace (measured on the 4096 x 11008 4-bit layer: 160 bins, 21.7 us unsplit, 23.5 us
+  // split in three).
+  {
+    const int n_tiles = e->in_pad / (512 / e->bits);
+    int ks;
+    if (g_stream_ksplit > 0) ks = std::min(std::min(g_stream_ksplit, PIPE_MAX_SPLIT), n_tiles);   // forced (tests, tuning)
+    else ks = std::min(256 / (e->n_bins > 0 ? e->n_bins : 1), std::min(PIPE_MAX_SPLIT, n_tiles / 16));
+    p.ksplit = std::max(ks, 1);
+    p.ws_sum = e->split_sum_dev; p.ws_cnt = e->split_cnt_dev;
+  }
   for (int m = 0; m < PIPE_MAX_K; ++m) { p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m]; p.member_of[m] = 0; }
   for (int m = 0; m < a.M; ++m)
     for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_of[k] = m;
-  const bool shared_x = a.qx_mstride == 0;
+  // distinct activation tensors: one, or one per member
+  const int xm = (a.qx_mstride == 0 || a.M <= 1) ? 1 : (a.M <= 2 ? 2 : 4);
   const bool acc_out = a.acc_out != nullptr;
   switch (e->bits) {
-    case 8: return launch_nw<8, 8>(p, e->n_bins, shared_x, acc_out, a, st);
-    case 4: return launch_nw<4, 8>(p, e->n_bins, shared_x, acc_out, a, st);
-    default: return launch_nw<2, 8>(p, e->n_bins, shared_x, acc_out, a, st);
+    case 8: return launch_nw<8, 8>(p, e->n_bins, xm, acc_out, a, st);
+    case 4: return launch_nw<4, 8>(p, e->n_bins, xm, acc_out, a, st);
+    default: return launch_nw<2, 8>(p, e->n_bins, xm, acc_out, a, st);
   }
 }

@@ -42,6 +42,7 @@ static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b 
 // hold every order of n_out output row blocks (items of one output row block are adjacent and
 // in ascending order k).
 constexpr int STREAM_BIN_CAP = 16;
+constexpr int PIPE_MAX_SPLIT = 8;   // workgroups per bin of the weight-streaming kernel, at most
 struct StreamBin {
   int32_t n_items, n_out;
   int32_t k[STREAM_BIN_CAP];       // 0-based order of the item
@@ -84,6 +85,9 @@ struct pipe_expansion {
   float* scales_all_dev = nullptr;    // [n_bins*bin_cap][16]
   int n_bins = 0, bin_cap = 0;
   StreamBin* bins_dev = nullptr;
+  // split bins of the weight-streaming kernel: partial tiles, and arrival counters (zero between launches)
+  int32_t* split_sum_dev = nullptr;   // [n_bins][PIPE_MAX_SPLIT][bin_cap][256]
+  uint32_t* split_cnt_dev = nullptr;  // [n_bins]
   int64_t stream_bytes = 0;  // packed codes + scales + indices
 };
 
@@ -178,3 +182,4 @@ struct GemmArgs {
   } while (0)
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
+extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic

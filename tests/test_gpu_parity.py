@@ -166,6 +166,35 @@ def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
         g.free()
 
 
+@pytest.mark.parametrize("split_k", [2, 3, 5])
+def test_streaming_kernel_split_bins_match_oracle(pipe, split_k):
+    """Bins split over several workgroups along in_features: integer partial sums meet in the
+    expansion's workspace; results equal the unsplit kernel bit for bit and the workspace is left
+    clean (a second call gives the same answer)."""
+    O, I, T = 320, 2304, 11
+    W, x = _w(510, O, I), _x(511, T, I)
+    b = np.random.default_rng(512).standard_normal(O).astype(f32)
+    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16)]:
+        spec = wl.LayerSpec(O, I, bits, K, gamma, group)
+        ora = oracle_expand(W, spec)
+        ref = po.forward(ora, x, bias=b)
+        g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+        pipe.pipe_set_kernel(2)
+        try:
+            y0 = pipe.pipe_forward(g, dev(x), bias=dev(b)).cpu().numpy()
+            pipe.pipe_set_stream_split(split_k)
+            acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+            y1 = pipe.pipe_forward(g, dev(x), bias=dev(b)).cpu().numpy()
+            y2 = pipe.pipe_forward(g, dev(x), bias=dev(b)).cpu().numpy()
+        finally:
+            pipe.pipe_set_stream_split(0)
+            pipe.pipe_set_kernel(0)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert np.array_equal(y0, y1) and np.array_equal(y1, y2)
+        assert_close_fp32(y1, ref["y"])
+        g.free()
+
+
 @pytest.mark.parametrize("tokens", [150, 9])
 @pytest.mark.parametrize("kind", ["gelu", "gated"])
 def test_mlp_parity(pipe, kind, tokens):
