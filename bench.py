@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 tiled MFMA, 2 weight streaming")
+    ap.add_argument("--token-tile", type=int, default=0,
+                    help="token-tile height of the tiled kernel: 16, 32, 64 (0 = automatic)")
     ap.add_argument("--stream-split", type=int, default=0,
                     help="workgroups per bin of the weight-streaming kernel (0 = automatic)")
     ap.add_argument("--no-graph", action="store_true", help="time decode steps eagerly instead of as one HIP graph")
@@ -74,6 +76,7 @@ def main():
     torch.cuda.set_device(dev)
     pipe.pipe_set_kernel(args.kernel)
     pipe.pipe_set_stream_split(args.stream_split)
+    pipe.pipe_set_token_tile(args.token_tile)
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
         b = torch.empty_like(a)

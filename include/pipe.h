@@ -133,6 +133,12 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
  * small-batch kernel.  Returns PIPE_EINVAL for other values.                    */
 int pipe_set_kernel(int which);
 
+/* Token-tile height of the tiled MFMA kernel (tuning and tests): 0 = automatic
+ * (64 tokens per workgroup when that still gives every CU several tiles, else 32
+ * or 16), or 16, 32, 64.  Results do not depend on the setting.  Returns
+ * PIPE_EINVAL for other values.                                                   */
+int pipe_set_token_tile(int tokens);
+
 /* Split of the weight-streaming kernel's bins along in_features (tuning and tests).
  * A bin (up to 4 stored row blocks holding every order of a few output row blocks)
  * is normally streamed by one workgroup; layers with few output channels and a long

@@ -47,6 +47,7 @@ def _load():
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
+    lib.pipe_set_token_tile.argtypes = [ci]
     lib.pipe_mfma_probe.argtypes = [ci, C.POINTER(C.c_double), vp]
     lib.pipe_timing_enable.argtypes = [ci]
     lib.pipe_timing_read.argtypes = [C.POINTER(C.c_double), pi]
@@ -55,7 +56,7 @@ def _load():
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
-              "pipe_set_kernel", "pipe_set_stream_split", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe"):
+              "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe"):
         getattr(lib, f).restype = ci
     return lib
 
@@ -217,6 +218,10 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
 
 def pipe_set_kernel(which: int) -> None:
     _check(_lib.pipe_set_kernel(int(which)), "pipe_set_kernel")
+
+
+def pipe_set_token_tile(tokens: int) -> None:
+    _check(_lib.pipe_set_token_tile(int(tokens)), "pipe_set_token_tile")
 
 
 def pipe_set_stream_split(workgroups_per_bin: int) -> None:

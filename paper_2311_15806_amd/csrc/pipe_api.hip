@@ -62,6 +62,12 @@ extern "C" int pipe_set_kernel(int which) {
   return PIPE_OK;
 }
 
+extern "C" int pipe_set_token_tile(int tokens) {
+  if (tokens != 0 && tokens != 16 && tokens != 32 && tokens != 64) return PIPE_EINVAL;
+  g_tiled_mtb = tokens / 16;
+  return PIPE_OK;
+}
+
 extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
   if (workgroups_per_bin < 0 || workgroups_per_bin > PIPE_MAX_SPLIT) return PIPE_EINVAL;
   g_stream_ksplit = workgroups_per_bin;

@@ -76,11 +76,23 @@ __device__ __forceinline__ void lds_read_frags(unsigned addr, v4i (&x)[N]) {
 // until the N fragments of x, issued before them, have arrived.
 template <int N, int PENDING>
 __device__ __forceinline__ void lds_wait(v4i (&x)[N]) {
-  static_assert(N == 4 && (PENDING == 0 || PENDING == 4), "token blocks per tile");
-  if constexpr (PENDING == 0)
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
-  else
-    asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
+  static_assert((N == 1 || N == 2 || N == 4) && (PENDING == 0 || PENDING == N), "token blocks per tile");
+  if constexpr (N == 4) {
+    if constexpr (PENDING == 0)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
+    else
+      asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])::"memory");
+  } else if constexpr (N == 2) {
+    if constexpr (PENDING == 0)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0]), "+v"(x[1])::"memory");
+    else
+      asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(x[0]), "+v"(x[1])::"memory");
+  } else {
+    if constexpr (PENDING == 0)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x[0])::"memory");
+    else
+      asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(x[0])::"memory");
+  }
 }
 
 template <int BITS>
@@ -122,6 +134,12 @@ __device__ __forceinline__ T cload(const T* base, size_t idx) {
 
 enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2 };
 
+}  // namespace
+
+int g_tiled_mtb = 0;   // 16-token blocks per tile of the tiled kernel: 0 = automatic, else 1, 2 or 4
+
+namespace {
+
 template <int BITS, int MTB, int NRW, int MINW, int MODE>
 __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams p) {
   constexpr bool ACC_OUT = MODE == MODE_ACC_OUT;
@@ -132,6 +150,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   constexpr int XCOPY = MTB * S / 4;              // activation fragments per wave per stage
   static_assert(TOK_TILE % (16 * MTB) == 0 || (16 * MTB) % TOK_TILE == 0, "token tile");
   __shared__ uint4 Xs[2][MTB * S * FRAG];
+  __shared__ uint4 Stg[MTB == 4 ? 1 : 4 * 256];   // output staging of narrow token tiles (wide ones reuse Xs[1])
   __shared__ float Scl[4][16 * NRW];   // per wave: row scales of the current order
 
   const int lane = threadIdx.x & 63;
@@ -248,10 +267,12 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
           for (int g = 0; g < (16 * NRW + 63) / 64; ++g) {
             const int e = g * 64 + lane, r = e >> 4;
-            int sr = src[0];
+            // src[r] for a lane-dependent r, written so that it stays a handful of selects on
+            // scalar registers (an indexed array would be placed in scratch memory)
+            int sr = 0;
 #pragma unroll
-            for (int q = 1; q < NRW; ++q) sr = (r == q) ? src[q] : sr;
-            const float* gp = sck + (size_t)(sr < 0 ? 0 : sr) * 16 + (e & 15);
+            for (int q = 0; q < NRW; ++q) sr |= (r == q) ? (src[q] < 0 ? 0 : src[q]) : 0;
+            const float* gp = sck + (size_t)sr * 16 + (e & 15);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
                                              (__attribute__((address_space(3))) void*)&Scl[wave][g * 64], 4, 0, 0);
           }
@@ -261,7 +282,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           // not an MFMA has to sit in the shadow of one: the fragments of step j+1 are requested
           // before step j's MFMAs start (two register sets), and the codes of row block r+1 are
           // widened between the MFMAs of row block r (two register sets).
-          constexpr int XB = BITS == 4 ? 1 : 2;   // the 4-bit variant has no registers for a second set
+          constexpr int XB = (BITS == 4 && MTB == 4) ? 1 : 2;   // the widest 4-bit variant has no registers for a second set
           v4i xf[XB][MTB];
           v4i wf[2];
           lds_read_frags<MTB, (buf * MTB * S) * 1024, S * 1024>(xs_lane, xf[0]);
@@ -286,7 +307,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
                 for (int b = 0; b < MTB; ++b) {
                   __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                  __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                  __builtin_amdgcn_sched_group_barrier(0x002, 8 / MTB, 0);
                 }
               }
               __builtin_amdgcn_sched_barrier(0);   // keep the row blocks apart: bounds live registers
@@ -350,7 +371,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));   // keeps the epilogue's address arithmetic out of the main loop's live range
       const int tl = lane_e & 15, g = lane_e >> 4;
-      const unsigned stg = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)&Xs[1][wave * 256];
+      const unsigned stg = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)(MTB == 4 ? &Xs[1][wave * 256] : &Stg[(MTB == 4 ? 0 : wave) * 256]);
       const unsigned wr_row = stg + tl * 256;                    // this lane's token row when writing
       int rb_l = rb_out[0];                                      // row block of the channels this lane stores
 #pragma unroll
@@ -441,10 +462,25 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   for (int m = 0; m < a.M; ++m)
     for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_nib |= (unsigned long long)m << (4 * k);
   const bool acc_out = a.acc_out != nullptr;
-  switch (e->bits) {
-    case 8: return launch_cfg<8, 4, 4, 1>(p, acc_out, a.ev_start, a.ev_stop, st);
-    case 4: return launch_cfg<4, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
-    case 2: return launch_cfg<2, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+  // Token-tile height: 64 tokens per workgroup when that still gives every CU several tiles,
+  // else 32 or 16 (more, smaller tiles; the packed codes are then re-read from L2 more often).
+  const int n_ct = ceil_div(e->n_ct * NRB_TILE, 16);
+  int mtb = g_tiled_mtb;
+  if (mtb != 1 && mtb != 2 && mtb != 4) {
+    mtb = 4;
+    if ((int64_t)n_ct * ceil_div(a.T, 64) < 1024) mtb = 2;
+    if ((int64_t)n_ct * ceil_div(a.T, 32) < 1024) mtb = 1;
+  }
+  switch (e->bits * 8 + mtb) {
+    case 8 * 8 + 4: return launch_cfg<8, 4, 4, 1>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 8 * 8 + 2: return launch_cfg<8, 2, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 8 * 8 + 1: return launch_cfg<8, 1, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 4 * 8 + 4: return launch_cfg<4, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 4 * 8 + 2: return launch_cfg<4, 2, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 4 * 8 + 1: return launch_cfg<4, 1, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 2 * 8 + 4: return launch_cfg<2, 4, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 2 * 8 + 2: return launch_cfg<2, 2, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
+    case 2 * 8 + 1: return launch_cfg<2, 1, 4, 2>(p, acc_out, a.ev_start, a.ev_stop, st);
     default: return PIPE_EINVAL;
   }
 }

@@ -182,4 +182,5 @@ struct GemmArgs {
   } while (0)
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
+extern int g_tiled_mtb;       // token blocks per tile of the tiled kernel; 0 = automatic
 extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic

@@ -52,6 +52,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_expansion_free(None) == 0
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0
+    assert lib.pipe_set_token_tile(48) == EINVAL and lib.pipe_set_token_tile(0) == 0
     for code in (0, -1, -2, -3, -4, -5):
         assert len(lib.pipe_strerror(code)) > 0
 

@@ -166,6 +166,37 @@ def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
         g.free()
 
 
+@pytest.mark.parametrize("tile", [16, 32, 64])
+def test_tiled_kernel_token_tiles_match_oracle(pipe, tile):
+    """Every token-tile height of the tiled kernel: integer accumulators bit-exact, fp32 output
+    bit-identical across heights (same fold order), members kept apart or summed."""
+    O, I, T = 448, 1300, 150
+    W, x = _w(520, O, I), _x(521, T, I)
+    b = np.random.default_rng(522).standard_normal(O).astype(f32)
+    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16)]:
+        spec = LayerSpec(O, I, bits, K, gamma, group)
+        ora = oracle_expand(W, spec)
+        split = [1] * K
+        ref = po.forward(ora, x, bias=b, split=split)
+        refm = po.forward(ora, x, bias=b, split=split, reduce_members=False)
+        g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+        pipe.pipe_set_kernel(1)
+        try:
+            y64 = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b)).cpu().numpy()
+            pipe.pipe_set_token_tile(tile)
+            acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+            y = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b)).cpu().numpy()
+            ym = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b), reduce_members=False).cpu().numpy()
+        finally:
+            pipe.pipe_set_token_tile(0)
+            pipe.pipe_set_kernel(0)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert np.array_equal(y, y64)
+        assert_close_fp32(y, ref["y"])
+        assert_close_fp32(ym, refm["y"])
+        g.free()
+
+
 @pytest.mark.parametrize("split_k", [2, 3, 5])
 def test_streaming_kernel_split_bins_match_oracle(pipe, split_k):
     """Bins split over several workgroups along in_features: integer partial sums meet in the
