@@ -525,8 +525,10 @@ extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, 
     rc = launch_absmax(x_dev, (int64_t)N * C * H * W, b.amax, nullptr, 0, st);
     if (rc) return rc;
   }
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)N * C * H * W);   // the input's codes, in its own layout
+  if (!q8) return PIPE_ENOMEM;
   rc = launch_quantize_im2col(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, s_x,
-                              b.amax, b.qx, b.rowsum, b.scale, st);
+                              b.amax, q8, b.qx, b.rowsum, b.scale, st);
   if (rc) return rc;
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;

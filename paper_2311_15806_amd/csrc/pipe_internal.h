@@ -110,7 +110,7 @@ struct PipeWorkspace {
 // Returns a device buffer of at least `bytes` from slot `slot` (grow-only; growing
 // synchronizes the device first).  nullptr on failure.
 void* pipe_ws_get(int slot, size_t bytes);
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
@@ -143,7 +143,7 @@ int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int i
 // Same for the virtual im2col matrix of a convolution.
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
-                           float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
+                           float s_static, const uint32_t* amax_bits, int8_t* q8_scratch, uint8_t* qx_frag,
                            int32_t* rowsum, float* scale_out, hipStream_t st);
 // Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h|.
 int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,

@@ -249,25 +249,60 @@ struct ConvGeom {
   int N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo;
 };
 
-__global__ __launch_bounds__(BLK) void quantize_im2col_kernel(const float* __restrict__ x, ConvGeom g, int T,
-                                                              int in, int in_pad, float s_static,
-                                                              const uint32_t* __restrict__ amax_bits,
-                                                              uint8_t* __restrict__ qx_frag,
-                                                              int32_t* __restrict__ rowsum,
-                                                              float* __restrict__ scale_out) {
+// Convolution input, step 1: every input element is quantized once, in the input's own layout
+// (an element appears in up to kh*kw patches; the IEEE division is paid once, not per patch).
+__global__ __launch_bounds__(BLK) void quantize_elem_kernel(const float* __restrict__ x, int64_t n, float s_static,
+                                                            const uint32_t* __restrict__ amax_bits,
+                                                            int8_t* __restrict__ q8, float* __restrict__ scale_out) {
   const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
-  // token t = (n, ho, wo); column k = (c, r, q) as in a weight row flattened [C, kh, kw]
-  auto fetch = [=](int t, int k) {
-    const int wo = t % g.Wo, ho = (t / g.Wo) % g.Ho, n = t / (g.Wo * g.Ho);
-    const int q = k % g.kw, r = (k / g.kw) % g.kh, c = k / (g.kw * g.kh);
-    const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + q;
-    if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) return 0.f;
-    const size_t off = g.nhwc ? (((size_t)n * g.H + hi) * g.W + wi) * g.C + c
-                              : (((size_t)n * g.C + c) * g.H + hi) * g.W + wi;
-    return x[off];
-  };
-  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, nullptr);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  const bool live = s > 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x; i < n; i += (int64_t)gridDim.x * BLK)
+    q8[i] = live ? (int8_t)quant1(x[i], s) : (int8_t)0;
+}
+
+// Step 2: patches of codes -> fragment layout and token code sums.  Token t = (n, ho, wo); column
+// k = (c, r, q) as in a weight row flattened [C, kh, kw].  A thread owns 16 consecutive k of one
+// token; (c, r, q) is split once per chunk and then stepped, not divided, element by element.
+__global__ __launch_bounds__(BLK) void im2col_codes_kernel(const int8_t* __restrict__ q8, ConvGeom g, int T, int in,
+                                                           int in_pad, uint8_t* __restrict__ qx_frag,
+                                                           int32_t* __restrict__ rowsum) {
+  const int tb = blockIdx.x;
+  const int n16 = threadIdx.x & 15;
+  const int t = tb * 16 + n16;
+  const int nks = in_pad >> 6;
+  const int nchunk = in_pad >> 4;
+  const int per = (nchunk + gridDim.y - 1) / gridDim.y;
+  const int c_lo = blockIdx.y * per;
+  const int c_hi = min(nchunk, c_lo + per);
+  const bool tok = t < T;
+  const int wo = tok ? t % g.Wo : 0, ho = tok ? (t / g.Wo) % g.Ho : 0, nimg = tok ? t / (g.Wo * g.Ho) : 0;
+  const int hi0 = ho * g.stride - g.pad, wi0 = wo * g.stride - g.pad;
+  int sum = 0;
+  for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
+    int k = c * 16;
+    int qq = k % g.kw, rr = (k / g.kw) % g.kh, cc = k / (g.kw * g.kh);
+    int q[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int v = 0;
+      const int hi = hi0 + rr, wi = wi0 + qq;
+      if (tok && k < in && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W) {
+        const size_t off = g.nhwc ? (((size_t)nimg * g.H + hi) * g.W + wi) * g.C + cc
+                                  : (((size_t)nimg * g.C + cc) * g.H + hi) * g.W + wi;
+        v = q8[off];
+      }
+      q[e] = v;
+      sum += v;
+      ++k;
+      if (++qq == g.kw) { qq = 0; if (++rr == g.kh) { rr = 0; ++cc; } }
+    }
+    const int ks = c >> 2, kc = c & 3;
+    const uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
+                               pack4(q[8], q[9], q[10], q[11]), pack4(q[12], q[13], q[14], q[15]));
+    *reinterpret_cast<uint4*>(qx_frag + (((size_t)tb * nks + ks) * 64 + kc * 16 + n16) * 16) = w;
+  }
+  if (tok && sum != 0) atomicAdd(&rowsum[t], sum);
 }
 
 // h = act(y1) for every member, and max|h| per member.
@@ -350,15 +385,19 @@ int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int i
 
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
-                           float s_static, const uint32_t* amax_bits, uint8_t* qx_frag,
+                           float s_static, const uint32_t* amax_bits, int8_t* q8_scratch, uint8_t* qx_frag,
                            int32_t* rowsum, float* scale_out, hipStream_t st) {
   int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
   if (rc) return rc;
+  const int64_t n = (int64_t)N * C * H * W;
+  int64_t blocks = (n + BLK - 1) / BLK;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits,
+                     q8_scratch, scale_out);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(quantize_im2col_kernel, grid, dim3(BLK), 0, st, x, g, T, in, in_pad, s_static,
-                     amax_bits, qx_frag, rowsum, scale_out);
+  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
