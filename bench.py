@@ -156,7 +156,7 @@ def main():
         step_ms = (t_b - t_a) * 1e3 / steps
         mode = "eager"
         # ---- decode-sized steps are launch bound: the same K steps as ONE HIP graph ----------
-        if T <= 16 and not args.no_graph and cfg.kind != "conv2d":
+        if T <= 64 and not args.no_graph and cfg.kind != "conv2d":
             try:
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
@@ -191,7 +191,7 @@ def main():
                     alg_bytes=alg_bytes, expansion_copies=copies)
 
     T0 = cfg.tokens if cfg.kind == "conv2d" else T_head
-    head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 16))
+    head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 64))
 
     mfma_bound = T0 > 64
     if mfma_bound:
@@ -208,11 +208,11 @@ def main():
 
     sweep = []
     if not args.no_sweep and cfg.kind != "conv2d":
-        for T in (1, 16, 256, 2048, 4096):
+        for T in (1, 16, 64, 256, 2048, 4096):
             if T == T0:
                 r = dict(head)
             else:
-                r = measure(T, max(10, args.steps // 2), 3, rotate=(T <= 16))
+                r = measure(T, max(10, args.steps // 2), 3, rotate=(T <= 64))
             r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
             r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
             sweep.append({k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()})

@@ -362,7 +362,7 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
 // ------------------------------------------------------------------ forward
 static bool use_stream_kernel(const pipe_expansion* e, int T) {
   if (g_kernel_choice == 1 || e->K > 4) return false;   // the streaming kernel holds at most 4 orders per bin
-  return T <= 16;
+  return T <= PIPE_STREAM_MAX_T;
 }
 
 struct ActBuffers {
@@ -598,12 +598,13 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     if (rc) return rc;
   }
   // each member quantizes its own hidden activation with its own scale
-  if (small) {
+  const bool one_launch = small;
+  if (one_launch) {
     rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, amax_h, qh, (int64_t)T_pad * l2->in_pad,
                                rowsum_h, nullptr, scale_h, st);
     if (rc) return rc;
   }
-  for (int m = 0; m < Mm && !small; ++m) {
+  for (int m = 0; m < Mm && !one_launch; ++m) {
     rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, 0.f, amax_h + m,
                              qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
                              scale_h + m, st);

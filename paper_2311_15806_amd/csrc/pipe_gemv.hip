@@ -1,4 +1,4 @@
-// Weight-streaming kernel of the expanded layer for decode-sized batches (T <= 16), where the
+// Weight-streaming kernel of the expanded layer for decode-sized batches (T <= 64), where the
 // path is bound by reading the packed codes from HBM once (App. B, Eq. (define_dre), same
 // arithmetic as the tiled kernel).
 //
@@ -10,7 +10,9 @@
 // activation fragments (also read straight from L2: waves use disjoint k, nothing is shared,
 // so the k loop has no LDS traffic and no barrier).  The waves' partial int32 tiles meet in
 // LDS and are summed exactly; the epilogue then applies offsets, row scales, activation scale,
-// bias and the member sum in a fixed order, so results are bit-reproducible.  Expansions with
+// bias and the member sum in a fixed order, so results are bit-reproducible.  A workgroup
+// handles one 16-token block; larger batches (up to 64 tokens) run one workgroup per bin and
+// token block, on the same XCD, so that the bin still comes from HBM once.  Expansions with
 // more than 4 orders take the tiled kernel at every batch size.
 #include "pipe_internal.h"
 
@@ -42,6 +44,8 @@ struct StreamParams {
   int zero_n;
   int T, out, K, nks, M, reduce, act;
   int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
+  int n_tb;                // 16-token blocks: one workgroup per (bin, k share, token block)
+  int n_bins;
   int32_t* ws_sum;         // [n_bins][ksplit][R][256] partial tiles of split bins
   uint32_t* ws_cnt;        // [n_bins] arrival counters, zero between launches
   int member_lo[PIPE_MAX_K];
@@ -93,9 +97,19 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   const int n_tiles = (p.nks * 64) / KSUP;
   if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
 
+  // Block index -> (bin, k share, token block).  Blocks are handed to the XCDs round robin, so the
+  // workgroups that stream the same bin (for different token blocks or k shares) get indices that
+  // are equal modulo 8: they run on one XCD and the bin comes from HBM once, then from that L2.
+  const int subs = p.ksplit * p.n_tb;
+  const int grp = (int)blockIdx.x / (8 * subs), within = (int)blockIdx.x - grp * (8 * subs);
+  const int bin = grp * 8 + (within & 7), sub = within >> 3;
+  const int ksp = sub % p.ksplit, tb = sub / p.ksplit;
+  if (bin >= p.n_bins) return;   // padding of the last group of eight bins
+
   // epilogue role of this thread: 256 threads per output row block, thread = (token t, channel ch)
   const int e = threadIdx.x & 255;
-  const int t = e >> 4, ch = e & 15;
+  const int t = e >> 4, ch = e & 15;   // token inside this workgroup's 16-token block
+  const int tg = tb * 16 + t;          // token of the call
   const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);   // lane*4 + i of the MFMA result layout
   const int o_first = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
   constexpr int O_STEP = (NW * 64) / 256;
@@ -105,8 +119,6 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   // stored row blocks sit at positions blockIdx.x * R + r of the schedule-ordered buffers, so
   // the code stream (the HBM traffic that bounds this kernel) starts at once.  Wave w streams
   // tiles w, w+NW, ...; two tiles per item are in flight.
-  const int bin = p.ksplit > 1 ? (int)blockIdx.x / p.ksplit : (int)blockIdx.x;
-  const int ksp = p.ksplit > 1 ? (int)blockIdx.x - bin * p.ksplit : 0;
   // this workgroup's share of the k tiles
   const int tile_lo = (int)((long long)n_tiles * ksp / p.ksplit), tile_hi = (int)((long long)n_tiles * (ksp + 1) / p.ksplit);
   const size_t pos0 = (size_t)bin * R;
@@ -122,7 +134,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   // member m's activations (members beyond M repeat the last one; never used)
   const uint8_t* xb[XM];
 #pragma unroll
-  for (int m = 0; m < XM; ++m) xb[m] = p.qx + (size_t)(m < p.M ? m : p.M - 1) * p.qx_mstride;
+  for (int m = 0; m < XM; ++m) xb[m] = p.qx + (size_t)(m < p.M ? m : p.M - 1) * p.qx_mstride + (size_t)tb * p.nks * 1024;
   auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
 #pragma unroll
     for (int m = 0; m < XM; ++m)
@@ -145,7 +157,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   for (int m = 0; m < R; ++m) {       // at most R members (K <= R)
     const int mm = m < p.M ? m : p.M - 1;
     sxm[m] = p.s_x[mm * p.sx_mstride];
-    rsm[m] = OFF ? p.rowsum[(size_t)mm * p.rowsum_mstride + t] : 0;
+    rsm[m] = OFF ? p.rowsum[(size_t)mm * p.rowsum_mstride + tg] : 0;
   }
 
   // ---- the descriptor: scalar reads out of one vector register
@@ -253,7 +265,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
         const float sc = fold_sx ? scv[r] * sx : scv[r];
         yacc = fmaf(sc, (float)a, yacc);
         if (ACC_OUT) {
-          if (t < p.T) p.acc_out[((size_t)itk[r] * p.T + t) * p.out + col] = a;
+          if (tg < p.T) p.acc_out[((size_t)itk[r] * p.T + tg) * p.out + col] = a;
         }
       }
       if (ACC_OUT) continue;
@@ -263,19 +275,19 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
       yacc = 0.f;
       if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
       if (p.amax_out != nullptr) {
-        float mx = t < p.T ? fabsf(v) : 0.f;
+        float mx = tg < p.T ? fabsf(v) : 0.f;
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
         if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
       }
-      if (t < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + t) * p.out + col] = v;
+      if (tg < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + tg) * p.out + col] = v;
     }
   }
 }
 
 template <int BITS, int NW>
 int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const GemmArgs& a, hipStream_t st) {
-  const dim3 grid((unsigned)(n_bins * p.ksplit)), blk(NW * 64);
+  const dim3 grid((unsigned)((n_bins + 7) / 8 * 8 * p.ksplit * p.n_tb)), blk(NW * 64);
   if (acc_out) {
     if (xm == 1) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
     else if (xm == 2) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 2, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
@@ -294,7 +306,7 @@ int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const Gem
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   const pipe_expansion* e = a.e;
   if (a.T <= 0) return PIPE_OK;
-  if (a.T > 16 || a.T_pad != 16 || e->K > R || e->bin_cap != R) return PIPE_ESHAPE;
+  if (a.T > PIPE_STREAM_MAX_T || a.T_pad != (int)round_up64(a.T, 16) || e->K > R || e->bin_cap != R) return PIPE_ESHAPE;
   StreamParams p;
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
@@ -312,6 +324,9 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
     int ks;
     if (g_stream_ksplit > 0) ks = std::min(std::min(g_stream_ksplit, PIPE_MAX_SPLIT), n_tiles);   // forced (tests, tuning)
     else ks = std::min(256 / (e->n_bins > 0 ? e->n_bins : 1), std::min(PIPE_MAX_SPLIT, n_tiles / 16));
+    p.n_tb = a.T_pad / 16;
+    p.n_bins = e->n_bins;
+    if (p.n_tb > 1) ks = 1;   // several token blocks already multiply the workgroups
     p.ksplit = std::max(ks, 1);
     p.ws_sum = e->split_sum_dev; p.ws_cnt = e->split_cnt_dev;
   }

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restri
   quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor, vec ? x : nullptr);
 }
 
-// Decode-sized batches (T <= 16): ONE launch does max|x|, scale, codes and code sums, so the
+// Decode-sized batches (up to 64 tokens): ONE launch does max|x|, scale, codes and code sums, so the
 // forward path is two launches (this one and the contraction).  Workgroup (n, m) owns token n
 // of member m: it first reduces max|x| over the member's whole input (every workgroup does,
 // redundantly -- the input is a few hundred KiB and L2 resident, and it spares a grid-wide
@@ -161,7 +161,8 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
                                                               int32_t* __restrict__ rowsum_all,
                                                               int8_t* __restrict__ qx_rowmajor,
                                                               float* __restrict__ scale_out) {
-  const int n = blockIdx.x;      // token 0..15
+  const int n = blockIdx.x;      // token 0..T_pad-1 (T_pad = gridDim.x, a multiple of 16)
+  const int nks = in_pad >> 6;
   const int m = blockIdx.y;
   const float* x = x_all + (size_t)m * x_mstride;
   uint8_t* qx_frag = qx_all + (size_t)m * qx_mstride;
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
     const int ks = c >> 2, kc = c & 3;
     const uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
                                pack4(q[8], q[9], q[10], q[11]), pack4(q[12], q[13], q[14], q[15]));
-    *reinterpret_cast<uint4*>(qx_frag + (((size_t)ks) * 64 + kc * 16 + n) * 16) = w;
+    *reinterpret_cast<uint4*>(qx_frag + (((size_t)(n >> 4) * nks + ks) * 64 + kc * 16 + (n & 15)) * 16) = w;
     if (qx_rowmajor != nullptr && n < T) {
 #pragma unroll
       for (int e = 0; e < 16; ++e)
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
     int tot = 0;
 #pragma unroll
     for (int i = 0; i < SBLK / 64; ++i) tot += ssum[i];
-    rowsum_all[(size_t)m * 16 + n] = tot;
+    rowsum_all[(size_t)m * gridDim.x + n] = tot;
   }
 }
 
@@ -377,7 +378,7 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
                           const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
-  hipLaunchKernelGGL(quantize_small_kernel, dim3(16, M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
+  hipLaunchKernelGGL(quantize_small_kernel, dim3((unsigned)round_up64(T, 16), M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
                      amax_bits, qx_frag, qx_mstride, rowsum, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;

@@ -143,12 +143,13 @@ def test_conv2d_parity(pipe):
 
 
 def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
-    """Both kernels fold the orders in the same fixed order, so on a decode-sized batch their
-    fp32 outputs are bit-identical."""
-    O, I, T = 384, 1024, 13
-    W, x = _w(500, O, I), _x(501, T, I)
+    """Both kernels fold the orders in the same fixed order, so on a decode-sized batch (one to
+    four 16-token blocks for the streaming kernel) their fp32 outputs are bit-identical."""
+    O, I = 384, 1024
     b = np.random.default_rng(502).standard_normal(O).astype(f32)
-    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16)]:
+    for T, bits, K, gamma, group in [(13, 2, 4, 0.25, 64), (13, 4, 3, 0.5, 32), (13, 8, 2, 1.0, 16),
+                                     (50, 2, 4, 0.25, 64), (64, 4, 3, 0.5, 32), (33, 8, 2, 1.0, 16)]:
+        W, x = _w(500, O, I), _x(501 + T, T, I)
         g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
         outs = []
         for which in (1, 2):
