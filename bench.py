@@ -156,7 +156,7 @@ def main():
         step_ms = (t_b - t_a) * 1e3 / steps
         mode = "eager"
         # ---- decode-sized steps are launch bound: the same K steps as ONE HIP graph ----------
-        if T <= 64 and not args.no_graph and cfg.kind != "conv2d":
+        if T <= 128 and not args.no_graph and cfg.kind != "conv2d":
             try:
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
@@ -191,9 +191,9 @@ def main():
                     alg_bytes=alg_bytes, expansion_copies=copies)
 
     T0 = cfg.tokens if cfg.kind == "conv2d" else T_head
-    head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 64))
+    head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 128))
 
-    mfma_bound = T0 > 64
+    mfma_bound = T0 > 128
     if mfma_bound:
         roofline = dict(bound="mfma", achieved=head["kernel_eff_tops"], peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
                         frac=(head["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS, traffic=None,
@@ -212,7 +212,7 @@ def main():
             if T == T0:
                 r = dict(head)
             else:
-                r = measure(T, max(10, args.steps // 2), 3, rotate=(T <= 64))
+                r = measure(T, max(10, args.steps // 2), 3, rotate=(T <= 128))
             r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
             r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
             sweep.append({k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()})

@@ -416,7 +416,7 @@ extern "C" int pipe_timing_read(double* total_ms, int* launches) {
 // single-launch path.
 static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s_x, const ActBuffers& b, bool small,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
-  if (small)
+  if (small && T <= PIPE_QUANT1_MAX_T)
     return launch_quantize_small(x_dev, 0, 1, T, in, in_pad, s_x, nullptr, b.qx, 0, b.rowsum, qx_rowmajor, scale_out, st);
   // The reduction slot is zero on entry (workspace allocation, then every contraction kernel
   // clears it again); the reduction kernel also clears the code sums, so a dynamic scale costs
@@ -598,7 +598,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     if (rc) return rc;
   }
   // each member quantizes its own hidden activation with its own scale
-  const bool one_launch = small;
+  const bool one_launch = small && T <= PIPE_QUANT1_MAX_T;
   if (one_launch) {
     rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, amax_h, qh, (int64_t)T_pad * l2->in_pad,
                                rowsum_h, nullptr, scale_h, st);

@@ -1,4 +1,4 @@
-// Weight-streaming kernel of the expanded layer for decode-sized batches (T <= 64), where the
+// Weight-streaming kernel of the expanded layer for decode-sized batches (T <= 128), where the
 // path is bound by reading the packed codes from HBM once (App. B, Eq. (define_dre), same
 // arithmetic as the tiled kernel).
 //
@@ -11,7 +11,7 @@
 // so the k loop has no LDS traffic and no barrier).  The waves' partial int32 tiles meet in
 // LDS and are summed exactly; the epilogue then applies offsets, row scales, activation scale,
 // bias and the member sum in a fixed order, so results are bit-reproducible.  A workgroup
-// handles one 16-token block; larger batches (up to 64 tokens) run one workgroup per bin and
+// handles one 16-token block; larger batches (up to 128 tokens) run one workgroup per bin and
 // token block, on the same XCD, so that the bin still comes from HBM once.  Expansions with
 // more than 4 orders take the tiled kernel at every batch size.
 #include "pipe_internal.h"

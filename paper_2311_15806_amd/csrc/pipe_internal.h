@@ -42,7 +42,8 @@ static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b 
 // hold every order of n_out output row blocks (items of one output row block are adjacent and
 // in ascending order k).
 constexpr int STREAM_BIN_CAP = 16;
-constexpr int PIPE_STREAM_MAX_T = 64;   // the weight-streaming kernel serves up to this many tokens
+constexpr int PIPE_STREAM_MAX_T = 128;   // the weight-streaming kernel serves up to this many tokens
+constexpr int PIPE_QUANT1_MAX_T = 64;    // the one-launch quantizer (every token's workgroup scans the whole input for the maximum) up to this many
 constexpr int PIPE_MAX_SPLIT = 8;   // workgroups per bin of the weight-streaming kernel, at most
 struct StreamBin {
   int32_t n_items, n_out;
