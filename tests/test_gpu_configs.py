@@ -120,7 +120,7 @@ def test_c4_expand_bit_exact(pipe, c4):
     assert g.macs_per_token() == po.expansion_macs(ora, 1) == 4096 * 19264
 
 
-@pytest.mark.parametrize("T", [1, 16, 256, 2048, 4096])
+@pytest.mark.parametrize("T", [1, 16, 64, 128, 256, 2048, 4096])
 def test_c4_forward(pipe, c4, T):
     w, ora, g = c4
     x = wl.make_input(wl.with_tokens(w, T))
@@ -160,7 +160,7 @@ def test_c5_expand_bit_exact(pipe, c5):
     assert_expansion_equal(g2, o2)
 
 
-@pytest.mark.parametrize("T", [1, 16, 4096])
+@pytest.mark.parametrize("T", [1, 16, 100, 4096])
 def test_c5_gated_mlp(pipe, c5, T):
     w, o1, o2, g1, g2 = c5
     split = list(w.split)

@@ -57,7 +57,7 @@ def test_expand_bit_exact(pipe, bits, K, gamma, group, O, I):
 
 
 @pytest.mark.parametrize("bits,K,gamma,group,O,I", EXPAND_CASES)
-@pytest.mark.parametrize("T", [1, 16, 37, 300])
+@pytest.mark.parametrize("T", [1, 16, 37, 100, 300])
 def test_forward_acc_bit_exact_and_output(pipe, bits, K, gamma, group, O, I, T):
     W = _w(200 + bits + K + O, O, I)
     x = _x(300 + T, T, I)
@@ -227,7 +227,7 @@ def test_streaming_kernel_split_bins_match_oracle(pipe, split_k):
         g.free()
 
 
-@pytest.mark.parametrize("tokens", [150, 9])
+@pytest.mark.parametrize("tokens", [150, 100, 40, 9])
 @pytest.mark.parametrize("kind", ["gelu", "gated"])
 def test_mlp_parity(pipe, kind, tokens):
     base = wl.C3 if kind == "gelu" else wl.C5
