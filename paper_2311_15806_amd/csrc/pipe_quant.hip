@@ -131,7 +131,19 @@ __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int i
         if (c * 16 + e < in) qx_rowmajor[(size_t)t * in + c * 16 + e] = (int8_t)q[e];
     }
   }
-  if (t < T && sum != 0) atomicAdd(&rowsum[t], sum);
+  // one atomic per token and workgroup: threads 16 apart hold the same token (lane bits 4 and 5
+  // inside a wave, then the waves through LDS)
+  sum += __shfl_xor(sum, 16, 64);
+  sum += __shfl_xor(sum, 32, 64);
+  __shared__ int wsum[BLK / 64][16];
+  if ((threadIdx.x & 63) < 16) wsum[threadIdx.x >> 6][threadIdx.x & 15] = sum;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < BLK / 64; ++w) tot += wsum[w][threadIdx.x];
+    if (t < T && tot != 0) atomicAdd(&rowsum[t], tot);
+  }
 }
 
 __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restrict__ x, int T, int in,
@@ -153,7 +165,7 @@ __global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restri
 // of member m: it first reduces max|x| over the member's whole input (every workgroup does,
 // redundantly -- the input is a few hundred KiB and L2 resident, and it spares a grid-wide
 // synchronization), then quantizes its own token and sums its codes without atomics.
-constexpr int SBLK = 256;
+constexpr int SBLK = 1024;   // a large workgroup: the scan for the maximum is the long part
 __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __restrict__ x_all, int64_t x_mstride,
                                                               int T, int in, int in_pad, float s_static,
                                                               const uint32_t* __restrict__ amax_bits,
