@@ -157,11 +157,19 @@ int pipe_set_stream_split(int workgroups_per_bin);
 int pipe_timing_enable(int on);
 int pipe_timing_read(double* total_ms, int* launches);
 
-/* Diagnostic for reports: runs an MFMA-only kernel (back-to-back independent
- * v_mfma_i32_16x16x64_i8 on registers, no memory traffic) for `iters` rounds of 16
- * instructions per wave and writes the int8 rate it sustained, in TOP/s, to
- * *tops_out (HOST).  Synchronizes the stream.                                   */
-int pipe_mfma_probe(int iters, double* tops_out, void* stream);
+/* Diagnostics for reports: reference rates measured on the chip the library runs on.
+ * pipe_mfma_probe runs an MFMA-only kernel (back-to-back independent
+ * v_mfma_i32_16x16x64_i8 on registers, no memory traffic in the loop) for `iters`
+ * rounds of 16 instructions per wave and writes the int8 rate it sustained, in TOP/s,
+ * to *tops_out (HOST).  `operands`: 0 = constant bytes, 1 = ternary offset codes
+ * against random int8 (what a ternary layer feeds the pipe), 2 = random int8 against
+ * random int8; the chip's clock under load depends on it.
+ * pipe_hbm_probe reads `bytes` (>= 1 MiB, rounded down to 128 KiB) of freshly
+ * allocated device memory with the access pattern of the weight-streaming kernel and
+ * writes the bandwidth, in GB/s, to *gbps_out (HOST); it allocates and frees `bytes`.
+ * Both synchronize the stream.                                                     */
+int pipe_mfma_probe(int iters, int operands, double* tops_out, void* stream);
+int pipe_hbm_probe(int64_t bytes, double* gbps_out, void* stream);
 
 const char* pipe_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */

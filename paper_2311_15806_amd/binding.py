@@ -48,7 +48,8 @@ def _load():
     lib.pipe_set_kernel.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
-    lib.pipe_mfma_probe.argtypes = [ci, C.POINTER(C.c_double), vp]
+    lib.pipe_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), vp]
+    lib.pipe_hbm_probe.argtypes = [C.c_int64, C.POINTER(C.c_double), vp]
     lib.pipe_timing_enable.argtypes = [ci]
     lib.pipe_timing_read.argtypes = [C.POINTER(C.c_double), pi]
     lib.pipe_strerror.argtypes = [ci]
@@ -56,7 +57,7 @@ def _load():
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
-              "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe"):
+              "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
         getattr(lib, f).restype = ci
     return lib
 
@@ -239,8 +240,16 @@ def pipe_timing_read():
     return ms.value, n.value
 
 
-def pipe_mfma_probe(iters: int = 20000) -> float:
-    """int8 TOP/s an MFMA-only kernel sustains on this chip (diagnostic for reports)."""
+def pipe_mfma_probe(iters: int = 20000, operands: int = 0) -> float:
+    """int8 TOP/s an MFMA-only kernel sustains on this chip (diagnostic for reports);
+    operands: 0 constant, 1 ternary codes x random int8, 2 random int8 x random int8."""
     t = C.c_double()
-    _check(_lib.pipe_mfma_probe(int(iters), C.byref(t), _stream()), "pipe_mfma_probe")
+    _check(_lib.pipe_mfma_probe(int(iters), int(operands), C.byref(t), _stream()), "pipe_mfma_probe")
+    return t.value
+
+
+def pipe_hbm_probe(nbytes: int = 1 << 31) -> float:
+    """GB/s of a plain streaming read with the weight-streaming kernel's access pattern."""
+    t = C.c_double()
+    _check(_lib.pipe_hbm_probe(int(nbytes), C.byref(t), _stream()), "pipe_hbm_probe")
     return t.value

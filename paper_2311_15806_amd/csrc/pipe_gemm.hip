@@ -484,48 +484,3 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
     default: return PIPE_EINVAL;
   }
 }
-
-// ---------------------------------------------------------------------------------------
-// MFMA-only probe: every wave issues back-to-back independent v_mfma_i32_16x16x64_i8 on
-// registers (no memory traffic).  Gives the int8 rate the chip sustains at its own clocks,
-// to put next to the vendor peak in reports.
-// ---------------------------------------------------------------------------------------
-namespace {
-__global__ __launch_bounds__(256, 2) void mfma_probe_kernel(int iters, int* sink) {
-  v4i a = v4i{(int)threadIdx.x, 1, 2, 3}, b = v4i{3, 2, 1, (int)blockIdx.x};
-  v4i c[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) c[i] = v4i{0, 0, 0, 0};
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) c[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c[i], 0, 0, 0);
-  }
-  int s = 0;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) s += c[i][0] + c[i][1] + c[i][2] + c[i][3];
-  if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never true
-}
-}  // namespace
-
-extern "C" int pipe_mfma_probe(int iters, double* tops_out, void* stream) {
-  if (iters <= 0 || !tops_out) return PIPE_EINVAL;
-  hipStream_t st = (hipStream_t)stream;
-  int* sink = (int*)pipe_ws_get(WS_MISC, 256);
-  if (!sink) return PIPE_ENOMEM;
-  hipEvent_t e0, e1;
-  PIPE_HIP(hipEventCreate(&e0));
-  PIPE_HIP(hipEventCreate(&e1));
-  const int blocks = 256 * 2 * 4;   // 2 workgroups per CU resident, 4 rounds
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, sink);   // warm-up
-  PIPE_HIP(hipEventRecord(e0, st));
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, sink);
-  PIPE_HIP(hipEventRecord(e1, st));
-  PIPE_HIP(hipEventSynchronize(e1));
-  float ms = 0.f;
-  PIPE_HIP(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  const double ops = (double)blocks * 4.0 * iters * 16.0 * (2.0 * 16 * 16 * 64);
-  *tops_out = ops / (ms * 1e-3) / 1e12;
-  return PIPE_OK;
-}
