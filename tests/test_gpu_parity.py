@@ -120,6 +120,56 @@ def test_degenerate_inputs(pipe):
     gz.free()
 
 
+@pytest.mark.parametrize("T", [5, 80, 200])
+def test_sixteen_orders_and_ragged_features(pipe, T):
+    """The largest order count (the streaming kernel holds at most 4 orders per bin, so the tiled
+    kernel serves every batch size) on a layer whose in_features is not a multiple of 4."""
+    O, I, K = 96, 77, 16
+    W, x = _w(530, O, I), _x(531 + T, T, I)
+    spec = LayerSpec(O, I, 4, K, 0.34, 16)
+    ora = oracle_expand(W, spec)
+    split = [5, 4, 4, 3]
+    ref = po.forward(ora, x, split=split)
+    refm = po.forward(ora, x, split=split, reduce_members=False)
+    g = pipe.pipe_expand(dev(W), 4, K, 0.34, 16)
+    assert_expansion_equal(g, ora)
+    acc, qx, _ = pipe.pipe_forward_acc(g, dev(x))
+    assert np.array_equal(qx.cpu().numpy(), ref["Qx"]) and np.array_equal(acc.cpu().numpy(), ref["acc"])
+    assert_close_fp32(pipe.pipe_forward(g, dev(x), split=split).cpu().numpy(), ref["y"])
+    assert_close_fp32(pipe.pipe_forward(g, dev(x), split=split, reduce_members=False).cpu().numpy(), refm["y"])
+    g.free()
+
+
+@pytest.mark.parametrize("T", [3, 70])
+def test_longest_rows_do_not_overflow_the_accumulator(pipe, T):
+    """in_features at the documented limit with every code and every activation at full scale:
+    the int32 accumulator (127 * 127 * 130000 < 2^31) is exact."""
+    O, I = 16, 130000
+    W = np.full((O, I), 0.5, f32)
+    W[::2] *= -1.0
+    x = np.full((T, I), 3.0, f32)
+    x[:, ::3] *= -1.0
+    for bits in (8, 2):
+        ora = po.expand(W, bits, 1, 1.0, 16)
+        ref = po.forward(ora, x)
+        g = pipe.pipe_expand(dev(W), bits, 1, 1.0, 16)
+        assert_expansion_equal(g, ora)
+        acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert_close_fp32(pipe.pipe_forward(g, dev(x)).cpu().numpy(), ref["y"])
+        g.free()
+    # all activations of one sign: the accumulator reaches 127 * q_max * in
+    xp = np.full((2, I), 1.0, f32)
+    Wp = np.full((O, I), 0.25, f32)
+    ora = po.expand(Wp, 8, 1, 1.0, 16)
+    ref = po.forward(ora, xp)
+    assert int(ref["acc"].max()) == 127 * 127 * I
+    g = pipe.pipe_expand(dev(Wp), 8, 1, 1.0, 16)
+    acc, _, _ = pipe.pipe_forward_acc(g, dev(xp))
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    g.free()
+
+
 def test_conv2d_parity(pipe):
     w = wl.scaled(wl.C2, out_div=4, in_div=8, tokens=2 * 196)
     spec, c = w.layers[0], w.conv
