@@ -115,6 +115,9 @@ static void free_expansion(pipe_expansion* e) {
   if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
   if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
   if (e->ct_mask_dev) (void)hipFree(e->ct_mask_dev);
+  if (e->gt_rb_out_dev) (void)hipFree(e->gt_rb_out_dev);
+  if (e->gt_src_dev) (void)hipFree(e->gt_src_dev);
+  if (e->gt_mask_dev) (void)hipFree(e->gt_mask_dev);
   if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->codes_dev) (void)hipFree(e->codes_dev);
   if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
@@ -201,6 +204,55 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
   PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
   PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));
   PIPE_HIP(hipMemcpy(e->ct_src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice));
+
+  // The pair schedule of a gate||up layer (see pipe_internal.h).
+  if (n_rb % 2 == 0) {
+    const int n_pairs = n_rb / 2;
+    struct Pair { uint32_t mg, mu; int pop; int i; };
+    std::vector<Pair> pairs(n_pairs);
+    auto mask_of = [&](int rb) {
+      uint32_t mask = 0;
+      for (int k = 0; k < K; ++k)
+        if (slot_of[k][rb / rbpg] >= 0) mask |= 1u << k;
+      return mask;
+    };
+    for (int i = 0; i < n_pairs; ++i) {
+      const uint32_t mg = mask_of(i), mu = mask_of(i + n_pairs);
+      pairs[i] = Pair{mg, mu, __builtin_popcount(mg) + __builtin_popcount(mu), i};
+    }
+    std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) {
+      if (x.pop != y.pop) return x.pop > y.pop;
+      if (x.mg != y.mg) return x.mg < y.mg;
+      if (x.mu != y.mu) return x.mu < y.mu;
+      return x.i < y.i;
+    });
+    e->n_ct_gated = ceil_div(n_pairs, 8);
+    e->n_sorted_gated = (int)round_up64((int64_t)e->n_ct_gated * 16, 64);
+    std::vector<int32_t> g_out((size_t)e->n_sorted_gated, -1);
+    std::vector<int32_t> g_src((size_t)K * e->n_sorted_gated, -1);
+    std::vector<uint32_t> g_mask((size_t)e->n_ct_gated, 0u);
+    for (int j = 0; j < n_pairs; ++j) {
+      const int t = j / 8, q = j % 8, i = pairs[j].i;
+      const int pos_g = t * 16 + q, pos_u = t * 16 + 8 + q;
+      g_out[pos_g] = i;
+      g_out[pos_u] = i;
+      g_mask[t] |= pairs[j].mg | pairs[j].mu;
+      for (int k = 0; k < K; ++k) {
+        const int rbs[2] = {i, i + n_pairs};
+        const int poss[2] = {pos_g, pos_u};
+        for (int h = 0; h < 2; ++h) {
+          const int g = rbs[h] / rbpg, b = rbs[h] % rbpg;
+          if (slot_of[k][g] >= 0) g_src[(size_t)k * e->n_sorted_gated + poss[h]] = e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b];
+        }
+      }
+    }
+    PIPE_HIP(hipMalloc(&e->gt_rb_out_dev, g_out.size() * 4));
+    PIPE_HIP(hipMalloc(&e->gt_src_dev, g_src.size() * 4));
+    PIPE_HIP(hipMalloc(&e->gt_mask_dev, g_mask.size() * 4));
+    PIPE_HIP(hipMemcpy(e->gt_rb_out_dev, g_out.data(), g_out.size() * 4, hipMemcpyHostToDevice));
+    PIPE_HIP(hipMemcpy(e->gt_src_dev, g_src.data(), g_src.size() * 4, hipMemcpyHostToDevice));
+    PIPE_HIP(hipMemcpy(e->gt_mask_dev, g_mask.data(), g_mask.size() * 4, hipMemcpyHostToDevice));
+  }
 
   // Move the stored row blocks to their positions and drop the per-order buffers.
   const int64_t rb_bytes = (int64_t)(e->in_pad / (512 / e->bits)) * 1024;
@@ -558,11 +610,6 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   if (rc) return rc;
   // hidden buffers
   const int T_pad = b.T_pad;
-  float* y1 = nullptr;
-  if (act == PIPE_ACT_SILU_GATED) {
-    y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
-    if (!y1) return PIPE_ENOMEM;
-  }
   float* h = h_dev ? h_dev : (float*)pipe_ws_get(WS_H, (size_t)Mm * T * H * sizeof(float));
   uint8_t* qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * l2->in_pad);
   int32_t* rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
@@ -590,7 +637,14 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
+  } else if (!small && l1->gt_src_dev != nullptr) {
+    // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly
+    a.act = PIPE_ACT_SILU_GATED; a.y = h; a.amax_out = amax_h;
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
   } else {
+    float* y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
+    if (!y1) return PIPE_ENOMEM;
     a.act = 0; a.y = y1; a.amax_out = nullptr;
     rc = run_gemm(a, small, st);
     if (rc) return rc;

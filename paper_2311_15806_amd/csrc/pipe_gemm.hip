@@ -49,6 +49,7 @@ struct TiledParams {
   uint32_t* zero_after;
   int zero_n;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
+  int hidden;                     // MODE_GATED: H; the layer's rows are gate [0,H) and up [H,2H), y is [M,T,H]
   int n_st_t;                     // super-tiles along tokens
   unsigned long long member_nib;  // member of order k in bits [4k, 4k+4)
 };
@@ -132,7 +133,7 @@ __device__ __forceinline__ T cload(const T* base, size_t idx) {
   return ((cptr)(unsigned long long)base)[idx];
 }
 
-enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2 };
+enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2, MODE_GATED = 3 };
 
 }  // namespace
 
@@ -371,15 +372,25 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));   // keeps the epilogue's address arithmetic out of the main loop's live range
       const int tl = lane_e & 15, g = lane_e >> 4;
-      const unsigned stg = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)(MTB == 4 ? &Xs[1][wave * 256] : &Stg[(MTB == 4 ? 0 : wave) * 256]);
+      auto stg_of = [&](int w) __attribute__((always_inline)) {
+        return (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint4*)(MTB == 4 ? &Xs[1][w * 256] : &Stg[(MTB == 4 ? 0 : w) * 256]);
+      };
+      const unsigned stg = stg_of(wave);
       const unsigned wr_row = stg + tl * 256;                    // this lane's token row when writing
       int rb_l = rb_out[0];                                      // row block of the channels this lane stores
 #pragma unroll
       for (int q = 1; q < NRW; ++q) rb_l = (tl >> 2) == q ? rb_out[q] : rb_l;
       const int ch = rb_l * 16 + 4 * (tl & 3);
-      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (rb_l >= 0 && (m == 0 || fold_sx) && p.bias != nullptr) bv = *reinterpret_cast<const float4*>(p.bias + ch);
+      // gate||up layer: waves 0,1 hold gate blocks, waves 2,3 the matching up blocks (rb_l is the
+      // block of the hidden channel for both); the up waves finish h = SiLU(gate) * up
+      const bool is_up = MODE == MODE_GATED && wave >= 2;
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f), bg = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (rb_l >= 0 && (m == 0 || fold_sx) && p.bias != nullptr) {
+        bv = *reinterpret_cast<const float4*>(p.bias + ch + (is_up ? p.hidden : 0));
+        if (is_up) bg = *reinterpret_cast<const float4*>(p.bias + ch);
+      }
       const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+      const float bgate[4] = {bg.x, bg.y, bg.z, bg.w};
       // the bias has to have arrived before the first (conditional) store block: a wait placed
       // inside those blocks would be repeated in each and then also wait for the stores before it
       __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -393,21 +404,40 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
           for (int i = 0; i < 4; ++i) yacc[r][b][i] = 0.f;
         }
-        v4f a[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int tq = 4 * q + g;
-          asm volatile("ds_read_b128 %0, %1" : "=v"(a[q]) : "v"(stg + tq * 256 + ((tl ^ tq) << 4)) : "memory");
+        if (MODE == MODE_GATED) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's block is in LDS ...
+          __syncthreads();                                     // ... and so is its partner's
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])::"memory");
+        v4f a[4];
+        if (MODE != MODE_GATED) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int tq = 4 * q + g;
+            asm volatile("ds_read_b128 %0, %1" : "=v"(a[q]) : "v"(stg + tq * 256 + ((tl ^ tq) << 4)) : "memory");
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])::"memory");
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+          if (MODE == MODE_GATED && !is_up) break;
           const int t = t0 + b * 16 + 4 * q + g;
+          v4f ga;
+          if (MODE == MODE_GATED) {
+            // one token row at a time: the up block from this wave's space, the gate block from its partner's
+            const int tq = 4 * q + g;
+            asm volatile("ds_read_b128 %0, %1" : "=v"(a[q]) : "v"(stg + tq * 256 + ((tl ^ tq) << 4)) : "memory");
+            asm volatile("ds_read_b128 %0, %1" : "=v"(ga) : "v"(stg_of(wave ^ 2) + tq * 256 + ((tl ^ tq) << 4)) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[q]), "+v"(ga)::"memory");
+          }
           float v[4] = {a[q][0], a[q][1], a[q][2], a[q][3]};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             v[i] = fold_sx ? v[i] + bb[i] : fmaf(sx, v[i], bb[i]);   // same rounding as the streaming kernel
             if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
+            if (MODE == MODE_GATED) {
+              const float gte = fmaf(sx, ga[i], bgate[i]);
+              v[i] = gte / (1.f + expf(-gte)) * v[i];
+            }
           }
           if (t < p.T && rb_l >= 0) {
 #pragma unroll
@@ -415,6 +445,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
             *reinterpret_cast<float4*>(ycol + (size_t)t * p.out) = make_float4(v[0], v[1], v[2], v[3]);
           }
         }
+        if (MODE == MODE_GATED) __syncthreads();   // both blocks have been read: the staging space is free again
       }
     }
     if (p.amax_out != nullptr) {
@@ -437,6 +468,8 @@ int launch_cfg(TiledParams& p, bool acc_out, hipEvent_t ev0, hipEvent_t ev1, hip
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), st, ev0, ev1, p);
   else if (p.act == PIPE_ACT_GELU)
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GELU>), grid, dim3(256), st, ev0, ev1, p);
+  else if (p.act == PIPE_ACT_SILU_GATED)
+    PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GATED>), grid, dim3(256), st, ev0, ev1, p);
   else
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_PLAIN>), grid, dim3(256), st, ev0, ev1, p);
   PIPE_HIP(hipGetLastError());
@@ -458,6 +491,15 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
+  p.hidden = 0;
+  if (a.act == PIPE_ACT_SILU_GATED) {
+    // gate||up layer: the pair schedule; the output is the hidden activation, H wide, members apart
+    if (e->gt_src_dev == nullptr || a.reduce || a.acc_out != nullptr) return PIPE_EINVAL;
+    p.rb_out = e->gt_rb_out_dev; p.rb_src = e->gt_src_dev; p.ct_mask = e->gt_mask_dev; p.n_sorted = e->n_sorted_gated;
+    p.n_ct = e->n_ct_gated;
+    p.hidden = e->out / 2;
+    p.out = e->out / 2;
+  }
   p.member_nib = 0;
   for (int m = 0; m < a.M; ++m)
     for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_nib |= (unsigned long long)m << (4 * k);

@@ -80,6 +80,14 @@ struct pipe_expansion {
   int32_t* ct_rb_out_dev = nullptr; // [n_sorted] output row block (channel/16) or -1
   int32_t* ct_src_dev = nullptr;    // [K][n_sorted] position (in codes_dev) of the row block in order k, or -1
   uint32_t* ct_mask_dev = nullptr;  // [n_ct] orders (bit k) that hold at least one row block of the column tile
+  // The same three tables for a layer used as gate||up of a gated MLP (out = 2H, rows [0,H) gate,
+  // [H,2H) up): row blocks are sorted as (gate block i, up block i) pairs, and a column tile is 8
+  // pairs -- sorted positions 16t..16t+7 the gate blocks, 16t+8..16t+15 their up blocks -- so that
+  // a workgroup holds both halves of SiLU(gate)*up.  Built when H is a multiple of 16.
+  int n_ct_gated = 0, n_sorted_gated = 0;
+  int32_t* gt_rb_out_dev = nullptr;  // [n_sorted_gated] gate row block (= block of the hidden channel), or -1
+  int32_t* gt_src_dev = nullptr;     // [K][n_sorted_gated]
+  uint32_t* gt_mask_dev = nullptr;   // [n_ct_gated]
   // Stored row blocks of all orders in schedule order: bin b of the weight-streaming kernel owns
   // positions [b*bin_cap, (b+1)*bin_cap), so that kernel addresses its codes from its block index
   // alone; the tiled kernel reaches them through ct_src_dev.  Unused positions are zero.
@@ -167,7 +175,8 @@ struct GemmArgs {
   int member_hi[PIPE_MAX_K];  // 0-based last order (inclusive)
   const float* bias;     // or nullptr
   int reduce;            // 1: y[T,out]; 0: y[M,T,out]
-  int act;               // 0 none, PIPE_ACT_GELU fused in the epilogue
+  int act;               // 0 none; PIPE_ACT_GELU fused in the epilogue; PIPE_ACT_SILU_GATED: the layer is gate||up and
+                         // the tiled kernel writes h = SiLU(gate)*up, [M,T,out/2] (members kept apart)
   float* y;
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
