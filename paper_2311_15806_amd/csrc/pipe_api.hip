@@ -220,7 +220,10 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
       const uint32_t mg = mask_of(i), mu = mask_of(i + n_pairs);
       pairs[i] = Pair{mg, mu, __builtin_popcount(mg) + __builtin_popcount(mu), i};
     }
+    // a tile runs the union of its blocks' order sets: tiles of one union first of all
     std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) {
+      const uint32_t ux = x.mg | x.mu, uy = y.mg | y.mu;
+      if (ux != uy) return __builtin_popcount(ux) != __builtin_popcount(uy) ? __builtin_popcount(ux) > __builtin_popcount(uy) : ux < uy;
       if (x.pop != y.pop) return x.pop > y.pop;
       if (x.mg != y.mg) return x.mg < y.mg;
       if (x.mu != y.mu) return x.mu < y.mu;

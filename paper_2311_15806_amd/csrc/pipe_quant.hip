@@ -78,48 +78,81 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
 }
 
 // One block: token block blockIdx.x (16 tokens), a range of 16-wide k-chunks given by
-// blockIdx.y.  Thread = (token n = tid & 15, chunk slot tid >> 4).  FETCH(t, k) returns the
-// fp32 activation (0 outside the valid region).
+// blockIdx.y (whole 64-k steps).  FETCH(t, k) returns the fp32 activation (0 outside the valid
+// region).  Rows that can be read 16 bytes at a time (xvec) take the wide path for every 64-k step
+// that lies inside the row: a wave owns 16 tokens x 64 k, lane = (token lane >> 2, quarter
+// lane & 3), so one load instruction reads 64 contiguous bytes of each of the 16 rows (and the
+// four loads of a step 256 contiguous bytes per row) and one store instruction writes 256
+// contiguous bytes of the fragment layout.  Everything else (ragged tail, padding, gathers) goes
+// through the generic path: thread = (token tid & 15, chunk slot tid >> 4).
 template <class Fetch>
 __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int in_pad, float s,
                                                uint8_t* __restrict__ qx_frag, int32_t* __restrict__ rowsum,
                                                int8_t* __restrict__ qx_rowmajor, const float* __restrict__ xvec = nullptr) {
   const int tb = blockIdx.x;
-  const int n = threadIdx.x & 15;
-  const int t = tb * 16 + n;
   const int nks = in_pad >> 6;
   const int nchunk = in_pad >> 4;
-  const int per = (nchunk + gridDim.y - 1) / gridDim.y;
-  const int c_lo = blockIdx.y * per;
+  const int per = ((nchunk + (int)gridDim.y - 1) / (int)gridDim.y + 3) & ~3;
+  const int c_lo = min(nchunk, (int)blockIdx.y * per);
   const int c_hi = min(nchunk, c_lo + per);
   const bool live = s > 0.f;
-  int sum = 0;
-  for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
-    int q[16];
-    if (xvec != nullptr && t < T && c * 16 + 15 < in) {
-      // rows are 16-byte aligned: four 16-byte loads per chunk
-      const float4* row = reinterpret_cast<const float4*>(xvec + (size_t)t * in + c * 16);
-      float f[16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int NWAVE = BLK / 64;
+
+  // wide path
+  int c_wide = c_lo;
+  int sum_w = 0;
+  if (xvec != nullptr && qx_rowmajor == nullptr) {
+    c_wide = max(c_lo, min(c_hi, (in >> 6) << 2));
+    const int nw = lane >> 2, sub = lane & 3;
+    const int tw = tb * 16 + nw;
+    const bool row_ok = live && tw < T;
+    const float* row = xvec + (size_t)min(tw, T - 1) * in + sub * 4;
+    uint8_t* dst = qx_frag + (size_t)tb * nks * 1024 + lane * 4;
+    auto load_step = [&](int ks, float4(&f)[4]) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) f[e] = *reinterpret_cast<const float4*>(row + ks * 64 + e * 16);
+    };
+    auto put_step = [&](int ks, const float4(&f)[4]) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float4 v4 = row[e];
-        f[4 * e] = v4.x; f[4 * e + 1] = v4.y; f[4 * e + 2] = v4.z; f[4 * e + 3] = v4.w;
+        int q0 = 0, q1 = 0, q2 = 0, q3 = 0;
+        if (row_ok) {
+          q0 = quant1(f[e].x, s); q1 = quant1(f[e].y, s); q2 = quant1(f[e].z, s); q3 = quant1(f[e].w, s);
+        }
+        sum_w += q0 + q1 + q2 + q3;
+        *reinterpret_cast<uint32_t*>(dst + (size_t)ks * 1024 + e * 256) = pack4(q0, q1, q2, q3);
       }
+    };
+    const int ks_hi = c_wide >> 2;
+    int ks = (c_lo >> 2) + wave;
+    for (; ks + NWAVE < ks_hi; ks += 2 * NWAVE) {   // two steps = eight 16-byte loads in flight
+      float4 f0[4], f1[4];
+      load_step(ks, f0);
+      load_step(ks + NWAVE, f1);
+      put_step(ks, f0);
+      put_step(ks + NWAVE, f1);
+    }
+    for (; ks < ks_hi; ks += NWAVE) {
+      float4 f0[4];
+      load_step(ks, f0);
+      put_step(ks, f0);
+    }
+  }
+
+  // generic path
+  const int n = threadIdx.x & 15;
+  const int t = tb * 16 + n;
+  int sum = 0;
+  for (int c = c_wide + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
+    int q[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int v = live ? quant1(f[e], s) : 0;
-        q[e] = v;
-        sum += v;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int k = c * 16 + e;
-        int v = 0;
-        if (live && t < T && k < in) v = quant1(fetch(t, k), s);
-        q[e] = v;
-        sum += v;
-      }
+    for (int e = 0; e < 16; ++e) {
+      const int k = c * 16 + e;
+      int v = 0;
+      if (live && t < T && k < in) v = quant1(fetch(t, k), s);
+      q[e] = v;
+      sum += v;
     }
     const int ks = c >> 2, kc = c & 3;
     uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
@@ -131,17 +164,20 @@ __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int i
         if (c * 16 + e < in) qx_rowmajor[(size_t)t * in + c * 16 + e] = (int8_t)q[e];
     }
   }
-  // one atomic per token and workgroup: threads 16 apart hold the same token (lane bits 4 and 5
-  // inside a wave, then the waves through LDS)
+  // one atomic per token and workgroup.  Generic path: threads 16 apart hold the same token
+  // (lane bits 4 and 5); wide path: the four lanes of a quarter group; then the waves through LDS.
   sum += __shfl_xor(sum, 16, 64);
   sum += __shfl_xor(sum, 32, 64);
-  __shared__ int wsum[BLK / 64][16];
-  if ((threadIdx.x & 63) < 16) wsum[threadIdx.x >> 6][threadIdx.x & 15] = sum;
+  sum_w += __shfl_xor(sum_w, 1, 64);
+  sum_w += __shfl_xor(sum_w, 2, 64);
+  __shared__ int wsum[2][NWAVE][16];
+  if (lane < 16) wsum[0][wave][lane] = sum;
+  if ((lane & 3) == 0) wsum[1][wave][lane >> 2] = sum_w;
   __syncthreads();
   if (threadIdx.x < 16) {
     int tot = 0;
 #pragma unroll
-    for (int w = 0; w < BLK / 64; ++w) tot += wsum[w][threadIdx.x];
+    for (int w = 0; w < NWAVE; ++w) tot += wsum[0][w][threadIdx.x] + wsum[1][w][threadIdx.x];
     if (t < T && tot != 0) atomicAdd(&rowsum[t], tot);
   }
 }
