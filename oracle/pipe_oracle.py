@@ -18,6 +18,7 @@ Passages followed
   * expanded-layer forward ....................... App. B, Eq. (define_dre)
   * ensemble members, bias in predictor 1 ........ Sec. 3.2, Fig. 2 caption,
                                                    App. B "Ensemble of more Layers"
+  * L-layer member chains with skips ............. App. B / App. D "more Layers", Fig. 2
   * operation head-count ......................... App. H
 
 Readings taken where the paper is silent (each is listed in the design notes):
@@ -27,13 +28,16 @@ keep the ceil(gamma*n_groups) groups of `group` consecutive output channels with
 the largest residual energy (sum of squares, fp64), re-selected at every order,
 ties to the lower group index; activations are per-tensor symmetric int8 with a
 static scale if given, else absmax/127; a member owns a contiguous range of
-orders in every layer and its own activation scale.
+orders in every layer and its own activation scale; in a chain a skip connection
+is member-wise, except one that reads the network input, which only the first
+member adds.
 
 Pins: every function here is checked in tests/test_oracle_pins.py against facts
 that do not come from this file (hand-worked example, exhaustive nearest-code
 search, the Lemma's bound, brute-force mask enumeration, torch integer matmul
 and conv2d, closed forms).  Not pinned by the paper (this build's reading only):
-the group-selection criterion and the member-wise treatment of gated MLPs.
+the group-selection criterion, the member-wise treatment of gated MLPs and the
+first-member-only skip from the network input.
 """
 from __future__ import annotations
 
@@ -418,6 +422,106 @@ def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None):
     members = np.stack(outs)
     return dict(y=sum_members(members), members=members, s_h=np.array(shs, dtype=f32),
                 Qh=np.stack(Qhs))
+
+
+# ----------------------------------------------------------------------------
+# App. B "Ensemble of more Layers" / App. D "Ensembling with more Layers":
+# an L-layer feed-forward network as M independent member chains
+# ----------------------------------------------------------------------------
+@dataclass
+class ChainLayer:
+    """One layer of the chain: z = expanded layer (+ bias), then activation and skip.
+
+    act          "none" | "relu" | "gelu" (erf form)
+    skip_from    -1: no skip; j >= 0: add the tensor that ENTERED layer j (0-based;
+                 j = 0 is the network input, j <= this layer's index), as in the residual
+                 network of Fig. 2
+    skip_pre_act True: a = act(z + r) (ResNet block); False: a = act(z) + r"""
+    exp: Expansion
+    bias: Optional[np.ndarray] = None
+    act: str = "none"
+    skip_from: int = -1
+    skip_pre_act: bool = True
+
+
+def relu(v: np.ndarray) -> np.ndarray:
+    return np.maximum(np.asarray(v, dtype=f32), f32(0))
+
+
+def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: bool, skips,
+                        split=None, s_x: Optional[float] = None) -> np.ndarray:
+    """One layer for all members.  inputs: [T, I] when every member reads the same tensor
+    (the network input; s_x is its static scale if given), else [M, T, I] and member m
+    quantizes inputs[m] with its own dynamic scale.  Member m contracts with its own orders
+    only; the bias goes to the first member.  skips: None, or a list of M entries (an array
+    [T, O] or None) added before or after the activation.  Returns [M, T, O] fp32."""
+    exp = layer.exp
+    rngs = member_ranges(exp.K, split)
+    M = len(rngs)
+    out = []
+    for m in range(M):
+        xin = inputs if shared_input else inputs[m]
+        Qa, sa = quantize_activations(xin, s_x if shared_input else None)
+        acc = forward_acc(exp, Qa)
+        z = dequantize(exp, acc, sa, split, layer.bias, f32)[m]
+        r = None if skips is None else skips[m]
+        if r is not None and layer.skip_pre_act:
+            z = (z + np.asarray(r, dtype=f32)).astype(f32)
+        if layer.act == "relu":
+            a = relu(z)
+        elif layer.act == "gelu":
+            a = gelu(z)
+        elif layer.act == "none":
+            a = z
+        else:
+            raise ValueError("act must be 'none', 'relu' or 'gelu'")
+        if r is not None and not layer.skip_pre_act:
+            a = (a + np.asarray(r, dtype=f32)).astype(f32)
+        out.append(a.astype(f32))
+    return np.stack(out)
+
+
+def chain_skips(layers: Sequence[ChainLayer], l: int, x: np.ndarray, acts: Sequence[np.ndarray], M: int):
+    """The tensors layer l adds: member m's own copy of what entered layer skip_from.  The
+    network input is not split over the members, so -- like the bias -- a skip that reads it
+    enters the sum once, through the first member."""
+    j = layers[l].skip_from
+    if j < 0:
+        return None
+    if j > l:
+        raise ValueError("a skip reads an earlier tensor")
+    if j == 0:
+        return [np.asarray(x, dtype=f32)] + [None] * (M - 1)
+    return [acts[j - 1][m] for m in range(M)]
+
+
+def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: Optional[float] = None):
+    """M member chains through L expanded layers, summed after the last one.
+
+    Member m is the whole architecture with, in every layer, only the orders of its own
+    cluster; it quantizes each hidden activation with its own dynamic per-tensor scale;
+    biases (and a skip from the network input) belong to the first member.  The last
+    layer has no activation of its own (act must be "none").
+    Returns dict(y [T, O_L], members [M, T, O_L], acts: list of L-1 arrays [M, T, O_l])."""
+    L = len(layers)
+    if L < 1:
+        raise ValueError("at least one layer")
+    K = layers[0].exp.K
+    if any(ly.exp.K != K for ly in layers):
+        raise ValueError("all layers need the same expansion order")
+    if layers[-1].act != "none":
+        raise ValueError("the last layer has no activation")
+    M = len(member_ranges(K, split))
+    acts: List[np.ndarray] = []
+    for l, ly in enumerate(layers):
+        skips = chain_skips(layers, l, x, acts, M)
+        if l == 0:
+            a = chain_layer_members(ly, np.asarray(x, dtype=f32), True, skips, split, s_x)
+        else:
+            a = chain_layer_members(ly, acts[l - 1], False, skips, split)
+        acts.append(a)
+    members = acts.pop()
+    return dict(y=sum_members(members), members=members, acts=acts)
 
 
 # ----------------------------------------------------------------------------

@@ -341,6 +341,153 @@ def test_mlp_ensemble_members_use_only_their_orders():
     assert np.abs(out["y"] - full).max() < 0.15 * np.abs(full).max()
 
 
+# ---------------------------------------------------------------- L-layer member chains
+def _frac(v):
+    from fractions import Fraction
+    return float(Fraction(v))
+
+
+def test_chain_worked_example(golden_dir):
+    """Two small networks worked in exact rationals from App. B: pins the member-wise skip,
+    the first-member-only bias and input skip, the per-member dynamic activation scales
+    and the sum after the last layer."""
+    g = json.load(open(os.path.join(golden_dir, "chain_worked.json")))
+    exps = {}
+    for name in ("W0", "W1", "W2"):
+        e = po.expand(np.array(g[name], dtype=f32), g["bits"], g["K"], 1.0, 1)
+        for k in range(g["K"]):
+            assert e.orders[k].codes.tolist() == g["expansion"][name]["codes"][k], (name, k)
+            want = [_frac(v) for v in g["expansion"][name]["scales"][k]]
+            assert np.allclose(e.orders[k].scales, want, rtol=1e-6, atol=0), (name, k)
+        exps[name] = e
+    x = np.array(g["x"], dtype=f32)
+    bias = {"W0": np.array(g["b0"], dtype=f32), "W1": None, "W2": np.array(g["b2"], dtype=f32)}
+    for case, names in (("case_A", ("W0", "W1", "W2")), ("case_B", ("W0", "W1"))):
+        c = g[case]
+        layers = [po.ChainLayer(exps[n], bias[n], d["act"], d["skip_from"], d.get("skip_pre_act", True))
+                  for n, d in zip(names, c["layers"])]
+        r = po.chain_forward(layers, x, split=g["split"])
+        for m, key in enumerate(("member_1", "member_2")):
+            mm = c[key]
+            assert np.allclose(r["acts"][0][m][0], [_frac(v) for v in mm["a1"]], rtol=1e-5, atol=1e-9), (case, key)
+            Qa, _ = po.quantize_activations(r["acts"][0][m])
+            assert Qa[0].tolist() == mm["Q_a1"], (case, key)
+            if "a2" in mm:
+                assert np.allclose(r["acts"][1][m][0], [_frac(v) for v in mm["a2"]], rtol=1e-5, atol=1e-9)
+                Qa, _ = po.quantize_activations(r["acts"][1][m])
+                assert Qa[0].tolist() == mm["Q_a2"], (case, key)
+            assert np.allclose(r["members"][m][0], [_frac(v) for v in mm["y"]], rtol=1e-5, atol=1e-9), (case, key)
+        assert np.allclose(r["y"][0], [_frac(v) for v in c["y"]], rtol=1e-5, atol=1e-9), case
+
+
+def _chain_net(seed, widths, K, bits, skips, acts):
+    rng = np.random.default_rng(seed)
+    layers, Ws, bs = [], [], []
+    for l in range(len(widths) - 1):
+        W = (rng.standard_normal((widths[l + 1], widths[l])) / math.sqrt(widths[l])).astype(f32)
+        b = (3.0 * rng.standard_normal(widths[l + 1])).astype(f32)
+        Ws.append(W)
+        bs.append(b)
+        sf, pre = skips[l]
+        layers.append(po.ChainLayer(po.expand(W, bits, K, 1.0, 8), b, acts[l], sf, pre))
+    return layers, Ws, bs
+
+
+def _float_net(Ws, bs, skips, acts, x):
+    """The full-precision network the chain expands, in fp64 (textbook forward pass)."""
+    tensors = [x.astype(np.float64)]
+    for l, (W, b) in enumerate(zip(Ws, bs)):
+        z = tensors[l] @ W.astype(np.float64).T + b
+        sf, pre = skips[l]
+        r = tensors[sf] if sf >= 0 else 0.0
+        if pre:
+            z = z + r
+        if acts[l] == "relu":
+            z = np.maximum(z, 0.0)
+        elif acts[l] == "gelu":
+            z = torch.nn.functional.gelu(torch.from_numpy(z)).numpy()
+        if not pre:
+            z = z + r
+        tensors.append(z)
+    return tensors
+
+
+@pytest.mark.parametrize("split", [None, [2, 2], [1, 1, 2]])
+def test_chain_converges_to_the_full_precision_network(split):
+    """With 8-bit orders and K = 4 the expansion is the full-precision weight to ~1e-7, so the
+    chain must reproduce the fp64 network up to the int8 activation grid (~1 % of a layer's
+    range).  Biases three times the pre-activations and skips from the input and from hidden
+    tensors make any misplaced bias or skip (all members, wrong tensor, wrong side of the
+    activation) an error many times that."""
+    widths = [24, 32, 32, 32, 16]
+    skips = [(-1, True), (1, True), (0, False), (-1, True)]
+    skips[2] = (2, False)
+    acts = ["relu", "relu", "gelu", "none"]
+    layers, Ws, bs = _chain_net(80, widths, 4, 8, skips, acts)
+    rng = np.random.default_rng(81)
+    x = (4.0 * rng.standard_normal((7, 24))).astype(f32)
+    ref = _float_net(Ws, bs, skips, acts, x)
+    r = po.chain_forward(layers, x, split=split)
+    for l in range(3):
+        tot = r["acts"][l].astype(np.float64).sum(axis=0)
+        assert np.abs(tot - ref[l + 1]).max() < 0.03 * np.abs(ref[l + 1]).max(), l
+    assert np.abs(r["y"] - ref[4]).max() < 0.03 * np.abs(ref[4]).max()
+    # the same with the first layer skipping from the network input itself
+    widths2 = [32, 32, 16]
+    skips2 = [(0, True), (-1, True)]
+    acts2 = ["relu", "none"]
+    layers2, Ws2, bs2 = _chain_net(82, widths2, 4, 8, skips2, acts2)
+    x2 = (4.0 * rng.standard_normal((7, 32))).astype(f32)
+    ref2 = _float_net(Ws2, bs2, skips2, acts2, x2)
+    r2 = po.chain_forward(layers2, x2, split=split)
+    assert np.abs(r2["y"] - ref2[2]).max() < 0.03 * np.abs(ref2[2]).max()
+
+
+def test_chain_single_member_is_layer_by_layer_forward():
+    """M = 1: the chain is the pinned single-layer forward applied L times with the
+    activation and the skip between (written out here for one fixed architecture)."""
+    skips = [(-1, True), (1, True), (-1, True)]
+    acts = ["relu", "relu", "none"]
+    layers, _, bs = _chain_net(83, [24, 32, 32, 8], 2, 4, skips, acts)
+    x = np.random.default_rng(84).standard_normal((5, 24)).astype(f32)
+    r = po.chain_forward(layers, x)
+    a1 = np.maximum(po.forward(layers[0].exp, x, bias=bs[0])["y"], 0)
+    a2 = np.maximum((po.forward(layers[1].exp, a1, bias=bs[1])["y"] + a1).astype(f32), 0)
+    y = po.forward(layers[2].exp, a2, bias=bs[2])["y"]
+    assert np.array_equal(r["acts"][0][0], a1) and np.array_equal(r["acts"][1][0], a2)
+    assert np.array_equal(r["y"], y)
+    # two layers with GELU between: the pinned MLP routine
+    l2 = [po.ChainLayer(layers[0].exp, bs[0], "gelu"), po.ChainLayer(layers[1].exp, bs[1], "none")]
+    m = po.mlp_forward(layers[0].exp, layers[1].exp, "gelu", x, split=[1, 1], bias1=bs[0], bias2=bs[1])
+    c = po.chain_forward(l2, x, split=[1, 1])
+    assert np.array_equal(c["y"], m["y"]) and np.array_equal(c["acts"][0], m["h"])
+
+
+def test_chain_members_are_independent_networks():
+    """Member 2 of split [1,1] equals a network built from the order-2 terms alone, with no
+    bias anywhere, fed the same input; member 1 does not change when order 2 is altered."""
+    skips = [(-1, True), (1, True), (-1, True)]
+    acts = ["relu", "relu", "none"]
+    layers, _, bs = _chain_net(85, [24, 32, 32, 8], 2, 4, skips, acts)
+    x = np.random.default_rng(86).standard_normal((5, 24)).astype(f32)
+    r = po.chain_forward(layers, x, split=[1, 1])
+
+    def order2(e, a):
+        Qa, sa = po.quantize_activations(a)
+        return f32(sa) * (e.dense_scales(2)[None, :] * po.contract(Qa, e.dense_codes(2)).astype(f32))
+
+    a1 = np.maximum(order2(layers[0].exp, x), 0)
+    a2 = np.maximum((order2(layers[1].exp, a1) + a1).astype(f32), 0)
+    y2 = order2(layers[2].exp, a2)
+    assert np.allclose(r["acts"][1][1], a2, rtol=1e-6, atol=1e-9)
+    assert np.allclose(r["members"][1], y2, rtol=1e-6, atol=1e-9)
+    assert np.array_equal(r["y"], (r["members"][0] + r["members"][1]).astype(f32))
+    one = po.chain_forward([po.ChainLayer(po.expand(
+        (ly.exp.dense_scales(1)[:, None] * ly.exp.dense_codes(1)).astype(f32), 4, 1, 1.0, 8), ly.bias, ly.act,
+        ly.skip_from, ly.skip_pre_act) for ly in layers], x)
+    assert np.allclose(r["members"][0], one["y"], rtol=1e-5, atol=1e-7)
+
+
 # ---------------------------------------------------------------- App. H
 def test_operation_head_count_closed_form():
     o, q, e = po.bit_operations(D=1, d=1, n_i=4096, n_o=11008, s=1, b=4, k=3)
