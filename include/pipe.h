@@ -49,7 +49,7 @@ enum {
   PIPE_ESPLIT = -5   /* split entries not positive or not summing to K            */
 };
 
-enum { PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2 };
+enum { PIPE_ACT_NONE = 0, PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2, PIPE_ACT_RELU = 3 };
 
 /* Build the expansion (R^1..R^K) of W (Sec. 3.1, Eq. (2)-(3); mask: masked Eq.).
  *   W_dev   [out, in] fp32, read only.
@@ -127,6 +127,37 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
                      const float* x_dev, int T, float s_x, const int* split, int M,
                      const float* bias1_dev, const float* bias2_dev, float* h_dev,
                      float* y_dev, void* stream);
+
+/* One layer of a member chain (pipe_chain_forward).                             */
+typedef struct pipe_chain_layer {
+  const pipe_expansion* e; /* [out_l, in_l]; in_l = width of the tensor entering it   */
+  const float* bias_dev;   /* DEVICE, NULL or [out_l]; first member only              */
+  int act;                 /* PIPE_ACT_NONE, PIPE_ACT_RELU or PIPE_ACT_GELU (erf)     */
+  int skip_from;           /* -1: no skip; j in 0..l: add the tensor that ENTERED
+                              layer j (0 = the network input), width out_l          */
+  int skip_pre_act;        /* 1: a = act(z + r) (residual block); 0: a = act(z) + r   */
+} pipe_chain_layer;
+
+/* An L-layer feed-forward network run as M independent member chains that are
+ * summed after the last layer (Sec. 3.2, Fig. 2; App. B "Ensemble of more Layers
+ * DNNs", App. D "Ensembling with more Layers").  Member m is the whole
+ * architecture with, in every layer, only the orders of its own cluster; it
+ * quantizes each tensor entering a layer with its own dynamic per-tensor scale
+ * (s_x applies to the network input, which all members share); biases belong to
+ * the first member.  A skip is member-wise -- member m adds its own copy of the
+ * earlier tensor -- except a skip from the network input, which is not split
+ * over the members and enters the sum once, through the first member.
+ *   layers   HOST [L], L >= 1, same K in every layer; the last layer's act must be
+ *            PIPE_ACT_NONE (the members are summed behind it)
+ *   acts_dev HOST [L-1] of DEVICE pointers, or NULL; entry l NULL or [M, T, out_l]
+ *            fp32 to receive the tensor leaving layer l of every member
+ *   y_dev    [T, out_{L-1}] = sum over members, ascending
+ * All members of a layer run in one launch.  Errors: PIPE_EINVAL (NULL, act or
+ * skip out of range), PIPE_ESHAPE (widths do not chain, skip width mismatch),
+ * PIPE_ESPLIT (layers differ in K, bad split), PIPE_ENOMEM, PIPE_EDEVICE.       */
+int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
+                       float s_x, const int* split, int M, float* const* acts_dev,
+                       float* y_dev, void* stream);
 
 /* Kernel selection for pipe_forward / pipe_mlp_forward (tuning and tests):
  * 0 = automatic by token count, 1 = tiled MFMA kernel, 2 = weight-streaming

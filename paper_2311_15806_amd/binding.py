@@ -17,8 +17,10 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpipe_hip.so")
 
+PIPE_ACT_NONE = 0
 PIPE_ACT_GELU = 1
 PIPE_ACT_SILU_GATED = 2
+PIPE_ACT_RELU = 3
 
 
 class PipeError(RuntimeError):
@@ -45,6 +47,7 @@ def _load():
     lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
+    lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
@@ -215,6 +218,32 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
                                  arr, m, _ptr(bias1, torch.float32), _ptr(bias2, torch.float32),
                                  _ptr(h), _ptr(y), _stream()), "pipe_mlp_forward")
     return (y, h) if return_hidden else y
+
+
+class _ChainLayer(C.Structure):
+    _fields_ = [("e", C.c_void_p), ("bias_dev", C.c_void_p), ("act", C.c_int), ("skip_from", C.c_int),
+                ("skip_pre_act", C.c_int)]
+
+
+def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, return_acts: bool = False,
+                       out: Optional[torch.Tensor] = None):
+    """layers: sequence of (Expansion, bias or None, act, skip_from, skip_pre_act)."""
+    T = x.shape[0]
+    L = len(layers)
+    M = 1 if split is None else len(split)
+    arr_l = (_ChainLayer * L)()
+    for l, (e, bias, act, skip_from, pre) in enumerate(layers):
+        arr_l[l] = _ChainLayer(e.handle, _ptr(bias, torch.float32), int(act), int(skip_from), 1 if pre else 0)
+    y = out if out is not None else torch.empty((T, layers[-1][0].out_features), dtype=torch.float32, device=x.device)
+    acts, acts_arr = None, None
+    if return_acts and L > 1:
+        acts = [torch.empty((M, T, layers[l][0].out_features), dtype=torch.float32, device=x.device)
+                for l in range(L - 1)]
+        acts_arr = (C.c_void_p * (L - 1))(*[_ptr(a) for a in acts])
+    arr, m = _split(split)
+    _check(_lib.pipe_chain_forward(arr_l, L, _ptr(x, torch.float32), T, float(s_x), arr, m, acts_arr, _ptr(y),
+                                   _stream()), "pipe_chain_forward")
+    return (y, acts) if return_acts else y
 
 
 def pipe_set_kernel(which: int) -> None:

@@ -626,7 +626,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   // after each use, by the layer-2 kernel that follows their last reader.  A call that failed
   // between the two leaves them dirty; then they are cleared by a launch of their own.
   if (g_amax_h_dirty) {
-    rc = launch_zero_u32(amax_h, PIPE_MAX_K, st);
+    rc = launch_zero_u32(amax_h, 2 * PIPE_MAX_K, st);
     if (rc) return rc;
   }
   g_amax_h_dirty = true;
@@ -677,4 +677,137 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   rc = run_gemm(a2, small, st);
   if (rc == PIPE_OK) g_amax_h_dirty = false;
   return rc;
+}
+
+// ------------------------------------------------------------------ member chains
+extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T, float s_x,
+                                  const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
+  for (int l = 0; l < L; ++l) {
+    const pipe_chain_layer& ly = layers[l];
+    if (!ly.e) return PIPE_EINVAL;
+    if (ly.act != PIPE_ACT_NONE && ly.act != PIPE_ACT_RELU && ly.act != PIPE_ACT_GELU) return PIPE_EINVAL;
+    if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
+    if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;
+    if (l > 0 && ly.e->in != layers[l - 1].e->out) return PIPE_ESHAPE;
+    // the tensor that entered layer j is in_j wide
+    if (ly.skip_from >= 0 && layers[ly.skip_from].e->in != ly.e->out) return PIPE_ESHAPE;
+  }
+  if (layers[L - 1].act != PIPE_ACT_NONE) return PIPE_EINVAL;
+  const int K = layers[0].e->K;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(layers[0].e, T);   // same K everywhere: one decision
+  int in_pad_max = 0;
+  for (int l = 1; l < L; ++l) in_pad_max = std::max(in_pad_max, layers[l].e->in_pad);
+  ActBuffers b;
+  rc = get_act_buffers(T, layers[0].e->in_pad, small, &b);
+  if (rc) return rc;
+  const int T_pad = b.T_pad;
+
+  // Tensors leaving layers 0..L-2, [M, T, out_l] each.  Tensor l lives until its last reader:
+  // layer l+1, or a later layer whose skip reads it.  Those the caller did not give a buffer
+  // for share a pool of equal slabs.
+  std::vector<float*> act(L > 1 ? L - 1 : 0, nullptr);
+  {
+    std::vector<int> last(L, 0), slab(L, -1);
+    size_t slab_floats = 0;
+    for (int l = 0; l + 1 < L; ++l) {
+      last[l] = l + 1;
+      for (int j = l + 1; j < L; ++j)
+        if (layers[j].skip_from == l + 1) last[l] = j;
+      if (!(acts_dev && acts_dev[l])) slab_floats = std::max(slab_floats, (size_t)Mm * T * layers[l].e->out);
+    }
+    slab_floats = (slab_floats + 63) & ~(size_t)63;
+    std::vector<int> busy_until;   // per slab: the last layer that reads its tensor
+    for (int l = 0; l + 1 < L; ++l) {
+      if (acts_dev && acts_dev[l]) continue;
+      int s = -1;
+      for (size_t i = 0; i < busy_until.size(); ++i)
+        if (busy_until[i] < l) { s = (int)i; break; }   // its last reader ran before layer l writes
+      if (s < 0) { s = (int)busy_until.size(); busy_until.push_back(0); }
+      busy_until[s] = last[l];
+      slab[l] = s;
+    }
+    float* pool = nullptr;
+    if (!busy_until.empty()) {
+      pool = (float*)pipe_ws_get(WS_CHAIN, busy_until.size() * slab_floats * sizeof(float));
+      if (!pool) return PIPE_ENOMEM;
+    }
+    for (int l = 0; l + 1 < L; ++l) act[l] = (acts_dev && acts_dev[l]) ? acts_dev[l] : pool + (size_t)slab[l] * slab_floats;
+  }
+  uint8_t* qh = nullptr;
+  int32_t* rowsum_h = nullptr;
+  if (L > 1) {
+    qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * in_pad_max);
+    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+    if (!qh || !rowsum_h) return PIPE_ENOMEM;
+  }
+  // max|tensor| per member, two sets used in turn: layer l writes set l & 1 in its epilogue, the
+  // quantizer of layer l+1 reads it, and the contraction of layer l+1 clears it again
+  uint32_t* amax_set[2] = {b.amax + 16, b.amax + 16 + PIPE_MAX_K};
+  float* scale_h = b.scale + 16;
+  if (g_amax_h_dirty) {
+    rc = launch_zero_u32(amax_set[0], 2 * PIPE_MAX_K, st);
+    if (rc) return rc;
+  }
+  g_amax_h_dirty = true;
+
+  rc = quantize_input(x_dev, T, layers[0].e->in, layers[0].e->in_pad, s_x, b, small, nullptr, b.scale, st);
+  if (rc) return rc;
+  for (int l = 0; l < L; ++l) {
+    const pipe_chain_layer& ly = layers[l];
+    const pipe_expansion* e = ly.e;
+    const bool last_layer = l == L - 1;
+    GemmArgs a{};
+    a.e = e; a.T = T; a.T_pad = T_pad;
+    if (l == 0) {
+      // every member reads the same Q(x)
+      a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale; a.zero_after = b.amax;
+    } else {
+      // each member quantizes its own tensor with its own scale
+      const float* src = act[l - 1];
+      const int in = e->in;
+      uint32_t* amax_in = amax_set[(l - 1) & 1];
+      if (small && T <= PIPE_QUANT1_MAX_T) {
+        rc = launch_quantize_small(src, (int64_t)T * in, Mm, T, in, e->in_pad, 0.f, amax_in, qh, (int64_t)T_pad * e->in_pad,
+                                   rowsum_h, nullptr, scale_h, st);
+        if (rc) return rc;
+      } else {
+        for (int m = 0; m < Mm; ++m) {
+          rc = launch_quantize_act(src + (size_t)m * T * in, T, in, e->in_pad, T_pad, 0.f, amax_in + m,
+                                   qh + (size_t)m * T_pad * e->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
+                                   scale_h + m, st);
+          if (rc) return rc;
+        }
+      }
+      a.qx = qh; a.qx_mstride = (int64_t)T_pad * e->in_pad;
+      a.rowsum = rowsum_h; a.rowsum_mstride = T_pad;
+      a.s_x = scale_h; a.sx_mstride = 1;
+      a.zero_after = amax_in; a.zero_n = Mm;
+    }
+    a.bias = ly.bias_dev;
+    a.act = ly.act;
+    if (ly.skip_from == 0) {
+      a.res = x_dev; a.res_mstride = 0; a.res_members = 1;
+    } else if (ly.skip_from > 0) {
+      a.res = act[ly.skip_from - 1]; a.res_mstride = (int64_t)T * e->out; a.res_members = Mm;
+    }
+    a.res_pre_act = ly.skip_pre_act ? 1 : 0;
+    if (last_layer) {
+      a.reduce = 1; a.y = y_dev;
+    } else {
+      a.reduce = 0; a.y = act[l]; a.amax_out = amax_set[l & 1];
+    }
+    fill_members(a, Mm, lo, hi);
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
+  }
+  // the last layer cleared the set it read; the other set was cleared one layer earlier
+  g_amax_h_dirty = false;
+  return PIPE_OK;
 }

@@ -49,6 +49,9 @@ struct TiledParams {
   uint32_t* zero_after;
   int zero_n;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
+  const float* res;               // MODE_CHAIN: skip tensor [res_members, T, out] or nullptr
+  long long res_mstride;
+  int res_members, res_pre_act;
   int hidden;                     // MODE_GATED: H; the layer's rows are gate [0,H) and up [H,2H), y is [M,T,H]
   int n_st_t;                     // super-tiles along tokens
   unsigned long long member_nib;  // member of order k in bits [4k, 4k+4)
@@ -133,7 +136,9 @@ __device__ __forceinline__ T cload(const T* base, size_t idx) {
   return ((cptr)(unsigned long long)base)[idx];
 }
 
-enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2, MODE_GATED = 3 };
+// MODE_CHAIN: activation chosen at run time (none, ReLU, GELU) and a skip tensor added before or
+// after it (a layer inside a member chain)
+enum { MODE_PLAIN = 0, MODE_ACC_OUT = 1, MODE_GELU = 2, MODE_GATED = 3, MODE_CHAIN = 4 };
 
 }  // namespace
 
@@ -395,8 +400,25 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       // inside those blocks would be repeated in each and then also wait for the stores before it
       __builtin_amdgcn_s_waitcnt(0x0F70);
       float* ycol = p.y + (size_t)(p.reduce ? 0 : m) * p.T * p.out + ch;
+      // skip tensor: the members summed into this output each add their own (members kept
+      // apart: member m adds its own if it has one)
+      const int n_res = (MODE == MODE_CHAIN && p.res != nullptr) ? (fold_sx || p.reduce ? p.res_members : (m < p.res_members ? 1 : 0)) : 0;
+      const float* rcol = MODE == MODE_CHAIN ? p.res + (size_t)(p.reduce ? 0 : m) * p.res_mstride + max(ch, 0) : nullptr;
 #pragma unroll
       for (int b = 0; b < MTB; ++b) {
+        float4 rq[4];
+        if (MODE == MODE_CHAIN) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) rq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+          for (int mm = 0; mm < n_res; ++mm) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int tc = min(t0 + b * 16 + 4 * q + g, p.T - 1);   // clamped: loaded unconditionally
+              const float4 r = *reinterpret_cast<const float4*>(rcol + (size_t)mm * p.res_mstride + (size_t)tc * p.out);
+              rq[q].x += r.x; rq[q].y += r.y; rq[q].z += r.z; rq[q].w += r.w;
+            }
+          }
+        }
 #pragma unroll
         for (int r = 0; r < NRW; ++r) {
           const v4f val = v4f{yacc[r][b][0], yacc[r][b][1], yacc[r][b][2], yacc[r][b][3]};
@@ -434,6 +456,13 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           for (int i = 0; i < 4; ++i) {
             v[i] = fold_sx ? v[i] + bb[i] : fmaf(sx, v[i], bb[i]);   // same rounding as the streaming kernel
             if (MODE == MODE_GELU) v[i] = gelu_erf(v[i]);
+            if (MODE == MODE_CHAIN) {
+              const float r = i == 0 ? rq[q].x : i == 1 ? rq[q].y : i == 2 ? rq[q].z : rq[q].w;
+              if (p.res_pre_act) v[i] += r;
+              if (p.act == PIPE_ACT_RELU) v[i] = fmaxf(v[i], 0.f);
+              else if (p.act == PIPE_ACT_GELU) v[i] = gelu_erf(v[i]);
+              if (!p.res_pre_act) v[i] += r;
+            }
             if (MODE == MODE_GATED) {
               const float gte = fmaf(sx, ga[i], bgate[i]);
               v[i] = gte / (1.f + expf(-gte)) * v[i];
@@ -466,6 +495,8 @@ int launch_cfg(TiledParams& p, bool acc_out, hipEvent_t ev0, hipEvent_t ev1, hip
   const dim3 grid((unsigned)(ceil_div(p.n_st_t * n_st_c, 8) * 8 * 64));
   if (acc_out)
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), st, ev0, ev1, p);
+  else if (p.res != nullptr || p.act == PIPE_ACT_RELU)
+    PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_CHAIN>), grid, dim3(256), st, ev0, ev1, p);
   else if (p.act == PIPE_ACT_GELU)
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_GELU>), grid, dim3(256), st, ev0, ev1, p);
   else if (p.act == PIPE_ACT_SILU_GATED)
@@ -492,6 +523,9 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.hidden = 0;
+  p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act;
+  if (a.res != nullptr && (a.acc_out != nullptr || a.act == PIPE_ACT_SILU_GATED || a.res_members < 1 || a.res_members > a.M))
+    return PIPE_EINVAL;
   if (a.act == PIPE_ACT_SILU_GATED) {
     // gate||up layer: the pair schedule; the output is the hidden activation, H wide, members apart
     if (e->gt_src_dev == nullptr || a.reduce || a.acc_out != nullptr) return PIPE_EINVAL;

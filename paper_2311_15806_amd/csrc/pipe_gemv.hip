@@ -40,6 +40,9 @@ struct StreamParams {
   float* y;
   int32_t* acc_out;
   uint32_t* amax_out;
+  const float* res;        // skip tensor [res_members, T, out] or nullptr
+  long long res_mstride;
+  int res_members, res_pre_act;
   uint32_t* zero_after;
   int zero_n;
   int T, out, K, nks, M, reduce, act;
@@ -273,7 +276,17 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
       const float bm = (m == 0 || fold_sx) ? bias : 0.f;
       float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the tiled kernel
       yacc = 0.f;
+      float rsum = 0.f;
+      if (p.res != nullptr) {
+        // the members summed into this output each add their own skip tensor
+        const int n_res = p.reduce ? p.res_members : (m < p.res_members ? 1 : 0);
+        const float* rp = p.res + (size_t)(p.reduce ? 0 : m) * p.res_mstride + (size_t)min(tg, p.T - 1) * p.out + col;
+        for (int mm = 0; mm < n_res; ++mm) rsum += rp[(size_t)mm * p.res_mstride];
+      }
+      if (p.res_pre_act) v += rsum;
       if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
+      else if (p.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
+      if (!p.res_pre_act) v += rsum;
       if (p.amax_out != nullptr) {
         float mx = tg < p.T ? fabsf(v) : 0.f;
 #pragma unroll
@@ -313,7 +326,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.bins = e->bins_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   // Fewer bins than half the CUs and a long k: split each bin over several workgroups (each still
   // with at least two tiles per wave).  With more bins a split only adds the exchange through

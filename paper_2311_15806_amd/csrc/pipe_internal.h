@@ -120,7 +120,7 @@ struct PipeWorkspace {
 // Returns a device buffer of at least `bytes` from slot `slot` (grow-only; growing
 // synchronizes the device first).  nullptr on failure.
 void* pipe_ws_get(int slot, size_t bytes);
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
@@ -177,6 +177,11 @@ struct GemmArgs {
   int reduce;            // 1: y[T,out]; 0: y[M,T,out]
   int act;               // 0 none; PIPE_ACT_GELU fused in the epilogue; PIPE_ACT_SILU_GATED: the layer is gate||up and
                          // the tiled kernel writes h = SiLU(gate)*up, [M,T,out/2] (members kept apart)
+                         // PIPE_ACT_RELU; GELU and ReLU combine with `res`
+  const float* res = nullptr;   // a tensor added to the output, [res_members, T, out], or nullptr
+  int64_t res_mstride = 0;      // floats between its members
+  int res_members = 0;          // members that add it: M, or 1 (the first member only)
+  int res_pre_act = 1;          // 1: act(z + res); 0: act(z) + res
   float* y;
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)

@@ -62,13 +62,16 @@ class LayerSpec:
 class Workload:
     name: str
     config: int                      # 1..5, index into the benchmark's config list
-    kind: str                        # "linear" | "conv2d" | "mlp_gelu" | "mlp_gated"
+    kind: str                        # "linear" | "conv2d" | "mlp_gelu" | "mlp_gated" | "chain"
     layers: Tuple[LayerSpec, ...]
     tokens: int                      # T (conv: N*H_out*W_out)
     split: Tuple[int, ...]           # ensemble grouping [K_1..K_M]
     conv: Optional[Dict[str, int]] = None   # N,C,H,W,kh,kw,stride,pad
     w_dist: Dict[str, float] = field(default_factory=dict)
     x_dist: Dict[str, float] = field(default_factory=dict)
+    # kind "chain": per layer (activation "none" | "relu" | "gelu", skip_from, skip_pre_act);
+    # skip_from = -1 none, j = the tensor that entered layer j (0 = the network input)
+    chain: Optional[Tuple[Tuple[str, int, bool], ...]] = None
 
 
 C1 = Workload(
@@ -99,6 +102,28 @@ C5 = Workload(
     x_dist=dict(kind=0, outlier_frac=0.005, outlier_mul=20.0))
 
 WORKLOADS = {w.config: w for w in (C1, C2, C3, C4, C5)}
+
+
+def residual_stack(width: int, blocks: int, out_features: int, bits: int, K: int, gamma: float, group: int,
+                   tokens: int, split, name: str = "chain_residual_stack") -> Workload:
+    """A synthetic residual network as a chain of fully-connected layers, standing in for the
+    residual ConvNet of the paper's run-time table: a stem layer, `blocks` residual blocks of two
+    layers each (a1 = ReLU(W1 a), a2 = ReLU(W2 a1 + a)), and a linear head.  He-scaled normal
+    weights keep the activations of the stack O(1)."""
+    layers = [LayerSpec(width, width, bits, K, gamma, group)]
+    chain = [("relu", -1, True)]
+    for b in range(blocks):
+        first = len(layers)                       # the block's input is the tensor entering this layer
+        layers += [LayerSpec(width, width, bits, K, gamma, group)] * 2
+        chain += [("relu", -1, True), ("relu", first, True)]
+    layers.append(LayerSpec(out_features, width, bits, K, gamma, group))
+    chain.append(("none", -1, True))
+    return Workload(name=name, config=6, kind="chain", layers=tuple(layers), tokens=tokens, split=tuple(split),
+                    w_dist=dict(kind=0, std=float(np.sqrt(2.0 / width))), x_dist=dict(kind=0), chain=tuple(chain))
+
+
+# ResNet-like stack for the ensemble run-time comparison: ternary, K = 8, half the groups kept
+CHAIN = residual_stack(2048, 3, 1024, 2, 8, 0.5, 64, 4096, (4, 4))
 
 
 def with_tokens(w: Workload, tokens: int) -> Workload:

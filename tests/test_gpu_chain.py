@@ -1,0 +1,133 @@
+"""GPU parity of the L-layer member chains (App. B "Ensemble of more Layers", Fig. 2) against
+the CPU checker, layer by layer: each layer of the checker is fed the tensors the GPU produced
+for the previous layers, so both sides quantize identical values and every layer is held to the
+single-layer bar; the free-running end-to-end comparison allows for the few codes that a
+last-bit difference of an activation can flip."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pipe_oracle as po
+from paper_2311_15806_amd import workloads as wl
+
+from _parity import assert_close_fp32, assert_expansion_equal, dev, oracle_expand
+
+pytestmark = pytest.mark.gpu
+
+ACT = {"none": 0, "gelu": 1, "relu": 3}
+
+
+@pytest.fixture(scope="module")
+def pipe():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2311_15806_amd.binding as b
+    return b
+
+
+def _build(pipe, w, with_bias=True):
+    Ws = [wl.make_weight(w, l) for l in range(len(w.layers))]
+    bs = [wl.make_bias(w, l) if with_bias else None for l in range(len(w.layers))]
+    ora = [oracle_expand(W, s) for W, s in zip(Ws, w.layers)]
+    gpu = [pipe.pipe_expand(dev(W), s.bits, s.K, s.gamma, s.group) for W, s in zip(Ws, w.layers)]
+    for g, o in zip(gpu, ora):
+        assert_expansion_equal(g, o)
+    olayers = [po.ChainLayer(o, b, c[0], c[1], c[2]) for o, b, c in zip(ora, bs, w.chain)]
+    glayers = [(g, None if b is None else dev(b), ACT[c[0]], c[1], c[2]) for g, b, c in zip(gpu, bs, w.chain)]
+    return olayers, glayers, gpu
+
+
+def _check_chain(pipe, w, olayers, glayers, x, split, s_x=0.0):
+    L = len(olayers)
+    y, acts = pipe.pipe_chain_forward(glayers, dev(x), s_x=s_x, split=split, return_acts=True)
+    y = y.cpu().numpy()
+    acts = [a.cpu().numpy() for a in acts]
+    M = 1 if split is None else len(split)
+    # teacher-forced: layer l of the checker on the GPU's own earlier tensors
+    for l in range(L):
+        skips = po.chain_skips(olayers, l, x, acts, M)
+        if l == 0:
+            ref = po.chain_layer_members(olayers[0], x, True, skips, split, s_x if s_x > 0 else None)
+        else:
+            ref = po.chain_layer_members(olayers[l], acts[l - 1], False, skips, split)
+        if l < L - 1:
+            assert acts[l].shape == ref.shape
+            for m in range(M):
+                assert_close_fp32(acts[l][m], ref[m], tol=2e-5)
+        else:
+            assert_close_fp32(y, po.sum_members(ref))
+    # free-running
+    full = po.chain_forward(olayers, x, split=split, s_x=s_x if s_x > 0 else None)
+    assert_close_fp32(y, full["y"], tol=3e-2, elementwise=False)
+    return y
+
+
+@pytest.mark.parametrize("tokens", [150, 37, 9])
+@pytest.mark.parametrize("bits,K,split", [(4, 4, [2, 2]), (2, 4, [1, 1, 2]), (8, 2, None), (2, 8, [3, 3, 2])])
+def test_residual_stack_parity(pipe, bits, K, split, tokens):
+    w = wl.residual_stack(128, 2, 64, bits, K, 0.5, 16, tokens, split or (K,))
+    olayers, glayers, gpu = _build(pipe, w)
+    _check_chain(pipe, w, olayers, glayers, wl.make_input(w), split)
+    for g in gpu:
+        g.free()
+
+
+def test_chain_skip_variants_and_static_scale(pipe):
+    """Skip from the network input (first member only) before and after the activation, a skip on
+    the last layer, GELU inside the chain, ragged widths, and a static input scale."""
+    spec = lambda o, i: wl.LayerSpec(o, i, 4, 4, 0.5, 16)
+    layers = (spec(112, 112), spec(112, 112), spec(80, 112), spec(80, 80))
+    chain = (("relu", 0, False), ("gelu", 0, True), ("none", -1, True), ("none", 3, True))
+    w = wl.Workload(name="chain_variants", config=6, kind="chain", layers=layers, tokens=70, split=(2, 1, 1),
+                    w_dist=dict(kind=0, std=0.13), x_dist=dict(kind=0), chain=chain)
+    olayers, glayers, gpu = _build(pipe, w)
+    x = wl.make_input(w)
+    for kernel in (0, 1):
+        pipe.pipe_set_kernel(kernel)
+        try:
+            _check_chain(pipe, w, olayers, glayers, x, [2, 1, 1])
+            _check_chain(pipe, w, olayers, glayers, x, None, s_x=0.03)
+        finally:
+            pipe.pipe_set_kernel(0)
+    for g in gpu:
+        g.free()
+
+
+def test_chain_of_one_and_two_layers_matches_the_other_entry_points(pipe):
+    """L = 1 is pipe_forward, L = 2 with GELU is pipe_mlp_forward: bit-identical outputs."""
+    w = wl.scaled(wl.C3, out_div=8, in_div=8, tokens=100)
+    l1, l2 = w.layers
+    W1, W2, x = wl.make_weight(w, 0), wl.make_weight(w, 1), wl.make_input(w)
+    b1, b2 = wl.make_bias(w, 0), wl.make_bias(w, 1)
+    g1 = pipe.pipe_expand(dev(W1), l1.bits, l1.K, l1.gamma, l1.group)
+    g2 = pipe.pipe_expand(dev(W2), l2.bits, l2.K, l2.gamma, l2.group)
+    xd = dev(x)
+    for split in (None, [2, 1]):
+        y1 = pipe.pipe_forward(g1, xd, split=split, bias=dev(b1))
+        c1 = pipe.pipe_chain_forward([(g1, dev(b1), 0, -1, True)], xd, split=split)
+        assert np.array_equal(y1.cpu().numpy(), c1.cpu().numpy())
+        y2 = pipe.pipe_mlp_forward(g1, g2, pipe.PIPE_ACT_GELU, xd, split=split, bias1=dev(b1), bias2=dev(b2))
+        c2 = pipe.pipe_chain_forward([(g1, dev(b1), 1, -1, True), (g2, dev(b2), 0, -1, True)], xd, split=split)
+        assert np.array_equal(y2.cpu().numpy(), c2.cpu().numpy())
+    g1.free(); g2.free()
+
+
+def test_chain_argument_errors(pipe):
+    w = wl.residual_stack(64, 1, 32, 4, 2, 1.0, 16, 8, (2,))
+    _, glayers, gpu = _build(pipe, w, with_bias=False)
+    x = dev(wl.make_input(w))
+    bad_last = list(glayers)
+    bad_last[-1] = (bad_last[-1][0], None, 3, -1, True)          # activation on the last layer
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward(bad_last, x)
+    bad_skip = list(glayers)
+    bad_skip[1] = (bad_skip[1][0], None, 3, 2, True)             # a skip cannot read a later tensor
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward(bad_skip, x)
+    bad_width = list(glayers)
+    bad_width[-1] = (bad_width[-1][0], None, 0, 0, True)         # 32 outputs, skip tensor 64 wide
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward(bad_width, x)
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward(glayers[:2] + glayers[3:], x, split=[1, 2])   # split does not sum to K
+    for g in gpu:
+        g.free()
