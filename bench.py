@@ -44,7 +44,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4",
-                    help="c4 (LLM-7B linear, ternary K=4) | c5 (gated MLP, int4 K=4) | c3 | c2 | c1")
+                    help="c4 (LLM-7B linear, ternary K=4) | c5 (gated MLP, int4 K=4) | c3 | c2 | c1 | "
+                         "chain (residual stack of 8 layers, ternary K=8, as member chains)")
     ap.add_argument("--tokens", type=int, default=0, help="override the headline token count")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -87,7 +88,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "calibrate_copy_bytes_written": a.numel() * 4}))
         return
 
-    cfg = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}[args.workload]
+    cfg = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "chain": wl.CHAIN}[args.workload]
     T_head = args.tokens or cfg.tokens
 
     # ---- build the expansion(s) once (offline step a0) ------------------------------------
@@ -110,7 +111,12 @@ def main():
     xd_full = torch.from_numpy(x_full).to(dev)
     split = list(cfg.split) if len(cfg.split) > 1 else None
 
-    def step_fn(e, xd, out=None):
+    chain_act = {"none": pipe.PIPE_ACT_NONE, "relu": pipe.PIPE_ACT_RELU, "gelu": pipe.PIPE_ACT_GELU}
+
+    def step_fn(e, xd, out=None, split=split):
+        if cfg.kind == "chain":
+            layers = [(e[i], None, chain_act[c[0]], c[1], c[2]) for i, c in enumerate(cfg.chain)]
+            return pipe.pipe_chain_forward(layers, xd, split=split, out=out)
         if cfg.kind == "linear":
             return pipe.pipe_forward(e[0], xd, split=split, out=out)
         if cfg.kind == "conv2d":
@@ -128,6 +134,8 @@ def main():
             last = i == len(cfg.layers) - 1
             b += T * l.in_features * (1 if i == 0 else M)
             b += 4 * T * l.out_features * (1 if last else M)
+            if cfg.chain is not None and cfg.chain[i][1] >= 0:     # the skip tensor is read once more
+                b += 4 * T * l.out_features * (1 if cfg.chain[i][1] == 0 else M)
         return b
 
     def measure(T, steps, warmup, rotate):
@@ -207,7 +215,7 @@ def main():
     roofline["algorithmic_bytes"] = head["alg_bytes"]
 
     sweep = []
-    if not args.no_sweep and cfg.kind != "conv2d":
+    if not args.no_sweep and cfg.kind not in ("conv2d", "chain"):
         for T in (1, 16, 64, 256, 2048, 4096):
             if T == T0:
                 r = dict(head)
@@ -222,6 +230,39 @@ def main():
             r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
             r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
             sweep.append({k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()})
+
+    # ---- the run-time comparison of the ensembles (a chain workload only): the same network and
+    # the same K under the groupings of the paper's run-time table, and the unexpanded K = 1 net
+    ensemble_ms = None
+    if cfg.kind == "chain" and not args.no_sweep:
+        ensemble_ms = {}
+        xd = xd_full[:T0].contiguous()
+        out_t = torch.empty((T0, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
+        K = cfg.layers[0].K
+
+        def timed(e, sp):
+            for _ in range(3):
+                step_fn(e, xd, out_t, split=sp)
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            for _ in range(max(10, args.steps // 2)):
+                step_fn(e, xd, out_t, split=sp)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - ta) * 1e3 / max(10, args.steps // 2)
+
+        groupings = [[K]]
+        if K % 2 == 0:
+            groupings.append([K // 2] * 2)
+        if K >= 3:
+            groupings.append([-(-K // 3)] * (K % 3 or 3) + [K // 3] * (3 - (K % 3 or 3)) if K % 3 else [K // 3] * 3)
+        if K % 4 == 0:
+            groupings.append([K // 4] * 4)
+        for sp in groupings:
+            ensemble_ms[str(sp)] = round(timed(exps[0], sp if len(sp) > 1 else None), 4)
+        e1 = [pipe.pipe_expand(Ws[i], l.bits, 1, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
+        ensemble_ms["[1] (K = 1, no expansion)"] = round(timed(e1, None), 4)
+        for e in e1:
+            e.free()
 
     # ---- CPU checker on a bounded sample of the same workload ------------------------------
     cpu = None
@@ -248,6 +289,21 @@ def main():
             macs = passes * po.expansion_macs(ex, T_s)
             sample = ("%d passes of forward (quantize, contract, de-quantize) over all %d output channels and "
                       "%d tokens; expansion built outside the timer" % (passes, O_s, T_s))
+        elif cfg.kind == "chain":
+            l0 = cfg.layers[0]
+            small = wl.residual_stack(l0.out_features // 4, (len(cfg.layers) - 2) // 2, cfg.layers[-1].out_features // 4,
+                                      l0.bits, l0.K, l0.gamma, l0.group, 512, cfg.split, name=cfg.name + "_small")
+            exs = [po.expand(wl.make_weight(small, i), l.bits, l.K, l.gamma, l.group) for i, l in enumerate(small.layers)]
+            layers_o = [po.ChainLayer(e, None, c[0], c[1], c[2]) for e, c in zip(exs, small.chain)]
+            xs = wl.make_input(small)
+            passes, dt = 0, 0.0
+            while dt < 10.0 and passes < 64:
+                tc = time.perf_counter()
+                po.chain_forward(layers_o, xs, split=split)
+                dt += time.perf_counter() - tc
+                passes += 1
+            macs = passes * sum(po.expansion_macs(e, small.tokens) for e in exs)
+            sample = "%d passes over the reduced copy %s, %d tokens" % (passes, small.name, small.tokens)
         else:
             small = wl.scaled(cfg, out_div=2, in_div=1, tokens=512) if cfg.kind != "conv2d" else cfg
             Wsm = [wl.make_weight(small, i) for i in range(len(small.layers))]
@@ -289,6 +345,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "sweep": sweep,
+        "ensemble_ms_per_step": ensemble_ms,
         # reference rates of this chip (not targets): MFMA-only loop with constant operands, with
         # ternary codes x random int8 (what C4 feeds the pipe), with random int8 x int8; plain
         # streaming read of 2 GiB with the weight-streaming kernel's access pattern

@@ -112,12 +112,11 @@ static void free_expansion(pipe_expansion* e) {
     if (o.packed_dev) (void)hipFree(o.packed_dev);
     if (o.pos_dev) (void)hipFree(o.pos_dev);
   }
-  if (e->ct_rb_out_dev) (void)hipFree(e->ct_rb_out_dev);
-  if (e->ct_src_dev) (void)hipFree(e->ct_src_dev);
-  if (e->ct_mask_dev) (void)hipFree(e->ct_mask_dev);
-  if (e->gt_rb_out_dev) (void)hipFree(e->gt_rb_out_dev);
-  if (e->gt_src_dev) (void)hipFree(e->gt_src_dev);
-  if (e->gt_mask_dev) (void)hipFree(e->gt_mask_dev);
+  for (auto& t : e->tables) {
+    if (t.rb_out_dev) (void)hipFree(t.rb_out_dev);
+    if (t.src_dev) (void)hipFree(t.src_dev);
+    if (t.cnt_dev) (void)hipFree(t.cnt_dev);
+  }
   if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->codes_dev) (void)hipFree(e->codes_dev);
   if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
@@ -126,8 +125,8 @@ static void free_expansion(pipe_expansion* e) {
   delete e;
 }
 
-// Sort row blocks by the set of orders that hold them (most orders first) and cut the sorted
-// list into column tiles of NRB_TILE row blocks.
+// Sort row blocks by the set of orders that hold them (most orders first) and pack them into the
+// bins of the weight-streaming kernel; a stored row block's bin and place fix its position.
 static int build_schedule(pipe_expansion* e, hipStream_t st) {
   const int K = e->K, n_rb = e->n_rb, rbpg = e->rbpg;
   std::vector<std::vector<int32_t>> slot_of(K, std::vector<int32_t>(e->n_groups, -1));
@@ -184,77 +183,12 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
   PIPE_HIP(hipMalloc(&e->bins_dev, bins.size() * sizeof(StreamBin)));
   PIPE_HIP(hipMemcpy(e->bins_dev, bins.data(), bins.size() * sizeof(StreamBin), hipMemcpyHostToDevice));
 
-  // Tile schedule of the tiled kernel over the same sorted row blocks.
-  e->n_ct = ceil_div(n_rb, NRB_TILE);
-  e->n_sorted = (int)round_up64(n_rb, 64);
-  std::vector<int32_t> rb_out((size_t)e->n_sorted, -1);
-  std::vector<int32_t> src((size_t)K * e->n_sorted, -1);
-  for (int i = 0; i < n_rb; ++i) {
-    const int rb = items[i].rb;
+  // where each output row block's stored orders sit: what the tiled kernel's schedules are built from
+  e->pos_of.assign((size_t)K * n_rb, -1);
+  for (int rb = 0; rb < n_rb; ++rb) {
     const int g = rb / rbpg, b = rb % rbpg;
-    rb_out[i] = rb;
     for (int k = 0; k < K; ++k)
-      if (slot_of[k][g] >= 0) src[(size_t)k * e->n_sorted + i] = e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b];
-  }
-  std::vector<uint32_t> ct_mask((size_t)e->n_ct, 0u);
-  for (int i = 0; i < n_rb; ++i) ct_mask[i / NRB_TILE] |= items[i].mask;
-  PIPE_HIP(hipMalloc(&e->ct_mask_dev, ct_mask.size() * 4));
-  PIPE_HIP(hipMemcpy(e->ct_mask_dev, ct_mask.data(), ct_mask.size() * 4, hipMemcpyHostToDevice));
-  PIPE_HIP(hipMalloc(&e->ct_rb_out_dev, rb_out.size() * 4));
-  PIPE_HIP(hipMalloc(&e->ct_src_dev, src.size() * 4));
-  PIPE_HIP(hipMemcpy(e->ct_rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice));
-  PIPE_HIP(hipMemcpy(e->ct_src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice));
-
-  // The pair schedule of a gate||up layer (see pipe_internal.h).
-  if (n_rb % 2 == 0) {
-    const int n_pairs = n_rb / 2;
-    struct Pair { uint32_t mg, mu; int pop; int i; };
-    std::vector<Pair> pairs(n_pairs);
-    auto mask_of = [&](int rb) {
-      uint32_t mask = 0;
-      for (int k = 0; k < K; ++k)
-        if (slot_of[k][rb / rbpg] >= 0) mask |= 1u << k;
-      return mask;
-    };
-    for (int i = 0; i < n_pairs; ++i) {
-      const uint32_t mg = mask_of(i), mu = mask_of(i + n_pairs);
-      pairs[i] = Pair{mg, mu, __builtin_popcount(mg) + __builtin_popcount(mu), i};
-    }
-    // a tile runs the union of its blocks' order sets: tiles of one union first of all
-    std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) {
-      const uint32_t ux = x.mg | x.mu, uy = y.mg | y.mu;
-      if (ux != uy) return __builtin_popcount(ux) != __builtin_popcount(uy) ? __builtin_popcount(ux) > __builtin_popcount(uy) : ux < uy;
-      if (x.pop != y.pop) return x.pop > y.pop;
-      if (x.mg != y.mg) return x.mg < y.mg;
-      if (x.mu != y.mu) return x.mu < y.mu;
-      return x.i < y.i;
-    });
-    e->n_ct_gated = ceil_div(n_pairs, 8);
-    e->n_sorted_gated = (int)round_up64((int64_t)e->n_ct_gated * 16, 64);
-    std::vector<int32_t> g_out((size_t)e->n_sorted_gated, -1);
-    std::vector<int32_t> g_src((size_t)K * e->n_sorted_gated, -1);
-    std::vector<uint32_t> g_mask((size_t)e->n_ct_gated, 0u);
-    for (int j = 0; j < n_pairs; ++j) {
-      const int t = j / 8, q = j % 8, i = pairs[j].i;
-      const int pos_g = t * 16 + q, pos_u = t * 16 + 8 + q;
-      g_out[pos_g] = i;
-      g_out[pos_u] = i;
-      g_mask[t] |= pairs[j].mg | pairs[j].mu;
-      for (int k = 0; k < K; ++k) {
-        const int rbs[2] = {i, i + n_pairs};
-        const int poss[2] = {pos_g, pos_u};
-        for (int h = 0; h < 2; ++h) {
-          const int g = rbs[h] / rbpg, b = rbs[h] % rbpg;
-          if (slot_of[k][g] >= 0) g_src[(size_t)k * e->n_sorted_gated + poss[h]] = e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b];
-        }
-      }
-    }
-    PIPE_HIP(hipMalloc(&e->gt_rb_out_dev, g_out.size() * 4));
-    PIPE_HIP(hipMalloc(&e->gt_src_dev, g_src.size() * 4));
-    PIPE_HIP(hipMalloc(&e->gt_mask_dev, g_mask.size() * 4));
-    PIPE_HIP(hipMemcpy(e->gt_rb_out_dev, g_out.data(), g_out.size() * 4, hipMemcpyHostToDevice));
-    PIPE_HIP(hipMemcpy(e->gt_src_dev, g_src.data(), g_src.size() * 4, hipMemcpyHostToDevice));
-    PIPE_HIP(hipMemcpy(e->gt_mask_dev, g_mask.data(), g_mask.size() * 4, hipMemcpyHostToDevice));
+      if (slot_of[k][g] >= 0) e->pos_of[(size_t)k * n_rb + rb] = e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b];
   }
 
   // Move the stored row blocks to their positions and drop the per-order buffers.
@@ -412,6 +346,102 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
     if (rc) return rc;
   }
   return PIPE_OK;
+}
+
+// ------------------------------------------------------------------ tile schedules
+const PassTables* pipe_get_tables(const pipe_expansion* ce, const GemmArgs& a, int kind, int* rc_out) {
+  pipe_expansion* e = const_cast<pipe_expansion*>(ce);
+  const int K = e->K, n_rb = e->n_rb;
+  int M = a.M;
+  int member_of[PIPE_MAX_K] = {0};
+  unsigned long long nib = 0;
+  if (kind == 2) {
+    M = 1;
+  } else {
+    for (int m = 0; m < a.M; ++m)
+      for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) { member_of[k] = m; nib |= (unsigned long long)m << (4 * k); }
+  }
+  for (const PassTables& t : e->tables)
+    if (t.kind == kind && t.M == M && t.member_nib == nib) return &t;
+  *rc_out = PIPE_OK;
+  if (kind == 1 && n_rb % 2 != 0) { *rc_out = PIPE_ESHAPE; return nullptr; }
+
+  // per row block and member: the positions of its stored orders, ascending
+  std::vector<std::vector<int32_t>> list((size_t)n_rb * M);
+  for (int rb = 0; rb < n_rb; ++rb)
+    for (int k = 0; k < K; ++k) {
+      const int32_t pos = e->pos_of[(size_t)k * n_rb + rb];
+      if (kind == 2) list[rb].push_back(pos);
+      else if (pos >= 0) list[(size_t)rb * M + member_of[k]].push_back(pos);
+    }
+  auto cnt = [&](int rb, int m) { return (int)list[(size_t)rb * M + m].size(); };
+  // units that must share a tile: row blocks, or (gate, up) pairs
+  const int n_units = kind == 1 ? n_rb / 2 : n_rb, per_tile = kind == 1 ? 8 : 16;
+  auto ucnt = [&](int u, int m) { return kind == 1 ? std::max(cnt(u, m), cnt(u + n_units, m)) : cnt(u, m); };
+  std::vector<int> units(n_units);
+  for (int u = 0; u < n_units; ++u) units[u] = u;
+  std::stable_sort(units.begin(), units.end(), [&](int x, int y) {
+    for (int m = 0; m < M; ++m)
+      if (ucnt(x, m) != ucnt(y, m)) return ucnt(x, m) > ucnt(y, m);
+    if (kind == 1) {
+      int tx = 0, ty = 0;
+      for (int m = 0; m < M; ++m) { tx += cnt(x, m) + cnt(x + n_units, m); ty += cnt(y, m) + cnt(y + n_units, m); }
+      if (tx != ty) return tx > ty;
+    }
+    return x < y;
+  });
+  PassTables t;
+  t.member_nib = nib; t.M = M; t.kind = kind;
+  t.n_ct = ceil_div(n_units, per_tile);
+  t.n_sorted = (int)round_up64((int64_t)t.n_ct * 16, 64);
+  // passes per (tile, member); heaviest tiles first
+  std::vector<int> tile_of(t.n_ct);
+  std::vector<std::vector<int>> passes(t.n_ct, std::vector<int>(M, 0));
+  std::vector<int> total(t.n_ct, 0);
+  for (int i = 0; i < n_units; ++i)
+    for (int m = 0; m < M; ++m) passes[i / per_tile][m] = std::max(passes[i / per_tile][m], ucnt(units[i], m));
+  for (int c = 0; c < t.n_ct; ++c) {
+    tile_of[c] = c;
+    for (int m = 0; m < M; ++m) { total[c] += passes[c][m]; t.p_max = std::max(t.p_max, passes[c][m]); }
+  }
+  std::stable_sort(tile_of.begin(), tile_of.end(), [&](int x, int y) { return total[x] > total[y]; });
+  if (t.p_max > 255 || M > 16) { *rc_out = PIPE_EINVAL; return nullptr; }
+  t.p_max = std::max(t.p_max, 1);
+  std::vector<int32_t> rb_out((size_t)t.n_sorted, -1);
+  std::vector<int32_t> src((size_t)M * t.p_max * t.n_sorted, -1);
+  std::vector<uint8_t> cnts((size_t)t.n_ct * 16, 0);
+  for (int c = 0; c < t.n_ct; ++c) {
+    const int from = tile_of[c];
+    for (int m = 0; m < M; ++m) cnts[(size_t)c * 16 + m] = (uint8_t)passes[from][m];
+    for (int q = 0; q < per_tile && from * per_tile + q < n_units; ++q) {
+      const int u = units[from * per_tile + q];
+      const int rbs[2] = {u, u + n_units}, poss[2] = {c * 16 + q, c * 16 + 8 + q};
+      for (int hh = 0; hh < (kind == 1 ? 2 : 1); ++hh) {
+        rb_out[poss[hh]] = u;   // a pair stores to the gate block's channels
+        for (int m = 0; m < M; ++m) {
+          const std::vector<int32_t>& l = list[(size_t)rbs[hh] * M + m];
+          for (size_t j = 0; j < l.size(); ++j) src[((size_t)m * t.p_max + j) * t.n_sorted + poss[hh]] = l[j];
+        }
+      }
+    }
+  }
+  auto fail = [&](hipError_t he, const char* what) {
+    pipe_note_hip_error(he, what);
+    if (t.rb_out_dev) (void)hipFree(t.rb_out_dev);
+    if (t.src_dev) (void)hipFree(t.src_dev);
+    if (t.cnt_dev) (void)hipFree(t.cnt_dev);
+    *rc_out = PIPE_EDEVICE;
+    return (const PassTables*)nullptr;
+  };
+  hipError_t he;
+  if ((he = hipMalloc(&t.rb_out_dev, rb_out.size() * 4)) != hipSuccess) return fail(he, "hipMalloc(rb_out)");
+  if ((he = hipMalloc(&t.src_dev, src.size() * 4)) != hipSuccess) return fail(he, "hipMalloc(src)");
+  if ((he = hipMalloc(&t.cnt_dev, cnts.size())) != hipSuccess) return fail(he, "hipMalloc(cnt)");
+  if ((he = hipMemcpy(t.rb_out_dev, rb_out.data(), rb_out.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(he, "hipMemcpy(rb_out)");
+  if ((he = hipMemcpy(t.src_dev, src.data(), src.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail(he, "hipMemcpy(src)");
+  if ((he = hipMemcpy(t.cnt_dev, cnts.data(), cnts.size(), hipMemcpyHostToDevice)) != hipSuccess) return fail(he, "hipMemcpy(cnt)");
+  e->tables.push_back(t);
+  return &e->tables.back();
 }
 
 // ------------------------------------------------------------------ forward
@@ -640,7 +670,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
-  } else if (!small && l1->gt_src_dev != nullptr) {
+  } else if (!small && l1->n_rb % 2 == 0) {
     // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly
     a.act = PIPE_ACT_SILU_GATED; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);

@@ -39,9 +39,10 @@ struct TiledParams {
   const uint8_t* codes;           // stored row blocks of all orders, schedule order
   const float* scales;            // their row scales, 16 per position
   const int32_t* rb_out;          // [n_sorted] output row block of sorted position i, or -1
-  const int32_t* rb_src;          // [K][n_sorted] position of the row block of order k, or -1
-  const uint32_t* ct_mask;        // [n_ct] orders present in the column tile
+  const int32_t* rb_src;          // [M][p_max][n_sorted] position of the row block's j-th stored order of member m, or -1
+  const uint8_t* ct_cnt;          // [n_ct][16] passes member m runs in the column tile
   int n_sorted;                   // padded to a multiple of 64
+  int p_max;
   const float* bias;
   float* y;
   int32_t* acc_out;
@@ -54,7 +55,6 @@ struct TiledParams {
   int res_members, res_pre_act;
   int hidden;                     // MODE_GATED: H; the layer's rows are gate [0,H) and up [H,2H), y is [M,T,H]
   int n_st_t;                     // super-tiles along tokens
-  unsigned long long member_nib;  // member of order k in bits [4k, 4k+4)
 };
 
 __device__ __forceinline__ float gelu_erf(float a) {
@@ -195,11 +195,11 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     }
   };
   xload(p.qx, 0, 0);   // member 0 owns order 1, which every tile holds
-  // tile_mask: orders that hold at least one row block of this column tile; rb_out: output row
-  // blocks of this wave's NRW sorted positions.  Scalar loads; member 0's activation scale and
-  // code sums (vector loads) travel at the same time.
+  // tile_cnt: passes each member runs in this column tile (one byte per member); rb_out: output
+  // row blocks of this wave's NRW sorted positions.  Scalar loads; member 0's activation scale
+  // and code sums (vector loads) travel at the same time.
   static_assert(NRW == 4, "descriptor loads are 4 wide");
-  const unsigned tile_mask = cload(p.ct_mask, (size_t)ct);
+  const v4i tile_cnt = cload(reinterpret_cast<const v4i*>(p.ct_cnt), (size_t)ct);
   const v4i rb_out4 = cload(reinterpret_cast<const v4i*>(p.rb_out), (size_t)(ct * NRB_WG + wave * NRW) / 4);
   const int rb_out[NRW] = {rb_out4[0], rb_out4[1], rb_out4[2], rb_out4[3]};
   float sx = p.s_x[0];
@@ -227,12 +227,15 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
     }
 
-    for (int k = 0; k < p.K; ++k) {
-      if ((int)((p.member_nib >> (4 * k)) & 15ull) != m) continue;
-      if (!((tile_mask >> k) & 1u)) continue;   // uniform over the workgroup
+    // In pass j every row block of the tile contributes its j-th stored order of this member (all
+    // of a member's orders multiply the same Q(x)); the tile runs as many passes as its fullest
+    // row block has orders.  Uniform over the workgroup.
+    const int cnt_word = m < 4 ? tile_cnt[0] : (m < 8 ? tile_cnt[1] : (m < 12 ? tile_cnt[2] : tile_cnt[3]));
+    const int n_pass = (cnt_word >> (8 * (m & 3))) & 255;
+    for (int k = 0; k < n_pass; ++k) {
       const uint8_t* pk = p.codes;
       const float* sck = p.scales;
-      const v4i src4 = cload(reinterpret_cast<const v4i*>(p.rb_src), ((size_t)k * p.n_sorted + ct * NRB_WG + wave * NRW) / 4);
+      const v4i src4 = cload(reinterpret_cast<const v4i*>(p.rb_src), ((size_t)(m * p.p_max + k) * p.n_sorted + ct * NRB_WG + wave * NRW) / 4);
       const int src[NRW] = {src4[0], src4[1], src4[2], src4[3]};
       const uint8_t* wb[NRW];
       bool active = false;
@@ -518,29 +521,29 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
-  p.rb_out = e->ct_rb_out_dev; p.rb_src = e->ct_src_dev; p.ct_mask = e->ct_mask_dev; p.n_sorted = e->n_sorted;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
-  p.n_ct = e->n_ct; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
+  p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.hidden = 0;
   p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act;
   if (a.res != nullptr && (a.acc_out != nullptr || a.act == PIPE_ACT_SILU_GATED || a.res_members < 1 || a.res_members > a.M))
     return PIPE_EINVAL;
   if (a.act == PIPE_ACT_SILU_GATED) {
     // gate||up layer: the pair schedule; the output is the hidden activation, H wide, members apart
-    if (e->gt_src_dev == nullptr || a.reduce || a.acc_out != nullptr) return PIPE_EINVAL;
-    p.rb_out = e->gt_rb_out_dev; p.rb_src = e->gt_src_dev; p.ct_mask = e->gt_mask_dev; p.n_sorted = e->n_sorted_gated;
-    p.n_ct = e->n_ct_gated;
+    if (a.reduce || a.acc_out != nullptr) return PIPE_EINVAL;
     p.hidden = e->out / 2;
     p.out = e->out / 2;
   }
-  p.member_nib = 0;
-  for (int m = 0; m < a.M; ++m)
-    for (int k = a.member_lo[m]; k <= a.member_hi[m]; ++k) p.member_nib |= (unsigned long long)m << (4 * k);
   const bool acc_out = a.acc_out != nullptr;
+  if (acc_out && a.M != 1) return PIPE_EINVAL;   // the integer export writes pass j as order j
+  int rc = PIPE_OK;
+  const PassTables* tb = pipe_get_tables(e, a, acc_out ? 2 : (a.act == PIPE_ACT_SILU_GATED ? 1 : 0), &rc);
+  if (tb == nullptr) return rc;
+  p.rb_out = tb->rb_out_dev; p.rb_src = tb->src_dev; p.ct_cnt = tb->cnt_dev; p.n_sorted = tb->n_sorted;
+  p.p_max = tb->p_max; p.n_ct = tb->n_ct;
   // Token-tile height: 64 tokens per workgroup when that still gives every CU several tiles,
   // else 32 or 16 (more, smaller tiles; the packed codes are then re-read from L2 more often).
-  const int n_ct = ceil_div(e->n_ct * NRB_TILE, 16);
+  const int n_ct = p.n_ct;
   int mtb = g_tiled_mtb;
   if (mtb != 1 && mtb != 2 && mtb != 4) {
     mtb = 4;

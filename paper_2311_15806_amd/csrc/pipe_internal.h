@@ -63,6 +63,37 @@ struct PipeOrder {
   std::vector<int32_t> pos;     // host copy
 };
 
+// Tile schedule of the tiled kernel for one grouping of the orders into members.
+//
+// All orders of a member multiply the same Q(x), so within a member a wave may take its row
+// blocks' stored orders in any grouping: in pass j each row block contributes its j-th stored
+// order of the member (ascending, so every output row is still summed in order k = 1..K).  A
+// column tile of 16 row blocks then runs max(count) passes per member instead of one pass per
+// order present anywhere in the tile: tiles need row blocks with equal order COUNTS per member,
+// not equal order sets, and sorting by count vector gets close to that even for few groups and
+// many orders.
+//   kind 0: row blocks sorted by count vector.
+//   kind 1: a gate||up layer (out = 2H, rows [0,H) gate, [H,2H) up): a tile is 8 (gate block i,
+//           up block i) pairs -- sorted positions 16t..16t+7 the gate blocks, 16t+8..16t+15
+//           their up blocks -- so a workgroup holds both halves of SiLU(gate)*up; rb_out is the
+//           gate block (= block of the hidden channel) for both.
+//   kind 2: one pass per order, pruned or not (pass j = order j): the integer export.
+struct PassTables {
+  unsigned long long member_nib = 0;   // member of order k in bits [4k, 4k+4)
+  int M = 0, kind = 0;
+  int n_ct = 0;                        // column tiles
+  int n_sorted = 0;                    // 16 * n_ct rounded up to a multiple of 64
+  int p_max = 0;                       // most passes any (tile, member) runs
+  int32_t* rb_out_dev = nullptr;       // [n_sorted] output row block of sorted position i, or -1
+  int32_t* src_dev = nullptr;          // [M][p_max][n_sorted] position of the row block's j-th stored order, or -1
+  uint8_t* cnt_dev = nullptr;          // [n_ct][16] passes of member m in tile t
+};
+struct pipe_expansion;
+struct GemmArgs;
+// The tables for the members of `a` (built and uploaded on first use: allocates and copies
+// synchronously); nullptr with *rc set on failure.  Not thread safe per expansion.
+const PassTables* pipe_get_tables(const pipe_expansion* e, const GemmArgs& a, int kind, int* rc);
+
 struct pipe_expansion {
   int out = 0, in = 0, bits = 0, K = 0, group = 0;
   float gamma = 1.f;
@@ -73,24 +104,13 @@ struct pipe_expansion {
   int nks = 0;        // in_pad/64
   int device = 0;
   std::vector<PipeOrder> orders;
-  // Tile schedule.  Row blocks are sorted by the set of orders that hold them so that the
-  // NRB_TILE row blocks of a column tile do the same work.
-  int n_ct = 0;                     // column tiles of NRB_TILE row blocks
-  int n_sorted = 0;                 // sorted row-block list length, padded to a multiple of 64
-  int32_t* ct_rb_out_dev = nullptr; // [n_sorted] output row block (channel/16) or -1
-  int32_t* ct_src_dev = nullptr;    // [K][n_sorted] position (in codes_dev) of the row block in order k, or -1
-  uint32_t* ct_mask_dev = nullptr;  // [n_ct] orders (bit k) that hold at least one row block of the column tile
-  // The same three tables for a layer used as gate||up of a gated MLP (out = 2H, rows [0,H) gate,
-  // [H,2H) up): row blocks are sorted as (gate block i, up block i) pairs, and a column tile is 8
-  // pairs -- sorted positions 16t..16t+7 the gate blocks, 16t+8..16t+15 their up blocks -- so that
-  // a workgroup holds both halves of SiLU(gate)*up.  Built when H is a multiple of 16.
-  int n_ct_gated = 0, n_sorted_gated = 0;
-  int32_t* gt_rb_out_dev = nullptr;  // [n_sorted_gated] gate row block (= block of the hidden channel), or -1
-  int32_t* gt_src_dev = nullptr;     // [K][n_sorted_gated]
-  uint32_t* gt_mask_dev = nullptr;   // [n_ct_gated]
+  // Tile schedules of the tiled kernel (PassTables below): built on first use for each grouping
+  // of the orders into members, kept until the expansion is freed.
+  std::vector<int32_t> pos_of;       // [K][n_rb] position (in codes_dev) of output row block rb at order k, or -1
+  std::vector<PassTables> tables;
   // Stored row blocks of all orders in schedule order: bin b of the weight-streaming kernel owns
   // positions [b*bin_cap, (b+1)*bin_cap), so that kernel addresses its codes from its block index
-  // alone; the tiled kernel reaches them through ct_src_dev.  Unused positions are zero.
+  // alone; the tiled kernel reaches them through its pass tables.  Unused positions are zero.
   uint8_t* codes_dev = nullptr;       // [n_bins*bin_cap][in_pad/KSUP][1 KiB]
   float* scales_all_dev = nullptr;    // [n_bins*bin_cap][16]
   int n_bins = 0, bin_cap = 0;
