@@ -244,11 +244,17 @@ def main():
             for _ in range(3):
                 step_fn(e, xd, out_t, split=sp)
             torch.cuda.synchronize()
+            n_it = max(10, args.steps // 2)
+            pipe.pipe_timing_read()
+            pipe.pipe_timing_enable(True)
             ta = time.perf_counter()
-            for _ in range(max(10, args.steps // 2)):
+            for _ in range(n_it):
                 step_fn(e, xd, out_t, split=sp)
             torch.cuda.synchronize()
-            return (time.perf_counter() - ta) * 1e3 / max(10, args.steps // 2)
+            tb = time.perf_counter()
+            pipe.pipe_timing_enable(False)
+            k_ms, _ = pipe.pipe_timing_read()
+            return {"ms_per_step": round((tb - ta) * 1e3 / n_it, 4), "contraction_ms_per_step": round(k_ms / n_it, 4)}
 
         groupings = [[K]]
         if K % 2 == 0:
@@ -258,9 +264,9 @@ def main():
         if K % 4 == 0:
             groupings.append([K // 4] * 4)
         for sp in groupings:
-            ensemble_ms[str(sp)] = round(timed(exps[0], sp if len(sp) > 1 else None), 4)
+            ensemble_ms[str(sp)] = timed(exps[0], sp if len(sp) > 1 else None)
         e1 = [pipe.pipe_expand(Ws[i], l.bits, 1, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
-        ensemble_ms["[1] (K = 1, no expansion)"] = round(timed(e1, None), 4)
+        ensemble_ms["[1] (K = 1, no expansion)"] = timed(e1, None)
         for e in e1:
             e.free()
 

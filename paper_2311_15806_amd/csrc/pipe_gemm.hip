@@ -483,7 +483,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     if (p.amax_out != nullptr) {
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
+      if (lane == 0) amax_raise(&p.amax_out[m], mx);
     }
   }  // members
 }
@@ -541,14 +541,20 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   if (tb == nullptr) return rc;
   p.rb_out = tb->rb_out_dev; p.rb_src = tb->src_dev; p.ct_cnt = tb->cnt_dev; p.n_sorted = tb->n_sorted;
   p.p_max = tb->p_max; p.n_ct = tb->n_ct;
-  // Token-tile height: 64 tokens per workgroup when that still gives every CU several tiles,
-  // else 32 or 16 (more, smaller tiles; the packed codes are then re-read from L2 more often).
+  // Token-tile height: the tallest of 64, 32, 16 tokens that still gives at least 1024 tiles (two
+  // rounds of the 512 workgroups the chip holds), or whose tiles fill whole rounds (the last one
+  // at least 7/8 full): taller tiles re-read the packed codes from L2 less often, but a round
+  // that leaves compute units idle costs more than that (measured on the 11008 x 4096 ternary
+  // layer, 192 to 3072 tokens, and on 2048 x 2048 layers at 4096 tokens).
   const int n_ct = p.n_ct;
   int mtb = g_tiled_mtb;
   if (mtb != 1 && mtb != 2 && mtb != 4) {
-    mtb = 4;
-    if ((int64_t)n_ct * ceil_div(a.T, 64) < 1024) mtb = 2;
-    if ((int64_t)n_ct * ceil_div(a.T, 32) < 1024) mtb = 1;
+    auto fits = [&](int tokens) {
+      const int64_t tiles = (int64_t)n_ct * ceil_div(a.T, tokens);
+      const int64_t last = tiles % 512;
+      return tiles >= 1024 || (tiles >= 448 && (last == 0 || last >= 448));
+    };
+    mtb = fits(64) ? 4 : (fits(32) ? 2 : 1);
   }
   switch (e->bits * 8 + mtb) {
     case 8 * 8 + 4: return launch_cfg<8, 4, 4, 1>(p, acc_out, a.ev_start, a.ev_stop, st);

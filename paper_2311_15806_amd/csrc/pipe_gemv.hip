@@ -291,7 +291,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
         float mx = tg < p.T ? fabsf(v) : 0.f;
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
-        if (lane == 0) atomicMax(&p.amax_out[m], __float_as_uint(mx));
+        if (lane == 0) amax_raise(&p.amax_out[m], mx);
       }
       if (tg < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + tg) * p.out + col] = v;
     }

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(BLK) void absmax_kernel(const float* __restrict__ x
     for (int64_t i = i0; i < n; i += stride) m = fmaxf(m, fabsf(x[i]));
   }
   m = block_max(m);
-  if (threadIdx.x == 0) atomicMax(amax_bits, __float_as_uint(m));
+  if (threadIdx.x == 0) amax_raise(amax_bits, m);
 }
 
 __device__ __forceinline__ float act_scale(float s_static, const uint32_t* amax_bits) {
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ 
     mx = fmaxf(mx, fabsf(v));
   }
   mx = block_max(mx);
-  if (threadIdx.x == 0) atomicMax(&amax_bits[m], __float_as_uint(mx));
+  if (threadIdx.x == 0) amax_raise(&amax_bits[m], mx);
 }
 
 }  // namespace
