@@ -665,6 +665,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   GemmArgs a{};
   a.e = l1; a.T = T; a.T_pad = T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
   a.bias = bias1_dev; a.reduce = 0; a.zero_after = b.amax;
+  a.zero_big = reinterpret_cast<uint32_t*>(rowsum_h); a.zero_big_n = Mm * T_pad;   // the code sums of Q(h) start at zero
   fill_members(a, Mm, lo, hi);
   if (act == PIPE_ACT_GELU) {
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
@@ -691,10 +692,10 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
                                rowsum_h, nullptr, scale_h, st);
     if (rc) return rc;
   }
-  for (int m = 0; m < Mm && !one_launch; ++m) {
-    rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, 0.f, amax_h + m,
-                             qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
-                             scale_h + m, st);
+  if (!one_launch) {
+    // the gated path's separate activation pass ran after layer 1: its code sums were cleared there too
+    rc = launch_quantize_members(h, (int64_t)T * H, Mm, T, H, l2->in_pad, T_pad, amax_h, qh, (int64_t)T_pad * l2->in_pad,
+                                 rowsum_h, true, scale_h, st);
     if (rc) return rc;
   }
   // layer 2: member m contracts its own input with its own orders; summed in the epilogue
@@ -774,9 +775,12 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
   int32_t* rowsum_h = nullptr;
   if (L > 1) {
     qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * in_pad_max);
-    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)2 * Mm * T_pad * 4);
     if (!qh || !rowsum_h) return PIPE_ENOMEM;
   }
+  // code sums of the members' quantized inputs, two buffers used in turn: the quantizer of layer l
+  // adds into buffer l & 1, which the contraction of layer l-1 cleared (it reads the other one)
+  int32_t* rs_buf[2] = {rowsum_h, rowsum_h ? rowsum_h + (size_t)Mm * T_pad : nullptr};
   // max|tensor| per member, two sets used in turn: layer l writes set l & 1 in its epilogue, the
   // quantizer of layer l+1 reads it, and the contraction of layer l+1 clears it again
   uint32_t* amax_set[2] = {b.amax + 16, b.amax + 16 + PIPE_MAX_K};
@@ -803,23 +807,22 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
       const float* src = act[l - 1];
       const int in = e->in;
       uint32_t* amax_in = amax_set[(l - 1) & 1];
+      int32_t* rs_in = rs_buf[l & 1];
       if (small && T <= PIPE_QUANT1_MAX_T) {
         rc = launch_quantize_small(src, (int64_t)T * in, Mm, T, in, e->in_pad, 0.f, amax_in, qh, (int64_t)T_pad * e->in_pad,
-                                   rowsum_h, nullptr, scale_h, st);
+                                   rs_in, nullptr, scale_h, st);
         if (rc) return rc;
       } else {
-        for (int m = 0; m < Mm; ++m) {
-          rc = launch_quantize_act(src + (size_t)m * T * in, T, in, e->in_pad, T_pad, 0.f, amax_in + m,
-                                   qh + (size_t)m * T_pad * e->in_pad, rowsum_h + (size_t)m * T_pad, false, nullptr,
-                                   scale_h + m, st);
-          if (rc) return rc;
-        }
+        rc = launch_quantize_members(src, (int64_t)T * in, Mm, T, in, e->in_pad, T_pad, amax_in, qh,
+                                     (int64_t)T_pad * e->in_pad, rs_in, true, scale_h, st);
+        if (rc) return rc;
       }
       a.qx = qh; a.qx_mstride = (int64_t)T_pad * e->in_pad;
-      a.rowsum = rowsum_h; a.rowsum_mstride = T_pad;
+      a.rowsum = rs_in; a.rowsum_mstride = T_pad;
       a.s_x = scale_h; a.sx_mstride = 1;
       a.zero_after = amax_in; a.zero_n = Mm;
     }
+    if (!last_layer) { a.zero_big = reinterpret_cast<uint32_t*>(rs_buf[(l + 1) & 1]); a.zero_big_n = Mm * T_pad; }
     a.bias = ly.bias_dev;
     a.act = ly.act;
     if (ly.skip_from == 0) {

@@ -49,6 +49,8 @@ struct TiledParams {
   uint32_t* amax_out;
   uint32_t* zero_after;
   int zero_n;
+  uint32_t* zero_big;
+  int zero_big_n;
   int T, out, K, nks, n_tt, n_ct, M, reduce, act;
   const float* res;               // MODE_CHAIN: skip tensor [res_members, T, out] or nullptr
   long long res_mstride;
@@ -163,6 +165,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
 
   // ---- (column tile, token tile) from blockIdx: 8x8 super-tiles, one per XCD at a time ----
+  if (p.zero_big != nullptr)
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < p.zero_big_n; i += gridDim.x * 256) p.zero_big[i] = 0u;
   int ct, tt;
   {
     const int i = blockIdx.x;
@@ -521,7 +525,7 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.hidden = 0;

@@ -45,6 +45,8 @@ struct StreamParams {
   int res_members, res_pre_act;
   uint32_t* zero_after;
   int zero_n;
+  uint32_t* zero_big;
+  int zero_big_n;
   int T, out, K, nks, M, reduce, act;
   int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
   int n_tb;                // 16-token blocks: one workgroup per (bin, k share, token block)
@@ -99,6 +101,8 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_tiles = (p.nks * 64) / KSUP;
   if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
+  if (p.zero_big != nullptr)
+    for (int i = blockIdx.x * (NW * 64) + threadIdx.x; i < p.zero_big_n; i += gridDim.x * (NW * 64)) p.zero_big[i] = 0u;
 
   // Block index -> (bin, k share, token block).  Blocks are handed to the XCDs round robin, so the
   // workgroups that stream the same bin (for different token blocks or k shares) get indices that
@@ -326,7 +330,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.bins = e->bins_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n;
+  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   // Fewer bins than half the CUs and a long k: split each bin over several workgroups (each still
   // with at least two tiles per wave).  With more bins a split only adds the exchange through

@@ -180,6 +180,11 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
                         int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
 // Decode-sized batches (T <= 16, T_pad == 16): max|x|, scale, codes and code sums in ONE launch,
 // one workgroup per member (x, qx_frag, rowsum [16 per member], scale_out [M] with member strides).
+// One launch for all members: member m quantizes x + m*x_mstride ([T, in]) with its own dynamic
+// scale (amax_bits[m]) into qx_frag + m*qx_mstride and rowsum + m*T_pad; scale_out[m].
+int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, int T_pad,
+                            const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
+                            bool rowsum_is_zero, float* scale_out, hipStream_t st);
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
                           const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
@@ -220,6 +225,8 @@ struct GemmArgs {
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
   uint32_t* zero_after;  // words the kernel clears (the max|x| slots this call consumed), or nullptr
   int zero_n = 1;        // how many (at most 64)
+  uint32_t* zero_big = nullptr;   // a buffer the kernel clears as well (the code sums the next layer's quantizer
+  int zero_big_n = 0;             // adds into: nobody reads them while this kernel runs), any length
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // if set: the dispatch's own begin/end timestamps
 };
 // Launches with the dispatch's begin/end timestamps recorded into the two events when they are set

@@ -182,18 +182,23 @@ __device__ __forceinline__ void quantize_block(Fetch fetch, int T, int in, int i
   }
 }
 
-__global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restrict__ x, int T, int in,
+// blockIdx.z = ensemble member: member m reads x + m*x_mstride with the scale slot m, and writes
+// its own fragment buffer, code sums and scale.
+__global__ __launch_bounds__(BLK) void quantize_act_kernel(const float* __restrict__ x_all, int64_t x_mstride, int T, int in,
                                                            int in_pad, float s_static,
                                                            const uint32_t* __restrict__ amax_bits,
-                                                           uint8_t* __restrict__ qx_frag,
-                                                           int32_t* __restrict__ rowsum,
+                                                           uint8_t* __restrict__ qx_all, int64_t qx_mstride,
+                                                           int32_t* __restrict__ rowsum_all, int rowsum_mstride,
                                                            int8_t* __restrict__ qx_rowmajor,
                                                            float* __restrict__ scale_out) {
-  const float s = act_scale(s_static, amax_bits);
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  const int m = blockIdx.z;
+  const float* x = x_all + (size_t)m * x_mstride;
+  const float s = act_scale(s_static, amax_bits + m);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && scale_out) scale_out[m] = s;
   auto fetch = [=](int t, int k) { return x[(size_t)t * in + k]; };
   const bool vec = (in & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
-  quantize_block(fetch, T, in, in_pad, s, qx_frag, rowsum, qx_rowmajor, vec ? x : nullptr);
+  quantize_block(fetch, T, in, in_pad, s, qx_all + (size_t)m * qx_mstride, rowsum_all + (size_t)m * rowsum_mstride,
+                 qx_rowmajor, vec ? x : nullptr);
 }
 
 // Decode-sized batches (up to 64 tokens): ONE launch does max|x|, scale, codes and code sums, so the
@@ -417,8 +422,22 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
     if (rc) return rc;
   }
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, s_static, amax_bits,
-                     qx_frag, rowsum, qx_rowmajor, scale_out);
+  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, (int64_t)0, T, in, in_pad, s_static, amax_bits,
+                     qx_frag, (int64_t)0, rowsum, 0, qx_rowmajor, scale_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, int T_pad,
+                            const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
+                            bool rowsum_is_zero, float* scale_out, hipStream_t st) {
+  if (!rowsum_is_zero) {
+    int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), M * T_pad, st);
+    if (rc) return rc;
+  }
+  dim3 grid(T_pad / 16, ksplit_for(T_pad * M, in_pad), M);
+  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, x_mstride, T, in, in_pad, 0.f, amax_bits,
+                     qx_frag, qx_mstride, rowsum, T_pad, (int8_t*)nullptr, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
