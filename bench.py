@@ -32,9 +32,9 @@ LLC_BYTES = 256 << 20           # Infinity Cache: rotate over more expansion byt
 # x2.00, WRITE_SIZE x1.00); the summaries are under profiles/.  Counters cannot be read from
 # inside this process, so the figure is attached only to the workloads that were profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c4", 4096): 226e6 + 180e6,
+    ("c4", 4096): 263e6 + 180e6,
     ("c4", 16): 22.5e6 + 0.70e6,
-    ("c5", 4096): (1.48e9 + 0.73e9) + (1.41e9 + 0.07e9),
+    ("c5", 4096): (1.30e9 + 0.37e9) + (1.18e9 + 0.07e9),
 }
 
 
