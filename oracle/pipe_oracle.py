@@ -26,8 +26,8 @@ scale = row absmax / (2^(b-1)-1) and codes clamped to +-(2^(b-1)-1); ties round
 to even; an all-zero row has scale 0 and codes 0; R^1 is dense and orders k>=2
 keep the ceil(gamma*n_groups) groups of `group` consecutive output channels with
 the largest residual energy (sum of squares, fp64), re-selected at every order,
-ties to the lower group index; activations are per-tensor symmetric int8 with a
-static scale if given, else absmax/127; a member owns a contiguous range of
+ties to the lower group index; activations are per-tensor symmetric a-bit codes
+(a = 8 unless stated) with a static scale if given, else absmax/(2^(a-1)-1); a member owns a contiguous range of
 orders in every layer and its own activation scale; in a chain a skip connection
 is member-wise, except one that reads the network input, which only the first
 member adds.
@@ -54,10 +54,11 @@ f32 = np.float32
 # Sec. 3, Eq. (1): Q(W) = round(W / s), Q^-1(q) = s * q   (per output channel)
 # ----------------------------------------------------------------------------
 def q_max(bits: int) -> int:
-    """Largest code magnitude 2^(b-1)-1 (the Lemma's constant): 127, 7, 1."""
-    if bits not in (8, 4, 2):
-        raise ValueError("bits must be 8, 4 or 2 (ternary)")
-    return 2 ** (bits - 1) - 1
+    """Largest code magnitude 2^(b-1)-1 (the Lemma's constant): 127, 31, 7, 3, 1 for
+    b = 8, 6, 4, 3, 2 (ternary)."""
+    if not 2 <= int(bits) <= 8:
+        raise ValueError("bits must lie in 2..8")
+    return 2 ** (int(bits) - 1) - 1
 
 
 def quantize_rows(E: np.ndarray, bits: int):
@@ -209,18 +210,20 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
 # ----------------------------------------------------------------------------
 # App. B, Eq. (define_dre): f(x) = sigma( sum_k R^(k) Q(x) lambda_{R^(k)} lambda_x + b )
 # ----------------------------------------------------------------------------
-def quantize_activations(x: np.ndarray, s_x: Optional[float] = None):
-    """Per-tensor symmetric int8.  s_x > 0: static scale; None or <= 0: max|x|/127.
+def quantize_activations(x: np.ndarray, s_x: Optional[float] = None, bits: int = 8):
+    """Per-tensor symmetric a-bit codes (a = bits, 8 unless stated; Sec. 4 also uses A6 and
+    A4), held in int8.  s_x > 0: static scale; None or <= 0: max|x| / (2^(a-1)-1).
     Returns (Qx int8 same shape, s_x fp32).  s_x == 0 (all-zero input) gives Qx = 0."""
     x = np.asarray(x, dtype=f32)
+    qa = q_max(bits)
     if s_x is None or not (s_x > 0):
         amax = np.max(np.abs(x)) if x.size else f32(0)
-        s = f32(f32(amax) / f32(127.0))
+        s = f32(f32(amax) / f32(qa))
     else:
         s = f32(s_x)
     if not (s > 0):
         return np.zeros(x.shape, np.int8), f32(0)
-    q = np.clip(np.rint(x / s), -127, 127)
+    q = np.clip(np.rint(x / s), -qa, qa)
     return q.astype(np.int8), s
 
 
@@ -286,10 +289,10 @@ def sum_members(ys: np.ndarray) -> np.ndarray:
 
 
 def forward(exp: Expansion, x: np.ndarray, s_x: Optional[float] = None, split=None,
-            bias=None, reduce_members: bool = True):
+            bias=None, reduce_members: bool = True, act_bits: int = 8):
     """Expanded linear layer on x [T, I].  Returns a dict with Qx, s_x, acc (int32
     [K,T,O]), y (fp32; [T,O] if reduce_members else [M,T,O]) and y64 (fp64 twin)."""
-    Qx, sx = quantize_activations(x, s_x)
+    Qx, sx = quantize_activations(x, s_x, act_bits)
     acc = forward_acc(exp, Qx)
     ys = dequantize(exp, acc, sx, split, bias, f32)
     ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
@@ -340,10 +343,10 @@ def im2col(Q: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.ndarray
 
 def forward_conv2d(exp: Expansion, x: np.ndarray, kh, kw, stride, pad,
                    s_x: Optional[float] = None, split=None, bias=None,
-                   reduce_members: bool = True):
+                   reduce_members: bool = True, act_bits: int = 8):
     """Expanded conv layer on x [N,C,H,W] fp32; output rows are tokens (n, ho, wo),
     i.e. y is [N*Ho*Wo, O] (channels last)."""
-    Qx, sx = quantize_activations(x, s_x)
+    Qx, sx = quantize_activations(x, s_x, act_bits)
     T = Qx.shape[0] * np.prod(conv_out_size(x.shape[2], x.shape[3], kh, kw, stride, pad))
     acc = np.zeros((exp.K, int(T), exp.out_features), dtype=np.int32)
     for k in range(1, exp.K + 1):
@@ -373,7 +376,7 @@ def silu_mul(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
 
 
 def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, split=None,
-                bias1=None, bias2=None, s_x: Optional[float] = None):
+                bias1=None, bias2=None, s_x: Optional[float] = None, act_bits: int = 8):
     """Two expanded layers with an activation between, run as an ensemble.
 
     Member m uses only its own orders in BOTH layers, quantizes its own hidden
@@ -385,7 +388,7 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
     if exp1.K != exp2.K:
         raise ValueError("both layers need the same expansion order")
     rngs = member_ranges(exp1.K, split)
-    Qx, sx = quantize_activations(x, s_x)
+    Qx, sx = quantize_activations(x, s_x, act_bits)
     acc1 = forward_acc(exp1, Qx)
     y1 = dequantize(exp1, acc1, sx, split, bias1, f32)          # [M, T, O1]
     hs = []
@@ -399,12 +402,12 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
             raise ValueError("kind must be 'gelu' or 'gated'")
         hs.append(h)
     hs = np.stack(hs)
-    second = mlp_second_layer(exp2, hs, split, bias2)
+    second = mlp_second_layer(exp2, hs, split, bias2, act_bits)
     second.update(h=hs, y1=y1, s_x=sx, Qx=Qx)
     return second
 
 
-def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None):
+def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, act_bits: int = 8):
     """Last layer of the ensemble on given hidden activations hs [M, T, H]: member m
     quantizes hs[m] with its own dynamic scale, uses its own orders of exp2 (bias in
     the first member only), and the members are summed in ascending order.
@@ -414,7 +417,7 @@ def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None):
         raise ValueError("one hidden activation per member")
     outs, shs, Qhs = [], [], []
     for m in range(len(rngs)):
-        Qh, sh = quantize_activations(hs[m])
+        Qh, sh = quantize_activations(hs[m], None, act_bits)
         acc2 = forward_acc(exp2, Qh)
         outs.append(dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m])
         shs.append(sh)
@@ -449,7 +452,7 @@ def relu(v: np.ndarray) -> np.ndarray:
 
 
 def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: bool, skips,
-                        split=None, s_x: Optional[float] = None) -> np.ndarray:
+                        split=None, s_x: Optional[float] = None, act_bits: int = 8) -> np.ndarray:
     """One layer for all members.  inputs: [T, I] when every member reads the same tensor
     (the network input; s_x is its static scale if given), else [M, T, I] and member m
     quantizes inputs[m] with its own dynamic scale.  Member m contracts with its own orders
@@ -461,7 +464,7 @@ def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: boo
     out = []
     for m in range(M):
         xin = inputs if shared_input else inputs[m]
-        Qa, sa = quantize_activations(xin, s_x if shared_input else None)
+        Qa, sa = quantize_activations(xin, s_x if shared_input else None, act_bits)
         acc = forward_acc(exp, Qa)
         z = dequantize(exp, acc, sa, split, layer.bias, f32)[m]
         r = None if skips is None else skips[m]
@@ -495,7 +498,8 @@ def chain_skips(layers: Sequence[ChainLayer], l: int, x: np.ndarray, acts: Seque
     return [acts[j - 1][m] for m in range(M)]
 
 
-def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: Optional[float] = None):
+def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: Optional[float] = None,
+                  act_bits: int = 8):
     """M member chains through L expanded layers, summed after the last one.
 
     Member m is the whole architecture with, in every layer, only the orders of its own
@@ -516,9 +520,9 @@ def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: 
     for l, ly in enumerate(layers):
         skips = chain_skips(layers, l, x, acts, M)
         if l == 0:
-            a = chain_layer_members(ly, np.asarray(x, dtype=f32), True, skips, split, s_x)
+            a = chain_layer_members(ly, np.asarray(x, dtype=f32), True, skips, split, s_x, act_bits)
         else:
-            a = chain_layer_members(ly, acts[l - 1], False, skips, split)
+            a = chain_layer_members(ly, acts[l - 1], False, skips, split, None, act_bits)
         acts.append(a)
     members = acts.pop()
     return dict(y=sum_members(members), members=members, acts=acts)

@@ -48,7 +48,7 @@ def test_hand_worked_example(golden_dir):
 
 
 # ---------------------------------------------------------------- Eq. (1): K = 1 is plain quantization
-@pytest.mark.parametrize("bits", [8, 4, 2])
+@pytest.mark.parametrize("bits", [8, 6, 4, 3, 2])
 def test_k1_is_nearest_code_by_exhaustive_search(bits):
     """For every element the code must be the integer in [-q_max, q_max] whose
     de-quantized value is nearest (searched exhaustively, no rounding formula),
@@ -82,8 +82,51 @@ def test_zero_row_and_zero_matrix():
     assert e0.orders[1].group_ids.tolist() == [0]
 
 
+@pytest.mark.parametrize("a", [8, 6, 4, 2])
+def test_activation_codes_are_nearest_on_the_a_bit_grid(a):
+    """Q(x) with a-bit activations (Sec. 4: A8, A6, A4): the code is the integer of
+    [-(2^(a-1)-1), 2^(a-1)-1] nearest to x / s_x (exhaustive search), the largest |x| sits on the
+    last code with the dynamic scale, a static scale clamps, and the hand-worked dynamic example of
+    the golden file holds at a = 8."""
+    rng = np.random.default_rng(40 + a)
+    x = (rng.standard_normal((5, 33)) * 1.7).astype(f32)
+    qa = 2 ** (a - 1) - 1
+    Q, s = po.quantize_activations(x, None, a)
+    assert abs(int(Q.reshape(-1)[np.argmax(np.abs(x))])) == qa
+    assert math.isclose(float(s) * qa, float(np.abs(x).max()), rel_tol=1e-6)
+    cand = np.arange(-qa, qa + 1)
+    for v, q in zip(x.reshape(-1), Q.reshape(-1)):
+        d = np.abs(float(v) - float(s) * cand)
+        assert abs(float(v) - float(s) * int(q)) <= d.min() * (1 + 1e-5) + 1e-12
+    Qs, ss = po.quantize_activations(x, 0.25, a)
+    assert ss == f32(0.25) and int(np.abs(Qs).max()) <= qa
+    big = np.abs(x) >= 0.25 * (qa + 0.5)
+    assert np.all(np.abs(Qs[big]) == qa)
+    # fewer bits are a coarser grid of the same range: the de-quantized error bound s/2 scales with it
+    assert np.abs(x - s * Q.astype(f32)).max() <= float(s) / 2 * (1 + 1e-5)
+
+
+def test_forward_with_narrow_activations_is_the_textbook_layer():
+    """W4/A4 and W4/A6 forward = integer matmul of the a-bit activation codes with the weight codes
+    (torch int64), scaled: pins that act_bits reaches the contraction and nothing else changes."""
+    W = _rand_w(45, 16, 24)
+    x = np.random.default_rng(46).standard_normal((7, 24)).astype(f32)
+    e = po.expand(W, 4, 2, 1.0, 8)
+    for a in (4, 6):
+        r = po.forward(e, x, act_bits=a)
+        Q, s = po.quantize_activations(x, None, a)
+        assert np.array_equal(r["Qx"], Q) and int(np.abs(Q).max()) == 2 ** (a - 1) - 1
+        want = np.zeros((7, 16))
+        for k in (1, 2):
+            acc = (torch.from_numpy(Q).long() @ torch.from_numpy(e.dense_codes(k)).long().T).numpy()
+            want += e.dense_scales(k).astype(np.float64)[None, :] * acc
+        want *= float(s)
+        assert np.allclose(r["y64"], want, rtol=1e-12, atol=0)
+        assert np.allclose(r["y"], want, rtol=1e-5, atol=1e-7)
+
+
 # ---------------------------------------------------------------- Lemma (exponential convergence)
-@pytest.mark.parametrize("bits,K", [(8, 3), (4, 4), (2, 6)])
+@pytest.mark.parametrize("bits,K", [(8, 3), (6, 3), (4, 4), (3, 5), (2, 6)])
 def test_lemma_bound_dense(bits, K):
     """Per element: |w - sum_k w^(k)| <= s_K/2, scales shrink by >= 2*q_max per
     order, hence the Lemma's bound (1/q_max)^(K-1) * s_1 / 2; the error norm
@@ -272,7 +315,8 @@ def test_bias_only_in_first_member():
 # ---------------------------------------------------------------- convolution
 def test_conv_direct_equals_im2col_and_torch():
     rng = np.random.default_rng(60)
-    for (N, C, H, Wd, O, kh, kw, stride, pad) in [(2, 3, 6, 5, 4, 3, 3, 1, 1), (1, 2, 7, 7, 3, 3, 2, 2, 0)]:
+    for (N, C, H, Wd, O, kh, kw, stride, pad) in [(2, 3, 6, 5, 4, 3, 3, 1, 1), (1, 2, 7, 7, 3, 3, 2, 2, 0),
+                                                   (2, 5, 8, 6, 4, 1, 1, 2, 0), (1, 3, 13, 11, 4, 7, 7, 2, 3)]:
         Qx = rng.integers(-127, 128, size=(N, C, H, Wd), dtype=np.int8)
         q = rng.integers(-7, 8, size=(O, C * kh * kw), dtype=np.int8)
         direct = po.conv2d_acc_direct(Qx, q, kh, kw, stride, pad)
