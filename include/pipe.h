@@ -27,7 +27,9 @@
  *   - The library keeps a per-process device workspace (quantized activations,
  *     hidden activations of the MLP call) that grows on demand; calls that share
  *     a device must not overlap in time (one stream at a time).
- *   - bits: 8 (int8), 4 (int4, codes in [-7,7]) or 2 (ternary, codes in {-1,0,1}).
+ *   - bits: 2..8; codes lie in +-(2^(bits-1)-1): 8 int8, 4 int4 (codes in [-7,7]), 2 ternary
+ *     (codes in {-1,0,1}).  Codes are stored 2, 4 or 8 bits wide: 3-bit codes occupy 4-bit fields
+ *     and 5..7-bit codes bytes (the arithmetic is the same; only the packed size is not minimal).
  */
 #ifndef PIPE_H_
 #define PIPE_H_
@@ -53,7 +55,7 @@ enum { PIPE_ACT_NONE = 0, PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2, PIPE_ACT_R
 
 /* Build the expansion (R^1..R^K) of W (Sec. 3.1, Eq. (2)-(3); mask: masked Eq.).
  *   W_dev   [out, in] fp32, read only.
- *   bits    8, 4 or 2.          K >= 1 (at most 16).
+ *   bits    2..8.               K >= 1 (at most 16).
  *   gamma   in (0,1]: fraction of channel groups KEPT at every order k >= 2
  *           (n_keep = ceil(gamma * out/group)); R^1 is always dense.
  *   group   output channels per group; out % group == 0 and group % 16 == 0.
@@ -158,6 +160,13 @@ typedef struct pipe_chain_layer {
 int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
                        float s_x, const int* split, int M, float* const* acts_dev,
                        float* y_dev, void* stream);
+
+/* Bit-width a of the activation quantizer of every forward entry point from now on
+ * (Sec. 4 compares W4/A4, W4/A6, W8/A8): Q(x) = clamp(rint(x / s_x), +-(2^(a-1)-1)),
+ * dynamic s_x = max|x| / (2^(a-1)-1).  Default 8.  Process-wide; the codes still travel as
+ * bytes and feed the int8 MFMA.  Synchronous (copies one word to the device); do not call
+ * it while forward calls are in flight.  Returns PIPE_EINVAL outside 2..8.              */
+int pipe_set_activation_bits(int bits);
 
 /* Kernel selection for pipe_forward / pipe_mlp_forward (tuning and tests):
  * 0 = automatic by token count, 1 = tiled MFMA kernel, 2 = weight-streaming

@@ -49,6 +49,7 @@ def _load():
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_set_activation_bits.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
     lib.pipe_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), vp]
@@ -248,6 +249,10 @@ def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, re
 
 def pipe_set_kernel(which: int) -> None:
     _check(_lib.pipe_set_kernel(int(which)), "pipe_set_kernel")
+
+
+def pipe_set_activation_bits(bits: int) -> None:
+    _check(_lib.pipe_set_activation_bits(int(bits)), "pipe_set_activation_bits")
 
 
 def pipe_set_token_tile(tokens: int) -> None:

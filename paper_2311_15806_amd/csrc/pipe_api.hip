@@ -68,6 +68,11 @@ extern "C" int pipe_set_token_tile(int tokens) {
   return PIPE_OK;
 }
 
+extern "C" int pipe_set_activation_bits(int bits) {
+  if (bits < 2 || bits > 8) return PIPE_EINVAL;
+  return set_act_qmax((float)((1 << (bits - 1)) - 1));
+}
+
 extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
   if (workgroups_per_bin < 0 || workgroups_per_bin > PIPE_MAX_SPLIT) return PIPE_EINVAL;
   g_stream_ksplit = workgroups_per_bin;
@@ -251,7 +256,7 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
       rc = launch_group_select(energy, n_groups, group, keep, o.gids_dev, st);
       if (rc) return rc;
     }
-    int rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, group, o.gids_dev, o.n_kept, o.scales_dev,
+    int rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, e->qbits, group, o.gids_dev, o.n_kept, o.scales_dev,
                                   o.packed_dev, st);
     if (rc) return rc;
     e->stream_bytes += (int64_t)o.packed_bytes + (int64_t)rows * 4 + (int64_t)o.n_kept * 4;
@@ -268,7 +273,7 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
 extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
                            int group, void* stream, pipe_expansion** exp_out) {
   if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;
-  if (bits != 8 && bits != 4 && bits != 2) return PIPE_EINVAL;
+  if (bits < 2 || bits > 8) return PIPE_EINVAL;
   if (K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
   if (!(gamma > 0.f) || !(gamma <= 1.f)) return PIPE_EINVAL;
   if (out <= 0 || in <= 0 || group <= 0) return PIPE_ESHAPE;
@@ -277,7 +282,7 @@ extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K,
   if ((int64_t)in > (int64_t)130000) return PIPE_ESHAPE;
   pipe_expansion* e = new (std::nothrow) pipe_expansion();
   if (!e) return PIPE_ENOMEM;
-  e->out = out; e->in = in; e->bits = bits; e->K = K; e->group = group; e->gamma = gamma;
+  e->out = out; e->in = in; e->qbits = bits; e->bits = bits == 2 ? 2 : (bits <= 4 ? 4 : 8); e->K = K; e->group = group; e->gamma = gamma;
   e->n_groups = out / group;
   e->rbpg = group / 16;
   e->n_rb = out / 16;
@@ -311,7 +316,7 @@ extern "C" int pipe_expansion_info(const pipe_expansion* e, int* out, int* in, i
   if (!e) return PIPE_EINVAL;
   if (out) *out = e->out;
   if (in) *in = e->in;
-  if (bits) *bits = e->bits;
+  if (bits) *bits = e->qbits;
   if (K) *K = e->K;
   if (group) *group = e->group;
   if (gamma) *gamma = e->gamma;

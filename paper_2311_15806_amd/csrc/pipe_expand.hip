@@ -71,8 +71,9 @@ template <int BITS>
 __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ E, int in, int in_pad,
                                                             int group, const int32_t* __restrict__ gids,
                                                             float* __restrict__ scales,
-                                                            uint8_t* __restrict__ packed) {
-  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+                                                            uint8_t* __restrict__ packed, int QMAX) {
+  // BITS is the width of the stored code (8, 4 or 2); QMAX = 2^(b-1)-1 of the quantizer, which
+  // may be narrower (3-bit codes in 4-bit fields, 5..7-bit codes in bytes)
   constexpr int KSUP = 512 / BITS;       // k-values per tile
   constexpr int STEPS = KSUP / 64;       // 64-k steps per tile
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
@@ -215,18 +216,19 @@ int launch_group_select(const double* row_energy, int n_groups, int group, int n
   return PIPE_OK;
 }
 
-int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int group,
+int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
                          hipStream_t st) {
+  const int qmax = (1 << (qbits - 1)) - 1;
   (void)out;
   const int rows = n_kept * group;
   if (rows == 0) return PIPE_OK;
   if (bits == 8)
-    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
   else if (bits == 4)
-    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
   else
-    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed);
+    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -95,7 +95,8 @@ struct GemmArgs;
 const PassTables* pipe_get_tables(const pipe_expansion* e, const GemmArgs& a, int kind, int* rc);
 
 struct pipe_expansion {
-  int out = 0, in = 0, bits = 0, K = 0, group = 0;
+  int out = 0, in = 0, bits = 0, K = 0, group = 0;   // bits: width of a stored code (8, 4 or 2)
+  int qbits = 0;      // width the quantizer was asked for (2..8); codes lie in +-(2^(qbits-1)-1)
   float gamma = 1.f;
   int n_groups = 0;
   int rbpg = 0;       // row blocks per group = group/16
@@ -159,7 +160,7 @@ enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID,
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
 int launch_group_select(const double* row_energy, int n_groups, int group, int n_keep,
                         int32_t* gids_out, hipStream_t st);
-int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int group,
+int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
                          hipStream_t st);
 int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bits, int rows, int in, int in_pad,
@@ -185,6 +186,7 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
 int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, int T_pad,
                             const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                             bool rowsum_is_zero, float* scale_out, hipStream_t st);
+int set_act_qmax(float qmax);   // largest activation code of all quantizers from now on (synchronous copy to the device)
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
                           const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st);

@@ -61,14 +61,18 @@ __global__ __launch_bounds__(BLK) void absmax_kernel(const float* __restrict__ x
   if (threadIdx.x == 0) amax_raise(amax_bits, m);
 }
 
+// Largest activation code 2^(a-1)-1: 127 for int8 activations, 31 / 7 for 6 / 4 bits (the codes
+// still travel as bytes).  Set by pipe_set_activation_bits through set_act_qmax below.
+__constant__ float c_act_qmax = 127.f;
+
 __device__ __forceinline__ float act_scale(float s_static, const uint32_t* amax_bits) {
   if (s_static > 0.f) return s_static;
-  return __fdiv_rn(__uint_as_float(*amax_bits), 127.f);
+  return __fdiv_rn(__uint_as_float(*amax_bits), c_act_qmax);
 }
 
 __device__ __forceinline__ int quant1(float v, float s) {
   float q = rintf(__fdiv_rn(v, s));
-  q = fminf(fmaxf(q, -127.f), 127.f);
+  q = fminf(fmaxf(q, -c_act_qmax), c_act_qmax);
   return (int)q;
 }
 
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
   float s = s_static;
   if (!(s_static > 0.f) && amax_bits != nullptr) {
     // the producer of x already reduced max|x| of member m
-    s = __fdiv_rn(__uint_as_float(amax_bits[m]), 127.f);
+    s = __fdiv_rn(__uint_as_float(amax_bits[m]), c_act_qmax);
   } else if (!(s_static > 0.f)) {
     float mx = 0.f;
     const int64_t cnt = (int64_t)T * in;
@@ -255,7 +259,7 @@ __global__ __launch_bounds__(SBLK) void quantize_small_kernel(const float* __res
     mx = smax[0];
 #pragma unroll
     for (int i = 1; i < SBLK / 64; ++i) mx = fmaxf(mx, smax[i]);
-    s = __fdiv_rn(mx, 127.f);
+    s = __fdiv_rn(mx, c_act_qmax);
   }
   if (n == 0 && threadIdx.x == 0 && scale_out) scale_out[m] = s;
   const bool live = s > 0.f && n < T;
@@ -387,6 +391,11 @@ __global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ 
 }
 
 }  // namespace
+
+int set_act_qmax(float qmax) {
+  PIPE_HIP(hipMemcpyToSymbol(HIP_SYMBOL(c_act_qmax), &qmax, sizeof(float)));
+  return PIPE_OK;
+}
 
 int launch_zero_u32(uint32_t* p, int n, hipStream_t st) {
   if (n <= 0) return PIPE_OK;

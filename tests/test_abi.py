@@ -40,7 +40,8 @@ def test_argument_errors_return_codes(lib):
     fake = vp(256)          # never dereferenced: validation fails first
     EINVAL, ESHAPE = -1, -2
     assert lib.pipe_expand(None, 64, 64, 4, 2, 0.5, 16, None, C.byref(h)) == EINVAL
-    assert lib.pipe_expand(fake, 64, 64, 3, 2, 0.5, 16, None, C.byref(h)) == EINVAL      # bits
+    assert lib.pipe_expand(fake, 64, 64, 9, 2, 0.5, 16, None, C.byref(h)) == EINVAL      # bits
+    assert lib.pipe_expand(fake, 64, 64, 1, 2, 0.5, 16, None, C.byref(h)) == EINVAL
     assert lib.pipe_expand(fake, 64, 64, 4, 0, 0.5, 16, None, C.byref(h)) == EINVAL      # K
     assert lib.pipe_expand(fake, 64, 64, 4, 2, 0.0, 16, None, C.byref(h)) == EINVAL      # gamma
     assert lib.pipe_expand(fake, 64, 64, 4, 2, 1.5, 16, None, C.byref(h)) == EINVAL
@@ -55,6 +56,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0
     assert lib.pipe_set_token_tile(48) == EINVAL and lib.pipe_set_token_tile(0) == 0
+    assert lib.pipe_set_activation_bits(9) == EINVAL and lib.pipe_set_activation_bits(1) == EINVAL
     for code in (0, -1, -2, -3, -4, -5):
         assert len(lib.pipe_strerror(code)) > 0
 

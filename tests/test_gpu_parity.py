@@ -1,6 +1,8 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU checker on the same
 seeded inputs.  Integer state (kept groups, codes, Q(x), int32 accumulators) must be
 bit-exact; scales are compared as fp32 bit patterns; the fp32 output within 1e-3 relative."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -192,6 +194,35 @@ def test_conv2d_parity(pipe):
     g.free()
 
 
+@pytest.mark.parametrize("C,H,W,O,kh,kw,stride,pad", [
+    (64, 14, 14, 128, 1, 1, 1, 0),      # pointwise
+    (64, 14, 14, 128, 1, 1, 2, 0),      # projection shortcut of a residual block
+    (3, 37, 29, 64, 7, 7, 2, 3),        # stem: 147 input features, ragged output size
+    (32, 9, 9, 64, 3, 3, 2, 1),
+])
+def test_conv2d_variants(pipe, C, H, W, O, kh, kw, stride, pad):
+    """Strided, pointwise and large-kernel convolutions of the paper's ConvNets, both input
+    layouts, with a bias and an ensemble split."""
+    N = 3
+    rng = np.random.default_rng(700 + C + kh + stride)
+    Wt = (rng.standard_normal((O, C * kh * kw)) * math.sqrt(2.0 / (C * kh * kw))).astype(f32)
+    x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(f32)
+    b = rng.standard_normal(O).astype(f32)
+    spec = wl.LayerSpec(O, C * kh * kw, 4, 3, 0.5, 16)
+    ora = oracle_expand(Wt, spec)
+    g = pipe.pipe_expand(dev(Wt), spec.bits, spec.K, spec.gamma, spec.group)
+    assert_expansion_equal(g, ora)
+    for split in ([2, 1], None):
+        ref = po.forward_conv2d(ora, x, kh, kw, stride, pad, split=split, bias=b)
+        y = pipe.pipe_forward_conv2d(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy()
+        assert y.shape == ref["y"].shape
+        assert_close_fp32(y, ref["y"])
+        xl = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        yl = pipe.pipe_forward_conv2d(g, dev(xl), kh, kw, stride, pad, nhwc=True, split=split, bias=dev(b)).cpu().numpy()
+        assert np.array_equal(y, yl)
+    g.free()
+
+
 def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
     """Both kernels fold the orders in the same fixed order, so on a decode-sized batch (one to
     four 16-token blocks for the streaming kernel) their fp32 outputs are bit-identical."""
@@ -310,3 +341,76 @@ def test_mlp_parity(pipe, kind, tokens):
         else:
             assert_close_fp32(y.cpu().numpy(), ref["y"], tol=3e-2, elementwise=False)
     g1.free(); g2.free()
+
+
+@pytest.mark.parametrize("bits,K", [(3, 3), (5, 2), (6, 2), (7, 2)])
+def test_intermediate_weight_widths(pipe, bits, K):
+    """3-bit codes travel in 4-bit fields, 5..7-bit codes in bytes: expansion bit-exact, forward
+    within the fp32 bar, integer accumulators exact; both kernels."""
+    O, I = 192, 328
+    W = _w(800 + bits, O, I)
+    spec = wl.LayerSpec(O, I, bits, K, 0.5, 16)
+    ora = oracle_expand(W, spec)
+    g = pipe.pipe_expand(dev(W), bits, K, 0.5, 16)
+    assert g.bits == bits
+    assert_expansion_equal(g, ora)
+    for T in (150, 21):
+        x = np.random.default_rng(810 + T).standard_normal((T, I)).astype(f32)
+        ref = po.forward(ora, x)
+        y = pipe.pipe_forward(g, dev(x)).cpu().numpy()
+        assert_close_fp32(y, ref["y"])
+        acc, qx, _ = pipe.pipe_forward_acc(g, dev(x))
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    g.free()
+
+
+@pytest.mark.parametrize("a", [4, 6])
+def test_narrow_activations(pipe, a):
+    """W4/A4 and W4/A6 (Sec. 4): the activation quantizer clamps to the a-bit grid in every entry
+    point -- linear (both kernels, dynamic and static scale), conv, MLP hidden activations."""
+    pipe.pipe_set_activation_bits(a)
+    try:
+        O, I = 256, 328
+        W = _w(820 + a, O, I)
+        spec = wl.LayerSpec(O, I, 4, 3, 0.5, 16)
+        ora = oracle_expand(W, spec)
+        g = pipe.pipe_expand(dev(W), 4, 3, 0.5, 16)
+        for T in (150, 70, 9):
+            x = np.random.default_rng(830 + T).standard_normal((T, I)).astype(f32)
+            for s_x in (0.0, 0.05):
+                ref = po.forward(ora, x, s_x=s_x if s_x > 0 else None, split=[2, 1], act_bits=a)
+                acc, qx, sx = pipe.pipe_forward_acc(g, dev(x), s_x=s_x)
+                assert np.array_equal(qx.cpu().numpy(), ref["Qx"])
+                assert int(np.abs(ref["Qx"]).max()) == 2 ** (a - 1) - 1
+                assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+                y = pipe.pipe_forward(g, dev(x), s_x=s_x, split=[2, 1]).cpu().numpy()
+                assert_close_fp32(y, ref["y"])
+        g.free()
+        # conv
+        w = wl.scaled(wl.C2, out_div=4, in_div=8, tokens=2 * 196)
+        spec, c = w.layers[0], w.conv
+        Wc, xc = wl.make_weight(w, 0), wl.make_input(w)
+        oc = oracle_expand(Wc, spec)
+        gc = pipe.pipe_expand(dev(Wc), spec.bits, spec.K, spec.gamma, spec.group)
+        refc = po.forward_conv2d(oc, xc, c["kh"], c["kw"], c["stride"], c["pad"], act_bits=a)
+        yc = pipe.pipe_forward_conv2d(gc, dev(xc), c["kh"], c["kw"], c["stride"], c["pad"]).cpu().numpy()
+        assert_close_fp32(yc, refc["y"])
+        gc.free()
+        # MLP: the members' hidden activations are quantized on the same grid
+        wm = wl.scaled(wl.C3, out_div=8, in_div=8, tokens=100)
+        l1, l2 = wm.layers
+        W1, W2, xm = wl.make_weight(wm, 0), wl.make_weight(wm, 1), wl.make_input(wm)
+        o1, o2 = oracle_expand(W1, l1), oracle_expand(W2, l2)
+        g1 = pipe.pipe_expand(dev(W1), l1.bits, l1.K, l1.gamma, l1.group)
+        g2 = pipe.pipe_expand(dev(W2), l2.bits, l2.K, l2.gamma, l2.group)
+        for tokens in (100, 150):
+            xt = np.ascontiguousarray(np.resize(xm, (tokens, xm.shape[1])))
+            y, h = pipe.pipe_mlp_forward(g1, g2, pipe.PIPE_ACT_GELU, dev(xt), split=[2, 1], return_hidden=True)
+            refm = po.mlp_forward(o1, o2, "gelu", xt, split=[2, 1], act_bits=a)
+            assert_close_fp32(h.cpu().numpy(), refm["h"], tol=1e-5)
+            ref2 = po.mlp_second_layer(o2, h.cpu().numpy(), split=[2, 1], act_bits=a)
+            assert int(np.abs(ref2["Qh"]).max()) == 2 ** (a - 1) - 1
+            assert_close_fp32(y.cpu().numpy(), ref2["y"])
+        g1.free(); g2.free()
+    finally:
+        pipe.pipe_set_activation_bits(8)
