@@ -19,6 +19,7 @@ Passages followed
   * ensemble members, bias in predictor 1 ........ Sec. 3.2, Fig. 2 caption,
                                                    App. B "Ensemble of more Layers"
   * L-layer member chains with skips ............. App. B / App. D "more Layers", Fig. 2
+  * error diagnostics (spectral norms, U) ........ App. C, Theorems 1-2; Lemmas of App. B
   * operation head-count ......................... App. H
 
 Readings taken where the paper is silent (each is listed in the design notes):
@@ -526,6 +527,73 @@ def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: 
         acts.append(a)
     members = acts.pop()
     return dict(y=sum_members(members), members=members, acts=acts)
+
+
+# ----------------------------------------------------------------------------
+# App. C: data-free error diagnostics (Theorems "dre_upperbound" / "slim_upperbound")
+# ----------------------------------------------------------------------------
+def power_start_vector(n: int) -> np.ndarray:
+    """The fixed start vector of the power iteration: +-1 by a multiplicative integer hash of
+    the index (bit 15 of i * 2654435761 mod 2^32), scaled to unit length.  Both sides use the
+    same vector so that the iterates can be compared step by step."""
+    i = np.arange(n, dtype=np.uint64)
+    bit = ((i * np.uint64(2654435761)) & np.uint64(0xFFFFFFFF)) >> np.uint64(15) & np.uint64(1)
+    v = np.where(bit == 1, 1.0, -1.0)
+    return v / math.sqrt(n)
+
+
+def spectral_norm(W: np.ndarray, iters: int) -> float:
+    """s = largest singular value of W (the theorems' s_l), by `iters` steps of the power
+    iteration on W^T W in fp64: v <- W^T (W v) / ||W^T (W v)||, returning ||W v|| for the last
+    v (a lower bound of s that converges to it).  A zero matrix gives 0."""
+    W = np.asarray(W, dtype=np.float64)
+    v = power_start_vector(W.shape[1])
+    sigma = 0.0
+    for _ in range(int(iters)):
+        y = W @ v
+        sigma = float(np.linalg.norm(y))
+        z = W.T @ y
+        nz = float(np.linalg.norm(z))
+        if nz == 0.0:
+            return 0.0
+        v = z / nz
+    return float(np.linalg.norm(W @ v))
+
+
+def lemma_bound_u(exp: Expansion) -> float:
+    """u^(K) of a dense expansion (Lemma, Eq. exponential_decrease): the element-wise bound
+    (1/q_max)^(K-1) * lambda / 2 with lambda read as the FIRST-order row scale (with the
+    order-K scale, as printed, the bound is not the one the proof gives: the tight fact is
+    |error| <= s_K / 2 and s_K <= s_1 / (2 q_max)^(K-1)); the layer's figure is its maximum
+    over rows.  Holds for every row that is stored at every order."""
+    qm = float(q_max(exp.bits))
+    s1 = float(np.max(exp.orders[0].scales)) if exp.orders[0].scales.size else 0.0
+    return (1.0 / qm) ** (exp.K - 1) * s1 / 2.0
+
+
+def stored_bound_u(exp: Expansion) -> float:
+    """Element-wise error bound of a (possibly sparse) expansion from what is stored: a row's
+    error after its LAST stored order k* is at most s_k*/2 and later orders that prune the row
+    pass the residual on unchanged.  The layer's figure is the maximum over rows.  This is the
+    provable counterpart of Lemma "slim", whose printed numerator (a norm vector N^(K) times an
+    indicator) the paper does not define."""
+    last = np.zeros(exp.out_features, dtype=np.float64)
+    for k in range(1, exp.K + 1):
+        rows = exp.rows(k)
+        last[rows] = exp.orders[k - 1].scales.astype(np.float64)
+    return float(last.max()) / 2.0 if last.size else 0.0
+
+
+def error_bound_U(s: Sequence[float], u: Sequence[float]) -> float:
+    """U = prod_{l=1..L} ( sum_{i=1..l} s_i u_i + 1 ) - 1 (Theorem dre_upperbound; the same
+    form with the sparse u gives U_sparse), exactly as printed."""
+    if len(s) != len(u):
+        raise ValueError("one s and one u per layer")
+    U, run = 1.0, 0.0
+    for sl, ul in zip(s, u):
+        run += float(sl) * float(ul)
+        U *= run + 1.0
+    return U - 1.0
 
 
 # ----------------------------------------------------------------------------

@@ -532,6 +532,62 @@ def test_chain_members_are_independent_networks():
     assert np.allclose(r["members"][0], one["y"], rtol=1e-5, atol=1e-7)
 
 
+# ---------------------------------------------------------------- App. C: diagnostics
+def test_spectral_norm_against_svd_and_closed_forms():
+    rng = np.random.default_rng(90)
+    for shape in [(24, 40), (64, 17), (5, 5)]:
+        W = rng.standard_normal(shape)
+        sv = np.linalg.svd(W, compute_uv=False)
+        got = po.spectral_norm(W, 400)
+        assert got <= sv[0] * (1 + 1e-12)                       # a Rayleigh quotient never exceeds s
+        assert math.isclose(got, sv[0], rel_tol=1e-6)
+        few = po.spectral_norm(W, 3)
+        assert few <= got * (1 + 1e-12)                          # and grows with the iterations
+    # rank one: s = |a| |b| after a single step; diagonal: the largest |entry|
+    a, b = rng.standard_normal(9), rng.standard_normal(13)
+    assert math.isclose(po.spectral_norm(np.outer(a, b), 2), np.linalg.norm(a) * np.linalg.norm(b), rel_tol=1e-12)
+    d = np.diag([0.5, -3.0, 2.0, 1.0])
+    assert math.isclose(po.spectral_norm(d, 200), 3.0, rel_tol=1e-9)
+    assert po.spectral_norm(np.zeros((4, 6)), 5) == 0.0
+    v0 = po.power_start_vector(1000)
+    assert math.isclose(float(np.linalg.norm(v0)), 1.0, rel_tol=1e-12) and 350 < int((v0 > 0).sum()) < 650
+
+
+@pytest.mark.parametrize("bits,K", [(8, 2), (4, 3), (2, 5)])
+def test_error_bounds_hold_element_wise(bits, K):
+    """u of the Lemma bounds every element's error of a dense expansion; the stored-order bound
+    does the same for a sparse one and is never looser than it has to be (some element comes
+    within a factor 2q_max of it); hence ||W - W^(K)||_2 <= sqrt(O I) u."""
+    W = _rand_w(91 + bits, 64, 96, heavy=True)
+    dense = po.expand(W, bits, K, 1.0, 16)
+    err = np.abs(W.astype(np.float64) - dense.reconstruct())
+    slack = np.abs(W).max() * 2.0 ** -21
+    assert err.max() <= po.lemma_bound_u(dense) + slack
+    assert err.max() <= po.stored_bound_u(dense) + slack
+    assert po.stored_bound_u(dense) <= po.lemma_bound_u(dense) * (1 + 1e-6)
+    sparse = po.expand(W, bits, K, 0.5, 16)
+    errs = np.abs(W.astype(np.float64) - sparse.reconstruct())
+    assert errs.max() <= po.stored_bound_u(sparse) + slack
+    assert np.linalg.svd(W - sparse.reconstruct(), compute_uv=False)[0] <= math.sqrt(W.size) * po.stored_bound_u(sparse) + slack
+    if K > 1:
+        assert po.stored_bound_u(sparse) >= po.stored_bound_u(dense)   # pruning cannot tighten the bound
+
+
+def test_U_closed_forms():
+    # one layer: U = s u; two layers, as in the theorem's proof: s_A u_A + (s_A u_A + s_B u_B) + s_A u_A (s_A u_A + s_B u_B)
+    assert math.isclose(po.error_bound_U([3.0], [0.01]), 0.03)
+    a, b = 2.0 * 0.05, 4.0 * 0.01
+    assert math.isclose(po.error_bound_U([2.0, 4.0], [0.05, 0.01]), (a + 1) * (a + b + 1) - 1)
+    assert po.error_bound_U([1.0, 1.0, 1.0], [0.0, 0.0, 0.0]) == 0.0
+    # more orders shrink u by q_max per order, hence U
+    W = _rand_w(95, 32, 48)
+    us = [po.lemma_bound_u(po.expand(W, 4, K, 1.0, 16)) for K in (1, 2, 3)]
+    assert math.isclose(us[1], us[0] / 7, rel_tol=1e-6) and math.isclose(us[2], us[0] / 49, rel_tol=1e-6)
+    s = po.spectral_norm(W, 200)
+    Us = [po.error_bound_U([s, s], [u, u]) for u in us]
+    assert Us[0] > Us[1] > Us[2] > 0
+
+
 # ---------------------------------------------------------------- App. H
 def test_operation_head_count_closed_form():
     o, q, e = po.bit_operations(D=1, d=1, n_i=4096, n_o=11008, s=1, b=4, k=3)
