@@ -330,6 +330,18 @@ def main():
         cpu = dict(value=2.0 * macs / dt / 1e12, unit="TOPS", cores=int(cores), kind="oracle",
                    sample=sample, seconds=dt)
 
+    # ---- data-free diagnostic (not part of a step): spectral norm of layer 0's fp32 weight by
+    # power iteration; every iteration reads W twice, the last product once more
+    sn_iters = 20
+    pipe.pipe_spectral_norm(Ws[0], 2)
+    torch.cuda.synchronize()
+    t_sn = time.perf_counter()
+    sigma0 = pipe.pipe_spectral_norm(Ws[0], sn_iters)     # synchronizes
+    t_sn = time.perf_counter() - t_sn
+    sn_bytes = (2 * sn_iters + 1) * Ws[0].numel() * 4
+    spectral = {"layer": 0, "iters": sn_iters, "sigma": sigma0, "ms": t_sn * 1e3, "achieved_gbs": sn_bytes / t_sn / 1e9,
+                "frac_of_hbm_peak": sn_bytes / t_sn / 1e9 / HBM_PEAK_GBS}
+
     out = {
         "metric": "effective int TOPS of the residual-expanded layer (2*T*in*stored_rows / step time)",
         "value": head["eff_tops"],
@@ -352,6 +364,7 @@ def main():
         "cpu_baseline": cpu,
         "sweep": sweep,
         "ensemble_ms_per_step": ensemble_ms,
+        "spectral_norm": spectral,
         # reference rates of this chip (not targets): MFMA-only loop with constant operands, with
         # ternary codes x random int8 (what C4 feeds the pipe), with random int8 x int8; plain
         # streaming read of 2 GiB with the weight-streaming kernel's access pattern

@@ -168,6 +168,35 @@ int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev
  * it while forward calls are in flight.  Returns PIPE_EINVAL outside 2..8.              */
 int pipe_set_activation_bits(int bits);
 
+/* ---- Data-free error diagnostics (App. C, Theorems 1 and 2; Lemmas of App. B) ----
+ * None of these is on the forward path.
+ *
+ * pipe_spectral_norm: s = largest singular value of W (the theorems' s_l), by `iters`
+ * steps of the power iteration on W^T W: v <- W^T (W v) / ||W^T (W v)||, from the fixed
+ * unit vector v0[i] = +-1/sqrt(in) (sign = bit 15 of i * 2654435761 mod 2^32); returns
+ * ||W v|| for the last v, a lower bound that converges to s.  fp64 accumulation.
+ *   W_dev [out, in] fp32 row-major, DEVICE.  sigma_host: HOST.  Synchronizes the stream.
+ *
+ * pipe_expansion_reconstruct: W_out_dev [out, in] fp32 = sum over orders k <= upto of
+ * R^k = s_k * codes_k (Eq. 3; pruned rows contribute nothing), 1 <= upto <= K.
+ *
+ * pipe_expansion_error_bound: element-wise bounds on |W - sum_k R^k| from the stored
+ * scales alone.  u_lemma = (1/q_max)^(K-1) * max_rows(s_1) / 2 (Lemma "dre" with lambda
+ * read as the first-order scale; valid for rows stored at every order).  u_stored =
+ * max over rows of (scale of the row's LAST stored order) / 2: valid for sparse
+ * expansions too (the provable counterpart of Lemma "slim", whose printed numerator the
+ * paper does not define).  HOST outputs, either may be NULL.  Synchronizes the device.
+ *
+ * pipe_error_bound_U: U = prod_{l=1..L} ( sum_{i<=l} s_i u_i + 1 ) - 1 as printed in
+ * Theorem 1 (U_res with u_lemma, U_sparse with u_stored).  HOST arrays; pure arithmetic.
+ * U_ens (Theorem 3) is not provided: its printed index ranges are not readable.        */
+int pipe_spectral_norm(const float* W_dev, int out, int in, int iters, float* sigma_host,
+                       void* stream);
+int pipe_expansion_reconstruct(const pipe_expansion* e, int upto, float* W_out_dev,
+                               void* stream);
+int pipe_expansion_error_bound(const pipe_expansion* e, double* u_lemma, double* u_stored);
+int pipe_error_bound_U(const double* s, const double* u, int L, double* U_out);
+
 /* Kernel selection for pipe_forward / pipe_mlp_forward (tuning and tests):
  * 0 = automatic by token count, 1 = tiled MFMA kernel, 2 = weight-streaming
  * small-batch kernel.  Returns PIPE_EINVAL for other values.                    */

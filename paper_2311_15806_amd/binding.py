@@ -49,6 +49,10 @@ def _load():
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_spectral_norm.argtypes = [vp, ci, ci, ci, C.POINTER(cf), vp]
+    lib.pipe_expansion_reconstruct.argtypes = [vp, ci, vp, vp]
+    lib.pipe_expansion_error_bound.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.pipe_error_bound_U.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), ci, C.POINTER(C.c_double)]
     lib.pipe_set_activation_bits.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
@@ -245,6 +249,34 @@ def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, re
     _check(_lib.pipe_chain_forward(arr_l, L, _ptr(x, torch.float32), T, float(s_x), arr, m, acts_arr, _ptr(y),
                                    _stream()), "pipe_chain_forward")
     return (y, acts) if return_acts else y
+
+
+def pipe_spectral_norm(W: torch.Tensor, iters: int = 50) -> float:
+    s = C.c_float()
+    _check(_lib.pipe_spectral_norm(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(iters), C.byref(s), _stream()),
+           "pipe_spectral_norm")
+    return s.value
+
+
+def pipe_expansion_reconstruct(e: Expansion, upto: Optional[int] = None) -> torch.Tensor:
+    W = torch.empty((e.out_features, e.in_features), dtype=torch.float32, device="cuda")
+    _check(_lib.pipe_expansion_reconstruct(e.handle, int(e.K if upto is None else upto), _ptr(W), _stream()),
+           "pipe_expansion_reconstruct")
+    return W
+
+
+def pipe_expansion_error_bound(e: Expansion):
+    """(u_lemma, u_stored): element-wise bounds on |W - sum_k R^k| from the stored scales."""
+    a, b = C.c_double(), C.c_double()
+    _check(_lib.pipe_expansion_error_bound(e.handle, C.byref(a), C.byref(b)), "pipe_expansion_error_bound")
+    return a.value, b.value
+
+
+def pipe_error_bound_U(s, u) -> float:
+    L = len(s)
+    sa, ua, U = (C.c_double * L)(*[float(v) for v in s]), (C.c_double * L)(*[float(v) for v in u]), C.c_double()
+    _check(_lib.pipe_error_bound_U(sa, ua, L, C.byref(U)), "pipe_error_bound_U")
+    return U.value
 
 
 def pipe_set_kernel(which: int) -> None:

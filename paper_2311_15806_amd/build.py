@@ -20,6 +20,7 @@ SOURCES = [
     ("pipe_gemm.hip", []),
     ("pipe_gemv.hip", []),
     ("pipe_probe.hip", []),
+    ("pipe_diag.hip", ["-ffp-contract=off"]),
 ]
 
 COMMON = [
