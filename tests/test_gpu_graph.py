@@ -43,3 +43,41 @@ def test_forward_graph_replays(T):
         torch.cuda.synchronize()
         assert torch.equal(other, eager[(i + 1) % 3])
     g.free()
+
+
+@pytest.mark.parametrize("T", [9, 200])
+def test_chain_graph_replays(T):
+    """A member chain (quantizers, contractions with fused activation and skip, slot clearing
+    inside the kernels) captured once and replayed with other inputs: no replay may depend on
+    what the previous one left in the max and code-sum slots."""
+    import paper_2311_15806_amd.binding as pipe
+    w = wl.residual_stack(128, 2, 64, 4, 4, 0.5, 16, T, (2, 2))
+    gs = [pipe.pipe_expand(torch.from_numpy(wl.make_weight(w, l)).cuda(), s.bits, s.K, s.gamma, s.group)
+          for l, s in enumerate(w.layers)]
+    act = {"none": 0, "gelu": 1, "relu": 3}
+    layers = [(g, None, act[c[0]], c[1], c[2]) for g, c in zip(gs, w.chain)]
+    xs = [torch.from_numpy(wl.make_input(w)).cuda() * s for s in (1.0, 0.25, 5.0)]
+    x = xs[0].clone()
+    out = torch.empty((T, w.layers[-1].out_features), device="cuda")
+    eager = [pipe.pipe_chain_forward(layers, xi, split=[2, 2]).clone() for xi in xs]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.pipe_chain_forward(layers, x, split=[2, 2], out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipe.pipe_chain_forward(layers, x, split=[2, 2], out=out)
+    for rep in range(6):
+        i = rep % 3
+        x.copy_(xs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[i]), "replay %d differs" % rep
+        other = pipe.pipe_chain_forward(layers, xs[(i + 1) % 3], split=[2, 2])
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager[(i + 1) % 3])
+    for g in gs:
+        g.free()
