@@ -16,8 +16,9 @@
 // skipped (no load, no MFMA).  Per order the int32 accumulators (minus offset * token code
 // sum, exact) are folded into an fp32 running sum with the row-wise scale; activation scale,
 // bias, optional GELU and the member sum are applied once in the epilogue.
-// Workgroups are mapped to (column tile, token tile) in 8x8 super-tiles per XCD so that the
-// 64 workgroups resident on one XCD share 8 weight strips and 8 activation strips in its L2.
+// Workgroups are mapped to (column tile, token tile) in super-tiles of 64 tiles per XCD (8 x 8, or
+// 16 x 4 when that deals every XCD a share of every column-tile row) so that the 64 workgroups
+// resident on one XCD share a few weight strips and activation strips in its L2.
 #include <type_traits>
 
 #include "pipe_internal.h"
@@ -57,6 +58,7 @@ struct TiledParams {
   int res_members, res_pre_act;
   int hidden;                     // MODE_GATED: H; the layer's rows are gate [0,H) and up [H,2H), y is [M,T,H]
   int n_st_t;                     // super-tiles along tokens
+  int st_c_log2;                  // a super-tile is 2^st_c_log2 column tiles x 64 / 2^st_c_log2 token tiles
 };
 
 __device__ __forceinline__ float gelu_erf(float a) {
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
 
-  // ---- (column tile, token tile) from blockIdx: 8x8 super-tiles, one per XCD at a time ----
+  // ---- (column tile, token tile) from blockIdx: super-tiles of 64 tiles, one per XCD at a time ----
   if (p.zero_big != nullptr)
     for (int i = blockIdx.x * 256 + threadIdx.x; i < p.zero_big_n; i += gridDim.x * 256) p.zero_big[i] = 0u;
   int ct, tt;
@@ -173,8 +175,9 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     const int xcd = i & 7, j = i >> 3;
     const int sidx = (j >> 6) * 8 + xcd, local = j & 63;
     const int sc = sidx / p.n_st_t, st = sidx - sc * p.n_st_t;
-    ct = sc * 8 + (local >> 3);
-    tt = st * 8 + (local & 7);
+    const int tl2 = 6 - p.st_c_log2;
+    ct = (sc << p.st_c_log2) + (local >> tl2);
+    tt = (st << tl2) + (local & ((1 << tl2) - 1));
     if (ct >= p.n_ct || tt >= p.n_tt) return;
   }
   if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
@@ -496,8 +499,14 @@ template <int BITS, int MTB, int NRW, int MINW>
 int launch_cfg(TiledParams& p, bool acc_out, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
   p.n_tt = ceil_div(p.T, 16 * MTB);
   p.n_ct = ceil_div(p.n_ct * NRB_TILE, 4 * NRW);   // column tiles of this variant's width
-  p.n_st_t = ceil_div(p.n_tt, 8);
-  const int n_st_c = ceil_div(p.n_ct, 8);
+  // Super-tiles are dealt to the 8 XCDs in turn, column-tile rows (heaviest first) outermost.  With
+  // 8 token super-tiles per row every XCD gets a share of every row; with 4 (e.g. 2048 tokens)
+  // the even rows would all land on XCDs 0-3 and the odd rows on 4-7, the heavier half finishing
+  // last: then 16 x 4 super-tiles restore 8 per row.
+  p.st_c_log2 = 3;
+  if (ceil_div(p.n_tt, 8) % 8 != 0 && ceil_div(p.n_tt, 4) % 8 == 0) p.st_c_log2 = 4;
+  p.n_st_t = ceil_div(p.n_tt, 64 >> p.st_c_log2);
+  const int n_st_c = ceil_div(p.n_ct, 1 << p.st_c_log2);
   // super-tile sidx runs on XCD sidx % 8 as blocks xcd + 8*(64*(sidx/8) + local), local = 0..63
   const dim3 grid((unsigned)(ceil_div(p.n_st_t * n_st_c, 8) * 8 * 64));
   if (acc_out)
