@@ -131,3 +131,18 @@ def test_chain_argument_errors(pipe):
         pipe.pipe_chain_forward(glayers[:2] + glayers[3:], x, split=[1, 2])   # split does not sum to K
     for g in gpu:
         g.free()
+
+
+def test_full_width_stack_in_the_benchmark_launch_configuration(pipe):
+    """The benchmark's residual stack at full width (8 layers, 2048 wide, ternary, K = 8, [4,4])
+    on 1024 tokens with the 64-token tiles the benchmark's 4096 tokens select: every layer against
+    the checker on the GPU's own earlier tensors."""
+    w = wl.with_tokens(wl.CHAIN, 1024)
+    olayers, glayers, gpu = _build(pipe, w, with_bias=False)
+    pipe.pipe_set_token_tile(64)
+    try:
+        _check_chain(pipe, w, olayers, glayers, wl.make_input(w), list(w.split))
+    finally:
+        pipe.pipe_set_token_tile(0)
+    for g in gpu:
+        g.free()
