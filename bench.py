@@ -209,7 +209,8 @@ def main():
     else:
         roofline = dict(bound="hbm", achieved=head["kernel_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=(head["kernel_gbs"] or 0) / HBM_PEAK_GBS, traffic=None,
-                        kernel="gemm_stream_kernel", kernel_ms=head["kernel_ms_per_step"])
+                        kernel="gemm_stream_kernel" if cfg.layers[0].K <= 4 else "gemm_tiled_kernel (K > 4: no streaming variant)",
+                        kernel_ms=head["kernel_ms_per_step"])
 
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, T0))
     roofline["algorithmic_bytes"] = head["alg_bytes"]
