@@ -154,7 +154,7 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
   // Bins of the weight-streaming kernel: output row blocks, most orders first, packed first-fit
   // into bins of `cap` stored row blocks.  A stored row block's position in the schedule-ordered
   // buffers is bin * cap + index inside the bin.
-  const int cap = std::min(STREAM_BIN_CAP, std::max(4, K));
+  const int cap = std::min(STREAM_BIN_CAP, (std::max(4, K) + 3) / 4 * 4);   // 4, 8, 12 or 16: the kernel streams 4 items at a time
   std::vector<StreamBin> bins;
   std::vector<int> room;
   for (int k = 0; k < K; ++k) e->orders[k].pos.assign((size_t)e->orders[k].n_kept * rbpg, -1);
@@ -450,8 +450,9 @@ const PassTables* pipe_get_tables(const pipe_expansion* ce, const GemmArgs& a, i
 }
 
 // ------------------------------------------------------------------ forward
-static bool use_stream_kernel(const pipe_expansion* e, int T) {
-  if (g_kernel_choice == 1 || e->K > 4) return false;   // the streaming kernel holds at most 4 orders per bin
+static bool use_stream_kernel(const pipe_expansion* e, int T, bool acc_out = false) {
+  if (g_kernel_choice == 1) return false;
+  if (e->K > 4 && acc_out) return false;   // bins of more than 4 items have no integer export
   return T <= PIPE_STREAM_MAX_T;
 }
 
@@ -572,7 +573,7 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   if (T == 0) return PIPE_OK;
   if (!x_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(e, T);
+  const bool small = use_stream_kernel(e, T, acc_dev != nullptr);
   ActBuffers b;
   int rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;

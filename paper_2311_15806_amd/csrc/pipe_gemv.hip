@@ -12,8 +12,9 @@
 // LDS and are summed exactly; the epilogue then applies offsets, row scales, activation scale,
 // bias and the member sum in a fixed order, so results are bit-reproducible.  A workgroup
 // handles one 16-token block; larger batches (up to 128 tokens) run one workgroup per bin and
-// token block, on the same XCD, so that the bin still comes from HBM once.  Expansions with
-// more than 4 orders take the tiled kernel at every batch size.
+// token block, on the same XCD, so that the bin still comes from HBM once.  Expansions with more
+// than 4 orders have bins of 8, 12 or 16 items: gemm_stream_multi_kernel streams them four at a
+// time and keeps the integer tiles of the whole bin in LDS for one epilogue.
 #include "pipe_internal.h"
 
 #include <algorithm>
@@ -33,7 +34,7 @@ struct StreamParams {
   int64_t rowsum_mstride;
   const float* s_x;
   int sx_mstride;
-  const uint8_t* codes;    // stored row blocks in schedule order: bin b owns positions [b*R, (b+1)*R)
+  const uint8_t* codes;    // stored row blocks in schedule order: bin b owns positions [b*cap, (b+1)*cap), cap = 4, 8, 12 or 16
   const float* scales;     // 16 row scales per position
   const StreamBin* bins;
   const float* bias;
@@ -51,7 +52,7 @@ struct StreamParams {
   int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
   int n_tb;                // 16-token blocks: one workgroup per (bin, k share, token block)
   int n_bins;
-  int32_t* ws_sum;         // [n_bins][ksplit][R][256] partial tiles of split bins
+  int32_t* ws_sum;         // [n_bins][ksplit][cap][256] partial tiles of split bins
   uint32_t* ws_cnt;        // [n_bins] arrival counters, zero between launches
   int member_lo[PIPE_MAX_K];
   int member_hi[PIPE_MAX_K];
@@ -302,6 +303,248 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   }
 }
 
+// Bins of CAP = 4 * NCH items (expansions with 5 to 16 orders).  The workgroup streams the bin in
+// chunks of R = 4 items exactly as above (waves split k, two tiles per item in flight), reduces
+// each chunk's per-wave tiles into isum and runs one epilogue over all items: per output row
+// block and member the items are summed in ascending order k, the same fp32 order as everywhere.
+// XM = 1: all items read one activation tensor; XM = 4: one stream per item of the chunk (its
+// member's tensor; the streams need the bin descriptor, so it is fetched first).
+template <int BITS, int NW, int XM, int NCH>
+__global__ __launch_bounds__(NW * 64, 2) void gemm_stream_multi_kernel(const StreamParams p) {
+  static_assert(XM == 1 || XM == R, "one stream, or one per item of a chunk");
+  constexpr int CAP = R * NCH;
+  constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
+  constexpr int KSUP = 512 / BITS;
+  constexpr int STEPS = KSUP / 64;
+  constexpr int NX = XM * STEPS;
+  constexpr int BIN_WORDS = sizeof(StreamBin) / 4;
+  static_assert(BIN_WORDS <= 64, "bin descriptor is fetched with one load per lane");
+  __shared__ int part[NW][R][256];   // each wave's partial tiles of the current chunk
+  __shared__ int isum[CAP][256];     // the bin's integer tiles, summed over the waves
+  __shared__ int s_last;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n_tiles = (p.nks * 64) / KSUP;
+  if (blockIdx.x == 0 && (int)threadIdx.x < p.zero_n && p.zero_after != nullptr) p.zero_after[threadIdx.x] = 0u;
+  if (p.zero_big != nullptr)
+    for (int i = blockIdx.x * (NW * 64) + threadIdx.x; i < p.zero_big_n; i += gridDim.x * (NW * 64)) p.zero_big[i] = 0u;
+
+  const int subs = p.ksplit * p.n_tb;
+  const int grp = (int)blockIdx.x / (8 * subs), within = (int)blockIdx.x - grp * (8 * subs);
+  const int bin = grp * 8 + (within & 7), sub = within >> 3;
+  const int ksp = sub % p.ksplit, tb = sub / p.ksplit;
+  if (bin >= p.n_bins) return;
+
+  const int e = threadIdx.x & 255;
+  const int t = e >> 4, ch = e & 15;
+  const int tg = tb * 16 + t;
+  const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);
+  const int o_first = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+  constexpr int O_STEP = (NW * 64) / 256;
+  const bool fold_sx = p.reduce && p.M > 1;
+  const int tile_lo = (int)((long long)n_tiles * ksp / p.ksplit), tile_hi = (int)((long long)n_tiles * (ksp + 1) / p.ksplit);
+
+  const int d0 = lane < BIN_WORDS ? reinterpret_cast<const int32_t*>(p.bins + bin)[lane] : 0;
+  auto word = [&](int i) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(d0, i); };
+  auto out_rb = [&](int o) __attribute__((always_inline)) { return word(2 + 2 * STREAM_BIN_CAP + o); };
+  // epilogue operands, requested now and used (or staged in LDS) only after the code stream has
+  // started: this thread's row scale of every item, and per member the activation scale and
+  // the token's code sum
+  float scv[CAP];
+#pragma unroll
+  for (int r = 0; r < CAP; ++r) scv[r] = p.scales[((size_t)bin * CAP + r) * 16 + ch];
+  __shared__ float s_sx[PIPE_MAX_K];
+  __shared__ int s_rs[PIPE_MAX_K][16];
+  const float my_sx = (int)threadIdx.x < p.M ? p.s_x[threadIdx.x * p.sx_mstride] : 0.f;
+  const int my_rs = (OFF && (int)threadIdx.x < p.M * 16)
+                        ? p.rowsum[(size_t)(threadIdx.x >> 4) * p.rowsum_mstride + tb * 16 + (threadIdx.x & 15)] : 0;
+  auto stage_member_operands = [&]() __attribute__((always_inline)) {
+    if ((int)threadIdx.x < p.M) s_sx[threadIdx.x] = my_sx;
+    if (OFF && (int)threadIdx.x < p.M * 16) s_rs[threadIdx.x >> 4][threadIdx.x & 15] = my_rs;
+  };
+
+  // One chunk of R items streamed by WPC waves (wave slot wk of WPC takes tiles wk, wk+WPC, ...);
+  // leaves the wave's partial tiles in part[wave].
+  auto run_chunk = [&](int c, int wk, int wpc) __attribute__((always_inline)) {
+    v4i acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = v4i{0, 0, 0, 0};
+    {
+      // The codes are requested before anything that needs the bin descriptor (their positions
+      // follow from the block index; unused positions of a bin hold zeros and are streamed too).
+      const size_t pos0 = (size_t)bin * CAP + (size_t)c * R;
+      const uint8_t* wb[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) wb[r] = p.codes + (pos0 + r) * (size_t)n_tiles * 1024;
+      uint4 w0[R], w1[R], x0[NX], x1[NX];
+      auto load_w = [&](int tl, uint4 (&w)[R]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) w[r] = reinterpret_cast<const uint4*>(wb[r] + (size_t)tl * 1024)[lane];
+      };
+#pragma unroll
+      for (int r = 0; r < R; ++r) { w0[r] = make_uint4(0, 0, 0, 0); w1[r] = make_uint4(0, 0, 0, 0); }
+      int tl = tile_lo + wk;
+      if (tl < tile_hi) load_w(tl, w0);
+      if (tl + wpc < tile_hi) load_w(tl + wpc, w1);
+      const int n_items = word(0);
+      const uint8_t* xb[XM];
+#pragma unroll
+      for (int s = 0; s < XM; ++s) {
+        // stream s feeds item s of the chunk: its member's tensor (items beyond the bin's last repeat it)
+        const int it = min(c * R + s, n_items - 1);
+        const int mem = XM == 1 ? 0 : pick(p.member_of, word(2 + it));
+        xb[s] = p.qx + (size_t)mem * p.qx_mstride + (size_t)tb * p.nks * 1024;
+      }
+      auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < XM; ++s)
+#pragma unroll
+          for (int j = 0; j < STEPS; ++j) x[s * STEPS + j] = reinterpret_cast<const uint4*>(xb[s] + (size_t)(tl * STEPS + j) * 1024)[lane];
+      };
+#pragma unroll
+      for (int j = 0; j < NX; ++j) { x0[j] = make_uint4(0, 0, 0, 0); x1[j] = make_uint4(0, 0, 0, 0); }
+      if (tl < tile_hi) load_x(tl, x0);
+      if (tl + wpc < tile_hi) load_x(tl + wpc, x1);
+      auto mul_tile = [&](uint4 (&w)[R], uint4 (&x)[NX]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+#pragma unroll
+          for (int r = 0; r < R; ++r) {
+            const uint4& xs = x[(XM == 1 ? 0 : r) * STEPS + j];
+            const v4i xf = v4i{(int)xs.x, (int)xs.y, (int)xs.z, (int)xs.w};
+            v4i wf;
+            unpack_step<BITS>(w[r], j, wf);
+            acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
+          }
+        }
+      };
+      for (; tl < tile_hi; tl += 2 * wpc) {
+        mul_tile(w0, x0);
+        if (tl + 2 * wpc < tile_hi) { load_w(tl + 2 * wpc, w0); load_x(tl + 2 * wpc, x0); }
+        if (tl + wpc < tile_hi) {
+          mul_tile(w1, x1);
+          if (tl + 3 * wpc < tile_hi) { load_w(tl + 3 * wpc, w1); load_x(tl + 3 * wpc, x1); }
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      *reinterpret_cast<v4i*>(&part[wave][r][lane * 4]) = acc[r];
+  };
+  if constexpr (NW % NCH == 0) {
+    // the waves share out the chunks: NW / NCH waves per chunk, all chunks in flight at once
+    constexpr int WPC = NW / NCH;
+    run_chunk(wave / WPC, wave % WPC, WPC);
+    stage_member_operands();
+    __syncthreads();
+    for (int i = threadIdx.x; i < CAP * 256; i += NW * 64) {
+      const int c = i / (R * 256), j = i - c * (R * 256);
+      int a = 0;
+#pragma unroll
+      for (int w = 0; w < WPC; ++w) a += (&part[c * WPC + w][0][0])[j];
+      (&isum[0][0])[i] = a;
+    }
+    __syncthreads();
+  } else {
+    for (int c = 0; c < NCH; ++c) {
+      if (c > 0 && c * R >= word(0)) continue;   // uniform; chunk 0 always holds items
+      run_chunk(c, wave, NW);
+      if (c == 0) stage_member_operands();
+      __syncthreads();
+      for (int i = threadIdx.x; i < R * 256; i += NW * 64) {
+        int a = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) a += (&part[w][0][0])[i];
+        (&isum[c * R][0])[i] = a;
+      }
+      __syncthreads();   // part is free for the next chunk, isum of this one complete
+    }
+  }
+
+  const int n_items = word(0), n_out = word(1);
+  // a split bin: as in the 4-item kernel, over the tiles of the bin's n_items items
+  if (p.ksplit > 1) {
+    const int n_words = n_items * 256;
+    int32_t* ws = p.ws_sum + ((size_t)bin * p.ksplit + ksp) * (CAP * 256);
+    for (int i = threadIdx.x; i < n_words; i += NW * 64)
+      __hip_atomic_store(&ws[i], (&isum[0][0])[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&p.ws_cnt[bin], 1u) == (unsigned)(p.ksplit - 1);
+    __syncthreads();
+    if (!s_last) return;
+    const int32_t* wsb = p.ws_sum + (size_t)bin * p.ksplit * (CAP * 256);
+    for (int i = threadIdx.x; i < n_words; i += NW * 64) {
+      int a = 0;
+      for (int q = 0; q < p.ksplit; ++q) a += __hip_atomic_load(&wsb[(size_t)q * (CAP * 256) + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      (&isum[0][0])[i] = a;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(&p.ws_cnt[bin], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+  }
+
+  // epilogue over all items of the bin (same arithmetic and order as the 4-item kernel)
+  for (int o = o_first; o < n_out; o += O_STEP) {
+    const int col = out_rb(o) * 16 + ch;
+    const float bias = p.bias != nullptr ? p.bias[col] : 0.f;
+    float yacc = 0.f;
+    for (int m = 0; m < p.M; ++m) {
+      const float sx = s_sx[m];
+      const int rs = OFF ? s_rs[m][t] : 0;
+      const int k_lo = pick(p.member_lo, m), k_hi = pick(p.member_hi, m);
+#pragma unroll
+      for (int r = 0; r < CAP; ++r) {
+        const int kk = word(2 + r);
+        if (r >= n_items || word(2 + STREAM_BIN_CAP + r) != o || kk < k_lo || kk > k_hi) continue;   // uniform
+        const int a = isum[r][fidx] - OFF * rs;
+        const float sc = fold_sx ? scv[r] * sx : scv[r];
+        yacc = fmaf(sc, (float)a, yacc);
+      }
+      if (fold_sx && m + 1 < p.M) continue;
+      const float bm = (m == 0 || fold_sx) ? bias : 0.f;
+      float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);
+      yacc = 0.f;
+      float rsum = 0.f;
+      if (p.res != nullptr) {
+        const int n_res = p.reduce ? p.res_members : (m < p.res_members ? 1 : 0);
+        const float* rp = p.res + (size_t)(p.reduce ? 0 : m) * p.res_mstride + (size_t)min(tg, p.T - 1) * p.out + col;
+        for (int mm = 0; mm < n_res; ++mm) rsum += rp[(size_t)mm * p.res_mstride];
+      }
+      if (p.res_pre_act) v += rsum;
+      if (p.act == PIPE_ACT_GELU) v = gelu_erf(v);
+      else if (p.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
+      if (!p.res_pre_act) v += rsum;
+      if (p.amax_out != nullptr) {
+        float mx = tg < p.T ? fabsf(v) : 0.f;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
+        if (lane == 0) amax_raise(&p.amax_out[m], mx);
+      }
+      if (tg < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + tg) * p.out + col] = v;
+    }
+  }
+}
+
+template <int BITS, int NW, int NCH>
+int launch_multi(const StreamParams& p, int n_bins, int xm, const GemmArgs& a, hipStream_t st) {
+  const dim3 grid((unsigned)((n_bins + 7) / 8 * 8 * p.ksplit * p.n_tb)), blk(NW * 64);
+  if (xm == 1) PIPE_LAUNCH((gemm_stream_multi_kernel<BITS, NW, 1, NCH>), grid, blk, st, a.ev_start, a.ev_stop, p);
+  else PIPE_LAUNCH((gemm_stream_multi_kernel<BITS, NW, R, NCH>), grid, blk, st, a.ev_start, a.ev_stop, p);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+template <int BITS>
+int launch_multi_cap(const StreamParams& p, int n_bins, int cap, int xm, const GemmArgs& a, hipStream_t st) {
+  switch (cap) {
+    case 8: return launch_multi<BITS, 8, 2>(p, n_bins, xm, a, st);
+    case 12: return launch_multi<BITS, 8, 3>(p, n_bins, xm, a, st);
+    case 16: return launch_multi<BITS, 8, 4>(p, n_bins, xm, a, st);
+    default: return PIPE_ESHAPE;
+  }
+}
+
 template <int BITS, int NW>
 int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const GemmArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)((n_bins + 7) / 8 * 8 * p.ksplit * p.n_tb)), blk(NW * 64);
@@ -323,7 +566,8 @@ int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const Gem
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   const pipe_expansion* e = a.e;
   if (a.T <= 0) return PIPE_OK;
-  if (a.T > PIPE_STREAM_MAX_T || a.T_pad != (int)round_up64(a.T, 16) || e->K > R || e->bin_cap != R) return PIPE_ESHAPE;
+  if (a.T > PIPE_STREAM_MAX_T || a.T_pad != (int)round_up64(a.T, 16) || e->K > e->bin_cap || e->bin_cap % R != 0) return PIPE_ESHAPE;
+  if (e->bin_cap != R && a.acc_out != nullptr) return PIPE_EINVAL;   // the integer export of wide bins goes through the tiled kernel
   StreamParams p;
   p.qx = a.qx; p.qx_mstride = a.qx_mstride;
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
@@ -353,6 +597,14 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   // distinct activation tensors: one, or one per member
   const int xm = (a.qx_mstride == 0 || a.M <= 1) ? 1 : (a.M <= 2 ? 2 : 4);
   const bool acc_out = a.acc_out != nullptr;
+  if (e->bin_cap != R) {
+    const int xmm = (a.qx_mstride == 0 || a.M <= 1) ? 1 : R;
+    switch (e->bits) {
+      case 8: return launch_multi_cap<8>(p, e->n_bins, e->bin_cap, xmm, a, st);
+      case 4: return launch_multi_cap<4>(p, e->n_bins, e->bin_cap, xmm, a, st);
+      default: return launch_multi_cap<2>(p, e->n_bins, e->bin_cap, xmm, a, st);
+    }
+  }
   switch (e->bits) {
     case 8: return launch_nw<8, 8>(p, e->n_bins, xm, acc_out, a, st);
     case 4: return launch_nw<4, 8>(p, e->n_bins, xm, acc_out, a, st);

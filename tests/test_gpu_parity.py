@@ -229,14 +229,17 @@ def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
     O, I = 384, 1024
     b = np.random.default_rng(502).standard_normal(O).astype(f32)
     for T, bits, K, gamma, group in [(13, 2, 4, 0.25, 64), (13, 4, 3, 0.5, 32), (13, 8, 2, 1.0, 16),
-                                     (50, 2, 4, 0.25, 64), (64, 4, 3, 0.5, 32), (33, 8, 2, 1.0, 16)]:
+                                     (50, 2, 4, 0.25, 64), (64, 4, 3, 0.5, 32), (33, 8, 2, 1.0, 16),
+                                     # more than 4 orders: bins of 8, 12 and 16 items, streamed four at a time
+                                     (13, 2, 8, 0.5, 16), (40, 4, 6, 0.5, 32), (13, 2, 11, 0.5, 16), (21, 4, 16, 0.25, 64),
+                                     (128, 2, 5, 0.5, 16)]:
         W, x = _w(500, O, I), _x(501 + T, T, I)
         g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
         outs = []
         for which in (1, 2):
             pipe.pipe_set_kernel(which)
             try:
-                split = [1] * K
+                split = [1] * K if K <= 4 else [2, K - 4, 2]
                 y = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b)).cpu().numpy()
                 ym = pipe.pipe_forward(g, dev(x), split=split, bias=dev(b), reduce_members=False).cpu().numpy()
                 acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
