@@ -209,7 +209,7 @@ int pipe_set_kernel(int which);
 int pipe_set_token_tile(int tokens);
 
 /* Split of the weight-streaming kernel's bins along in_features (tuning and tests).
- * A bin (up to 4 stored row blocks holding every order of a few output row blocks)
+ * A bin (up to 4 stored row blocks -- 8, 12 or 16 for more than 4 orders -- holding every order of a few output row blocks)
  * is normally streamed by one workgroup; layers with few output channels and a long
  * in_features are split over several workgroups per bin, whose exact integer
  * partial sums meet in a workspace owned by the expansion (so two forward calls on
