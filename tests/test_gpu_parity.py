@@ -290,7 +290,8 @@ def test_streaming_kernel_split_bins_match_oracle(pipe, split_k):
     O, I, T = 320, 2304, 11
     W, x = _w(510, O, I), _x(511, T, I)
     b = np.random.default_rng(512).standard_normal(O).astype(f32)
-    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16)]:
+    for bits, K, gamma, group in [(2, 4, 0.25, 64), (4, 3, 0.5, 32), (8, 2, 1.0, 16),
+                                  (2, 8, 0.5, 16), (4, 6, 0.5, 32), (2, 11, 0.5, 16), (4, 13, 0.25, 64)]:   # wide bins split too
         spec = wl.LayerSpec(O, I, bits, K, gamma, group)
         ora = oracle_expand(W, spec)
         ref = po.forward(ora, x, bias=b)
