@@ -209,6 +209,23 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
 
 
 # ----------------------------------------------------------------------------
+# Sec. 4.1: batch-normalization layers are folded into the preceding layer before anything else
+# ----------------------------------------------------------------------------
+def fold_batchnorm(W: np.ndarray, b, gamma: np.ndarray, beta: np.ndarray, mean: np.ndarray,
+                   var: np.ndarray, eps: float):
+    """The layer y = BN(W x + b), BN(z) = gamma (z - mean) / sqrt(var + eps) + beta per output
+    channel, as one affine layer: W'[o,:] = W[o,:] * g[o], b'[o] = (b[o] - mean[o]) * g[o] + beta[o]
+    with g = gamma / sqrt(var + eps).  fp32, one rounding per operation (the folded weight is
+    what gets quantized, so its bits matter).  b may be None (taken as 0).  Returns (W', b')."""
+    W = np.asarray(W, dtype=f32)
+    g = (np.asarray(gamma, f32) / np.sqrt((np.asarray(var, f32) + f32(eps)).astype(f32)).astype(f32)).astype(f32)
+    Wf = (W * g[:, None]).astype(f32)
+    b0 = np.zeros(W.shape[0], f32) if b is None else np.asarray(b, f32)
+    bf = (((b0 - np.asarray(mean, f32)).astype(f32) * g).astype(f32) + np.asarray(beta, f32)).astype(f32)
+    return Wf, bf
+
+
+# ----------------------------------------------------------------------------
 # App. B, Eq. (define_dre): f(x) = sigma( sum_k R^(k) Q(x) lambda_{R^(k)} lambda_x + b )
 # ----------------------------------------------------------------------------
 def quantize_activations(x: np.ndarray, s_x: Optional[float] = None, bits: int = 8):

@@ -340,6 +340,27 @@ def test_conv_forward_matches_linear_on_im2col():
     assert np.array_equal(conv["acc"], lin["acc"]) and np.array_equal(conv["y"], lin["y"])
 
 
+def test_batchnorm_fold_equals_conv_then_batchnorm():
+    """The folded layer computes what torch's conv2d followed by batch_norm (inference mode)
+    computes, for a conv and for a fully-connected layer, with and without a bias."""
+    rng = np.random.default_rng(65)
+    O, C, kh, kw = 6, 3, 3, 3
+    Wc = rng.standard_normal((O, C * kh * kw)).astype(f32)
+    x = rng.standard_normal((2, C, 7, 5)).astype(f32)
+    gamma, beta = (1 + 0.3 * rng.standard_normal(O)).astype(f32), rng.standard_normal(O).astype(f32)
+    mean, var = rng.standard_normal(O).astype(f32), (0.5 + rng.random(O)).astype(f32)
+    for b in (None, rng.standard_normal(O).astype(f32)):
+        Wf, bf = po.fold_batchnorm(Wc, b, gamma, beta, mean, var, 1e-5)
+        t = lambda a: torch.from_numpy(np.asarray(a)).double()
+        z = torch.nn.functional.conv2d(t(x), t(Wc).reshape(O, C, kh, kw), None if b is None else t(b), padding=1)
+        ref = torch.nn.functional.batch_norm(z, t(mean), t(var), t(gamma), t(beta), False, 0.0, 1e-5)
+        got = torch.nn.functional.conv2d(t(x), t(Wf).reshape(O, C, kh, kw), t(bf), padding=1)
+        assert torch.allclose(got, ref, rtol=1e-5, atol=1e-5)
+    # identity statistics leave the layer alone
+    Wi, bi = po.fold_batchnorm(Wc, None, np.ones(O, f32), np.zeros(O, f32), np.zeros(O, f32), np.ones(O, f32), 0.0)
+    assert np.array_equal(Wi, Wc) and not bi.any()
+
+
 # ---------------------------------------------------------------- MLP ensemble
 def test_mlp_single_member_is_plain_composition():
     rng = np.random.default_rng(70)
