@@ -53,6 +53,18 @@ enum {
 
 enum { PIPE_ACT_NONE = 0, PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2, PIPE_ACT_RELU = 3 };
 
+/* Batch-normalization folding (Sec. 4.1: done before anything else): the layer
+ * y = BN(W x + b), BN(z) = gamma (z - mean) / sqrt(var + eps) + beta per output channel,
+ * as one affine layer W' x + b' with g = gamma / sqrt(var + eps), W'[o,:] = W[o,:] g[o],
+ * b'[o] = (b[o] - mean[o]) g[o] + beta[o]; g in fp64 rounded once to fp32, the rest fp32
+ * with one rounding per operation.  A conv
+ * weight is passed as [out, C*kh*kw].  All pointers DEVICE; bias_dev NULL = no bias;
+ * bias_out_dev NULL = not wanted; W_out_dev may equal W_dev.  eps >= 0.              */
+int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, const float* gamma_dev,
+                        const float* beta_dev, const float* mean_dev, const float* var_dev,
+                        float eps, int out, int in, float* W_out_dev, float* bias_out_dev,
+                        void* stream);
+
 /* Build the expansion (R^1..R^K) of W (Sec. 3.1, Eq. (2)-(3); mask: masked Eq.).
  *   W_dev   [out, in] fp32, read only.
  *   bits    2..8.               K >= 1 (at most 16).

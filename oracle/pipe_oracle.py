@@ -215,10 +215,13 @@ def fold_batchnorm(W: np.ndarray, b, gamma: np.ndarray, beta: np.ndarray, mean: 
                    var: np.ndarray, eps: float):
     """The layer y = BN(W x + b), BN(z) = gamma (z - mean) / sqrt(var + eps) + beta per output
     channel, as one affine layer: W'[o,:] = W[o,:] * g[o], b'[o] = (b[o] - mean[o]) * g[o] + beta[o]
-    with g = gamma / sqrt(var + eps).  fp32, one rounding per operation (the folded weight is
-    what gets quantized, so its bits matter).  b may be None (taken as 0).  Returns (W', b')."""
+    with g = gamma / sqrt(var + eps) evaluated in fp64 from the fp32 inputs (eps as fp32) and
+    rounded once to fp32; the products and sums are fp32, one rounding per operation (the
+    folded weight is what gets quantized, so its bits matter).  b may be None (taken as 0).
+    Returns (W', b')."""
     W = np.asarray(W, dtype=f32)
-    g = (np.asarray(gamma, f32) / np.sqrt((np.asarray(var, f32) + f32(eps)).astype(f32)).astype(f32)).astype(f32)
+    g = (np.asarray(gamma, f32).astype(np.float64)
+         / np.sqrt(np.asarray(var, f32).astype(np.float64) + np.float64(f32(eps)))).astype(f32)
     Wf = (W * g[:, None]).astype(f32)
     b0 = np.zeros(W.shape[0], f32) if b is None else np.asarray(b, f32)
     bf = (((b0 - np.asarray(mean, f32)).astype(f32) * g).astype(f32) + np.asarray(beta, f32)).astype(f32)

@@ -49,6 +49,7 @@ def _load():
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
+    lib.pipe_fold_batchnorm.argtypes = [vp] * 6 + [cf, ci, ci, vp, vp, vp]
     lib.pipe_spectral_norm.argtypes = [vp, ci, ci, ci, C.POINTER(cf), vp]
     lib.pipe_expansion_reconstruct.argtypes = [vp, ci, vp, vp]
     lib.pipe_expansion_error_bound.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -277,6 +278,17 @@ def pipe_error_bound_U(s, u) -> float:
     sa, ua, U = (C.c_double * L)(*[float(v) for v in s]), (C.c_double * L)(*[float(v) for v in u]), C.c_double()
     _check(_lib.pipe_error_bound_U(sa, ua, L, C.byref(U)), "pipe_error_bound_U")
     return U.value
+
+
+def pipe_fold_batchnorm(W: torch.Tensor, bias, gamma, beta, mean, var, eps: float):
+    """(W', b') of the layer followed by a batch normalization, as one affine layer."""
+    Wf = torch.empty_like(W)
+    bf = torch.empty(W.shape[0], dtype=torch.float32, device=W.device)
+    _check(_lib.pipe_fold_batchnorm(_ptr(W, torch.float32), _ptr(bias, torch.float32), _ptr(gamma, torch.float32),
+                                    _ptr(beta, torch.float32), _ptr(mean, torch.float32), _ptr(var, torch.float32),
+                                    float(eps), W.shape[0], W.shape[1], _ptr(Wf), _ptr(bf), _stream()),
+           "pipe_fold_batchnorm")
+    return Wf, bf
 
 
 def pipe_set_kernel(which: int) -> None:

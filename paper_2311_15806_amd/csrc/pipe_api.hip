@@ -270,6 +270,15 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
   return build_schedule(e, st);
 }
 
+extern "C" int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, const float* gamma_dev,
+                                   const float* beta_dev, const float* mean_dev, const float* var_dev, float eps,
+                                   int out, int in, float* W_out_dev, float* bias_out_dev, void* stream) {
+  if (!W_dev || !gamma_dev || !beta_dev || !mean_dev || !var_dev || !W_out_dev || !(eps >= 0.f)) return PIPE_EINVAL;
+  if (out < 1 || in < 1) return PIPE_ESHAPE;
+  return launch_fold_batchnorm(W_dev, bias_dev, gamma_dev, beta_dev, mean_dev, var_dev, eps, out, in, W_out_dev,
+                               bias_out_dev, (hipStream_t)stream);
+}
+
 extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
                            int group, void* stream, pipe_expansion** exp_out) {
   if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;

@@ -216,6 +216,29 @@ int launch_group_select(const double* row_energy, int n_groups, int group, int n
   return PIPE_OK;
 }
 
+// Sec. 4.1: y = BN(W x + b) as one affine layer (the folded weight is what gets quantized, so
+// every rounding is fixed): g = gamma / sqrt(var + eps) in fp64 rounded once to fp32, then
+// W' = W * g, b' = (b - mean) * g + beta in explicitly rounded fp32.
+__global__ __launch_bounds__(BLK) void fold_batchnorm_kernel(const float* __restrict__ W, const float* __restrict__ b,
+                                                             const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                             const float* __restrict__ mean, const float* __restrict__ var,
+                                                             float eps, int in, float* __restrict__ W_out,
+                                                             float* __restrict__ b_out) {
+  const int o = blockIdx.x;
+  // the scale in fp64, rounded once (fp32 sqrt is not correctly rounded on this target)
+  const float g = (float)((double)gamma[o] / sqrt((double)var[o] + (double)eps));
+  for (int i = threadIdx.x; i < in; i += BLK) W_out[(size_t)o * in + i] = __fmul_rn(W[(size_t)o * in + i], g);
+  if (threadIdx.x == 0 && b_out != nullptr)
+    b_out[o] = __fadd_rn(__fmul_rn(__fsub_rn(b != nullptr ? b[o] : 0.f, mean[o]), g), beta[o]);
+}
+
+int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, const float* beta, const float* mean,
+                          const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st) {
+  hipLaunchKernelGGL(fold_batchnorm_kernel, dim3(out), dim3(BLK), 0, st, W, b, gamma, beta, mean, var, eps, in, W_out, b_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
                          hipStream_t st) {

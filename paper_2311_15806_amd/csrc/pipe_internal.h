@@ -160,6 +160,8 @@ enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID,
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
 int launch_group_select(const double* row_energy, int n_groups, int group, int n_keep,
                         int32_t* gids_out, hipStream_t st);
+int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, const float* beta, const float* mean,
+                          const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st);
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
                          hipStream_t st);

@@ -59,6 +59,7 @@ def test_argument_errors_return_codes(lib):
     s2, u2, U = (C.c_double * 2)(2.0, 4.0), (C.c_double * 2)(0.05, 0.01), C.c_double()
     assert lib.pipe_error_bound_U(s2, u2, 2, C.byref(U)) == 0 and abs(U.value - ((0.1 + 1) * (0.14 + 1) - 1)) < 1e-15
     assert lib.pipe_error_bound_U(s2, u2, 0, C.byref(U)) == EINVAL
+    assert lib.pipe_fold_batchnorm(None, None, None, None, None, None, C.c_float(1e-5), 4, 4, None, None, None) == EINVAL
     assert lib.pipe_expansion_free(None) == 0
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0

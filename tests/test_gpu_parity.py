@@ -418,3 +418,28 @@ def test_narrow_activations(pipe, a):
         g1.free(); g2.free()
     finally:
         pipe.pipe_set_activation_bits(8)
+
+
+def test_batchnorm_fold_then_expand(pipe):
+    """Folding is bit-identical to the checker's, so the expansion of the folded weight is too,
+    and the folded conv layer runs through the expanded forward."""
+    rng = np.random.default_rng(840)
+    O, C, kh, kw = 64, 32, 3, 3
+    W = (rng.standard_normal((O, C * kh * kw)) * 0.06).astype(f32)
+    bias = rng.standard_normal(O).astype(f32)
+    gamma, beta = (1 + 0.3 * rng.standard_normal(O)).astype(f32), rng.standard_normal(O).astype(f32)
+    mean, var = rng.standard_normal(O).astype(f32), (0.5 + rng.random(O)).astype(f32)
+    for b in (bias, None):
+        Wf, bf = pipe.pipe_fold_batchnorm(dev(W), None if b is None else dev(b), dev(gamma), dev(beta), dev(mean), dev(var), 1e-5)
+        Wr, br = po.fold_batchnorm(W, b, gamma, beta, mean, var, 1e-5)
+        assert np.array_equal(Wf.cpu().numpy().view(np.uint32), Wr.view(np.uint32))
+        assert np.array_equal(bf.cpu().numpy().view(np.uint32), br.view(np.uint32))
+    spec = wl.LayerSpec(O, C * kh * kw, 4, 3, 0.5, 16)
+    ora = oracle_expand(Wr, spec)
+    g = pipe.pipe_expand(Wf, 4, 3, 0.5, 16)
+    assert_expansion_equal(g, ora)
+    x = np.maximum(rng.standard_normal((2, C, 9, 9)), 0).astype(f32)
+    ref = po.forward_conv2d(ora, x, kh, kw, 1, 1, bias=br)
+    y = pipe.pipe_forward_conv2d(g, dev(x), kh, kw, 1, 1, bias=bf).cpu().numpy()
+    assert_close_fp32(y, ref["y"])
+    g.free()
