@@ -380,6 +380,44 @@ def forward_conv2d(exp: Expansion, x: np.ndarray, kh, kw, stride, pad,
     return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
 
 
+def depthwise_acc_direct(Qx: np.ndarray, codes: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.ndarray:
+    """Depthwise integer convolution: one kh x kw filter per channel (App. H: a conv with
+    n_i = 1).  Qx int8 [N,C,H,W], codes int8 [C, kh*kw] (row c = filter of channel c, flattened
+    [kh, kw]).  Returns int32 [N*Ho*Wo, C]: acc[(n,ho,wo), c] = sum_{r,q} Qx[n,c,ho*s-p+r,wo*s-p+q]
+    * codes[c, r*kw+q], zero outside the image.  Exact (int64 sums of |terms| <= 127*127)."""
+    N, C, H, W = Qx.shape
+    Ho, Wo = conv_out_size(H, W, kh, kw, stride, pad)
+    xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=np.int64)
+    xp[:, :, pad:pad + H, pad:pad + W] = Qx
+    acc = np.zeros((N, Ho, Wo, C), dtype=np.int64)
+    for r in range(kh):
+        for q in range(kw):
+            win = xp[:, :, r:r + stride * (Ho - 1) + 1:stride, q:q + stride * (Wo - 1) + 1:stride]   # [N,C,Ho,Wo]
+            acc += win.transpose(0, 2, 3, 1) * codes[:, r * kw + q].astype(np.int64)[None, None, None, :]
+    return acc.reshape(N * Ho * Wo, C).astype(np.int32)
+
+
+def forward_depthwise2d(exp: Expansion, x: np.ndarray, kh, kw, stride, pad,
+                        s_x: Optional[float] = None, split=None, bias=None,
+                        reduce_members: bool = True, act_bits: int = 8):
+    """Expanded depthwise conv layer: exp was built from W [C, kh*kw]; x [N,C,H,W] fp32.
+    Output rows are pixels (n, ho, wo): y is [N*Ho*Wo, C] (channels last).  Same quantizer,
+    per-channel scales, member ranges and evaluation order as the dense layers."""
+    if exp.out_features != x.shape[1] or exp.in_features != kh * kw:
+        raise ValueError("depthwise: expansion must be [C, kh*kw]")
+    Qx, sx = quantize_activations(x, s_x, act_bits)
+    T = Qx.shape[0] * int(np.prod(conv_out_size(x.shape[2], x.shape[3], kh, kw, stride, pad)))
+    acc = np.zeros((exp.K, T, exp.out_features), dtype=np.int32)
+    for k in range(1, exp.K + 1):
+        rows = exp.rows(k)
+        acc[k - 1][:, rows] = depthwise_acc_direct(Qx[:, rows], exp.orders[k - 1].codes, kh, kw, stride, pad)
+    ys = dequantize(exp, acc, sx, split, bias, f32)
+    ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
+    if reduce_members:
+        return dict(Qx=Qx, s_x=sx, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
+    return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
+
+
 # ----------------------------------------------------------------------------
 # Sec. 3.2 / App. B: ensemble of M predictors over a two-layer MLP
 # ----------------------------------------------------------------------------

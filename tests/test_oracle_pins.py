@@ -340,6 +340,31 @@ def test_conv_forward_matches_linear_on_im2col():
     assert np.array_equal(conv["acc"], lin["acc"]) and np.array_equal(conv["y"], lin["y"])
 
 
+def test_depthwise_against_torch_grouped_conv():
+    """Depthwise accumulators equal torch's grouped conv2d (groups = C) on the integer codes, and
+    the expanded depthwise layer converges to the full-precision depthwise conv."""
+    rng = np.random.default_rng(66)
+    for (N, C, H, Wd, kh, kw, stride, pad) in [(2, 5, 7, 6, 3, 3, 1, 1), (1, 4, 9, 9, 3, 3, 2, 1), (2, 3, 11, 8, 5, 5, 2, 2)]:
+        Qx = rng.integers(-127, 128, size=(N, C, H, Wd), dtype=np.int8)
+        q = rng.integers(-7, 8, size=(C, kh * kw), dtype=np.int8)
+        got = po.depthwise_acc_direct(Qx, q, kh, kw, stride, pad)
+        ref = torch.nn.functional.conv2d(torch.from_numpy(Qx).double(), torch.from_numpy(q).double().reshape(C, 1, kh, kw),
+                                         stride=stride, padding=pad, groups=C)
+        assert np.array_equal(got.astype(np.float64), ref.permute(0, 2, 3, 1).reshape(-1, C).numpy())
+    C, kh, kw = 16, 3, 3
+    W = rng.standard_normal((C, kh * kw)).astype(f32)
+    x = rng.standard_normal((2, C, 8, 8)).astype(f32)
+    b = rng.standard_normal(C).astype(f32)
+    e = po.expand(W, 8, 3, 1.0, 8)
+    r = po.forward_depthwise2d(e, x, kh, kw, 1, 1, bias=b, split=[2, 1])
+    full = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(W).double().reshape(C, 1, kh, kw),
+                                      torch.from_numpy(b).double(), padding=1, groups=C)
+    full = full.permute(0, 2, 3, 1).reshape(-1, C).numpy()
+    assert np.abs(r["y"] - full).max() < 0.02 * np.abs(full).max()      # the int8 activation grid is all that is left
+    parts = po.forward_depthwise2d(e, x, kh, kw, 1, 1, bias=b, split=[2, 1], reduce_members=False)["y"]
+    assert np.array_equal(r["y"], (parts[0] + parts[1]).astype(f32))
+
+
 def test_batchnorm_fold_equals_conv_then_batchnorm():
     """The folded layer computes what torch's conv2d followed by batch_norm (inference mode)
     computes, for a conv and for a fully-connected layer, with and without a bias."""
