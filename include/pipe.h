@@ -127,6 +127,19 @@ int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int 
                         const int* split, int M, const float* bias_dev,
                         int reduce_members, float* y_dev, void* stream);
 
+/* Expanded depthwise convolution (App. H: a convolution whose filters see one input
+ * channel each; the separable blocks of MobileNet / EfficientNet).  The expansion was
+ * built from W [C, kh*kw] (row c = the filter of channel c, flattened [kh, kw]; kh*kw
+ * <= 49).  x_dev and y_dev as in pipe_forward_conv2d: y_dev is [N*Ho*Wo, C] (channels
+ * last) or [M, N*Ho*Wo, C].  Same quantizer, scales, member ranges and summation order as
+ * the dense layers; runs on the vector ALUs (kh*kw multiply-adds per output and order is
+ * no contraction for the matrix cores).  The first call on an expansion builds a dense
+ * copy of its codes (allocates, synchronizes).                                       */
+int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,
+                             int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
+                             const int* split, int M, const float* bias_dev,
+                             int reduce_members, float* y_dev, void* stream);
+
 /* Two expanded layers with an activation between, run as an ensemble of M
  * members (Sec. 3.2; App. B "Ensemble of more Layers"): member m uses only its
  * own orders in both layers, quantizes its own hidden activation with its own

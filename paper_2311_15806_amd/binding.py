@@ -46,6 +46,7 @@ def _load():
     lib.pipe_forward.argtypes = [vp, vp, ci, cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
+    lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
@@ -209,6 +210,26 @@ def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride:
     _check(_lib.pipe_forward_conv2d(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
                                     1 if nhwc else 0, float(s_x), arr, m, _ptr(bias, torch.float32),
                                     1 if reduce_members else 0, _ptr(y), _stream()), "pipe_forward_conv2d")
+    return y
+
+
+def pipe_forward_depthwise2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
+                             nhwc: bool = False, s_x: float = 0.0, split=None, bias=None,
+                             reduce_members: bool = True) -> torch.Tensor:
+    if x.dim() != 4:
+        raise ValueError("x must be [N,C,H,W] or [N,H,W,C]")
+    if nhwc:
+        N, H, W, Cc = x.shape
+    else:
+        N, Cc, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    M = 1 if split is None else len(split)
+    T = N * Ho * Wo
+    y = torch.empty((T, Cc) if reduce_members else (M, T, Cc), dtype=torch.float32, device=x.device)
+    arr, m = _split(split)
+    _check(_lib.pipe_forward_depthwise2d(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
+                                         1 if nhwc else 0, float(s_x), arr, m, _ptr(bias, torch.float32),
+                                         1 if reduce_members else 0, _ptr(y), _stream()), "pipe_forward_depthwise2d")
     return y
 
 

@@ -21,6 +21,7 @@ SOURCES = [
     ("pipe_gemv.hip", []),
     ("pipe_probe.hip", []),
     ("pipe_diag.hip", ["-ffp-contract=off"]),
+    ("pipe_depthwise.hip", ["-ffp-contract=off"]),
 ]
 
 COMMON = [

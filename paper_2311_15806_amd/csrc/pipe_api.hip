@@ -56,6 +56,7 @@ void* pipe_ws_get(int slot, size_t bytes) {
 }
 
 static int g_kernel_choice = 0;
+float g_act_qmax_host = 127.f;
 extern "C" int pipe_set_kernel(int which) {
   if (which < 0 || which > 2) return PIPE_EINVAL;
   g_kernel_choice = which;
@@ -70,7 +71,8 @@ extern "C" int pipe_set_token_tile(int tokens) {
 
 extern "C" int pipe_set_activation_bits(int bits) {
   if (bits < 2 || bits > 8) return PIPE_EINVAL;
-  return set_act_qmax((float)((1 << (bits - 1)) - 1));
+  g_act_qmax_host = (float)((1 << (bits - 1)) - 1);
+  return set_act_qmax(g_act_qmax_host);
 }
 
 extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
@@ -122,6 +124,8 @@ static void free_expansion(pipe_expansion* e) {
     if (t.src_dev) (void)hipFree(t.src_dev);
     if (t.cnt_dev) (void)hipFree(t.cnt_dev);
   }
+  if (e->dw_codes_dev) (void)hipFree(e->dw_codes_dev);
+  if (e->dw_scales_dev) (void)hipFree(e->dw_scales_dev);
   if (e->bins_dev) (void)hipFree(e->bins_dev);
   if (e->codes_dev) (void)hipFree(e->codes_dev);
   if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
@@ -635,6 +639,43 @@ extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, 
   a.s_x = b.scale; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev; a.zero_after = b.amax;
   fill_members(a, Mm, lo, hi);
   return run_gemm(a, small, st);
+}
+
+extern "C" int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W,
+                                        int kh, int kw, int stride, int pad, int nhwc, float s_x, const int* split,
+                                        int M, const float* bias_dev, int reduce_members, float* y_dev, void* stream) {
+  if (!e) return PIPE_EINVAL;
+  if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
+  if (C != e->out || kh * kw != e->in || kh * kw > 49) return PIPE_ESHAPE;
+  if (H + 2 * pad < kh || W + 2 * pad < kw) return PIPE_ESHAPE;
+  const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+  if ((int64_t)N * Ho * Wo * C > (int64_t)1 << 40) return PIPE_ESHAPE;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (N == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  rc = pipe_depthwise_prepare(const_cast<pipe_expansion*>(e), st);
+  if (rc) return rc;
+  ActBuffers b;
+  rc = get_act_buffers(16, IN_PAD, true, &b);   // only the scale and max slots are used
+  if (rc) return rc;
+  const int64_t n = (int64_t)N * C * H * W;
+  if (!(s_x > 0.f)) {
+    rc = launch_absmax(x_dev, n, b.amax, nullptr, 0, st);
+    if (rc) return rc;
+  }
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)n);
+  if (!q8) return PIPE_ENOMEM;
+  // the codes of the input, channels last whatever the input's layout
+  if (nhwc) rc = launch_quantize_elem(x_dev, n, s_x, b.amax, q8, b.scale, st);
+  else rc = launch_quantize_to_nhwc(x_dev, N, C, H * W, s_x, b.amax, g_act_qmax_host, q8, b.scale, st);
+  if (rc) return rc;
+  rc = launch_depthwise(e, q8, b.scale, N, C, H, W, kh, kw, stride, pad, Ho, Wo, Mm, lo, hi, bias_dev,
+                        reduce_members ? 1 : 0, y_dev, st);
+  if (rc) return rc;
+  return launch_zero_u32(b.amax, 1, st);   // no contraction kernel follows to clear the max slot
 }
 
 extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,

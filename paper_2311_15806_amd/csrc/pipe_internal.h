@@ -109,6 +109,10 @@ struct pipe_expansion {
   // of the orders into members, kept until the expansion is freed.
   std::vector<int32_t> pos_of;       // [K][n_rb] position (in codes_dev) of output row block rb at order k, or -1
   std::vector<PassTables> tables;
+  // dense per-order codes [K][in][out] (int8, tap-major, pruned rows zero) and scales [K][out] of a depthwise layer
+  // (in = kh*kw), built on first use of pipe_forward_depthwise2d
+  int8_t* dw_codes_dev = nullptr;
+  float* dw_scales_dev = nullptr;
   // Stored row blocks of all orders in schedule order: bin b of the weight-streaming kernel owns
   // positions [b*bin_cap, (b+1)*bin_cap), so that kernel addresses its codes from its block index
   // alone; the tiled kernel reaches them through its pass tables.  Unused positions are zero.
@@ -189,6 +193,9 @@ int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int
                             const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                             bool rowsum_is_zero, float* scale_out, hipStream_t st);
 int set_act_qmax(float qmax);   // largest activation code of all quantizers from now on (synchronous copy to the device)
+// every element quantized once, in the input's own layout (scale from s_static or the max slot)
+int launch_quantize_elem(const float* x, int64_t n, float s_static, const uint32_t* amax_bits, int8_t* q8,
+                         float* scale_out, hipStream_t st);
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
                           const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st);
@@ -241,6 +248,14 @@ struct GemmArgs {
     else hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                         \
   } while (0)
 int launch_gemm_tiled(const GemmArgs& a, hipStream_t st);
+// depthwise layers: dense per-order codes and scales (built once), then the forward kernel
+int pipe_depthwise_prepare(pipe_expansion* e, hipStream_t st);
+int launch_quantize_to_nhwc(const float* x, int N, int C, int HW, float s_static, const uint32_t* amax_bits, float qmax,
+                            int8_t* q8, float* scale_out, hipStream_t st);   // fp32 [N,C,H,W] -> int8 codes [N,H,W,C]
+int launch_depthwise(const pipe_expansion* e, const int8_t* q8, const float* s_x, int N, int C, int H, int W, int kh, int kw,
+                     int stride, int pad, int Ho, int Wo, int M, const int* lo, const int* hi,
+                     const float* bias, int reduce, float* y, hipStream_t st);   // q8 channels last
+extern float g_act_qmax_host;   // the activation quantizer's largest code (host copy of the device constant)
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
 extern int g_tiled_mtb;       // token blocks per tile of the tiled kernel; 0 = automatic
 extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic

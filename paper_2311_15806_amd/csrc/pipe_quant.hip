@@ -460,6 +460,16 @@ int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int i
   return PIPE_OK;
 }
 
+int launch_quantize_elem(const float* x, int64_t n, float s_static, const uint32_t* amax_bits, int8_t* q8,
+                         float* scale_out, hipStream_t st) {
+  int64_t blocks = (n + BLK - 1) / BLK;
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits, q8, scale_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
 int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, int kw, int stride,
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, int8_t* q8_scratch, uint8_t* qx_frag,

@@ -60,6 +60,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_error_bound_U(s2, u2, 2, C.byref(U)) == 0 and abs(U.value - ((0.1 + 1) * (0.14 + 1) - 1)) < 1e-15
     assert lib.pipe_error_bound_U(s2, u2, 0, C.byref(U)) == EINVAL
     assert lib.pipe_fold_batchnorm(None, None, None, None, None, None, C.c_float(1e-5), 4, 4, None, None, None) == EINVAL
+    assert lib.pipe_forward_depthwise2d(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, C.c_float(0), None, 0, None, 1, None, None) == EINVAL
     assert lib.pipe_expansion_free(None) == 0
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0

@@ -443,3 +443,39 @@ def test_batchnorm_fold_then_expand(pipe):
     y = pipe.pipe_forward_conv2d(g, dev(x), kh, kw, 1, 1, bias=bf).cpu().numpy()
     assert_close_fp32(y, ref["y"])
     g.free()
+
+
+@pytest.mark.parametrize("C,H,W,kh,kw,stride,pad,bits,K", [
+    (96, 14, 14, 3, 3, 1, 1, 4, 3),     # a MobileNet block
+    (64, 15, 11, 3, 3, 2, 1, 2, 4),     # strided, ragged output size, ternary
+    (48, 9, 9, 5, 5, 1, 2, 8, 2),       # EfficientNet's 5 x 5
+    (32, 12, 12, 7, 7, 2, 3, 3, 3),
+])
+def test_depthwise_conv_parity(pipe, C, H, W, kh, kw, stride, pad, bits, K):
+    N = 3
+    rng = np.random.default_rng(860 + C + kh)
+    Wt = (rng.standard_normal((C, kh * kw)) * math.sqrt(2.0 / (kh * kw))).astype(f32)
+    x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(f32)
+    b = rng.standard_normal(C).astype(f32)
+    spec = wl.LayerSpec(C, kh * kw, bits, K, 0.5, 16)
+    ora = oracle_expand(Wt, spec)
+    g = pipe.pipe_expand(dev(Wt), bits, K, 0.5, 16)
+    assert_expansion_equal(g, ora)
+    split = [1, K - 1]
+    for s_x in (0.0, 0.02):
+        ref = po.forward_depthwise2d(ora, x, kh, kw, stride, pad, s_x=s_x if s_x > 0 else None, split=split, bias=b)
+        y = pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        assert y.shape == ref["y"].shape
+        assert_close_fp32(y, ref["y"])
+        xl = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        yl = pipe.pipe_forward_depthwise2d(g, dev(xl), kh, kw, stride, pad, nhwc=True, s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        assert np.array_equal(y, yl)
+        refm = po.forward_depthwise2d(ora, x, kh, kw, stride, pad, s_x=s_x if s_x > 0 else None, split=split, bias=b,
+                                      reduce_members=False)
+        ym = pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, s_x=s_x, split=split, bias=dev(b),
+                                           reduce_members=False).cpu().numpy()
+        assert_close_fp32(ym, refm["y"])
+    # a dense forward afterwards still works on the same process-wide scratch
+    y2 = pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy()
+    assert np.array_equal(y2, pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy())
+    g.free()
