@@ -76,3 +76,24 @@ def test_binding_names_match_header():
         if n in ("pipe_strerror", "pipe_last_device_error", "pipe_expansion_free", "pipe_expansion_info"):
             continue      # reached through PipeError / Expansion
         assert hasattr(b, n), "binding lacks " + n
+
+
+def test_product_never_reaches_the_checker():
+    """The package (binding, workloads, build) holds no reference to the CPU checker, and the
+    checker none to the package: they share only the seeded input generators, which hold no
+    arithmetic of the method."""
+    pkg = os.path.join(ROOT, "paper_2311_15806_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert "oracle" not in src.lower(), "%s mentions the checker" % f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            src = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2311_15806_amd" not in src and "ctypes" not in src
+    wl = open(os.path.join(pkg, "workloads.py")).read()
+    for word in ("rint", "clip", "quantize(", "expand("):
+        assert word not in wl, "the input generators must hold none of the method's arithmetic"
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    assert bench.count("from oracle import") == 1 and "if not args.no_cpu" in bench
