@@ -498,12 +498,36 @@ class ChainLayer:
     skip_from    -1: no skip; j >= 0: add the tensor that ENTERED layer j (0-based;
                  j = 0 is the network input, j <= this layer's index), as in the residual
                  network of Fig. 2
-    skip_pre_act True: a = act(z + r) (ResNet block); False: a = act(z) + r"""
+    skip_pre_act True: a = act(z + r) (ResNet block); False: a = act(z) + r
+    kh, kw, stride, pad   kh = 0: a fully-connected layer applied to every token; kh > 0: a
+                 convolution over the [N, H, W] grid the tokens form (tensors are channels
+                 last, tokens ordered (n, h, w)), exp built from W [O, C*kh*kw]"""
     exp: Expansion
     bias: Optional[np.ndarray] = None
     act: str = "none"
     skip_from: int = -1
     skip_pre_act: bool = True
+    kh: int = 0
+    kw: int = 0
+    stride: int = 1
+    pad: int = 0
+
+
+def chain_layer_acc(layer: ChainLayer, Qa: np.ndarray, grid):
+    """Integer accumulators [K, T', O] of one layer on codes Qa [T, C] whose tokens form the
+    grid (N, H, W); returns them with the output grid.  A fully-connected layer keeps the grid."""
+    exp = layer.exp
+    if layer.kh == 0:
+        return forward_acc(exp, Qa), grid
+    N, H, W = grid
+    C = Qa.shape[1]
+    Qn = Qa.reshape(N, H, W, C).transpose(0, 3, 1, 2)
+    Ho, Wo = conv_out_size(H, W, layer.kh, layer.kw, layer.stride, layer.pad)
+    acc = np.zeros((exp.K, N * Ho * Wo, exp.out_features), dtype=np.int32)
+    for k in range(1, exp.K + 1):
+        acc[k - 1][:, exp.rows(k)] = conv2d_acc_direct(Qn, exp.orders[k - 1].codes, layer.kh, layer.kw,
+                                                        layer.stride, layer.pad)
+    return acc, (N, Ho, Wo)
 
 
 def relu(v: np.ndarray) -> np.ndarray:
@@ -511,12 +535,14 @@ def relu(v: np.ndarray) -> np.ndarray:
 
 
 def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: bool, skips,
-                        split=None, s_x: Optional[float] = None, act_bits: int = 8) -> np.ndarray:
+                        split=None, s_x: Optional[float] = None, act_bits: int = 8, grid=None) -> np.ndarray:
     """One layer for all members.  inputs: [T, I] when every member reads the same tensor
     (the network input; s_x is its static scale if given), else [M, T, I] and member m
     quantizes inputs[m] with its own dynamic scale.  Member m contracts with its own orders
     only; the bias goes to the first member.  skips: None, or a list of M entries (an array
-    [T, O] or None) added before or after the activation.  Returns [M, T, O] fp32."""
+    [T, O] or None) added before or after the activation.  grid = (N, H, W) of the tokens
+    (needed by convolution layers; default: T tokens, no spatial extent).
+    Returns [M, T', O] fp32."""
     exp = layer.exp
     rngs = member_ranges(exp.K, split)
     M = len(rngs)
@@ -524,7 +550,7 @@ def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: boo
     for m in range(M):
         xin = inputs if shared_input else inputs[m]
         Qa, sa = quantize_activations(xin, s_x if shared_input else None, act_bits)
-        acc = forward_acc(exp, Qa)
+        acc, _ = chain_layer_acc(layer, Qa, grid if grid is not None else (Qa.shape[0], 1, 1))
         z = dequantize(exp, acc, sa, split, layer.bias, f32)[m]
         r = None if skips is None else skips[m]
         if r is not None and layer.skip_pre_act:
@@ -557,15 +583,27 @@ def chain_skips(layers: Sequence[ChainLayer], l: int, x: np.ndarray, acts: Seque
     return [acts[j - 1][m] for m in range(M)]
 
 
+def chain_grids(layers: Sequence[ChainLayer], grid):
+    """The token grid (N, H, W) entering every layer, and the one leaving the last."""
+    grids = [tuple(grid)]
+    for ly in layers:
+        N, H, W = grids[-1]
+        if ly.kh > 0:
+            H, W = conv_out_size(H, W, ly.kh, ly.kw, ly.stride, ly.pad)
+        grids.append((N, H, W))
+    return grids
+
+
 def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: Optional[float] = None,
-                  act_bits: int = 8):
+                  act_bits: int = 8, grid=None):
     """M member chains through L expanded layers, summed after the last one.
 
     Member m is the whole architecture with, in every layer, only the orders of its own
     cluster; it quantizes each hidden activation with its own dynamic per-tensor scale;
     biases (and a skip from the network input) belong to the first member.  The last
-    layer has no activation of its own (act must be "none").
-    Returns dict(y [T, O_L], members [M, T, O_L], acts: list of L-1 arrays [M, T, O_l])."""
+    layer has no activation of its own (act must be "none").  x is [T, C]; with convolution
+    layers its tokens form grid = (N, H, W), ordered (n, h, w) (a channels-last image).
+    Returns dict(y [T_L, O_L], members [M, T_L, O_L], acts: list of L-1 arrays [M, T_l, O_l])."""
     L = len(layers)
     if L < 1:
         raise ValueError("at least one layer")
@@ -575,13 +613,15 @@ def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: 
     if layers[-1].act != "none":
         raise ValueError("the last layer has no activation")
     M = len(member_ranges(K, split))
+    x = np.asarray(x, dtype=f32)
+    grids = chain_grids(layers, grid if grid is not None else (x.shape[0], 1, 1))
     acts: List[np.ndarray] = []
     for l, ly in enumerate(layers):
         skips = chain_skips(layers, l, x, acts, M)
         if l == 0:
-            a = chain_layer_members(ly, np.asarray(x, dtype=f32), True, skips, split, s_x, act_bits)
+            a = chain_layer_members(ly, x, True, skips, split, s_x, act_bits, grids[0])
         else:
-            a = chain_layer_members(ly, acts[l - 1], False, skips, split, None, act_bits)
+            a = chain_layer_members(ly, acts[l - 1], False, skips, split, None, act_bits, grids[l])
         acts.append(a)
     members = acts.pop()
     return dict(y=sum_members(members), members=members, acts=acts)

@@ -578,6 +578,48 @@ def test_chain_members_are_independent_networks():
     assert np.allclose(r["members"][0], one["y"], rtol=1e-5, atol=1e-7)
 
 
+def test_conv_chain_is_layer_by_layer_conv_and_converges_to_torch():
+    """A residual conv stack as member chains: with one member it is the pinned conv forward
+    applied layer by layer (ReLU, skip); with 8-bit orders it reproduces torch's fp64 ConvNet."""
+    rng = np.random.default_rng(87)
+    N, H, W, C = 2, 8, 8, 8
+    geo = [(16, C, 3, 1, 1), (16, 16, 3, 1, 1), (16, 16, 3, 1, 1), (24, 16, 3, 2, 1), (16, 24, 1, 1, 0)]   # O, Cin, k, stride, pad
+    Ws = [(rng.standard_normal((o, c * k * k)) * math.sqrt(2.0 / (c * k * k))).astype(f32) for o, c, k, _, _ in geo]
+    bs = [(0.5 * rng.standard_normal(o)).astype(f32) for o, *_ in geo]
+    acts = ["relu", "relu", "relu", "relu", "none"]
+    skip = [-1, -1, 1, -1, -1]          # layer 2 adds the tensor that entered layer 1: a residual block
+    x = rng.standard_normal((N, C, H, W)).astype(f32)
+    xt = np.ascontiguousarray(x.transpose(0, 2, 3, 1)).reshape(N * H * W, C)
+
+    def layers(bits, K):
+        return [po.ChainLayer(po.expand(Wl, bits, K, 1.0, 8), b, a, sk, True, k, k, st, pd)
+                for Wl, b, a, sk, (o, c, k, st, pd) in zip(Ws, bs, acts, skip, geo)]
+
+    # one member, 4-bit: composition of the pinned single-layer conv forward
+    L4 = layers(4, 2)
+    r = po.chain_forward(L4, xt, grid=(N, H, W))
+    to_nchw = lambda a, g: a.reshape(g[0], g[1], g[2], -1).transpose(0, 3, 1, 2)
+    grids = po.chain_grids(L4, (N, H, W))
+    a0 = np.maximum(po.forward_conv2d(L4[0].exp, x, 3, 3, 1, 1, bias=bs[0])["y"], 0)
+    a1 = np.maximum(po.forward_conv2d(L4[1].exp, to_nchw(a0, grids[1]), 3, 3, 1, 1, bias=bs[1])["y"], 0)
+    a2 = np.maximum((po.forward_conv2d(L4[2].exp, to_nchw(a1, grids[2]), 3, 3, 1, 1, bias=bs[2])["y"] + a0).astype(f32), 0)
+    assert np.array_equal(r["acts"][0][0], a0) and np.array_equal(r["acts"][1][0], a1) and np.array_equal(r["acts"][2][0], a2)
+    assert grids[-1] == (N, 4, 4) and r["y"].shape == (N * 16, 16)
+    # 8-bit, K = 4, two members: torch's ConvNet up to the activation grid
+    t = lambda a: torch.from_numpy(np.asarray(a)).double()
+    h = t(x)
+    saved = {}
+    for l, (Wl, b, (o, c, k, st, pd)) in enumerate(zip(Ws, bs, geo)):
+        saved[l] = h
+        z = torch.nn.functional.conv2d(h, t(Wl).reshape(o, c, k, k), t(b), stride=st, padding=pd)
+        if skip[l] >= 0:
+            z = z + saved[skip[l]]
+        h = torch.relu(z) if acts[l] == "relu" else z
+    ref = h.permute(0, 2, 3, 1).reshape(-1, 16).numpy()
+    r8 = po.chain_forward(layers(8, 4), xt, split=[2, 2], grid=(N, H, W))
+    assert np.abs(r8["y"] - ref).max() < 0.03 * np.abs(ref).max()
+
+
 # ---------------------------------------------------------------- App. C: diagnostics
 def test_spectral_norm_against_svd_and_closed_forms():
     rng = np.random.default_rng(90)
