@@ -155,14 +155,20 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
                      const float* bias1_dev, const float* bias2_dev, float* h_dev,
                      float* y_dev, void* stream);
 
-/* One layer of a member chain (pipe_chain_forward).                             */
+/* One layer of a member chain (pipe_chain_forward, pipe_chain_forward_conv).     */
 typedef struct pipe_chain_layer {
-  const pipe_expansion* e; /* [out_l, in_l]; in_l = width of the tensor entering it   */
+  const pipe_expansion* e; /* [out_l, in_l]; in_l = width of the tensor entering it,
+                              or C_l*kh*kw (a row flattened as [C, kh, kw], as for
+                              pipe_forward_conv2d) for a convolution                 */
   const float* bias_dev;   /* DEVICE, NULL or [out_l]; first member only              */
   int act;                 /* PIPE_ACT_NONE, PIPE_ACT_RELU or PIPE_ACT_GELU (erf)     */
   int skip_from;           /* -1: no skip; j in 0..l: add the tensor that ENTERED
                               layer j (0 = the network input), width out_l          */
   int skip_pre_act;        /* 1: a = act(z + r) (residual block); 0: a = act(z) + r   */
+  int kh, kw;              /* 0, 0: fully connected, applied at every grid position;
+                              else the kernel size of a convolution over the grid    */
+  int stride, pad;         /* of the convolution (stride >= 1, pad >= 0); ignored when
+                              kh = kw = 0                                            */
 } pipe_chain_layer;
 
 /* An L-layer feed-forward network run as M independent member chains that are
@@ -185,6 +191,22 @@ typedef struct pipe_chain_layer {
 int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
                        float s_x, const int* split, int M, float* const* acts_dev,
                        float* y_dev, void* stream);
+
+/* The same member chains over convolution layers (Fig. 2 draws the expansion of a
+ * convolutional network; Sec. 4 evaluates ResNets and MobileNets).  Every tensor is
+ * channels-last: tokens are the positions (n, h, w) of an N x H_l x W_l grid in that
+ * order, x_dev is [N, H, W, C_0].  A layer with kh, kw > 0 is a convolution (the
+ * contraction of pipe_forward_conv2d over the member's quantized tensor) and maps the
+ * grid to H_{l+1} = (H_l + 2 pad - kh) / stride + 1, likewise W; a layer with
+ * kh = kw = 0 keeps the grid (a 1x1 convolution, or a classifier when the grid is
+ * N x 1 x 1).  A skip needs equal grids and channel counts at both ends.
+ *   acts_dev entry l: NULL or [M, N*H_{l+1}*W_{l+1}, out_l];  y_dev [N*H_L*W_L, out_{L-1}]
+ * pipe_chain_forward is this call on a T x 1 x 1 grid and rejects convolution layers
+ * (PIPE_EINVAL).  Further errors: PIPE_ESHAPE (kernel larger than the padded grid,
+ * in_l not a multiple of kh*kw, grids of a skip differ).                            */
+int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, const float* x_dev,
+                            int N, int H, int W, float s_x, const int* split, int M,
+                            float* const* acts_dev, float* y_dev, void* stream);
 
 /* Bit-width a of the activation quantizer of every forward entry point from now on
  * (Sec. 4 compares W4/A4, W4/A6, W8/A8): Q(x) = clamp(rint(x / s_x), +-(2^(a-1)-1)),

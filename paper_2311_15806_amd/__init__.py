@@ -8,7 +8,7 @@ from . import workloads  # noqa: F401
 
 _BINDING_NAMES = (
     "Expansion", "PipeError", "pipe_expand", "pipe_expansion_order", "pipe_forward", "pipe_forward_acc",
-    "pipe_forward_conv2d", "pipe_mlp_forward", "pipe_chain_forward", "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read", "PIPE_ACT_NONE", "PIPE_ACT_GELU", "PIPE_ACT_SILU_GATED", "PIPE_ACT_RELU",
+    "pipe_forward_conv2d", "pipe_mlp_forward", "pipe_chain_forward", "pipe_chain_forward_conv", "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read", "PIPE_ACT_NONE", "PIPE_ACT_GELU", "PIPE_ACT_SILU_GATED", "PIPE_ACT_RELU",
 )
 
 

@@ -49,6 +49,7 @@ def _load():
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
+    lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_set_kernel.argtypes = [ci]
     lib.pipe_fold_batchnorm.argtypes = [vp] * 6 + [cf, ci, ci, vp, vp, vp]
     lib.pipe_spectral_norm.argtypes = [vp, ci, ci, ci, C.POINTER(cf), vp]
@@ -249,7 +250,18 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
 
 class _ChainLayer(C.Structure):
     _fields_ = [("e", C.c_void_p), ("bias_dev", C.c_void_p), ("act", C.c_int), ("skip_from", C.c_int),
-                ("skip_pre_act", C.c_int)]
+                ("skip_pre_act", C.c_int), ("kh", C.c_int), ("kw", C.c_int), ("stride", C.c_int), ("pad", C.c_int)]
+
+
+def _chain_layers(layers):
+    """(Expansion, bias or None, act, skip_from, skip_pre_act[, kh, kw, stride, pad]) -> C array."""
+    arr = (_ChainLayer * len(layers))()
+    for l, ly in enumerate(layers):
+        e, bias, act, skip_from, pre = ly[:5]
+        kh, kw, stride, pad = ly[5:9] if len(ly) >= 9 else (0, 0, 1, 0)
+        arr[l] = _ChainLayer(e.handle, _ptr(bias, torch.float32), int(act), int(skip_from), 1 if pre else 0,
+                             int(kh), int(kw), int(stride), int(pad))
+    return arr
 
 
 def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, return_acts: bool = False,
@@ -258,9 +270,7 @@ def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, re
     T = x.shape[0]
     L = len(layers)
     M = 1 if split is None else len(split)
-    arr_l = (_ChainLayer * L)()
-    for l, (e, bias, act, skip_from, pre) in enumerate(layers):
-        arr_l[l] = _ChainLayer(e.handle, _ptr(bias, torch.float32), int(act), int(skip_from), 1 if pre else 0)
+    arr_l = _chain_layers(layers)
     y = out if out is not None else torch.empty((T, layers[-1][0].out_features), dtype=torch.float32, device=x.device)
     acts, acts_arr = None, None
     if return_acts and L > 1:
@@ -270,6 +280,35 @@ def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, re
     arr, m = _split(split)
     _check(_lib.pipe_chain_forward(arr_l, L, _ptr(x, torch.float32), T, float(s_x), arr, m, acts_arr, _ptr(y),
                                    _stream()), "pipe_chain_forward")
+    return (y, acts) if return_acts else y
+
+
+def pipe_chain_forward_conv(layers, x: torch.Tensor, s_x: float = 0.0, split=None, return_acts: bool = False,
+                            out: Optional[torch.Tensor] = None):
+    """x [N, H, W, C] channels-last; layers: (Expansion, bias or None, act, skip_from, skip_pre_act, kh, kw,
+    stride, pad), kh = kw = 0 for a layer applied per grid position.  Returns y [N, H_L, W_L, out] (and the
+    tensors leaving layers 0..L-2 as [M, N, H_l, W_l, out_l])."""
+    N, H, W, _ = x.shape
+    L = len(layers)
+    M = 1 if split is None else len(split)
+    arr_l = _chain_layers(layers)
+    grids = []
+    h, w = H, W
+    for l in range(L):
+        if arr_l[l].kh > 0 and arr_l[l].kw > 0 and arr_l[l].stride > 0:
+            h = (h + 2 * arr_l[l].pad - arr_l[l].kh) // arr_l[l].stride + 1
+            w = (w + 2 * arr_l[l].pad - arr_l[l].kw) // arr_l[l].stride + 1
+        grids.append((max(h, 0), max(w, 0)))
+    shape_y = (N,) + grids[-1] + (layers[-1][0].out_features,)
+    y = out if out is not None else torch.empty(shape_y, dtype=torch.float32, device=x.device)
+    acts, acts_arr = None, None
+    if return_acts and L > 1:
+        acts = [torch.empty((M, N) + grids[l] + (layers[l][0].out_features,), dtype=torch.float32, device=x.device)
+                for l in range(L - 1)]
+        acts_arr = (C.c_void_p * (L - 1))(*[_ptr(a) for a in acts])
+    arr, m = _split(split)
+    _check(_lib.pipe_chain_forward_conv(arr_l, L, _ptr(x, torch.float32), N, H, W, float(s_x), arr, m, acts_arr,
+                                        _ptr(y), _stream()), "pipe_chain_forward_conv")
     return (y, acts) if return_acts else y
 
 

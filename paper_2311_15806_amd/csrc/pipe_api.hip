@@ -767,36 +767,61 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
 }
 
 // ------------------------------------------------------------------ member chains
-extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T, float s_x,
-                                  const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
-  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
+// Tokens form an N x H x W grid (channels-last tensors); a fully-connected layer keeps the grid,
+// a convolution layer maps it to its output grid.
+static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float* x_dev, int N, int H0, int W0,
+                              float s_x, const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || N < 0 || H0 < 1 || W0 < 1) return PIPE_EINVAL;
+  std::vector<int> Hin(L + 1), Win(L + 1), Cin(L);
+  std::vector<int64_t> Tin(L + 1);
+  Hin[0] = H0; Win[0] = W0; Tin[0] = (int64_t)N * H0 * W0;
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
     if (!ly.e) return PIPE_EINVAL;
     if (ly.act != PIPE_ACT_NONE && ly.act != PIPE_ACT_RELU && ly.act != PIPE_ACT_GELU) return PIPE_EINVAL;
     if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
     if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;
-    if (l > 0 && ly.e->in != layers[l - 1].e->out) return PIPE_ESHAPE;
-    // the tensor that entered layer j is in_j wide
-    if (ly.skip_from >= 0 && layers[ly.skip_from].e->in != ly.e->out) return PIPE_ESHAPE;
+    if (ly.kh < 0 || ly.kw < 0 || (ly.kh == 0) != (ly.kw == 0)) return PIPE_EINVAL;
+    if (ly.kh == 0) {
+      Cin[l] = ly.e->in; Hin[l + 1] = Hin[l]; Win[l + 1] = Win[l];
+    } else {
+      if (ly.stride < 1 || ly.pad < 0 || ly.e->in % (ly.kh * ly.kw) != 0) return PIPE_ESHAPE;
+      if (Hin[l] + 2 * ly.pad < ly.kh || Win[l] + 2 * ly.pad < ly.kw) return PIPE_ESHAPE;
+      Cin[l] = ly.e->in / (ly.kh * ly.kw);
+      Hin[l + 1] = (Hin[l] + 2 * ly.pad - ly.kh) / ly.stride + 1;
+      Win[l + 1] = (Win[l] + 2 * ly.pad - ly.kw) / ly.stride + 1;
+    }
+    Tin[l + 1] = (int64_t)N * Hin[l + 1] * Win[l + 1];
+    if (Tin[l + 1] > (int64_t)1 << 30) return PIPE_ESHAPE;
+    if (l > 0 && Cin[l] != layers[l - 1].e->out) return PIPE_ESHAPE;
+    // the tensor that entered layer j is [Tin_j, Cin_j]; a skip adds it to this layer's output
+    if (ly.skip_from >= 0 && (Cin[ly.skip_from] != ly.e->out || Tin[ly.skip_from] != Tin[l + 1])) return PIPE_ESHAPE;
   }
   if (layers[L - 1].act != PIPE_ACT_NONE) return PIPE_EINVAL;
   const int K = layers[0].e->K;
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(K, split, M, lo, hi, &Mm);
   if (rc) return rc;
-  if (T == 0) return PIPE_OK;
+  if (N == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(layers[0].e, T);   // same K everywhere: one decision
-  int in_pad_max = 0;
-  for (int l = 1; l < L; ++l) in_pad_max = std::max(in_pad_max, layers[l].e->in_pad);
+  // per layer: the contraction's token count is the layer's output grid
+  std::vector<char> small(L);
+  std::vector<int> Tpad(L);
+  int T_pad_max = 0;
+  size_t qh_bytes = 0, q8_bytes = 0;
+  for (int l = 0; l < L; ++l) {
+    small[l] = use_stream_kernel(layers[l].e, (int)Tin[l + 1]);
+    Tpad[l] = (int)round_up64(Tin[l + 1], small[l] ? 16 : TOK_TILE);
+    T_pad_max = std::max(T_pad_max, Tpad[l]);
+    if (l > 0) qh_bytes = std::max(qh_bytes, (size_t)Mm * Tpad[l] * layers[l].e->in_pad);
+    if (layers[l].kh > 0) q8_bytes = std::max(q8_bytes, (size_t)Tin[l] * Cin[l]);
+  }
   ActBuffers b;
-  rc = get_act_buffers(T, layers[0].e->in_pad, small, &b);
+  rc = get_act_buffers((int)Tin[1], layers[0].e->in_pad, small[0], &b);
   if (rc) return rc;
-  const int T_pad = b.T_pad;
 
-  // Tensors leaving layers 0..L-2, [M, T, out_l] each.  Tensor l lives until its last reader:
+  // Tensors leaving layers 0..L-2, [M, T_l, out_l] each.  Tensor l lives until its last reader:
   // layer l+1, or a later layer whose skip reads it.  Those the caller did not give a buffer
   // for share a pool of equal slabs.
   std::vector<float*> act(L > 1 ? L - 1 : 0, nullptr);
@@ -807,18 +832,18 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
       last[l] = l + 1;
       for (int j = l + 1; j < L; ++j)
         if (layers[j].skip_from == l + 1) last[l] = j;
-      if (!(acts_dev && acts_dev[l])) slab_floats = std::max(slab_floats, (size_t)Mm * T * layers[l].e->out);
+      if (!(acts_dev && acts_dev[l])) slab_floats = std::max(slab_floats, (size_t)Mm * Tin[l + 1] * layers[l].e->out);
     }
     slab_floats = (slab_floats + 63) & ~(size_t)63;
     std::vector<int> busy_until;   // per slab: the last layer that reads its tensor
     for (int l = 0; l + 1 < L; ++l) {
       if (acts_dev && acts_dev[l]) continue;
-      int s = -1;
+      int sl = -1;
       for (size_t i = 0; i < busy_until.size(); ++i)
-        if (busy_until[i] < l) { s = (int)i; break; }   // its last reader ran before layer l writes
-      if (s < 0) { s = (int)busy_until.size(); busy_until.push_back(0); }
-      busy_until[s] = last[l];
-      slab[l] = s;
+        if (busy_until[i] < l) { sl = (int)i; break; }   // its last reader ran before layer l writes
+      if (sl < 0) { sl = (int)busy_until.size(); busy_until.push_back(0); }
+      busy_until[sl] = last[l];
+      slab[l] = sl;
     }
     float* pool = nullptr;
     if (!busy_until.empty()) {
@@ -829,14 +854,19 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
   }
   uint8_t* qh = nullptr;
   int32_t* rowsum_h = nullptr;
+  int8_t* q8 = nullptr;
   if (L > 1) {
-    qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * in_pad_max);
-    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)2 * Mm * T_pad * 4);
+    qh = (uint8_t*)pipe_ws_get(WS_QH, qh_bytes);
+    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)2 * Mm * T_pad_max * 4);
     if (!qh || !rowsum_h) return PIPE_ENOMEM;
+  }
+  if (q8_bytes) {
+    q8 = (int8_t*)pipe_ws_get(WS_Q8X, q8_bytes);
+    if (!q8) return PIPE_ENOMEM;
   }
   // code sums of the members' quantized inputs, two buffers used in turn: the quantizer of layer l
   // adds into buffer l & 1, which the contraction of layer l-1 cleared (it reads the other one)
-  int32_t* rs_buf[2] = {rowsum_h, rowsum_h ? rowsum_h + (size_t)Mm * T_pad : nullptr};
+  int32_t* rs_buf[2] = {rowsum_h, rowsum_h ? rowsum_h + (size_t)Mm * T_pad_max : nullptr};
   // max|tensor| per member, two sets used in turn: layer l writes set l & 1 in its epilogue, the
   // quantizer of layer l+1 reads it, and the contraction of layer l+1 clears it again
   uint32_t* amax_set[2] = {b.amax + 16, b.amax + 16 + PIPE_MAX_K};
@@ -847,16 +877,26 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
   }
   g_amax_h_dirty = true;
 
-  rc = quantize_input(x_dev, T, layers[0].e->in, layers[0].e->in_pad, s_x, b, small, nullptr, b.scale, st);
-  if (rc) return rc;
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
     const pipe_expansion* e = ly.e;
-    const bool last_layer = l == L - 1;
+    const bool last_layer = l == L - 1, conv = ly.kh > 0;
+    const int T = (int)Tin[l + 1], T_pad = Tpad[l];
     GemmArgs a{};
     a.e = e; a.T = T; a.T_pad = T_pad;
     if (l == 0) {
       // every member reads the same Q(x)
+      if (conv) {
+        if (!(s_x > 0.f)) {
+          rc = launch_absmax(x_dev, Tin[0] * Cin[0], b.amax, nullptr, 0, st);
+          if (rc) return rc;
+        }
+        rc = launch_quantize_im2col(x_dev, N, Cin[0], Hin[0], Win[0], ly.kh, ly.kw, ly.stride, ly.pad, 1, Hin[1], Win[1],
+                                    e->in_pad, T_pad, s_x, b.amax, q8, b.qx, b.rowsum, b.scale, st);
+      } else {
+        rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small[0], nullptr, b.scale, st);
+      }
+      if (rc) return rc;
       a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale; a.zero_after = b.amax;
     } else {
       // each member quantizes its own tensor with its own scale
@@ -864,21 +904,33 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
       const int in = e->in;
       uint32_t* amax_in = amax_set[(l - 1) & 1];
       int32_t* rs_in = rs_buf[l & 1];
-      if (small && T <= PIPE_QUANT1_MAX_T) {
-        rc = launch_quantize_small(src, (int64_t)T * in, Mm, T, in, e->in_pad, 0.f, amax_in, qh, (int64_t)T_pad * e->in_pad,
-                                   rs_in, nullptr, scale_h, st);
+      const int64_t q_ms = (int64_t)T_pad * e->in_pad;
+      if (conv) {
+        for (int m = 0; m < Mm; ++m) {
+          rc = launch_quantize_im2col(src + (size_t)m * Tin[l] * Cin[l], N, Cin[l], Hin[l], Win[l], ly.kh, ly.kw, ly.stride,
+                                      ly.pad, 1, Hin[l + 1], Win[l + 1], e->in_pad, T_pad, 0.f, amax_in + m, q8,
+                                      qh + (size_t)m * q_ms, rs_in + (size_t)m * T_pad_max, scale_h + m, st);
+          if (rc) return rc;
+        }
+      } else if (small[l] && T <= PIPE_QUANT1_MAX_T && T_pad == T_pad_max) {
+        rc = launch_quantize_small(src, (int64_t)T * in, Mm, T, in, e->in_pad, 0.f, amax_in, qh, q_ms, rs_in, nullptr, scale_h, st);
+        if (rc) return rc;
+      } else if (T_pad == T_pad_max) {
+        rc = launch_quantize_members(src, (int64_t)T * in, Mm, T, in, e->in_pad, T_pad, amax_in, qh, q_ms, rs_in, true, scale_h, st);
         if (rc) return rc;
       } else {
-        rc = launch_quantize_members(src, (int64_t)T * in, Mm, T, in, e->in_pad, T_pad, amax_in, qh,
-                                     (int64_t)T_pad * e->in_pad, rs_in, true, scale_h, st);
-        if (rc) return rc;
+        for (int m = 0; m < Mm; ++m) {
+          rc = launch_quantize_act(src + (size_t)m * T * in, T, in, e->in_pad, T_pad, 0.f, amax_in + m, qh + (size_t)m * q_ms,
+                                   rs_in + (size_t)m * T_pad_max, true, nullptr, scale_h + m, st);
+          if (rc) return rc;
+        }
       }
-      a.qx = qh; a.qx_mstride = (int64_t)T_pad * e->in_pad;
-      a.rowsum = rs_in; a.rowsum_mstride = T_pad;
+      a.qx = qh; a.qx_mstride = q_ms;
+      a.rowsum = rs_in; a.rowsum_mstride = T_pad_max;
       a.s_x = scale_h; a.sx_mstride = 1;
       a.zero_after = amax_in; a.zero_n = Mm;
     }
-    if (!last_layer) { a.zero_big = reinterpret_cast<uint32_t*>(rs_buf[(l + 1) & 1]); a.zero_big_n = Mm * T_pad; }
+    if (!last_layer && rs_buf[0]) { a.zero_big = reinterpret_cast<uint32_t*>(rs_buf[(l + 1) & 1]); a.zero_big_n = Mm * T_pad_max; }
     a.bias = ly.bias_dev;
     a.act = ly.act;
     if (ly.skip_from == 0) {
@@ -893,10 +945,24 @@ extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const f
       a.reduce = 0; a.y = act[l]; a.amax_out = amax_set[l & 1];
     }
     fill_members(a, Mm, lo, hi);
-    rc = run_gemm(a, small, st);
+    rc = run_gemm(a, small[l], st);
     if (rc) return rc;
   }
   // the last layer cleared the set it read; the other set was cleared one layer earlier
   g_amax_h_dirty = false;
   return PIPE_OK;
+}
+
+extern "C" int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev, int T, float s_x,
+                                  const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
+  for (int l = 0; l < L; ++l)
+    if (layers[l].kh != 0 || layers[l].kw != 0) return PIPE_EINVAL;   // convolution layers need the grid: pipe_chain_forward_conv
+  return chain_forward_grid(layers, L, x_dev, T, 1, 1, s_x, split, M, acts_dev, y_dev, stream);
+}
+
+extern "C" int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, const float* x_dev, int N, int H, int W,
+                                       float s_x, const int* split, int M, float* const* acts_dev, float* y_dev,
+                                       void* stream) {
+  return chain_forward_grid(layers, L, x_dev, N, H, W, s_x, split, M, acts_dev, y_dev, stream);
 }

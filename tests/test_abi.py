@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"pipe_expand", "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
-            "pipe_chain_forward", "pipe_expansion_order", "pipe_expansion_free", "pipe_strerror"} <= set(names)
+            "pipe_chain_forward", "pipe_chain_forward_conv", "pipe_expansion_order", "pipe_expansion_free", "pipe_strerror"} <= set(names)
     for n in names:
         assert hasattr(lib, n), "missing symbol " + n
 
@@ -52,6 +52,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_forward(None, None, 4, C.c_float(0), None, 0, None, 1, None, None) == EINVAL
     assert lib.pipe_chain_forward(None, 1, None, 4, C.c_float(0), None, 0, None, None, None) == EINVAL
     assert lib.pipe_chain_forward(fake, 0, None, 4, C.c_float(0), None, 0, None, None, None) == EINVAL
+    assert lib.pipe_chain_forward_conv(None, 1, None, 1, 4, 4, C.c_float(0), None, 0, None, None, None) == EINVAL
     assert lib.pipe_spectral_norm(None, 4, 4, 3, None, None) == EINVAL
     assert lib.pipe_expansion_reconstruct(None, 1, None, None) == EINVAL
     assert lib.pipe_expansion_error_bound(None, None, None) == EINVAL

@@ -146,3 +146,89 @@ def test_full_width_stack_in_the_benchmark_launch_configuration(pipe):
         pipe.pipe_set_token_tile(0)
     for g in gpu:
         g.free()
+
+
+def _conv_stack(pipe, geo, acts, skips, bits, K, gamma, group, seed):
+    """geo: per layer (O, C_in, k, stride, pad), k = 0 for a layer applied per grid position."""
+    rng = np.random.default_rng(seed)
+    olayers, glayers, gpu = [], [], []
+    for (o, c, k, st, pd), a, sk in zip(geo, acts, skips):
+        cols = c * max(k, 1) ** 2
+        Wl = (rng.standard_normal((o, cols)) * np.sqrt(2.0 / cols)).astype(np.float32)
+        b = (0.3 * rng.standard_normal(o)).astype(np.float32)
+        spec = wl.LayerSpec(o, cols, bits, K, gamma, group)
+        oe = oracle_expand(Wl, spec)
+        ge = pipe.pipe_expand(dev(Wl), bits, K, gamma, group)
+        assert_expansion_equal(ge, oe)
+        olayers.append(po.ChainLayer(oe, b, a, sk, True, k, k, st, pd))
+        glayers.append((ge, dev(b), ACT[a], sk, True, k, k, st, pd))
+        gpu.append(ge)
+    return olayers, glayers, gpu
+
+
+@pytest.mark.parametrize("N,H,W", [(2, 12, 12), (1, 5, 7)])
+@pytest.mark.parametrize("bits,K,split", [(4, 4, [2, 2]), (2, 4, [1, 3]), (8, 2, None)])
+def test_conv_residual_stack_parity(pipe, bits, K, split, N, H, W):
+    """A ResNet-like stack as member chains (Fig. 2): 3x3 stem, a residual block of two 3x3
+    convolutions, a strided 3x3 convolution that changes the grid, a 1x1 projection given as a
+    convolution and one given as a per-position layer; teacher-forced layer by layer, then
+    free-running.  Grids of 288/72 and 35/12 tokens exercise both contraction kernels."""
+    C0 = 16
+    geo = [(32, C0, 3, 1, 1), (32, 32, 3, 1, 1), (32, 32, 3, 1, 1), (48, 32, 3, 2, 1), (32, 48, 1, 1, 0), (16, 32, 0, 1, 0)]
+    acts = ["relu", "relu", "relu", "relu", "gelu", "none"]
+    skips = [-1, -1, 1, -1, -1, -1]
+    olayers, glayers, gpu = _conv_stack(pipe, geo, acts, skips, bits, K, 0.5, 16, seed=300 + bits)
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal((N, H, W, C0)).astype(np.float32)
+    xt = x.reshape(N * H * W, C0)
+    y, acts_g = pipe.pipe_chain_forward_conv(glayers, dev(x), split=split, return_acts=True)
+    grids = po.chain_grids(olayers, (N, H, W))
+    assert tuple(y.shape) == (N, grids[-1][1], grids[-1][2], 16)
+    y = y.cpu().numpy().reshape(-1, 16)
+    acts_g = [a.cpu().numpy().reshape(a.shape[0], -1, a.shape[-1]) for a in acts_g]
+    M = 1 if split is None else len(split)
+    L = len(olayers)
+    for l in range(L):
+        sk = po.chain_skips(olayers, l, xt, acts_g, M)
+        if l == 0:
+            ref = po.chain_layer_members(olayers[0], xt, True, sk, split, None, 8, grids[0])
+        else:
+            ref = po.chain_layer_members(olayers[l], acts_g[l - 1], False, sk, split, None, 8, grids[l])
+        if l < L - 1:
+            assert acts_g[l].shape == ref.shape, (l, acts_g[l].shape, ref.shape)
+            for m in range(M):
+                assert_close_fp32(acts_g[l][m], ref[m], tol=2e-5)
+        else:
+            assert_close_fp32(y, po.sum_members(ref))
+    full = po.chain_forward(olayers, xt, split=split, grid=(N, H, W))
+    assert_close_fp32(y, full["y"], tol=3e-2, elementwise=False)
+    # a static input scale, and the same chain again (slots left clean by the first call)
+    y2 = pipe.pipe_chain_forward_conv(glayers, dev(x), split=split).cpu().numpy().reshape(-1, 16)
+    assert np.array_equal(y, y2)
+    ys = pipe.pipe_chain_forward_conv(glayers, dev(x), s_x=0.04, split=split).cpu().numpy().reshape(-1, 16)
+    fs = po.chain_forward(olayers, xt, split=split, s_x=0.04, grid=(N, H, W))
+    assert_close_fp32(ys, fs["y"], tol=3e-2, elementwise=False)
+    for g in gpu:
+        g.free()
+
+
+def test_conv_chain_argument_errors(pipe):
+    geo = [(32, 16, 3, 1, 1), (32, 32, 3, 2, 1), (16, 32, 0, 1, 0)]
+    olayers, glayers, gpu = _conv_stack(pipe, geo, ["relu", "relu", "none"], [-1, -1, -1], 4, 2, 1.0, 16, seed=5)
+    x = dev(np.zeros((1, 6, 6, 16), dtype=np.float32))
+    # the flat entry point has no grid to convolve over
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward(glayers, x.reshape(36, 16))
+    # a skip across the strided layer joins different grids
+    bad = list(glayers)
+    bad[1] = bad[1][:3] + (1,) + bad[1][4:]
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward_conv(bad, x)
+    # kernel larger than the (unpadded) grid
+    nopad = [glayers[0][:5] + (3, 3, 1, 0)] + glayers[1:]
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward_conv(nopad, dev(np.zeros((1, 2, 2, 16), dtype=np.float32)))
+    y = pipe.pipe_chain_forward_conv(glayers, x)
+    assert tuple(y.shape) == (1, 3, 3, 16)
+    for g in gpu:
+        g.free()
