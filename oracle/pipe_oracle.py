@@ -694,6 +694,57 @@ def error_bound_U(s: Sequence[float], u: Sequence[float]) -> float:
     return U - 1.0
 
 
+def order_norms(exp: Expansion, iters: int) -> List[float]:
+    """||R^(k)|| for k = 1..K: the spectral norm (power iteration above) of each term of the
+    expansion as a real matrix, row scale times codes, pruned rows zero (Eq. 3).  These are the
+    operator norms Theorem "ensemble" and its two-layer corollary are written in."""
+    out = []
+    for k in range(1, exp.K + 1):
+        Rk = exp.dense_scales(k).astype(np.float64)[:, None] * exp.dense_codes(k).astype(np.float64)
+        out.append(spectral_norm(Rk, iters))
+    return out
+
+
+def error_bound_U_ens(norms: Sequence[Sequence[float]], split, lam: Optional[Sequence[Sequence[float]]] = None) -> float:
+    """U_ens of Theorem "ensemble" (App. C) for an L-layer network split into M predictors:
+
+        U_ens = ( sum_{k in cluster 1} ||R_L^(k)|| / 2^(L-1) )
+                * ( 1 + sum_{m=2..M} prod_{l=1..L-1} sum_{k in cluster m} ||R_l^(k)|| lam_l^(k) )
+
+    norms[l][k] = ||R_{l+1}^(k+1)|| (L rows of K).  The printed inner sum runs over
+    k = K_m..K_{m+1} and writes R_L inside the product over l; read here as "the orders of
+    cluster m" and "the weights of layer l".  lam[l][k] stands for the printed
+    lambda_{h~_l^(k)} (the scale of the quantized tensor entering the next layer), which the
+    paper does not make data-free; None means 1."""
+    L = len(norms)
+    if L < 1:
+        raise ValueError("at least one layer")
+    K = len(norms[0])
+    if any(len(r) != K for r in norms):
+        raise ValueError("one norm per order and layer")
+    rngs = member_ranges(K, split)
+    lo1, hi1 = rngs[0]
+    head = sum(float(norms[L - 1][k - 1]) for k in range(lo1, hi1 + 1)) / (2.0 ** (L - 1))
+    tail = 0.0
+    for lo, hi in rngs[1:]:
+        prod = 1.0
+        for l in range(L - 1):
+            prod *= sum(float(norms[l][k - 1]) * (1.0 if lam is None else float(lam[l][k - 1])) for k in range(lo, hi + 1))
+        tail += prod
+    return head * (1.0 + tail)
+
+
+def first_predictor_size(norms, logit_norm: float, ratio: float, lam=None) -> int:
+    """The predictor-size rule of App. A as a procedure: the smallest K_1 for which the
+    two-predictor ensemble [K_1, K - K_1] has U_ens <= ratio * logit_norm (the bound
+    "vanishes compared to" the amplitude of the logits); K if no split qualifies."""
+    K = len(norms[0])
+    for K1 in range(1, K):
+        if error_bound_U_ens(norms, [K1, K - K1], lam) <= ratio * logit_norm:
+            return K1
+    return K
+
+
 # ----------------------------------------------------------------------------
 # App. H: operation head-count
 # ----------------------------------------------------------------------------

@@ -701,3 +701,44 @@ def test_workload_shapes_and_seeding():
     assert abs(float(a.std()) - 0.02) < 1e-3
     x = wl.make_input(wl.scaled(wl.C2, 8, 32, 196))
     assert x.min() == 0.0 and x.shape == (1, 8, 14, 14)
+
+
+def test_order_norms_against_svd_of_the_order_matrices():
+    """||R^(k)|| of every order against numpy's SVD of the matrix that the (separately pinned)
+    partial reconstructions differ by; pruned rows contribute nothing."""
+    rng = np.random.default_rng(95)
+    W = (rng.standard_normal((48, 40)) * 0.1).astype(f32)
+    for bits, K, gamma in [(4, 3, 0.5), (2, 4, 0.25), (8, 2, 1.0)]:
+        e = po.expand(W, bits, K, gamma, 8)
+        got = po.order_norms(e, 600)
+        assert len(got) == K
+        for k in range(1, K + 1):
+            Rk = e.reconstruct(k) - (e.reconstruct(k - 1) if k > 1 else 0.0)
+            sv = np.linalg.svd(Rk, compute_uv=False)[0]
+            assert got[k - 1] <= sv * (1 + 1e-12) and math.isclose(got[k - 1], sv, rel_tol=1e-5), (bits, k)
+        assert all(got[k] < got[k - 1] for k in range(1, K))      # the residual shrinks with every order
+    # the first order of a fine expansion is W up to the grid: Weyl's inequality
+    e8 = po.expand(W, 8, 2, 1.0, 8)
+    n8 = po.order_norms(e8, 600)
+    assert abs(n8[0] - np.linalg.svd(W.astype(np.float64), compute_uv=False)[0]) <= n8[1] * (1 + 1e-6) + np.linalg.svd(W - e8.reconstruct(), compute_uv=False)[0]
+
+
+def test_U_ens_worked_examples_and_predictor_size_rule(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "uens_worked.json")))
+    for c in g["cases"]:
+        assert math.isclose(po.error_bound_U_ens(c["norms"], c["split"], c["lam"]), c["U"], rel_tol=1e-12), c["name"]
+    r = g["k1_rule"]
+    K = len(r["norms"][0])
+    for K1, U in enumerate(r["U_by_K1"], start=1):
+        assert math.isclose(po.error_bound_U_ens(r["norms"], [K1, K - K1]), U, rel_tol=1e-12)
+    for q in r["queries"]:
+        assert po.first_predictor_size(r["norms"], q["logit_norm"], q["ratio"]) == q["K1"], q
+    # scaling every lambda of one hidden layer by c scales every ensembling term by c
+    norms = [[3, 1, 0.5, 0.25], [2, 1, 0.5, 0.125], [8, 2, 1, 1]]
+    ones = [[1.0] * 4, [1.0] * 4]
+    base = po.error_bound_U_ens(norms, [2, 1, 1], ones)
+    scaled = po.error_bound_U_ens(norms, [2, 1, 1], [[3.0] * 4, [1.0] * 4])
+    head = (8 + 2) / 4
+    assert math.isclose(scaled - head, 3.0 * (base - head), rel_tol=1e-12)
+    with pytest.raises(ValueError):
+        po.error_bound_U_ens(norms, [2, 1])
