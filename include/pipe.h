@@ -236,13 +236,38 @@ int pipe_set_activation_bits(int bits);
  *
  * pipe_error_bound_U: U = prod_{l=1..L} ( sum_{i<=l} s_i u_i + 1 ) - 1 as printed in
  * Theorem 1 (U_res with u_lemma, U_sparse with u_stored).  HOST arrays; pure arithmetic.
- * U_ens (Theorem 3) is not provided: its printed index ranges are not readable.        */
+ *
+ * pipe_expansion_order_norms: norms_host[k-1] = ||R^(k)||, k = 1..K, the spectral norm of
+ * each term s_k * codes_k of the expansion (Eq. 3) by the power iteration of
+ * pipe_spectral_norm on the order's stored rows (pruned rows are zero rows and change no
+ * singular value); 0 for an order with no stored row.  HOST [K] doubles.  Synchronizes.
+ *
+ * pipe_error_bound_U_ens (App. C, Theorem "ensemble"): for L layers, K orders and the
+ * grouping split [K_1..K_M] (NULL = one predictor),
+ *   U_ens = ( sum_{k in cluster 1} norms[L-1][k] / 2^(L-1) )
+ *           * ( 1 + sum_{m=2..M} prod_{l=0..L-2} sum_{k in cluster m} norms[l][k] lam[l][k] ).
+ * The printed inner sum runs over k = K_m..K_{m+1} and writes R_L inside the product over
+ * l: read as "the orders of cluster m" and "layer l's weights".  norms HOST [L][K]
+ * (pipe_expansion_order_norms of each layer); lam HOST [L-1][K] stands for the printed
+ * lambda of the quantized tensor entering the next layer, NULL = all 1.  Pure arithmetic.
+ * Errors: PIPE_EINVAL, PIPE_ESPLIT (split does not sum to K).
+ *
+ * pipe_first_predictor_size (App. A, the paragraph on K_1; App. C closing remark): the
+ * smallest K_1 for which the two-predictor ensemble [K_1, K-K_1] has
+ * U_ens <= ratio * logit_norm (logit_norm: the caller's estimate of E||f^(K)||, e.g. from
+ * the last batch-norm's statistics); K when no split qualifies.  Pure arithmetic.      */
 int pipe_spectral_norm(const float* W_dev, int out, int in, int iters, float* sigma_host,
                        void* stream);
 int pipe_expansion_reconstruct(const pipe_expansion* e, int upto, float* W_out_dev,
                                void* stream);
 int pipe_expansion_error_bound(const pipe_expansion* e, double* u_lemma, double* u_stored);
 int pipe_error_bound_U(const double* s, const double* u, int L, double* U_out);
+int pipe_expansion_order_norms(const pipe_expansion* e, int iters, double* norms_host,
+                               void* stream);
+int pipe_error_bound_U_ens(const double* norms, const double* lam, int L, int K,
+                           const int* split, int M, double* U_out);
+int pipe_first_predictor_size(const double* norms, const double* lam, int L, int K,
+                              double logit_norm, double ratio, int* K1_out);
 
 /* Kernel selection for pipe_forward / pipe_mlp_forward (tuning and tests):
  * 0 = automatic by token count, 1 = tiled MFMA kernel, 2 = weight-streaming

@@ -20,6 +20,7 @@ Passages followed
                                                    App. B "Ensemble of more Layers"
   * L-layer member chains with skips ............. App. B / App. D "more Layers", Fig. 2
   * error diagnostics (spectral norms, U) ........ App. C, Theorems 1-2; Lemmas of App. B
+  * per-order norms, U_ens, predictor size ....... App. C, Theorem "ensemble"; App. A on K_1
   * operation head-count ......................... App. H
 
 Readings taken where the paper is silent (each is listed in the design notes):
@@ -37,8 +38,10 @@ Pins: every function here is checked in tests/test_oracle_pins.py against facts
 that do not come from this file (hand-worked example, exhaustive nearest-code
 search, the Lemma's bound, brute-force mask enumeration, torch integer matmul
 and conv2d, closed forms).  Not pinned by the paper (this build's reading only):
-the group-selection criterion, the member-wise treatment of gated MLPs and the
-first-member-only skip from the network input.
+the group-selection criterion, the member-wise treatment of gated MLPs, the
+first-member-only skip from the network input, and the reading of U_ens' index
+ranges with the predictor-size procedure built on it (parity unpinned: only
+hand-evaluated instances of this reading; the per-order norms are pinned by SVD).
 """
 from __future__ import annotations
 

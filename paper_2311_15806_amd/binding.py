@@ -56,6 +56,10 @@ def _load():
     lib.pipe_expansion_reconstruct.argtypes = [vp, ci, vp, vp]
     lib.pipe_expansion_error_bound.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.pipe_error_bound_U.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), ci, C.POINTER(C.c_double)]
+    pd = C.POINTER(C.c_double)
+    lib.pipe_expansion_order_norms.argtypes = [vp, ci, pd, vp]
+    lib.pipe_error_bound_U_ens.argtypes = [pd, pd, ci, ci, pi, ci, pd]
+    lib.pipe_first_predictor_size.argtypes = [pd, pd, ci, ci, C.c_double, C.c_double, C.POINTER(ci)]
     lib.pipe_set_activation_bits.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
@@ -338,6 +342,37 @@ def pipe_error_bound_U(s, u) -> float:
     sa, ua, U = (C.c_double * L)(*[float(v) for v in s]), (C.c_double * L)(*[float(v) for v in u]), C.c_double()
     _check(_lib.pipe_error_bound_U(sa, ua, L, C.byref(U)), "pipe_error_bound_U")
     return U.value
+
+
+def pipe_expansion_order_norms(e: Expansion, iters: int = 50):
+    out = (C.c_double * e.K)()
+    _check(_lib.pipe_expansion_order_norms(e.handle, int(iters), out, _stream()), "pipe_expansion_order_norms")
+    return list(out)
+
+
+def _norm_table(norms, lam):
+    L, K = len(norms), len(norms[0])
+    flat = (C.c_double * (L * K))(*[float(v) for row in norms for v in row])
+    lam_flat = None
+    if lam is not None:
+        lam_flat = (C.c_double * ((L - 1) * K))(*[float(v) for row in lam for v in row])
+    return L, K, flat, lam_flat
+
+
+def pipe_error_bound_U_ens(norms, split=None, lam=None) -> float:
+    L, K, flat, lam_flat = _norm_table(norms, lam)
+    arr, m = _split(split)
+    U = C.c_double()
+    _check(_lib.pipe_error_bound_U_ens(flat, lam_flat, L, K, arr, m, C.byref(U)), "pipe_error_bound_U_ens")
+    return U.value
+
+
+def pipe_first_predictor_size(norms, logit_norm: float, ratio: float, lam=None) -> int:
+    L, K, flat, lam_flat = _norm_table(norms, lam)
+    K1 = C.c_int()
+    _check(_lib.pipe_first_predictor_size(flat, lam_flat, L, K, float(logit_norm), float(ratio), C.byref(K1)),
+           "pipe_first_predictor_size")
+    return K1.value
 
 
 def pipe_fold_batchnorm(W: torch.Tensor, bias, gamma, beta, mean, var, eps: float):

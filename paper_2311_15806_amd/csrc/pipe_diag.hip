@@ -128,12 +128,18 @@ __global__ __launch_bounds__(BLK) void add_order_kernel(const int8_t* __restrict
   for (int i = threadIdx.x; i < in; i += BLK) w[i] = __fadd_rn(w[i], __fmul_rn(s, (float)c[i]));
 }
 
-}  // namespace
+// R[r, i] = s[r] * code[r, i] for the stored rows of one order, compact (pruned rows left out:
+// zero rows do not change a matrix's singular values)
+__global__ __launch_bounds__(BLK) void scale_rows_kernel(const int8_t* __restrict__ codes, const float* __restrict__ scales_all,
+                                                         const int32_t* __restrict__ pos, int in, float* __restrict__ R) {
+  const int r = blockIdx.x;
+  const float s = scales_all[(size_t)pos[r >> 4] * 16 + (r & 15)];
+  const int8_t* c = codes + (size_t)r * in;
+  float* w = R + (size_t)r * in;
+  for (int i = threadIdx.x; i < in; i += BLK) w[i] = __fmul_rn(s, (float)c[i]);
+}
 
-extern "C" int pipe_spectral_norm(const float* W_dev, int out, int in, int iters, float* sigma_host, void* stream) {
-  if (!W_dev || !sigma_host || iters < 1) return PIPE_EINVAL;
-  if (out < 1 || in < 1) return PIPE_ESHAPE;
-  hipStream_t st = (hipStream_t)stream;
+int spectral_norm_dev(const float* W_dev, int out, int in, int iters, double* sigma_host, hipStream_t st) {
   // v [in] fp32 | y [out] fp64 | z [in] fp64 | sigma fp64 | ||z||^2 shares | partial [ROW_CHUNKS][in] fp64
   const int n_part = ceil_div(in, BLK);
   const size_t off_y = ((size_t)in * 4 + 255) & ~(size_t)255;
@@ -163,7 +169,39 @@ extern "C" int pipe_spectral_norm(const float* W_dev, int out, int in, int iters
   double s = 0.0;
   PIPE_HIP(hipMemcpyAsync(&s, sigma, sizeof(double), hipMemcpyDeviceToHost, st));
   PIPE_HIP(hipStreamSynchronize(st));
-  *sigma_host = (float)s;
+  *sigma_host = s;
+  return PIPE_OK;
+}
+
+}  // namespace
+
+extern "C" int pipe_spectral_norm(const float* W_dev, int out, int in, int iters, float* sigma_host, void* stream) {
+  if (!W_dev || !sigma_host || iters < 1) return PIPE_EINVAL;
+  if (out < 1 || in < 1) return PIPE_ESHAPE;
+  double s = 0.0;
+  const int rc = spectral_norm_dev(W_dev, out, in, iters, &s, (hipStream_t)stream);
+  if (rc == PIPE_OK) *sigma_host = (float)s;
+  return rc;
+}
+
+extern "C" int pipe_expansion_order_norms(const pipe_expansion* e, int iters, double* norms_host, void* stream) {
+  if (!e || !norms_host || iters < 1) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  for (int k = 0; k < e->K; ++k) {
+    const PipeOrder& o = e->orders[k];
+    const int rows = o.n_kept * e->group;
+    norms_host[k] = 0.0;
+    if (rows == 0) continue;
+    int8_t* tmp = (int8_t*)pipe_ws_get(WS_DIAG_CODES, (size_t)rows * e->in);
+    float* R = (float*)pipe_ws_get(WS_DIAG_DENSE, (size_t)rows * e->in * sizeof(float));
+    if (!tmp || !R) return PIPE_ENOMEM;
+    int rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, rows, e->in, e->in_pad, tmp, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(scale_rows_kernel, dim3(rows), dim3(BLK), 0, st, tmp, e->scales_all_dev, o.pos_dev, e->in, R);
+    PIPE_HIP(hipGetLastError());
+    rc = spectral_norm_dev(R, rows, e->in, iters, &norms_host[k], st);
+    if (rc) return rc;
+  }
   return PIPE_OK;
 }
 
@@ -221,5 +259,56 @@ extern "C" int pipe_error_bound_U(const double* s, const double* u, int L, doubl
     U *= run + 1.0;
   }
   *U_out = U - 1.0;
+  return PIPE_OK;
+}
+
+static int u_ens(const double* norms, const double* lam, int L, int K, const int* split, int M, double* out) {
+  int lo = 0;
+  double head = 0.0, tail = 0.0;
+  for (int m = 0; m < M; ++m) {
+    const int hi = lo + split[m];
+    if (m == 0) {
+      for (int k = lo; k < hi; ++k) head += norms[(size_t)(L - 1) * K + k];
+      head /= std::ldexp(1.0, L - 1);
+    } else {
+      double prod = 1.0;
+      for (int l = 0; l + 1 < L; ++l) {
+        double sum = 0.0;
+        for (int k = lo; k < hi; ++k) sum += norms[(size_t)l * K + k] * (lam ? lam[(size_t)l * K + k] : 1.0);
+        prod *= sum;
+      }
+      tail += prod;
+    }
+    lo = hi;
+  }
+  *out = head * (1.0 + tail);
+  return PIPE_OK;
+}
+
+extern "C" int pipe_error_bound_U_ens(const double* norms, const double* lam, int L, int K, const int* split, int M,
+                                      double* U_out) {
+  if (!norms || !U_out || L < 1 || K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
+  const int whole[1] = {K};
+  if (!split) { split = whole; M = 1; }
+  if (M < 1) return PIPE_ESPLIT;
+  int sum = 0;
+  for (int m = 0; m < M; ++m) {
+    if (split[m] < 1) return PIPE_ESPLIT;
+    sum += split[m];
+  }
+  if (sum != K) return PIPE_ESPLIT;
+  return u_ens(norms, lam, L, K, split, M, U_out);
+}
+
+extern "C" int pipe_first_predictor_size(const double* norms, const double* lam, int L, int K, double logit_norm,
+                                         double ratio, int* K1_out) {
+  if (!norms || !K1_out || L < 1 || K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
+  *K1_out = K;
+  for (int K1 = 1; K1 < K; ++K1) {
+    const int split[2] = {K1, K - K1};
+    double U = 0.0;
+    u_ens(norms, lam, L, K, split, 2, &U);
+    if (U <= ratio * logit_norm) { *K1_out = K1; break; }
+  }
   return PIPE_OK;
 }

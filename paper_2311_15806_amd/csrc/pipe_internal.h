@@ -158,7 +158,7 @@ struct PipeWorkspace {
 // Returns a device buffer of at least `bytes` from slot `slot` (grow-only; growing
 // synchronizes the device first).  nullptr on failure.
 void* pipe_ws_get(int slot, size_t bytes);
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);

@@ -60,6 +60,7 @@ def test_argument_errors_return_codes(lib):
     s2, u2, U = (C.c_double * 2)(2.0, 4.0), (C.c_double * 2)(0.05, 0.01), C.c_double()
     assert lib.pipe_error_bound_U(s2, u2, 2, C.byref(U)) == 0 and abs(U.value - ((0.1 + 1) * (0.14 + 1) - 1)) < 1e-15
     assert lib.pipe_error_bound_U(s2, u2, 0, C.byref(U)) == EINVAL
+    assert lib.pipe_expansion_order_norms(None, 3, None, None) == EINVAL
     assert lib.pipe_fold_batchnorm(None, None, None, None, None, None, C.c_float(1e-5), 4, 4, None, None, None) == EINVAL
     assert lib.pipe_forward_depthwise2d(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, C.c_float(0), None, 0, None, 1, None, None) == EINVAL
     assert lib.pipe_expansion_free(None) == 0
@@ -98,3 +99,37 @@ def test_product_never_reaches_the_checker():
         assert word not in wl, "the input generators must hold none of the method's arithmetic"
     bench = open(os.path.join(ROOT, "bench.py")).read()
     assert bench.count("from oracle import") == 1 and "if not args.no_cpu" in bench
+
+
+def test_U_ens_and_predictor_size_rule_host_arithmetic():
+    """The library's U_ens and K_1 rule are host arithmetic: checked here, without a GPU, against
+    the hand-evaluated instances (the same file pins the checker)."""
+    import json
+    lib = C.CDLL(LIB)
+    pd, pi = C.POINTER(C.c_double), C.POINTER(C.c_int)
+    lib.pipe_error_bound_U_ens.argtypes = [pd, pd, C.c_int, C.c_int, pi, C.c_int, pd]
+    lib.pipe_first_predictor_size.argtypes = [pd, pd, C.c_int, C.c_int, C.c_double, C.c_double, pi]
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "uens_worked.json")))
+
+    def flat(rows):
+        return None if rows is None else (C.c_double * (len(rows) * len(rows[0])))(*[float(v) for r in rows for v in r])
+
+    U = C.c_double()
+    for c in g["cases"]:
+        L, K = len(c["norms"]), len(c["norms"][0])
+        sp = (C.c_int * len(c["split"]))(*c["split"])
+        assert lib.pipe_error_bound_U_ens(flat(c["norms"]), flat(c["lam"]), L, K, sp, len(c["split"]), C.byref(U)) == 0
+        assert abs(U.value - c["U"]) <= 1e-12 * c["U"], c["name"]
+    r = g["k1_rule"]
+    norms, K = flat(r["norms"]), len(r["norms"][0])
+    for K1, want in enumerate(r["U_by_K1"], start=1):
+        sp = (C.c_int * 2)(K1, K - K1)
+        assert lib.pipe_error_bound_U_ens(norms, None, 2, K, sp, 2, C.byref(U)) == 0 and abs(U.value - want) < 1e-12
+    k1 = C.c_int()
+    for q in r["queries"]:
+        assert lib.pipe_first_predictor_size(norms, None, 2, K, q["logit_norm"], q["ratio"], C.byref(k1)) == 0
+        assert k1.value == q["K1"], q
+    bad = (C.c_int * 2)(1, 1)
+    assert lib.pipe_error_bound_U_ens(norms, None, 2, K, bad, 2, C.byref(U)) == -5     # does not sum to K
+    assert lib.pipe_error_bound_U_ens(norms, None, 2, K, None, 0, C.byref(U)) == 0     # one predictor
+    assert abs(U.value - (4 + 1 + 0.25 + 0.0625) / 2) < 1e-12

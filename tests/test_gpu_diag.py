@@ -66,3 +66,34 @@ def test_spectral_norm_of_the_headline_layer(pipe):
     ref = po.spectral_norm(W, 4)
     got = pipe.pipe_spectral_norm(dev(W), 4)
     assert math.isclose(got, ref, rel_tol=2e-6)
+
+
+@pytest.mark.parametrize("bits,K,gamma,group", [(4, 3, 0.5, 32), (2, 5, 0.25, 16), (8, 2, 1.0, 16)])
+def test_order_norms_and_U_ens_parity(pipe, bits, K, gamma, group):
+    """||R^(k)|| of every order: the same power iteration on both sides, step for step; then
+    U_ens and the predictor-size rule of a two-layer stack of this layer."""
+    O, I = 192, 328
+    rng = np.random.default_rng(940 + bits)
+    W = (rng.standard_t(3, size=(O, I)) * 0.015).astype(f32)
+    ora = oracle_expand(W, wl.LayerSpec(O, I, bits, K, gamma, group))
+    g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+    assert_expansion_equal(g, ora)
+    for iters in (2, 30):
+        ref = po.order_norms(ora, iters)
+        got = pipe.pipe_expansion_order_norms(g, iters)
+        assert len(got) == K
+        for k in range(K):
+            assert math.isclose(got[k], ref[k], rel_tol=2e-6), (iters, k, got[k], ref[k])
+    # each norm is a lower bound of the order matrix's largest singular value
+    for k in range(1, K + 1):
+        Rk = ora.reconstruct(k) - (ora.reconstruct(k - 1) if k > 1 else 0.0)
+        assert got[k - 1] <= np.linalg.svd(Rk, compute_uv=False)[0] * (1 + 1e-6)   # the GPU rounds s * code to fp32
+    norms = [got, got]
+    for split in ([K], [1, K - 1], [1] * K):
+        assert math.isclose(pipe.pipe_error_bound_U_ens(norms, split), po.error_bound_U_ens(norms, split), rel_tol=1e-12)
+    lam = [[0.5 + 0.1 * k for k in range(K)]]
+    assert math.isclose(pipe.pipe_error_bound_U_ens(norms, [1, K - 1], lam), po.error_bound_U_ens(norms, [1, K - 1], lam),
+                        rel_tol=1e-12)
+    for ratio in (0.01, 0.5, 2.0):
+        assert pipe.pipe_first_predictor_size(norms, got[0], ratio) == po.first_predictor_size(norms, got[0], ratio)
+    g.free()
