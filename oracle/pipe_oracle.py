@@ -65,18 +65,28 @@ def q_max(bits: int) -> int:
     return 2 ** (int(bits) - 1) - 1
 
 
-def quantize_rows(E: np.ndarray, bits: int):
+def quantize_rows(E: np.ndarray, bits: int, operator=None, k: int = 1):
     """Row-wise symmetric quantizer.  E fp32 [R, I] -> (codes int8 [R, I], s fp32 [R]).
 
     s[o] = max_i |E[o,i]| / q_max (fp32 division); q = clamp(rint(E / s), +-q_max),
-    rint rounds half to even.  A row whose scale is 0 gets codes 0."""
+    rint rounds half to even.  A row whose scale is 0 gets codes 0.
+
+    The method does not depend on how a value is rounded onto the grid (Sec. 1 and Sec. 4.4:
+    the expansion combines with any quantization operator): `operator`, if given, replaces the
+    rint step.  It is called as operator(k, E, s, q_max) and returns integer codes [R, I]; they
+    are clamped to +-q_max and rows of scale 0 get codes 0, as above."""
     E = np.asarray(E, dtype=f32)
     qm = f32(q_max(bits))
     amax = np.max(np.abs(E), axis=1) if E.shape[1] else np.zeros(E.shape[0], f32)
     s = (amax / qm).astype(f32)
     live = s > 0
-    div = np.where(live, s, f32(1.0)).astype(f32)
-    q = np.rint(E / div[:, None])
+    if operator is None:
+        div = np.where(live, s, f32(1.0)).astype(f32)
+        q = np.rint(E / div[:, None])
+    else:
+        q = np.asarray(operator(k, E, s, int(qm)), dtype=np.float64)
+        if q.shape != E.shape:
+            raise ValueError("the operator returns one code per element")
     q = np.clip(q, -qm, qm)
     q[~live, :] = 0
     return q.astype(np.int8), s
@@ -173,7 +183,7 @@ class Expansion:
 
 
 def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
-           residuals: Optional[list] = None, gaps: Optional[list] = None) -> Expansion:
+           residuals: Optional[list] = None, gaps: Optional[list] = None, operator=None) -> Expansion:
     """Residual expansion of W [O, I] to order K.
 
     E_1 = W.  For k = 1..K: (k>=2 and gamma<1: keep the top n_keep groups of E_k
@@ -181,7 +191,8 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
     E_{k+1} = E_k - s_k*q_k (fp32 multiply, then fp32 subtract); pruned rows pass
     their residual on unchanged.  If `residuals` is a list, E_2..E_{K+1} are
     appended to it (copies); if `gaps` is a list, the selection_gap of every mask
-    that was chosen is appended to it."""
+    that was chosen is appended to it.  `operator` replaces round-to-nearest in every
+    order (see quantize_rows)."""
     W = np.asarray(W, dtype=f32)
     if W.ndim != 2:
         raise ValueError("W must be [out, in]")
@@ -202,7 +213,7 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
             if gaps is not None:
                 gaps.append(selection_gap(scores, keep))
         rows = (gids[:, None].astype(np.int64) * group + np.arange(group)[None, :]).reshape(-1)
-        q, s = quantize_rows(E[rows], bits)
+        q, s = quantize_rows(E[rows], bits, operator, k)
         Rk = (s[:, None] * q.astype(f32)).astype(f32)      # Q^-1(Q(.)), one rounding
         E[rows] = (E[rows] - Rk).astype(f32)               # second rounding, no FMA
         orders.append(Order(gids, s, q))

@@ -742,3 +742,41 @@ def test_U_ens_worked_examples_and_predictor_size_rule(golden_dir):
     assert math.isclose(scaled - head, 3.0 * (base - head), rel_tol=1e-12)
     with pytest.raises(ValueError):
         po.error_bound_U_ens(norms, [2, 1])
+
+
+def test_expansion_with_another_rounding_operator():
+    """The rounding operator is a plug-in (Sec. 4.4).  Round-to-nearest passed in as an operator
+    reproduces the built-in expansion bit for bit; truncation toward zero still telescopes
+    (W = sum of the terms + last residual, exactly in fp32 steps) with the one-step error
+    |residual| < s instead of s/2, and orders computed from it still shrink the error."""
+    rng = np.random.default_rng(97)
+    W = (rng.standard_normal((32, 40)) * 0.05).astype(f32)
+    calls = []
+
+    def rne(k, E, s, qm):
+        calls.append((k, E.shape))
+        return np.rint(E / np.where(s > 0, s, 1).astype(f32)[:, None])
+
+    a = po.expand(W, 4, 3, 0.5, 8)
+    b = po.expand(W, 4, 3, 0.5, 8, operator=rne)
+    assert [c[0] for c in calls] == [1, 2, 3] and calls[0][1] == (32, 40) and calls[1][1] == (16, 40)
+    for oa, ob in zip(a.orders, b.orders):
+        assert np.array_equal(oa.group_ids, ob.group_ids) and np.array_equal(oa.scales, ob.scales)
+        assert np.array_equal(oa.codes, ob.codes)
+
+    trunc = lambda k, E, s, qm: np.trunc(E / np.where(s > 0, s, 1).astype(f32)[:, None])
+    res = []
+    t = po.expand(W, 4, 3, 1.0, 8, residuals=res, operator=trunc)
+    for k in range(1, 4):
+        sk = t.dense_scales(k).astype(np.float64)[:, None]
+        assert np.all(np.abs(res[k - 1]) <= sk * (1 + 1e-6))            # less than one step
+        assert np.all(np.abs(t.dense_codes(k)) <= 7)
+    assert np.abs(res[0]).max() > a.dense_scales(1).max() / 2          # and really not nearest
+    assert np.allclose(W.astype(np.float64), t.reconstruct() + res[-1], rtol=0, atol=1e-7)
+    errs = [np.abs(W - t.reconstruct(k)).max() for k in (1, 2, 3)]
+    assert errs[2] < errs[1] < errs[0]
+    # codes out of range are clamped; a wrong shape is refused
+    big = po.expand(W, 4, 1, 1.0, 8, operator=lambda k, E, s, qm: np.full(E.shape, 100))
+    assert np.all(big.orders[0].codes == 7)
+    with pytest.raises(ValueError):
+        po.expand(W, 4, 1, 1.0, 8, operator=lambda k, E, s, qm: np.zeros((1, 1)))
