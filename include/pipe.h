@@ -80,6 +80,25 @@ int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, const float* 
 int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
                 int group, void* stream, pipe_expansion** exp_out);
 
+/* The same expansion with another rounding operator (Sec. 1 and Sec. 4.4: the method is
+ * agnostic to the quantization operator and combines with operators that choose the
+ * rounding direction themselves).  For every order k = 1..K the builder writes, on
+ * `stream`, the rows this order quantizes to rows_dev [rows, in] (compact: the kept
+ * groups in ascending order) and their scales max|row| / q_max to scales_dev [rows], then
+ * calls fn on the host; fn enqueues, on the same stream, work that writes one integer code
+ * per element to codes_dev [rows, in] and returns 0 (anything else aborts the build with
+ * PIPE_EINVAL).  The builder clamps the codes to +-q_max, gives rows of scale 0 the code 0,
+ * forms R^k = s * code and the residual exactly as pipe_expand does; masks, scales and
+ * layout are unchanged, so every forward entry point accepts the result.
+ *   rows_dev, codes_dev  caller-owned DEVICE scratch of out*in elements; scales_dev [out]
+ *   user                 passed through to fn
+ * Round-to-nearest-even as fn reproduces pipe_expand bit for bit.                     */
+typedef int (*pipe_rounding_fn)(void* user, int k, int rows, int in, int q_max, void* stream);
+int pipe_expand_with_operator(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                              int group, pipe_rounding_fn fn, void* user, float* rows_dev,
+                              float* scales_dev, int8_t* codes_dev, void* stream,
+                              pipe_expansion** exp_out);
+
 int pipe_expansion_free(pipe_expansion* e);
 
 /* Shape query; any output pointer may be NULL.  packed_bytes = bytes of packed

@@ -7,7 +7,7 @@ it is missing.
 from . import workloads  # noqa: F401
 
 _BINDING_NAMES = (
-    "Expansion", "PipeError", "pipe_expand", "pipe_expansion_order", "pipe_forward", "pipe_forward_acc",
+    "Expansion", "PipeError", "pipe_expand", "pipe_expand_with_operator", "pipe_expansion_order", "pipe_forward", "pipe_forward_acc",
     "pipe_forward_conv2d", "pipe_mlp_forward", "pipe_chain_forward", "pipe_chain_forward_conv", "pipe_set_kernel", "pipe_timing_enable", "pipe_timing_read", "PIPE_ACT_NONE", "PIPE_ACT_GELU", "PIPE_ACT_SILU_GATED", "PIPE_ACT_RELU",
 )
 

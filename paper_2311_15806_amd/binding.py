@@ -23,6 +23,9 @@ PIPE_ACT_SILU_GATED = 2
 PIPE_ACT_RELU = 3
 
 
+_ROUNDING_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p)
+
+
 class PipeError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -40,6 +43,7 @@ def _load():
     vp, ci, cf = C.c_void_p, C.c_int, C.c_float
     pi = C.POINTER(C.c_int)
     lib.pipe_expand.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
+    lib.pipe_expand_with_operator.argtypes = [vp, ci, ci, ci, ci, cf, ci, _ROUNDING_FN, vp, vp, vp, vp, vp, C.POINTER(vp)]
     lib.pipe_expansion_free.argtypes = [vp]
     lib.pipe_expansion_info.argtypes = [vp, pi, pi, pi, pi, pi, C.POINTER(cf), C.POINTER(C.c_int64)]
     lib.pipe_expansion_order.argtypes = [vp, ci, pi, vp, vp, vp]
@@ -154,6 +158,38 @@ def pipe_expand(W: torch.Tensor, bits: int, K: int, gamma: float, group: int) ->
     h = C.c_void_p()
     _check(_lib.pipe_expand(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(bits), int(K),
                             float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand")
+    return Expansion(h.value)
+
+
+def pipe_expand_with_operator(W: torch.Tensor, bits: int, K: int, gamma: float, group: int, operator) -> Expansion:
+    """operator(k, rows [R, in] fp32, scales [R] fp32, q_max) -> codes [R, in] (any integer-valued
+    tensor on W's device), called once per order with views of the builder's scratch."""
+    if W.dim() != 2:
+        raise ValueError("W must be [out, in]")
+    out, inn = W.shape
+    rows_t = torch.empty((out, inn), dtype=torch.float32, device=W.device)
+    scales_t = torch.empty((out,), dtype=torch.float32, device=W.device)
+    codes_t = torch.empty((out, inn), dtype=torch.int8, device=W.device)
+    failure = []
+
+    def hook(_user, k, rows, in_, q_max, _stream_ptr):
+        try:
+            q = operator(k, rows_t[:rows], scales_t[:rows], q_max)
+            if tuple(q.shape) != (rows, in_):
+                raise ValueError("the operator returns one code per element")
+            codes_t[:rows].copy_(q.clamp(-127, 127).to(torch.int8))
+            return 0
+        except BaseException as exc:   # never unwind through the C frames
+            failure.append(exc)
+            return 1
+
+    cb = _ROUNDING_FN(hook)
+    h = C.c_void_p()
+    rc = _lib.pipe_expand_with_operator(_ptr(W, torch.float32), out, inn, int(bits), int(K), float(gamma), int(group), cb,
+                                        None, _ptr(rows_t), _ptr(scales_t), _ptr(codes_t), _stream(), C.byref(h))
+    if failure:
+        raise failure[0]
+    _check(rc, "pipe_expand_with_operator")
     return Expansion(h.value)
 
 

@@ -227,8 +227,16 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
   return PIPE_OK;
 }
 
+struct RoundingHook {
+  pipe_rounding_fn fn = nullptr;
+  void* user = nullptr;
+  float* rows = nullptr;     // caller's scratch, DEVICE
+  float* scales = nullptr;
+  int8_t* codes = nullptr;
+};
+
 static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, float** resid_out,
-                       double** energy_out) {
+                       double** energy_out, const RoundingHook& hook) {
   const int out = e->out, in = e->in, K = e->K, group = e->group;
   const int n_groups = e->n_groups;
   const int keep = n_keep_of(e->gamma, n_groups);
@@ -260,8 +268,15 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
       rc = launch_group_select(energy, n_groups, group, keep, o.gids_dev, st);
       if (rc) return rc;
     }
-    int rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, e->qbits, group, o.gids_dev, o.n_kept, o.scales_dev,
-                                  o.packed_dev, st);
+    int rc = PIPE_OK;
+    if (hook.fn) {
+      // another rounding operator: hand it the rows of this order and their scales, take its codes
+      rc = launch_gather_rows(E, in, e->qbits, group, o.gids_dev, o.n_kept, hook.rows, hook.scales, st);
+      if (rc) return rc;
+      if (hook.fn(hook.user, k + 1, (int)rows, in, (1 << (e->qbits - 1)) - 1, (void*)st) != 0) return PIPE_EINVAL;
+    }
+    rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, e->qbits, group, o.gids_dev, o.n_kept, o.scales_dev,
+                              o.packed_dev, hook.fn ? hook.codes : nullptr, st);
     if (rc) return rc;
     e->stream_bytes += (int64_t)o.packed_bytes + (int64_t)rows * 4 + (int64_t)o.n_kept * 4;
   }
@@ -283,8 +298,8 @@ extern "C" int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, co
                                bias_out_dev, (hipStream_t)stream);
 }
 
-extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
-                           int group, void* stream, pipe_expansion** exp_out) {
+static int expand_checked(const float* W_dev, int out, int in, int bits, int K, float gamma, int group,
+                          const RoundingHook& hook, void* stream, pipe_expansion** exp_out) {
   if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;
   if (bits < 2 || bits > 8) return PIPE_EINVAL;
   if (K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
@@ -304,7 +319,7 @@ extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K,
   if (hipGetDevice(&e->device) != hipSuccess) { delete e; return PIPE_EDEVICE; }
   float* resid = nullptr;
   double* energy = nullptr;
-  int rc = expand_impl(e, W_dev, (hipStream_t)stream, &resid, &energy);
+  int rc = expand_impl(e, W_dev, (hipStream_t)stream, &resid, &energy, hook);
   if (rc != PIPE_OK) (void)hipDeviceSynchronize();
   if (resid) (void)hipFree(resid);
   if (energy) (void)hipFree(energy);
@@ -315,6 +330,20 @@ extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K,
   }
   *exp_out = e;
   return PIPE_OK;
+}
+
+extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                           int group, void* stream, pipe_expansion** exp_out) {
+  return expand_checked(W_dev, out, in, bits, K, gamma, group, RoundingHook{}, stream, exp_out);
+}
+
+extern "C" int pipe_expand_with_operator(const float* W_dev, int out, int in, int bits, int K, float gamma, int group,
+                                         pipe_rounding_fn fn, void* user, float* rows_dev, float* scales_dev,
+                                         int8_t* codes_dev, void* stream, pipe_expansion** exp_out) {
+  if (!fn || !rows_dev || !scales_dev || !codes_dev) return PIPE_EINVAL;
+  RoundingHook hook;
+  hook.fn = fn; hook.user = user; hook.rows = rows_dev; hook.scales = scales_dev; hook.codes = codes_dev;
+  return expand_checked(W_dev, out, in, bits, K, gamma, group, hook, stream, exp_out);
 }
 
 extern "C" int pipe_expansion_free(pipe_expansion* e) {

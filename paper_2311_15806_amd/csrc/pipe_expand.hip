@@ -71,9 +71,11 @@ template <int BITS>
 __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ E, int in, int in_pad,
                                                             int group, const int32_t* __restrict__ gids,
                                                             float* __restrict__ scales,
-                                                            uint8_t* __restrict__ packed, int QMAX) {
+                                                            uint8_t* __restrict__ packed, int QMAX,
+                                                            const int8_t* __restrict__ given) {
   // BITS is the width of the stored code (8, 4 or 2); QMAX = 2^(b-1)-1 of the quantizer, which
-  // may be narrower (3-bit codes in 4-bit fields, 5..7-bit codes in bytes)
+  // may be narrower (3-bit codes in 4-bit fields, 5..7-bit codes in bytes).  given: NULL, or the
+  // codes [rows, in] another rounding operator chose for these rows (clamped here)
   constexpr int KSUP = 512 / BITS;       // k-values per tile
   constexpr int STEPS = KSUP / 64;       // 64-k steps per tile
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
@@ -107,7 +109,8 @@ __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ 
       int q = 0;
       if (live && k < in) {
         const float v = e[k];
-        float qf = rintf(__fdiv_rn(v, s));                 // round half to even
+        float qf = given != nullptr ? (float)given[(size_t)r * in + k]
+                                    : rintf(__fdiv_rn(v, s));   // round half to even
         qf = fminf(fmaxf(qf, (float)-QMAX), (float)QMAX);
         e[k] = __fsub_rn(v, __fmul_rn(s, qf));             // Q^-1 then residual: two roundings
         q = (int)qf;
@@ -145,6 +148,29 @@ __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ 
       dst[j] = w;
     }
   }
+}
+
+// ---- operator hook: the rows an order quantizes, compact, with their scales ---------------
+__global__ __launch_bounds__(BLK) void gather_rows_kernel(const float* __restrict__ E, int in, int group,
+                                                          const int32_t* __restrict__ gids, int QMAX,
+                                                          float* __restrict__ rows_out, float* __restrict__ scales_out) {
+  const int r = blockIdx.x;
+  const int slot = r / group;
+  const float* e = E + (size_t)(gids[slot] * group + (r - slot * group)) * in;
+  float amax = 0.f;
+  for (int i = threadIdx.x; i < in; i += BLK) {
+    const float v = e[i];
+    rows_out[(size_t)r * in + i] = v;
+    amax = fmaxf(amax, fabsf(v));
+  }
+  __shared__ float sm[BLK];
+  sm[threadIdx.x] = amax;
+  __syncthreads();
+  for (int s = BLK / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sm[threadIdx.x] = fmaxf(sm[threadIdx.x], sm[threadIdx.x + s]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) scales_out[r] = __fdiv_rn(sm[0], (float)QMAX);
 }
 
 // ---- introspection: tile layout -> one signed code per byte, [rows, in] -------------------
@@ -241,17 +267,27 @@ int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, co
 
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
-                         hipStream_t st) {
+                         const int8_t* given, hipStream_t st) {
   const int qmax = (1 << (qbits - 1)) - 1;
   (void)out;
   const int rows = n_kept * group;
   if (rows == 0) return PIPE_OK;
   if (bits == 8)
-    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
+    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
   else if (bits == 4)
-    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
+    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
   else
-    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax);
+    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_gather_rows(const float* E, int in, int qbits, int group, const int32_t* gids, int n_kept,
+                       float* rows_out, float* scales_out, hipStream_t st) {
+  const int rows = n_kept * group;
+  if (rows == 0) return PIPE_OK;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(rows), dim3(BLK), 0, st, E, in, group, gids, (1 << (qbits - 1)) - 1, rows_out,
+                     scales_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -168,7 +168,10 @@ int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, co
                           const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st);
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
-                         hipStream_t st);
+                         const int8_t* given, hipStream_t st);
+// the rows an order quantizes, compact [n_kept*group, in], and their scales max|row| / q_max
+int launch_gather_rows(const float* E, int in, int qbits, int group, const int32_t* gids, int n_kept,
+                       float* rows_out, float* scales_out, hipStream_t st);
 int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bits, int rows, int in, int in_pad,
                         int8_t* codes, hipStream_t st);
 int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, const int32_t* pos_of_dev, int n_crb,

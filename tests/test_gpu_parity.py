@@ -479,3 +479,49 @@ def test_depthwise_conv_parity(pipe, C, H, W, kh, kw, stride, pad, bits, K):
     y2 = pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy()
     assert np.array_equal(y2, pipe.pipe_forward_depthwise2d(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy())
     g.free()
+
+
+def test_expand_with_another_rounding_operator(pipe):
+    """The rounding operator as a plug-in (Sec. 4.4): round-to-nearest through the hook is the
+    built-in expansion bit for bit; a truncating operator gives, on both sides, the same masks,
+    scales and codes, and the forward pass of that expansion matches the checker."""
+    O, I, bits, K, gamma, group = 96, 200, 4, 3, 0.5, 16
+    rng = np.random.default_rng(411)
+    W = (rng.standard_t(3, size=(O, I)) * 0.02).astype(np.float32)
+    spec = wl.LayerSpec(O, I, bits, K, gamma, group)
+
+    def div(E, s):
+        return E / torch.where(s > 0, s, torch.ones_like(s))[:, None]
+
+    seen = []
+
+    def rne(k, E, s, qm):
+        seen.append((k, tuple(E.shape), qm))
+        return torch.round(div(E, s))          # half to even
+
+    g0 = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+    g1 = pipe.pipe_expand_with_operator(dev(W), bits, K, gamma, group, rne)
+    assert seen == [(1, (O, I), 7), (2, (48, I), 7), (3, (48, I), 7)]
+    for k in range(1, K + 1):
+        a, b = pipe.pipe_expansion_order(g0, k), pipe.pipe_expansion_order(g1, k)
+        for u, v in zip(a, b):
+            assert np.array_equal(u, v)
+
+    trunc_np = lambda k, E, s, qm: np.trunc(E / np.where(s > 0, s, 1).astype(np.float32)[:, None])
+    ora = po.expand(W, bits, K, gamma, group, operator=trunc_np)
+    g2 = pipe.pipe_expand_with_operator(dev(W), bits, K, gamma, group, lambda k, E, s, qm: torch.trunc(div(E, s)))
+    assert_expansion_equal(g2, ora)
+    x = rng.standard_normal((37, I)).astype(np.float32)
+    y = pipe.pipe_forward(g2, dev(x), split=[1, 2]).cpu().numpy()
+    assert_close_fp32(y, po.forward(ora, x, split=[1, 2])["y"])
+    # out-of-range codes are clamped; an operator that fails aborts the build
+    g3 = pipe.pipe_expand_with_operator(dev(W), bits, 1, 1.0, group, lambda k, E, s, qm: torch.full_like(E, 100.0))
+    assert np.all(pipe.pipe_expansion_order(g3, 1)[2] == 7)
+
+    def broken(k, E, s, qm):
+        raise RuntimeError("operator failed")
+
+    with pytest.raises(RuntimeError, match="operator failed"):
+        pipe.pipe_expand_with_operator(dev(W), bits, K, gamma, group, broken)
+    for g in (g0, g1, g2, g3):
+        g.free()
