@@ -15,6 +15,7 @@ Passages followed
   * quantizer Q and de-quantizer Q^-1 ............ Sec. 3, Eq. (1)
   * residual expansion R^1..R^K .................. Sec. 3.1, Eq. (2), (3)
   * structured mask M^k, sparsity ratio gamma .... Sec. 3.1, masked Eq. after (4)
+  * unstructured mask M^k (a sparse tensor) ...... Sec. 3.1, same passage
   * expanded-layer forward ....................... App. B, Eq. (define_dre)
   * ensemble members, bias in predictor 1 ........ Sec. 3.2, Fig. 2 caption,
                                                    App. B "Ensemble of more Layers"
@@ -28,7 +29,10 @@ scale = row absmax / (2^(b-1)-1) and codes clamped to +-(2^(b-1)-1); ties round
 to even; an all-zero row has scale 0 and codes 0; R^1 is dense and orders k>=2
 keep the ceil(gamma*n_groups) groups of `group` consecutive output channels with
 the largest residual energy (sum of squares, fp64), re-selected at every order,
-ties to the lower group index; activations are per-tensor symmetric a-bit codes
+ties to the lower group index; an unstructured mask keeps the ceil(gamma*O*I)
+entries of the residual that are largest in magnitude, re-selected at every
+order k>=2, ties to the lower flat index, and a row's scale is the largest kept
+magnitude over q_max; activations are per-tensor symmetric a-bit codes
 (a = 8 unless stated) with a static scale if given, else absmax/(2^(a-1)-1); a member owns a contiguous range of
 orders in every layer and its own activation scale; in a chain a skip connection
 is member-wise, except one that reads the network input, which only the first
@@ -38,7 +42,8 @@ Pins: every function here is checked in tests/test_oracle_pins.py against facts
 that do not come from this file (hand-worked example, exhaustive nearest-code
 search, the Lemma's bound, brute-force mask enumeration, torch integer matmul
 and conv2d, closed forms).  Not pinned by the paper (this build's reading only):
-the group-selection criterion, the member-wise treatment of gated MLPs, the
+the group-selection criterion, the entry-selection criterion of an unstructured
+mask, the member-wise treatment of gated MLPs, the
 first-member-only skip from the network input, and the reading of U_ens' index
 ranges with the predictor-size procedure built on it (parity unpinned: only
 hand-evaluated instances of this reading; the per-order norms are pinned by SVD).
@@ -134,6 +139,39 @@ def selection_gap(scores: np.ndarray, keep: int) -> float:
     return (a - b) / a if a > 0 else 0.0
 
 
+def select_entries(E: np.ndarray, keep: int) -> np.ndarray:
+    """Unstructured mask (Sec. 3.1: M^k a sparse tensor): boolean [O, I], True on the `keep`
+    entries of E largest in magnitude; entries of equal magnitude go to the lower flat
+    (row-major) index."""
+    a = np.abs(np.asarray(E, dtype=f32)).ravel()
+    n = a.shape[0]
+    M = np.zeros(n, dtype=bool)
+    if keep >= n:
+        M[:] = True
+        return M.reshape(E.shape)
+    thr = np.partition(a, n - keep)[n - keep]          # the keep-th largest magnitude
+    M[a > thr] = True
+    ties = np.flatnonzero(a == thr)
+    M[ties[:keep - int(M.sum())]] = True
+    return M.reshape(E.shape)
+
+
+def quantize_rows_masked(E: np.ndarray, M: np.ndarray, bits: int):
+    """quantize_rows over the entries M keeps: s[o] = max_{i: M[o,i]} |E[o,i]| / q_max, codes
+    clamp(rint(E / s)) on kept entries and 0 elsewhere; a row without a kept entry (or whose
+    kept entries are all zero) has scale 0 and codes 0."""
+    E = np.asarray(E, dtype=f32)
+    qm = f32(q_max(bits))
+    amax = np.max(np.where(M, np.abs(E), f32(0)), axis=1).astype(f32)
+    s = (amax / qm).astype(f32)
+    live = s > 0
+    div = np.where(live, s, f32(1.0)).astype(f32)
+    q = np.clip(np.rint(E / div[:, None]), -qm, qm)
+    q[~live, :] = 0
+    q[~M] = 0
+    return q.astype(np.int8), s
+
+
 # ----------------------------------------------------------------------------
 # Sec. 3.1, Eq. (2)-(3) and the masked form: R^k = M^k Q^-1(Q(W - sum_{j<k} R^j))
 # ----------------------------------------------------------------------------
@@ -183,7 +221,8 @@ class Expansion:
 
 
 def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
-           residuals: Optional[list] = None, gaps: Optional[list] = None, operator=None) -> Expansion:
+           residuals: Optional[list] = None, gaps: Optional[list] = None, operator=None,
+           mask: str = "structured", masks: Optional[list] = None) -> Expansion:
     """Residual expansion of W [O, I] to order K.
 
     E_1 = W.  For k = 1..K: (k>=2 and gamma<1: keep the top n_keep groups of E_k
@@ -192,7 +231,12 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
     their residual on unchanged.  If `residuals` is a list, E_2..E_{K+1} are
     appended to it (copies); if `gaps` is a list, the selection_gap of every mask
     that was chosen is appended to it.  `operator` replaces round-to-nearest in every
-    order (see quantize_rows)."""
+    order (see quantize_rows).
+
+    mask = "unstructured": orders k >= 2 keep the n_keep(gamma, O*I) entries of E_k largest in
+    magnitude instead of whole groups (select_entries); every row is stored, pruned entries have
+    code 0 and pass their residual on unchanged.  If `masks` is a list, the boolean mask of every
+    order k >= 2 is appended to it."""
     W = np.asarray(W, dtype=f32)
     if W.ndim != 2:
         raise ValueError("W must be [out, in]")
@@ -201,10 +245,27 @@ def expand(W: np.ndarray, bits: int, K: int, gamma: float, group: int,
         raise ValueError("need K >= 1 and out % group == 0")
     q_max(bits)
     n_g = O // group
-    keep = n_keep(gamma, n_g)
+    if mask not in ("structured", "unstructured"):
+        raise ValueError("mask is 'structured' or 'unstructured'")
+    unstructured = mask == "unstructured"
+    if unstructured and operator is not None:
+        raise ValueError("the operator plug-in goes with structured masks")
+    keep = n_g if unstructured else n_keep(gamma, n_g)
+    keep_entries = n_keep(gamma, O * I)
     E = W.copy()
     orders: List[Order] = []
     for k in range(1, K + 1):
+        if unstructured and k >= 2 and keep_entries < O * I:
+            Mk = select_entries(E, keep_entries)
+            if masks is not None:
+                masks.append(Mk.copy())
+            q, s = quantize_rows_masked(E, Mk, bits)
+            Rk = (s[:, None] * q.astype(f32)).astype(f32)
+            E = np.where(Mk, (E - Rk).astype(f32), E)          # pruned entries pass on unchanged
+            orders.append(Order(np.arange(n_g, dtype=np.int32), s, q))
+            if residuals is not None:
+                residuals.append(E.copy())
+            continue
         if k == 1 or keep == n_g:
             gids = np.arange(n_g, dtype=np.int32)
         else:

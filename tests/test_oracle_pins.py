@@ -220,6 +220,71 @@ def test_mask_is_energy_optimal_by_enumeration():
         assert sorted(best) == e.orders[1].group_ids.tolist()
 
 
+# ---------------------------------------------------------------- unstructured masks (Sec. 3.1)
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_unstructured_mask_structure(bits):
+    """Orders k >= 2 keep exactly ceil(gamma * O * I) entries; pruned entries have code 0 and hand
+    their residual on bit for bit; kept entries obey |e| <= s/2; every kept magnitude is at least
+    every pruned one; gamma = 1 is the dense expansion."""
+    W = _rand_w(40, 48, 72, heavy=True)
+    K, gamma = 4, 0.3
+    res, masks = [], []
+    e = po.expand(W, bits, K, gamma, 16, residuals=res, masks=masks, mask="unstructured")
+    keep = math.ceil(gamma * W.size - 1e-6)
+    assert len(masks) == K - 1
+    prev = res[0]
+    for k in range(2, K + 1):
+        M = masks[k - 2]
+        assert M.sum() == keep
+        o = e.orders[k - 1]
+        assert o.group_ids.tolist() == list(range(3))            # every row is stored
+        assert not np.any(o.codes[~M])
+        assert np.array_equal(res[k - 1][~M], prev[~M])
+        assert np.all(np.abs(res[k - 1])[M] <= (o.scales[:, None] / 2 * (1 + 1e-6) + 1e-30 + 0 * prev)[M])
+        assert np.abs(prev)[M].min() >= np.abs(prev)[~M].max()
+        # the scale of a row is its largest kept magnitude over q_max (independent quantizer)
+        amax = np.where(M, np.abs(prev), 0).max(axis=1)
+        assert np.array_equal(o.scales, (amax / f32(po.q_max(bits))).astype(f32))
+        prev = res[k - 1]
+    d = po.expand(W, bits, K, 1.0, 16)
+    u1 = po.expand(W, bits, K, 1.0, 16, mask="unstructured")
+    for k in range(K):
+        assert np.array_equal(d.orders[k].codes, u1.orders[k].codes)
+        assert np.array_equal(d.orders[k].scales, u1.orders[k].scales)
+    assert np.array_equal(e.orders[0].codes, d.orders[0].codes)      # R^1 is dense either way
+
+
+def test_unstructured_mask_by_enumeration_and_ties():
+    """Tiny layers: of all masks with n_keep entries the chosen one keeps the most residual
+    magnitude; among equal magnitudes the lower flat index wins."""
+    for seed, (O, I, gamma) in enumerate([(2, 5, 0.5), (3, 4, 0.34), (2, 6, 0.25)]):
+        W = _rand_w(50 + seed, O, I, heavy=True)
+        masks = []
+        e = po.expand(W, 4, 2, gamma, 1, masks=masks, mask="unstructured")
+        E2 = np.abs(W.astype(np.float64) - e.reconstruct(1)).ravel()
+        keep = po.n_keep(gamma, O * I)
+        best = max(itertools.combinations(range(O * I), keep), key=lambda c: sum(E2[i] for i in c))
+        assert sorted(best) == np.flatnonzero(masks[0].ravel()).tolist()
+    E = np.array([[0.5, -0.25, 0.25], [0.25, -0.5, 0.125]], dtype=f32)
+    assert np.flatnonzero(po.select_entries(E, 3).ravel()).tolist() == [0, 1, 4]     # first of the three 0.25s
+    assert np.flatnonzero(po.select_entries(E, 4).ravel()).tolist() == [0, 1, 2, 4]
+    assert po.select_entries(E, 6).all() and po.select_entries(E, 1).ravel().tolist() == [True] + [False] * 5
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_unstructured_expansion_beats_the_dense_one_at_equal_budget(bits):
+    """Sec. 3.1: at a matched budget of operations the sparse expansion is closer to the
+    weights than the standard one.  Budget of two dense orders: K = 3 with half the entries kept
+    in orders 2 and 3, against the dense K = 2."""
+    for seed, heavy in [(60, False), (61, True)]:
+        W = _rand_w(seed, 64, 96, heavy=heavy)
+        dense2 = po.expand(W, bits, 2, 1.0, 16)
+        sparse3 = po.expand(W, bits, 3, 0.5, 16, mask="unstructured")
+        stored = sum(int(np.count_nonzero(sparse3.dense_codes(k))) for k in (2, 3))
+        assert stored <= W.size                                       # no more entries than one dense order
+        assert np.linalg.norm(W - sparse3.reconstruct()) < np.linalg.norm(W - dense2.reconstruct())
+
+
 def test_n_keep_rounding():
     assert po.n_keep(0.25, 172) == 43 and po.n_keep(0.5, 344) == 172
     assert po.n_keep(0.5, 16) == 8 and po.n_keep(0.5, 96) == 48 and po.n_keep(0.5, 24) == 12
