@@ -80,6 +80,22 @@ int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, const float* 
 int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
                 int group, void* stream, pipe_expansion** exp_out);
 
+/* The expansion with an unstructured mask (Sec. 3.1: the pruning mask M^k of the masked
+ * equation as a sparse tensor instead of row-wise zeros).  R^1 is dense; every order
+ * k >= 2 keeps the ceil(gamma * out * in) entries of the residual that are largest in
+ * magnitude (re-selected at every order; entries of equal magnitude go to the lower
+ * row-major index), quantizes each row over its kept entries (scale = largest kept
+ * magnitude / q_max, a row without kept entries has scale 0) and leaves the pruned
+ * entries' residual to the next order.  Every row of every order is stored (pruned
+ * entries are zero codes), so the stored size and the integer work are those of the
+ * dense expansion: the mask buys accuracy per non-zero code, not speed on this
+ * device.  `group` only fixes the row-block layout (same constraints as pipe_expand).
+ * Arguments, ownership, errors and the arithmetic of the quantizer as pipe_expand;
+ * every forward entry point accepts the result.  pipe_expansion_error_bound does not
+ * (PIPE_EINVAL): a pruned entry keeps an earlier order's residual.                    */
+int pipe_expand_unstructured(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                             int group, void* stream, pipe_expansion** exp_out);
+
 /* The same expansion with another rounding operator (Sec. 1 and Sec. 4.4: the method is
  * agnostic to the quantization operator and combines with operators that choose the
  * rounding direction themselves).  For every order k = 1..K the builder writes, on

@@ -43,6 +43,7 @@ def _load():
     vp, ci, cf = C.c_void_p, C.c_int, C.c_float
     pi = C.POINTER(C.c_int)
     lib.pipe_expand.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
+    lib.pipe_expand_unstructured.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
     lib.pipe_expand_with_operator.argtypes = [vp, ci, ci, ci, ci, cf, ci, _ROUNDING_FN, vp, vp, vp, vp, vp, C.POINTER(vp)]
     lib.pipe_expansion_free.argtypes = [vp]
     lib.pipe_expansion_info.argtypes = [vp, pi, pi, pi, pi, pi, C.POINTER(cf), C.POINTER(C.c_int64)]
@@ -74,7 +75,7 @@ def _load():
     lib.pipe_strerror.argtypes = [ci]
     lib.pipe_strerror.restype = C.c_char_p
     lib.pipe_last_device_error.restype = C.c_char_p
-    for f in ("pipe_expand", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
+    for f in ("pipe_expand", "pipe_expand_unstructured", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
               "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
         getattr(lib, f).restype = ci
@@ -158,6 +159,15 @@ def pipe_expand(W: torch.Tensor, bits: int, K: int, gamma: float, group: int) ->
     h = C.c_void_p()
     _check(_lib.pipe_expand(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(bits), int(K),
                             float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand")
+    return Expansion(h.value)
+
+
+def pipe_expand_unstructured(W: torch.Tensor, bits: int, K: int, gamma: float, group: int) -> Expansion:
+    if W.dim() != 2:
+        raise ValueError("W must be [out, in]")
+    h = C.c_void_p()
+    _check(_lib.pipe_expand_unstructured(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(bits), int(K),
+                                         float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand_unstructured")
     return Expansion(h.value)
 
 

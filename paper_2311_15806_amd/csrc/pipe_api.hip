@@ -82,13 +82,14 @@ extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
 }
 
 // ------------------------------------------------------------------ helpers
-static int n_keep_of(float gamma, int n_groups) {
-  const double v = (double)gamma * (double)n_groups * (1.0 - 1e-6);
-  int k = (int)std::ceil(v);
+static long long n_keep_of64(float gamma, long long n) {
+  const double v = (double)gamma * (double)n * (1.0 - 1e-6);
+  long long k = (long long)std::ceil(v);
   if (k < 1) k = 1;
-  if (k > n_groups) k = n_groups;
+  if (k > n) k = n;
   return k;
 }
+static int n_keep_of(float gamma, int n_groups) { return (int)n_keep_of64(gamma, n_groups); }
 
 static int parse_split(int K, const int* split, int M, int* lo, int* hi, int* M_out) {
   if (split == nullptr) {
@@ -239,13 +240,16 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
                        double** energy_out, const RoundingHook& hook) {
   const int out = e->out, in = e->in, K = e->K, group = e->group;
   const int n_groups = e->n_groups;
-  const int keep = n_keep_of(e->gamma, n_groups);
+  const int keep = e->unstructured ? n_groups : n_keep_of(e->gamma, n_groups);
+  const long long n_entries = (long long)out * in, keep_entries = n_keep_of64(e->gamma, n_entries);
   float* E = nullptr;
   PIPE_HIP(hipMalloc(&E, (size_t)out * in * sizeof(float)));
   *resid_out = E;
   PIPE_HIP(hipMemcpyAsync(E, W_dev, (size_t)out * in * sizeof(float), hipMemcpyDeviceToDevice, st));
   double* energy = nullptr;
-  PIPE_HIP(hipMalloc(&energy, ((size_t)out + n_groups) * sizeof(double) + (size_t)n_groups * sizeof(int32_t)));
+  // scratch: row energies, group scores and flags of the group selection; or the histogram of the entry selection
+  PIPE_HIP(hipMalloc(&energy, std::max(((size_t)out + n_groups) * sizeof(double) + (size_t)n_groups * sizeof(int32_t),
+                                       (size_t)2049 * sizeof(uint32_t))));
   *energy_out = energy;
   const int ksup = 512 / e->bits;
   e->orders.resize(K);
@@ -269,6 +273,12 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
       if (rc) return rc;
     }
     int rc = PIPE_OK;
+    uint32_t thr_key = PIPE_NO_MASK_KEY;
+    long long tie_cut = PIPE_NO_MASK_CUT;
+    if (e->unstructured && k > 0 && keep_entries < n_entries) {
+      rc = select_entry_threshold(E, n_entries, keep_entries, reinterpret_cast<uint32_t*>(energy), &thr_key, &tie_cut, st);
+      if (rc) return rc;
+    }
     if (hook.fn) {
       // another rounding operator: hand it the rows of this order and their scales, take its codes
       rc = launch_gather_rows(E, in, e->qbits, group, o.gids_dev, o.n_kept, hook.rows, hook.scales, st);
@@ -276,7 +286,7 @@ static int expand_impl(pipe_expansion* e, const float* W_dev, hipStream_t st, fl
       if (hook.fn(hook.user, k + 1, (int)rows, in, (1 << (e->qbits - 1)) - 1, (void*)st) != 0) return PIPE_EINVAL;
     }
     rc = launch_quantize_rows(E, out, in, e->in_pad, e->bits, e->qbits, group, o.gids_dev, o.n_kept, o.scales_dev,
-                              o.packed_dev, hook.fn ? hook.codes : nullptr, st);
+                              o.packed_dev, hook.fn ? hook.codes : nullptr, thr_key, tie_cut, st);
     if (rc) return rc;
     e->stream_bytes += (int64_t)o.packed_bytes + (int64_t)rows * 4 + (int64_t)o.n_kept * 4;
   }
@@ -299,7 +309,7 @@ extern "C" int pipe_fold_batchnorm(const float* W_dev, const float* bias_dev, co
 }
 
 static int expand_checked(const float* W_dev, int out, int in, int bits, int K, float gamma, int group,
-                          const RoundingHook& hook, void* stream, pipe_expansion** exp_out) {
+                          const RoundingHook& hook, bool unstructured, void* stream, pipe_expansion** exp_out) {
   if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;
   if (bits < 2 || bits > 8) return PIPE_EINVAL;
   if (K < 1 || K > PIPE_MAX_K) return PIPE_EINVAL;
@@ -310,7 +320,7 @@ static int expand_checked(const float* W_dev, int out, int in, int bits, int K, 
   if ((int64_t)in > (int64_t)130000) return PIPE_ESHAPE;
   pipe_expansion* e = new (std::nothrow) pipe_expansion();
   if (!e) return PIPE_ENOMEM;
-  e->out = out; e->in = in; e->qbits = bits; e->bits = bits == 2 ? 2 : (bits <= 4 ? 4 : 8); e->K = K; e->group = group; e->gamma = gamma;
+  e->out = out; e->in = in; e->qbits = bits; e->bits = bits == 2 ? 2 : (bits <= 4 ? 4 : 8); e->K = K; e->group = group; e->gamma = gamma; e->unstructured = unstructured;
   e->n_groups = out / group;
   e->rbpg = group / 16;
   e->n_rb = out / 16;
@@ -334,7 +344,12 @@ static int expand_checked(const float* W_dev, int out, int in, int bits, int K, 
 
 extern "C" int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamma,
                            int group, void* stream, pipe_expansion** exp_out) {
-  return expand_checked(W_dev, out, in, bits, K, gamma, group, RoundingHook{}, stream, exp_out);
+  return expand_checked(W_dev, out, in, bits, K, gamma, group, RoundingHook{}, false, stream, exp_out);
+}
+
+extern "C" int pipe_expand_unstructured(const float* W_dev, int out, int in, int bits, int K, float gamma,
+                                        int group, void* stream, pipe_expansion** exp_out) {
+  return expand_checked(W_dev, out, in, bits, K, gamma, group, RoundingHook{}, true, stream, exp_out);
 }
 
 extern "C" int pipe_expand_with_operator(const float* W_dev, int out, int in, int bits, int K, float gamma, int group,
@@ -343,7 +358,7 @@ extern "C" int pipe_expand_with_operator(const float* W_dev, int out, int in, in
   if (!fn || !rows_dev || !scales_dev || !codes_dev) return PIPE_EINVAL;
   RoundingHook hook;
   hook.fn = fn; hook.user = user; hook.rows = rows_dev; hook.scales = scales_dev; hook.codes = codes_dev;
-  return expand_checked(W_dev, out, in, bits, K, gamma, group, hook, stream, exp_out);
+  return expand_checked(W_dev, out, in, bits, K, gamma, group, hook, false, stream, exp_out);
 }
 
 extern "C" int pipe_expansion_free(pipe_expansion* e) {

@@ -227,6 +227,7 @@ extern "C" int pipe_expansion_reconstruct(const pipe_expansion* e, int upto, flo
 
 extern "C" int pipe_expansion_error_bound(const pipe_expansion* e, double* u_lemma, double* u_stored) {
   if (!e) return PIPE_EINVAL;
+  if (e->unstructured) return PIPE_EINVAL;   // a pruned entry keeps an earlier order's residual: the row scales do not bound it
   PIPE_HIP(hipDeviceSynchronize());
   const size_t n_pos = (size_t)e->n_bins * e->bin_cap;
   std::vector<float> all(n_pos * 16);

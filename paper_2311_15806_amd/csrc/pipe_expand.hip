@@ -1,11 +1,18 @@
 // Residual-expansion builder (Sec. 3.1, Eq. (2)-(3) and the masked form; quantizer: Sec. 3,
 // Eq. (1)).  Row-parallel kernels: residual energy per row (fp64), top-gamma group selection,
 // per-row quantization with in-place residual update and packing into the tile layout.
+// Unstructured masks (Sec. 3.1: M^k a sparse tensor): the magnitude of the keep-th largest
+// residual entry is found exactly by a three-level radix select over the entries' bit patterns,
+// entries of that magnitude are kept in flat-index order up to a cut, and the row quantizer
+// skips the entries the mask prunes.
 //
 // The integer codes depend on the fp32 arithmetic, so every operation that feeds a rounding
 // decision is written with an explicitly rounded intrinsic (IEEE division, separate multiply
 // and subtract) and this file is compiled with floating-point contraction off.
 #include "pipe_internal.h"
+
+#include <algorithm>
+#include <vector>
 
 namespace {
 
@@ -66,13 +73,51 @@ __global__ void group_compact_kernel(const int32_t* __restrict__ flag, int n_gro
   gids[idx] = g;
 }
 
+// ---- unstructured mask: histogram of one digit of the magnitudes' bit patterns ------------
+// key = bits of |e| (monotone in |e| for finite values); entries whose key >> prefix_shift equals
+// prefix (all entries if prefix_shift is 32) are counted in bin (key >> shift) & (bins - 1).
+constexpr int SEL_BINS = 2048;
+__global__ __launch_bounds__(BLK) void key_histogram_kernel(const float* __restrict__ E, long long n, int shift, int bins,
+                                                            int prefix_shift, uint32_t prefix, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t h[SEL_BINS];
+  for (int i = threadIdx.x; i < bins; i += BLK) h[i] = 0u;
+  __syncthreads();
+  for (long long i = (long long)blockIdx.x * BLK + threadIdx.x; i < n; i += (long long)gridDim.x * BLK) {
+    const uint32_t key = __float_as_uint(fabsf(E[i]));
+    if (prefix_shift >= 32 || (key >> prefix_shift) == prefix) atomicAdd(&h[(key >> shift) & (uint32_t)(bins - 1)], 1u);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < bins; i += BLK)
+    if (h[i]) atomicAdd(&hist[i], h[i]);
+}
+
+// ---- entries of magnitude exactly thr_key with flat index <= cut ---------------------------
+__global__ __launch_bounds__(BLK) void count_ties_kernel(const float* __restrict__ E, long long n, uint32_t thr_key,
+                                                         long long cut, uint32_t* __restrict__ count) {
+  uint32_t c = 0;
+  const long long hi = cut + 1 < n ? cut + 1 : n;
+  for (long long i = (long long)blockIdx.x * BLK + threadIdx.x; i < hi; i += (long long)gridDim.x * BLK)
+    c += __float_as_uint(fabsf(E[i])) == thr_key;
+  __shared__ uint32_t sm[BLK];
+  sm[threadIdx.x] = c;
+  __syncthreads();
+  for (int s = BLK / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && sm[0]) atomicAdd(count, sm[0]);
+}
+
 // ---- quantize one stored row, update its residual in place, pack its codes ----------------
+// An entry takes part if its magnitude's bit pattern exceeds thr_key, or equals it with a flat
+// index of at most tie_cut (thr_key = 0 with the largest tie_cut: every entry, the structured case).
 template <int BITS>
 __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ E, int in, int in_pad,
                                                             int group, const int32_t* __restrict__ gids,
                                                             float* __restrict__ scales,
                                                             uint8_t* __restrict__ packed, int QMAX,
-                                                            const int8_t* __restrict__ given) {
+                                                            const int8_t* __restrict__ given,
+                                                            uint32_t thr_key, long long tie_cut) {
   // BITS is the width of the stored code (8, 4 or 2); QMAX = 2^(b-1)-1 of the quantizer, which
   // may be narrower (3-bit codes in 4-bit fields, 5..7-bit codes in bytes).  given: NULL, or the
   // codes [rows, in] another rounding operator chose for these rows (clamped here)
@@ -83,9 +128,17 @@ __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ 
   const int slot = r / group;
   const int o = gids[slot] * group + (r - slot * group);
   float* e = E + (size_t)o * in;
+  const long long flat0 = (long long)o * in;
+  auto kept = [&](float v, int k) {
+    const uint32_t key = __float_as_uint(fabsf(v));
+    return key > thr_key || (key == thr_key && flat0 + k <= tie_cut);
+  };
 
   float amax = 0.f;
-  for (int i = threadIdx.x; i < in; i += BLK) amax = fmaxf(amax, fabsf(e[i]));
+  for (int i = threadIdx.x; i < in; i += BLK) {
+    const float v = e[i];
+    amax = fmaxf(amax, kept(v, i) ? fabsf(v) : 0.f);
+  }
   __shared__ float sm[BLK];
   sm[threadIdx.x] = amax;
   __syncthreads();
@@ -107,7 +160,7 @@ __global__ __launch_bounds__(BLK) void quantize_rows_kernel(float* __restrict__ 
     for (int t = 0; t < 16; ++t) {
       const int k = c * 16 + t;
       int q = 0;
-      if (live && k < in) {
+      if (live && k < in && kept(e[k], k)) {
         const float v = e[k];
         float qf = given != nullptr ? (float)given[(size_t)r * in + k]
                                     : rintf(__fdiv_rn(v, s));   // round half to even
@@ -265,19 +318,67 @@ int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, co
   return PIPE_OK;
 }
 
+// The keep-th largest magnitude of the n entries of E and the cut among the entries that share
+// it: *thr_key = its bit pattern, *tie_cut = the flat index up to which entries of exactly that
+// magnitude are kept (ties go to the lower flat index).  hist_dev: SEL_BINS + 1 words of scratch.
+// Synchronizes the stream several times (an offline step).
+int select_entry_threshold(const float* E, long long n, long long keep, uint32_t* hist_dev, uint32_t* thr_key,
+                           long long* tie_cut, hipStream_t st) {
+  if (keep < 1 || keep > n) return PIPE_EINVAL;
+  const unsigned grid = (unsigned)std::min<long long>((n + BLK - 1) / BLK, 4096);
+  std::vector<uint32_t> h(SEL_BINS);
+  // digits of the 31-bit key, most significant first: 11, 11 and 9 bits
+  const int shifts[3] = {20, 9, 0}, nbins[3] = {2048, 2048, 512};
+  uint32_t prefix = 0;
+  long long want = keep;   // entries still to take from the current prefix class, largest first
+  uint32_t ties = 0;
+  for (int lvl = 0; lvl < 3; ++lvl) {
+    PIPE_HIP(hipMemsetAsync(hist_dev, 0, SEL_BINS * sizeof(uint32_t), st));
+    hipLaunchKernelGGL(key_histogram_kernel, dim3(grid), dim3(BLK), 0, st, E, n, shifts[lvl], nbins[lvl],
+                       lvl == 0 ? 32 : shifts[lvl - 1], prefix, hist_dev);
+    PIPE_HIP(hipGetLastError());
+    PIPE_HIP(hipMemcpyAsync(h.data(), hist_dev, SEL_BINS * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    PIPE_HIP(hipStreamSynchronize(st));
+    int b = nbins[lvl] - 1;
+    for (; b > 0 && (long long)h[b] < want; --b) want -= h[b];
+    prefix = lvl == 0 ? (uint32_t)b : ((prefix << (shifts[lvl - 1] - shifts[lvl])) | (uint32_t)b);
+    ties = h[b];
+  }
+  *thr_key = prefix;
+  if (want >= (long long)ties) {   // every entry of the threshold magnitude is kept
+    *tie_cut = n;
+    return PIPE_OK;
+  }
+  // the smallest flat index c with `want` entries of the threshold magnitude at or below it
+  long long lo = 0, hi = n - 1;
+  uint32_t* cnt_dev = hist_dev + SEL_BINS;
+  while (lo < hi) {
+    const long long mid = lo + (hi - lo) / 2;
+    uint32_t c = 0;
+    PIPE_HIP(hipMemsetAsync(cnt_dev, 0, sizeof(uint32_t), st));
+    hipLaunchKernelGGL(count_ties_kernel, dim3(grid), dim3(BLK), 0, st, E, n, prefix, mid, cnt_dev);
+    PIPE_HIP(hipGetLastError());
+    PIPE_HIP(hipMemcpyAsync(&c, cnt_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    PIPE_HIP(hipStreamSynchronize(st));
+    if ((long long)c >= want) hi = mid; else lo = mid + 1;
+  }
+  *tie_cut = lo;
+  return PIPE_OK;
+}
+
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
-                         const int8_t* given, hipStream_t st) {
+                         const int8_t* given, uint32_t thr_key, long long tie_cut, hipStream_t st) {
   const int qmax = (1 << (qbits - 1)) - 1;
   (void)out;
   const int rows = n_kept * group;
   if (rows == 0) return PIPE_OK;
   if (bits == 8)
-    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
+    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   else if (bits == 4)
-    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
+    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   else
-    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given);
+    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -98,6 +98,7 @@ struct pipe_expansion {
   int out = 0, in = 0, bits = 0, K = 0, group = 0;   // bits: width of a stored code (8, 4 or 2)
   int qbits = 0;      // width the quantizer was asked for (2..8); codes lie in +-(2^(qbits-1)-1)
   float gamma = 1.f;
+  bool unstructured = false;   // orders k >= 2 keep single entries (all rows stored) instead of groups
   int n_groups = 0;
   int rbpg = 0;       // row blocks per group = group/16
   int n_rb = 0;       // out/16
@@ -166,9 +167,17 @@ int launch_group_select(const double* row_energy, int n_groups, int group, int n
                         int32_t* gids_out, hipStream_t st);
 int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, const float* beta, const float* mean,
                           const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st);
+// An entry takes part if the bit pattern of its magnitude exceeds thr_key, or equals it with a
+// flat index <= tie_cut; PIPE_NO_MASK_KEY / PIPE_NO_MASK_CUT: every entry.
+constexpr uint32_t PIPE_NO_MASK_KEY = 0u;
+constexpr long long PIPE_NO_MASK_CUT = 0x7fffffffffffffffll;
 int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qbits, int group,
                          const int32_t* gids, int n_kept, float* scales, uint8_t* packed,
-                         const int8_t* given, hipStream_t st);
+                         const int8_t* given, uint32_t thr_key, long long tie_cut, hipStream_t st);
+// unstructured mask: bit pattern of the keep-th largest magnitude among the n entries of E and the
+// flat index up to which entries of exactly that magnitude are kept; hist_dev: 2049 words of scratch
+int select_entry_threshold(const float* E, long long n, long long keep, uint32_t* hist_dev, uint32_t* thr_key,
+                           long long* tie_cut, hipStream_t st);
 // the rows an order quantizes, compact [n_kept*group, in], and their scales max|row| / q_max
 int launch_gather_rows(const float* E, int in, int qbits, int group, const int32_t* gids, int n_kept,
                        float* rows_out, float* scales_out, hipStream_t st);

@@ -49,6 +49,9 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_expand(fake, 64, 64, 4, 2, 0.5, 8, None, C.byref(h)) == ESHAPE       # group % 16
     assert lib.pipe_expand(fake, 0, 64, 4, 2, 0.5, 16, None, C.byref(h)) == ESHAPE
     assert h.value is None
+    assert lib.pipe_expand_unstructured(None, 64, 64, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == EINVAL
+    assert lib.pipe_expand_unstructured(fake, 64, 64, 4, 2, C.c_float(1.5), 16, None, C.byref(h)) == EINVAL
+    assert lib.pipe_expand_unstructured(fake, 60, 64, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == ESHAPE
     assert lib.pipe_expand_with_operator(fake, 64, 64, 4, 2, C.c_float(0.5), 16, None, None, fake, fake, fake, None, C.byref(h)) == EINVAL   # no operator
     assert lib.pipe_forward(None, None, 4, C.c_float(0), None, 0, None, 1, None, None) == EINVAL
     assert lib.pipe_chain_forward(None, 1, None, 4, C.c_float(0), None, 0, None, None, None) == EINVAL

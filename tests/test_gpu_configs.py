@@ -182,3 +182,21 @@ def test_c5_gated_mlp(pipe, c5, T):
         members.append(po.dequantize(o2, acc2, sh, split, None, f32)[m])
     y_ref = po.sum_members(np.stack(members))
     assert_close_fp32(y.cpu().numpy()[sel], y_ref)
+
+
+def test_c4_weight_with_unstructured_mask(pipe):
+    """The 11008 x 4096 layer expanded with an unstructured mask (Sec. 3.1): 45 million entries per
+    selection, so every level of the builder's radix select holds bins far beyond 16 bits; codes
+    and scales equal the checker's bit for bit, and a decode-sized forward its accumulators."""
+    w = wl.with_tokens(wl.C4, 16)
+    spec = w.layers[0]
+    W, x = wl.make_weight(w, 0), wl.make_input(w)
+    K = 3
+    ora = po.expand(W, spec.bits, K, spec.gamma, spec.group, mask="unstructured")
+    g = pipe.pipe_expand_unstructured(dev(W), spec.bits, K, spec.gamma, spec.group)
+    assert_expansion_equal(g, ora)
+    ref = po.forward(ora, x)
+    acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    assert_close_fp32(pipe.pipe_forward(g, dev(x)).cpu().numpy(), ref["y"])
+    g.free()

@@ -525,3 +525,51 @@ def test_expand_with_another_rounding_operator(pipe):
         pipe.pipe_expand_with_operator(dev(W), bits, K, gamma, group, broken)
     for g in (g0, g1, g2, g3):
         g.free()
+
+
+@pytest.mark.parametrize("bits,K,gamma,O,I", [(4, 3, 0.5, 96, 200), (2, 4, 0.25, 128, 333), (8, 2, 0.1, 64, 520),
+                                               (3, 3, 0.37, 48, 257), (4, 2, 1.0, 32, 64)])
+def test_unstructured_mask_expansion_and_forward(pipe, bits, K, gamma, O, I):
+    """Unstructured masks (Sec. 3.1): the builder's exact top-magnitude selection (radix select over
+    the entries' bit patterns) gives the checker's codes and scales bit for bit; both contraction
+    kernels then give its integer accumulators and output."""
+    W = _w(600 + bits, O, I)
+    ora = po.expand(W, bits, K, gamma, 16, mask="unstructured")
+    g = pipe.pipe_expand_unstructured(dev(W), bits, K, gamma, 16)
+    assert_expansion_equal(g, ora)
+    for T in (7, 150):
+        x = _x(610 + T, T, I)
+        ref = po.forward(ora, x)
+        acc, _, _ = pipe.pipe_forward_acc(g, dev(x))
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert_close_fp32(pipe.pipe_forward(g, dev(x)).cpu().numpy(), ref["y"])
+    if K >= 2:
+        split = [1, K - 1]
+        x = _x(613, 20, I)
+        assert_close_fp32(pipe.pipe_forward(g, dev(x), split=split).cpu().numpy(), po.forward(ora, x, split=split)["y"])
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_expansion_error_bound(g)
+    g.free()
+
+
+def test_unstructured_mask_ties_go_to_the_lower_index(pipe):
+    """Weights drawn from a handful of magnitudes: the threshold magnitude is shared by thousands of
+    entries, of which the builder must keep exactly the first ones in row-major order."""
+    rng = np.random.default_rng(620)
+    O, I = 64, 384
+    levels = np.array([0.5, 0.25, 0.125, 0.0625, 0.03125], dtype=np.float32)
+    for bits, K, gamma in [(8, 2, 0.3), (4, 3, 0.55), (2, 3, 0.5)]:
+        W = (levels[rng.integers(0, 5, size=(O, I))] * rng.choice([-1.0, 1.0], size=(O, I))).astype(np.float32)
+        masks = []
+        ora = po.expand(W, bits, K, gamma, 16, mask="unstructured", masks=masks)
+        assert 0 < np.count_nonzero(masks[0]) < W.size
+        g = pipe.pipe_expand_unstructured(dev(W), bits, K, gamma, 16)
+        assert_expansion_equal(g, ora)
+        g.free()
+    # a mask that keeps every non-zero entry and some of the zeros: which zeros does not matter
+    W = np.zeros((32, 128), dtype=np.float32)
+    W[::3, ::5] = rng.standard_normal(W[::3, ::5].shape).astype(np.float32)
+    ora = po.expand(W, 4, 3, 0.5, 16, mask="unstructured")
+    g = pipe.pipe_expand_unstructured(dev(W), 4, 3, 0.5, 16)
+    assert_expansion_equal(g, ora)
+    g.free()
