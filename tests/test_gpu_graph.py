@@ -81,3 +81,80 @@ def test_chain_graph_replays(T):
         assert torch.equal(other, eager[(i + 1) % 3])
     for g in gs:
         g.free()
+
+
+@pytest.mark.parametrize("kind,T", [("gelu", 11), ("gelu", 300), ("gated", 11), ("gated", 300)])
+def test_mlp_graph_replays(kind, T):
+    """The two-layer MLP call (quantizers, both contractions, hidden maxima raised in layer 1's
+    epilogue and consumed by the hidden quantizer, slots cleared inside the kernels) captured once
+    and replayed with other inputs, for decode-sized and tiled batches."""
+    import paper_2311_15806_amd.binding as pipe
+    base = wl.C3 if kind == "gelu" else wl.C5
+    w = wl.scaled(base, out_div=8, in_div=8, tokens=T)
+    split = list(w.split) if w.split else None
+    es = [pipe.pipe_expand(torch.from_numpy(wl.make_weight(w, l)).cuda(), s.bits, s.K, s.gamma, s.group)
+          for l, s in enumerate(w.layers)]
+    act = pipe.PIPE_ACT_GELU if kind == "gelu" else pipe.PIPE_ACT_SILU_GATED
+    xs = [torch.from_numpy(wl.make_input(w)).cuda() * s for s in (1.0, 0.3, 4.0)]
+    x = xs[0].clone()
+    out = torch.empty((T, w.layers[-1].out_features), device="cuda")
+    eager = [pipe.pipe_mlp_forward(es[0], es[1], act, xi, split=split).clone() for xi in xs]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.pipe_mlp_forward(es[0], es[1], act, x, split=split, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipe.pipe_mlp_forward(es[0], es[1], act, x, split=split, out=out)
+    for rep in range(6):
+        i = rep % 3
+        x.copy_(xs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[i]), "replay %d differs" % rep
+        other = pipe.pipe_mlp_forward(es[0], es[1], act, xs[(i + 1) % 3], split=split)
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager[(i + 1) % 3])
+    for e in es:
+        e.free()
+
+
+@pytest.mark.parametrize("T", [16, 2048])
+def test_several_steps_in_one_graph_keep_their_order(T):
+    """The benchmark's form of a timed region: K forward steps captured into ONE graph.  Every
+    step reads the shared workspace the previous one wrote (activation codes, maxima, code sums),
+    so a step that started before its predecessor had finished would change a result.  Steps
+    alternate between inputs and write to their own outputs; each must equal its eager result.
+    Full-size layer of the headline workload."""
+    import paper_2311_15806_amd.binding as pipe
+    w = wl.with_tokens(wl.C4, T)
+    spec = w.layers[0]
+    W = torch.from_numpy(wl.make_weight(w, 0)).cuda()
+    g = pipe.pipe_expand(W, spec.bits, spec.K, spec.gamma, spec.group)
+    x0 = torch.from_numpy(wl.make_input(w)).cuda()
+    xs = [x0, x0 * 0.37, torch.roll(x0, 1, dims=0) * 2.5]
+    eager = [pipe.pipe_forward(g, xi).clone() for xi in xs]
+    K = 9
+    outs = [torch.empty_like(eager[0]) for _ in range(K)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.pipe_forward(g, xs[0], out=outs[0])
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(K):
+            pipe.pipe_forward(g, xs[i % 3], out=outs[i])
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(K):
+            assert torch.equal(outs[i], eager[i % 3]), "replay %d, step %d differs" % (rep, i)
+    g.free()
