@@ -16,6 +16,8 @@ Passages followed
   * residual expansion R^1..R^K .................. Sec. 3.1, Eq. (2), (3)
   * structured mask M^k, sparsity ratio gamma .... Sec. 3.1, masked Eq. after (4)
   * unstructured mask M^k (a sparse tensor) ...... Sec. 3.1, same passage
+  * asymmetric activation codes .................. Sec. 4.3 (the comparison of Table
+                                                   compar_sota is made under asymmetric quantization)
   * expanded-layer forward ....................... App. B, Eq. (define_dre)
   * ensemble members, bias in predictor 1 ........ Sec. 3.2, Fig. 2 caption,
                                                    App. B "Ensemble of more Layers"
@@ -33,7 +35,8 @@ ties to the lower group index; an unstructured mask keeps the ceil(gamma*O*I)
 entries of the residual that are largest in magnitude, re-selected at every
 order k>=2, ties to the lower flat index, and a row's scale is the largest kept
 magnitude over q_max; activations are per-tensor symmetric a-bit codes
-(a = 8 unless stated) with a static scale if given, else absmax/(2^(a-1)-1); a member owns a contiguous range of
+(a = 8 unless stated) with a static scale if given, else absmax/(2^(a-1)-1); asymmetric activation codes are
+the unsigned a-bit grid over [min(x, 0), max(x, 0)] with an integer zero point; a member owns a contiguous range of
 orders in every layer and its own activation scale; in a chain a skip connection
 is member-wise, except one that reads the network input, which only the first
 member adds.
@@ -323,14 +326,37 @@ def quantize_activations(x: np.ndarray, s_x: Optional[float] = None, bits: int =
     return q.astype(np.int8), s
 
 
+def quantize_activations_asymmetric(x: np.ndarray, bits: int = 8):
+    """Per-tensor asymmetric a-bit codes (Sec. 4.3 runs its comparison under asymmetric
+    quantization; the paper gives no formula, this is the usual affine quantizer):
+    with hi = max(x, 0) and lo = min(x, 0) over the tensor (so that 0 is a grid point),
+      s = (hi - lo) / (2^a - 1),  z = clamp(rint(-lo / s), 0, 2^a - 1),
+      Q(x) = clamp(rint(x / s) + z, 0, 2^a - 1),   x ~ s * (Q(x) - z),
+    fp32 sums and divisions, rint half to even.  Returns (Q int16 in [0, 2^a - 1], s fp32, z int).
+    An all-zero input gives Q = 0, s = 0, z = 0."""
+    x = np.asarray(x, dtype=f32)
+    if not 2 <= int(bits) <= 8:
+        raise ValueError("bits must lie in 2..8")
+    qa = 2 ** int(bits) - 1
+    hi = f32(max(float(np.max(x)), 0.0)) if x.size else f32(0)
+    nlo = f32(max(float(np.max(-x)), 0.0)) if x.size else f32(0)
+    s = f32(f32(hi + nlo) / f32(qa))
+    if not (s > 0):
+        return np.zeros(x.shape, np.int16), f32(0), 0
+    z = int(np.clip(np.rint(f32(nlo) / s), 0, qa))
+    q = np.clip(np.rint(x / s) + f32(z), 0, qa)
+    return q.astype(np.int16), s, z
+
+
 def contract(Qx: np.ndarray, codes: np.ndarray) -> np.ndarray:
     """acc[t, r] = sum_i Qx[t,i] * codes[r,i], exact, returned as int32.
 
     The products are formed and summed by an fp64 matmul: every operand is an
-    integer of magnitude <= 127 and every partial sum is an integer below
-    127*127*I < 2^53, so each fp64 operation is exact whatever the order."""
+    integer of magnitude <= 255 and every partial sum is an integer below
+    255*127*I < 2^53, so each fp64 operation is exact whatever the order."""
     I = Qx.shape[1]
-    if 127 * 127 * max(I, 1) >= 2 ** 31:
+    bound = int(np.max(np.abs(Qx.astype(np.int64)))) if Qx.size else 0     # 127, or up to 255 for centred asymmetric codes
+    if max(bound, 127) * 127 * max(I, 1) >= 2 ** 31:
         raise ValueError("accumulator would not fit int32")
     a = Qx.astype(np.float64) @ codes.astype(np.float64).T
     return a.astype(np.int64).astype(np.int32)
@@ -395,6 +421,17 @@ def forward(exp: Expansion, x: np.ndarray, s_x: Optional[float] = None, split=No
     if reduce_members:
         return dict(Qx=Qx, s_x=sx, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
     return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
+
+
+def forward_asymmetric(exp: Expansion, x: np.ndarray, split=None, bias=None, act_bits: int = 8):
+    """The expanded layer with asymmetric activation codes: acc_k[t,o] = sum_i (Q(x)[t,i] - z) q_k[o,i]
+    (exact), y = s * sum_k s_k acc_k (+ b), members summed.  Returns a dict with Qx (unsigned codes),
+    s_x, z, acc (int32 [K,T,O]), y (fp32 [T,O]) and y64."""
+    Qx, sx, z = quantize_activations_asymmetric(x, act_bits)
+    acc = forward_acc(exp, Qx.astype(np.int32) - z)
+    ys = dequantize(exp, acc, sx, split, bias, f32)
+    ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
+    return dict(Qx=Qx, s_x=sx, z=z, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
 
 
 # ----------------------------------------------------------------------------

@@ -293,6 +293,61 @@ def test_n_keep_rounding():
 
 
 # ---------------------------------------------------------------- integer contraction
+@pytest.mark.parametrize("a", [8, 6, 4])
+def test_asymmetric_activation_codes(a):
+    """The affine quantizer: every code is the nearest grid point (exhaustive search over the
+    2^a codes), zero is represented exactly, in-range values are off by at most s/2, and a
+    non-negative tensor gets a grid twice as fine as the symmetric one."""
+    rng = np.random.default_rng(70 + a)
+    x = (rng.standard_normal((5, 40)) * 1.7 + 0.6).astype(f32)
+    x[0, 0] = 0.0
+    Q, s, z = po.quantize_activations_asymmetric(x, a)
+    qa = 2 ** a - 1
+    assert Q.min() >= 0 and Q.max() <= qa and 0 <= z <= qa
+    grid = (np.arange(qa + 1) - z).astype(np.float64) * float(s)
+    best = np.abs(x.astype(np.float64)[..., None] - grid).min(axis=-1)
+    mine = np.abs(x.astype(np.float64) - (Q.astype(np.float64) - z) * float(s))
+    assert np.all(mine <= best + 1e-6 * float(s))                      # nearest code (ties aside)
+    assert Q[0, 0] == z                                                # zero is exact
+    inside = (x >= grid[0]) & (x <= grid[-1])
+    assert np.all(mine[inside] <= float(s) / 2 * (1 + 1e-5))
+    assert abs(float(s) - float(x.max() - x.min()) / qa) <= 1e-6 * float(s)
+    r = np.maximum(x, 0)                                               # after a ReLU
+    Qr, sr, zr = po.quantize_activations_asymmetric(r, a)
+    _, ss = po.quantize_activations(r, None, a)
+    assert zr == 0 and abs(float(sr) / float(ss) - (2 ** (a - 1) - 1) / qa) < 1e-6
+    Q0, s0, z0 = po.quantize_activations_asymmetric(np.zeros((2, 3), f32), a)
+    assert not Q0.any() and s0 == 0 and z0 == 0
+
+
+def test_asymmetric_forward_is_the_textbook_affine_layer():
+    """K = 1: the integer layer on (Q(x) - z) by an independent int64 einsum; shifting the codes by
+    any constant c and adding c * (row sums of the weight codes) back gives the same accumulators
+    (the identity a kernel with signed 8-bit operands relies on); with 8-bit weights and K = 3 the
+    output converges to s * (Q(x) - z) W^T."""
+    rng = np.random.default_rng(75)
+    W = _rand_w(76, 32, 48)
+    x = np.maximum(rng.standard_normal((9, 48)), 0).astype(f32) * 2.0
+    e = po.expand(W, 4, 1, 1.0, 16)
+    r = po.forward_asymmetric(e, x)
+    Qc = r["Qx"].astype(np.int64) - r["z"]
+    ref = np.einsum("ti,oi->to", Qc, e.orders[0].codes.astype(np.int64))
+    assert np.array_equal(r["acc"][0], ref)
+    c = 128 - r["z"]
+    shifted = np.einsum("ti,oi->to", r["Qx"].astype(np.int64) - 128, e.orders[0].codes.astype(np.int64))
+    assert np.array_equal(shifted + c * e.orders[0].codes.astype(np.int64).sum(axis=1)[None, :], ref)
+    y = float(r["s_x"]) * (e.orders[0].scales.astype(np.float64)[None, :] * ref)
+    assert np.allclose(r["y64"], y, rtol=1e-12, atol=0)
+    e8 = po.expand(W, 8, 3, 1.0, 16)
+    r8 = po.forward_asymmetric(e8, x, split=[1, 2])
+    full = float(r8["s_x"]) * ((r8["Qx"].astype(np.float64) - r8["z"]) @ W.astype(np.float64).T)
+    assert np.abs(r8["y64"] - full).max() <= 1e-5 * np.abs(full).max()
+    # and the affine codes halve the input error of the symmetric ones on a non-negative tensor
+    es = po.forward(e8, x)
+    exact = x.astype(np.float64) @ W.astype(np.float64).T
+    assert np.abs(r8["y64"] - exact).mean() < 0.75 * np.abs(es["y64"] - exact).mean()
+
+
 def test_contraction_against_torch_int64_and_loops():
     rng = np.random.default_rng(40)
     Qx = rng.integers(-127, 128, size=(7, 333), dtype=np.int8)
