@@ -151,6 +151,29 @@ int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, float s_x,
 int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
                      int32_t* acc_dev, int8_t* qx_dev, float* s_x_out_dev, void* stream);
 
+/* The layer with asymmetric activation codes (Sec. 4.3 makes its comparison under
+ * asymmetric quantization; the affine quantizer is the usual one):  with
+ * hi = max(x, 0) and lo = min(x, 0) over the tensor, a = the activation width set by
+ * pipe_set_activation_bits,
+ *   s = (hi - lo) / (2^a - 1),  z = clamp(rint(-lo / s), 0, 2^a - 1),
+ *   Q(x) = clamp(rint(x / s) + z, 0, 2^a - 1),
+ *   y[t,o] = s * sum_k s_k[o] * sum_i (Q(x)[t,i] - z) q_k[o,i]  (+ b[o]),
+ * fp32 sums and IEEE divisions, rint half to even, the scale always dynamic.  The
+ * contraction kernels run unchanged on the codes Q(x) - 2^(a-1); the term that does
+ * not depend on the token, s (2^(a-1) - z) sum_k s_k[o] sum_i q_k[o,i], is added
+ * with the bias (the sums of the codes are built on the first call: it allocates and
+ * synchronizes once per expansion).  Members given by split are summed.
+ *   x_dev [T, in], bias_dev NULL or [out], y_dev [T, out]: DEVICE, caller-owned.
+ * PIPE_ESHAPE if (2^a - 1) * q_max * in does not fit the 32-bit accumulator.      */
+int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_dev, int T, const int* split, int M,
+                            const float* bias_dev, float* y_dev, void* stream);
+
+/* Debug export of the same call: the exact accumulators acc_dev [K, T, out]
+ * (sum_i (Q(x) - z) q_k; pruned rows 0), optionally the unsigned codes qx_dev [T, in],
+ * the scale and the zero point (DEVICE; NULL to skip).  Synchronizes.               */
+int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float* x_dev, int T, int32_t* acc_dev,
+                                uint8_t* qx_dev, float* s_x_out_dev, int32_t* z_out_dev, void* stream);
+
 /* Expanded convolution as a GEMM over output pixels (App. H treats conv and FC
  * alike).  The expansion was built from W [out, C*kh*kw], a row flattened as
  * [C, kh, kw].  x_dev is [N,C,H,W] (nhwc == 0) or [N,H,W,C] (nhwc != 0), zero

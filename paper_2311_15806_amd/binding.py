@@ -50,6 +50,8 @@ def _load():
     lib.pipe_expansion_order.argtypes = [vp, ci, pi, vp, vp, vp]
     lib.pipe_forward.argtypes = [vp, vp, ci, cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
+    lib.pipe_forward_asymmetric.argtypes = [vp, vp, ci, pi, ci, vp, vp, vp]
+    lib.pipe_forward_acc_asymmetric.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp]
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
@@ -76,7 +78,7 @@ def _load():
     lib.pipe_strerror.restype = C.c_char_p
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expand_unstructured", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
-              "pipe_forward", "pipe_forward_acc", "pipe_forward_conv2d", "pipe_mlp_forward",
+              "pipe_forward", "pipe_forward_acc", "pipe_forward_asymmetric", "pipe_forward_acc_asymmetric", "pipe_forward_conv2d", "pipe_mlp_forward",
               "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
         getattr(lib, f).restype = ci
     return lib
@@ -241,6 +243,30 @@ def pipe_forward_acc(e: Expansion, x: torch.Tensor, s_x: float = 0.0):
     _check(_lib.pipe_forward_acc(e.handle, _ptr(x, torch.float32), T, float(s_x), _ptr(acc), _ptr(qx),
                                  _ptr(sx), _stream()), "pipe_forward_acc")
     return acc, qx, sx
+
+
+def pipe_forward_asymmetric(e: Expansion, x: torch.Tensor, split=None, bias=None,
+                            out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != e.in_features:
+        raise ValueError("x must be [T, in]")
+    y = out if out is not None else torch.empty((T, e.out_features), dtype=torch.float32, device=x.device)
+    arr, m = _split(split)
+    _check(_lib.pipe_forward_asymmetric(e.handle, _ptr(x, torch.float32), T, arr, m, _ptr(bias, torch.float32),
+                                        _ptr(y, torch.float32), _stream()), "pipe_forward_asymmetric")
+    return y
+
+
+def pipe_forward_acc_asymmetric(e: Expansion, x: torch.Tensor):
+    """(acc int32 [K,T,out], Q(x) uint8 [T,in], scale, zero point) of the asymmetric layer."""
+    T = x.shape[0]
+    acc = torch.empty((e.K, T, e.out_features), dtype=torch.int32, device=x.device)
+    qx = torch.empty((T, e.in_features), dtype=torch.uint8, device=x.device)
+    sx = torch.zeros(1, dtype=torch.float32, device=x.device)
+    z = torch.zeros(1, dtype=torch.int32, device=x.device)
+    _check(_lib.pipe_forward_acc_asymmetric(e.handle, _ptr(x, torch.float32), T, _ptr(acc), _ptr(qx), _ptr(sx), _ptr(z),
+                                            _stream()), "pipe_forward_acc_asymmetric")
+    return acc, qx, float(sx.item()), int(z.item())
 
 
 def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,

@@ -132,6 +132,9 @@ static void free_expansion(pipe_expansion* e) {
   if (e->scales_all_dev) (void)hipFree(e->scales_all_dev);
   if (e->split_sum_dev) (void)hipFree(e->split_sum_dev);
   if (e->split_cnt_dev) (void)hipFree(e->split_cnt_dev);
+  if (e->asym_wsum_dev) (void)hipFree(e->asym_wsum_dev);
+  if (e->asym_C_dev) (void)hipFree(e->asym_C_dev);
+  if (e->asym_bias_dev) (void)hipFree(e->asym_bias_dev);
   delete e;
 }
 
@@ -645,6 +648,148 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   int lo = 0, hi = e->K - 1;
   fill_members(a, 1, &lo, &hi);
   return run_gemm(a, small, st);
+}
+
+// ------------------------------------------------------------------ asymmetric activation codes
+// Sums of the stored codes per order and output channel, and C[o] = sum_k s_k[o] * wsum_k[o] (fp32,
+// ascending k), built once per expansion (synchronizes; allocates).
+static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
+  pipe_expansion* e = const_cast<pipe_expansion*>(ce);
+  if (e->asym_C_dev) return PIPE_OK;
+  const size_t out = (size_t)e->out;
+  int32_t* wsum = nullptr;
+  float* C = nullptr;
+  float* be = nullptr;
+  PIPE_HIP(hipMalloc(&wsum, (size_t)e->K * out * sizeof(int32_t)));
+  hipError_t he = hipMemsetAsync(wsum, 0, (size_t)e->K * out * sizeof(int32_t), st);
+  int rc = he == hipSuccess ? PIPE_OK : PIPE_EDEVICE;
+  int8_t* tmp = nullptr;
+  size_t max_rows = 0;
+  for (auto& o : e->orders) max_rows = std::max(max_rows, (size_t)o.n_kept * e->group);
+  if (rc == PIPE_OK && hipMalloc(&tmp, max_rows * (size_t)e->in) != hipSuccess) rc = PIPE_ENOMEM;
+  for (int k = 0; k < e->K && rc == PIPE_OK; ++k) {
+    const PipeOrder& o = e->orders[k];
+    const int rows = o.n_kept * e->group;
+    rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, rows, e->in, e->in_pad, tmp, st);
+    if (rc == PIPE_OK) rc = launch_row_code_sums(tmp, rows, e->in, e->group, o.gids_dev, wsum + (size_t)k * out, st);
+  }
+  std::vector<int32_t> hw((size_t)e->K * out);
+  std::vector<float> all((size_t)e->n_bins * e->bin_cap * 16), hC(out, 0.f);
+  if (rc == PIPE_OK && (hipStreamSynchronize(st) != hipSuccess ||
+                        hipMemcpy(hw.data(), wsum, hw.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+                        hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess))
+    rc = PIPE_EDEVICE;
+  if (tmp) (void)hipFree(tmp);
+  if (rc == PIPE_OK) {
+    for (int k = 0; k < e->K; ++k) {
+      const PipeOrder& o = e->orders[k];
+      for (int slot = 0; slot < o.n_kept; ++slot)
+        for (int j = 0; j < e->group; ++j) {
+          const int r = slot * e->group + j;
+          const size_t ch = (size_t)o.gids[slot] * e->group + j;
+          hC[ch] += all[(size_t)o.pos[r >> 4] * 16 + (r & 15)] * (float)hw[(size_t)k * out + ch];
+        }
+    }
+    if (hipMalloc(&C, out * sizeof(float)) != hipSuccess || hipMalloc(&be, out * sizeof(float)) != hipSuccess ||
+        hipMemcpy(C, hC.data(), out * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+      rc = PIPE_EDEVICE;
+  }
+  if (rc != PIPE_OK) {
+    if (wsum) (void)hipFree(wsum);
+    if (C) (void)hipFree(C);
+    if (be) (void)hipFree(be);
+    return rc;
+  }
+  e->asym_wsum_dev = wsum; e->asym_C_dev = C; e->asym_bias_dev = be;
+  return PIPE_OK;
+}
+
+// quantizes x with asymmetric codes into the activation buffers; dz (= 2^(a-1) - z) and the scale stay on the device
+static int asym_quantize(const pipe_expansion* e, const float* x_dev, int T, const ActBuffers& b, uint8_t* qx_u8,
+                         uint32_t** slots_out, int32_t** dz_out, hipStream_t st) {
+  const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
+  // |Q(x) - z| <= 2^a - 1: the exact accumulator must fit 32 bits
+  if ((int64_t)((1 << act_bits) - 1) * ((1 << (e->qbits - 1)) - 1) * e->in >= ((int64_t)1 << 31)) return PIPE_ESHAPE;
+  uint32_t* slots = b.amax + 64;              // two range slots, zero between calls
+  int32_t* dz = reinterpret_cast<int32_t*>(b.amax + 66);
+  int rc = launch_minmax(x_dev, (int64_t)T * e->in, slots, st);
+  if (rc) return rc;
+  rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, b.T_pad, slots, act_bits, b.qx, b.rowsum, qx_u8, b.scale, dz, st);
+  *slots_out = slots; *dz_out = dz;
+  return rc;
+}
+
+extern "C" int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_dev, int T, const int* split, int M,
+                                       const float* bias_dev, float* y_dev, void* stream) {
+  if (!e || T < 0) return PIPE_EINVAL;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  rc = asym_prepare(e, st);
+  if (rc) return rc;
+  const bool small = use_stream_kernel(e, T);
+  ActBuffers b;
+  rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  uint32_t* slots = nullptr;
+  int32_t* dz = nullptr;
+  rc = asym_quantize(e, x_dev, T, b, nullptr, &slots, &dz, st);
+  if (rc) return rc;
+  rc = launch_asym_bias(bias_dev, e->asym_C_dev, b.scale, dz, e->asym_bias_dev, e->out, slots, st);
+  if (rc) return rc;
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.qx_mstride = 0; a.rowsum = b.rowsum; a.rowsum_mstride = 0;
+  a.s_x = b.scale; a.sx_mstride = 0; a.bias = e->asym_bias_dev; a.reduce = 1; a.act = 0;
+  a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr; a.zero_after = b.amax;
+  fill_members(a, Mm, lo, hi);
+  return run_gemm(a, small, st);
+}
+
+extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float* x_dev, int T, int32_t* acc_dev,
+                                           uint8_t* qx_dev, float* s_x_out_dev, int32_t* z_out_dev, void* stream) {
+  if (!e || T < 0) return PIPE_EINVAL;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !acc_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = asym_prepare(e, st);
+  if (rc) return rc;
+  const bool small = use_stream_kernel(e, T, true);
+  ActBuffers b;
+  rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  uint32_t* slots = nullptr;
+  int32_t* dz = nullptr;
+  rc = asym_quantize(e, x_dev, T, b, qx_dev, &slots, &dz, st);
+  if (rc) return rc;
+  rc = launch_asym_bias(nullptr, e->asym_C_dev, b.scale, dz, e->asym_bias_dev, e->out, slots, st);   // clears the range slots
+  if (rc) return rc;
+  PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
+  a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev; a.zero_after = b.amax;
+  int klo = 0, khi = e->K - 1;
+  fill_members(a, 1, &klo, &khi);
+  rc = run_gemm(a, small, st);
+  if (rc) return rc;
+  rc = launch_asym_acc_fix(acc_dev, e->asym_wsum_dev, dz, e->K, T, e->out, st);
+  if (rc) return rc;
+  if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
+  if (z_out_dev) {
+    // z = 2^(a-1) - dz; an all-zero input has z = 0 and dz = 0
+    const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
+    int32_t hdz = 0;
+    float hs = 0.f;
+    PIPE_HIP(hipMemcpyAsync(&hdz, dz, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    PIPE_HIP(hipMemcpyAsync(&hs, b.scale, sizeof(float), hipMemcpyDeviceToHost, st));
+    PIPE_HIP(hipStreamSynchronize(st));
+    const int32_t z = hs > 0.f ? (1 << (act_bits - 1)) - hdz : 0;
+    PIPE_HIP(hipMemcpyAsync(z_out_dev, &z, sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PIPE_HIP(hipStreamSynchronize(st));
+  }
+  return PIPE_OK;
 }
 
 extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,

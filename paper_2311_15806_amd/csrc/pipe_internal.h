@@ -121,6 +121,11 @@ struct pipe_expansion {
   float* scales_all_dev = nullptr;    // [n_bins*bin_cap][16]
   int n_bins = 0, bin_cap = 0;
   StreamBin* bins_dev = nullptr;
+  // asymmetric activations (built on first use of pipe_forward_asymmetric): per order and output channel the sum of
+  // the row's codes [K][out] (pruned rows 0), C[o] = sum_k s_k[o] * wsum_k[o], and the effective bias of the last call
+  int32_t* asym_wsum_dev = nullptr;
+  float* asym_C_dev = nullptr;
+  float* asym_bias_dev = nullptr;
   // split bins of the weight-streaming kernel: partial tiles, and arrival counters (zero between launches)
   int32_t* split_sum_dev = nullptr;   // [n_bins][PIPE_MAX_SPLIT][bin_cap][256]
   uint32_t* split_cnt_dev = nullptr;  // [n_bins]
@@ -189,6 +194,16 @@ int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, cons
 // ------------------------------------------------------------------ activation kernels (pipe_quant.hip)
 // amax_bits: device uint32 holding the bit pattern of max|x| (must be zeroed first).
 int launch_zero_u32(uint32_t* p, int n, hipStream_t st);
+// asymmetric activation codes: range slots {max(x,0), max(-x,0)}; unsigned a-bit codes stored minus 2^(a-1) in the
+// fragment layout with their token sums, scale and 2^(a-1) - z to device memory; the token-free correction as a bias
+int launch_minmax(const float* x, int64_t n, uint32_t* slots, hipStream_t st);
+int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
+                         uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
+                         hipStream_t st);
+int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
+                     uint32_t* slots, hipStream_t st);
+int launch_asym_acc_fix(int32_t* acc, const int32_t* wsum, const int32_t* dz, int K, int T, int out, hipStream_t st);
+int launch_row_code_sums(const int8_t* codes, int rows, int in, int group, const int32_t* gids, int32_t* wsum, hipStream_t st);
 // launch_absmax also zeroes n_zero ints at zero_me (the code sums of the quantizer that follows).
 int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_me, int n_zero, hipStream_t st);
 // Quantize x [T, in] into the fragment layout (padded region written as zero), row sums and

@@ -6,6 +6,8 @@
 // this file is compiled with floating-point contraction off.
 #include "pipe_internal.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int BLK = 256;
@@ -390,6 +392,124 @@ __global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ 
   if (threadIdx.x == 0) amax_raise(&amax_bits[m], mx);
 }
 
+
+// ---------------------------------------------------------------- asymmetric activation codes
+// Sec. 4.3 compares under asymmetric quantization; the affine quantizer over [min(x,0), max(x,0)]:
+//   s = (hi - lo) / (2^a - 1),  z = clamp(rint(-lo / s), 0, 2^a - 1),  Q(x) = clamp(rint(x / s) + z, 0, 2^a - 1).
+// The contraction kernels multiply signed bytes, so the stored code is Q(x) - 2^(a-1); the exact
+// accumulator is then acc' + (2^(a-1) - z) * (sum of the row's weight codes), a term without the
+// token that the entry point folds into the bias.
+
+// slots[0] = max(x, 0), slots[1] = max(-x, 0) (bit patterns; both order independent, hence exact)
+__global__ __launch_bounds__(BLK) void minmax_kernel(const float* __restrict__ x, int64_t n, uint32_t* __restrict__ slots) {
+  float hi = 0.f, nlo = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x; i < n; i += (int64_t)gridDim.x * BLK) {
+    const float v = x[i];
+    hi = fmaxf(hi, v);
+    nlo = fmaxf(nlo, -v);
+  }
+  hi = block_max(hi);
+  nlo = block_max(nlo);
+  if (threadIdx.x == 0) {
+    amax_raise(slots, hi);
+    amax_raise(slots + 1, nlo);
+  }
+}
+
+// thread = (token tid & 15, chunk slot tid >> 4) of token block blockIdx.x; blockIdx.y splits k.
+// qa = 2^a - 1, shift = 2^(a-1).  Writes the fragment layout, adds the token code sums (zero on
+// entry), optionally the unsigned codes row-major, and (block 0,0) the scale and shift - z.
+__global__ __launch_bounds__(BLK) void quantize_asym_kernel(const float* __restrict__ x, int T, int in, int in_pad,
+                                                            const uint32_t* __restrict__ slots, float qa, int shift,
+                                                            uint8_t* __restrict__ qx_frag, int32_t* __restrict__ rowsum,
+                                                            uint8_t* __restrict__ qx_rowmajor, float* __restrict__ scale_out,
+                                                            int32_t* __restrict__ dz_out) {
+  const float hi = __uint_as_float(slots[0]), nlo = __uint_as_float(slots[1]);
+  const float s = __fdiv_rn(__fadd_rn(hi, nlo), qa);
+  const bool live = s > 0.f;
+  const float zf = live ? fminf(fmaxf(rintf(__fdiv_rn(nlo, s)), 0.f), qa) : 0.f;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    scale_out[0] = s;
+    dz_out[0] = live ? shift - (int)zf : 0;
+  }
+  const int tb = blockIdx.x;
+  const int nks = in_pad >> 6, nchunk = in_pad >> 4;
+  const int per = ((nchunk + (int)gridDim.y - 1) / (int)gridDim.y + 3) & ~3;
+  const int c_lo = min(nchunk, (int)blockIdx.y * per), c_hi = min(nchunk, c_lo + per);
+  const int n = threadIdx.x & 15, t = tb * 16 + n;
+  int sum = 0;
+  for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
+    int q[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int k = c * 16 + e;
+      int v = 0;
+      if (live && t < T && k < in) {
+        const float u = fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x[(size_t)t * in + k], s)), zf), 0.f), qa);
+        if (qx_rowmajor != nullptr) qx_rowmajor[(size_t)t * in + k] = (uint8_t)(int)u;
+        v = (int)u - shift;
+      } else if (qx_rowmajor != nullptr && t < T && k < in) {
+        qx_rowmajor[(size_t)t * in + k] = 0;
+      }
+      q[e] = v;
+      sum += v;
+    }
+    const int ks = c >> 2, kc = c & 3;
+    uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
+                         pack4(q[8], q[9], q[10], q[11]), pack4(q[12], q[13], q[14], q[15]));
+    *reinterpret_cast<uint4*>(qx_frag + (((size_t)tb * nks + ks) * 64 + kc * 16 + n) * 16) = w;
+  }
+  sum += __shfl_xor(sum, 16, 64);
+  sum += __shfl_xor(sum, 32, 64);
+  __shared__ int wsum[BLK / 64][16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane < 16) wsum[wave][lane] = sum;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < BLK / 64; ++w) tot += wsum[w][threadIdx.x];
+    if (t < T && tot != 0) atomicAdd(&rowsum[t], tot);
+  }
+}
+
+// bias_eff[o] = b[o] + (s * dz) * C[o], C[o] = sum_k s_k[o] * (sum_i q_k[o,i]); also clears the
+// two range slots for the next call
+__global__ void asym_bias_kernel(const float* __restrict__ bias, const float* __restrict__ C, const float* __restrict__ scale,
+                                 const int32_t* __restrict__ dz, float* __restrict__ out, int n, uint32_t* __restrict__ slots) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o == 0) { slots[0] = 0u; slots[1] = 0u; }
+  if (o >= n) return;
+  const float f = scale[0] * (float)dz[0];
+  out[o] = (bias != nullptr ? bias[o] : 0.f) + f * C[o];
+}
+
+// exact accumulators of the debug export: acc[k][t][o] += dz * wsum[k][o]
+__global__ void asym_acc_fix_kernel(int32_t* __restrict__ acc, const int32_t* __restrict__ wsum, const int32_t* __restrict__ dz,
+                                    int K, int T, int out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)K * T * out) return;
+  const int o = (int)(i % out), k = (int)(i / ((int64_t)T * out));
+  acc[i] += dz[0] * wsum[(size_t)k * out + o];
+}
+
+// sum of the codes of every stored row of one order -> wsum[o] (dense over output channels)
+__global__ __launch_bounds__(BLK) void row_code_sums_kernel(const int8_t* __restrict__ codes, int in, int group,
+                                                            const int32_t* __restrict__ gids, int32_t* __restrict__ wsum) {
+  const int r = blockIdx.x, slot = r / group;
+  const int o = gids[slot] * group + (r - slot * group);
+  int s = 0;
+  for (int i = threadIdx.x; i < in; i += BLK) s += codes[(size_t)r * in + i];
+  __shared__ int sm[BLK];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = BLK / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) wsum[o] = sm[0];
+}
+
 }  // namespace
 
 int set_act_qmax(float qmax) {
@@ -496,6 +616,49 @@ int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint
   int64_t blocks = (n + BLK * 4 - 1) / (BLK * 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+// ---- asymmetric activation codes (host side) ----------------------------------------------
+int launch_minmax(const float* x, int64_t n, uint32_t* slots, hipStream_t st) {
+  int64_t blocks = std::min<int64_t>((n + BLK - 1) / BLK, 2048);
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(minmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
+                         uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
+                         hipStream_t st) {
+  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
+  if (rc) return rc;
+  dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
+  hipLaunchKernelGGL(quantize_asym_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, slots, (float)((1 << act_bits) - 1),
+                     1 << (act_bits - 1), qx_frag, rowsum, qx_rowmajor, scale_out, dz_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
+                     uint32_t* slots, hipStream_t st) {
+  hipLaunchKernelGGL(asym_bias_kernel, dim3((n + 255) / 256), dim3(256), 0, st, bias, C, scale, dz, out, n, slots);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_asym_acc_fix(int32_t* acc, const int32_t* wsum, const int32_t* dz, int K, int T, int out, hipStream_t st) {
+  const int64_t n = (int64_t)K * T * out;
+  if (n == 0) return PIPE_OK;
+  hipLaunchKernelGGL(asym_acc_fix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, acc, wsum, dz, K, T, out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_row_code_sums(const int8_t* codes, int rows, int in, int group, const int32_t* gids, int32_t* wsum, hipStream_t st) {
+  if (rows == 0) return PIPE_OK;
+  hipLaunchKernelGGL(row_code_sums_kernel, dim3(rows), dim3(BLK), 0, st, codes, in, group, gids, wsum);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -573,3 +573,68 @@ def test_unstructured_mask_ties_go_to_the_lower_index(pipe):
     g = pipe.pipe_expand_unstructured(dev(W), 4, 3, 0.5, 16)
     assert_expansion_equal(g, ora)
     g.free()
+
+
+@pytest.mark.parametrize("bits,K,gamma,group,O,I,T", [(4, 3, 0.5, 32, 192, 300, 9), (2, 4, 0.25, 64, 256, 520, 150),
+                                                       (8, 2, 1.0, 16, 64, 260, 33), (4, 4, 0.5, 16, 96, 1000, 200)])
+def test_asymmetric_activation_codes(pipe, bits, K, gamma, group, O, I, T):
+    """Asymmetric activation codes (Sec. 4.3): unsigned codes, scale and zero point bit for bit, the
+    exact accumulators sum (Q(x) - z) q bit for bit from both contraction kernels (they run on the
+    codes minus 128; the shift comes back through the sums of the weight codes), the output within
+    the fp32 tolerance, with bias and with members summed."""
+    W = _w(700 + bits, O, I)
+    rng = np.random.default_rng(710 + T)
+    x = (np.maximum(rng.standard_normal((T, I)), -0.3) * 1.5 + 0.2).astype(np.float32)   # a skewed range
+    b = rng.standard_normal(O).astype(np.float32)
+    spec = wl.LayerSpec(O, I, bits, K, gamma, group)
+    ora = oracle_expand(W, spec)
+    ref = po.forward_asymmetric(ora, x, bias=b)
+    g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+    acc, qx, sx, z = pipe.pipe_forward_acc_asymmetric(g, dev(x))
+    assert z == ref["z"] and np.float32(sx) == ref["s_x"]
+    assert np.array_equal(qx.cpu().numpy().astype(np.int16), ref["Qx"])
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    y = pipe.pipe_forward_asymmetric(g, dev(x), bias=dev(b)).cpu().numpy()
+    assert_close_fp32(y, ref["y"])
+    y2 = pipe.pipe_forward_asymmetric(g, dev(x), bias=dev(b)).cpu().numpy()      # the range slots were cleared
+    assert np.array_equal(y, y2)
+    if K >= 2:
+        split = [1, K - 1]
+        assert_close_fp32(pipe.pipe_forward_asymmetric(g, dev(x), split=split, bias=dev(b)).cpu().numpy(),
+                          po.forward_asymmetric(ora, x, split=split, bias=b)["y"])
+    # the symmetric entry points still work on the same expansion and workspace
+    assert_close_fp32(pipe.pipe_forward(g, dev(x), bias=dev(b)).cpu().numpy(), po.forward(ora, x, bias=b)["y"])
+    g.free()
+
+
+def test_asymmetric_activation_degenerate_inputs_and_widths(pipe):
+    """All-zero input (scale 0: the output is the bias), a non-negative input (zero point 0), a
+    non-positive one (zero point 2^a - 1), and 6- and 4-bit activation grids."""
+    O, I, T = 64, 192, 21
+    W = _w(720, O, I)
+    spec = wl.LayerSpec(O, I, 4, 2, 0.5, 16)
+    ora = oracle_expand(W, spec)
+    g = pipe.pipe_expand(dev(W), 4, 2, 0.5, 16)
+    b = np.random.default_rng(721).standard_normal(O).astype(np.float32)
+    x0 = np.zeros((T, I), np.float32)
+    assert np.array_equal(pipe.pipe_forward_asymmetric(g, dev(x0), bias=dev(b)).cpu().numpy(), np.tile(b, (T, 1)))
+    xr = np.abs(_x(722, T, I))
+    for x in (xr, -xr):
+        ref = po.forward_asymmetric(ora, x)
+        acc, qx, sx, z = pipe.pipe_forward_acc_asymmetric(g, dev(x))
+        assert z == ref["z"] and z in (0, 255)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert_close_fp32(pipe.pipe_forward_asymmetric(g, dev(x)).cpu().numpy(), ref["y"])
+    x = _x(723, T, I) + 0.5
+    for a in (6, 4):
+        pipe.pipe_set_activation_bits(a)
+        try:
+            ref = po.forward_asymmetric(ora, x, act_bits=a)
+            acc, qx, sx, z = pipe.pipe_forward_acc_asymmetric(g, dev(x))
+            y = pipe.pipe_forward_asymmetric(g, dev(x)).cpu().numpy()
+        finally:
+            pipe.pipe_set_activation_bits(8)
+        assert z == ref["z"] and np.array_equal(qx.cpu().numpy().astype(np.int16), ref["Qx"])
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        assert_close_fp32(y, ref["y"])
+    g.free()
