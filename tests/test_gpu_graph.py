@@ -158,3 +158,38 @@ def test_several_steps_in_one_graph_keep_their_order(T):
         for i in range(K):
             assert torch.equal(outs[i], eager[i % 3]), "replay %d, step %d differs" % (rep, i)
     g.free()
+
+
+@pytest.mark.parametrize("T", [7, 200])
+def test_asymmetric_forward_graph_replays(T):
+    """The asymmetric layer (range reduction, quantizer, bias kernel that also clears the range
+    slots, contraction) captured once and replayed with inputs of other ranges."""
+    import paper_2311_15806_amd.binding as pipe
+    w = wl.scaled(wl.C4, out_div=4, in_div=4)
+    spec = w.layers[0]
+    W = torch.from_numpy(wl.make_weight(w, 0)).cuda()
+    g = pipe.pipe_expand(W, spec.bits, spec.K, spec.gamma, spec.group)
+    x0 = torch.from_numpy(wl.make_input(wl.with_tokens(w, T))).cuda()
+    xs = [torch.relu(x0), x0 * 0.5 + 1.0, -torch.relu(x0) * 3.0]
+    x = xs[0].clone()
+    out = torch.empty((T, spec.out_features), device="cuda")
+    eager = [pipe.pipe_forward_asymmetric(g, xi).clone() for xi in xs]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.pipe_forward_asymmetric(g, x, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipe.pipe_forward_asymmetric(g, x, out=out)
+    for rep in range(6):
+        i = rep % 3
+        x.copy_(xs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[i]), "replay %d differs" % rep
+        other = pipe.pipe_forward(g, xs[(i + 1) % 3])          # symmetric eager work on the same workspace
+        torch.cuda.synchronize()
+    g.free()
