@@ -142,8 +142,9 @@ def main():
                 b += 4 * T * l.out_features * (1 if cfg.chain[i][1] == 0 else M)
         return b
 
-    def measure(T, steps, warmup, rotate):
+    def measure(T, steps, warmup, rotate, settle_ms=None, graph=True):
         """Times `steps` passes; returns dict with step time and contraction-kernel time."""
+        settle_ms = args.settle_ms if settle_ms is None else settle_ms
         xd = xd_full if cfg.kind == "conv2d" else xd_full[:T].contiguous()
         out = None if cfg.kind == "conv2d" else torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
         copies = 1
@@ -153,7 +154,7 @@ def main():
                 exps.append(build())
         # sustained load first (clocks settle), then the W warm-up steps
         t_s, i_s = time.perf_counter(), 0
-        while (time.perf_counter() - t_s) * 1e3 < args.settle_ms:
+        while (time.perf_counter() - t_s) * 1e3 < settle_ms:
             for _ in range(8):
                 step_fn(exps[i_s % copies], xd, out)
                 i_s += 1
@@ -176,7 +177,7 @@ def main():
         mode = "eager"
         # ---- the same K steps as ONE HIP graph: decode-sized steps are launch bound, and the small
         # layers' five launches leave gaps as long as their kernels when launched eagerly --------
-        if not args.no_graph and cfg.kind != "conv2d":
+        if graph and not args.no_graph and cfg.kind != "conv2d":
             try:
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
@@ -192,7 +193,7 @@ def main():
                 t_s = time.perf_counter()      # capture left the chip idle: load it again before the timed replay
                 g.replay()
                 torch.cuda.synchronize()
-                while (time.perf_counter() - t_s) * 1e3 < args.settle_ms:
+                while (time.perf_counter() - t_s) * 1e3 < settle_ms:
                     g.replay()
                     torch.cuda.synchronize()
                 t_a = time.perf_counter()
@@ -215,6 +216,9 @@ def main():
                     alg_bytes=alg_bytes, expansion_copies=copies)
 
     T0 = cfg.tokens if cfg.kind == "conv2d" else T_head
+    # the same workload from an idle chip first (no sustained load before it, 5 warm-up steps, 50
+    # eager steps): what a burst after an idle period sees, reported next to the settled figure
+    cold = measure(T0, min(50, args.steps), min(5, args.warmup), rotate=(T0 <= 128), settle_ms=0.0, graph=False)
     head = measure(T0, args.steps, args.warmup, rotate=(T0 <= 128))
 
     mfma_bound = T0 > 128
@@ -373,6 +377,8 @@ def main():
         "warmup": args.warmup,
         "settle_ms": args.settle_ms,          # untimed load before the warm-up steps (clocks)
         "step_mode": head["step_mode"],       # the K timed steps as one HIP graph, or launched eagerly
+        "cold_start": {"ms_per_step": cold["ms_per_step"], "kernel_ms": cold["kernel_ms_per_step"],
+                       "steps": min(50, args.steps), "warmup": min(5, args.warmup), "step_mode": cold["step_mode"]},
         "ms_per_step": head["ms_per_step"],
         "tokens_per_s": head["tokens_per_s"],
         "higher_is_better": True,
