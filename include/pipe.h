@@ -96,7 +96,7 @@ int pipe_expand(const float* W_dev, int out, int in, int bits, int K, float gamm
 int pipe_expand_unstructured(const float* W_dev, int out, int in, int bits, int K, float gamma,
                              int group, void* stream, pipe_expansion** exp_out);
 
-/* The same expansion with another rounding operator (Sec. 1 and Sec. 4.4: the method is
+/* The same expansion with another rounding operator (Sec. 1 and Sec. 4.5: the method is
  * agnostic to the quantization operator and combines with operators that choose the
  * rounding direction themselves).  For every order k = 1..K the builder writes, on
  * `stream`, the rows this order quantizes to rows_dev [rows, in] (compact: the kept

@@ -79,7 +79,7 @@ def quantize_rows(E: np.ndarray, bits: int, operator=None, k: int = 1):
     s[o] = max_i |E[o,i]| / q_max (fp32 division); q = clamp(rint(E / s), +-q_max),
     rint rounds half to even.  A row whose scale is 0 gets codes 0.
 
-    The method does not depend on how a value is rounded onto the grid (Sec. 1 and Sec. 4.4:
+    The method does not depend on how a value is rounded onto the grid (Sec. 1 and Sec. 4.5:
     the expansion combines with any quantization operator): `operator`, if given, replaces the
     rint step.  It is called as operator(k, E, s, q_max) and returns integer codes [R, I]; they
     are clamped to +-q_max and rows of scale 0 get codes 0, as above."""

@@ -482,7 +482,7 @@ def test_depthwise_conv_parity(pipe, C, H, W, kh, kw, stride, pad, bits, K):
 
 
 def test_expand_with_another_rounding_operator(pipe):
-    """The rounding operator as a plug-in (Sec. 4.4): round-to-nearest through the hook is the
+    """The rounding operator as a plug-in (Sec. 4.5): round-to-nearest through the hook is the
     built-in expansion bit for bit; a truncating operator gives, on both sides, the same masks,
     scales and codes, and the forward pass of that expansion matches the checker."""
     O, I, bits, K, gamma, group = 96, 200, 4, 3, 0.5, 16

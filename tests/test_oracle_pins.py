@@ -865,7 +865,7 @@ def test_U_ens_worked_examples_and_predictor_size_rule(golden_dir):
 
 
 def test_expansion_with_another_rounding_operator():
-    """The rounding operator is a plug-in (Sec. 4.4).  Round-to-nearest passed in as an operator
+    """The rounding operator is a plug-in (Sec. 4.5).  Round-to-nearest passed in as an operator
     reproduces the built-in expansion bit for bit; truncation toward zero still telescopes
     (W = sum of the terms + last residual, exactly in fp32 steps) with the one-step error
     |residual| < s instead of s/2, and orders computed from it still shrink the error."""
