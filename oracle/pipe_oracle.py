@@ -492,6 +492,22 @@ def forward_conv2d(exp: Expansion, x: np.ndarray, kh, kw, stride, pad,
     return dict(Qx=Qx, s_x=sx, acc=acc, y=ys, y64=ys64)
 
 
+def forward_conv2d_asymmetric(exp: Expansion, x: np.ndarray, kh, kw, stride, pad, split=None, bias=None,
+                              act_bits: int = 8):
+    """The expanded conv layer with asymmetric activation codes (quantize_activations_asymmetric over
+    the whole input tensor): the direct integer convolution runs on Q(x) - z, so the zero padding
+    of the input is the real value 0 (code z).  Members summed; y is [N*Ho*Wo, O]."""
+    Qx, sx, z = quantize_activations_asymmetric(x, act_bits)
+    Qc = Qx.astype(np.int32) - z
+    T = Qx.shape[0] * np.prod(conv_out_size(x.shape[2], x.shape[3], kh, kw, stride, pad))
+    acc = np.zeros((exp.K, int(T), exp.out_features), dtype=np.int32)
+    for k in range(1, exp.K + 1):
+        acc[k - 1][:, exp.rows(k)] = conv2d_acc_direct(Qc, exp.orders[k - 1].codes, kh, kw, stride, pad)
+    ys = dequantize(exp, acc, sx, split, bias, f32)
+    ys64 = dequantize(exp, acc, sx, split, bias, np.float64)
+    return dict(Qx=Qx, s_x=sx, z=z, acc=acc, y=sum_members(ys), y64=sum_members(ys64))
+
+
 def depthwise_acc_direct(Qx: np.ndarray, codes: np.ndarray, kh: int, kw: int, stride: int, pad: int) -> np.ndarray:
     """Depthwise integer convolution: one kh x kw filter per channel (App. H: a conv with
     n_i = 1).  Qx int8 [N,C,H,W], codes int8 [C, kh*kw] (row c = filter of channel c, flattened

@@ -348,6 +348,28 @@ def test_asymmetric_forward_is_the_textbook_affine_layer():
     assert np.abs(r8["y64"] - exact).mean() < 0.75 * np.abs(es["y64"] - exact).mean()
 
 
+def test_asymmetric_conv_is_torch_conv_on_centred_codes():
+    """The asymmetric conv layer: accumulators equal torch's conv2d (fp64, exact on these integers)
+    of Q(x) - z with zero padding, and on a post-ReLU input the layer is closer to the
+    full-precision convolution than with symmetric codes."""
+    rng = np.random.default_rng(78)
+    C, O, H = 8, 16, 7
+    W4 = (rng.standard_normal((O, C, 3, 3)) * 0.2).astype(f32)
+    x = np.maximum(rng.standard_normal((2, C, H, H)), 0).astype(f32)
+    e = po.expand(W4.reshape(O, -1), 8, 2, 1.0, 16)
+    for stride, pad in [(1, 1), (2, 0)]:
+        r = po.forward_conv2d_asymmetric(e, x, 3, 3, stride, pad)
+        Qc = torch.from_numpy((r["Qx"].astype(np.int64) - r["z"]).astype(np.float64))
+        for k in range(2):
+            wk = torch.from_numpy(e.orders[k].codes.astype(np.float64).reshape(O, C, 3, 3))
+            ref = torch.nn.functional.conv2d(Qc, wk, stride=stride, padding=pad).permute(0, 2, 3, 1).reshape(-1, O)
+            assert np.array_equal(r["acc"][k], ref.numpy().astype(np.int64))
+        full = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)), torch.from_numpy(W4.astype(np.float64)),
+                                          stride=stride, padding=pad).permute(0, 2, 3, 1).reshape(-1, O).numpy()
+        sym = po.forward_conv2d(e, x, 3, 3, stride, pad)
+        assert np.abs(r["y64"] - full).mean() < 0.75 * np.abs(sym["y64"] - full).mean()
+
+
 def test_contraction_against_torch_int64_and_loops():
     rng = np.random.default_rng(40)
     Qx = rng.integers(-127, 128, size=(7, 333), dtype=np.int8)
