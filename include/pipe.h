@@ -168,6 +168,14 @@ int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s
 int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_dev, int T, const int* split, int M,
                             const float* bias_dev, float* y_dev, void* stream);
 
+/* The convolution layer with the same asymmetric codes (range over the whole input
+ * tensor): taps outside the image hold the real value 0, i.e. the code z.  Geometry,
+ * layouts and the [N*Ho*Wo, out] channels-last output as pipe_forward_conv2d; members
+ * summed; errors as pipe_forward_conv2d and pipe_forward_asymmetric.                 */
+int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W,
+                                   int kh, int kw, int stride, int pad, int nhwc, const int* split, int M,
+                                   const float* bias_dev, float* y_dev, void* stream);
+
 /* Debug export of the same call: the exact accumulators acc_dev [K, T, out]
  * (sum_i (Q(x) - z) q_k; pruned rows 0), optionally the unsigned codes qx_dev [T, in],
  * the scale and the zero point (DEVICE; NULL to skip).  Synchronizes.               */

@@ -52,6 +52,7 @@ def _load():
     lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
     lib.pipe_forward_asymmetric.argtypes = [vp, vp, ci, pi, ci, vp, vp, vp]
     lib.pipe_forward_acc_asymmetric.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp]
+    lib.pipe_forward_conv2d_asymmetric.argtypes = [vp, vp] + [ci] * 9 + [pi, ci, vp, vp, vp]
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
@@ -78,7 +79,7 @@ def _load():
     lib.pipe_strerror.restype = C.c_char_p
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expand_unstructured", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
-              "pipe_forward", "pipe_forward_acc", "pipe_forward_asymmetric", "pipe_forward_acc_asymmetric", "pipe_forward_conv2d", "pipe_mlp_forward",
+              "pipe_forward", "pipe_forward_acc", "pipe_forward_asymmetric", "pipe_forward_acc_asymmetric", "pipe_forward_conv2d_asymmetric", "pipe_forward_conv2d", "pipe_mlp_forward",
               "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
         getattr(lib, f).restype = ci
     return lib
@@ -254,6 +255,23 @@ def pipe_forward_asymmetric(e: Expansion, x: torch.Tensor, split=None, bias=None
     arr, m = _split(split)
     _check(_lib.pipe_forward_asymmetric(e.handle, _ptr(x, torch.float32), T, arr, m, _ptr(bias, torch.float32),
                                         _ptr(y, torch.float32), _stream()), "pipe_forward_asymmetric")
+    return y
+
+
+def pipe_forward_conv2d_asymmetric(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
+                                   split=None, bias=None, nhwc: bool = False) -> torch.Tensor:
+    if x.dim() != 4:
+        raise ValueError("x must be [N,C,H,W] (or [N,H,W,C] with nhwc=True)")
+    if nhwc:
+        N, H, W, Cc = x.shape
+    else:
+        N, Cc, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    y = torch.empty((N * Ho * Wo, e.out_features), dtype=torch.float32, device=x.device)
+    arr, m = _split(split)
+    _check(_lib.pipe_forward_conv2d_asymmetric(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
+                                               1 if nhwc else 0, arr, m, _ptr(bias, torch.float32), _ptr(y),
+                                               _stream()), "pipe_forward_conv2d_asymmetric")
     return y
 
 

@@ -748,6 +748,49 @@ extern "C" int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_d
   return run_gemm(a, small, st);
 }
 
+extern "C" int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W,
+                                              int kh, int kw, int stride, int pad, int nhwc, const int* split, int M,
+                                              const float* bias_dev, float* y_dev, void* stream) {
+  if (!e) return PIPE_EINVAL;
+  if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
+  if ((int64_t)C * kh * kw != e->in) return PIPE_ESHAPE;
+  const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+  if (H + 2 * pad < kh || W + 2 * pad < kw) return PIPE_ESHAPE;
+  const int64_t T64 = (int64_t)N * Ho * Wo;
+  if (T64 > (int64_t)1 << 30) return PIPE_ESHAPE;
+  const int T = (int)T64;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
+  if ((int64_t)((1 << act_bits) - 1) * ((1 << (e->qbits - 1)) - 1) * e->in >= ((int64_t)1 << 31)) return PIPE_ESHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  rc = asym_prepare(e, st);
+  if (rc) return rc;
+  const bool small = use_stream_kernel(e, T);
+  ActBuffers b;
+  rc = get_act_buffers(T, e->in_pad, small, &b);
+  if (rc) return rc;
+  uint32_t* slots = b.amax + 64;
+  int32_t* dz = reinterpret_cast<int32_t*>(b.amax + 66);
+  rc = launch_minmax(x_dev, (int64_t)N * C * H * W, slots, st);
+  if (rc) return rc;
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)N * C * H * W);   // the input's codes, in its own layout
+  if (!q8) return PIPE_ENOMEM;
+  rc = launch_quantize_im2col_asym(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, slots,
+                                   act_bits, q8, b.qx, b.rowsum, b.scale, dz, st);
+  if (rc) return rc;
+  rc = launch_asym_bias(bias_dev, e->asym_C_dev, b.scale, dz, e->asym_bias_dev, e->out, slots, st);
+  if (rc) return rc;
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
+  a.s_x = b.scale; a.bias = e->asym_bias_dev; a.reduce = 1; a.y = y_dev; a.zero_after = b.amax;
+  fill_members(a, Mm, lo, hi);
+  return run_gemm(a, small, st);
+}
+
 extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float* x_dev, int T, int32_t* acc_dev,
                                            uint8_t* qx_dev, float* s_x_out_dev, int32_t* z_out_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;

@@ -324,9 +324,12 @@ __global__ __launch_bounds__(BLK) void quantize_elem_kernel(const float* __restr
 // Step 2: patches of codes -> fragment layout and token code sums.  Token t = (n, ho, wo); column
 // k = (c, r, q) as in a weight row flattened [C, kh, kw].  A thread owns 16 consecutive k of one
 // token; (c, r, q) is split once per chunk and then stepped, not divided, element by element.
+// pad_neg: nullptr (taps outside the image read code 0), or a device word whose negation is the code
+// of the real value 0 (asymmetric codes: the zero point minus 2^(a-1)).
 __global__ __launch_bounds__(BLK) void im2col_codes_kernel(const int8_t* __restrict__ q8, ConvGeom g, int T, int in,
                                                            int in_pad, uint8_t* __restrict__ qx_frag,
-                                                           int32_t* __restrict__ rowsum) {
+                                                           int32_t* __restrict__ rowsum, const int32_t* __restrict__ pad_neg) {
+  const int padv = pad_neg != nullptr ? -pad_neg[0] : 0;
   const int tb = blockIdx.x;
   const int n16 = threadIdx.x & 15;
   const int t = tb * 16 + n16;
@@ -347,10 +350,14 @@ __global__ __launch_bounds__(BLK) void im2col_codes_kernel(const int8_t* __restr
     for (int e = 0; e < 16; ++e) {
       int v = 0;
       const int hi = hi0 + rr, wi = wi0 + qq;
-      if (tok && k < in && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W) {
-        const size_t off = g.nhwc ? (((size_t)nimg * g.H + hi) * g.W + wi) * g.C + cc
-                                  : (((size_t)nimg * g.C + cc) * g.H + hi) * g.W + wi;
-        v = q8[off];
+      if (tok && k < in) {
+        if (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W) {
+          const size_t off = g.nhwc ? (((size_t)nimg * g.H + hi) * g.W + wi) * g.C + cc
+                                    : (((size_t)nimg * g.C + cc) * g.H + hi) * g.W + wi;
+          v = q8[off];
+        } else {
+          v = padv;
+        }
       }
       q[e] = v;
       sum += v;
@@ -470,6 +477,26 @@ __global__ __launch_bounds__(BLK) void quantize_asym_kernel(const float* __restr
 #pragma unroll
     for (int w = 0; w < BLK / 64; ++w) tot += wsum[w][threadIdx.x];
     if (t < T && tot != 0) atomicAdd(&rowsum[t], tot);
+  }
+}
+
+// every element of a tensor once, in its own layout (the convolution's first step): code minus shift
+__global__ __launch_bounds__(BLK) void quantize_elem_asym_kernel(const float* __restrict__ x, int64_t n,
+                                                                 const uint32_t* __restrict__ slots, float qa, int shift,
+                                                                 int8_t* __restrict__ q8, float* __restrict__ scale_out,
+                                                                 int32_t* __restrict__ dz_out) {
+  const float hi = __uint_as_float(slots[0]), nlo = __uint_as_float(slots[1]);
+  const float s = __fdiv_rn(__fadd_rn(hi, nlo), qa);
+  const bool live = s > 0.f;
+  const float zf = live ? fminf(fmaxf(rintf(__fdiv_rn(nlo, s)), 0.f), qa) : 0.f;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    scale_out[0] = s;
+    dz_out[0] = live ? shift - (int)zf : 0;
+  }
+  for (int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x; i < n; i += (int64_t)gridDim.x * BLK) {
+    int v = 0;
+    if (live) v = (int)fminf(fmaxf(__fadd_rn(rintf(__fdiv_rn(x[i], s)), zf), 0.f), qa) - shift;
+    q8[i] = (int8_t)v;
   }
 }
 
@@ -604,7 +631,30 @@ int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, i
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum);
+  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
+                     (const int32_t*)nullptr);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+// the same with asymmetric codes: every element once (code minus 2^(a-1), scale and 2^(a-1) - z to device
+// memory), then the patches, whose taps outside the image hold the code of the real value 0
+int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int kh, int kw, int stride, int pad, int nhwc,
+                                int Ho, int Wo, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
+                                int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out, int32_t* dz_out,
+                                hipStream_t st) {
+  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
+  if (rc) return rc;
+  const int64_t n = (int64_t)N * C * H * W;
+  int64_t blocks = (n + BLK - 1) / BLK;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots,
+                     (float)((1 << act_bits) - 1), 1 << (act_bits - 1), q8_scratch, scale_out, dz_out);
+  ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
+  const int T = N * Ho * Wo, in = C * kh * kw;
+  dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
+  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
+                     (const int32_t*)dz_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

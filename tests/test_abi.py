@@ -69,6 +69,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_forward_depthwise2d(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, C.c_float(0), None, 0, None, 1, None, None) == EINVAL
     assert lib.pipe_forward_asymmetric(None, None, 4, None, 0, None, None, None) == EINVAL
     assert lib.pipe_forward_acc_asymmetric(None, None, 4, None, None, None, None, None) == EINVAL
+    assert lib.pipe_forward_conv2d_asymmetric(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, None, 0, None, None, None) == EINVAL
     assert lib.pipe_expansion_free(None) == 0
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0

@@ -638,3 +638,31 @@ def test_asymmetric_activation_degenerate_inputs_and_widths(pipe):
         assert np.array_equal(acc.cpu().numpy(), ref["acc"])
         assert_close_fp32(y, ref["y"])
     g.free()
+
+
+@pytest.mark.parametrize("C,H,W,O,kh,kw,stride,pad", [(32, 14, 14, 64, 3, 3, 1, 1), (16, 9, 11, 32, 3, 3, 2, 0),
+                                                       (48, 7, 7, 48, 1, 1, 1, 0), (8, 12, 12, 32, 5, 5, 2, 2)])
+def test_asymmetric_conv2d(pipe, C, H, W, O, kh, kw, stride, pad):
+    """The convolution with asymmetric codes on a post-ReLU input (config 2's distribution): taps
+    outside the image carry the zero point, so the result equals the checker's convolution of
+    Q(x) - z with zero padding; both input layouts, with bias and members summed."""
+    rng = np.random.default_rng(730 + C)
+    N = 3
+    x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(np.float32)
+    Wt = (rng.standard_normal((O, C * kh * kw)) * np.sqrt(2.0 / (C * kh * kw))).astype(np.float32)
+    b = rng.standard_normal(O).astype(np.float32)
+    bits, K, gamma, group = 4, 3, 0.5, 16
+    ora = oracle_expand(Wt, wl.LayerSpec(O, C * kh * kw, bits, K, gamma, group))
+    g = pipe.pipe_expand(dev(Wt), bits, K, gamma, group)
+    for split in (None, [2, 1]):
+        ref = po.forward_conv2d_asymmetric(ora, x, kh, kw, stride, pad, split=split, bias=b)
+        y = pipe.pipe_forward_conv2d_asymmetric(g, dev(x), kh, kw, stride, pad, split=split, bias=dev(b)).cpu().numpy()
+        assert y.shape == ref["y"].shape
+        assert_close_fp32(y, ref["y"])
+        xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        yh = pipe.pipe_forward_conv2d_asymmetric(g, dev(xh), kh, kw, stride, pad, split=split, bias=dev(b), nhwc=True).cpu().numpy()
+        assert np.array_equal(y, yh)
+    # the symmetric call on the same expansion afterwards (shared workspace, cleared slots)
+    assert_close_fp32(pipe.pipe_forward_conv2d(g, dev(x), kh, kw, stride, pad).cpu().numpy(),
+                      po.forward_conv2d(ora, x, kh, kw, stride, pad)["y"])
+    g.free()
