@@ -125,7 +125,7 @@ def main():
             return pipe.pipe_forward(e[0], xd, split=split, out=out)
         if cfg.kind == "conv2d":
             c = cfg.conv
-            return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split)
+            return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split, out=out)
         act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
         return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split, out=out)
 
@@ -146,7 +146,7 @@ def main():
         """Times `steps` passes; returns dict with step time and contraction-kernel time."""
         settle_ms = args.settle_ms if settle_ms is None else settle_ms
         xd = xd_full if cfg.kind == "conv2d" else xd_full[:T].contiguous()
-        out = None if cfg.kind == "conv2d" else torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
+        out = torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
         copies = 1
         if rotate:
             copies = max(2, -(-int(1.25 * LLC_BYTES) // max(stream_bytes, 1)))
@@ -177,7 +177,7 @@ def main():
         mode = "eager"
         # ---- the same K steps as ONE HIP graph: decode-sized steps are launch bound, and the small
         # layers' five launches leave gaps as long as their kernels when launched eagerly --------
-        if graph and not args.no_graph and cfg.kind != "conv2d":
+        if graph and not args.no_graph:
             try:
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())

@@ -289,7 +289,7 @@ def pipe_forward_acc_asymmetric(e: Expansion, x: torch.Tensor):
 
 def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
                         nhwc: bool = False, s_x: float = 0.0, split=None, bias=None,
-                        reduce_members: bool = True) -> torch.Tensor:
+                        reduce_members: bool = True, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     if x.dim() != 4:
         raise ValueError("x must be 4-D")
     if nhwc:
@@ -300,11 +300,13 @@ def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride:
     T = N * Ho * Wo
     M = 1 if split is None else len(split)
     shape = (T, e.out_features) if reduce_members else (M, T, e.out_features)
-    y = torch.empty(shape, dtype=torch.float32, device=x.device)
+    y = out if out is not None else torch.empty(shape, dtype=torch.float32, device=x.device)
+    if tuple(y.shape) != shape:
+        raise ValueError("output has the wrong shape")
     arr, m = _split(split)
     _check(_lib.pipe_forward_conv2d(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
                                     1 if nhwc else 0, float(s_x), arr, m, _ptr(bias, torch.float32),
-                                    1 if reduce_members else 0, _ptr(y), _stream()), "pipe_forward_conv2d")
+                                    1 if reduce_members else 0, _ptr(y, torch.float32), _stream()), "pipe_forward_conv2d")
     return y
 
 

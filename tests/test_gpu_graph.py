@@ -193,3 +193,40 @@ def test_asymmetric_forward_graph_replays(T):
         other = pipe.pipe_forward(g, xs[(i + 1) % 3])          # symmetric eager work on the same workspace
         torch.cuda.synchronize()
     g.free()
+
+
+def test_conv_graph_replays():
+    """The convolution call (range reduction, element-wise codes, code-sum clearing, patch gather,
+    contraction) captured once and replayed with other inputs."""
+    import paper_2311_15806_amd.binding as pipe
+    w = wl.scaled(wl.C2, out_div=4, in_div=4, tokens=4 * 14 * 14)
+    spec, c = w.layers[0], w.conv
+    W = torch.from_numpy(wl.make_weight(w, 0)).cuda()
+    g = pipe.pipe_expand(W, spec.bits, spec.K, spec.gamma, spec.group)
+    x0 = torch.from_numpy(wl.make_input(w)).cuda()
+    xs = [x0, x0 * 0.3, torch.flip(x0, dims=[0]) * 2.0]
+    split = list(w.split)
+    args = (c["kh"], c["kw"], c["stride"], c["pad"])
+    eager = [pipe.pipe_forward_conv2d(g, xi, *args, split=split).clone() for xi in xs]
+    x = xs[0].clone()
+    out = torch.empty_like(eager[0])
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipe.pipe_forward_conv2d(g, x, *args, split=split, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipe.pipe_forward_conv2d(g, x, *args, split=split, out=out)
+    for rep in range(6):
+        i = rep % 3
+        x.copy_(xs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[i]), "replay %d differs" % rep
+        other = pipe.pipe_forward_conv2d(g, xs[(i + 1) % 3], *args, split=split)
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager[(i + 1) % 3])
+    g.free()
