@@ -313,7 +313,10 @@ struct ConvGeom {
 // (an element appears in up to kh*kw patches; the IEEE division is paid once, not per patch).
 __global__ __launch_bounds__(BLK) void quantize_elem_kernel(const float* __restrict__ x, int64_t n, float s_static,
                                                             const uint32_t* __restrict__ amax_bits,
-                                                            int8_t* __restrict__ q8, float* __restrict__ scale_out) {
+                                                            int8_t* __restrict__ q8, float* __restrict__ scale_out,
+                                                            int32_t* __restrict__ zero_me, int n_zero) {
+  // also clears the token code sums the gather that follows adds into
+  for (int i = blockIdx.x * BLK + threadIdx.x; i < n_zero; i += gridDim.x * BLK) zero_me[i] = 0;
   const float s = act_scale(s_static, amax_bits);
   if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
   const bool live = s > 0.f;
@@ -341,28 +344,40 @@ __global__ __launch_bounds__(BLK) void im2col_codes_kernel(const int8_t* __restr
   const bool tok = t < T;
   const int wo = tok ? t % g.Wo : 0, ho = tok ? (t / g.Wo) % g.Ho : 0, nimg = tok ? t / (g.Wo * g.Ho) : 0;
   const int hi0 = ho * g.stride - g.pad, wi0 = wo * g.stride - g.pad;
+  // offset = base_n + c * step_c + h * step_r + w * step_q in either layout
+  const int step_q = g.nhwc ? g.C : 1, step_r = g.nhwc ? g.W * g.C : g.W, step_c = g.nhwc ? 1 : g.H * g.W;
+  const int base_n = nimg * g.C * g.H * g.W;
   int sum = 0;
   for (int c = c_lo + (threadIdx.x >> 4); c < c_hi; c += BLK / 16) {
     int k = c * 16;
     int qq = k % g.kw, rr = (k / g.kw) % g.kh, cc = k / (g.kw * g.kh);
+    // The element offset is stepped, not recomputed (32-bit: the input has fewer than 2^31 elements), and
+    // all 16 byte loads are issued before the first one is used: offsets of taps that are not read are
+    // clamped to element 0 and the value is replaced afterwards.
+    int off = base_n + cc * step_c + (hi0 + rr) * step_r + (wi0 + qq) * step_q;
     int q[16];
+    int offs[16];
+    int kind[16];   // 0: code 0 (beyond the row or the batch), 1: read, 2: outside the image
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      int v = 0;
       const int hi = hi0 + rr, wi = wi0 + qq;
-      if (tok && k < in) {
-        if (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W) {
-          const size_t off = g.nhwc ? (((size_t)nimg * g.H + hi) * g.W + wi) * g.C + cc
-                                    : (((size_t)nimg * g.C + cc) * g.H + hi) * g.W + wi;
-          v = q8[off];
-        } else {
-          v = padv;
-        }
-      }
-      q[e] = v;
-      sum += v;
+      const bool inside = hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+      kind[e] = (tok && k < in) ? (inside ? 1 : 2) : 0;
+      offs[e] = kind[e] == 1 ? off : 0;
       ++k;
-      if (++qq == g.kw) { qq = 0; if (++rr == g.kh) { rr = 0; ++cc; } }
+      off += step_q;
+      if (++qq == g.kw) {
+        qq = 0;
+        off += step_r - g.kw * step_q;
+        if (++rr == g.kh) { rr = 0; ++cc; off += step_c - g.kh * step_r; }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) q[e] = q8[offs[e]];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      q[e] = kind[e] == 1 ? q[e] : (kind[e] == 2 ? padv : 0);
+      sum += q[e];
     }
     const int ks = c >> 2, kc = c & 3;
     const uint4 w = make_uint4(pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7]),
@@ -484,7 +499,9 @@ __global__ __launch_bounds__(BLK) void quantize_asym_kernel(const float* __restr
 __global__ __launch_bounds__(BLK) void quantize_elem_asym_kernel(const float* __restrict__ x, int64_t n,
                                                                  const uint32_t* __restrict__ slots, float qa, int shift,
                                                                  int8_t* __restrict__ q8, float* __restrict__ scale_out,
-                                                                 int32_t* __restrict__ dz_out) {
+                                                                 int32_t* __restrict__ dz_out, int32_t* __restrict__ zero_me,
+                                                                 int n_zero) {
+  for (int i = blockIdx.x * BLK + threadIdx.x; i < n_zero; i += gridDim.x * BLK) zero_me[i] = 0;
   const float hi = __uint_as_float(slots[0]), nlo = __uint_as_float(slots[1]);
   const float s = __fdiv_rn(__fadd_rn(hi, nlo), qa);
   const bool live = s > 0.f;
@@ -612,7 +629,8 @@ int launch_quantize_elem(const float* x, int64_t n, float s_static, const uint32
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits, q8, scale_out);
+  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits, q8, scale_out,
+                     (int32_t*)nullptr, 0);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -621,13 +639,13 @@ int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, i
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, int8_t* q8_scratch, uint8_t* qx_frag,
                            int32_t* rowsum, float* scale_out, hipStream_t st) {
-  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
-  if (rc) return rc;
   const int64_t n = (int64_t)N * C * H * W;
+  if (n >= ((int64_t)1 << 31)) return PIPE_ESHAPE;   // the gather steps 32-bit element offsets
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits,
-                     q8_scratch, scale_out);
+                     q8_scratch, scale_out, rowsum, T_pad);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
@@ -643,13 +661,12 @@ int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int 
                                 int Ho, int Wo, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
                                 int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out, int32_t* dz_out,
                                 hipStream_t st) {
-  int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
-  if (rc) return rc;
   const int64_t n = (int64_t)N * C * H * W;
+  if (n >= ((int64_t)1 << 31)) return PIPE_ESHAPE;   // the gather steps 32-bit element offsets
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots,
-                     (float)((1 << act_bits) - 1), 1 << (act_bits - 1), q8_scratch, scale_out, dz_out);
+                     (float)((1 << act_bits) - 1), 1 << (act_bits - 1), q8_scratch, scale_out, dz_out, rowsum, T_pad);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
