@@ -416,6 +416,8 @@ def main():
         "mfma_probe_tops": pipe.pipe_mfma_probe(20000, 0),
         "mfma_probe_tops_ternary_x_int8": pipe.pipe_mfma_probe(20000, 1),
         "mfma_probe_tops_int8_x_int8": pipe.pipe_mfma_probe(20000, 2),
+        # the same on v_mfma_i32_32x32x32_i8 (twice the work per operand byte, but a lower sustained rate)
+        "mfma_probe_tops_32x32x32_ternary_x_int8": pipe.pipe_mfma_probe(20000, 11),
         "hbm_probe_gbs": pipe.pipe_hbm_probe(1 << 31),
         # the same step counted as if all K orders were dense (2*T*in*out*K): NOT the roofline numerator
         "dense_equivalent_tops": 2.0 * T0 * sum(l.in_features * l.out_features * l.K for l in cfg.layers)

@@ -370,7 +370,9 @@ int pipe_timing_read(double* total_ms, int* launches);
  * rounds of 16 instructions per wave and writes the int8 rate it sustained, in TOP/s,
  * to *tops_out (HOST).  `operands`: 0 = constant bytes, 1 = ternary offset codes
  * against random int8 (what a ternary layer feeds the pipe), 2 = random int8 against
- * random int8; the chip's clock under load depends on it.
+ * random int8; the chip's clock under load depends on it.  10, 11, 12 = the same
+ * operand kinds on v_mfma_i32_32x32x32_i8 (eight instructions per round, the same
+ * multiply-adds), the instruction with twice the work per operand byte.
  * pipe_hbm_probe reads `bytes` (>= 1 MiB, rounded down to 128 KiB) of freshly
  * allocated device memory with the access pattern of the weight-streaming kernel and
  * writes the bandwidth, in GB/s, to *gbps_out (HOST); it allocates and frees `bytes`.

@@ -40,6 +40,38 @@ __global__ __launch_bounds__(256, 2) void mfma_probe_kernel(int iters, const v4i
   if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never true
 }
 
+// The same loop on v_mfma_i32_32x32x32_i8 (twice the multiply-adds per operand byte): eight
+// independent instructions per round, the same 16 x 16384 multiply-adds per round and wave.
+typedef int v16i __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256, 2) void mfma_probe32_kernel(int iters, const v4i* __restrict__ ops, int* sink) {
+  v4i a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = ops[i * 256 + threadIdx.x];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = ops[(4 + i) * 256 + threadIdx.x];
+  v16i c[4][2];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c[r][t][i] = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) c[r][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[t], c[r][t], 0, 0, 0);
+  }
+  int s = 0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += c[r][t][i];
+  if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never true
+}
+
 // Streaming read: every 512-thread workgroup reads a contiguous 128 KiB, wave w the 1-KiB tiles
 // w, w+8, ..., four loads in flight per lane -- the access pattern of the weight-streaming kernel.
 __global__ __launch_bounds__(512) void hbm_probe_kernel(const uint4* __restrict__ x, unsigned* sink) {
@@ -59,6 +91,8 @@ __global__ __launch_bounds__(512) void hbm_probe_kernel(const uint4* __restrict_
 }  // namespace
 
 extern "C" int pipe_mfma_probe(int iters, int operands, double* tops_out, void* stream) {
+  const bool wide = operands >= 10;   // 10..12: the same operand kinds on the 32x32x32 instruction
+  if (wide) operands -= 10;
   if (iters <= 0 || !tops_out || operands < 0 || operands > 2) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   int* sink = (int*)pipe_ws_get(WS_MISC, 256 + 8 * 256 * 16);
@@ -80,9 +114,11 @@ extern "C" int pipe_mfma_probe(int iters, int operands, double* tops_out, void* 
   PIPE_HIP(hipEventCreate(&e0));
   PIPE_HIP(hipEventCreate(&e1));
   const int blocks = 256 * 2 * 4;   // 2 workgroups per CU resident, 4 rounds
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);   // warm-up
+  if (wide) hipLaunchKernelGGL(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);   // warm-up
+  else hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);
   PIPE_HIP(hipEventRecord(e0, st));
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
+  if (wide) hipLaunchKernelGGL(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
+  else hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
   PIPE_HIP(hipEventRecord(e1, st));
   PIPE_HIP(hipEventSynchronize(e1));
   float ms = 0.f;
