@@ -87,7 +87,9 @@ __device__ __forceinline__ void unpack_step(const uint4& w, int j, v4i& o) {
 
 // XM = number of distinct activation tensors the items of a bin can read: 1 (one input for all
 // orders), or 2 / 4 (one input per ensemble member, at most XM members).
-template <int BITS, int NW, int XM, bool ACC_OUT>
+// XMASK: the batch does not fill its last 16-token block; the activation loads of that block are
+// issued for the lanes of real tokens only.
+template <int BITS, int NW, int XM, bool ACC_OUT, bool XMASK>
 __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)) <= 4) ? 4 : 2) void gemm_stream_kernel(const StreamParams p) {
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
@@ -143,11 +145,22 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   const uint8_t* xb[XM];
 #pragma unroll
   for (int m = 0; m < XM; ++m) xb[m] = p.qx + (size_t)(m < p.M ? m : p.M - 1) * p.qx_mstride + (size_t)tb * p.nks * 1024;
+  // lanes of tokens beyond the batch keep the zeros they start with: their codes are zero anyway, and
+  // a load instruction costs the memory pipeline only its active lanes (one token in sixteen at T = 1)
+  const bool xlive = tb * 16 + (lane & 15) < p.T;
+  const bool xfull = !XMASK || tb * 16 + 16 <= p.T;   // uniform: a whole block needs no lane mask
   auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
+    if (xfull) {
 #pragma unroll
-    for (int m = 0; m < XM; ++m)
+      for (int m = 0; m < XM; ++m)
 #pragma unroll
-      for (int j = 0; j < STEPS; ++j) x[m * STEPS + j] = reinterpret_cast<const uint4*>(xb[m] + (size_t)(tl * STEPS + j) * 1024)[lane];
+        for (int j = 0; j < STEPS; ++j) x[m * STEPS + j] = reinterpret_cast<const uint4*>(xb[m] + (size_t)(tl * STEPS + j) * 1024)[lane];
+    } else if (xlive) {
+#pragma unroll
+      for (int m = 0; m < XM; ++m)
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) x[m * STEPS + j] = reinterpret_cast<const uint4*>(xb[m] + (size_t)(tl * STEPS + j) * 1024)[lane];
+    }
   };
 #pragma unroll
   for (int j = 0; j < NX; ++j) { x0[j] = make_uint4(0, 0, 0, 0); x1[j] = make_uint4(0, 0, 0, 0); }
@@ -548,15 +561,18 @@ int launch_multi_cap(const StreamParams& p, int n_bins, int cap, int xm, const G
 template <int BITS, int NW>
 int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const GemmArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)((n_bins + 7) / 8 * 8 * p.ksplit * p.n_tb)), blk(NW * 64);
-  if (acc_out) {
-    if (xm == 1) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else if (xm == 2) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 2, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 4, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
-  } else {
-    if (xm == 1) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else if (xm == 2) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 2, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
-    else PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 4, false>), grid, blk, st, a.ev_start, a.ev_stop, p);
-  }
+  const bool xmask = p.T % 16 != 0;
+#define PIPE_STREAM_LAUNCH(XMV, ACC, MASK) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, XMV, ACC, MASK>), grid, blk, st, a.ev_start, a.ev_stop, p)
+#define PIPE_STREAM_PICK(XMV)                                                     \
+  do {                                                                            \
+    if (acc_out) { if (xmask) PIPE_STREAM_LAUNCH(XMV, true, true); else PIPE_STREAM_LAUNCH(XMV, true, false); }   \
+    else { if (xmask) PIPE_STREAM_LAUNCH(XMV, false, true); else PIPE_STREAM_LAUNCH(XMV, false, false); }         \
+  } while (0)
+  if (xm == 1) PIPE_STREAM_PICK(1);
+  else if (xm == 2) PIPE_STREAM_PICK(2);
+  else PIPE_STREAM_PICK(4);
+#undef PIPE_STREAM_PICK
+#undef PIPE_STREAM_LAUNCH
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
