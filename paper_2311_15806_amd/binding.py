@@ -70,6 +70,7 @@ def _load():
     lib.pipe_first_predictor_size.argtypes = [pd, pd, ci, ci, C.c_double, C.c_double, C.POINTER(ci)]
     lib.pipe_set_activation_bits.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
+    lib.pipe_set_decode_fusion.argtypes = [ci]
     lib.pipe_set_token_tile.argtypes = [ci]
     lib.pipe_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), vp]
     lib.pipe_hbm_probe.argtypes = [C.c_int64, C.POINTER(C.c_double), vp]
@@ -80,7 +81,7 @@ def _load():
     lib.pipe_last_device_error.restype = C.c_char_p
     for f in ("pipe_expand", "pipe_expand_unstructured", "pipe_expansion_free", "pipe_expansion_info", "pipe_expansion_order",
               "pipe_forward", "pipe_forward_acc", "pipe_forward_asymmetric", "pipe_forward_acc_asymmetric", "pipe_forward_conv2d_asymmetric", "pipe_forward_conv2d", "pipe_mlp_forward",
-              "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
+              "pipe_set_kernel", "pipe_set_stream_split", "pipe_set_decode_fusion", "pipe_set_token_tile", "pipe_timing_enable", "pipe_timing_read", "pipe_mfma_probe", "pipe_hbm_probe"):
         getattr(lib, f).restype = ci
     return lib
 
@@ -492,6 +493,10 @@ def pipe_set_token_tile(tokens: int) -> None:
 
 def pipe_set_stream_split(workgroups_per_bin: int) -> None:
     _check(_lib.pipe_set_stream_split(int(workgroups_per_bin)), "pipe_set_stream_split")
+
+
+def pipe_set_decode_fusion(on: bool) -> None:
+    _check(_lib.pipe_set_decode_fusion(1 if on else 0), "pipe_set_decode_fusion")
 
 
 def pipe_timing_enable(on: bool) -> None:

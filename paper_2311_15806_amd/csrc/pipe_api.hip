@@ -75,6 +75,14 @@ extern "C" int pipe_set_activation_bits(int bits) {
   return set_act_qmax(g_act_qmax_host);
 }
 
+int g_decode_fusion = 1;
+
+extern "C" int pipe_set_decode_fusion(int on) {
+  if (on != 0 && on != 1) return PIPE_EINVAL;
+  g_decode_fusion = on;
+  return PIPE_OK;
+}
+
 extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
   if (workgroups_per_bin < 0 || workgroups_per_bin > PIPE_MAX_SPLIT) return PIPE_EINVAL;
   g_stream_ksplit = workgroups_per_bin;
@@ -617,12 +625,18 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
-  if (rc) return rc;
+  // A handful of tokens: the streaming kernel quantizes them itself, one launch instead of two
+  const bool fused = small && g_decode_fusion && T <= PIPE_FUSED_QUANT_MAX_T && e->in_pad <= PIPE_FUSED_QUANT_MAX_IN &&
+                     e->in % 4 == 0 && (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0 && e->bin_cap == 4;
+  if (!fused) {
+    rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
+    if (rc) return rc;
+  }
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.qx_mstride = 0; a.rowsum = b.rowsum; a.rowsum_mstride = 0;
   a.s_x = b.scale; a.sx_mstride = 0; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.act = 0;
   a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr; a.zero_after = b.amax;
+  if (fused) { a.x_f32 = x_dev; a.s_static = s_x; }
   fill_members(a, Mm, lo, hi);
   return run_gemm(a, small, st);
 }

@@ -52,6 +52,10 @@ struct StreamParams {
   int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
   int n_tb;                // 16-token blocks: one workgroup per (bin, k share, token block)
   int n_bins;
+  const float* x_f32;      // QFUSE: the fp32 input [T, in] (T <= 4), quantized by every workgroup itself
+  float s_static;          // QFUSE: given activation scale, or <= 0 for max|x| / act_qmax
+  float act_qmax;          // QFUSE: largest activation code
+  int in;                  // QFUSE: in_features (multiple of 4)
   int32_t* ws_sum;         // [n_bins][ksplit][cap][256] partial tiles of split bins
   uint32_t* ws_cnt;        // [n_bins] arrival counters, zero between launches
   int member_lo[PIPE_MAX_K];
@@ -89,8 +93,17 @@ __device__ __forceinline__ void unpack_step(const uint4& w, int j, v4i& o) {
 // orders), or 2 / 4 (one input per ensemble member, at most XM members).
 // XMASK: the batch does not fill its last 16-token block; the activation loads of that block are
 // issued for the lanes of real tokens only.
-template <int BITS, int NW, int XM, bool ACC_OUT, bool XMASK>
+// QFUSE (a single token, one activation tensor): there is no quantizer launch; every
+// workgroup reduces max|x| over the few-KiB input itself, quantizes it into LDS with the same
+// arithmetic as the quantizer kernels (IEEE division, round half to even) while its first codes are
+// on their way, and builds its activation fragments from there.
+constexpr int QF_T = 1, QF_IN = 8192;
+template <int BITS, int NW, int XM, bool ACC_OUT, bool XMASK, bool QFUSE = false>
 __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)) <= 4) ? 4 : 2) void gemm_stream_kernel(const StreamParams p) {
+  static_assert(!QFUSE || (XM == 1 && !ACC_OUT), "the fused quantizer serves one shared input");
+  __shared__ __attribute__((aligned(16))) uint8_t s_qx[QFUSE ? QF_T * QF_IN : 16];
+  __shared__ float s_red[NW];
+  __shared__ int s_rs[QF_T];
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
   constexpr int KSUP = 512 / BITS;
   constexpr int STEPS = KSUP / 64;      // 64-k steps per packed tile
@@ -149,8 +162,16 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   // a load instruction costs the memory pipeline only its active lanes (one token in sixteen at T = 1)
   const bool xlive = tb * 16 + (lane & 15) < p.T;
   const bool xfull = !XMASK || tb * 16 + 16 <= p.T;   // uniform: a whole block needs no lane mask
+  const int in_pad_q = p.nks * 64;
   auto load_x = [&](int tl, uint4 (&x)[NX]) __attribute__((always_inline)) {
-    if (xfull) {
+    if constexpr (QFUSE) {
+      // the fragment of a 64-k step: lane (kc, n) holds codes 16 kc .. 16 kc + 15 of token n
+      if ((lane & 15) < p.T) {
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j)
+          x[j] = *reinterpret_cast<const uint4*>(&s_qx[(size_t)(lane & 15) * in_pad_q + (size_t)(tl * STEPS + j) * 64 + (lane >> 4) * 16]);
+      }
+    } else if (xfull) {
 #pragma unroll
       for (int m = 0; m < XM; ++m)
 #pragma unroll
@@ -165,8 +186,8 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
 #pragma unroll
   for (int j = 0; j < NX; ++j) { x0[j] = make_uint4(0, 0, 0, 0); x1[j] = make_uint4(0, 0, 0, 0); }
   int tl = tile_lo + wave;
-  if (tl < tile_hi) { load_w(tl, w0); load_x(tl, x0); }
-  if (tl + NW < tile_hi) { load_w(tl + NW, w1); load_x(tl + NW, x1); }
+  if (tl < tile_hi) { load_w(tl, w0); if (!QFUSE) load_x(tl, x0); }
+  if (tl + NW < tile_hi) { load_w(tl + NW, w1); if (!QFUSE) load_x(tl + NW, x1); }
   // epilogue operands that need no descriptor: row scales (same positions), and per member the
   // activation scale and this thread's token code sum
   float scv[R];
@@ -174,11 +195,63 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   for (int r = 0; r < R; ++r) scv[r] = p.scales[(pos0 + r) * 16 + ch];
   float sxm[R];
   int rsm[R];
+  if constexpr (!QFUSE) {
 #pragma unroll
-  for (int m = 0; m < R; ++m) {       // at most R members (K <= R)
-    const int mm = m < p.M ? m : p.M - 1;
-    sxm[m] = p.s_x[mm * p.sx_mstride];
-    rsm[m] = OFF ? p.rowsum[(size_t)mm * p.rowsum_mstride + tg] : 0;
+    for (int m = 0; m < R; ++m) {       // at most R members (K <= R)
+      const int mm = m < p.M ? m : p.M - 1;
+      sxm[m] = p.s_x[mm * p.sx_mstride];
+      rsm[m] = OFF ? p.rowsum[(size_t)mm * p.rowsum_mstride + tg] : 0;
+    }
+  } else {
+    // ---- quantize the input here (the codes already requested are on their way meanwhile)
+    const int in = p.in;
+    const float4* x4 = reinterpret_cast<const float4*>(p.x_f32);
+    const int n4 = (p.T * in) >> 2;
+    if ((int)threadIdx.x < QF_T) s_rs[threadIdx.x] = 0;
+    float s_act = p.s_static;
+    if (!(s_act > 0.f)) {
+      float mx = 0.f;
+      for (int i = threadIdx.x; i < n4; i += NW * 64) {
+        const float4 v = x4[i];
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+      if (lane == 0) s_red[wave] = mx;
+      __syncthreads();
+      mx = s_red[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_red[w]);
+      s_act = __fdiv_rn(mx, p.act_qmax);
+    } else {
+      __syncthreads();   // the cleared code sums
+    }
+    const bool live_q = s_act > 0.f;
+    auto q1 = [&](float v) __attribute__((always_inline)) {
+      const float q = fminf(fmaxf(rintf(__fdiv_rn(v, s_act)), -p.act_qmax), p.act_qmax);
+      return live_q ? (int)q : 0;
+    };
+    for (int i = threadIdx.x; i < n4; i += NW * 64) {
+      const float4 v = x4[i];
+      const int tq = (i * 4) / in, k = i * 4 - tq * in;   // in is a multiple of 4: one token per float4
+      const int a = q1(v.x), b = q1(v.y), c = q1(v.z), d = q1(v.w);
+      *reinterpret_cast<uint32_t*>(&s_qx[(size_t)tq * in_pad_q + k]) =
+          (uint32_t)(uint8_t)a | ((uint32_t)(uint8_t)b << 8) | ((uint32_t)(uint8_t)c << 16) | ((uint32_t)(uint8_t)d << 24);
+      const int sum4 = a + b + c + d;
+      if (sum4 != 0) atomicAdd(&s_rs[tq], sum4);
+    }
+    // codes beyond in_features are zero
+    const int pad4 = (in_pad_q - in) >> 2;
+    for (int i = threadIdx.x; i < p.T * pad4; i += NW * 64) {
+      const int tq = i / pad4, k = in + (i - tq * pad4) * 4;
+      *reinterpret_cast<uint32_t*>(&s_qx[(size_t)tq * in_pad_q + k]) = 0u;
+    }
+    __syncthreads();
+    const int rs_q = (OFF && tg < p.T) ? s_rs[min(tg, QF_T - 1)] : 0;
+#pragma unroll
+    for (int m = 0; m < R; ++m) { sxm[m] = s_act; rsm[m] = rs_q; }
+    if (tl < tile_hi) load_x(tl, x0);
+    if (tl + NW < tile_hi) load_x(tl + NW, x1);
   }
 
   // ---- the descriptor: scalar reads out of one vector register
@@ -561,6 +634,13 @@ int launch_multi_cap(const StreamParams& p, int n_bins, int cap, int xm, const G
 template <int BITS, int NW>
 int launch_nw(const StreamParams& p, int n_bins, int xm, bool acc_out, const GemmArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)((n_bins + 7) / 8 * 8 * p.ksplit * p.n_tb)), blk(NW * 64);
+  if (p.x_f32 != nullptr) {
+    // no quantizer launch: the contraction quantizes its few tokens itself
+    if (xm != 1 || acc_out || p.T > QF_T || p.nks * 64 > QF_IN || p.in % 4 != 0 || p.n_tb != 1) return PIPE_EINVAL;
+    PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, 1, false, true, true>), grid, blk, st, a.ev_start, a.ev_stop, p);
+    PIPE_HIP(hipGetLastError());
+    return PIPE_OK;
+  }
   const bool xmask = p.T % 16 != 0;
 #define PIPE_STREAM_LAUNCH(XMV, ACC, MASK) PIPE_LAUNCH((gemm_stream_kernel<BITS, NW, XMV, ACC, MASK>), grid, blk, st, a.ev_start, a.ev_stop, p)
 #define PIPE_STREAM_PICK(XMV)                                                     \
@@ -592,6 +672,8 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.bins = e->bins_dev;
   p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
+  p.x_f32 = a.x_f32; p.s_static = a.s_static; p.act_qmax = g_act_qmax_host; p.in = e->in;
+  if (a.x_f32 != nullptr && e->bin_cap != R) return PIPE_EINVAL;
   // Fewer bins than half the CUs and a long k: split each bin over several workgroups (each still
   // with at least two tiles per wave).  With more bins a split only adds the exchange through
   // the workspace (measured on the 4096 x 11008 4-bit layer: 160 bins, 21.7 us unsplit, 23.5 us

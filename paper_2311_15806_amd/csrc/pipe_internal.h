@@ -43,6 +43,8 @@ static inline int64_t round_up64(int64_t a, int64_t b) { return (a + b - 1) / b 
 // in ascending order k).
 constexpr int STREAM_BIN_CAP = 16;
 constexpr int PIPE_STREAM_MAX_T = 128;   // the weight-streaming kernel serves up to this many tokens
+constexpr int PIPE_FUSED_QUANT_MAX_T = 1;     // the streaming kernel quantizes a single token itself (no quantizer launch); every workgroup repeats the work, which costs more than the launch it saves from 2 tokens on
+constexpr int PIPE_FUSED_QUANT_MAX_IN = 8192; // ... for layers of at most this many (padded) input features
 constexpr int PIPE_QUANT1_MAX_T = 64;    // the one-launch quantizer (every token's workgroup scans the whole input for the maximum) up to this many
 constexpr int PIPE_MAX_SPLIT = 8;   // workgroups per bin of the weight-streaming kernel, at most
 struct StreamBin {
@@ -253,6 +255,9 @@ struct GemmArgs {
   int M;                 // members
   int member_lo[PIPE_MAX_K];  // 0-based first order of member m
   int member_hi[PIPE_MAX_K];  // 0-based last order (inclusive)
+  const float* x_f32;    // streaming kernel, at most 4 tokens: the fp32 input [T, in] when the contraction quantizes it
+                         // itself (then qx, rowsum and s_x are not read), else nullptr
+  float s_static;        // with x_f32: the given activation scale, or <= 0 for the dynamic one
   const float* bias;     // or nullptr
   int reduce;            // 1: y[T,out]; 0: y[M,T,out]
   int act;               // 0 none; PIPE_ACT_GELU fused in the epilogue; PIPE_ACT_SILU_GATED: the layer is gate||up and
@@ -290,3 +295,4 @@ extern float g_act_qmax_host;   // the activation quantizer's largest code (host
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
 extern int g_tiled_mtb;       // token blocks per tile of the tiled kernel; 0 = automatic
 extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic
+extern int g_decode_fusion;   // 1: batches of at most 4 tokens are quantized inside the streaming kernel

@@ -9,7 +9,7 @@ from paper_2311_15806_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("T", [7, 200])
+@pytest.mark.parametrize("T", [3, 7, 200])
 def test_forward_graph_replays(T):
     import paper_2311_15806_amd.binding as pipe
     w = wl.scaled(wl.C4, out_div=4, in_div=4)

@@ -666,3 +666,46 @@ def test_asymmetric_conv2d(pipe, C, H, W, O, kh, kw, stride, pad):
     assert_close_fp32(pipe.pipe_forward_conv2d(g, dev(x), kh, kw, stride, pad).cpu().numpy(),
                       po.forward_conv2d(ora, x, kh, kw, stride, pad)["y"])
     g.free()
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4])
+def test_decode_with_the_quantizer_inside_the_streaming_kernel(pipe, T):
+    """Batches of at most four tokens: the streaming kernel reduces max|x| and quantizes the input itself
+    (one launch).  The result equals the two-launch path bit for bit -- same codes, same code sums,
+    same scale -- and the checker within the fp32 tolerance, for every code width, a static scale,
+    members, a bias, a ragged in_features and a split bin; an input that does not qualify
+    (in_features not a multiple of 4) takes the two-launch path."""
+    rng = np.random.default_rng(740 + T)
+    for bits, K, gamma, group, O, I, split, s_x in [(2, 4, 0.25, 64, 256, 1024, None, 0.0), (4, 4, 0.5, 32, 192, 332, [2, 2], 0.0),
+                                                  (8, 2, 1.0, 16, 64, 520, None, 0.0), (4, 3, 0.5, 16, 96, 4096, [1, 2], 0.031),
+                                                  (2, 3, 0.5, 16, 64, 250, None, 0.0)]:
+        W, x = _w(741 + bits, O, I), _x(742 + T, T, I)
+        b = rng.standard_normal(O).astype(np.float32)
+        ora = oracle_expand(W, wl.LayerSpec(O, I, bits, K, gamma, group))
+        ref = po.forward(ora, x, s_x=s_x if s_x > 0 else None, split=split, bias=b)
+        g = pipe.pipe_expand(dev(W), bits, K, gamma, group)
+        try:
+            y1 = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+            pipe.pipe_set_stream_split(2)
+            y1s = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+            pipe.pipe_set_stream_split(0)
+            pipe.pipe_set_decode_fusion(False)
+            y0 = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        finally:
+            pipe.pipe_set_decode_fusion(True)
+            pipe.pipe_set_stream_split(0)
+        assert np.array_equal(y1, y0) and np.array_equal(y1s, y0)
+        assert_close_fp32(y1, ref["y"])
+        if split is not None:
+            ym = pipe.pipe_forward(g, dev(x), s_x=s_x, split=split, bias=dev(b), reduce_members=False).cpu().numpy()
+            refm = po.forward(ora, x, s_x=s_x if s_x > 0 else None, split=split, bias=b, reduce_members=False)["y"]
+            for m in range(len(split)):
+                assert_close_fp32(ym[m], np.asarray(refm[m]))
+        g.free()
+    # an all-zero input: scale 0, the output is the bias
+    W = _w(750, 64, 256)
+    g = pipe.pipe_expand(dev(W), 4, 2, 0.5, 16)
+    b = rng.standard_normal(64).astype(np.float32)
+    y = pipe.pipe_forward(g, dev(np.zeros((T, 256), np.float32)), bias=dev(b)).cpu().numpy()
+    assert np.array_equal(y, np.tile(b, (T, 1)))
+    g.free()
