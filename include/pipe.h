@@ -356,7 +356,7 @@ int pipe_set_token_tile(int tokens);
  * do not depend on the setting.  Returns PIPE_EINVAL outside 0..8.                */
 int pipe_set_stream_split(int workgroups_per_bin);
 
-/* A single token (pipe_forward on a layer of at most 8192 input features, a multiple
+/* A single token (pipe_forward, and layer 1 of pipe_mlp_forward, on a layer of at most 8192 input features, a multiple
  * of 4, 16-byte aligned input): by default the weight-streaming kernel quantizes the
  * input itself -- every workgroup reduces max|x| and rounds the few KiB of activations
  * with the quantizer's own arithmetic -- so the step is one launch instead of two.

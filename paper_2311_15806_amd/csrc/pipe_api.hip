@@ -573,6 +573,12 @@ extern "C" int pipe_timing_read(double* total_ms, int* launches) {
 
 // Activation quantization of a [T, in] input into the buffers of `b`; small batches take the
 // single-launch path.
+// A single token: the streaming kernel quantizes it itself, one launch instead of two
+static bool fuse_decode_quant(const pipe_expansion* e, int T, const float* x_dev, bool small) {
+  return small && g_decode_fusion && T <= PIPE_FUSED_QUANT_MAX_T && e->in_pad <= PIPE_FUSED_QUANT_MAX_IN &&
+         e->in % 4 == 0 && (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0 && e->bin_cap == 4;
+}
+
 static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s_x, const ActBuffers& b, bool small,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
   if (small && T <= PIPE_QUANT1_MAX_T)
@@ -625,9 +631,7 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  // A handful of tokens: the streaming kernel quantizes them itself, one launch instead of two
-  const bool fused = small && g_decode_fusion && T <= PIPE_FUSED_QUANT_MAX_T && e->in_pad <= PIPE_FUSED_QUANT_MAX_IN &&
-                     e->in % 4 == 0 && (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0 && e->bin_cap == 4;
+  const bool fused = fuse_decode_quant(e, T, x_dev, small);
   if (!fused) {
     rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
     if (rc) return rc;
@@ -952,8 +956,11 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   uint32_t* amax_h = b.amax + 16;
   float* scale_h = b.scale + 16;
 
-  rc = quantize_input(x_dev, T, l1->in, l1->in_pad, s_x, b, small, nullptr, b.scale, st);
-  if (rc) return rc;
+  const bool fused = fuse_decode_quant(l1, T, x_dev, small);
+  if (!fused) {
+    rc = quantize_input(x_dev, T, l1->in, l1->in_pad, s_x, b, small, nullptr, b.scale, st);
+    if (rc) return rc;
+  }
   // The members' max|h| slots are zero on entry: cleared when the workspace is allocated and,
   // after each use, by the layer-2 kernel that follows their last reader.  A call that failed
   // between the two leaves them dirty; then they are cleared by a launch of their own.
@@ -968,6 +975,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   a.e = l1; a.T = T; a.T_pad = T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
   a.bias = bias1_dev; a.reduce = 0; a.zero_after = b.amax;
   a.zero_big = reinterpret_cast<uint32_t*>(rowsum_h); a.zero_big_n = Mm * T_pad;   // the code sums of Q(h) start at zero
+  if (fused) { a.x_f32 = x_dev; a.s_static = s_x; }
   fill_members(a, Mm, lo, hi);
   if (act == PIPE_ACT_GELU) {
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;

@@ -702,6 +702,21 @@ def test_decode_with_the_quantizer_inside_the_streaming_kernel(pipe, T):
             for m in range(len(split)):
                 assert_close_fp32(ym[m], np.asarray(refm[m]))
         g.free()
+    # the two-layer call: layer 1 takes the same one-launch path
+    for kind, act in [("gelu", pipe.PIPE_ACT_GELU), ("gated", pipe.PIPE_ACT_SILU_GATED)]:
+        w = wl.scaled(wl.C3 if kind == "gelu" else wl.C5, out_div=8, in_div=8, tokens=T)
+        split = list(w.split) if w.split else None
+        es = [pipe.pipe_expand(dev(wl.make_weight(w, l)), s.bits, s.K, s.gamma, s.group) for l, s in enumerate(w.layers)]
+        xm = dev(wl.make_input(w))
+        try:
+            ya = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split).cpu().numpy()
+            pipe.pipe_set_decode_fusion(False)
+            yb = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split).cpu().numpy()
+        finally:
+            pipe.pipe_set_decode_fusion(True)
+        assert np.array_equal(ya, yb)
+        for e in es:
+            e.free()
     # an all-zero input: scale 0, the output is the bias
     W = _w(750, 64, 256)
     g = pipe.pipe_expand(dev(W), 4, 2, 0.5, 16)
