@@ -9,7 +9,7 @@ from paper_2311_15806_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("T", [3, 7, 200])
+@pytest.mark.parametrize("T", [1, 7, 200])
 def test_forward_graph_replays(T):
     import paper_2311_15806_amd.binding as pipe
     w = wl.scaled(wl.C4, out_div=4, in_div=4)
@@ -83,11 +83,12 @@ def test_chain_graph_replays(T):
         g.free()
 
 
-@pytest.mark.parametrize("kind,T", [("gelu", 11), ("gelu", 300), ("gated", 11), ("gated", 300)])
+@pytest.mark.parametrize("kind,T", [("gelu", 1), ("gelu", 11), ("gelu", 300), ("gated", 1), ("gated", 11), ("gated", 300)])
 def test_mlp_graph_replays(kind, T):
     """The two-layer MLP call (quantizers, both contractions, hidden maxima raised in layer 1's
     epilogue and consumed by the hidden quantizer, slots cleared inside the kernels) captured once
-    and replayed with other inputs, for decode-sized and tiled batches."""
+    and replayed with other inputs, for a single token (layer 1 quantizes its input itself),
+    decode-sized and tiled batches."""
     import paper_2311_15806_amd.binding as pipe
     base = wl.C3 if kind == "gelu" else wl.C5
     w = wl.scaled(base, out_div=8, in_div=8, tokens=T)
