@@ -574,9 +574,15 @@ extern "C" int pipe_timing_read(double* total_ms, int* launches) {
 // Activation quantization of a [T, in] input into the buffers of `b`; small batches take the
 // single-launch path.
 // A single token: the streaming kernel quantizes it itself, one launch instead of two
-static bool fuse_decode_quant(const pipe_expansion* e, int T, const float* x_dev, bool small) {
+// (the kernel reads x while other workgroups already write results, so an output buffer that
+// overlaps x -- legal on the two-launch path, whose quantizer has consumed x by then -- keeps that path)
+static bool fuse_decode_quant(const pipe_expansion* e, int T, const float* x_dev, bool small,
+                              const float* out_dev, size_t out_floats) {
+  const uintptr_t x0 = reinterpret_cast<uintptr_t>(x_dev), x1 = x0 + (size_t)T * e->in * sizeof(float);
+  const uintptr_t o0 = reinterpret_cast<uintptr_t>(out_dev), o1 = o0 + out_floats * sizeof(float);
+  const bool apart = x1 <= o0 || o1 <= x0;
   return small && g_decode_fusion && T <= PIPE_FUSED_QUANT_MAX_T && e->in_pad <= PIPE_FUSED_QUANT_MAX_IN &&
-         e->in % 4 == 0 && (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0 && e->bin_cap == 4;
+         e->in % 4 == 0 && (x0 & 15) == 0 && e->bin_cap == 4 && apart;
 }
 
 static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s_x, const ActBuffers& b, bool small,
@@ -631,7 +637,7 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  const bool fused = fuse_decode_quant(e, T, x_dev, small);
+  const bool fused = fuse_decode_quant(e, T, x_dev, small, y_dev, (size_t)(reduce_members ? 1 : Mm) * T * e->out);
   if (!fused) {
     rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
     if (rc) return rc;
@@ -956,7 +962,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   uint32_t* amax_h = b.amax + 16;
   float* scale_h = b.scale + 16;
 
-  const bool fused = fuse_decode_quant(l1, T, x_dev, small);
+  const bool fused = fuse_decode_quant(l1, T, x_dev, small, h, (size_t)Mm * T * H);
   if (!fused) {
     rc = quantize_input(x_dev, T, l1->in, l1->in_pad, s_x, b, small, nullptr, b.scale, st);
     if (rc) return rc;

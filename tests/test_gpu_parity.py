@@ -717,6 +717,15 @@ def test_decode_with_the_quantizer_inside_the_streaming_kernel(pipe, T):
         assert np.array_equal(ya, yb)
         for e in es:
             e.free()
+    # an output buffer that IS the input (square layer): the two-launch path, whose quantizer has
+    # consumed x before anything is written, serves it
+    W = _w(751, 256, 256)
+    g = pipe.pipe_expand(dev(W), 4, 3, 0.5, 16)
+    xs = dev(_x(752 + T, T, 256))
+    want = pipe.pipe_forward(g, xs).clone()
+    pipe.pipe_forward(g, xs, out=xs)
+    assert torch.equal(xs, want)
+    g.free()
     # an all-zero input: scale 0, the output is the bias
     W = _w(750, 64, 256)
     g = pipe.pipe_expand(dev(W), 4, 2, 0.5, 16)
