@@ -356,13 +356,14 @@ int pipe_set_token_tile(int tokens);
  * do not depend on the setting.  Returns PIPE_EINVAL outside 0..8.                */
 int pipe_set_stream_split(int workgroups_per_bin);
 
-/* A single token (pipe_forward, and layer 1 of pipe_mlp_forward, on a layer of at most 8192 input features, a multiple
- * of 4, 16-byte aligned input): by default the weight-streaming kernel quantizes the
+/* A single token (pipe_forward, and layer 1 of pipe_mlp_forward, on a layer of at
+ * most 8192 input features, a multiple of 4, 16-byte aligned input): by default the weight-streaming kernel quantizes the
  * input itself -- every workgroup reduces max|x| and rounds the few KiB of activations
  * with the quantizer's own arithmetic -- so the step is one launch instead of two.
  * (From two tokens on the repeated work costs more than the launch it saves.)
- * An output buffer that overlaps the input keeps the two-launch path.  0 switches this off (tuning and tests), 1 on (default).  Results do
- * not depend on the setting.  Returns PIPE_EINVAL for other values.                  */
+ * An output buffer that overlaps the input keeps the two-launch path.  0 switches
+ * this off (tuning and tests), 1 on (default).  Results do not depend on the
+ * setting.  Returns PIPE_EINVAL for other values.                                    */
 int pipe_set_decode_fusion(int on);
 
 /* Kernel timing for benchmarks.  While enabled, every forward call brackets its
