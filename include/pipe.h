@@ -24,9 +24,20 @@
  *   - Every function returns PIPE_OK (0) or a negative error code and never
  *     throws or aborts.  On an error detected before launch (bad argument,
  *     shape or split) no output is written.
- *   - The library keeps a per-process device workspace (quantized activations,
- *     hidden activations of the MLP call) that grows on demand; calls that share
- *     a device must not overlap in time (one stream at a time).
+ *   - Scratch (quantized activations, code sums, scales, hidden activations) lives in a
+ *     library-owned workspace per (device, stream): calls on different streams use disjoint
+ *     scratch and may overlap in time, calls on one stream are ordered by the stream.  Two
+ *     calls that use the SAME expansion must not overlap in time (its tile schedules are
+ *     built on first use and the weight-streaming kernel's split bins exchange partial sums
+ *     through a buffer the expansion owns).  A workspace grows on demand; a block that has
+ *     been handed out is never freed before the process ends, so graphs captured earlier
+ *     keep valid pointers.  Growing allocates: a forward call on a stream that is being
+ *     captured never allocates or synchronizes; if it would have to (first use of that
+ *     stream, a larger batch, a new grouping of the orders) it returns PIPE_ENOTREADY and
+ *     launches nothing.  pipe_prepare / pipe_prepare_mlp / pipe_prepare_chain do that work
+ *     ahead of time, so that the first forward call on a stream may already be captured.
+ *   - The tuning switches (pipe_set_*) are process-wide and read on the host at call time;
+ *     change them only while no other thread is inside a forward call.
  *   - bits: 2..8; codes lie in +-(2^(bits-1)-1): 8 int8, 4 int4 (codes in [-7,7]), 2 ternary
  *     (codes in {-1,0,1}).  Codes are stored 2, 4 or 8 bits wide: 3-bit codes occupy 4-bit fields
  *     and 5..7-bit codes bytes (the arithmetic is the same; only the packed size is not minimal).
@@ -48,7 +59,10 @@ enum {
   PIPE_ESHAPE = -2,  /* out % group != 0, group % 16 != 0, sizes <= 0, overflow   */
   PIPE_ENOMEM = -3,  /* device or host allocation failed                         */
   PIPE_EDEVICE = -4, /* a HIP call failed (see pipe_last_device_error)           */
-  PIPE_ESPLIT = -5   /* split entries not positive or not summing to K            */
+  PIPE_ESPLIT = -5,  /* split entries not positive or not summing to K            */
+  PIPE_ENOTREADY = -6 /* the call would have to allocate or synchronize where it may not
+                         (its stream is being captured into a graph): run the matching
+                         pipe_prepare* call first.  Nothing was launched.                */
 };
 
 enum { PIPE_ACT_NONE = 0, PIPE_ACT_GELU = 1, PIPE_ACT_SILU_GATED = 2, PIPE_ACT_RELU = 3 };
@@ -144,6 +158,19 @@ int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, float s_x,
                  const int* split, int M, const float* bias_dev, int reduce_members,
                  float* y_dev, void* stream);
 
+/* Preparation for stream capture and for first calls that must not block: does everything
+ * pipe_forward(e, x, T <= T_max, ..., split, M, ..., stream) would otherwise do on first
+ * use -- builds the tile schedule of this grouping of the orders and sizes the scratch of
+ * `stream` for T_max tokens -- and launches nothing.  Allocates and may synchronize: call it
+ * outside capture.  Afterwards pipe_forward with the same expansion, grouping and stream and
+ * any T <= T_max neither allocates nor synchronizes.  pipe_prepare_mlp and pipe_prepare_chain
+ * are the same for pipe_mlp_forward and for pipe_chain_forward / pipe_chain_forward_conv
+ * (arguments as in those calls; a chain over T tokens is the grid T x 1 x 1).
+ * Errors: those of the forward call for the same arguments.                               */
+int pipe_prepare(const pipe_expansion* e, const int* split, int M, int T_max, void* stream);
+int pipe_prepare_mlp(const pipe_expansion* l1, const pipe_expansion* l2, int act, const int* split, int M,
+                     int T_max, void* stream);
+
 /* Debug twin of pipe_forward: exports the integer state for bit-exact checks.
  *   acc_dev     [K, T, out] int32, rows pruned at order k are 0 (may be NULL)
  *   qx_dev      [T, in] int8 Q(x), row-major                   (may be NULL)
@@ -192,6 +219,18 @@ int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int 
                         int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
                         const int* split, int M, const float* bias_dev,
                         int reduce_members, float* y_dev, void* stream);
+
+/* Debug twin of pipe_forward_conv2d (App. B, Eq. (define_dre) on the contraction of App. H):
+ * exports the integer state of the convolution layer for bit-exact checks.
+ *   acc_dev     [K, N*Ho*Wo, out] int32: acc_k[t,o] = sum over (c, r, s) of Q(x)[n, c, ho*stride+r-pad,
+ *               wo*stride+s-pad] * q_k[o, (c, r, s)], taps outside the image contributing 0; rows pruned
+ *               at order k are 0.  Required (PIPE_EINVAL if NULL).
+ *   qx_dev      int8 Q(x) in the layout of x_dev ([N,C,H,W] or [N,H,W,C])        (may be NULL)
+ *   s_x_out_dev one float: the activation scale used                           (may be NULL)
+ * Geometry arguments, s_x and errors as pipe_forward_conv2d.  All pointers DEVICE, caller-owned. */
+int pipe_forward_conv2d_acc(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W,
+                            int kh, int kw, int stride, int pad, int nhwc, float s_x, int32_t* acc_dev,
+                            int8_t* qx_dev, float* s_x_out_dev, void* stream);
 
 /* Expanded depthwise convolution (App. H: a convolution whose filters see one input
  * channel each; the separable blocks of MobileNet / EfficientNet).  The expansion was
@@ -273,6 +312,9 @@ int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev
 int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, const float* x_dev,
                             int N, int H, int W, float s_x, const int* split, int M,
                             float* const* acts_dev, float* y_dev, void* stream);
+
+int pipe_prepare_chain(const pipe_chain_layer* layers, int L, int N, int H, int W, const int* split, int M,
+                       void* stream);
 
 /* Bit-width a of the activation quantizer of every forward entry point from now on
  * (Sec. 4 compares W4/A4, W4/A6, W8/A8): Q(x) = clamp(rint(x / s_x), +-(2^(a-1)-1)),

@@ -54,10 +54,14 @@ def _load():
     lib.pipe_forward_acc_asymmetric.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp]
     lib.pipe_forward_conv2d_asymmetric.argtypes = [vp, vp] + [ci] * 9 + [pi, ci, vp, vp, vp]
     lib.pipe_forward_conv2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
+    lib.pipe_forward_conv2d_acc.argtypes = [vp, vp] + [ci] * 9 + [cf, vp, vp, vp, vp]
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
+    lib.pipe_prepare.argtypes = [vp, pi, ci, ci, vp]
+    lib.pipe_prepare_mlp.argtypes = [vp, vp, ci, pi, ci, ci, vp]
+    lib.pipe_prepare_chain.argtypes = [vp, ci, ci, ci, ci, pi, ci, vp]
     lib.pipe_set_kernel.argtypes = [ci]
     lib.pipe_fold_batchnorm.argtypes = [vp] * 6 + [cf, ci, ci, vp, vp, vp]
     lib.pipe_spectral_norm.argtypes = [vp, ci, ci, ci, C.POINTER(cf), vp]
@@ -311,6 +315,25 @@ def pipe_forward_conv2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride:
     return y
 
 
+def pipe_forward_conv2d_acc(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
+                            nhwc: bool = False, s_x: float = 0.0):
+    """(acc int32 [K, N*Ho*Wo, out], Q(x) int8 shaped like x, s_x fp32 [1]) of the convolution layer."""
+    if x.dim() != 4:
+        raise ValueError("x must be 4-D")
+    if nhwc:
+        N, H, W, Cc = x.shape
+    else:
+        N, Cc, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    acc = torch.empty((e.K, N * Ho * Wo, e.out_features), dtype=torch.int32, device=x.device)
+    qx = torch.empty(tuple(x.shape), dtype=torch.int8, device=x.device)
+    sx = torch.zeros(1, dtype=torch.float32, device=x.device)
+    _check(_lib.pipe_forward_conv2d_acc(e.handle, _ptr(x, torch.float32), N, Cc, H, W, kh, kw, stride, pad,
+                                        1 if nhwc else 0, float(s_x), _ptr(acc), _ptr(qx), _ptr(sx), _stream()),
+           "pipe_forward_conv2d_acc")
+    return acc, qx, sx
+
+
 def pipe_forward_depthwise2d(e: Expansion, x: torch.Tensor, kh: int, kw: int, stride: int, pad: int,
                              nhwc: bool = False, s_x: float = 0.0, split=None, bias=None,
                              reduce_members: bool = True) -> torch.Tensor:
@@ -407,6 +430,24 @@ def pipe_chain_forward_conv(layers, x: torch.Tensor, s_x: float = 0.0, split=Non
     _check(_lib.pipe_chain_forward_conv(arr_l, L, _ptr(x, torch.float32), N, H, W, float(s_x), arr, m, acts_arr,
                                         _ptr(y), _stream()), "pipe_chain_forward_conv")
     return (y, acts) if return_acts else y
+
+
+def pipe_prepare(e: Expansion, T_max: int, split=None) -> None:
+    """Everything pipe_forward(e, x[T <= T_max], split=split) on the current stream would do on first use."""
+    arr, m = _split(split)
+    _check(_lib.pipe_prepare(e.handle, arr, m, int(T_max), _stream()), "pipe_prepare")
+
+
+def pipe_prepare_mlp(l1: Expansion, l2: Expansion, act: int, T_max: int, split=None) -> None:
+    arr, m = _split(split)
+    _check(_lib.pipe_prepare_mlp(l1.handle, l2.handle, int(act), arr, m, int(T_max), _stream()), "pipe_prepare_mlp")
+
+
+def pipe_prepare_chain(layers, N: int, H: int = 1, W: int = 1, split=None) -> None:
+    """layers as for pipe_chain_forward / pipe_chain_forward_conv; a chain over T tokens is the grid T x 1 x 1."""
+    arr_l = _chain_layers(layers)
+    arr, m = _split(split)
+    _check(_lib.pipe_prepare_chain(arr_l, len(layers), int(N), int(H), int(W), arr, m, _stream()), "pipe_prepare_chain")
 
 
 def pipe_spectral_norm(W: torch.Tensor, iters: int = 50) -> float:

@@ -5,8 +5,11 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <string>
+#include <utility>
 
 #include "pipe_internal.h"
 
@@ -27,30 +30,87 @@ extern "C" const char* pipe_strerror(int code) {
     case PIPE_ENOMEM: return "out of memory";
     case PIPE_EDEVICE: return "HIP call failed";
     case PIPE_ESPLIT: return "ensemble split must be positive and sum to K";
+    case PIPE_ENOTREADY: return "the call would have to allocate or synchronize while its stream is being captured: run pipe_prepare first";
     default: return "unknown error";
   }
 }
 
 // ------------------------------------------------------------------ workspace
-static PipeWorkspace g_ws[WS_SLOTS];
+// One set of scratch blocks per (device, stream).  An entry point opens a CallScope on its
+// stream; pipe_ws_get then serves that stream's set.  Blocks only grow, and a block that was
+// handed out is never freed (a graph captured earlier may still hold its address): it is
+// retired until the process ends.  Growth at least doubles a block, so retired blocks sum to
+// less than the live one.
+struct WsSet {
+  PipeWorkspace slot[WS_SLOTS];
+  bool amax_h_dirty = false;   // the members' max|h| slots hold a value no kernel will clear
+};
+static std::mutex g_ws_mu;
+static std::map<std::pair<int, hipStream_t>, WsSet*> g_ws_sets;
+static std::vector<void*> g_ws_retired;
+static thread_local WsSet* t_ws = nullptr;
+static thread_local bool t_capturing = false;
+static thread_local bool t_dry = false;
+static thread_local int t_ws_err = PIPE_ENOMEM;
+
+bool pipe_dry_run() { return t_dry; }
+bool pipe_capturing() { return t_capturing; }
+int pipe_ws_error() { return t_ws_err; }
+
+static WsSet* ws_set_of(hipStream_t st) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  std::lock_guard<std::mutex> lk(g_ws_mu);
+  WsSet*& w = g_ws_sets[std::make_pair(dev, st)];
+  if (w == nullptr) w = new WsSet();
+  return w;
+}
+
+namespace {
+struct CallScope {
+  WsSet* prev_ws;
+  bool prev_cap;
+  explicit CallScope(void* stream) : prev_ws(t_ws), prev_cap(t_capturing) {
+    hipStream_t st = (hipStream_t)stream;
+    t_ws = ws_set_of(st);
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+      (void)hipGetLastError();   // e.g. the legacy null stream while another stream captures
+      cs = hipStreamCaptureStatusNone;
+    }
+    t_capturing = cs != hipStreamCaptureStatusNone;
+  }
+  ~CallScope() { t_ws = prev_ws; t_capturing = prev_cap; }
+};
+struct DryScope {
+  bool prev;
+  DryScope() : prev(t_dry) { t_dry = true; }
+  ~DryScope() { t_dry = prev; }
+};
+}  // namespace
 
 void* pipe_ws_get(int slot, size_t bytes) {
-  PipeWorkspace& w = g_ws[slot];
+  if (t_ws == nullptr) t_ws = ws_set_of(nullptr);   // calls outside a scope (diagnostics): the null stream's set
+  PipeWorkspace& w = t_ws->slot[slot];
   if (bytes == 0) bytes = 256;
   if (w.bytes >= bytes) return w.ptr;
-  if (w.ptr) {
-    if (hipDeviceSynchronize() != hipSuccess) return nullptr;
-    (void)hipFree(w.ptr);
-    w.ptr = nullptr;
-    w.bytes = 0;
-  }
-  const size_t want = (size_t)round_up64((int64_t)bytes, 1 << 20);
-  hipError_t e = hipMalloc(&w.ptr, want);
-  if (e != hipSuccess) {
-    pipe_note_hip_error(e, "hipMalloc(workspace)");
-    w.ptr = nullptr;
+  if (t_capturing) {
+    t_ws_err = PIPE_ENOTREADY;
     return nullptr;
   }
+  const size_t want = (size_t)round_up64((int64_t)std::max(bytes, 2 * w.bytes), 1 << 20);
+  void* fresh = nullptr;
+  hipError_t e = hipMalloc(&fresh, want);
+  if (e != hipSuccess) {
+    pipe_note_hip_error(e, "hipMalloc(workspace)");
+    t_ws_err = PIPE_ENOMEM;
+    return nullptr;
+  }
+  if (w.ptr) {
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    g_ws_retired.push_back(w.ptr);
+  }
+  w.ptr = fresh;
   w.bytes = want;
   return w.ptr;
 }
@@ -438,6 +498,7 @@ const PassTables* pipe_get_tables(const pipe_expansion* ce, const GemmArgs& a, i
     if (t.kind == kind && t.M == M && t.member_nib == nib) return &t;
   *rc_out = PIPE_OK;
   if (kind == 1 && n_rb % 2 != 0) { *rc_out = PIPE_ESHAPE; return nullptr; }
+  if (pipe_capturing()) { *rc_out = PIPE_ENOTREADY; return nullptr; }   // building allocates and copies synchronously
 
   // per row block and member: the positions of its stored orders, ascending
   std::vector<std::vector<int32_t>> list((size_t)n_rb * M);
@@ -536,17 +597,34 @@ static int get_act_buffers(int T, int in_pad, bool small, ActBuffers* b) {
   b->T_pad = (int)round_up64(T, small ? 16 : TOK_TILE);
   b->qx = (uint8_t*)pipe_ws_get(WS_QX, (size_t)b->T_pad * in_pad);
   b->rowsum = (int32_t*)pipe_ws_get(WS_ROWSUM, (size_t)b->T_pad * 4);
-  const bool fresh = g_ws[WS_SCAL].ptr == nullptr;
+  const bool fresh = t_ws == nullptr || t_ws->slot[WS_SCAL].ptr == nullptr;
   uint8_t* sc = (uint8_t*)pipe_ws_get(WS_SCAL, 4096);
-  if (!b->qx || !b->rowsum || !sc) return PIPE_ENOMEM;
-  if (fresh) PIPE_HIP(hipMemset(sc, 0, 4096));
+  if (!b->qx || !b->rowsum || !sc) return pipe_ws_error();
+  if (fresh) PIPE_HIP(hipMemset(sc, 0, 4096));   // never under capture: a fresh block is refused there
   b->amax = (uint32_t*)sc;
   b->scale = (float*)(sc + 1024);
   return PIPE_OK;
 }
 
+// The tile schedule the tiled kernel will need, fetched before anything is launched (so a failure
+// leaves no reduction slot raised).
+static int ensure_tables(const pipe_expansion* e, int M, const int* lo, const int* hi, int kind) {
+  GemmArgs a{};
+  a.e = e;
+  a.M = M;
+  for (int m = 0; m < M; ++m) { a.member_lo[m] = lo[m]; a.member_hi[m] = hi[m]; }
+  int rc = PIPE_OK;
+  return pipe_get_tables(e, a, kind, &rc) != nullptr ? PIPE_OK : rc;
+}
+
+// An error after the max|x| reduction was launched: the slot is raised and the contraction kernel
+// that would clear it will not run.  Clears it so that the next dynamic scale starts from zero.
+static int fail_after_reduction(int rc, const ActBuffers& b, hipStream_t st) {
+  (void)launch_zero_u32(b.amax, 1, st);
+  return rc;
+}
+
 // ------------------------------------------------------------------ kernel timing
-static bool g_amax_h_dirty = false;   // the members' max|h| slots hold a value no kernel will clear
 static bool g_timing_on = false;
 static std::vector<hipEvent_t> g_events;   // pairs: start, stop
 static size_t g_events_used = 0;
@@ -601,6 +679,7 @@ static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s
 }
 
 static int run_gemm(const GemmArgs& a0, bool small, hipStream_t st) {
+  if (pipe_dry_run()) return PIPE_OK;
   GemmArgs a = a0;
   const bool timed = g_timing_on && g_events_used / 2 < MAX_TIMED;
   if (timed) {
@@ -633,10 +712,12 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  if (!small && (rc = ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
   const bool fused = fuse_decode_quant(e, T, x_dev, small, y_dev, (size_t)(reduce_members ? 1 : Mm) * T * e->out);
   if (!fused) {
     rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
@@ -648,7 +729,22 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
   a.y = y_dev; a.acc_out = nullptr; a.amax_out = nullptr; a.zero_after = b.amax;
   if (fused) { a.x_f32 = x_dev; a.s_static = s_x; }
   fill_members(a, Mm, lo, hi);
-  return run_gemm(a, small, st);
+  rc = run_gemm(a, small, st);
+  return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
+}
+
+extern "C" int pipe_prepare(const pipe_expansion* e, const int* split, int M, int T_max, void* stream) {
+  if (!e || T_max < 1) return PIPE_EINVAL;
+  DryScope dry;
+  // the addresses are never dereferenced: nothing is launched in a dry run.  Two passes: the
+  // largest batch sizes the scratch, and whichever kernel serves it gets its schedule; batches
+  // up to T_max may also take the tiled kernel's path, whose schedule the second pass builds.
+  const float* fake_x = reinterpret_cast<const float*>(uintptr_t(256));
+  float* fake_y = reinterpret_cast<float*>(uintptr_t(512));
+  int rc = pipe_forward(e, fake_x, T_max, 1.f, split, M, nullptr, 1, fake_y, stream);
+  if (rc == PIPE_OK && T_max > PIPE_STREAM_MAX_T + 1)
+    rc = pipe_forward(e, fake_x, PIPE_STREAM_MAX_T + 1, 1.f, split, M, nullptr, 1, fake_y, stream);
+  return rc;
 }
 
 extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
@@ -657,10 +753,13 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   if (T == 0) return PIPE_OK;
   if (!x_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   const bool small = use_stream_kernel(e, T, acc_dev != nullptr);
   ActBuffers b;
   int rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  int lo = 0, hi = e->K - 1;
+  if (acc_dev && !small && (rc = ensure_tables(e, 1, &lo, &hi, 2)) != PIPE_OK) return rc;
   rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, qx_dev, b.scale, st);
   if (rc) return rc;
   if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
@@ -669,9 +768,9 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
   a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev; a.zero_after = b.amax;
-  int lo = 0, hi = e->K - 1;
   fill_members(a, 1, &lo, &hi);
-  return run_gemm(a, small, st);
+  rc = run_gemm(a, small, st);
+  return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
 }
 
 // ------------------------------------------------------------------ asymmetric activation codes
@@ -680,6 +779,7 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
 static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
   pipe_expansion* e = const_cast<pipe_expansion*>(ce);
   if (e->asym_C_dev) return PIPE_OK;
+  if (pipe_capturing()) return PIPE_ENOTREADY;   // allocates and synchronizes: run the call once outside capture
   const size_t out = (size_t)e->out;
   int32_t* wsum = nullptr;
   float* C = nullptr;
@@ -752,12 +852,14 @@ extern "C" int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_d
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   rc = asym_prepare(e, st);
   if (rc) return rc;
   const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  if (!small && (rc = ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
   uint32_t* slots = nullptr;
   int32_t* dz = nullptr;
   rc = asym_quantize(e, x_dev, T, b, nullptr, &slots, &dz, st);
@@ -791,18 +893,20 @@ extern "C" int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const flo
   const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
   if ((int64_t)((1 << act_bits) - 1) * ((1 << (e->qbits - 1)) - 1) * e->in >= ((int64_t)1 << 31)) return PIPE_ESHAPE;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   rc = asym_prepare(e, st);
   if (rc) return rc;
   const bool small = use_stream_kernel(e, T);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  if (!small && (rc = ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)N * C * H * W);   // the input's codes, in its own layout
+  if (!q8) return pipe_ws_error();
   uint32_t* slots = b.amax + 64;
   int32_t* dz = reinterpret_cast<int32_t*>(b.amax + 66);
   rc = launch_minmax(x_dev, (int64_t)N * C * H * W, slots, st);
   if (rc) return rc;
-  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)N * C * H * W);   // the input's codes, in its own layout
-  if (!q8) return PIPE_ENOMEM;
   rc = launch_quantize_im2col_asym(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, slots,
                                    act_bits, q8, b.qx, b.rowsum, b.scale, dz, st);
   if (rc) return rc;
@@ -821,12 +925,15 @@ extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float*
   if (T == 0) return PIPE_OK;
   if (!x_dev || !acc_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   int rc = asym_prepare(e, st);
   if (rc) return rc;
   const bool small = use_stream_kernel(e, T, true);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  int klo = 0, khi = e->K - 1;
+  if (!small && (rc = ensure_tables(e, 1, &klo, &khi, 2)) != PIPE_OK) return rc;
   uint32_t* slots = nullptr;
   int32_t* dz = nullptr;
   rc = asym_quantize(e, x_dev, T, b, qx_dev, &slots, &dz, st);
@@ -837,7 +944,6 @@ extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float*
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
   a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev; a.zero_after = b.amax;
-  int klo = 0, khi = e->K - 1;
   fill_members(a, 1, &klo, &khi);
   rc = run_gemm(a, small, st);
   if (rc) return rc;
@@ -859,10 +965,11 @@ extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float*
   return PIPE_OK;
 }
 
-extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,
-                                   int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
-                                   const int* split, int M, const float* bias_dev,
-                                   int reduce_members, float* y_dev, void* stream) {
+// The convolution layer; with acc_dev set, the integer export (accumulators per order, the input's codes in the
+// input's own layout, the scale) instead of the fp32 output.
+static int conv2d_impl(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W, int kh, int kw, int stride,
+                       int pad, int nhwc, float s_x, const int* split, int M, const float* bias_dev, int reduce_members,
+                       float* y_dev, int32_t* acc_dev, int8_t* qx_dev, float* s_x_out_dev, void* stream) {
   if (!e) return PIPE_EINVAL;
   if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
   if ((int64_t)C * kh * kw != e->in) return PIPE_ESHAPE;
@@ -875,26 +982,61 @@ extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, 
   int rc = parse_split(e->K, split, M, lo, hi, &Mm);
   if (rc) return rc;
   if (T == 0) return PIPE_OK;
-  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  const bool export_acc = acc_dev != nullptr;
+  if (!x_dev || (!y_dev && !export_acc)) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  const bool small = use_stream_kernel(e, T);
+  CallScope scope(stream);
+  const bool small = use_stream_kernel(e, T, export_acc);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
+  const size_t n_in = (size_t)N * C * H * W;
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, n_in);   // the input's codes, in its own layout
+  if (!q8) return pipe_ws_error();
+  {
+    int klo = 0, khi = e->K - 1;
+    if (!small && (rc = export_acc ? ensure_tables(e, 1, &klo, &khi, 2) : ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  }
   if (!(s_x > 0.f)) {
-    rc = launch_absmax(x_dev, (int64_t)N * C * H * W, b.amax, nullptr, 0, st);
+    rc = launch_absmax(x_dev, (int64_t)n_in, b.amax, nullptr, 0, st);
     if (rc) return rc;
   }
-  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)N * C * H * W);   // the input's codes, in its own layout
-  if (!q8) return PIPE_ENOMEM;
   rc = launch_quantize_im2col(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, s_x,
                               b.amax, q8, b.qx, b.rowsum, b.scale, st);
   if (rc) return rc;
   GemmArgs a{};
   a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum;
-  a.s_x = b.scale; a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev; a.zero_after = b.amax;
-  fill_members(a, Mm, lo, hi);
-  return run_gemm(a, small, st);
+  a.s_x = b.scale; a.zero_after = b.amax;
+  if (export_acc) {
+    if (pipe_dry_run()) return PIPE_OK;
+    if (qx_dev) PIPE_HIP(hipMemcpyAsync(qx_dev, q8, n_in, hipMemcpyDeviceToDevice, st));
+    if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
+    PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
+    a.reduce = 1; a.acc_out = acc_dev;
+    int klo = 0, khi = e->K - 1;
+    fill_members(a, 1, &klo, &khi);
+  } else {
+    a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev;
+    fill_members(a, Mm, lo, hi);
+  }
+  rc = run_gemm(a, small, st);
+  return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
+}
+
+extern "C" int pipe_forward_conv2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H,
+                                   int W, int kh, int kw, int stride, int pad, int nhwc, float s_x,
+                                   const int* split, int M, const float* bias_dev,
+                                   int reduce_members, float* y_dev, void* stream) {
+  return conv2d_impl(e, x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, s_x, split, M, bias_dev, reduce_members, y_dev,
+                     nullptr, nullptr, nullptr, stream);
+}
+
+extern "C" int pipe_forward_conv2d_acc(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W, int kh,
+                                       int kw, int stride, int pad, int nhwc, float s_x, int32_t* acc_dev,
+                                       int8_t* qx_dev, float* s_x_out_dev, void* stream) {
+  if (!acc_dev) return PIPE_EINVAL;
+  return conv2d_impl(e, x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, s_x, nullptr, 0, nullptr, 1, nullptr, acc_dev,
+                     qx_dev, s_x_out_dev, stream);
 }
 
 extern "C" int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_dev, int N, int C, int H, int W,
@@ -912,18 +1054,19 @@ extern "C" int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_
   if (N == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   rc = pipe_depthwise_prepare(const_cast<pipe_expansion*>(e), st);
   if (rc) return rc;
   ActBuffers b;
   rc = get_act_buffers(16, IN_PAD, true, &b);   // only the scale and max slots are used
   if (rc) return rc;
   const int64_t n = (int64_t)N * C * H * W;
+  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)n);
+  if (!q8) return pipe_ws_error();
   if (!(s_x > 0.f)) {
     rc = launch_absmax(x_dev, n, b.amax, nullptr, 0, st);
     if (rc) return rc;
   }
-  int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, (size_t)n);
-  if (!q8) return PIPE_ENOMEM;
   // the codes of the input, channels last whatever the input's layout
   if (nhwc) rc = launch_quantize_elem(x_dev, n, s_x, b.amax, q8, b.scale, st);
   else rc = launch_quantize_to_nhwc(x_dev, N, C, H * W, s_x, b.amax, g_act_qmax_host, q8, b.scale, st);
@@ -949,6 +1092,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   const bool small = use_stream_kernel(l1, T);   // both layers have the same K
   ActBuffers b;
   rc = get_act_buffers(T, l1->in_pad, small, &b);
@@ -958,9 +1102,22 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   float* h = h_dev ? h_dev : (float*)pipe_ws_get(WS_H, (size_t)Mm * T * H * sizeof(float));
   uint8_t* qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * l2->in_pad);
   int32_t* rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
-  if (!h || !qh || !rowsum_h) return PIPE_ENOMEM;
+  if (!h || !qh || !rowsum_h) return pipe_ws_error();
   uint32_t* amax_h = b.amax + 16;
   float* scale_h = b.scale + 16;
+  // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly; otherwise
+  // the gated layer's raw outputs pass through a buffer and an element-wise launch
+  const bool paired = act == PIPE_ACT_SILU_GATED && !small && l1->n_rb % 2 == 0;
+  float* y1 = nullptr;
+  if (act == PIPE_ACT_SILU_GATED && !paired) {
+    y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
+    if (!y1) return pipe_ws_error();
+  }
+  if (!small) {
+    if ((rc = ensure_tables(l1, Mm, lo, hi, paired ? 1 : 0)) != PIPE_OK) return rc;
+    if ((rc = ensure_tables(l2, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  }
+  if (pipe_dry_run()) return PIPE_OK;
 
   const bool fused = fuse_decode_quant(l1, T, x_dev, small, h, (size_t)Mm * T * H);
   if (!fused) {
@@ -970,11 +1127,11 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   // The members' max|h| slots are zero on entry: cleared when the workspace is allocated and,
   // after each use, by the layer-2 kernel that follows their last reader.  A call that failed
   // between the two leaves them dirty; then they are cleared by a launch of their own.
-  if (g_amax_h_dirty) {
+  if (t_ws->amax_h_dirty) {
     rc = launch_zero_u32(amax_h, 2 * PIPE_MAX_K, st);
     if (rc) return rc;
   }
-  g_amax_h_dirty = true;
+  t_ws->amax_h_dirty = true;
 
   // layer 1: every member reads the same Q(x); outputs stay separate
   GemmArgs a{};
@@ -986,15 +1143,12 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   if (act == PIPE_ACT_GELU) {
     a.act = PIPE_ACT_GELU; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);
-    if (rc) return rc;
-  } else if (!small && l1->n_rb % 2 == 0) {
-    // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly
+    if (rc) return fail_after_reduction(rc, b, st);
+  } else if (paired) {
     a.act = PIPE_ACT_SILU_GATED; a.y = h; a.amax_out = amax_h;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
   } else {
-    float* y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
-    if (!y1) return PIPE_ENOMEM;
     a.act = 0; a.y = y1; a.amax_out = nullptr;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
@@ -1022,7 +1176,19 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   a2.zero_after = amax_h; a2.zero_n = Mm;
   fill_members(a2, Mm, lo, hi);
   rc = run_gemm(a2, small, st);
-  if (rc == PIPE_OK) g_amax_h_dirty = false;
+  if (rc == PIPE_OK) t_ws->amax_h_dirty = false;
+  return rc;
+}
+
+extern "C" int pipe_prepare_mlp(const pipe_expansion* l1, const pipe_expansion* l2, int act, const int* split, int M,
+                                int T_max, void* stream) {
+  if (!l1 || !l2 || T_max < 1) return PIPE_EINVAL;
+  DryScope dry;
+  const float* fake_x = reinterpret_cast<const float*>(uintptr_t(256));
+  float* fake_y = reinterpret_cast<float*>(uintptr_t(512));
+  int rc = pipe_mlp_forward(l1, l2, act, fake_x, T_max, 1.f, split, M, nullptr, nullptr, nullptr, fake_y, stream);
+  if (rc == PIPE_OK && T_max > PIPE_STREAM_MAX_T + 1)
+    rc = pipe_mlp_forward(l1, l2, act, fake_x, PIPE_STREAM_MAX_T + 1, 1.f, split, M, nullptr, nullptr, nullptr, fake_y, stream);
   return rc;
 }
 
@@ -1065,6 +1231,7 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   if (N == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
   // per layer: the contraction's token count is the layer's output grid
   std::vector<char> small(L);
   std::vector<int> Tpad(L);
@@ -1108,7 +1275,7 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
     float* pool = nullptr;
     if (!busy_until.empty()) {
       pool = (float*)pipe_ws_get(WS_CHAIN, busy_until.size() * slab_floats * sizeof(float));
-      if (!pool) return PIPE_ENOMEM;
+      if (!pool) return pipe_ws_error();
     }
     for (int l = 0; l + 1 < L; ++l) act[l] = (acts_dev && acts_dev[l]) ? acts_dev[l] : pool + (size_t)slab[l] * slab_floats;
   }
@@ -1118,11 +1285,11 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   if (L > 1) {
     qh = (uint8_t*)pipe_ws_get(WS_QH, qh_bytes);
     rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)2 * Mm * T_pad_max * 4);
-    if (!qh || !rowsum_h) return PIPE_ENOMEM;
+    if (!qh || !rowsum_h) return pipe_ws_error();
   }
   if (q8_bytes) {
     q8 = (int8_t*)pipe_ws_get(WS_Q8X, q8_bytes);
-    if (!q8) return PIPE_ENOMEM;
+    if (!q8) return pipe_ws_error();
   }
   // code sums of the members' quantized inputs, two buffers used in turn: the quantizer of layer l
   // adds into buffer l & 1, which the contraction of layer l-1 cleared (it reads the other one)
@@ -1131,11 +1298,14 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   // quantizer of layer l+1 reads it, and the contraction of layer l+1 clears it again
   uint32_t* amax_set[2] = {b.amax + 16, b.amax + 16 + PIPE_MAX_K};
   float* scale_h = b.scale + 16;
-  if (g_amax_h_dirty) {
+  for (int l = 0; l < L; ++l)
+    if (!small[l] && (rc = ensure_tables(layers[l].e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  if (pipe_dry_run()) return PIPE_OK;
+  if (t_ws->amax_h_dirty) {
     rc = launch_zero_u32(amax_set[0], 2 * PIPE_MAX_K, st);
     if (rc) return rc;
   }
-  g_amax_h_dirty = true;
+  t_ws->amax_h_dirty = true;
 
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
@@ -1209,7 +1379,7 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
     if (rc) return rc;
   }
   // the last layer cleared the set it read; the other set was cleared one layer earlier
-  g_amax_h_dirty = false;
+  t_ws->amax_h_dirty = false;
   return PIPE_OK;
 }
 
@@ -1225,4 +1395,13 @@ extern "C" int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, co
                                        float s_x, const int* split, int M, float* const* acts_dev, float* y_dev,
                                        void* stream) {
   return chain_forward_grid(layers, L, x_dev, N, H, W, s_x, split, M, acts_dev, y_dev, stream);
+}
+
+extern "C" int pipe_prepare_chain(const pipe_chain_layer* layers, int L, int N, int H, int W, const int* split, int M,
+                                  void* stream) {
+  if (N < 1) return PIPE_EINVAL;
+  DryScope dry;
+  const float* fake_x = reinterpret_cast<const float*>(uintptr_t(256));
+  float* fake_y = reinterpret_cast<float*>(uintptr_t(512));
+  return chain_forward_grid(layers, L, fake_x, N, H, W, 1.f, split, M, nullptr, fake_y, stream);
 }

@@ -148,10 +148,10 @@ int pipe_depthwise_prepare(pipe_expansion* e, hipStream_t st) {
     const int rows = o.n_kept * e->group;
     if (rows == 0) continue;
     int8_t* tmp = (int8_t*)pipe_ws_get(WS_DIAG_CODES, (size_t)rows * e->in);
-    if (!tmp) return PIPE_ENOMEM;
+    if (!tmp) return pipe_ws_error();
     int rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, rows, e->in, e->in_pad, tmp, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(dense_order_kernel, dim3(rows), dim3(64), 0, st, tmp, e->scales_all_dev, o.pos_dev, o.gids_dev,
+    PIPE_KLAUNCH(dense_order_kernel, dim3(rows), dim3(64), 0, st, tmp, e->scales_all_dev, o.pos_dev, o.gids_dev,
                        e->group, e->in, e->out, e->dw_codes_dev + (size_t)k * e->out * e->in, e->dw_scales_dev + (size_t)k * e->out);
     PIPE_HIP(hipGetLastError());
   }
@@ -161,7 +161,7 @@ int pipe_depthwise_prepare(pipe_expansion* e, hipStream_t st) {
 
 int launch_quantize_to_nhwc(const float* x, int N, int C, int HW, float s_static, const uint32_t* amax_bits, float qmax,
                             int8_t* q8, float* scale_out, hipStream_t st) {
-  hipLaunchKernelGGL(quantize_to_nhwc_kernel, dim3(ceil_div(HW, 32), ceil_div(C, 32), N), dim3(256), 0, st, x, C, HW, s_static,
+  PIPE_KLAUNCH(quantize_to_nhwc_kernel, dim3(ceil_div(HW, 32), ceil_div(C, 32), N), dim3(256), 0, st, x, C, HW, s_static,
                      amax_bits, qmax, q8, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -179,10 +179,10 @@ int launch_depthwise(const pipe_expansion* e, const int8_t* q8, const float* s_x
   const long long total = (long long)N * Ho * Wo * (C / 4);
   if (total <= 0) return PIPE_OK;
   const dim3 grid((unsigned)((total + BLK - 1) / BLK));
-  if (kh == 3 && kw == 3) hipLaunchKernelGGL((depthwise_kernel<3, 3>), grid, dim3(BLK), 0, st, p);
-  else if (kh == 5 && kw == 5) hipLaunchKernelGGL((depthwise_kernel<5, 5>), grid, dim3(BLK), 0, st, p);
-  else if (kh == 7 && kw == 7) hipLaunchKernelGGL((depthwise_kernel<7, 7>), grid, dim3(BLK), 0, st, p);
-  else hipLaunchKernelGGL((depthwise_kernel<0, 0>), grid, dim3(BLK), 0, st, p);
+  if (kh == 3 && kw == 3) PIPE_KLAUNCH((depthwise_kernel<3, 3>), grid, dim3(BLK), 0, st, p);
+  else if (kh == 5 && kw == 5) PIPE_KLAUNCH((depthwise_kernel<5, 5>), grid, dim3(BLK), 0, st, p);
+  else if (kh == 7 && kw == 7) PIPE_KLAUNCH((depthwise_kernel<7, 7>), grid, dim3(BLK), 0, st, p);
+  else PIPE_KLAUNCH((depthwise_kernel<0, 0>), grid, dim3(BLK), 0, st, p);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

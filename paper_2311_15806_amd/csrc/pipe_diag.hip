@@ -148,23 +148,23 @@ int spectral_norm_dev(const float* W_dev, int out, int in, int iters, double* si
   const size_t off_n = off_s + 256;
   const size_t off_p = off_n + (((size_t)n_part * 8 + 255) & ~(size_t)255);
   uint8_t* ws = (uint8_t*)pipe_ws_get(WS_DIAG, off_p + (size_t)ROW_CHUNKS * in * 8);
-  if (!ws) return PIPE_ENOMEM;
+  if (!ws) return pipe_ws_error();
   float* v = (float*)ws;
   double* y = (double*)(ws + off_y);
   double* z = (double*)(ws + off_z);
   double* sigma = (double*)(ws + off_s);
   double* nz_part = (double*)(ws + off_n);
   double* partial = (double*)(ws + off_p);
-  hipLaunchKernelGGL(start_vector_kernel, dim3(ceil_div(in, BLK)), dim3(BLK), 0, st, v, in);
+  PIPE_KLAUNCH(start_vector_kernel, dim3(ceil_div(in, BLK)), dim3(BLK), 0, st, v, in);
   const dim3 g_mv(ceil_div(out, BLK / 64)), g_mt(ceil_div(in, BLK), ROW_CHUNKS);
   for (int it = 0; it < iters; ++it) {
-    hipLaunchKernelGGL(matvec_kernel, g_mv, dim3(BLK), 0, st, W_dev, out, in, v, y);
-    hipLaunchKernelGGL(matvec_t_kernel, g_mt, dim3(BLK), 0, st, W_dev, out, in, y, partial);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(n_part), dim3(BLK), 0, st, partial, in, z, nz_part);
-    hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, y, out, nz_part, n_part, in, v, z, sigma);
+    PIPE_KLAUNCH(matvec_kernel, g_mv, dim3(BLK), 0, st, W_dev, out, in, v, y);
+    PIPE_KLAUNCH(matvec_t_kernel, g_mt, dim3(BLK), 0, st, W_dev, out, in, y, partial);
+    PIPE_KLAUNCH(reduce_partials_kernel, dim3(n_part), dim3(BLK), 0, st, partial, in, z, nz_part);
+    PIPE_KLAUNCH(normalize_kernel, dim3(1), dim3(1024), 0, st, y, out, nz_part, n_part, in, v, z, sigma);
   }
-  hipLaunchKernelGGL(matvec_kernel, g_mv, dim3(BLK), 0, st, W_dev, out, in, v, y);
-  hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, st, y, out, (const double*)nullptr, 0, in, v, z, sigma);
+  PIPE_KLAUNCH(matvec_kernel, g_mv, dim3(BLK), 0, st, W_dev, out, in, v, y);
+  PIPE_KLAUNCH(normalize_kernel, dim3(1), dim3(1024), 0, st, y, out, (const double*)nullptr, 0, in, v, z, sigma);
   PIPE_HIP(hipGetLastError());
   double s = 0.0;
   PIPE_HIP(hipMemcpyAsync(&s, sigma, sizeof(double), hipMemcpyDeviceToHost, st));
@@ -194,10 +194,10 @@ extern "C" int pipe_expansion_order_norms(const pipe_expansion* e, int iters, do
     if (rows == 0) continue;
     int8_t* tmp = (int8_t*)pipe_ws_get(WS_DIAG_CODES, (size_t)rows * e->in);
     float* R = (float*)pipe_ws_get(WS_DIAG_DENSE, (size_t)rows * e->in * sizeof(float));
-    if (!tmp || !R) return PIPE_ENOMEM;
+    if (!tmp || !R) return pipe_ws_error();
     int rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, rows, e->in, e->in_pad, tmp, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(scale_rows_kernel, dim3(rows), dim3(BLK), 0, st, tmp, e->scales_all_dev, o.pos_dev, e->in, R);
+    PIPE_KLAUNCH(scale_rows_kernel, dim3(rows), dim3(BLK), 0, st, tmp, e->scales_all_dev, o.pos_dev, e->in, R);
     PIPE_HIP(hipGetLastError());
     rc = spectral_norm_dev(R, rows, e->in, iters, &norms_host[k], st);
     if (rc) return rc;
@@ -215,10 +215,10 @@ extern "C" int pipe_expansion_reconstruct(const pipe_expansion* e, int upto, flo
     const int rows = o.n_kept * e->group;
     if (rows == 0) continue;
     int8_t* tmp = (int8_t*)pipe_ws_get(WS_DIAG_CODES, (size_t)rows * e->in);
-    if (!tmp) return PIPE_ENOMEM;
+    if (!tmp) return pipe_ws_error();
     int rc = launch_unpack_codes(e->codes_dev, o.pos_dev, e->bits, rows, e->in, e->in_pad, tmp, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(add_order_kernel, dim3(rows), dim3(BLK), 0, st, tmp, e->scales_all_dev, o.pos_dev, o.gids_dev,
+    PIPE_KLAUNCH(add_order_kernel, dim3(rows), dim3(BLK), 0, st, tmp, e->scales_all_dev, o.pos_dev, o.gids_dev,
                        e->group, e->in, W_out_dev);
     PIPE_HIP(hipGetLastError());
   }

@@ -269,14 +269,14 @@ __global__ __launch_bounds__(256) void gather_row_blocks_kernel(const uint8_t* _
 int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, const int32_t* pos_of_dev, int n_crb,
                              int64_t rb_bytes, uint8_t* codes_all, float* scales_all, hipStream_t st) {
   if (n_crb <= 0) return PIPE_OK;
-  hipLaunchKernelGGL(gather_row_blocks_kernel, dim3((unsigned)n_crb), dim3(256), 0, st, codes_k, scales_k, pos_of_dev,
+  PIPE_KLAUNCH(gather_row_blocks_kernel, dim3((unsigned)n_crb), dim3(256), 0, st, codes_k, scales_k, pos_of_dev,
                      rb_bytes, codes_all, scales_all);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
 
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st) {
-  hipLaunchKernelGGL(row_energy_kernel, dim3(out), dim3(BLK), 0, st, E, in, row_energy);
+  PIPE_KLAUNCH(row_energy_kernel, dim3(out), dim3(BLK), 0, st, E, in, row_energy);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -288,9 +288,9 @@ int launch_group_select(const double* row_energy, int n_groups, int group, int n
   double* score = const_cast<double*>(row_energy) + (size_t)n_groups * group;
   int32_t* flag = reinterpret_cast<int32_t*>(score + n_groups);
   const int g = ceil_div(n_groups, 128);
-  hipLaunchKernelGGL(group_score_kernel, dim3(g), dim3(128), 0, st, row_energy, n_groups, group, score);
-  hipLaunchKernelGGL(group_rank_kernel, dim3(g), dim3(128), 0, st, score, n_groups, n_keep, flag);
-  hipLaunchKernelGGL(group_compact_kernel, dim3(g), dim3(128), 0, st, flag, n_groups, gids_out);
+  PIPE_KLAUNCH(group_score_kernel, dim3(g), dim3(128), 0, st, row_energy, n_groups, group, score);
+  PIPE_KLAUNCH(group_rank_kernel, dim3(g), dim3(128), 0, st, score, n_groups, n_keep, flag);
+  PIPE_KLAUNCH(group_compact_kernel, dim3(g), dim3(128), 0, st, flag, n_groups, gids_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(BLK) void fold_batchnorm_kernel(const float* __rest
 
 int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, const float* beta, const float* mean,
                           const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st) {
-  hipLaunchKernelGGL(fold_batchnorm_kernel, dim3(out), dim3(BLK), 0, st, W, b, gamma, beta, mean, var, eps, in, W_out, b_out);
+  PIPE_KLAUNCH(fold_batchnorm_kernel, dim3(out), dim3(BLK), 0, st, W, b, gamma, beta, mean, var, eps, in, W_out, b_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -334,7 +334,7 @@ int select_entry_threshold(const float* E, long long n, long long keep, uint32_t
   uint32_t ties = 0;
   for (int lvl = 0; lvl < 3; ++lvl) {
     PIPE_HIP(hipMemsetAsync(hist_dev, 0, SEL_BINS * sizeof(uint32_t), st));
-    hipLaunchKernelGGL(key_histogram_kernel, dim3(grid), dim3(BLK), 0, st, E, n, shifts[lvl], nbins[lvl],
+    PIPE_KLAUNCH(key_histogram_kernel, dim3(grid), dim3(BLK), 0, st, E, n, shifts[lvl], nbins[lvl],
                        lvl == 0 ? 32 : shifts[lvl - 1], prefix, hist_dev);
     PIPE_HIP(hipGetLastError());
     PIPE_HIP(hipMemcpyAsync(h.data(), hist_dev, SEL_BINS * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
@@ -356,7 +356,7 @@ int select_entry_threshold(const float* E, long long n, long long keep, uint32_t
     const long long mid = lo + (hi - lo) / 2;
     uint32_t c = 0;
     PIPE_HIP(hipMemsetAsync(cnt_dev, 0, sizeof(uint32_t), st));
-    hipLaunchKernelGGL(count_ties_kernel, dim3(grid), dim3(BLK), 0, st, E, n, prefix, mid, cnt_dev);
+    PIPE_KLAUNCH(count_ties_kernel, dim3(grid), dim3(BLK), 0, st, E, n, prefix, mid, cnt_dev);
     PIPE_HIP(hipGetLastError());
     PIPE_HIP(hipMemcpyAsync(&c, cnt_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     PIPE_HIP(hipStreamSynchronize(st));
@@ -374,11 +374,11 @@ int launch_quantize_rows(float* E, int out, int in, int in_pad, int bits, int qb
   const int rows = n_kept * group;
   if (rows == 0) return PIPE_OK;
   if (bits == 8)
-    hipLaunchKernelGGL(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
+    PIPE_KLAUNCH(quantize_rows_kernel<8>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   else if (bits == 4)
-    hipLaunchKernelGGL(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
+    PIPE_KLAUNCH(quantize_rows_kernel<4>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   else
-    hipLaunchKernelGGL(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
+    PIPE_KLAUNCH(quantize_rows_kernel<2>, dim3(rows), dim3(BLK), 0, st, E, in, in_pad, group, gids, scales, packed, qmax, given, thr_key, tie_cut);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -387,7 +387,7 @@ int launch_gather_rows(const float* E, int in, int qbits, int group, const int32
                        float* rows_out, float* scales_out, hipStream_t st) {
   const int rows = n_kept * group;
   if (rows == 0) return PIPE_OK;
-  hipLaunchKernelGGL(gather_rows_kernel, dim3(rows), dim3(BLK), 0, st, E, in, group, gids, (1 << (qbits - 1)) - 1, rows_out,
+  PIPE_KLAUNCH(gather_rows_kernel, dim3(rows), dim3(BLK), 0, st, E, in, group, gids, (1 << (qbits - 1)) - 1, rows_out,
                      scales_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -397,7 +397,7 @@ int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bi
                         int8_t* codes, hipStream_t st) {
   const int64_t n = (int64_t)rows * in;
   if (n == 0) return PIPE_OK;
-  hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, rb_map_dev,
+  PIPE_KLAUNCH(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, rb_map_dev,
                      bits, rows, in, in_pad, codes);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;

@@ -163,9 +163,23 @@ struct PipeWorkspace {
   void* ptr = nullptr;
   size_t bytes = 0;
 };
-// Returns a device buffer of at least `bytes` from slot `slot` (grow-only; growing
-// synchronizes the device first).  nullptr on failure.
+// Returns a device buffer of at least `bytes` from slot `slot` of the workspace of the calling
+// entry point's (device, stream).  Grow-only: a larger block is allocated next to the old one,
+// which stays allocated until the process ends (graphs captured earlier keep its address).
+// nullptr on failure; pipe_ws_error() then tells why (PIPE_ENOMEM, or PIPE_ENOTREADY when the
+// stream is being captured and the block would have to grow).
 void* pipe_ws_get(int slot, size_t bytes);
+int pipe_ws_error();
+// true while a pipe_prepare* call walks a forward entry point: sizes and schedules are set up,
+// nothing is launched or copied
+bool pipe_dry_run();
+// true while the calling entry point's stream is being captured into a graph
+bool pipe_capturing();
+// every kernel launch of the library goes through this (or PIPE_LAUNCH below)
+#define PIPE_KLAUNCH(...)                                   \
+  do {                                                      \
+    if (!pipe_dry_run()) hipLaunchKernelGGL(__VA_ARGS__);   \
+  } while (0)
 enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
@@ -280,6 +294,7 @@ struct GemmArgs {
 // (the kernel alone: no event-record packets on the stream in between).
 #define PIPE_LAUNCH(kernel, grid, block, st, ev0, ev1, ...)                                   \
   do {                                                                                       \
+    if (pipe_dry_run()) break;                                                               \
     if ((ev0) != nullptr) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__); \
     else hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                         \
   } while (0)

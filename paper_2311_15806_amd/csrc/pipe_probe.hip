@@ -96,7 +96,7 @@ extern "C" int pipe_mfma_probe(int iters, int operands, double* tops_out, void* 
   if (iters <= 0 || !tops_out || operands < 0 || operands > 2) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   int* sink = (int*)pipe_ws_get(WS_MISC, 256 + 8 * 256 * 16);
-  if (!sink) return PIPE_ENOMEM;
+  if (!sink) return pipe_ws_error();
   v4i* ops_dev = reinterpret_cast<v4i*>(reinterpret_cast<uint8_t*>(sink) + 256);
   // operands: 0 = constant bytes; 1 = ternary offset codes {0,1,2} against random int8
   // activations (what the ternary layers feed the pipe); 2 = random int8 against random int8
@@ -114,11 +114,11 @@ extern "C" int pipe_mfma_probe(int iters, int operands, double* tops_out, void* 
   PIPE_HIP(hipEventCreate(&e0));
   PIPE_HIP(hipEventCreate(&e1));
   const int blocks = 256 * 2 * 4;   // 2 workgroups per CU resident, 4 rounds
-  if (wide) hipLaunchKernelGGL(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);   // warm-up
-  else hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);
+  if (wide) PIPE_KLAUNCH(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);   // warm-up
+  else PIPE_KLAUNCH(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, 16, ops_dev, sink);
   PIPE_HIP(hipEventRecord(e0, st));
-  if (wide) hipLaunchKernelGGL(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
-  else hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
+  if (wide) PIPE_KLAUNCH(mfma_probe32_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
+  else PIPE_KLAUNCH(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, ops_dev, sink);
   PIPE_HIP(hipEventRecord(e1, st));
   PIPE_HIP(hipEventSynchronize(e1));
   float ms = 0.f;
@@ -143,9 +143,9 @@ extern "C" int pipe_hbm_probe(int64_t bytes, double* gbps_out, void* stream) {
   if (he == hipSuccess) he = hipEventCreate(&e1);
   float ms = 0.f;
   if (he == hipSuccess) {
-    hipLaunchKernelGGL(hbm_probe_kernel, dim3((unsigned)blocks), dim3(512), 0, st, reinterpret_cast<const uint4*>(buf), sink);
+    PIPE_KLAUNCH(hbm_probe_kernel, dim3((unsigned)blocks), dim3(512), 0, st, reinterpret_cast<const uint4*>(buf), sink);
     he = hipEventRecord(e0, st);
-    hipLaunchKernelGGL(hbm_probe_kernel, dim3((unsigned)blocks), dim3(512), 0, st, reinterpret_cast<const uint4*>(buf), sink);
+    PIPE_KLAUNCH(hbm_probe_kernel, dim3((unsigned)blocks), dim3(512), 0, st, reinterpret_cast<const uint4*>(buf), sink);
     if (he == hipSuccess) he = hipEventRecord(e1, st);
     if (he == hipSuccess) he = hipEventSynchronize(e1);
     if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);

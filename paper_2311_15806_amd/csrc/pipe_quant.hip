@@ -563,7 +563,7 @@ int set_act_qmax(float qmax) {
 
 int launch_zero_u32(uint32_t* p, int n, hipStream_t st) {
   if (n <= 0) return PIPE_OK;
-  hipLaunchKernelGGL(zero_u32_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, p, n);
+  PIPE_KLAUNCH(zero_u32_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, p, n);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -573,7 +573,7 @@ int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_
   int64_t blocks = (n / 4 + BLK - 1) / BLK;
   if (blocks < 1) blocks = 1;
   if (blocks > 256) blocks = 256;   // 1 per CU: every thread keeps 8 loads (128 B) in flight
-  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits, zero_me, n_zero);
+  PIPE_KLAUNCH(absmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, amax_bits, zero_me, n_zero);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -595,7 +595,7 @@ int launch_quantize_act(const float* x, int T, int in, int in_pad, int T_pad, fl
     if (rc) return rc;
   }
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, (int64_t)0, T, in, in_pad, s_static, amax_bits,
+  PIPE_KLAUNCH(quantize_act_kernel, grid, dim3(BLK), 0, st, x, (int64_t)0, T, in, in_pad, s_static, amax_bits,
                      qx_frag, (int64_t)0, rowsum, 0, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -609,7 +609,7 @@ int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int
     if (rc) return rc;
   }
   dim3 grid(T_pad / 16, ksplit_for(T_pad * M, in_pad), M);
-  hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(BLK), 0, st, x, x_mstride, T, in, in_pad, 0.f, amax_bits,
+  PIPE_KLAUNCH(quantize_act_kernel, grid, dim3(BLK), 0, st, x, x_mstride, T, in, in_pad, 0.f, amax_bits,
                      qx_frag, qx_mstride, rowsum, T_pad, (int8_t*)nullptr, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -618,7 +618,7 @@ int launch_quantize_members(const float* x, int64_t x_mstride, int M, int T, int
 int launch_quantize_small(const float* x, int64_t x_mstride, int M, int T, int in, int in_pad, float s_static,
                           const uint32_t* amax_bits, uint8_t* qx_frag, int64_t qx_mstride, int32_t* rowsum,
                           int8_t* qx_rowmajor, float* scale_out, hipStream_t st) {
-  hipLaunchKernelGGL(quantize_small_kernel, dim3((unsigned)round_up64(T, 16), M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
+  PIPE_KLAUNCH(quantize_small_kernel, dim3((unsigned)round_up64(T, 16), M), dim3(SBLK), 0, st, x, x_mstride, T, in, in_pad, s_static,
                      amax_bits, qx_frag, qx_mstride, rowsum, qx_rowmajor, scale_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -629,7 +629,7 @@ int launch_quantize_elem(const float* x, int64_t n, float s_static, const uint32
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits, q8, scale_out,
+  PIPE_KLAUNCH(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits, q8, scale_out,
                      (int32_t*)nullptr, 0);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -644,12 +644,12 @@ int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, i
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits,
+  PIPE_KLAUNCH(quantize_elem_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, s_static, amax_bits,
                      q8_scratch, scale_out, rowsum, T_pad);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
+  PIPE_KLAUNCH(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
                      (const int32_t*)nullptr);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -665,12 +665,12 @@ int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int 
   if (n >= ((int64_t)1 << 31)) return PIPE_ESHAPE;   // the gather steps 32-bit element offsets
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots,
+  PIPE_KLAUNCH(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots,
                      (float)((1 << act_bits) - 1), 1 << (act_bits - 1), q8_scratch, scale_out, dz_out, rowsum, T_pad);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
+  PIPE_KLAUNCH(im2col_codes_kernel, grid, dim3(BLK), 0, st, q8_scratch, g, T, in, in_pad, qx_frag, rowsum,
                      (const int32_t*)dz_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -682,7 +682,7 @@ int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint
   if (n <= 0) return PIPE_OK;
   int64_t blocks = (n + BLK * 4 - 1) / (BLK * 4);
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits);
+  PIPE_KLAUNCH(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -691,7 +691,7 @@ int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint
 int launch_minmax(const float* x, int64_t n, uint32_t* slots, hipStream_t st) {
   int64_t blocks = std::min<int64_t>((n + BLK - 1) / BLK, 2048);
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(minmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots);
+  PIPE_KLAUNCH(minmax_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -702,7 +702,7 @@ int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, c
   int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
   if (rc) return rc;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  hipLaunchKernelGGL(quantize_asym_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, slots, (float)((1 << act_bits) - 1),
+  PIPE_KLAUNCH(quantize_asym_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, slots, (float)((1 << act_bits) - 1),
                      1 << (act_bits - 1), qx_frag, rowsum, qx_rowmajor, scale_out, dz_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -710,7 +710,7 @@ int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, c
 
 int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
                      uint32_t* slots, hipStream_t st) {
-  hipLaunchKernelGGL(asym_bias_kernel, dim3((n + 255) / 256), dim3(256), 0, st, bias, C, scale, dz, out, n, slots);
+  PIPE_KLAUNCH(asym_bias_kernel, dim3((n + 255) / 256), dim3(256), 0, st, bias, C, scale, dz, out, n, slots);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -718,14 +718,14 @@ int launch_asym_bias(const float* bias, const float* C, const float* scale, cons
 int launch_asym_acc_fix(int32_t* acc, const int32_t* wsum, const int32_t* dz, int K, int T, int out, hipStream_t st) {
   const int64_t n = (int64_t)K * T * out;
   if (n == 0) return PIPE_OK;
-  hipLaunchKernelGGL(asym_acc_fix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, acc, wsum, dz, K, T, out);
+  PIPE_KLAUNCH(asym_acc_fix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, acc, wsum, dz, K, T, out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
 
 int launch_row_code_sums(const int8_t* codes, int rows, int in, int group, const int32_t* gids, int32_t* wsum, hipStream_t st) {
   if (rows == 0) return PIPE_OK;
-  hipLaunchKernelGGL(row_code_sums_kernel, dim3(rows), dim3(BLK), 0, st, codes, in, group, gids, wsum);
+  PIPE_KLAUNCH(row_code_sums_kernel, dim3(rows), dim3(BLK), 0, st, codes, in, group, gids, wsum);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

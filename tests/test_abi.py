@@ -70,13 +70,19 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_forward_asymmetric(None, None, 4, None, 0, None, None, None) == EINVAL
     assert lib.pipe_forward_acc_asymmetric(None, None, 4, None, None, None, None, None) == EINVAL
     assert lib.pipe_forward_conv2d_asymmetric(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, None, 0, None, None, None) == EINVAL
+    assert lib.pipe_forward_conv2d_acc(None, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, C.c_float(0), fake, None, None, None) == EINVAL
+    assert lib.pipe_forward_conv2d_acc(fake, None, 1, 4, 4, 4, 3, 3, 1, 1, 0, C.c_float(0), None, None, None, None) == EINVAL   # no accumulator buffer
+    assert lib.pipe_prepare(None, None, 0, 16, None) == EINVAL
+    assert lib.pipe_prepare(fake, None, 0, 0, None) == EINVAL
+    assert lib.pipe_prepare_mlp(None, None, 1, None, 0, 16, None) == EINVAL
+    assert lib.pipe_prepare_chain(None, 1, 4, 1, 1, None, 0, None) == EINVAL
     assert lib.pipe_expansion_free(None) == 0
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0
     assert lib.pipe_set_decode_fusion(2) == EINVAL and lib.pipe_set_decode_fusion(1) == 0
     assert lib.pipe_set_token_tile(48) == EINVAL and lib.pipe_set_token_tile(0) == 0
     assert lib.pipe_set_activation_bits(9) == EINVAL and lib.pipe_set_activation_bits(1) == EINVAL
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         assert len(lib.pipe_strerror(code)) > 0
 
 
