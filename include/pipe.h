@@ -60,6 +60,7 @@ enum {
   PIPE_ENOMEM = -3,  /* device or host allocation failed                         */
   PIPE_EDEVICE = -4, /* a HIP call failed (see pipe_last_device_error)           */
   PIPE_ESPLIT = -5,  /* split entries not positive or not summing to K            */
+  PIPE_ELIMIT = -7,  /* pipe_forward_noalloc: the input exceeds its fixed scratch         */
   PIPE_ENOTREADY = -6 /* the call would have to allocate or synchronize where it may not
                          (its stream is being captured into a graph): run the matching
                          pipe_prepare* call first.  Nothing was launched.                */
@@ -170,6 +171,23 @@ int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, float s_x,
 int pipe_prepare(const pipe_expansion* e, const int* split, int M, int T_max, void* stream);
 int pipe_prepare_mlp(const pipe_expansion* l1, const pipe_expansion* l2, int act, const int* split, int M,
                      int T_max, void* stream);
+
+/* pipe_forward for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic and results
+ * (bit for bit) as pipe_forward; it calls no allocating routine and does not synchronize.
+ *   - Its scratch (max|x| slot, scale, token code sums, Q(x)) is a fixed array of 8 MiB + 36 KiB
+ *     in device memory that every GPU the library runs on holds until the process ends.  Limits:
+ *     T <= 8192 and (T rounded up to 16, or to 64 above 128 tokens) x (in rounded up to 256)
+ *     <= 8 MiB, e.g. 2048 tokens of 4096 features; beyond them PIPE_ELIMIT, nothing launched.
+ *   - Above 128 tokens the tile schedule of this grouping of the orders must exist already
+ *     (pipe_prepare, or any earlier pipe_forward with the same grouping above 128 tokens);
+ *     otherwise PIPE_ENOTREADY, nothing launched.
+ *   - All calls on one GPU share the one array, whatever their stream: calls that overlap in
+ *     time on a GPU race on it.  Order them (one stream, or events).  Kernel timing
+ *     (pipe_timing_enable) does not see this entry point.                                   */
+int pipe_forward_noalloc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
+                         const int* split, int M, const float* bias_dev, int reduce_members,
+                         float* y_dev, void* stream);
 
 /* Debug twin of pipe_forward: exports the integer state for bit-exact checks.
  *   acc_dev     [K, T, out] int32, rows pruned at order k are 0 (may be NULL)

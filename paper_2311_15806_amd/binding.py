@@ -49,6 +49,7 @@ def _load():
     lib.pipe_expansion_info.argtypes = [vp, pi, pi, pi, pi, pi, C.POINTER(cf), C.POINTER(C.c_int64)]
     lib.pipe_expansion_order.argtypes = [vp, ci, pi, vp, vp, vp]
     lib.pipe_forward.argtypes = [vp, vp, ci, cf, pi, ci, vp, ci, vp, vp]
+    lib.pipe_forward_noalloc.argtypes = [vp, vp, ci, cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_forward_acc.argtypes = [vp, vp, ci, cf, vp, vp, vp, vp]
     lib.pipe_forward_asymmetric.argtypes = [vp, vp, ci, pi, ci, vp, vp, vp]
     lib.pipe_forward_acc_asymmetric.argtypes = [vp, vp, ci, vp, vp, vp, vp, vp]
@@ -238,6 +239,23 @@ def pipe_forward(e: Expansion, x: torch.Tensor, s_x: float = 0.0, split=None, bi
                              _ptr(bias, torch.float32), 1 if reduce_members else 0,
                              _ptr(y, torch.float32), _stream()), "pipe_forward")
     return y
+
+
+def pipe_forward_noalloc(e: Expansion, x: torch.Tensor, out: torch.Tensor, s_x: float = 0.0, split=None, bias=None,
+                         reduce_members: bool = True) -> torch.Tensor:
+    """pipe_forward through the entry point that allocates nothing; the caller brings the output."""
+    T = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != e.in_features:
+        raise ValueError("x must be [T, in]")
+    M = 1 if split is None else len(split)
+    shape = (T, e.out_features) if reduce_members else (M, T, e.out_features)
+    if tuple(out.shape) != shape:
+        raise ValueError("output has the wrong shape")
+    arr, m = _split(split)
+    _check(_lib.pipe_forward_noalloc(e.handle, _ptr(x, torch.float32), T, float(s_x), arr, m,
+                                     _ptr(bias, torch.float32), 1 if reduce_members else 0,
+                                     _ptr(out, torch.float32), _stream()), "pipe_forward_noalloc")
+    return out
 
 
 def pipe_forward_acc(e: Expansion, x: torch.Tensor, s_x: float = 0.0):

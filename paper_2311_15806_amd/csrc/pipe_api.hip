@@ -30,6 +30,7 @@ extern "C" const char* pipe_strerror(int code) {
     case PIPE_ENOMEM: return "out of memory";
     case PIPE_EDEVICE: return "HIP call failed";
     case PIPE_ESPLIT: return "ensemble split must be positive and sum to K";
+    case PIPE_ELIMIT: return "input larger than the fixed scratch of pipe_forward_noalloc (tokens <= 8192, padded tokens x padded in_features <= 8 MiB)";
     case PIPE_ENOTREADY: return "the call would have to allocate or synchronize while its stream is being captured: run pipe_prepare first";
     default: return "unknown error";
   }
@@ -51,10 +52,11 @@ static std::vector<void*> g_ws_retired;
 static thread_local WsSet* t_ws = nullptr;
 static thread_local bool t_capturing = false;
 static thread_local bool t_dry = false;
+static thread_local bool t_no_alloc = false;   // inside the entry point that allocates nothing
 static thread_local int t_ws_err = PIPE_ENOMEM;
 
 bool pipe_dry_run() { return t_dry; }
-bool pipe_capturing() { return t_capturing; }
+bool pipe_capturing() { return t_capturing || t_no_alloc; }
 int pipe_ws_error() { return t_ws_err; }
 
 static WsSet* ws_set_of(hipStream_t st) {
@@ -770,6 +772,78 @@ extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int
   a.s_x = b.scale; a.reduce = 1; a.acc_out = acc_dev; a.zero_after = b.amax;
   fill_members(a, 1, &lo, &hi);
   rc = run_gemm(a, small, st);
+  return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
+}
+
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// pipe_forward for callers that cannot allocate: its scratch -- max|x| slot and scale, token code
+// sums, Q(x) in the fragment layout -- is a fixed array in device memory, one copy per GPU, shared
+// by every call on that GPU and keeping the last call's contents.
+constexpr size_t NOALLOC_SCAL_BYTES = 4096;                 // max|x| slot at 0, scale at 1024
+constexpr int NOALLOC_MAX_TOKENS = 8192;
+constexpr size_t NOALLOC_ROWSUM_BYTES = (size_t)NOALLOC_MAX_TOKENS * 4;
+constexpr size_t NOALLOC_QX_BYTES = (size_t)8 << 20;        // padded tokens x padded in_features
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCAL_BYTES + NOALLOC_ROWSUM_BYTES + NOALLOC_QX_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static unsigned char* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};   // device address of `scratch` on each GPU
+static std::mutex g_scratch_mu;
+
+// The array's address on the current device (each GPU holds its own copy at its own address),
+// looked up once per device.
+static int noalloc_scratch(unsigned char** out) {
+  int dev = 0;
+  PIPE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return PIPE_EDEVICE;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    unsigned char* ptr = nullptr;
+    PIPE_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return PIPE_EDEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PIPE_OK;
+}
+
+extern "C" int pipe_forward_noalloc(const pipe_expansion* e, const float* x_dev, int T, float s_x, const int* split,
+                                    int M, const float* bias_dev, int reduce_members, float* y_dev, void* stream) {
+  if (!e || T < 0) return PIPE_EINVAL;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(e->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const bool small = use_stream_kernel(e, T);
+  ActBuffers b;
+  b.T_pad = (int)round_up64(T, small ? 16 : TOK_TILE);
+  if (b.T_pad > NOALLOC_MAX_TOKENS || (size_t)b.T_pad * e->in_pad > NOALLOC_QX_BYTES) return PIPE_ELIMIT;
+  unsigned char* base = nullptr;
+  if ((rc = noalloc_scratch(&base)) != PIPE_OK) return rc;
+  b.amax = reinterpret_cast<uint32_t*>(base);
+  b.scale = reinterpret_cast<float*>(base + 1024);
+  b.rowsum = reinterpret_cast<int32_t*>(base + NOALLOC_SCAL_BYTES);
+  b.qx = base + NOALLOC_SCAL_BYTES + NOALLOC_ROWSUM_BYTES;
+  struct Guard {   // schedules are looked up, never built, inside this call
+    Guard() { t_no_alloc = true; }
+    ~Guard() { t_no_alloc = false; }
+  } guard;
+  if (!small && (rc = ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  const bool fused = fuse_decode_quant(e, T, x_dev, small, y_dev, (size_t)(reduce_members ? 1 : Mm) * T * e->out);
+  if (!fused) {
+    // The array keeps what the last call left: the max|x| slot has to start at zero (a call that
+    // failed after its reduction, or that overlapped another one, may have left it raised).
+    const bool uses_slot = !(s_x > 0.f) && !(small && T <= PIPE_QUANT1_MAX_T);
+    if (uses_slot && (rc = launch_zero_u32(b.amax, 1, st)) != PIPE_OK) return rc;
+    rc = quantize_input(x_dev, T, e->in, e->in_pad, s_x, b, small, nullptr, b.scale, st);
+    if (rc) return rc;
+  }
+  GemmArgs a{};
+  a.e = e; a.T = T; a.T_pad = b.T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
+  a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev; a.zero_after = b.amax;
+  if (fused) { a.x_f32 = x_dev; a.s_static = s_x; }
+  fill_members(a, Mm, lo, hi);
+  rc = small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);   // no timing events: creating one allocates
   return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
 }
 
