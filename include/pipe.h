@@ -426,6 +426,25 @@ int pipe_set_stream_split(int workgroups_per_bin);
  * setting.  Returns PIPE_EINVAL for other values.                                    */
 int pipe_set_decode_fusion(int on);
 
+/* Decode-sized batches (at most 16 tokens) through pipe_chain_forward and pipe_mlp_forward: by default
+ * the whole chain of layers runs as ONE resident launch (one workgroup per compute unit walks the
+ * layers; the packed codes of the next layer stream from HBM while the current layer's results are
+ * exchanged between the workgroups) instead of two launches per layer.  Conditions: fully-connected
+ * layers only, at most 4 orders and at most 2 members, every layer stored at the same code width, at most
+ * 16 layers, in_features of the first layer a multiple of 4 and a 16-byte aligned input; otherwise,
+ * and with 0 here, the calls take the per-layer launches.  Results do not depend on the setting (the
+ * fp32 arithmetic and its order are those of the per-layer kernels).  Returns PIPE_EINVAL for other values.
+ * The resident launch needs every workgroup of its grid on the chip at once; its waits for other
+ * workgroups are bounded (pipe_set_resident_spin_limit polls, 0 = the default of 2^19, about a second):
+ * a workgroup whose wait runs out records it and runs to its end without waiting again, so the launch
+ * always ends, with wrong results.  pipe_resident_status synchronizes `stream` and writes to *status_out
+ * (HOST) 0, or a non-zero value if a launch on that stream's scratch ran into the limit since the last
+ * query (then clears it).  Two resident launches in flight at once on one GPU (two streams) can starve
+ * each other into that limit: order them.                                                          */
+int pipe_set_decode_resident(int on);
+int pipe_set_resident_spin_limit(int polls);
+int pipe_resident_status(void* stream, int* status_out);
+
 /* Kernel timing for benchmarks.  While enabled, every forward call brackets its
  * contraction kernel (the dominant kernel of the path) with a pair of HIP events
  * recorded on the call's stream.  pipe_timing_read waits for the recorded events,

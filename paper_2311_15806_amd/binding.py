@@ -76,6 +76,9 @@ def _load():
     lib.pipe_set_activation_bits.argtypes = [ci]
     lib.pipe_set_stream_split.argtypes = [ci]
     lib.pipe_set_decode_fusion.argtypes = [ci]
+    lib.pipe_set_decode_resident.argtypes = [ci]
+    lib.pipe_set_resident_spin_limit.argtypes = [ci]
+    lib.pipe_resident_status.argtypes = [vp, pi]
     lib.pipe_set_token_tile.argtypes = [ci]
     lib.pipe_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), vp]
     lib.pipe_hbm_probe.argtypes = [C.c_int64, C.POINTER(C.c_double), vp]
@@ -556,6 +559,21 @@ def pipe_set_stream_split(workgroups_per_bin: int) -> None:
 
 def pipe_set_decode_fusion(on: bool) -> None:
     _check(_lib.pipe_set_decode_fusion(1 if on else 0), "pipe_set_decode_fusion")
+
+
+def pipe_set_decode_resident(on: bool) -> None:
+    _check(_lib.pipe_set_decode_resident(1 if on else 0), "pipe_set_decode_resident")
+
+
+def pipe_set_resident_spin_limit(polls: int) -> None:
+    _check(_lib.pipe_set_resident_spin_limit(int(polls)), "pipe_set_resident_spin_limit")
+
+
+def pipe_resident_status() -> int:
+    """0, or non-zero if a resident launch on the current stream ran into its wait limit (synchronizes)."""
+    v = C.c_int()
+    _check(_lib.pipe_resident_status(_stream(), C.byref(v)), "pipe_resident_status")
+    return v.value
 
 
 def pipe_timing_enable(on: bool) -> None:

@@ -19,6 +19,7 @@ SOURCES = [
     ("pipe_quant.hip", ["-ffp-contract=off"]),
     ("pipe_gemm.hip", []),
     ("pipe_gemv.hip", []),
+    ("pipe_resident.hip", []),
     ("pipe_probe.hip", []),
     ("pipe_diag.hip", ["-ffp-contract=off"]),
     ("pipe_depthwise.hip", ["-ffp-contract=off"]),

@@ -145,6 +145,18 @@ extern "C" int pipe_set_decode_fusion(int on) {
   return PIPE_OK;
 }
 
+extern "C" int pipe_set_decode_resident(int on) {
+  if (on != 0 && on != 1) return PIPE_EINVAL;
+  g_decode_resident = on;
+  return PIPE_OK;
+}
+
+extern "C" int pipe_set_resident_spin_limit(int polls) {
+  if (polls < 0) return PIPE_EINVAL;
+  g_resident_spin_limit = polls == 0 ? (1 << 19) : polls;
+  return PIPE_OK;
+}
+
 extern "C" int pipe_set_stream_split(int workgroups_per_bin) {
   if (workgroups_per_bin < 0 || workgroups_per_bin > PIPE_MAX_SPLIT) return PIPE_EINVAL;
   g_stream_ksplit = workgroups_per_bin;
@@ -194,6 +206,10 @@ static void free_expansion(pipe_expansion* e) {
     if (t.rb_out_dev) (void)hipFree(t.rb_out_dev);
     if (t.src_dev) (void)hipFree(t.src_dev);
     if (t.cnt_dev) (void)hipFree(t.cnt_dev);
+  }
+  for (auto& rt : e->res_tables) {
+    if (rt.subs_dev) (void)hipFree(rt.subs_dev);
+    if (rt.epi_dev) (void)hipFree(rt.epi_dev);
   }
   if (e->dw_codes_dev) (void)hipFree(e->dw_codes_dev);
   if (e->dw_scales_dev) (void)hipFree(e->dw_scales_dev);
@@ -1151,6 +1167,80 @@ extern "C" int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_
   return launch_zero_u32(b.amax, 1, st);   // no contraction kernel follows to clear the max slot
 }
 
+// ------------------------------------------------------------------ resident decode launch
+// Scratch of the resident kernel in the stream's workspace: flag words, tagged maxima, the epoch the
+// last launch ended with and the status word (all zero when allocated; the kernels keep them
+// consistent afterwards), and one code buffer per layer.
+constexpr size_t RES_FLAGS_BYTES = 4096, RES_TAG_BYTES = 1024 * 2 * 8, RES_CTRL_BYTES = RES_FLAGS_BYTES + RES_TAG_BYTES + 256;
+
+struct ResidentLayerSpec {
+  const pipe_expansion* e;
+  const float* bias;
+  float* out;
+  const float* res;
+  long long res_mstride;
+  int res_members, res_pre_act, res_device, act, gated;
+};
+
+static bool resident_eligible(const pipe_expansion* const* es, int L, int T, int M, const float* x_dev) {
+  if (!g_decode_resident || g_kernel_choice == 1) return false;
+  if (T < 1 || T > 16 || M > PIPE_RES_MAX_M || L > PIPE_RES_MAX_LAYERS) return false;
+  if (es[0]->in % 4 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15) != 0) return false;
+  for (int l = 0; l < L; ++l)
+    if (es[l]->bin_cap != 4 || es[l]->K > 4 || es[l]->bits != es[0]->bits) return false;
+  return true;
+}
+
+static int run_resident(const ResidentLayerSpec* ls, int L, const float* x_dev, int T, float s_x, int M, const int* lo,
+                        const int* hi, hipStream_t st) {
+  ResidentArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.L = L; a.T = T; a.M = M; a.G = pipe_resident_workgroups();
+  for (int m = 0; m < M; ++m) { a.member_lo[m] = lo[m]; a.member_hi[m] = hi[m]; }
+  a.x = x_dev; a.s_static = s_x;
+  const bool fresh = t_ws == nullptr || t_ws->slot[WS_RES].ptr == nullptr;
+  uint8_t* ctrl = (uint8_t*)pipe_ws_get(WS_RES, RES_CTRL_BYTES);
+  if (!ctrl) return pipe_ws_error();
+  if (fresh) PIPE_HIP(hipMemset(ctrl, 0, RES_CTRL_BYTES));   // never under capture: a fresh block is refused there
+  a.flags = reinterpret_cast<uint32_t*>(ctrl);
+  a.amax_tag = reinterpret_cast<unsigned long long*>(ctrl + RES_FLAGS_BYTES);
+  a.gen = reinterpret_cast<uint32_t*>(ctrl + RES_FLAGS_BYTES + RES_TAG_BYTES);
+  a.status = a.gen + 16;
+  size_t q_bytes = 0;
+  std::vector<size_t> q_off(L);
+  for (int l = 0; l < L; ++l) {
+    q_off[l] = q_bytes;
+    q_bytes += (size_t)round_up64((int64_t)(l == 0 ? 1 : M) * 16 * ls[l].e->in_pad, 256);
+  }
+  uint8_t* qbuf = (uint8_t*)pipe_ws_get(WS_RES_Q, q_bytes);
+  if (!qbuf) return pipe_ws_error();
+  for (int l = 0; l < L; ++l) {
+    ResidentLayerArgs& la = a.layers[l];
+    la.e = ls[l].e;
+    int rc = pipe_resident_tables(ls[l].e, ls[l].gated ? 1 : 0, a.G, &la.tables);
+    if (rc) return rc;
+    la.bias = ls[l].bias; la.out = ls[l].out; la.res = ls[l].res; la.res_mstride = ls[l].res_mstride;
+    la.res_members = ls[l].res_members; la.res_pre_act = ls[l].res_pre_act; la.res_device = ls[l].res_device;
+    la.act = ls[l].act; la.gated = ls[l].gated;
+    la.qin = qbuf + q_off[l];
+  }
+  return launch_resident_chain(a, st);
+}
+
+extern "C" int pipe_resident_status(void* stream, int* status_out) {
+  if (!status_out) return PIPE_EINVAL;
+  CallScope scope(stream);
+  *status_out = 0;
+  if (t_ws->slot[WS_RES].ptr == nullptr) return PIPE_OK;
+  uint32_t* status = reinterpret_cast<uint32_t*>((uint8_t*)t_ws->slot[WS_RES].ptr + RES_FLAGS_BYTES + RES_TAG_BYTES) + 16;
+  PIPE_HIP(hipStreamSynchronize((hipStream_t)stream));
+  uint32_t v = 0;
+  PIPE_HIP(hipMemcpy(&v, status, sizeof(v), hipMemcpyDeviceToHost));
+  if (v != 0) PIPE_HIP(hipMemset(status, 0, sizeof(v)));
+  *status_out = (int)v;
+  return PIPE_OK;
+}
+
 extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,
                                 const float* x_dev, int T, float s_x, const int* split, int M,
                                 const float* bias1_dev, const float* bias2_dev, float* h_dev,
@@ -1179,6 +1269,18 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   if (!h || !qh || !rowsum_h) return pipe_ws_error();
   uint32_t* amax_h = b.amax + 16;
   float* scale_h = b.scale + 16;
+  {
+    // decode-sized batches: both layers in one resident launch
+    const pipe_expansion* es[2] = {l1, l2};
+    const bool gated = act == PIPE_ACT_SILU_GATED;
+    if (small && resident_eligible(es, 2, T, Mm, x_dev) && (!gated || l1->n_rb % 2 == 0)) {
+      ResidentLayerSpec ls[2] = {};
+      ls[0].e = l1; ls[0].bias = bias1_dev; ls[0].out = h; ls[0].act = gated ? PIPE_ACT_NONE : PIPE_ACT_GELU; ls[0].gated = gated ? 1 : 0;
+      ls[0].res_pre_act = 1;
+      ls[1].e = l2; ls[1].bias = bias2_dev; ls[1].out = y_dev; ls[1].act = PIPE_ACT_NONE; ls[1].res_pre_act = 1;
+      return run_resident(ls, 2, x_dev, T, s_x, Mm, lo, hi, st);
+    }
+  }
   // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly; otherwise
   // the gated layer's raw outputs pass through a buffer and an element-wise launch
   const bool paired = act == PIPE_ACT_SILU_GATED && !small && l1->n_rb % 2 == 0;
@@ -1372,6 +1474,28 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   // quantizer of layer l+1 reads it, and the contraction of layer l+1 clears it again
   uint32_t* amax_set[2] = {b.amax + 16, b.amax + 16 + PIPE_MAX_K};
   float* scale_h = b.scale + 16;
+  {
+    // decode-sized batches of fully-connected layers: the whole chain in one resident launch
+    std::vector<const pipe_expansion*> es(L);
+    bool fc = H0 == 1 && W0 == 1;
+    for (int l = 0; l < L; ++l) { es[l] = layers[l].e; fc = fc && layers[l].kh == 0 && small[l]; }
+    if (fc && resident_eligible(es.data(), L, (int)Tin[0], Mm, x_dev)) {
+      const int T = (int)Tin[0];
+      std::vector<ResidentLayerSpec> ls(L);
+      for (int l = 0; l < L; ++l) {
+        const pipe_chain_layer& ly = layers[l];
+        ls[l] = ResidentLayerSpec{};
+        ls[l].e = ly.e; ls[l].bias = ly.bias_dev; ls[l].out = l == L - 1 ? y_dev : act[l]; ls[l].act = ly.act;
+        ls[l].res_pre_act = ly.skip_pre_act ? 1 : 0;
+        if (ly.skip_from == 0) {
+          ls[l].res = x_dev; ls[l].res_mstride = 0; ls[l].res_members = 1; ls[l].res_device = 0;
+        } else if (ly.skip_from > 0) {
+          ls[l].res = act[ly.skip_from - 1]; ls[l].res_mstride = (long long)T * ly.e->out; ls[l].res_members = Mm; ls[l].res_device = 1;
+        }
+      }
+      return run_resident(ls.data(), L, x_dev, T, s_x, Mm, lo, hi, st);
+    }
+  }
   for (int l = 0; l < L; ++l)
     if (!small[l] && (rc = ensure_tables(layers[l].e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
   if (pipe_dry_run()) return PIPE_OK;

@@ -90,6 +90,20 @@ struct PassTables {
   int32_t* src_dev = nullptr;          // [M][p_max][n_sorted] position of the row block's j-th stored order, or -1
   uint8_t* cnt_dev = nullptr;          // [n_ct][16] passes of member m in tile t
 };
+// Work units of the resident decode kernel (pipe_resident.hip), built on first use per expansion.
+//   sub-unit: 16 ints  {pos[4] (items a sub-unit does not have repeat pos[0]), k[4], n_items,
+//             first LDS tile of its items, 1 = last sub-unit of its unit, 5 unused}
+//   unit:     32 ints  {n_items, n_out, k[8], slot[8], pos[8], out_rb[4], 2 unused}; a gate||up pair:
+//             items 0-3 the gate block's orders (slot 0), 4-7 the up block's (slot 1), order -1 = absent,
+//             out_rb = {hidden block, gate row block, up row block}
+constexpr int PIPE_RES_MAX_LAYERS = 16;
+constexpr int PIPE_RES_MAX_M = 2;
+constexpr int PIPE_RES_MAX_ITEMS = 8;
+struct ResidentTables {
+  int32_t* subs_dev = nullptr;
+  int32_t* epi_dev = nullptr;
+  int n_units = 0, nsub = 1, G = 0;
+};
 struct pipe_expansion;
 struct GemmArgs;
 // The tables for the members of `a` (built and uploaded on first use: allocates and copies
@@ -132,6 +146,7 @@ struct pipe_expansion {
   int32_t* split_sum_dev = nullptr;   // [n_bins][PIPE_MAX_SPLIT][bin_cap][256]
   uint32_t* split_cnt_dev = nullptr;  // [n_bins]
   int64_t stream_bytes = 0;  // packed codes + scales + indices
+  ResidentTables res_tables[2];   // resident decode kernel: plain units, gate||up pairs
 };
 
 // max|.| reduction slot (fp32 bit pattern of a non-negative value).  Atomics of many waves on
@@ -180,7 +195,7 @@ bool pipe_capturing();
   do {                                                      \
     if (!pipe_dry_run()) hipLaunchKernelGGL(__VA_ARGS__);   \
   } while (0)
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_RES, WS_RES_Q, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
@@ -308,6 +323,34 @@ int launch_depthwise(const pipe_expansion* e, const int8_t* q8, const float* s_x
                      const float* bias, int reduce, float* y, hipStream_t st);   // q8 channels last
 extern float g_act_qmax_host;   // the activation quantizer's largest code (host copy of the device constant)
 int launch_gemm_stream(const GemmArgs& a, hipStream_t st);
+// ---- resident decode kernel (pipe_resident.hip)
+struct ResidentLayerArgs {
+  const pipe_expansion* e;
+  ResidentTables tables;
+  const float* bias;
+  float* out;             // [M, T, width] (hidden layers) or [T, out] (last layer)
+  const float* res;       // skip tensor or nullptr
+  long long res_mstride;
+  int res_members, res_pre_act, res_device;   // res_device: the skip tensor is produced inside the launch
+  int act, gated;
+  uint8_t* qin;           // scratch for the codes entering the layer: M * 16 * in_pad bytes (first layer: 16 * in_pad)
+};
+struct ResidentArgs {
+  ResidentLayerArgs layers[PIPE_RES_MAX_LAYERS];
+  int L, T, M, G;
+  int member_lo[PIPE_RES_MAX_M], member_hi[PIPE_RES_MAX_M];
+  const float* x;
+  float s_static;
+  uint32_t* flags;                 // zero when allocated; the kernels keep them consistent from then on
+  unsigned long long* amax_tag;
+  uint32_t* gen;
+  uint32_t* status;
+};
+int pipe_resident_workgroups();   // one per compute unit
+int pipe_resident_tables(const pipe_expansion* e, int kind, int G, ResidentTables* out);
+int launch_resident_chain(const ResidentArgs& a, hipStream_t st);
+extern int g_decode_resident;        // 1: chains of decode-sized batches run as one resident launch
+extern int g_resident_spin_limit;    // polls of a grid-wide wait before a workgroup gives up
 extern int g_tiled_mtb;       // token blocks per tile of the tiled kernel; 0 = automatic
 extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic
 extern int g_decode_fusion;   // 1: batches of at most 4 tokens are quantized inside the streaming kernel

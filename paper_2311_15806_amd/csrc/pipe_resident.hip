@@ -1,0 +1,774 @@
+// Resident kernel for decode-sized batches (T <= 16): ONE launch walks a whole chain of expanded
+// layers (App. B "Ensemble of more Layers", Sec. 3.2: a member is the whole network; App. B,
+// Eq. (define_dre) per layer), so the packed codes of layer l+1 stream from HBM while layer l's
+// results are still being exchanged, and no launch boundary separates the layers.
+//
+// One workgroup per compute unit, 12 waves:
+//   waves 0-7  ("workers") stream packed codes and multiply.  A wave owns the 1-KiB code tiles
+//              w, w+8, ... of every item (stored row block) of its workgroup's units and keeps RD
+//              rounds of 4 tiles in flight in registers, across unit and LAYER boundaries: the
+//              codes do not depend on the activations, so the first rounds of the next layer are
+//              requested before the grid-wide exchange that makes its input codes available.
+//              Exact int32 partial tiles are added up in LDS; token code sums (for the offset-binary
+//              codes) come from one more MFMA per 64-k step against a row of ones.
+//   waves 8-11 ("epilogue") turn the integer tiles into fp32 outputs with the arithmetic and order of
+//              the per-layer kernels (bit-identical results), and run the exchange between layers:
+//              every workgroup quantizes the outputs it produced itself (network input: a slice of x).
+// Exchange between layers, two grid-wide steps, no read-modify-write atomics and no cache-wide
+// fences (a release or acquire fence at device scope costs 10-30 us on this chip, measured):
+//   A  max|.|: each workgroup publishes {epoch, max} as one 64-bit device-scope store per tensor and
+//      reads everybody's, so all derive the same scale max/q_max (skipped for a given static scale);
+//   B  codes:  each workgroup writes its own outputs' codes with device-scope (write-through) stores,
+//      waits for their completion, publishes its epoch in its flag word and polls the others' flags.
+//   Everything one workgroup writes for another goes through device-scope stores; the consumers'
+//   bulk reads of the codes are ordinary loads from a buffer that no cache can hold stale (each
+//   layer has its own, first read in this launch after the flags were seen).
+// Every wait is bounded: after `spin_limit` polls a workgroup records the failure in a status word,
+// stops waiting for the rest of the launch and runs to its end, so the grid always drains.
+#include "pipe_internal.h"
+
+#include <algorithm>
+#include <cstring>
+
+int g_decode_resident = 1;
+int g_resident_spin_limit = 1 << 19;
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int RES_WORKERS = 8;
+constexpr int RES_EPI = 4;
+constexpr int RES_THREADS = (RES_WORKERS + RES_EPI) * 64;
+constexpr int RES_STASH = 48;            // 1-KiB slots of fp32 outputs a workgroup keeps in LDS between a layer and the next exchange
+constexpr int RES_PAD_LDS = 88 * 1024;   // dynamic LDS: the stash, the rest untouched (it keeps a compute unit to one workgroup)
+
+struct ResLayer {
+  const uint8_t* codes;     // stored row blocks of the layer, schedule order
+  const float* scales;      // 16 row scales per position
+  const int32_t* subs;      // [n_units * nsub] ResSub
+  const int32_t* epi;       // [n_units] ResUnitEpi
+  const float* bias;        // or nullptr
+  float* out;               // hidden layer: [M, T, out_w]; last layer: [T, out_w] (members summed)
+  const float* res;         // skip tensor or nullptr
+  long long res_mstride;
+  uint8_t* qin;             // codes entering the layer: [xm][nks][1 KiB] (fragment layout, one 16-token block)
+  int n_units, nsub, n_tiles, nks;
+  int out_w;                // width of a row of `out` (gated layer: hidden width)
+  int in, in_pad;
+  int xm;                   // distinct activation tensors entering the layer: 1 (first layer) or M
+  int act, res_members, res_pre_act, gated, reduce, res_device;
+};
+
+struct ResParams {
+  ResLayer layer[PIPE_RES_MAX_LAYERS];
+  int L, T, M, G;
+  int member_lo[PIPE_RES_MAX_M], member_hi[PIPE_RES_MAX_M];
+  int member_of[4];
+  const float* x;           // network input [T, in0]
+  float s_static;           // > 0: given scale of the network input
+  float act_qmax;
+  uint32_t* flags;          // [G] epoch each workgroup reached
+  unsigned long long* amax_tag;   // [G][2] {epoch, bit pattern of the local max}
+  uint32_t* gen;            // epoch the previous launch on this scratch ended with
+  uint32_t* status;         // != 0: a wait ran into the spin limit
+  int spin_limit;
+};
+
+static_assert(sizeof(ResParams) <= 3584, "kernel arguments are limited to 4 KiB");
+
+__device__ __forceinline__ float gelu_erf_r(float a) {
+  return 0.5f * a * (1.f + erff(a * 0.70710678118654752440f));
+}
+
+template <int BITS>
+__device__ __forceinline__ void unpack_step_r(const uint4& w, int j, v4i& o) {
+  if (BITS == 8) {
+    o = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+  } else if (BITS == 4) {
+    const uint32_t a = j == 0 ? w.x : w.z, b = j == 0 ? w.y : w.w;
+    o = v4i{(int)(a & 0x0F0F0F0Fu), (int)((a >> 4) & 0x0F0F0F0Fu), (int)(b & 0x0F0F0F0Fu), (int)((b >> 4) & 0x0F0F0F0Fu)};
+  } else {
+    const uint32_t a = j == 0 ? w.x : (j == 1 ? w.y : (j == 2 ? w.z : w.w));
+    o = v4i{(int)(a & 0x03030303u), (int)((a >> 2) & 0x03030303u), (int)((a >> 4) & 0x03030303u), (int)((a >> 6) & 0x03030303u)};
+  }
+}
+
+// wave-uniform loads of the schedule tables (written once by the host): scalar loads
+template <class T>
+__device__ __forceinline__ T cload_r(const void* base, size_t idx) {
+  typedef const __attribute__((address_space(4))) T* cptr;
+  return ((cptr)(unsigned long long)base)[idx];
+}
+
+__device__ __forceinline__ void st_dev_u32(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_dev_u32(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// XM: activation tensors a unit's items can read (1, or one per member: 2).  RD: rounds of four code
+// tiles a worker wave keeps in flight.
+template <int BITS, int XM, int RD>
+__global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const ResParams p) {
+  static_assert(RD % 2 == 0, "the activation fragments alternate between two register sets");
+  constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
+  constexpr int KSUP = 512 / BITS;
+  constexpr int STEPS = KSUP / 64;
+  __shared__ int tile[2][PIPE_RES_MAX_ITEMS + 2][256];
+  __shared__ float s_wmax[RES_EPI][2];
+  __shared__ float s_scale[2];   // scales of the codes entering the current layer
+  __shared__ int s_fail;
+  extern __shared__ int pad_lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wg = blockIdx.x, G = p.G;
+  for (int i = threadIdx.x; i < 2 * (PIPE_RES_MAX_ITEMS + 2) * 256; i += RES_THREADS) (&tile[0][0][0])[i] = 0;
+  if (threadIdx.x == 0) { s_fail = 0; s_scale[0] = 0.f; s_scale[1] = 0.f; }
+  __syncthreads();
+  auto units_of = [&](int n_units) { return n_units > wg ? (n_units - wg + G - 1) / G : 0; };
+
+  if (wave < RES_WORKERS) {
+    // ============================================================== workers
+    // The loads of a step are unconditional and their number fixed (a step without real work loads
+    // a valid address and drops the result), so the waits for them are exact counts: the codes of the
+    // next half-batch stay in flight while the current one is multiplied.
+    constexpr int HB = RD / 2;             // rounds of a half-batch
+    constexpr int NXL = XM * STEPS;        // fragment loads of a round
+    const bool xlive = (lane & 15) < p.T;
+    // lanes of tokens beyond the batch re-read token 0's bytes of their k chunk (no further cache lines) and are zeroed
+    const int xl = xlive ? lane : (lane & 48);
+    v4i acc[4], acc1[XM];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < XM; ++m) acc1[m] = v4i{0, 0, 0, 0};
+    uint4 wreg[2][HB][4], xreg[HB][NXL];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int i = 0; i < HB; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) wreg[s][i][r] = make_uint4(0, 0, 0, 0);
+
+    // rounds of this wave in layer l: units x sub-units x tiles; a wave beyond the layer's tiles
+    // still walks one empty round per sub-unit (it takes part in the unit's barrier)
+    auto ru_of = [&](int l) { const int nt = p.layer[l].n_tiles; return nt > wave ? (nt - wave + RES_WORKERS - 1) / RES_WORKERS : 0; };
+    auto rounds_of = [&](int l) { return units_of(p.layer[l].n_units) * p.layer[l].nsub * max(ru_of(l), 1); };
+
+    // ---- issue cursor: the next round whose codes have not been requested (runs ahead, across layers)
+    int il = 0, iq = 0, iu = 0, ig = 0, ij = 0;       // layer, round in layer, local unit, sub-unit, tile step
+    int ipos[4] = {0, 0, 0, 0};
+    auto issue_desc = [&]() __attribute__((always_inline)) {
+      const ResLayer& ly = p.layer[il];
+      const size_t sub = (size_t)(wg + iu * G) * ly.nsub + ig;
+      const v4i a = cload_r<v4i>(ly.subs, sub * 4);
+      ipos[0] = a[0]; ipos[1] = a[1]; ipos[2] = a[2]; ipos[3] = a[3];
+    };
+    auto issue_seek = [&]() __attribute__((always_inline)) {   // skip layers without rounds, fetch the descriptor
+      while (il < p.L && rounds_of(il) == 0) ++il;
+      if (il < p.L) issue_desc();
+    };
+    issue_seek();
+    // Four code loads: the cursor's round if `real`, else a valid address whose data nobody uses.
+    auto issue_codes = [&](uint4 (&w)[4], bool real) __attribute__((always_inline)) {
+      const int li = il < p.L ? il : p.L - 1;
+      const ResLayer& ly = p.layer[li];
+      const int ru = ru_of(li);
+      const bool has = real && ru > 0;
+      const int tl = has ? wave + RES_WORKERS * ij : 0;
+      // items a sub-unit does not have repeat its first one (a cache hit; the product is dropped)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        w[r] = reinterpret_cast<const uint4*>(ly.codes + ((size_t)(has ? ipos[r] : 0) * ly.n_tiles + tl) * 1024)[lane];
+      if (real) {
+        ++iq;
+        if (++ij >= max(ru, 1)) {
+          ij = 0;
+          if (++ig >= ly.nsub) { ig = 0; ++iu; }
+          if (iu >= units_of(ly.n_units)) { ++il; iq = 0; iu = 0; issue_seek(); }
+          else issue_desc();
+        }
+      }
+    };
+
+    int buf = 0;
+    for (int l = 0; l < p.L; ++l) {
+      const ResLayer& ly = p.layer[l];
+      const int ru = ru_of(l), ru_eff = max(ru, 1);
+      const int rounds = rounds_of(l);
+      const int nhb_pad = ((rounds + HB - 1) / HB + 1) & ~1;   // half-batches, padded to an even number
+      // codes of the first half-batch, unless the previous layer's last step requested them already
+      if (il == l && iq == 0) {
+#pragma unroll
+        for (int i = 0; i < HB; ++i)
+          if (il == l && iq == i) issue_codes(wreg[0][i], true);
+      }
+      // the codes entering this layer are being produced: four workgroup barriers of the exchange
+      __syncthreads();
+      __syncthreads();
+      __syncthreads();
+      __syncthreads();
+      int xj = 0;   // tile step of the next round whose fragments have not been requested
+      auto issue_x = [&](uint4 (&x)[NXL], bool real) __attribute__((always_inline)) {
+        const bool has = real && ru > 0;
+        const int tl = has ? wave + RES_WORKERS * xj : 0;
+#pragma unroll
+        for (int m = 0; m < XM; ++m)
+#pragma unroll
+          for (int j = 0; j < STEPS; ++j) {
+            x[m * STEPS + j] = reinterpret_cast<const uint4*>(ly.qin + ((size_t)(m < ly.xm ? m : 0) * ly.nks + (size_t)tl * STEPS + j) * 1024)[xl];
+          }
+        if (real && ++xj >= ru_eff) xj = 0;
+      };
+      // ---- consume cursor
+      int cu = 0, cg = 0, cj = 0, cn = 0, cslot0 = 0, clast = 0, citm[4] = {0, 0, 0, 0};
+      auto cons_desc = [&]() __attribute__((always_inline)) {
+        const size_t sub = (size_t)(wg + cu * G) * ly.nsub + cg;
+        const v4i a = cload_r<v4i>(ly.subs, sub * 4 + 1), b = cload_r<v4i>(ly.subs, sub * 4 + 2);
+        cn = b[0]; cslot0 = b[1]; clast = b[2];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int k = a[r];
+          citm[r] = (XM == 1 || ly.xm == 1) ? 0 : (k == 0 ? p.member_of[0] : (k == 1 ? p.member_of[1] : (k == 2 ? p.member_of[2] : p.member_of[3])));
+        }
+      };
+      if (rounds > 0) cons_desc();
+
+      for (int h0 = 0; h0 < nhb_pad; h0 += 2) {
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+          const int h = h0 + par;
+          // 1. activation fragments of this half-batch
+#pragma unroll
+          for (int i = 0; i < HB; ++i) issue_x(xreg[i], h * HB + i < rounds);
+          // 2. codes of the next half-batch; the layer's last step requests the next layer's first
+#pragma unroll
+          for (int i = 0; i < HB; ++i) {
+            const bool real = il < p.L && ((il == l && iq == (h + 1) * HB + i) || (h == nhb_pad - 1 && il > l && iq == i));
+            issue_codes(wreg[par ^ 1][i], real);
+          }
+          // 3. multiply this half-batch
+#pragma unroll
+          for (int i = 0; i < HB; ++i) {
+            const int q = h * HB + i;
+            if (q >= rounds) continue;
+            if (ru > 0) {
+              uint4 (&w)[4] = wreg[par][i];
+#pragma unroll
+              for (int j = 0; j < STEPS; ++j) {
+                // the fragments of this 64-k step, lanes of tokens beyond the batch zeroed (at use, not at
+                // load: nothing waits for a load before the step that needs it)
+                v4i x[XM];
+#pragma unroll
+                for (int m = 0; m < XM; ++m) {
+                  const uint4& xr = xreg[i][m * STEPS + j];
+                  x[m] = v4i{xlive ? (int)xr.x : 0, xlive ? (int)xr.y : 0, xlive ? (int)xr.z : 0, xlive ? (int)xr.w : 0};
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  v4i xf = x[0];
+                  if (XM == 2) {
+                    const bool pick1 = citm[r] == 1;
+                    xf[0] = pick1 ? x[1][0] : xf[0];
+                    xf[1] = pick1 ? x[1][1] : xf[1];
+                    xf[2] = pick1 ? x[1][2] : xf[2];
+                    xf[3] = pick1 ? x[1][3] : xf[3];
+                  }
+                  v4i wf;
+                  unpack_step_r<BITS>(w[r], j, wf);
+                  acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xf, acc[r], 0, 0, 0);
+                }
+                if (OFF != 0 && cg == 0) {
+                  // token code sums: a row block of ones against the same fragments
+                  const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+#pragma unroll
+                  for (int m = 0; m < XM; ++m) acc1[m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, x[m], acc1[m], 0, 0, 0);
+                }
+              }
+            }
+            if (cj + 1 >= ru_eff) {
+              // end of a sub-unit: this wave's share of its integer tiles joins the others' in LDS
+              if (ru > 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  if (r < cn) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) atomicAdd(&tile[buf][cslot0 + r][lane * 4 + c], acc[r][c]);
+                  }
+                  acc[r] = v4i{0, 0, 0, 0};
+                }
+              }
+              if (clast) {
+                if (OFF != 0 && ru > 0) {
+#pragma unroll
+                  for (int m = 0; m < XM; ++m) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) atomicAdd(&tile[buf][PIPE_RES_MAX_ITEMS + m][lane * 4 + c], acc1[m][c]);
+                    acc1[m] = v4i{0, 0, 0, 0};
+                  }
+                }
+                __syncthreads();   // the unit's tiles are complete: the epilogue waves take them
+                buf ^= 1;
+              }
+              cj = 0;
+              if (++cg >= ly.nsub) { cg = 0; ++cu; }
+              if (q + 1 < rounds) cons_desc();
+            } else {
+              ++cj;
+            }
+          }
+        }
+      }
+    }
+  } else {
+    // ============================================================== epilogue waves
+    const int e = threadIdx.x - RES_WORKERS * 64;   // 0..255
+    const int ewave = e >> 6;
+    const int t = e >> 4, ch = e & 15;
+    const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);
+    const bool tok = t < p.T;
+    uint32_t epoch = 0;
+    if (wave == RES_WORKERS) epoch = ld_dev_u32(p.gen);
+    const uint32_t epoch0 = epoch;
+    int buf = 0;
+    const float qmax = p.act_qmax;
+    // what this thread produced in the current layer: its max|.| per member, and the values themselves
+    // (LDS, as far as it reaches; the rest is read back from the layer's output)
+    float* stash = reinterpret_cast<float*>(pad_lds);
+    float mx_out[2] = {0.f, 0.f};
+
+    // one grid-wide step: publish this workgroup's epoch, wait until every workgroup has reached it
+    auto grid_wait = [&]() __attribute__((always_inline)) {
+      ++epoch;
+      if (lane == 0) st_dev_u32(&p.flags[wg], epoch);
+      bool ok = s_fail != 0;
+      for (int it = 0; it < p.spin_limit && !ok; ++it) {
+        bool mine = true;
+        for (int i = lane; i < G; i += 64) mine &= (int)(ld_dev_u32(&p.flags[i]) - epoch) >= 0;
+        ok = __all(mine);
+      }
+      if (!ok) {
+        if (lane == 0) { s_fail = 1; st_dev_u32(p.status, 1u); }
+      }
+    };
+
+    for (int l = 0; l < p.L; ++l) {
+      const ResLayer& ly = p.layer[l];
+      const int n_in = ly.xm;   // tensors to quantize for this layer
+      const ResLayer& lp = p.layer[l > 0 ? l - 1 : 0];
+      const int nu_prev = l > 0 ? units_of(lp.n_units) : 0;
+      const bool dynamic = l > 0 || !(p.s_static > 0.f);
+      // ---------------- exchange, step A: max|.| of the tensor(s) entering layer l
+      float mx[2] = {0.f, 0.f};
+      if (dynamic) {
+        if (l == 0) {
+          const int n4 = (p.T * ly.in) >> 2;
+          const float4* x4 = reinterpret_cast<const float4*>(p.x);
+          for (int i = wg * 256 + e; i < n4; i += G * 256) {
+            const float4 v = x4[i];
+            mx[0] = fmaxf(mx[0], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+          }
+        } else {
+          // the outputs this workgroup produced in layer l-1
+          mx[0] = mx_out[0]; mx[1] = mx_out[1];
+        }
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) mx[m] = fmaxf(mx[m], __shfl_xor(mx[m], o, 64));
+          if (lane == 0) s_wmax[ewave][m] = mx[m];
+        }
+      }
+      __syncthreads();   // P1
+      if (wave == RES_WORKERS) {
+        if (dynamic) {
+          ++epoch;
+          if (lane < n_in) {
+            float v = s_wmax[0][lane];
+#pragma unroll
+            for (int w = 1; w < RES_EPI; ++w) v = fmaxf(v, s_wmax[w][lane]);
+            __hip_atomic_store(&p.amax_tag[wg * 2 + lane], ((unsigned long long)epoch << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+          if (lane == 0) st_dev_u32(&p.flags[wg], epoch);   // keeps the flag word in step with the epoch
+          float g0 = 0.f, g1 = 0.f;
+          bool ok = s_fail != 0;
+          for (int it = 0; it < p.spin_limit && !ok; ++it) {
+            bool mine = true;
+            g0 = 0.f; g1 = 0.f;
+            for (int i = lane; i < G * n_in; i += 64) {
+              const int w = i / n_in, m = i - w * n_in;
+              const unsigned long long tv = __hip_atomic_load(&p.amax_tag[w * 2 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              mine &= (uint32_t)(tv >> 32) == epoch;
+              const float v = __uint_as_float((uint32_t)tv);
+              if (m == 0) g0 = fmaxf(g0, v); else g1 = fmaxf(g1, v);
+            }
+            ok = __all(mine);
+          }
+          if (!ok && lane == 0) { s_fail = 1; st_dev_u32(p.status, 2u); }
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) { g0 = fmaxf(g0, __shfl_xor(g0, o, 64)); g1 = fmaxf(g1, __shfl_xor(g1, o, 64)); }
+          if (lane == 0) { s_scale[0] = __fdiv_rn(g0, qmax); s_scale[1] = __fdiv_rn(g1, qmax); }
+        } else if (lane == 0) {
+          s_scale[0] = p.s_static; s_scale[1] = p.s_static;
+        }
+      }
+      __syncthreads();   // P2
+      // ---------------- exchange, step B: every workgroup writes the codes of what it produced
+      {
+        const float s0 = s_scale[0], s1 = s_scale[1];
+        auto q1 = [&](float v, float s) __attribute__((always_inline)) {
+          const float q = fminf(fmaxf(rintf(__fdiv_rn(v, s)), -qmax), qmax);
+          return s > 0.f ? (int)q : 0;
+        };
+        uint32_t* qw = reinterpret_cast<uint32_t*>(ly.qin);
+        if (l == 0) {
+          const int in = ly.in, q4 = in >> 2, n4 = p.T * q4;
+          const float4* x4 = reinterpret_cast<const float4*>(p.x);
+          for (int i = wg * 256 + e; i < n4; i += G * 256) {
+            const float4 v = x4[i];
+            const int tq = i / q4, k = (i - tq * q4) * 4;
+            const uint32_t c = (uint32_t)(uint8_t)q1(v.x, s0) | ((uint32_t)(uint8_t)q1(v.y, s0) << 8) | ((uint32_t)(uint8_t)q1(v.z, s0) << 16) |
+                               ((uint32_t)(uint8_t)q1(v.w, s0) << 24);
+            st_dev_u32(&qw[(((k >> 6) * 64 + ((k >> 4) & 3) * 16 + tq) * 16 + (k & 15)) >> 2], c);
+          }
+        } else {
+          for (int u = 0; u < nu_prev; ++u) {
+            const int32_t* ep = lp.epi + (size_t)(wg + u * G) * 32;
+            const int n_out = lp.gated ? 1 : cload_r<int>(ep, 1);
+            for (int o = 0; o < n_out; ++o) {
+              const int col = cload_r<int>(ep, 26 + o) * 16 + ch;
+#pragma unroll
+              for (int m = 0; m < 2; ++m)
+                if (m < n_in) {
+                  int c = 0;
+                  if (tok) {
+                    const int si = (u * 4 + o) * 2 + m;
+                    const float v = si < RES_STASH ? stash[si * 256 + e]
+                                                   : __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(lp.out + ((size_t)m * p.T + t) * lp.out_w + col)));
+                    c = q1(v, m == 0 ? s0 : s1);
+                  }
+                  // four neighbouring channels of a token are four neighbouring bytes of a fragment
+                  uint32_t w = (uint32_t)(uint8_t)c;
+                  w |= (uint32_t)(uint8_t)__shfl_down(c, 1, 64) << 8;
+                  w |= (uint32_t)(uint8_t)__shfl_down(c, 2, 64) << 16;
+                  w |= (uint32_t)(uint8_t)__shfl_down(c, 3, 64) << 24;
+                  if ((ch & 3) == 0 && tok)
+                    st_dev_u32(&qw[((size_t)m * ly.nks * 1024 + (size_t)(((col >> 6) * 64 + ((col >> 4) & 3) * 16 + t) * 16 + (col & 15))) >> 2], w);
+                }
+            }
+          }
+        }
+        // codes beyond in_features are zero: the first workgroup writes them
+        if (wg == 0) {
+          const int pad4 = (ly.in_pad - ly.in) >> 2;
+          for (int i = e; i < p.T * pad4 * n_in; i += 256) {
+            const int m = i / (p.T * pad4), r = i - m * (p.T * pad4);
+            const int tq = r / pad4, k = ly.in + (r - tq * pad4) * 4;
+            st_dev_u32(&qw[((size_t)m * ly.nks * 1024 + (size_t)(((k >> 6) * 64 + ((k >> 4) & 3) * 16 + tq) * 16 + (k & 15))) >> 2], 0u);
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
+      }
+      __syncthreads();   // P3
+      if (wave == RES_WORKERS) grid_wait();
+      __syncthreads();   // P4: the workers may read the codes entering layer l
+
+      // ---------------- the layer's units
+      const float sx0 = s_scale[0], sx1 = s_scale[1];
+      const int nu = units_of(ly.n_units);
+      const bool last = l == p.L - 1;
+      const bool fold_sx = ly.reduce && p.M > 1;
+      mx_out[0] = 0.f; mx_out[1] = 0.f;
+      for (int u = 0; u < nu; ++u) {
+        const int32_t* ep = ly.epi + (size_t)(wg + u * G) * 32;
+        int d[32];   // the unit's descriptor: scalar registers
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const v4i q = cload_r<v4i>(ep, i);
+          d[4 * i] = q[0]; d[4 * i + 1] = q[1]; d[4 * i + 2] = q[2]; d[4 * i + 3] = q[3];
+        }
+        const int n_items = d[0], n_out = d[1];
+        float scv[PIPE_RES_MAX_ITEMS];
+#pragma unroll
+        for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) scv[i] = i < n_items ? ly.scales[(size_t)d[18 + i] * 16 + ch] : 0.f;
+        __syncthreads();   // the workers have added up this unit's tiles
+        int a_it[PIPE_RES_MAX_ITEMS];
+#pragma unroll
+        for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
+          a_it[i] = i < n_items ? tile[buf][i][fidx] : 0;
+          if (i < n_items) tile[buf][i][fidx] = 0;
+        }
+        int rs[2] = {0, 0};
+        if (OFF != 0) {
+#pragma unroll
+          for (int m = 0; m < XM; ++m) { rs[m] = tile[buf][PIPE_RES_MAX_ITEMS + m][fidx]; tile[buf][PIPE_RES_MAX_ITEMS + m][fidx] = 0; }
+        }
+        buf ^= 1;
+        if (ly.gated) {
+          // items with slot 0 are the gate block's orders, slot 1 the up block's; h = SiLU(gate) * up per member
+          const int hcol = d[26] * 16 + ch, gcol = d[27] * 16 + ch, ucol = d[28] * 16 + ch;
+          const float bgate = ly.bias != nullptr ? ly.bias[gcol] : 0.f, bup = ly.bias != nullptr ? ly.bias[ucol] : 0.f;
+          for (int m = 0; m < p.M; ++m) {
+            const int k_lo = p.member_lo[m < PIPE_RES_MAX_M ? m : 0], k_hi = p.member_hi[m < PIPE_RES_MAX_M ? m : 0];
+            float gs = 0.f, us = 0.f;
+#pragma unroll
+            for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
+              const int kk = d[2 + i], sl = d[10 + i];
+              if (i >= n_items || kk < k_lo || kk > k_hi) continue;
+              const int a = a_it[i] - OFF * rs[0];
+              if (sl == 0) gs = fmaf(scv[i], (float)a, gs); else us = fmaf(scv[i], (float)a, us);
+            }
+            const float vg = fmaf(sx0, gs, m == 0 ? bgate : 0.f), vu = fmaf(sx0, us, m == 0 ? bup : 0.f);
+            const float h = vg / (1.f + expf(-vg)) * vu;
+            if (tok) {
+              st_dev_u32(reinterpret_cast<uint32_t*>(ly.out + ((size_t)m * p.T + t) * ly.out_w + hcol), __float_as_uint(h));
+              const int si = (u * 4) * 2 + m;
+              if (si < RES_STASH) stash[si * 256 + e] = h;
+              if (m == 0) mx_out[0] = fmaxf(mx_out[0], fabsf(h)); else mx_out[1] = fmaxf(mx_out[1], fabsf(h));
+            }
+          }
+        } else {
+          for (int o = 0; o < n_out; ++o) {
+            const int col = (o == 0 ? d[26] : (o == 1 ? d[27] : (o == 2 ? d[28] : d[29]))) * 16 + ch;
+            const float bias = ly.bias != nullptr ? ly.bias[col] : 0.f;
+            float yacc = 0.f;
+            for (int m = 0; m < p.M; ++m) {
+              const int st_m = ly.xm == 1 ? 0 : m;
+              const int rsm = st_m == 0 ? rs[0] : rs[1];
+              const float sx = st_m == 0 ? sx0 : sx1;
+              const int k_lo = p.member_lo[m < PIPE_RES_MAX_M ? m : 0], k_hi = p.member_hi[m < PIPE_RES_MAX_M ? m : 0];
+#pragma unroll
+              for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
+                const int kk = d[2 + i], sl = d[10 + i];
+                if (i >= n_items || sl != o || kk < k_lo || kk > k_hi) continue;
+                const int a = a_it[i] - OFF * rsm;
+                const float sc = fold_sx ? scv[i] * sx : scv[i];
+                yacc = fmaf(sc, (float)a, yacc);
+              }
+              if (fold_sx && m + 1 < p.M) continue;
+              const float bm = (m == 0 || fold_sx) ? bias : 0.f;
+              float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);
+              yacc = 0.f;
+              float rsum = 0.f;
+              if (ly.res != nullptr) {
+                const int n_res = ly.reduce ? ly.res_members : (m < ly.res_members ? 1 : 0);
+                const float* rp = ly.res + (size_t)(ly.reduce ? 0 : m) * ly.res_mstride + (size_t)min(t, p.T - 1) * ly.out_w + col;
+                for (int mm = 0; mm < n_res; ++mm) {
+                  // a tensor an earlier layer of this launch produced is read with device scope
+                  const float* rq = rp + (size_t)mm * ly.res_mstride;
+                  rsum += ly.res_device ? __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(rq))) : *rq;
+                }
+              }
+              if (ly.res_pre_act) v += rsum;
+              if (ly.act == PIPE_ACT_GELU) v = gelu_erf_r(v);
+              else if (ly.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
+              if (!ly.res_pre_act) v += rsum;
+              if (tok) {
+                float* dst = ly.out + ((size_t)(ly.reduce ? 0 : m) * p.T + t) * ly.out_w + col;
+                if (last) {
+                  *dst = v;
+                } else {
+                  st_dev_u32(reinterpret_cast<uint32_t*>(dst), __float_as_uint(v));
+                  const int si = (u * 4 + o) * 2 + m;
+                  if (si < RES_STASH) stash[si * 256 + e] = v;
+                  if (m == 0) mx_out[0] = fmaxf(mx_out[0], fabsf(v)); else mx_out[1] = fmaxf(mx_out[1], fabsf(v));
+                }
+              }
+            }
+          }
+        }
+      }
+      if (!last) __builtin_amdgcn_s_waitcnt(0x0F70);   // the outputs are re-read (own stores) and published in the next exchange
+    }
+    if (wg == 0 && wave == RES_WORKERS && lane == 0 && epoch != epoch0) st_dev_u32(p.gen, epoch);
+  }
+}
+
+template <int BITS, int XM>
+int launch_res(const ResParams& p, hipStream_t st) {
+  constexpr int RD = (XM == 2 && BITS == 2) ? 2 : 4;   // rounds of code registers (two half-batches); two tensors of ternary fragments leave room for two
+  static bool attr_set = false;
+  if (!attr_set) {
+    PIPE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_resident_kernel<BITS, XM, RD>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, RES_PAD_LDS));
+    attr_set = true;
+  }
+  if (pipe_dry_run()) return PIPE_OK;
+  hipLaunchKernelGGL((chain_resident_kernel<BITS, XM, RD>), dim3((unsigned)p.G), dim3(RES_THREADS), RES_PAD_LDS, st, p);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ host side
+// Work units of the resident kernel for one expansion.  kind 0: the bins of the weight-streaming kernel
+// (all orders of a few output row blocks, at most 4 items) when there are at least as many bins as
+// workgroups, else one unit per output row block; kind 1: a gate||up layer as (gate block, up block)
+// pairs, two sub-units of at most 4 items.
+int pipe_resident_tables(const pipe_expansion* ce, int kind, int G, ResidentTables* out) {
+  pipe_expansion* e = const_cast<pipe_expansion*>(ce);
+  ResidentTables& t = e->res_tables[kind];
+  if (t.subs_dev != nullptr && t.G == G) { *out = t; return PIPE_OK; }
+  if (pipe_capturing()) return PIPE_ENOTREADY;
+  if (e->bin_cap != 4 || e->K > 4) return PIPE_ESHAPE;
+  std::vector<StreamBin> bins(e->n_bins);
+  PIPE_HIP(hipMemcpy(bins.data(), e->bins_dev, bins.size() * sizeof(StreamBin), hipMemcpyDeviceToHost));
+  std::vector<int32_t> subs, epi;
+  int n_units = 0, nsub = 1;
+  auto push_sub = [&](const int* pos, const int* k, int n, int slot0, int last) {
+    int32_t s[16] = {0};
+    for (int r = 0; r < 4; ++r) { s[r] = pos[r < n ? r : 0]; s[4 + r] = r < n ? k[r] : 0; }
+    s[8] = n; s[9] = slot0; s[10] = last;
+    subs.insert(subs.end(), s, s + 16);
+  };
+  auto push_epi = [&](int n_items, int n_out, const int* k, const int* slot, const int* pos, const int* orb) {
+    int32_t s[32] = {0};
+    s[0] = n_items; s[1] = n_out;
+    for (int i = 0; i < n_items; ++i) { s[2 + i] = k[i]; s[10 + i] = slot[i]; s[18 + i] = pos[i]; }
+    for (int o = 0; o < 4; ++o) s[26 + o] = orb[o];
+    epi.insert(epi.end(), s, s + 32);
+  };
+  if (kind == 0) {
+    const bool by_bin = e->n_bins >= G;
+    struct U { int n; int pos[4], k[4], slot[4], orb[4], n_out; };
+    std::vector<U> us;
+    for (int b = 0; b < e->n_bins; ++b) {
+      const StreamBin& bn = bins[b];
+      if (by_bin) {
+        U u{};
+        u.n = bn.n_items; u.n_out = bn.n_out;
+        for (int i = 0; i < bn.n_items; ++i) { u.pos[i] = b * 4 + i; u.k[i] = bn.k[i]; u.slot[i] = bn.slot[i]; }
+        for (int o = 0; o < bn.n_out; ++o) u.orb[o] = bn.out_rb[o];
+        us.push_back(u);
+      } else {
+        for (int o = 0; o < bn.n_out; ++o) {
+          U u{};
+          u.n_out = 1; u.orb[0] = bn.out_rb[o];
+          for (int i = 0; i < bn.n_items; ++i)
+            if (bn.slot[i] == o) { u.pos[u.n] = b * 4 + i; u.k[u.n] = bn.k[i]; u.slot[u.n] = 0; ++u.n; }
+          us.push_back(u);
+        }
+      }
+    }
+    std::stable_sort(us.begin(), us.end(), [](const U& a, const U& b) { return a.n > b.n; });
+    for (const U& u : us) {
+      push_sub(u.pos, u.k, u.n, 0, 1);
+      push_epi(u.n, u.n_out, u.k, u.slot, u.pos, u.orb);
+    }
+    n_units = (int)us.size();
+  } else {
+    if (e->n_rb % 2 != 0) return PIPE_ESHAPE;
+    nsub = 2;
+    const int half = e->n_rb / 2;
+    struct P { int rb; int n; };
+    std::vector<P> ps;
+    auto items_of = [&](int rb, int* pos, int* k) {
+      int n = 0;
+      for (int kk = 0; kk < e->K; ++kk) {
+        const int32_t q = e->pos_of[(size_t)kk * e->n_rb + rb];
+        if (q >= 0) { pos[n] = q; k[n] = kk; ++n; }
+      }
+      return n;
+    };
+    for (int rb = 0; rb < half; ++rb) {
+      int pos[4], k[4];
+      ps.push_back(P{rb, items_of(rb, pos, k) + items_of(rb + half, pos, k)});
+    }
+    std::stable_sort(ps.begin(), ps.end(), [](const P& a, const P& b) { return a.n > b.n; });
+    for (const P& pr : ps) {
+      int pg[4], kg[4], pu[4], ku[4];
+      const int ng = items_of(pr.rb, pg, kg), nu = items_of(pr.rb + half, pu, ku);
+      push_sub(pg, kg, ng, 0, 0);
+      push_sub(pu, ku, nu, 4, 1);
+      int k8[8] = {0}, slot8[8] = {0}, pos8[8] = {0};
+      // the epilogue indexes the LDS tiles: gate items at 0.., up items at 4..
+      int kk[8] = {0}, ss[8] = {0}, pp[8] = {0};
+      for (int i = 0; i < ng; ++i) { kk[i] = kg[i]; ss[i] = 0; pp[i] = pg[i]; }
+      for (int i = 0; i < nu; ++i) { kk[4 + i] = ku[i]; ss[4 + i] = 1; pp[4 + i] = pu[i]; }
+      // items the blocks do not have: order -1 matches no member
+      for (int i = ng; i < 4; ++i) kk[i] = -1;
+      for (int i = nu; i < 4; ++i) kk[4 + i] = -1;
+      (void)k8; (void)slot8; (void)pos8;
+      const int orb[4] = {pr.rb, pr.rb, pr.rb + half, 0};
+      int32_t s[32] = {0};
+      s[0] = 8; s[1] = 1;
+      for (int i = 0; i < 8; ++i) { s[2 + i] = kk[i]; s[10 + i] = ss[i]; s[18 + i] = pp[i]; }
+      for (int o = 0; o < 4; ++o) s[26 + o] = orb[o];
+      epi.insert(epi.end(), s, s + 32);
+    }
+    n_units = (int)ps.size();
+  }
+  int32_t *sd = nullptr, *ed = nullptr;
+  PIPE_HIP(hipMalloc(&sd, subs.size() * 4));
+  if (hipMalloc(&ed, epi.size() * 4) != hipSuccess) { (void)hipFree(sd); return PIPE_ENOMEM; }
+  if (hipMemcpy(sd, subs.data(), subs.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(ed, epi.data(), epi.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(sd); (void)hipFree(ed);
+    return PIPE_EDEVICE;
+  }
+  if (t.subs_dev) (void)hipFree(t.subs_dev);
+  if (t.epi_dev) (void)hipFree(t.epi_dev);
+  t.subs_dev = sd; t.epi_dev = ed; t.n_units = n_units; t.nsub = nsub; t.G = G;
+  *out = t;
+  return PIPE_OK;
+}
+
+int pipe_resident_workgroups() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 64;
+    cus = std::min(n, 1024);
+  }
+  return cus;
+}
+
+int launch_resident_chain(const ResidentArgs& a, hipStream_t st) {
+  if (a.L < 1 || a.L > PIPE_RES_MAX_LAYERS || a.T < 1 || a.T > 16 || a.M < 1 || a.M > PIPE_RES_MAX_M) return PIPE_ESHAPE;
+  ResParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.L = a.L; p.T = a.T; p.M = a.M; p.G = a.G;
+  for (int m = 0; m < a.M; ++m) {
+    p.member_lo[m] = a.member_lo[m]; p.member_hi[m] = a.member_hi[m];
+    for (int k = a.member_lo[m]; k <= a.member_hi[m] && k < 4; ++k) p.member_of[k] = m;
+  }
+  p.x = a.x; p.s_static = a.s_static; p.act_qmax = g_act_qmax_host;
+  p.flags = a.flags; p.amax_tag = a.amax_tag; p.gen = a.gen; p.status = a.status;
+  p.spin_limit = g_resident_spin_limit;
+  const int bits = a.layers[0].e->bits;
+  for (int l = 0; l < a.L; ++l) {
+    const ResidentLayerArgs& la = a.layers[l];
+    const pipe_expansion* e = la.e;
+    if (e->bits != bits || e->bin_cap != 4) return PIPE_ESHAPE;
+    ResLayer& ly = p.layer[l];
+    ly.codes = e->codes_dev; ly.scales = e->scales_all_dev;
+    ly.subs = la.tables.subs_dev; ly.epi = la.tables.epi_dev;
+    ly.n_units = la.tables.n_units; ly.nsub = la.tables.nsub;
+    ly.bias = la.bias; ly.out = la.out; ly.res = la.res; ly.res_mstride = la.res_mstride;
+    ly.qin = la.qin;
+    ly.n_tiles = e->in_pad / (512 / e->bits); ly.nks = e->nks;
+    ly.out_w = la.gated ? e->out / 2 : e->out;
+    ly.in = e->in; ly.in_pad = e->in_pad;
+    ly.xm = l == 0 ? 1 : a.M;
+    ly.act = la.act; ly.res_members = la.res_members; ly.res_pre_act = la.res_pre_act; ly.gated = la.gated;
+    ly.reduce = l == a.L - 1 ? 1 : 0;
+    ly.res_device = la.res_device;
+  }
+  if (a.M == 1) {
+    switch (bits) {
+      case 8: return launch_res<8, 1>(p, st);
+      case 4: return launch_res<4, 1>(p, st);
+      default: return launch_res<2, 1>(p, st);
+    }
+  }
+  switch (bits) {
+    case 8: return launch_res<8, 2>(p, st);
+    case 4: return launch_res<4, 2>(p, st);
+    default: return launch_res<2, 2>(p, st);
+  }
+}
