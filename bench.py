@@ -33,15 +33,24 @@ INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8, vendor figure (5.0 POP/s)
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, vendor figure (8 TB/s)
 LLC_BYTES = 256 << 20           # Infinity Cache: rotate over more expansion bytes than this
 
-# HBM-side bytes per step of the contraction launches, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script, each counter scaled by what it reads for a 1 GiB device copy (FETCH_SIZE
-# x2.00, WRITE_SIZE x1.00); the summaries are under profiles/.  Counters cannot be read from
-# inside this process, so the figure is attached only to the workloads that were profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("c4", 4096): 263e6 + 180e6,
-    ("c4", 16): 22.5e6 + 0.70e6,
-    ("c5", 4096): (1.30e9 + 0.37e9) + (1.18e9 + 0.07e9),
-}
+# HBM-side bytes per step of the contraction launches come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script (each counter scaled by what it reads for a 1 GiB device copy).  Counters cannot
+# be read from inside this process: the figures live in profiles/hbm_traffic.txt, next to the summaries
+# they were taken from, one line "workload tokens fetch_bytes write_bytes" per profiled workload.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic():
+    out = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                line = line.split("#", 1)[0].split()
+                if len(line) == 4:
+                    out[(line[0], int(line[1]))] = float(line[2]) + float(line[3])
+    except OSError:
+        pass
+    return out
 
 
 def parse():
@@ -55,7 +64,12 @@ def parse():
                          "milliseconds after an idle period and 205 us from about 25 ms on)")
     ap.add_argument("--workload", default="c4",
                     help="c4 (LLM-7B linear, ternary K=4) | c5 (gated MLP, int4 K=4) | c3 | c2 | c1 | "
-                         "chain (residual stack of 8 layers, ternary K=8, as member chains)")
+                         "chain (residual stack of 8 layers, ternary K=8, as member chains) | "
+                         "stack (decode stack: 8 layers of the c4 shape, 11008x4096 and back, as one chain)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the rows of the other workloads (c5 at 1, 16, 4096 tokens; the decode stack at 1, 16)")
+    ap.add_argument("--resident", type=int, default=1,
+                    help="decode-sized chains as one resident launch: 0 never, 1 automatic, 2 whenever possible")
     ap.add_argument("--tokens", type=int, default=0, help="override the headline token count")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -88,6 +102,7 @@ def main():
     pipe.pipe_set_kernel(args.kernel)
     pipe.pipe_set_stream_split(args.stream_split)
     pipe.pipe_set_token_tile(args.token_tile)
+    pipe.pipe_set_decode_resident(args.resident)
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
         b = torch.empty_like(a)
@@ -98,132 +113,165 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "calibrate_copy_bytes_written": a.numel() * 4}))
         return
 
-    cfg = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "chain": wl.CHAIN}[args.workload]
-    T_head = args.tokens or cfg.tokens
-
-    # ---- build the expansion(s) once (offline step a0) ------------------------------------
-    t0 = time.time()
-    Ws = [torch.from_numpy(wl.make_weight(cfg, i)).to(dev) for i in range(len(cfg.layers))]
-
-    def build():
-        return [pipe.pipe_expand(Ws[i], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
-
-    torch.cuda.synchronize()
-    t1 = time.time()
-    exps = [build()]
-    torch.cuda.synchronize()
-    expand_s = time.time() - t1
-    stream_bytes = sum(e.packed_bytes for e in exps[0])
-    macs_per_token = sum(e.macs_per_token() for e in exps[0])
-    gen_s = t1 - t0
-
-    x_full = wl.make_input(cfg if cfg.kind == "conv2d" else wl.with_tokens(cfg, max(T_head, 4096)))
-    xd_full = torch.from_numpy(x_full).to(dev)
-    split = list(cfg.split) if len(cfg.split) > 1 else None
-
+    WORKLOADS = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "chain": wl.CHAIN, "stack": wl.DECODE_STACK}
     chain_act = {"none": pipe.PIPE_ACT_NONE, "relu": pipe.PIPE_ACT_RELU, "gelu": pipe.PIPE_ACT_GELU}
+    traffic = measured_traffic()
 
-    static_sx = [0.0]   # > 0: the activation scale is given (the paper's static ranges) instead of max|x| / 127
+    class Runner:
+        """One workload: its expansions (built once, offline step a0; further copies for rotation), input, step."""
 
-    def step_fn(e, xd, out=None, split=split):
-        if cfg.kind == "linear" and static_sx[0] > 0:
-            return pipe.pipe_forward(e[0], xd, s_x=static_sx[0], split=split, out=out)
-        if cfg.kind == "chain":
-            layers = [(e[i], None, chain_act[c[0]], c[1], c[2]) for i, c in enumerate(cfg.chain)]
-            return pipe.pipe_chain_forward(layers, xd, split=split, out=out)
-        if cfg.kind == "linear":
-            return pipe.pipe_forward(e[0], xd, split=split, out=out)
-        if cfg.kind == "conv2d":
-            c = cfg.conv
-            return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split, out=out)
-        act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
-        return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split, out=out)
-
-    def io_bytes(T):
-        """Bytes the contraction launches of one step must move besides the packed codes:
-        int8 activations in, fp32 results out (hidden activations of an MLP: out and back in)."""
-        M = len(split) if split else 1
-        b = 0
-        for i, l in enumerate(cfg.layers):
-            last = i == len(cfg.layers) - 1
-            b += T * l.in_features * (1 if i == 0 else M)
-            b += 4 * T * l.out_features * (1 if last else M)
-            if cfg.chain is not None and cfg.chain[i][1] >= 0:     # the skip tensor is read once more
-                b += 4 * T * l.out_features * (1 if cfg.chain[i][1] == 0 else M)
-        return b
-
-    def measure(T, steps, warmup, rotate, settle_ms=None, graph=True):
-        """Times `steps` passes; returns dict with step time and contraction-kernel time."""
-        settle_ms = args.settle_ms if settle_ms is None else settle_ms
-        xd = xd_full if cfg.kind == "conv2d" else xd_full[:T].contiguous()
-        out = torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
-        copies = 1
-        if rotate:
-            copies = max(2, -(-int(1.25 * LLC_BYTES) // max(stream_bytes, 1)))
-            while len(exps) < copies:
-                exps.append(build())
-        # sustained load first (clocks settle), then the W warm-up steps
-        t_s, i_s = time.perf_counter(), 0
-        while (time.perf_counter() - t_s) * 1e3 < settle_ms:
-            for _ in range(8):
-                step_fn(exps[i_s % copies], xd, out)
-                i_s += 1
+        def __init__(self, name):
+            self.name = name
+            cfg = self.cfg = WORKLOADS[name]
+            t0 = time.time()
+            # the decode stack repeats two shapes: the layers share the two fp32 weights, every layer has
+            # its own expansion (its own codes in HBM)
+            n_w = 2 if name == "stack" else len(cfg.layers)
+            self.Ws = [torch.from_numpy(wl.make_weight(cfg, i)).to(dev) for i in range(n_w)]
             torch.cuda.synchronize()
-        for i in range(warmup):
-            step_fn(exps[i % copies], xd, out)
-        torch.cuda.synchronize()
-        # ---- K steps, eager, contraction kernels bracketed by events on the launch stream ----
-        pipe.pipe_timing_read()
-        pipe.pipe_timing_enable(True)
-        torch.cuda.synchronize()
-        t_a = time.perf_counter()
-        for i in range(steps):
-            step_fn(exps[i % copies], xd, out)
-        torch.cuda.synchronize()
-        t_b = time.perf_counter()
-        pipe.pipe_timing_enable(False)
-        k_ms, k_n = pipe.pipe_timing_read()
-        step_ms = (t_b - t_a) * 1e3 / steps
-        mode = "eager"
-        # ---- the same K steps as ONE HIP graph: decode-sized steps are launch bound, and the small
-        # layers' five launches leave gaps as long as their kernels when launched eagerly --------
-        if graph and not args.no_graph:
-            try:
-                side = torch.cuda.Stream()
-                side.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(side):          # the library keeps its scratch per stream: warm the capture stream
-                    for i in range(max(2, copies)):
-                        step_fn(exps[i % copies], xd, out)
-                torch.cuda.current_stream().wait_stream(side)
+            t1 = time.time()
+            self.exps = [self.build()]
+            torch.cuda.synchronize()
+            self.expand_s = time.time() - t1
+            self.gen_s = t1 - t0
+            self.stream_bytes = sum(e.packed_bytes for e in self.exps[0])
+            self.macs_per_token = sum(e.macs_per_token() for e in self.exps[0])
+            self.T_max = cfg.tokens if cfg.kind == "conv2d" else (16 if name == "stack" else 4096)
+            self.x_full = wl.make_input(cfg if cfg.kind == "conv2d" else wl.with_tokens(cfg, self.T_max))
+            self.xd_full = torch.from_numpy(self.x_full).to(dev)
+            self.split = list(cfg.split) if len(cfg.split) > 1 else None
+            self.static_sx = 0.0   # > 0: the activation scale is given (the paper's static ranges) instead of max|x| / 127
+
+        def build(self):
+            cfg = self.cfg
+            return [pipe.pipe_expand(self.Ws[i % len(self.Ws)], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
+
+        def free(self):
+            for es in self.exps:
+                for e in es:
+                    e.free()
+            self.exps = []
+
+        def step_fn(self, e, xd, out=None, split="default"):
+            cfg = self.cfg
+            split = self.split if split == "default" else split
+            if cfg.kind == "linear" and self.static_sx > 0:
+                return pipe.pipe_forward(e[0], xd, s_x=self.static_sx, split=split, out=out)
+            if cfg.kind == "chain":
+                layers = [(e[i], None, chain_act[c[0]], c[1], c[2]) for i, c in enumerate(cfg.chain)]
+                return pipe.pipe_chain_forward(layers, xd, split=split, out=out)
+            if cfg.kind == "linear":
+                return pipe.pipe_forward(e[0], xd, split=split, out=out)
+            if cfg.kind == "conv2d":
+                c = cfg.conv
+                return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split, out=out)
+            act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
+            return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split, out=out)
+
+        def io_bytes(self, T):
+            """Bytes the contraction launches of one step must move besides the packed codes:
+            int8 activations in, fp32 results out (hidden activations of an MLP: out and back in)."""
+            cfg = self.cfg
+            M = len(self.split) if self.split else 1
+            b = 0
+            for i, l in enumerate(cfg.layers):
+                last = i == len(cfg.layers) - 1
+                b += T * l.in_features * (1 if i == 0 else M)
+                b += 4 * T * l.out_features * (1 if last else M)
+                if cfg.chain is not None and cfg.chain[i][1] >= 0:     # the skip tensor is read once more
+                    b += 4 * T * l.out_features * (1 if cfg.chain[i][1] == 0 else M)
+            return b
+
+        def measure(self, T, steps, warmup, rotate, settle_ms=None, graph=True):
+            """Times `steps` passes; returns dict with step time and contraction-kernel time."""
+            cfg, exps = self.cfg, self.exps
+            settle_ms = args.settle_ms if settle_ms is None else settle_ms
+            xd = self.xd_full if cfg.kind == "conv2d" else self.xd_full[:T].contiguous()
+            out = torch.empty((T, cfg.layers[-1].out_features), dtype=torch.float32, device=dev)
+            copies = 1
+            if rotate:
+                copies = max(2, -(-int(1.25 * LLC_BYTES) // max(self.stream_bytes, 1)))
+                while len(exps) < copies:
+                    exps.append(self.build())
+            step_fn = self.step_fn
+            # sustained load first (clocks settle), then the W warm-up steps
+            t_s, i_s = time.perf_counter(), 0
+            while (time.perf_counter() - t_s) * 1e3 < settle_ms:
+                for _ in range(8):
+                    step_fn(exps[i_s % copies], xd, out)
+                    i_s += 1
                 torch.cuda.synchronize()
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=side):
-                    for i in range(steps):
-                        step_fn(exps[i % copies], xd, out)
-                t_s = time.perf_counter()      # capture left the chip idle: load it again before the timed replay
-                g.replay()
-                torch.cuda.synchronize()
-                while (time.perf_counter() - t_s) * 1e3 < settle_ms:
+            for i in range(warmup):
+                step_fn(exps[i % copies], xd, out)
+            torch.cuda.synchronize()
+            # ---- K steps, eager, contraction kernels bracketed by events on the launch stream ----
+            pipe.pipe_timing_read()
+            pipe.pipe_timing_enable(True)
+            torch.cuda.synchronize()
+            t_a = time.perf_counter()
+            for i in range(steps):
+                step_fn(exps[i % copies], xd, out)
+            torch.cuda.synchronize()
+            t_b = time.perf_counter()
+            pipe.pipe_timing_enable(False)
+            k_ms, k_n = pipe.pipe_timing_read()
+            step_ms = (t_b - t_a) * 1e3 / steps
+            mode = "eager"
+            # ---- the same K steps as ONE HIP graph: decode-sized steps are launch bound, and the small
+            # layers' five launches leave gaps as long as their kernels when launched eagerly --------
+            if graph and not args.no_graph:
+                try:
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(side):          # the library keeps its scratch per stream: warm the capture stream
+                        for i in range(max(2, copies)):
+                            step_fn(exps[i % copies], xd, out)
+                    torch.cuda.current_stream().wait_stream(side)
+                    torch.cuda.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        for i in range(steps):
+                            step_fn(exps[i % copies], xd, out)
+                    t_s = time.perf_counter()      # capture left the chip idle: load it again before the timed replay
                     g.replay()
                     torch.cuda.synchronize()
-                t_a = time.perf_counter()
-                g.replay()
-                torch.cuda.synchronize()
-                t_b = time.perf_counter()
-                step_ms = (t_b - t_a) * 1e3 / steps
-                mode = "hipgraph"
-            except Exception as ex:      # keep the eager number
-                mode = "eager (graph capture failed: %s)" % type(ex).__name__
-        per_step_kernel_ms = k_ms / steps
-        ops = 2.0 * T * macs_per_token
-        alg_bytes = stream_bytes + io_bytes(T)
-        return dict(tokens=T, ms_per_step=step_ms, kernel_ms_per_step=per_step_kernel_ms,
-                    kernel_launches_per_step=k_n / steps, step_mode=mode,
-                    eff_tops=ops / (step_ms * 1e-3) / 1e12,
-                    kernel_eff_tops=ops / (per_step_kernel_ms * 1e-3) / 1e12 if k_ms > 0 else None,
-                    tokens_per_s=T / (step_ms * 1e-3),
-                    kernel_gbs=alg_bytes / (per_step_kernel_ms * 1e-3) / 1e9 if k_ms > 0 else None,
-                    alg_bytes=alg_bytes, expansion_copies=copies)
+                    while (time.perf_counter() - t_s) * 1e3 < settle_ms:
+                        g.replay()
+                        torch.cuda.synchronize()
+                    t_a = time.perf_counter()
+                    g.replay()
+                    torch.cuda.synchronize()
+                    t_b = time.perf_counter()
+                    step_ms = (t_b - t_a) * 1e3 / steps
+                    mode = "hipgraph"
+                except Exception as ex:      # keep the eager number
+                    mode = "eager (graph capture failed: %s)" % type(ex).__name__
+            per_step_kernel_ms = k_ms / steps
+            ops = 2.0 * T * self.macs_per_token
+            alg_bytes = self.stream_bytes + self.io_bytes(T)
+            return dict(tokens=T, ms_per_step=step_ms, kernel_ms_per_step=per_step_kernel_ms,
+                        kernel_launches_per_step=k_n / steps, step_mode=mode,
+                        eff_tops=ops / (step_ms * 1e-3) / 1e12,
+                        kernel_eff_tops=ops / (per_step_kernel_ms * 1e-3) / 1e12 if k_ms > 0 else None,
+                        tokens_per_s=T / (step_ms * 1e-3),
+                        kernel_gbs=alg_bytes / (per_step_kernel_ms * 1e-3) / 1e9 if k_ms > 0 else None,
+                        step_gbs=alg_bytes / (step_ms * 1e-3) / 1e9,
+                        alg_bytes=alg_bytes, expansion_copies=copies)
+
+    def fractions(r):
+        """Roofline fractions of a row: the contraction kernels alone and the whole step."""
+        r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
+        r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
+        r["step_mfma_frac"] = r["eff_tops"] / INT8_MFMA_PEAK_TOPS
+        r["step_hbm_frac"] = r["step_gbs"] / HBM_PEAK_GBS
+        return {k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()}
+
+    run = Runner(args.workload)
+    cfg, Ws, exps = run.cfg, run.Ws, run.exps
+    x_full, xd_full, split = run.x_full, run.xd_full, run.split
+    stream_bytes, macs_per_token, expand_s, gen_s = run.stream_bytes, run.macs_per_token, run.expand_s, run.gen_s
+    T_head = args.tokens or cfg.tokens
+    measure, step_fn = run.measure, run.step_fn
 
     T0 = cfg.tokens if cfg.kind == "conv2d" else T_head
     # the same workload from an idle chip first (no sustained load before it, 5 warm-up steps, 50
@@ -235,24 +283,30 @@ def main():
     # ranges): no max|x| reduction in the step.  Reported next to the headline, which keeps the dynamic scale.
     static = None
     if cfg.kind == "linear":
-        static_sx[0] = float(xd_full[:T0].abs().max().item()) / 127.0
+        run.static_sx = float(xd_full[:T0].abs().max().item()) / 127.0
         r = measure(T0, args.steps, args.warmup, rotate=(T0 <= 128))
-        static_sx[0] = 0.0
+        run.static_sx = 0.0
         static = {"ms_per_step": r["ms_per_step"], "eff_tops": r["eff_tops"], "tokens_per_s": r["tokens_per_s"],
                   "step_mode": r["step_mode"]}
 
+    # the dominant kernel's roofline (its own launch duration) and, next to it, the same figure over
+    # the whole step (activation quantization included)
     mfma_bound = T0 > 128
+    one_launch = head["kernel_launches_per_step"] <= 1.0 and cfg.kind in ("chain", "mlp_gelu", "mlp_gated") and T0 <= 16
     if mfma_bound:
         roofline = dict(bound="mfma", achieved=head["kernel_eff_tops"], peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
                         frac=(head["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS, traffic=None,
-                        kernel="gemm_tiled_kernel", kernel_ms=head["kernel_ms_per_step"])
+                        kernel="gemm_tiled_kernel", kernel_ms=head["kernel_ms_per_step"],
+                        step_achieved=head["eff_tops"], step_frac=head["eff_tops"] / INT8_MFMA_PEAK_TOPS)
     else:
         roofline = dict(bound="hbm", achieved=head["kernel_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=(head["kernel_gbs"] or 0) / HBM_PEAK_GBS, traffic=None,
-                        kernel="gemm_stream_kernel" if cfg.layers[0].K <= 4 else "gemm_tiled_kernel (K > 4: no streaming variant)",
-                        kernel_ms=head["kernel_ms_per_step"])
+                        kernel=("chain_resident_kernel" if one_launch else
+                                "gemm_stream_kernel" if cfg.layers[0].K <= 4 else "gemm_stream_multi_kernel"),
+                        kernel_ms=head["kernel_ms_per_step"],
+                        step_achieved=head["step_gbs"], step_frac=head["step_gbs"] / HBM_PEAK_GBS)
 
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, T0))
+    roofline["traffic"] = traffic.get((args.workload, T0))
     roofline["algorithmic_bytes"] = head["alg_bytes"]
 
     sweep = []
@@ -268,9 +322,22 @@ def main():
                 r["resident_ms_per_step"] = rr["ms_per_step"]
                 r["resident_kernel_ms_per_step"] = rr["kernel_ms_per_step"]
                 r["resident_kernel_gbs"] = rr["kernel_gbs"]
-            r["mfma_frac"] = (r["kernel_eff_tops"] or 0) / INT8_MFMA_PEAK_TOPS
-            r["hbm_frac"] = (r["kernel_gbs"] or 0) / HBM_PEAK_GBS
-            sweep.append({k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()})
+            sweep.append(fractions(r))
+
+    # ---- the other workloads' rows: the largest config (gated MLP) at decode and prefill sizes, and the
+    # decode stack (8 layers of this run's headline shape in one chain), each with both rooflines
+    extra = []
+    if not args.no_extra and not args.no_sweep and args.workload == "c4":
+        for name, tokens in (("c5", (1, 16, 4096)), ("stack", (1, 16))):
+            other = Runner(name)
+            for T in tokens:
+                r = other.measure(T, max(10, args.steps // 2), 3, rotate=(T <= 128))
+                r["workload"] = other.cfg.name
+                r["traffic"] = traffic.get((name, T))
+                extra.append(fractions(r))
+            other.free()
+            del other
+            torch.cuda.empty_cache()
 
     # ---- the run-time comparison of the ensembles (a chain workload only): the same network and
     # the same K under the groupings of the paper's run-time table, and the unexpanded K = 1 net
@@ -327,7 +394,7 @@ def main():
             cores = os.cpu_count() or 1
         O_s = cfg.layers[0].out_features
         l0 = cfg.layers[0]
-        if cfg.kind == "linear":
+        if cfg.kind == "linear" or args.workload == "stack":
             T_s = min(T0, 4096)
             Wn = Ws[0][:O_s].cpu().numpy()
             ex = po.expand(Wn, l0.bits, l0.K, l0.gamma, l0.group)
@@ -340,7 +407,8 @@ def main():
                 passes += 1
             macs = passes * po.expansion_macs(ex, T_s)
             sample = ("%d passes of forward (quantize, contract, de-quantize) over all %d output channels and "
-                      "%d tokens; expansion built outside the timer" % (passes, O_s, T_s))
+                      "%d tokens%s; expansion built outside the timer"
+                      % (passes, O_s, T_s, " of the stack's first layer" if args.workload == "stack" else ""))
         elif cfg.kind == "chain":
             l0 = cfg.layers[0]
             small = wl.residual_stack(l0.out_features // 4, (len(cfg.layers) - 2) // 2, cfg.layers[-1].out_features // 4,
@@ -415,6 +483,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "sweep": sweep,
+        "other_workloads": extra,
         "ensemble_ms_per_step": ensemble_ms,
         "spectral_norm": spectral,
         # reference rates of this chip (not targets): MFMA-only loop with constant operands, with

@@ -426,14 +426,17 @@ int pipe_set_stream_split(int workgroups_per_bin);
  * setting.  Returns PIPE_EINVAL for other values.                                    */
 int pipe_set_decode_fusion(int on);
 
-/* Decode-sized batches (at most 16 tokens) through pipe_chain_forward and pipe_mlp_forward: by default
- * the whole chain of layers runs as ONE resident launch (one workgroup per compute unit walks the
+/* Decode-sized batches (at most 16 tokens) through pipe_chain_forward and pipe_mlp_forward: the
+ * whole chain of layers can run as ONE resident launch (one workgroup per compute unit walks the
  * layers; the packed codes of the next layer stream from HBM while the current layer's results are
  * exchanged between the workgroups) instead of two launches per layer.  Conditions: fully-connected
  * layers only, at most 4 orders and at most 2 members, every layer stored at the same code width, at most
- * 16 layers, in_features of the first layer a multiple of 4 and a 16-byte aligned input; otherwise,
- * and with 0 here, the calls take the per-layer launches.  Results do not depend on the setting (the
- * fp32 arithmetic and its order are those of the per-layer kernels).  Returns PIPE_EINVAL for other values.
+ * 16 layers, in_features of the first layer a multiple of 4 and a 16-byte aligned input; otherwise
+ * the calls take the per-layer launches.  `on`: 0 never, 2 whenever the conditions hold, 1 (default)
+ * where it measured faster: chains of three or more layers at any batch, shorter chains and the MLP
+ * call from 8 tokens on (the exchange between workgroups costs about 8 us per layer, two launches
+ * per layer about 10-17 us).  Results do not depend on the setting (the fp32 arithmetic and its
+ * order are those of the per-layer kernels).  Returns PIPE_EINVAL for other values.
  * The resident launch needs every workgroup of its grid on the chip at once; its waits for other
  * workgroups are bounded (pipe_set_resident_spin_limit polls, 0 = the default of 2^19, about a second):
  * a workgroup whose wait runs out records it and runs to its end without waiting again, so the launch
@@ -444,6 +447,13 @@ int pipe_set_decode_fusion(int on);
 int pipe_set_decode_resident(int on);
 int pipe_set_resident_spin_limit(int polls);
 int pipe_resident_status(void* stream, int* status_out);
+/* Profiling of the resident launch: with trace_dev != NULL (DEVICE, [workgroups][layers][8] 64-bit
+ * words, workgroups = compute units of the chip) every later resident launch records, per workgroup and
+ * layer, the time (100 MHz counter) at which 0 the exchange before the layer begins, 1 the scales are
+ * known, 2 its codes are stored, 3 all workgroups' codes are visible, 4 its last unit's outputs are
+ * written, 7 its first worker wave has multiplied its last round (5, 6 unused).  NULL switches it off
+ * (default).  Process-wide.                                                                          */
+int pipe_resident_trace(unsigned long long* trace_dev);
 
 /* Kernel timing for benchmarks.  While enabled, every forward call brackets its
  * contraction kernel (the dominant kernel of the path) with a pair of HIP events

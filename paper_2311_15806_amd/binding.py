@@ -79,6 +79,7 @@ def _load():
     lib.pipe_set_decode_resident.argtypes = [ci]
     lib.pipe_set_resident_spin_limit.argtypes = [ci]
     lib.pipe_resident_status.argtypes = [vp, pi]
+    lib.pipe_resident_trace.argtypes = [vp]
     lib.pipe_set_token_tile.argtypes = [ci]
     lib.pipe_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), vp]
     lib.pipe_hbm_probe.argtypes = [C.c_int64, C.POINTER(C.c_double), vp]
@@ -561,8 +562,9 @@ def pipe_set_decode_fusion(on: bool) -> None:
     _check(_lib.pipe_set_decode_fusion(1 if on else 0), "pipe_set_decode_fusion")
 
 
-def pipe_set_decode_resident(on: bool) -> None:
-    _check(_lib.pipe_set_decode_resident(1 if on else 0), "pipe_set_decode_resident")
+def pipe_set_decode_resident(on) -> None:
+    """0 / False: per-layer launches; 1: automatic (default); 2 / True: the resident launch whenever it applies."""
+    _check(_lib.pipe_set_decode_resident(2 if on is True else int(on)), "pipe_set_decode_resident")
 
 
 def pipe_set_resident_spin_limit(polls: int) -> None:
@@ -574,6 +576,11 @@ def pipe_resident_status() -> int:
     v = C.c_int()
     _check(_lib.pipe_resident_status(_stream(), C.byref(v)), "pipe_resident_status")
     return v.value
+
+
+def pipe_resident_trace(buf: Optional[torch.Tensor]) -> None:
+    """buf: int64 device tensor [compute units, layers, 8] that later resident launches fill with phase timestamps; None = off."""
+    _check(_lib.pipe_resident_trace(None if buf is None else _ptr(buf, torch.int64)), "pipe_resident_trace")
 
 
 def pipe_timing_enable(on: bool) -> None:

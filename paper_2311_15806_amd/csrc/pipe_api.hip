@@ -146,8 +146,13 @@ extern "C" int pipe_set_decode_fusion(int on) {
 }
 
 extern "C" int pipe_set_decode_resident(int on) {
-  if (on != 0 && on != 1) return PIPE_EINVAL;
+  if (on < 0 || on > 2) return PIPE_EINVAL;
   g_decode_resident = on;
+  return PIPE_OK;
+}
+
+extern "C" int pipe_resident_trace(unsigned long long* trace_dev) {
+  g_resident_trace = trace_dev;
   return PIPE_OK;
 }
 
@@ -696,20 +701,27 @@ static int quantize_input(const float* x_dev, int T, int in, int in_pad, float s
   return launch_quantize_act(x_dev, T, in, in_pad, b.T_pad, s_x, b.amax, b.qx, b.rowsum, dynamic, qx_rowmajor, scale_out, st);
 }
 
+// While timing is on: the pair of events the next contraction launch records its begin and end into.
+static int timing_events(hipEvent_t* ev0, hipEvent_t* ev1, bool* timed) {
+  *timed = g_timing_on && g_events_used / 2 < MAX_TIMED;
+  if (!*timed) return PIPE_OK;
+  while (g_events.size() < g_events_used + 2) {
+    hipEvent_t ev;
+    PIPE_HIP(hipEventCreate(&ev));
+    g_events.push_back(ev);
+  }
+  *ev0 = g_events[g_events_used];
+  *ev1 = g_events[g_events_used + 1];
+  return PIPE_OK;
+}
+
 static int run_gemm(const GemmArgs& a0, bool small, hipStream_t st) {
   if (pipe_dry_run()) return PIPE_OK;
   GemmArgs a = a0;
-  const bool timed = g_timing_on && g_events_used / 2 < MAX_TIMED;
-  if (timed) {
-    while (g_events.size() < g_events_used + 2) {
-      hipEvent_t ev;
-      PIPE_HIP(hipEventCreate(&ev));
-      g_events.push_back(ev);
-    }
-    a.ev_start = g_events[g_events_used];
-    a.ev_stop = g_events[g_events_used + 1];
-  }
-  const int rc = small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
+  bool timed = false;
+  int rc = timing_events(&a.ev_start, &a.ev_stop, &timed);
+  if (rc) return rc;
+  rc = small ? launch_gemm_stream(a, st) : launch_gemm_tiled(a, st);
   if (timed && rc == PIPE_OK) g_events_used += 2;
   return rc;
 }
@@ -1184,6 +1196,7 @@ struct ResidentLayerSpec {
 
 static bool resident_eligible(const pipe_expansion* const* es, int L, int T, int M, const float* x_dev) {
   if (!g_decode_resident || g_kernel_choice == 1) return false;
+  if (g_decode_resident == 1 && L < 3 && T < 8) return false;   // automatic: where it measured faster
   if (T < 1 || T > 16 || M > PIPE_RES_MAX_M || L > PIPE_RES_MAX_LAYERS) return false;
   if (es[0]->in % 4 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15) != 0) return false;
   for (int l = 0; l < L; ++l)
@@ -1224,7 +1237,19 @@ static int run_resident(const ResidentLayerSpec* ls, int L, const float* x_dev, 
     la.act = ls[l].act; la.gated = ls[l].gated;
     la.qin = qbuf + q_off[l];
   }
-  return launch_resident_chain(a, st);
+  // the busiest workgroup's unit descriptors have to fit the kernel's LDS copy; else the caller
+  // takes the per-layer launches
+  int desc_ints = 0;
+  for (int l = 0; l < L; ++l) desc_ints += ceil_div(a.layers[l].tables.n_units, a.G) * (a.layers[l].tables.nsub * 16 + 32);
+  if (desc_ints > PIPE_RES_DESC_INTS) return 1;
+  bool timed = false;
+  if (!pipe_dry_run()) {
+    int rc = timing_events(&a.ev_start, &a.ev_stop, &timed);
+    if (rc) return rc;
+  }
+  const int rc = launch_resident_chain(a, st);
+  if (timed && rc == PIPE_OK) g_events_used += 2;
+  return rc;
 }
 
 extern "C" int pipe_resident_status(void* stream, int* status_out) {
@@ -1278,7 +1303,8 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
       ls[0].e = l1; ls[0].bias = bias1_dev; ls[0].out = h; ls[0].act = gated ? PIPE_ACT_NONE : PIPE_ACT_GELU; ls[0].gated = gated ? 1 : 0;
       ls[0].res_pre_act = 1;
       ls[1].e = l2; ls[1].bias = bias2_dev; ls[1].out = y_dev; ls[1].act = PIPE_ACT_NONE; ls[1].res_pre_act = 1;
-      return run_resident(ls, 2, x_dev, T, s_x, Mm, lo, hi, st);
+      rc = run_resident(ls, 2, x_dev, T, s_x, Mm, lo, hi, st);
+      if (rc != 1) return rc;   // 1: does not fit the resident kernel, per-layer launches below
     }
   }
   // the tiled kernel pairs gate and up blocks in one workgroup and writes h directly; otherwise
@@ -1493,7 +1519,8 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
           ls[l].res = act[ly.skip_from - 1]; ls[l].res_mstride = (long long)T * ly.e->out; ls[l].res_members = Mm; ls[l].res_device = 1;
         }
       }
-      return run_resident(ls.data(), L, x_dev, T, s_x, Mm, lo, hi, st);
+      rc = run_resident(ls.data(), L, x_dev, T, s_x, Mm, lo, hi, st);
+      if (rc != 1) return rc;   // 1: does not fit the resident kernel, per-layer launches below
     }
   }
   for (int l = 0; l < L; ++l)

@@ -99,6 +99,7 @@ struct PassTables {
 constexpr int PIPE_RES_MAX_LAYERS = 16;
 constexpr int PIPE_RES_MAX_M = 2;
 constexpr int PIPE_RES_MAX_ITEMS = 8;
+constexpr int PIPE_RES_DESC_INTS = 4096;   // LDS copy of one workgroup's unit descriptors, all layers
 struct ResidentTables {
   int32_t* subs_dev = nullptr;
   int32_t* epi_dev = nullptr;
@@ -345,12 +346,14 @@ struct ResidentArgs {
   unsigned long long* amax_tag;
   uint32_t* gen;
   uint32_t* status;
+  hipEvent_t ev_start, ev_stop;    // if set: the dispatch's own begin/end timestamps
 };
 int pipe_resident_workgroups();   // one per compute unit
 int pipe_resident_tables(const pipe_expansion* e, int kind, int G, ResidentTables* out);
 int launch_resident_chain(const ResidentArgs& a, hipStream_t st);
 extern int g_decode_resident;        // 1: chains of decode-sized batches run as one resident launch
 extern int g_resident_spin_limit;    // polls of a grid-wide wait before a workgroup gives up
+extern unsigned long long* g_resident_trace;   // profiling buffer of the resident kernel, or nullptr
 extern int g_tiled_mtb;       // token blocks per tile of the tiled kernel; 0 = automatic
 extern int g_stream_ksplit;   // workgroups per bin of the streaming kernel; 0 = automatic
 extern int g_decode_fusion;   // 1: batches of at most 4 tokens are quantized inside the streaming kernel

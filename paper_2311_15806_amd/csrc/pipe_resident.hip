@@ -32,6 +32,7 @@
 
 int g_decode_resident = 1;
 int g_resident_spin_limit = 1 << 19;
+unsigned long long* g_resident_trace = nullptr;
 
 namespace {
 
@@ -73,6 +74,7 @@ struct ResParams {
   uint32_t* gen;            // epoch the previous launch on this scratch ended with
   uint32_t* status;         // != 0: a wait ran into the spin limit
   int spin_limit;
+  unsigned long long* trace;   // profiling: [G][L][8] timestamps (100 MHz) of the phases of every layer, or nullptr
 };
 
 static_assert(sizeof(ResParams) <= 3584, "kernel arguments are limited to 4 KiB");
@@ -120,6 +122,11 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
   __shared__ float s_wmax[RES_EPI][2];
   __shared__ float s_scale[2];   // scales of the codes entering the current layer
   __shared__ int s_fail;
+  __shared__ uint32_t s_seen;   // the last epoch one of the polling waves has seen every workgroup reach
+  // this workgroup's unit descriptors of all layers, copied once (a cold scalar load per unit on the
+  // workers' path costs more than the unit's arithmetic): per layer, per local unit, its sub-units
+  // (16 ints each) and then its epilogue descriptor (32 ints)
+  __shared__ int s_desc[PIPE_RES_DESC_INTS];
   extern __shared__ int pad_lds[];
 
   const int lane = threadIdx.x & 63;
@@ -127,15 +134,34 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
   const int wg = blockIdx.x, G = p.G;
   for (int i = threadIdx.x; i < 2 * (PIPE_RES_MAX_ITEMS + 2) * 256; i += RES_THREADS) (&tile[0][0][0])[i] = 0;
   if (threadIdx.x == 0) { s_fail = 0; s_scale[0] = 0.f; s_scale[1] = 0.f; }
-  __syncthreads();
   auto units_of = [&](int n_units) { return n_units > wg ? (n_units - wg + G - 1) / G : 0; };
+  auto dstride_of = [&](int l) { return p.layer[l].nsub * 16 + 32; };
+  {
+    int off = 0;
+    for (int l = 0; l < p.L; ++l) {
+      const ResLayer& ly = p.layer[l];
+      const int stride = ly.nsub * 16 + 32, cnt = units_of(ly.n_units) * stride;
+      for (int i = threadIdx.x; i < cnt; i += RES_THREADS) {
+        const int u = i / stride, w = i - u * stride;
+        const size_t unit = (size_t)(wg + u * G);
+        s_desc[off + i] = w < ly.nsub * 16 ? ly.subs[unit * ly.nsub * 16 + w] : ly.epi[unit * 32 + (w - ly.nsub * 16)];
+      }
+      off += cnt;   // the host has checked that all layers fit
+    }
+  }
+  __syncthreads();
+  auto dword = [&](int i) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(s_desc[i]); };
+  // profiling: slot 0 exchange begins, 1 maxima known, 2 codes stored, 3 all flags seen, 4 last unit's epilogue done
+  // (first epilogue wave); 7 worker wave 0 has multiplied its last round and passed the unit's barrier
+  auto stamp = [&](int l, int slot) __attribute__((always_inline)) {
+    if (p.trace != nullptr && lane == 0) p.trace[((size_t)wg * p.L + l) * 8 + slot] = wall_clock64();
+  };
 
   if (wave < RES_WORKERS) {
     // ============================================================== workers
     // The loads of a step are unconditional and their number fixed (a step without real work loads
-    // a valid address and drops the result), so the waits for them are exact counts: the codes of the
-    // next half-batch stay in flight while the current one is multiplied.
-    constexpr int HB = RD / 2;             // rounds of a half-batch
+    // a valid address and drops the result), so the waits for them are exact counts: RD - 1 rounds of
+    // codes (across layer boundaries) and a round of fragments stay in flight while a round is multiplied.
     constexpr int NXL = XM * STEPS;        // fragment loads of a round
     const bool xlive = (lane & 15) < p.T;
     // lanes of tokens beyond the batch re-read token 0's bytes of their k chunk (no further cache lines) and are zeroed
@@ -145,13 +171,13 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
     for (int r = 0; r < 4; ++r) acc[r] = v4i{0, 0, 0, 0};
 #pragma unroll
     for (int m = 0; m < XM; ++m) acc1[m] = v4i{0, 0, 0, 0};
-    uint4 wreg[2][HB][4], xreg[HB][NXL];
+    // a ring of RD rounds of codes (round q of a layer lives in slot q % RD; every layer's rounds are
+    // padded to a multiple of RD, so the mapping is static) and two rounds of activation fragments
+    uint4 wreg[RD][4], xreg[2][NXL];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < RD; ++s)
 #pragma unroll
-      for (int i = 0; i < HB; ++i)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) wreg[s][i][r] = make_uint4(0, 0, 0, 0);
+      for (int r = 0; r < 4; ++r) wreg[s][r] = make_uint4(0, 0, 0, 0);
 
     // rounds of this wave in layer l: units x sub-units x tiles; a wave beyond the layer's tiles
     // still walks one empty round per sub-unit (it takes part in the unit's barrier)
@@ -160,15 +186,15 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
 
     // ---- issue cursor: the next round whose codes have not been requested (runs ahead, across layers)
     int il = 0, iq = 0, iu = 0, ig = 0, ij = 0;       // layer, round in layer, local unit, sub-unit, tile step
+    int ioff = 0;                                     // where layer il's descriptors begin in s_desc
     int ipos[4] = {0, 0, 0, 0};
     auto issue_desc = [&]() __attribute__((always_inline)) {
-      const ResLayer& ly = p.layer[il];
-      const size_t sub = (size_t)(wg + iu * G) * ly.nsub + ig;
-      const v4i a = cload_r<v4i>(ly.subs, sub * 4);
-      ipos[0] = a[0]; ipos[1] = a[1]; ipos[2] = a[2]; ipos[3] = a[3];
+      const int at = ioff + iu * dstride_of(il) + ig * 16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ipos[r] = dword(at + r);
     };
     auto issue_seek = [&]() __attribute__((always_inline)) {   // skip layers without rounds, fetch the descriptor
-      while (il < p.L && rounds_of(il) == 0) ++il;
+      while (il < p.L && rounds_of(il) == 0) { ioff += units_of(p.layer[il].n_units) * dstride_of(il); ++il; }
       if (il < p.L) issue_desc();
     };
     issue_seek();
@@ -188,23 +214,24 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         if (++ij >= max(ru, 1)) {
           ij = 0;
           if (++ig >= ly.nsub) { ig = 0; ++iu; }
-          if (iu >= units_of(ly.n_units)) { ++il; iq = 0; iu = 0; issue_seek(); }
+          if (iu >= units_of(ly.n_units)) { ioff += units_of(ly.n_units) * dstride_of(il); ++il; iq = 0; iu = 0; issue_seek(); }
           else issue_desc();
         }
       }
     };
 
     int buf = 0;
-    for (int l = 0; l < p.L; ++l) {
+    int coff = 0;   // where layer l's descriptors begin in s_desc
+    for (int l = 0; l < p.L; coff += units_of(p.layer[l].n_units) * dstride_of(l), ++l) {
       const ResLayer& ly = p.layer[l];
       const int ru = ru_of(l), ru_eff = max(ru, 1);
       const int rounds = rounds_of(l);
-      const int nhb_pad = ((rounds + HB - 1) / HB + 1) & ~1;   // half-batches, padded to an even number
-      // codes of the first half-batch, unless the previous layer's last step requested them already
+      const int rounds_pad = (rounds + RD - 1) / RD * RD;
+      // codes of the first rounds, unless the previous layer's last steps requested them already
       if (il == l && iq == 0) {
 #pragma unroll
-        for (int i = 0; i < HB; ++i)
-          if (il == l && iq == i) issue_codes(wreg[0][i], true);
+        for (int s = 0; s < RD; ++s)
+          if (il == l && iq == s) issue_codes(wreg[s], true);
       }
       // the codes entering this layer are being produced: four workgroup barriers of the exchange
       __syncthreads();
@@ -218,45 +245,35 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
 #pragma unroll
         for (int m = 0; m < XM; ++m)
 #pragma unroll
-          for (int j = 0; j < STEPS; ++j) {
+          for (int j = 0; j < STEPS; ++j)
             x[m * STEPS + j] = reinterpret_cast<const uint4*>(ly.qin + ((size_t)(m < ly.xm ? m : 0) * ly.nks + (size_t)tl * STEPS + j) * 1024)[xl];
-          }
         if (real && ++xj >= ru_eff) xj = 0;
       };
+      if (rounds_pad > 0) {
+        issue_x(xreg[0], 0 < rounds);
+        issue_x(xreg[1], 1 < rounds);
+      }
       // ---- consume cursor
       int cu = 0, cg = 0, cj = 0, cn = 0, cslot0 = 0, clast = 0, citm[4] = {0, 0, 0, 0};
       auto cons_desc = [&]() __attribute__((always_inline)) {
-        const size_t sub = (size_t)(wg + cu * G) * ly.nsub + cg;
-        const v4i a = cload_r<v4i>(ly.subs, sub * 4 + 1), b = cload_r<v4i>(ly.subs, sub * 4 + 2);
-        cn = b[0]; cslot0 = b[1]; clast = b[2];
+        const int at = coff + cu * dstride_of(l) + cg * 16;
+        cn = dword(at + 8); cslot0 = dword(at + 9); clast = dword(at + 10);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int k = a[r];
+          const int k = (XM == 1) ? 0 : dword(at + 4 + r);
           citm[r] = (XM == 1 || ly.xm == 1) ? 0 : (k == 0 ? p.member_of[0] : (k == 1 ? p.member_of[1] : (k == 2 ? p.member_of[2] : p.member_of[3])));
         }
       };
       if (rounds > 0) cons_desc();
 
-      for (int h0 = 0; h0 < nhb_pad; h0 += 2) {
+      for (int q0 = 0; q0 < rounds_pad; q0 += RD) {
 #pragma unroll
-        for (int par = 0; par < 2; ++par) {
-          const int h = h0 + par;
-          // 1. activation fragments of this half-batch
-#pragma unroll
-          for (int i = 0; i < HB; ++i) issue_x(xreg[i], h * HB + i < rounds);
-          // 2. codes of the next half-batch; the layer's last step requests the next layer's first
-#pragma unroll
-          for (int i = 0; i < HB; ++i) {
-            const bool real = il < p.L && ((il == l && iq == (h + 1) * HB + i) || (h == nhb_pad - 1 && il > l && iq == i));
-            issue_codes(wreg[par ^ 1][i], real);
-          }
-          // 3. multiply this half-batch
-#pragma unroll
-          for (int i = 0; i < HB; ++i) {
-            const int q = h * HB + i;
-            if (q >= rounds) continue;
+        for (int s = 0; s < RD; ++s) {
+          const int q = q0 + s;
+          // 1. multiply round q
+          if (q < rounds) {
             if (ru > 0) {
-              uint4 (&w)[4] = wreg[par][i];
+              uint4 (&w)[4] = wreg[s];
 #pragma unroll
               for (int j = 0; j < STEPS; ++j) {
                 // the fragments of this 64-k step, lanes of tokens beyond the batch zeroed (at use, not at
@@ -264,7 +281,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                 v4i x[XM];
 #pragma unroll
                 for (int m = 0; m < XM; ++m) {
-                  const uint4& xr = xreg[i][m * STEPS + j];
+                  const uint4& xr = xreg[s & 1][m * STEPS + j];
                   x[m] = v4i{xlive ? (int)xr.x : 0, xlive ? (int)xr.y : 0, xlive ? (int)xr.z : 0, xlive ? (int)xr.w : 0};
                 }
 #pragma unroll
@@ -289,8 +306,14 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                 }
               }
             }
+          }
+          // 2. fragments of round q + 2 into the set just read; codes of round q + RD into the slot just read
+          //    (once this layer's are all requested: round s of the next layer).  Always NXL + 4 loads.
+          issue_x(xreg[s & 1], q + 2 < rounds);
+          issue_codes(wreg[s], il < p.L && (il == l ? iq == q + RD : iq == s));
+          // 3. end of a sub-unit: this wave's share of its integer tiles joins the others' in LDS
+          if (q < rounds) {
             if (cj + 1 >= ru_eff) {
-              // end of a sub-unit: this wave's share of its integer tiles joins the others' in LDS
               if (ru > 0) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -316,6 +339,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
               cj = 0;
               if (++cg >= ly.nsub) { cg = 0; ++cu; }
               if (q + 1 < rounds) cons_desc();
+              else if (wave == 0) stamp(l, 7);
             } else {
               ++cj;
             }
@@ -330,38 +354,45 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
     const int t = e >> 4, ch = e & 15;
     const int fidx = ((ch >> 2) * 16 + t) * 4 + (ch & 3);
     const bool tok = t < p.T;
-    uint32_t epoch = 0;
-    if (wave == RES_WORKERS) epoch = ld_dev_u32(p.gen);
+    // Every epilogue wave tracks the epoch; the first one polls and tells the others through LDS and
+    // the workgroup barrier that follows.
+    uint32_t epoch = ld_dev_u32(p.gen);
     const uint32_t epoch0 = epoch;
+    if (e == 0) s_seen = epoch;
     int buf = 0;
     const float qmax = p.act_qmax;
     // what this thread produced in the current layer: its max|.| per member, and the values themselves
     // (LDS, as far as it reaches; the rest is read back from the layer's output)
     float* stash = reinterpret_cast<float*>(pad_lds);
     float mx_out[2] = {0.f, 0.f};
+    auto seen = [&]() __attribute__((always_inline)) {
+      return (int)(__hip_atomic_load(&s_seen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - epoch) >= 0 || s_fail != 0;
+    };
 
     // one grid-wide step: publish this workgroup's epoch, wait until every workgroup has reached it
     auto grid_wait = [&]() __attribute__((always_inline)) {
-      ++epoch;
-      if (lane == 0) st_dev_u32(&p.flags[wg], epoch);
-      bool ok = s_fail != 0;
+      if (ewave != 0) return;   // one polling wave per workgroup: more of them only crowd the flags' memory channel (measured)
+      if (e == 0) st_dev_u32(&p.flags[wg], epoch);
+      bool ok = seen();
       for (int it = 0; it < p.spin_limit && !ok; ++it) {
         bool mine = true;
         for (int i = lane; i < G; i += 64) mine &= (int)(ld_dev_u32(&p.flags[i]) - epoch) >= 0;
         ok = __all(mine);
+        if (ok && lane == 0) __hip_atomic_store(&s_seen, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        ok = ok || seen();
       }
-      if (!ok) {
-        if (lane == 0) { s_fail = 1; st_dev_u32(p.status, 1u); }
-      }
+      if (!ok && lane == 0) { s_fail = 1; st_dev_u32(p.status, 1u); }
     };
 
-    for (int l = 0; l < p.L; ++l) {
+    int eoff = 0, eoff_prev = 0;   // where the descriptors of layer l and of layer l-1 begin in s_desc
+    for (int l = 0; l < p.L; eoff_prev = eoff, eoff += units_of(p.layer[l].n_units) * dstride_of(l), ++l) {
       const ResLayer& ly = p.layer[l];
       const int n_in = ly.xm;   // tensors to quantize for this layer
       const ResLayer& lp = p.layer[l > 0 ? l - 1 : 0];
       const int nu_prev = l > 0 ? units_of(lp.n_units) : 0;
       const bool dynamic = l > 0 || !(p.s_static > 0.f);
       // ---------------- exchange, step A: max|.| of the tensor(s) entering layer l
+      if (wave == RES_WORKERS) stamp(l, 0);
       float mx[2] = {0.f, 0.f};
       if (dynamic) {
         if (l == 0) {
@@ -383,9 +414,9 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         }
       }
       __syncthreads();   // P1
-      if (wave == RES_WORKERS) {
-        if (dynamic) {
-          ++epoch;
+      if (dynamic) {
+        ++epoch;
+        if (ewave == 0) {
           if (lane < n_in) {
             float v = s_wmax[0][lane];
 #pragma unroll
@@ -394,29 +425,36 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                                __HIP_MEMORY_SCOPE_AGENT);
           }
           if (lane == 0) st_dev_u32(&p.flags[wg], epoch);   // keeps the flag word in step with the epoch
-          float g0 = 0.f, g1 = 0.f;
-          bool ok = s_fail != 0;
-          for (int it = 0; it < p.spin_limit && !ok; ++it) {
-            bool mine = true;
-            g0 = 0.f; g1 = 0.f;
-            for (int i = lane; i < G * n_in; i += 64) {
-              const int w = i / n_in, m = i - w * n_in;
-              const unsigned long long tv = __hip_atomic_load(&p.amax_tag[w * 2 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              mine &= (uint32_t)(tv >> 32) == epoch;
-              const float v = __uint_as_float((uint32_t)tv);
-              if (m == 0) g0 = fmaxf(g0, v); else g1 = fmaxf(g1, v);
-            }
-            ok = __all(mine);
-          }
-          if (!ok && lane == 0) { s_fail = 1; st_dev_u32(p.status, 2u); }
-#pragma unroll
-          for (int o = 32; o > 0; o >>= 1) { g0 = fmaxf(g0, __shfl_xor(g0, o, 64)); g1 = fmaxf(g1, __shfl_xor(g1, o, 64)); }
-          if (lane == 0) { s_scale[0] = __fdiv_rn(g0, qmax); s_scale[1] = __fdiv_rn(g1, qmax); }
-        } else if (lane == 0) {
-          s_scale[0] = p.s_static; s_scale[1] = p.s_static;
         }
+        bool ok = ewave != 0 || seen();   // one polling wave per workgroup
+        for (int it = 0; it < p.spin_limit && !ok; ++it) {
+          bool mine = true;
+          float g0 = 0.f, g1 = 0.f;
+          for (int i = lane; i < G * n_in; i += 64) {
+            const int w = i / n_in, m = i - w * n_in;
+            const unsigned long long tv = __hip_atomic_load(&p.amax_tag[w * 2 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            mine &= (uint32_t)(tv >> 32) == epoch;
+            const float v = __uint_as_float((uint32_t)tv);
+            if (m == 0) g0 = fmaxf(g0, v); else g1 = fmaxf(g1, v);
+          }
+          ok = __all(mine);
+          if (ok) {
+            // every workgroup's maximum of this epoch: the scales (any wave that gets here writes the same values)
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) { g0 = fmaxf(g0, __shfl_xor(g0, o, 64)); g1 = fmaxf(g1, __shfl_xor(g1, o, 64)); }
+            if (lane == 0) {
+              s_scale[0] = __fdiv_rn(g0, qmax); s_scale[1] = __fdiv_rn(g1, qmax);
+              __hip_atomic_store(&s_seen, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+          }
+          ok = ok || seen();
+        }
+        if (!ok && lane == 0) { s_fail = 1; s_scale[0] = 0.f; s_scale[1] = 0.f; st_dev_u32(p.status, 2u); }
+      } else if (e == 0) {
+        s_scale[0] = p.s_static; s_scale[1] = p.s_static;
       }
       __syncthreads();   // P2
+      if (wave == RES_WORKERS) stamp(l, 1);
       // ---------------- exchange, step B: every workgroup writes the codes of what it produced
       {
         const float s0 = s_scale[0], s1 = s_scale[1];
@@ -437,18 +475,23 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
           }
         } else {
           for (int u = 0; u < nu_prev; ++u) {
-            const int32_t* ep = lp.epi + (size_t)(wg + u * G) * 32;
-            const int n_out = lp.gated ? 1 : cload_r<int>(ep, 1);
+            const int ep = eoff_prev + u * dstride_of(l - 1) + lp.nsub * 16;
+            const int n_out = lp.gated ? 1 : dword(ep + 1);
             for (int o = 0; o < n_out; ++o) {
-              const int col = cload_r<int>(ep, 26 + o) * 16 + ch;
+              const int col = dword(ep + 26 + o) * 16 + ch;
 #pragma unroll
               for (int m = 0; m < 2; ++m)
                 if (m < n_in) {
                   int c = 0;
                   if (tok) {
                     const int si = (u * 4 + o) * 2 + m;
-                    const float v = si < RES_STASH ? stash[si * 256 + e]
-                                                   : __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(lp.out + ((size_t)m * p.T + t) * lp.out_w + col)));
+                    float v;
+                    if (si < RES_STASH) {
+                      v = stash[si * 256 + e];
+                    } else {
+                      __builtin_amdgcn_s_waitcnt(0x0F70);   // this thread's own store of the value has completed
+                      v = __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(lp.out + ((size_t)m * p.T + t) * lp.out_w + col)));
+                    }
                     c = q1(v, m == 0 ? s0 : s1);
                   }
                   // four neighbouring channels of a token are four neighbouring bytes of a fragment
@@ -474,7 +517,10 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
       }
       __syncthreads();   // P3
-      if (wave == RES_WORKERS) grid_wait();
+      if (wave == RES_WORKERS) stamp(l, 2);
+      ++epoch;
+      grid_wait();
+      if (wave == RES_WORKERS) stamp(l, 3);
       __syncthreads();   // P4: the workers may read the codes entering layer l
 
       // ---------------- the layer's units
@@ -484,17 +530,47 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       const bool fold_sx = ly.reduce && p.M > 1;
       mx_out[0] = 0.f; mx_out[1] = 0.f;
       for (int u = 0; u < nu; ++u) {
-        const int32_t* ep = ly.epi + (size_t)(wg + u * G) * 32;
         int d[32];   // the unit's descriptor: scalar registers
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const v4i q = cload_r<v4i>(ep, i);
-          d[4 * i] = q[0]; d[4 * i + 1] = q[1]; d[4 * i + 2] = q[2]; d[4 * i + 3] = q[3];
-        }
-        const int n_items = d[0], n_out = d[1];
+        for (int i = 0; i < 32; ++i) d[i] = dword(eoff + u * dstride_of(l) + ly.nsub * 16 + i);
+        const int n_items = d[0], n_out = ly.gated ? 1 : d[1];
+        // Every global load of the unit's epilogue is issued here, before the unit's barrier, and every
+        // result is computed before the first store: a wait for a load also waits for the stores
+        // before it, and a device-scope (write-through) store takes more than a microsecond to complete.
         float scv[PIPE_RES_MAX_ITEMS];
 #pragma unroll
         for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) scv[i] = i < n_items ? ly.scales[(size_t)d[18 + i] * 16 + ch] : 0.f;
+        float bsv[4] = {0.f, 0.f, 0.f, 0.f};   // plain: bias of output o; gated: bias of the gate and of the up channel
+        float rsv[4][2];                         // skip tensor: what output o of member m (or the member sum) adds
+#pragma unroll
+        for (int o = 0; o < 4; ++o) { rsv[o][0] = 0.f; rsv[o][1] = 0.f; }
+        if (ly.gated) {
+          if (ly.bias != nullptr) { bsv[0] = ly.bias[d[27] * 16 + ch]; bsv[1] = ly.bias[d[28] * 16 + ch]; }
+        } else {
+#pragma unroll
+          for (int o = 0; o < 4; ++o) {
+            if (o >= n_out) continue;
+            const int col = d[26 + o] * 16 + ch;
+            if (ly.bias != nullptr) bsv[o] = ly.bias[col];
+            if (ly.res != nullptr) {
+#pragma unroll
+              for (int m = 0; m < 2; ++m) {
+                if (m >= p.M || (ly.reduce && m > 0)) continue;
+                // the members summed into this output each add their own skip tensor (members kept apart:
+                // member m adds its own if it has one)
+                const int n_res = ly.reduce ? ly.res_members : (m < ly.res_members ? 1 : 0);
+                const float* rp = ly.res + (size_t)(ly.reduce ? 0 : m) * ly.res_mstride + (size_t)min(t, p.T - 1) * ly.out_w + col;
+                float rsum = 0.f;
+                for (int mm = 0; mm < n_res; ++mm) {
+                  // a tensor an earlier layer of this launch produced is read with device scope
+                  const float* rq = rp + (size_t)mm * ly.res_mstride;
+                  rsum += ly.res_device ? __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(rq))) : *rq;
+                }
+                rsv[o][m] = rsum;
+              }
+            }
+          }
+        }
         __syncthreads();   // the workers have added up this unit's tiles
         int a_it[PIPE_RES_MAX_ITEMS];
 #pragma unroll
@@ -508,12 +584,15 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
           for (int m = 0; m < XM; ++m) { rs[m] = tile[buf][PIPE_RES_MAX_ITEMS + m][fidx]; tile[buf][PIPE_RES_MAX_ITEMS + m][fidx] = 0; }
         }
         buf ^= 1;
+        float vout[4][2];   // output o of member m (the member sum in vout[o][0] when members are summed)
+#pragma unroll
+        for (int o = 0; o < 4; ++o) { vout[o][0] = 0.f; vout[o][1] = 0.f; }
         if (ly.gated) {
           // items with slot 0 are the gate block's orders, slot 1 the up block's; h = SiLU(gate) * up per member
-          const int hcol = d[26] * 16 + ch, gcol = d[27] * 16 + ch, ucol = d[28] * 16 + ch;
-          const float bgate = ly.bias != nullptr ? ly.bias[gcol] : 0.f, bup = ly.bias != nullptr ? ly.bias[ucol] : 0.f;
-          for (int m = 0; m < p.M; ++m) {
-            const int k_lo = p.member_lo[m < PIPE_RES_MAX_M ? m : 0], k_hi = p.member_hi[m < PIPE_RES_MAX_M ? m : 0];
+#pragma unroll
+          for (int m = 0; m < 2; ++m) {
+            if (m >= p.M) continue;
+            const int k_lo = p.member_lo[m], k_hi = p.member_hi[m];
             float gs = 0.f, us = 0.f;
 #pragma unroll
             for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
@@ -522,25 +601,21 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
               const int a = a_it[i] - OFF * rs[0];
               if (sl == 0) gs = fmaf(scv[i], (float)a, gs); else us = fmaf(scv[i], (float)a, us);
             }
-            const float vg = fmaf(sx0, gs, m == 0 ? bgate : 0.f), vu = fmaf(sx0, us, m == 0 ? bup : 0.f);
-            const float h = vg / (1.f + expf(-vg)) * vu;
-            if (tok) {
-              st_dev_u32(reinterpret_cast<uint32_t*>(ly.out + ((size_t)m * p.T + t) * ly.out_w + hcol), __float_as_uint(h));
-              const int si = (u * 4) * 2 + m;
-              if (si < RES_STASH) stash[si * 256 + e] = h;
-              if (m == 0) mx_out[0] = fmaxf(mx_out[0], fabsf(h)); else mx_out[1] = fmaxf(mx_out[1], fabsf(h));
-            }
+            const float vg = fmaf(sx0, gs, m == 0 ? bsv[0] : 0.f), vu = fmaf(sx0, us, m == 0 ? bsv[1] : 0.f);
+            vout[0][m] = vg / (1.f + expf(-vg)) * vu;
           }
         } else {
-          for (int o = 0; o < n_out; ++o) {
-            const int col = (o == 0 ? d[26] : (o == 1 ? d[27] : (o == 2 ? d[28] : d[29]))) * 16 + ch;
-            const float bias = ly.bias != nullptr ? ly.bias[col] : 0.f;
+#pragma unroll
+          for (int o = 0; o < 4; ++o) {
+            if (o >= n_out) continue;
             float yacc = 0.f;
-            for (int m = 0; m < p.M; ++m) {
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+              if (m >= p.M) continue;
               const int st_m = ly.xm == 1 ? 0 : m;
               const int rsm = st_m == 0 ? rs[0] : rs[1];
               const float sx = st_m == 0 ? sx0 : sx1;
-              const int k_lo = p.member_lo[m < PIPE_RES_MAX_M ? m : 0], k_hi = p.member_hi[m < PIPE_RES_MAX_M ? m : 0];
+              const int k_lo = p.member_lo[m], k_hi = p.member_hi[m];
 #pragma unroll
               for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
                 const int kk = d[2 + i], sl = d[10 + i];
@@ -550,47 +625,51 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                 yacc = fmaf(sc, (float)a, yacc);
               }
               if (fold_sx && m + 1 < p.M) continue;
-              const float bm = (m == 0 || fold_sx) ? bias : 0.f;
-              float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);
+              const float bm = (m == 0 || fold_sx) ? bsv[o] : 0.f;
+              float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the per-layer kernels
               yacc = 0.f;
-              float rsum = 0.f;
-              if (ly.res != nullptr) {
-                const int n_res = ly.reduce ? ly.res_members : (m < ly.res_members ? 1 : 0);
-                const float* rp = ly.res + (size_t)(ly.reduce ? 0 : m) * ly.res_mstride + (size_t)min(t, p.T - 1) * ly.out_w + col;
-                for (int mm = 0; mm < n_res; ++mm) {
-                  // a tensor an earlier layer of this launch produced is read with device scope
-                  const float* rq = rp + (size_t)mm * ly.res_mstride;
-                  rsum += ly.res_device ? __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(rq))) : *rq;
-                }
-              }
+              const float rsum = rsv[o][ly.reduce ? 0 : m];
               if (ly.res_pre_act) v += rsum;
               if (ly.act == PIPE_ACT_GELU) v = gelu_erf_r(v);
               else if (ly.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
               if (!ly.res_pre_act) v += rsum;
-              if (tok) {
-                float* dst = ly.out + ((size_t)(ly.reduce ? 0 : m) * p.T + t) * ly.out_w + col;
-                if (last) {
-                  *dst = v;
-                } else {
-                  st_dev_u32(reinterpret_cast<uint32_t*>(dst), __float_as_uint(v));
-                  const int si = (u * 4 + o) * 2 + m;
-                  if (si < RES_STASH) stash[si * 256 + e] = v;
-                  if (m == 0) mx_out[0] = fmaxf(mx_out[0], fabsf(v)); else mx_out[1] = fmaxf(mx_out[1], fabsf(v));
-                }
+              vout[o][ly.reduce ? 0 : m] = v;
+            }
+          }
+        }
+        // ---- stores: the last layer's result plainly, a hidden tensor with device scope (other workgroups'
+        // skips read it), into the stash (this thread quantizes it in the next exchange), and its max
+        if (tok) {
+#pragma unroll
+          for (int o = 0; o < 4; ++o) {
+            if (o >= n_out) continue;
+            const int col = d[26 + o] * 16 + ch;
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+              if (m >= (ly.reduce ? 1 : p.M)) continue;
+              const float v = vout[o][m];
+              float* dst = ly.out + ((size_t)m * p.T + t) * ly.out_w + col;
+              if (last) {
+                *dst = v;
+              } else {
+                st_dev_u32(reinterpret_cast<uint32_t*>(dst), __float_as_uint(v));
+                const int si = (u * 4 + o) * 2 + m;
+                if (si < RES_STASH) stash[si * 256 + e] = v;
+                if (m == 0) mx_out[0] = fmaxf(mx_out[0], fabsf(v)); else mx_out[1] = fmaxf(mx_out[1], fabsf(v));
               }
             }
           }
         }
       }
-      if (!last) __builtin_amdgcn_s_waitcnt(0x0F70);   // the outputs are re-read (own stores) and published in the next exchange
+      if (wave == RES_WORKERS) stamp(l, 4);
     }
-    if (wg == 0 && wave == RES_WORKERS && lane == 0 && epoch != epoch0) st_dev_u32(p.gen, epoch);
+    if (wg == 0 && e == 0 && epoch != epoch0) st_dev_u32(p.gen, epoch);
   }
 }
 
 template <int BITS, int XM>
-int launch_res(const ResParams& p, hipStream_t st) {
-  constexpr int RD = (XM == 2 && BITS == 2) ? 2 : 4;   // rounds of code registers (two half-batches); two tensors of ternary fragments leave room for two
+int launch_res(const ResParams& p, hipEvent_t ev0, hipEvent_t ev1, hipStream_t st) {
+  constexpr int RD = (XM == 2 && BITS == 2) ? 2 : 4;   // rounds of code registers; two tensors of ternary fragments leave room for two
   static bool attr_set = false;
   if (!attr_set) {
     PIPE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_resident_kernel<BITS, XM, RD>),
@@ -598,7 +677,10 @@ int launch_res(const ResParams& p, hipStream_t st) {
     attr_set = true;
   }
   if (pipe_dry_run()) return PIPE_OK;
-  hipLaunchKernelGGL((chain_resident_kernel<BITS, XM, RD>), dim3((unsigned)p.G), dim3(RES_THREADS), RES_PAD_LDS, st, p);
+  if (ev0 != nullptr)
+    hipExtLaunchKernelGGL((chain_resident_kernel<BITS, XM, RD>), dim3((unsigned)p.G), dim3(RES_THREADS), RES_PAD_LDS, st, ev0, ev1, 0, p);
+  else
+    hipLaunchKernelGGL((chain_resident_kernel<BITS, XM, RD>), dim3((unsigned)p.G), dim3(RES_THREADS), RES_PAD_LDS, st, p);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }
@@ -740,6 +822,7 @@ int launch_resident_chain(const ResidentArgs& a, hipStream_t st) {
   p.x = a.x; p.s_static = a.s_static; p.act_qmax = g_act_qmax_host;
   p.flags = a.flags; p.amax_tag = a.amax_tag; p.gen = a.gen; p.status = a.status;
   p.spin_limit = g_resident_spin_limit;
+  p.trace = g_resident_trace;
   const int bits = a.layers[0].e->bits;
   for (int l = 0; l < a.L; ++l) {
     const ResidentLayerArgs& la = a.layers[l];
@@ -759,16 +842,20 @@ int launch_resident_chain(const ResidentArgs& a, hipStream_t st) {
     ly.reduce = l == a.L - 1 ? 1 : 0;
     ly.res_device = la.res_device;
   }
+  // the descriptors of the busiest workgroup (the first) have to fit their LDS copy
+  int desc_ints = 0;
+  for (int l = 0; l < a.L; ++l) desc_ints += ceil_div(p.layer[l].n_units, p.G) * (p.layer[l].nsub * 16 + 32);
+  if (desc_ints > PIPE_RES_DESC_INTS) return PIPE_ESHAPE;
   if (a.M == 1) {
     switch (bits) {
-      case 8: return launch_res<8, 1>(p, st);
-      case 4: return launch_res<4, 1>(p, st);
-      default: return launch_res<2, 1>(p, st);
+      case 8: return launch_res<8, 1>(p, a.ev_start, a.ev_stop, st);
+      case 4: return launch_res<4, 1>(p, a.ev_start, a.ev_stop, st);
+      default: return launch_res<2, 1>(p, a.ev_start, a.ev_stop, st);
     }
   }
   switch (bits) {
-    case 8: return launch_res<8, 2>(p, st);
-    case 4: return launch_res<4, 2>(p, st);
-    default: return launch_res<2, 2>(p, st);
+    case 8: return launch_res<8, 2>(p, a.ev_start, a.ev_stop, st);
+    case 4: return launch_res<4, 2>(p, a.ev_start, a.ev_stop, st);
+    default: return launch_res<2, 2>(p, a.ev_start, a.ev_stop, st);
   }
 }

@@ -126,6 +126,21 @@ def residual_stack(width: int, blocks: int, out_features: int, bits: int, K: int
 CHAIN = residual_stack(2048, 3, 1024, 2, 8, 0.5, 64, 4096, (4, 4))
 
 
+def decode_stack(layers: int = 8, tokens: int = 16) -> Workload:
+    """A decode-time stack of layers of config 4's shape and distributions (11008 x 4096 and back,
+    ternary, K = 4, a quarter of the groups kept), ReLU between them: what a resident decode step
+    streams layer after layer.  The expansions of the two shapes are shared by the layers."""
+    up = LayerSpec(11008, 4096, 2, 4, 0.25, 64)
+    down = LayerSpec(4096, 11008, 2, 4, 0.25, 64)
+    specs = tuple(up if l % 2 == 0 else down for l in range(layers))
+    chain = tuple(("relu", -1, True) if l < layers - 1 else ("none", -1, True) for l in range(layers))
+    return Workload(name="decode_stack_%d_layers_c4_shape" % layers, config=4, kind="chain", layers=specs, tokens=tokens,
+                    split=(4,), w_dist=C4.w_dist, x_dist=C4.x_dist, chain=chain)
+
+
+DECODE_STACK = decode_stack()
+
+
 def with_tokens(w: Workload, tokens: int) -> Workload:
     """Same layer, another token count (conv workloads keep their geometry)."""
     if w.kind == "conv2d":

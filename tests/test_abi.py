@@ -80,7 +80,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_set_kernel(7) == EINVAL and lib.pipe_set_kernel(0) == 0
     assert lib.pipe_set_stream_split(-1) == EINVAL and lib.pipe_set_stream_split(0) == 0
     assert lib.pipe_set_decode_fusion(2) == EINVAL and lib.pipe_set_decode_fusion(1) == 0
-    assert lib.pipe_set_decode_resident(2) == EINVAL and lib.pipe_set_decode_resident(1) == 0
+    assert lib.pipe_set_decode_resident(3) == EINVAL and lib.pipe_set_decode_resident(1) == 0
     assert lib.pipe_set_resident_spin_limit(-1) == EINVAL and lib.pipe_set_resident_spin_limit(0) == 0
     assert lib.pipe_resident_status(None, None) == EINVAL
     assert lib.pipe_set_token_tile(48) == EINVAL and lib.pipe_set_token_tile(0) == 0

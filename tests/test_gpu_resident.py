@@ -18,8 +18,9 @@ ACT = {"none": 0, "gelu": 1, "relu": 3}
 def pipe():
     assert torch.cuda.is_available(), "these tests need the GPU"
     import paper_2311_15806_amd.binding as b
+    b.pipe_set_decode_resident(True)        # the resident launch wherever it applies, not only where it is the default
     yield b
-    b.pipe_set_decode_resident(True)
+    b.pipe_set_decode_resident(1)
     b.pipe_set_resident_spin_limit(0)
 
 
