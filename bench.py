@@ -144,6 +144,9 @@ def main():
 
         def build(self):
             cfg = self.cfg
+            if cfg.kind == "conv2d":       # the convolution as an implicit GEMM: the expansion is stored tap-major
+                c, l = cfg.conv, cfg.layers[0]
+                return [pipe.pipe_expand_conv2d(self.Ws[0], c["C"], c["kh"], c["kw"], l.bits, l.K, l.gamma, l.group)]
             return [pipe.pipe_expand(self.Ws[i % len(self.Ws)], l.bits, l.K, l.gamma, l.group) for i, l in enumerate(cfg.layers)]
 
         def free(self):

@@ -130,6 +130,21 @@ int pipe_expand_with_operator(const float* W_dev, int out, int in, int bits, int
                               float* scales_dev, int8_t* codes_dev, void* stream,
                               pipe_expansion** exp_out);
 
+/* The expansion of a convolution weight for the implicit-GEMM path of pipe_forward_conv2d
+ * (App. H: a convolution is the same contraction with in = C*kh*kw; Sec. 3.1 for the expansion).
+ *   W_dev [out, C*kh*kw] fp32, a row flattened [C, kh, kw], read only.  C a multiple of 64.
+ * Same arithmetic, masks and result as pipe_expand on the same matrix (pipe_expansion_order returns the
+ * codes flattened [C, kh, kw] again); only the stored order of the in_features axis differs -- tap-major,
+ * channel-minor -- so that pipe_forward_conv2d and pipe_forward_conv2d_acc read every tap's channels
+ * straight from the channels-last codes of the input tensor and build no patch matrix.  The group
+ * scores are fp64 sums over the rows in the stored order: a decision closer than the rounding of such
+ * a sum may differ from pipe_expand's.  Only those two entry points (with the same C, kh, kw) accept
+ * the result; every other forward entry point and pipe_expansion_reconstruct return PIPE_EINVAL.
+ * Errors: as pipe_expand; PIPE_ESHAPE if C is not a multiple of 64 (use pipe_expand: pipe_forward_conv2d
+ * then gathers the patches explicitly).                                                                */
+int pipe_expand_conv2d(const float* W_dev, int out, int C, int kh, int kw, int bits, int K, float gamma,
+                       int group, void* stream, pipe_expansion** exp_out);
+
 int pipe_expansion_free(pipe_expansion* e);
 
 /* Shape query; any output pointer may be NULL.  packed_bytes = bytes of packed
@@ -229,7 +244,8 @@ int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float* x_dev, int
 
 /* Expanded convolution as a GEMM over output pixels (App. H treats conv and FC
  * alike).  The expansion was built from W [out, C*kh*kw], a row flattened as
- * [C, kh, kw].  x_dev is [N,C,H,W] (nhwc == 0) or [N,H,W,C] (nhwc != 0), zero
+ * [C, kh, kw]: by pipe_expand (the patches of Q(x) are gathered into a matrix first) or by
+ * pipe_expand_conv2d (implicit GEMM: no patch matrix, three launches).  x_dev is [N,C,H,W] (nhwc == 0) or [N,H,W,C] (nhwc != 0), zero
  * padded by `pad`.  Tokens are output pixels ordered (n, ho, wo):
  * y_dev is [N*Ho*Wo, out] (channels last), or [M, N*Ho*Wo, out].
  * Remaining arguments as pipe_forward.                                        */

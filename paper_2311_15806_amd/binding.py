@@ -44,6 +44,7 @@ def _load():
     pi = C.POINTER(C.c_int)
     lib.pipe_expand.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
     lib.pipe_expand_unstructured.argtypes = [vp, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
+    lib.pipe_expand_conv2d.argtypes = [vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, C.POINTER(vp)]
     lib.pipe_expand_with_operator.argtypes = [vp, ci, ci, ci, ci, cf, ci, _ROUNDING_FN, vp, vp, vp, vp, vp, C.POINTER(vp)]
     lib.pipe_expansion_free.argtypes = [vp]
     lib.pipe_expansion_info.argtypes = [vp, pi, pi, pi, pi, pi, C.POINTER(cf), C.POINTER(C.c_int64)]
@@ -172,6 +173,16 @@ def pipe_expand(W: torch.Tensor, bits: int, K: int, gamma: float, group: int) ->
     h = C.c_void_p()
     _check(_lib.pipe_expand(_ptr(W, torch.float32), W.shape[0], W.shape[1], int(bits), int(K),
                             float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand")
+    return Expansion(h.value)
+
+
+def pipe_expand_conv2d(W: torch.Tensor, Cin: int, kh: int, kw: int, bits: int, K: int, gamma: float, group: int) -> Expansion:
+    """W [out, Cin*kh*kw] (rows flattened [Cin, kh, kw]) expanded for the implicit-GEMM convolution."""
+    if W.dim() != 2 or W.shape[1] != Cin * kh * kw:
+        raise ValueError("W must be [out, Cin*kh*kw]")
+    h = C.c_void_p()
+    _check(_lib.pipe_expand_conv2d(_ptr(W, torch.float32), W.shape[0], int(Cin), int(kh), int(kw), int(bits), int(K),
+                                   float(gamma), int(group), _stream(), C.byref(h)), "pipe_expand_conv2d")
     return Expansion(h.value)
 
 

@@ -216,6 +216,7 @@ static void free_expansion(pipe_expansion* e) {
     if (rt.subs_dev) (void)hipFree(rt.subs_dev);
     if (rt.epi_dev) (void)hipFree(rt.epi_dev);
   }
+  if (e->conv_zero_dev) (void)hipFree(e->conv_zero_dev);
   if (e->dw_codes_dev) (void)hipFree(e->dw_codes_dev);
   if (e->dw_scales_dev) (void)hipFree(e->dw_scales_dev);
   if (e->bins_dev) (void)hipFree(e->bins_dev);
@@ -455,6 +456,28 @@ extern "C" int pipe_expand_with_operator(const float* W_dev, int out, int in, in
   return expand_checked(W_dev, out, in, bits, K, gamma, group, hook, false, stream, exp_out);
 }
 
+extern "C" int pipe_expand_conv2d(const float* W_dev, int out, int C, int kh, int kw, int bits, int K, float gamma,
+                                  int group, void* stream, pipe_expansion** exp_out) {
+  if (W_dev == nullptr || exp_out == nullptr) return PIPE_EINVAL;
+  if (out <= 0 || C <= 0 || kh <= 0 || kw <= 0 || C % 64 != 0 || (int64_t)C * kh * kw > 130000) return PIPE_ESHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  const int in = C * kh * kw;
+  float* Wp = nullptr;
+  PIPE_HIP(hipMalloc(&Wp, (size_t)out * in * sizeof(float)));
+  int rc = launch_permute_conv_weight(W_dev, out, C, kh * kw, Wp, st);
+  pipe_expansion* e = nullptr;
+  if (rc == PIPE_OK) rc = expand_checked(Wp, out, in, bits, K, gamma, group, RoundingHook{}, false, stream, &e);   // synchronizes
+  (void)hipFree(Wp);
+  if (rc != PIPE_OK) return rc;
+  e->conv_C = C; e->conv_kh = kh; e->conv_kw = kw;
+  if (hipMalloc(&e->conv_zero_dev, 256) != hipSuccess || hipMemset(e->conv_zero_dev, 0, 256) != hipSuccess) {
+    free_expansion(e);
+    return PIPE_ENOMEM;
+  }
+  *exp_out = e;
+  return PIPE_OK;
+}
+
 extern "C" int pipe_expansion_free(pipe_expansion* e) {
   if (!e) return PIPE_OK;
   (void)hipDeviceSynchronize();
@@ -500,6 +523,17 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
     }
     (void)hipFree(tmp);
     if (rc) return rc;
+    if (e->conv_C > 0) {
+      // stored tap-major: hand the rows back flattened [C, kh, kw], as the weight was given
+      const int taps = e->conv_kh * e->conv_kw, C = e->conv_C;
+      std::vector<int8_t> row((size_t)e->in);
+      for (size_t r = 0; r < rows; ++r) {
+        int8_t* dst = codes_unpacked + r * (size_t)e->in;
+        std::memcpy(row.data(), dst, (size_t)e->in);
+        for (int tap = 0; tap < taps; ++tap)
+          for (int c = 0; c < C; ++c) dst[(size_t)c * taps + tap] = row[(size_t)tap * C + c];
+      }
+    }
   }
   return PIPE_OK;
 }
@@ -736,6 +770,7 @@ extern "C" int pipe_forward(const pipe_expansion* e, const float* x_dev, int T, 
                             const int* split, int M, const float* bias_dev, int reduce_members,
                             float* y_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(e->K, split, M, lo, hi, &Mm);
   if (rc) return rc;
@@ -780,6 +815,7 @@ extern "C" int pipe_prepare(const pipe_expansion* e, const int* split, int M, in
 extern "C" int pipe_forward_acc(const pipe_expansion* e, const float* x_dev, int T, float s_x,
                                 int32_t* acc_dev, int8_t* qx_dev, float* s_x_out_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   if (T == 0) return PIPE_OK;
   if (!x_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
@@ -836,6 +872,7 @@ static int noalloc_scratch(unsigned char** out) {
 extern "C" int pipe_forward_noalloc(const pipe_expansion* e, const float* x_dev, int T, float s_x, const int* split,
                                     int M, const float* bias_dev, int reduce_members, float* y_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(e->K, split, M, lo, hi, &Mm);
   if (rc) return rc;
@@ -948,6 +985,7 @@ static int asym_quantize(const pipe_expansion* e, const float* x_dev, int T, con
 extern "C" int pipe_forward_asymmetric(const pipe_expansion* e, const float* x_dev, int T, const int* split, int M,
                                        const float* bias_dev, float* y_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(e->K, split, M, lo, hi, &Mm);
   if (rc) return rc;
@@ -980,6 +1018,7 @@ extern "C" int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const flo
                                               int kh, int kw, int stride, int pad, int nhwc, const int* split, int M,
                                               const float* bias_dev, float* y_dev, void* stream) {
   if (!e) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
   if ((int64_t)C * kh * kw != e->in) return PIPE_ESHAPE;
   const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
@@ -1024,6 +1063,7 @@ extern "C" int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const flo
 extern "C" int pipe_forward_acc_asymmetric(const pipe_expansion* e, const float* x_dev, int T, int32_t* acc_dev,
                                            uint8_t* qx_dev, float* s_x_out_dev, int32_t* z_out_dev, void* stream) {
   if (!e || T < 0) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   if (T == 0) return PIPE_OK;
   if (!x_dev || !acc_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
@@ -1088,11 +1128,55 @@ static int conv2d_impl(const pipe_expansion* e, const float* x_dev, int N, int C
   if (!x_dev || (!y_dev && !export_acc)) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   CallScope scope(stream);
+  const size_t n_in = (size_t)N * C * H * W;
+  if (e->conv_C > 0) {
+    // ---- implicit GEMM (an expansion stored tap-major by pipe_expand_conv2d): no patch matrix.  The input
+    // is quantized once into channels-last codes with per-pixel channel sums; the tiled kernel's activation
+    // stage gathers each tap's 64-channel chunks from them.  Launches: max|x| (also clears the sums),
+    // quantizer, contraction.
+    if (C != e->conv_C || kh != e->conv_kh || kw != e->conv_kw) return PIPE_ESHAPE;
+    if (n_in >= ((size_t)1 << 31)) return PIPE_ESHAPE;   // 32-bit element offsets in the kernel
+    ActBuffers b;
+    rc = get_act_buffers(16, IN_PAD, true, &b);   // only the scale and max slots are used
+    if (rc) return rc;
+    int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, n_in);
+    int32_t* csum = (int32_t*)pipe_ws_get(WS_CSUM, (size_t)N * H * W * sizeof(int32_t));
+    if (!q8 || !csum) return pipe_ws_error();
+    int klo = 0, khi = e->K - 1;
+    if ((rc = export_acc ? ensure_tables(e, 1, &klo, &khi, 2) : ensure_tables(e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+    if (!(s_x > 0.f)) rc = launch_absmax(x_dev, (int64_t)n_in, b.amax, csum, N * H * W, st);
+    else rc = launch_zero_u32(reinterpret_cast<uint32_t*>(csum), N * H * W, st);
+    if (rc) return rc;
+    rc = launch_quantize_nhwc_sums(x_dev, N, C, H * W, nhwc, s_x, b.amax, q8, csum, b.scale, st);
+    if (rc) return fail_after_reduction(rc, b, st);
+    GemmArgs a{};
+    a.e = e; a.T = T; a.T_pad = (int)round_up64(T, TOK_TILE); a.s_x = b.scale; a.zero_after = b.amax;
+    a.conv_q8 = q8; a.conv_csum = csum; a.conv_zero = e->conv_zero_dev;
+    a.conv_C = C; a.conv_H = H; a.conv_W = W; a.conv_kh = kh; a.conv_kw = kw; a.conv_stride = stride; a.conv_pad = pad;
+    a.conv_Ho = Ho; a.conv_Wo = Wo;
+    if (export_acc) {
+      if (!pipe_dry_run()) {
+        if (qx_dev) {
+          // the codes in the input's own layout
+          if (nhwc) PIPE_HIP(hipMemcpyAsync(qx_dev, q8, n_in, hipMemcpyDeviceToDevice, st));
+          else if ((rc = launch_quantize_elem(x_dev, (int64_t)n_in, s_x, b.amax, qx_dev, nullptr, st)) != PIPE_OK) return fail_after_reduction(rc, b, st);
+        }
+        if (s_x_out_dev) PIPE_HIP(hipMemcpyAsync(s_x_out_dev, b.scale, sizeof(float), hipMemcpyDeviceToDevice, st));
+        PIPE_HIP(hipMemsetAsync(acc_dev, 0, (size_t)e->K * T * e->out * sizeof(int32_t), st));
+      }
+      a.reduce = 1; a.acc_out = acc_dev;
+      fill_members(a, 1, &klo, &khi);
+    } else {
+      a.bias = bias_dev; a.reduce = reduce_members ? 1 : 0; a.y = y_dev;
+      fill_members(a, Mm, lo, hi);
+    }
+    rc = run_gemm(a, false, st);
+    return rc == PIPE_OK ? rc : fail_after_reduction(rc, b, st);
+  }
   const bool small = use_stream_kernel(e, T, export_acc);
   ActBuffers b;
   rc = get_act_buffers(T, e->in_pad, small, &b);
   if (rc) return rc;
-  const size_t n_in = (size_t)N * C * H * W;
   int8_t* q8 = (int8_t*)pipe_ws_get(WS_Q8X, n_in);   // the input's codes, in its own layout
   if (!q8) return pipe_ws_error();
   {
@@ -1145,6 +1229,7 @@ extern "C" int pipe_forward_depthwise2d(const pipe_expansion* e, const float* x_
                                         int kh, int kw, int stride, int pad, int nhwc, float s_x, const int* split,
                                         int M, const float* bias_dev, int reduce_members, float* y_dev, void* stream) {
   if (!e) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: only the convolution entry points read it
   if (N < 0 || C <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return PIPE_ESHAPE;
   if (C != e->out || kh * kw != e->in || kh * kw > 49) return PIPE_ESHAPE;
   if (H + 2 * pad < kh || W + 2 * pad < kw) return PIPE_ESHAPE;
@@ -1271,6 +1356,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
                                 const float* bias1_dev, const float* bias2_dev, float* h_dev,
                                 float* y_dev, void* stream) {
   if (!l1 || !l2 || T < 0) return PIPE_EINVAL;
+  if (l1->conv_C > 0 || l2->conv_C > 0) return PIPE_EINVAL;
   if (act != PIPE_ACT_GELU && act != PIPE_ACT_SILU_GATED) return PIPE_EINVAL;
   if (l1->K != l2->K) return PIPE_ESPLIT;
   const int H = l2->in;
@@ -1405,7 +1491,7 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   Hin[0] = H0; Win[0] = W0; Tin[0] = (int64_t)N * H0 * W0;
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
-    if (!ly.e) return PIPE_EINVAL;
+    if (!ly.e || ly.e->conv_C > 0) return PIPE_EINVAL;
     if (ly.act != PIPE_ACT_NONE && ly.act != PIPE_ACT_RELU && ly.act != PIPE_ACT_GELU) return PIPE_EINVAL;
     if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
     if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;

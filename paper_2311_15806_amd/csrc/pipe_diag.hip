@@ -208,6 +208,7 @@ extern "C" int pipe_expansion_order_norms(const pipe_expansion* e, int iters, do
 extern "C" int pipe_expansion_reconstruct(const pipe_expansion* e, int upto, float* W_out_dev, void* stream) {
   if (!e || !W_out_dev) return PIPE_EINVAL;
   if (upto < 1 || upto > e->K) return PIPE_EINVAL;
+  if (e->conv_C > 0) return PIPE_EINVAL;   // stored tap-major: its rows are not laid out as the weight was given
   hipStream_t st = (hipStream_t)stream;
   PIPE_HIP(hipMemsetAsync(W_out_dev, 0, (size_t)e->out * e->in * sizeof(float), st));
   for (int k = 0; k < upto; ++k) {

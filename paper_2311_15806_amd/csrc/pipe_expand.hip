@@ -264,6 +264,17 @@ __global__ __launch_bounds__(256) void gather_row_blocks_kernel(const uint8_t* _
   if (threadIdx.x < 16) scales_all[pos * 16 + threadIdx.x] = scales_k[(size_t)crb * 16 + threadIdx.x];
 }
 
+// A convolution weight row flattened [C, kh, kw] -> flattened [kh, kw, C] (tap-major, channel-minor):
+// the k axis the implicit-GEMM convolution walks (one tap's channels are contiguous in a channels-last input)
+__global__ void permute_conv_weight_kernel(const float* __restrict__ W, int C, int taps, float* __restrict__ W_out) {
+  const size_t row = blockIdx.x;
+  const int in = C * taps;
+  for (int i = threadIdx.x; i < in; i += blockDim.x) {
+    const int tap = i / C, c = i - tap * C;
+    W_out[row * in + i] = W[row * in + (size_t)c * taps + tap];
+  }
+}
+
 }  // namespace
 
 int launch_gather_row_blocks(const uint8_t* codes_k, const float* scales_k, const int32_t* pos_of_dev, int n_crb,
@@ -399,6 +410,12 @@ int launch_unpack_codes(const uint8_t* packed, const int32_t* rb_map_dev, int bi
   if (n == 0) return PIPE_OK;
   PIPE_KLAUNCH(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, rb_map_dev,
                      bits, rows, in, in_pad, codes);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_permute_conv_weight(const float* W, int out, int C, int taps, float* W_out, hipStream_t st) {
+  PIPE_KLAUNCH(permute_conv_weight_kernel, dim3(out), dim3(BLK), 0, st, W, C, taps, W_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -59,6 +59,12 @@ struct TiledParams {
   int hidden;                     // MODE_GATED: H; the layer's rows are gate [0,H) and up [H,2H), y is [M,T,H]
   int n_st_t;                     // super-tiles along tokens
   int st_c_log2;                  // a super-tile is 2^st_c_log2 column tiles x 64 / 2^st_c_log2 token tiles
+  // CONV (implicit GEMM: the expansion's k runs tap-major, channel-minor): the activation stage gathers
+  // each 64-channel chunk of a tap straight from the channels-last codes of the input tensor
+  const int8_t* cq8;              // Q(x) [N, H, W, C]
+  const int32_t* ccsum;           // per input pixel: sum of its C codes
+  const uint8_t* czero;           // 16 zero bytes: what a tap outside the image (or beyond in_features) reads
+  int cC, cH, cW, ckh, ckw, cstride, cpad, cHo, cWo;
 };
 
 __device__ __forceinline__ float gelu_erf(float a) {
@@ -150,7 +156,7 @@ int g_tiled_mtb = 0;   // 16-token blocks per tile of the tiled kernel: 0 = auto
 
 namespace {
 
-template <int BITS, int MTB, int NRW, int MINW, int MODE>
+template <int BITS, int MTB, int NRW, int MINW, int MODE, bool CONV = false>
 __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams p) {
   constexpr bool ACC_OUT = MODE == MODE_ACC_OUT;
   constexpr int OFF = BITS == 8 ? 0 : (BITS == 4 ? 8 : 1);
@@ -187,6 +193,24 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   const int nksup = (p.nks * 64) / KSUP;
   const int n_stage = p.nks / S;
 
+  // CONV: this lane's token (output pixel) of each of the fragments it loads: element offset of the
+  // window's first tap and channel 0 in Q(x), and the tap's row and column in the input (may lie
+  // outside the image; a token beyond the batch lies outside for every tap)
+  constexpr int NCB = CONV ? XCOPY : 1;
+  int c_off[NCB], c_h0[NCB], c_w0[NCB];
+  int c_r[NCB], c_q[NCB], c_c0[NCB];   // wave-uniform: tap (row, column) and first channel of the 64-k step each fragment loads next
+  if constexpr (CONV) {
+#pragma unroll
+    for (int f = 0; f < XCOPY; ++f) {
+      const int b = (wave * XCOPY + f) / S;
+      const int t = t0 + b * 16 + (lane & 15);
+      const int wo = t % p.cWo, ho = (t / p.cWo) % p.cHo, img = t / (p.cWo * p.cHo);
+      const int h0 = ho * p.cstride - p.cpad;
+      c_h0[f] = t < p.T ? h0 : -(1 << 20);   // a token beyond the batch: every tap outside
+      c_w0[f] = wo * p.cstride - p.cpad;
+      c_off[f] = ((img * p.cH + h0) * p.cW + c_w0[f]) * p.cC + (lane >> 4) * 16;   // used only for taps inside the image
+    }
+  }
   // ---- tile descriptors, fetched once (one memory round trip) -------------------------------
   // the first activation stage does not depend on them: request it first
   auto xload = [&](const uint8_t* qx, int s, int buf) __attribute__((always_inline)) {
@@ -196,9 +220,31 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     for (int f = 0; f < XCOPY; ++f) {
       const int idx = wave * XCOPY + f;          // fragment (b, j) = (idx / S, idx % S)
       const int b = idx / S, j = idx - b * S;
-      const uint4* g = reinterpret_cast<const uint4*>(qx + ((size_t)(t0 / 16 + b) * p.nks + (size_t)s * S + j) * 1024) + lane;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                       (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
+      if constexpr (CONV) {
+        // 64-k step s*S + j of the tap-major k axis: tap (r, q), channels c0 .. c0 + 63 (C is a multiple of
+        // 64).  The stages of a pass are requested in order, so the position is stepped, not divided out.
+        if (s == 0) {
+          const int tap = (j * 64) / p.cC;
+          c_c0[f] = j * 64 - tap * p.cC;
+          c_r[f] = tap / p.ckw;
+          c_q[f] = tap - c_r[f] * p.ckw;
+        } else {
+          c_c0[f] += S * 64;
+          while (c_c0[f] >= p.cC) {
+            c_c0[f] -= p.cC;
+            if (++c_q[f] == p.ckw) { c_q[f] = 0; ++c_r[f]; }
+          }
+        }
+        const int r = c_r[f], q = c_q[f], c0 = c_c0[f];
+        const bool inside = r < p.ckh && (unsigned)(c_h0[f] + r) < (unsigned)p.cH && (unsigned)(c_w0[f] + q) < (unsigned)p.cW;
+        const int8_t* g = inside ? p.cq8 + (c_off[f] + (r * p.cW + q) * p.cC + c0) : reinterpret_cast<const int8_t*>(p.czero);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
+      } else {
+        const uint4* g = reinterpret_cast<const uint4*>(qx + ((size_t)(t0 / 16 + b) * p.nks + (size_t)s * S + j) * 1024) + lane;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)&Xs[buf][idx * FRAG], 16, 0, 0);
+      }
     }
   };
   xload(p.qx, 0, 0);   // member 0 owns order 1, which every tile holds
@@ -211,8 +257,27 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
   const int rb_out[NRW] = {rb_out4[0], rb_out4[1], rb_out4[2], rb_out4[3]};
   float sx = p.s_x[0];
   int rs[MTB];
+  if constexpr (CONV) {
+    // token code sum = the channel sums of the window's pixels that lie inside the image
 #pragma unroll
-  for (int b = 0; b < MTB; ++b) rs[b] = OFF ? p.rowsum[t0 + b * 16 + (lane & 15)] : 0;
+    for (int b = 0; b < MTB; ++b) {
+      int sum = 0;
+      if (OFF) {
+        const int t = t0 + b * 16 + (lane & 15);
+        const int wo = t % p.cWo, ho = (t / p.cWo) % p.cHo, img = t / (p.cWo * p.cHo);
+        const int h0 = ho * p.cstride - p.cpad, w0 = wo * p.cstride - p.cpad;
+        if (t < p.T)
+          for (int r = 0; r < p.ckh; ++r)
+            for (int q = 0; q < p.ckw; ++q)
+              if ((unsigned)(h0 + r) < (unsigned)p.cH && (unsigned)(w0 + q) < (unsigned)p.cW)
+                sum += p.ccsum[(img * p.cH + h0 + r) * p.cW + w0 + q];
+      }
+      rs[b] = sum;
+    }
+  } else {
+#pragma unroll
+    for (int b = 0; b < MTB; ++b) rs[b] = OFF ? p.rowsum[t0 + b * 16 + (lane & 15)] : 0;
+  }
 
   const bool fold_sx = p.reduce && p.M > 1;   // multi-member sum: fold s_x into the row scale
   const unsigned scl_lane = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)&Scl[wave][0] + (lane >> 4) * 16;
@@ -230,8 +295,10 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     const int32_t* rowsum = p.rowsum + (size_t)m * p.rowsum_mstride;
     if (m > 0) {
       sx = p.s_x[m * p.sx_mstride];
+      if constexpr (!CONV) {   // the members of a convolution layer share its input: their code sums stay
 #pragma unroll
-      for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
+        for (int b = 0; b < MTB; ++b) rs[b] = OFF ? rowsum[t0 + b * 16 + (lane & 15)] : 0;
+      }
     }
 
     // In pass j every row block of the tile contributes its j-th stored order of this member (all
@@ -509,6 +576,16 @@ int launch_cfg(TiledParams& p, bool acc_out, hipEvent_t ev0, hipEvent_t ev1, hip
   const int n_st_c = ceil_div(p.n_ct, 1 << p.st_c_log2);
   // super-tile sidx runs on XCD sidx % 8 as blocks xcd + 8*(64*(sidx/8) + local), local = 0..63
   const dim3 grid((unsigned)(ceil_div(p.n_st_t * n_st_c, 8) * 8 * 64));
+  if (p.cq8 != nullptr) {
+    // implicit-GEMM convolution: plain epilogue or the integer export
+    if (p.res != nullptr || p.act != 0) return PIPE_EINVAL;
+    if (acc_out)
+      PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT, true>), grid, dim3(256), st, ev0, ev1, p);
+    else
+      PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_PLAIN, true>), grid, dim3(256), st, ev0, ev1, p);
+    PIPE_HIP(hipGetLastError());
+    return PIPE_OK;
+  }
   if (acc_out)
     PIPE_LAUNCH((gemm_tiled_kernel<BITS, MTB, NRW, MINW, MODE_ACC_OUT>), grid, dim3(256), st, ev0, ev1, p);
   else if (p.res != nullptr || p.act == PIPE_ACT_RELU)
@@ -538,6 +615,10 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.hidden = 0;
+  p.cq8 = a.conv_q8; p.ccsum = a.conv_csum; p.czero = a.conv_zero;
+  p.cC = a.conv_C; p.cH = a.conv_H; p.cW = a.conv_W; p.ckh = a.conv_kh; p.ckw = a.conv_kw; p.cstride = a.conv_stride; p.cpad = a.conv_pad;
+  p.cHo = a.conv_Ho; p.cWo = a.conv_Wo;
+  if (a.conv_q8 != nullptr && (a.conv_C % 64 != 0 || (a.M > 1 && a.qx_mstride != 0))) return PIPE_ESHAPE;
   p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act;
   if (a.res != nullptr && (a.acc_out != nullptr || a.act == PIPE_ACT_SILU_GATED || a.res_members < 1 || a.res_members > a.M))
     return PIPE_EINVAL;

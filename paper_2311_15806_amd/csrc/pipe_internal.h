@@ -148,6 +148,10 @@ struct pipe_expansion {
   uint32_t* split_cnt_dev = nullptr;  // [n_bins]
   int64_t stream_bytes = 0;  // packed codes + scales + indices
   ResidentTables res_tables[2];   // resident decode kernel: plain units, gate||up pairs
+  // an expansion of a convolution weight with its k axis stored tap-major, channel-minor
+  // (pipe_expand_conv2d): channels, kernel size; 0 = a plain [out, in] expansion
+  int conv_C = 0, conv_kh = 0, conv_kw = 0;
+  uint8_t* conv_zero_dev = nullptr;   // 256 zero bytes
 };
 
 // max|.| reduction slot (fp32 bit pattern of a non-negative value).  Atomics of many waves on
@@ -196,12 +200,17 @@ bool pipe_capturing();
   do {                                                      \
     if (!pipe_dry_run()) hipLaunchKernelGGL(__VA_ARGS__);   \
   } while (0)
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_RES, WS_RES_Q, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_RES, WS_RES_Q, WS_CSUM, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
 int launch_group_select(const double* row_energy, int n_groups, int group, int n_keep,
                         int32_t* gids_out, hipStream_t st);
+// W [out, C*kh*kw] with rows flattened [C, kh, kw] -> rows flattened [kh, kw, C] (tap-major)
+int launch_permute_conv_weight(const float* W, int out, int C, int taps, float* W_out, hipStream_t st);
+// channels-last int8 codes of a convolution input and the per-pixel sums of their channels (zero on entry)
+int launch_quantize_nhwc_sums(const float* x, int N, int C, int HW, int nhwc, float s_static, const uint32_t* amax_bits,
+                              int8_t* q8, int32_t* csum, float* scale_out, hipStream_t st);
 int launch_fold_batchnorm(const float* W, const float* b, const float* gamma, const float* beta, const float* mean,
                           const float* var, float eps, int out, int in, float* W_out, float* b_out, hipStream_t st);
 // An entry takes part if the bit pattern of its magnitude exceeds thr_key, or equals it with a
@@ -305,6 +314,13 @@ struct GemmArgs {
   uint32_t* zero_big = nullptr;   // a buffer the kernel clears as well (the code sums the next layer's quantizer
   int zero_big_n = 0;             // adds into: nobody reads them while this kernel runs), any length
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // if set: the dispatch's own begin/end timestamps
+  // implicit-GEMM convolution (tiled kernel, an expansion built by pipe_expand_conv2d): the channels-last
+  // codes of the input tensor, the per-pixel sums of their channels, 16 zero bytes, the geometry;
+  // qx and rowsum are then not read
+  const int8_t* conv_q8 = nullptr;
+  const int32_t* conv_csum = nullptr;
+  const uint8_t* conv_zero = nullptr;
+  int conv_C = 0, conv_H = 0, conv_W = 0, conv_kh = 0, conv_kw = 0, conv_stride = 1, conv_pad = 0, conv_Ho = 0, conv_Wo = 0;
 };
 // Launches with the dispatch's begin/end timestamps recorded into the two events when they are set
 // (the kernel alone: no event-record packets on the stream in between).

@@ -554,7 +554,56 @@ __global__ __launch_bounds__(BLK) void row_code_sums_kernel(const int8_t* __rest
   if (threadIdx.x == 0) wsum[o] = sm[0];
 }
 
+// Convolution input for the implicit GEMM: channels-last int8 codes [N, H, W, C] and, per pixel,
+// the sum of its C codes (added into csum, zero on entry).  NCHW input: 32 channels x 32 pixels per
+// workgroup through LDS, so that reads run along the pixels and writes along the channels; NHWC input:
+// element-wise, a group of 32 consecutive threads holds 32 consecutive channels of one pixel (C is a
+// multiple of 64).
+__global__ __launch_bounds__(BLK) void quantize_nhwc_sums_kernel(const float* __restrict__ x, int C, int HW, int nhwc,
+                                                                 float s_static, const uint32_t* __restrict__ amax_bits,
+                                                                 int8_t* __restrict__ q8, int32_t* __restrict__ csum,
+                                                                 float* __restrict__ scale_out) {
+  __shared__ int8_t tile[32][33];
+  const float s = act_scale(s_static, amax_bits);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+  const bool live = s > 0.f;
+  const int n = blockIdx.z, c0 = blockIdx.y * 32, p0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  if (!nhwc) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = c0 + ty + 8 * j, pp = p0 + tx;
+      int v = 0;
+      if (c < C && pp < HW && live) v = quant1(x[((size_t)n * C + c) * HW + pp], s);
+      tile[ty + 8 * j][tx] = (int8_t)v;
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int pp = p0 + ty + 8 * j, c = c0 + tx;
+    int v = 0;
+    if (c < C && pp < HW) {
+      v = nhwc ? (live ? quant1(x[((size_t)n * HW + pp) * C + c], s) : 0) : (int)tile[tx][ty + 8 * j];
+      q8[((size_t)n * HW + pp) * C + c] = (int8_t)v;
+    }
+    // the 32 threads of a half wave hold 32 channels of one pixel
+    int sum = v;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (tx == 0 && pp < HW && sum != 0) atomicAdd(&csum[(size_t)n * HW + pp], sum);
+  }
+}
+
 }  // namespace
+
+int launch_quantize_nhwc_sums(const float* x, int N, int C, int HW, int nhwc, float s_static, const uint32_t* amax_bits,
+                              int8_t* q8, int32_t* csum, float* scale_out, hipStream_t st) {
+  PIPE_KLAUNCH(quantize_nhwc_sums_kernel, dim3(ceil_div(HW, 32), ceil_div(C, 32), N), dim3(BLK), 0, st, x, C, HW, nhwc, s_static,
+               amax_bits, q8, csum, scale_out);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
 
 int set_act_qmax(float qmax) {
   PIPE_HIP(hipMemcpyToSymbol(HIP_SYMBOL(c_act_qmax), &qmax, sizeof(float)));

@@ -49,6 +49,8 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_expand(fake, 64, 64, 4, 2, 0.5, 8, None, C.byref(h)) == ESHAPE       # group % 16
     assert lib.pipe_expand(fake, 0, 64, 4, 2, 0.5, 16, None, C.byref(h)) == ESHAPE
     assert h.value is None
+    assert lib.pipe_expand_conv2d(None, 64, 64, 3, 3, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == EINVAL
+    assert lib.pipe_expand_conv2d(fake, 64, 48, 3, 3, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == ESHAPE    # C % 64
     assert lib.pipe_expand_unstructured(None, 64, 64, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == EINVAL
     assert lib.pipe_expand_unstructured(fake, 64, 64, 4, 2, C.c_float(1.5), 16, None, C.byref(h)) == EINVAL
     assert lib.pipe_expand_unstructured(fake, 60, 64, 4, 2, C.c_float(0.5), 16, None, C.byref(h)) == ESHAPE

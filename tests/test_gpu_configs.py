@@ -70,7 +70,8 @@ def test_c2_full_conv(pipe):
     spec, c = w.layers[0], w.conv
     W, x = wl.make_weight(w, 0), wl.make_input(w)
     ora = oracle_expand(W, spec)
-    g = pipe.pipe_expand(dev(W), spec.bits, spec.K, spec.gamma, spec.group)
+    # the config's form: the convolution as an implicit GEMM (no patch matrix)
+    g = pipe.pipe_expand_conv2d(dev(W), c["C"], c["kh"], c["kw"], spec.bits, spec.K, spec.gamma, spec.group)
     assert_expansion_equal(g, ora)
     # the checker's conv on its im2col matrix (direct conv == im2col GEMM is pinned on the CPU)
     Qx, sx = po.quantize_activations(x)
@@ -91,7 +92,14 @@ def test_c2_full_conv(pipe):
     ym = pipe.pipe_forward_conv2d(g, dev(x), c["kh"], c["kw"], c["stride"], c["pad"], split=list(w.split),
                                   reduce_members=False).cpu().numpy()
     assert_close_fp32(ym, ys)
-    g.free()
+    # the explicit-gather path on a plain expansion of the same weight: same integers, same output bits
+    ge = pipe.pipe_expand(dev(W), spec.bits, spec.K, spec.gamma, spec.group)
+    assert_expansion_equal(ge, ora)
+    acc_e, _, _ = pipe.pipe_forward_conv2d_acc(ge, dev(x), c["kh"], c["kw"], c["stride"], c["pad"])
+    assert np.array_equal(acc_e.cpu().numpy(), acc_direct)
+    ye = pipe.pipe_forward_conv2d(ge, dev(x), c["kh"], c["kw"], c["stride"], c["pad"], split=list(w.split)).cpu().numpy()
+    assert np.array_equal(y, ye)
+    g.free(); ge.free()
 
 
 def test_c3_full_mlp(pipe):

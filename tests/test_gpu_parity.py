@@ -223,6 +223,56 @@ def test_conv2d_variants(pipe, C, H, W, O, kh, kw, stride, pad):
     g.free()
 
 
+@pytest.mark.parametrize("C,H,W,O,kh,kw,stride,pad,bits,K", [
+    (64, 14, 14, 64, 3, 3, 1, 1, 4, 3),
+    (128, 9, 11, 96, 3, 3, 2, 0, 2, 4),
+    (64, 7, 7, 48, 1, 1, 1, 0, 8, 2),          # pointwise: one tap
+    (64, 12, 12, 32, 5, 5, 2, 2, 4, 3),        # 1600 input features: the last code tile is partly padding
+    (192, 6, 5, 64, 3, 3, 1, 1, 4, 2),
+])
+def test_implicit_gemm_conv2d(pipe, C, H, W, O, kh, kw, stride, pad, bits, K):
+    """The convolution without a patch matrix (an expansion stored tap-major, the tiled kernel gathers each
+    tap's channels from the channels-last codes): codes and scales equal the checker's, the integer
+    accumulators of every order equal its direct convolution bit for bit, the fp32 output is within
+    tolerance, both input layouts agree, and the result equals the explicit-gather path bit for bit."""
+    N = 5
+    rng = np.random.default_rng(900 + C + kh + stride + bits)
+    Wt = (rng.standard_normal((O, C * kh * kw)) * math.sqrt(2.0 / (C * kh * kw))).astype(f32)
+    x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(f32)
+    b = rng.standard_normal(O).astype(f32)
+    spec = wl.LayerSpec(O, C * kh * kw, bits, K, 0.5, 16)
+    ora = oracle_expand(Wt, spec)
+    g = pipe.pipe_expand_conv2d(dev(Wt), C, kh, kw, bits, K, 0.5, 16)
+    assert_expansion_equal(g, ora)
+    ge = pipe.pipe_expand(dev(Wt), bits, K, 0.5, 16)
+    xl = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    split = [1, K - 1]
+    for s_x in (0.0, 0.02):
+        ref = po.forward_conv2d(ora, x, kh, kw, stride, pad, s_x=s_x if s_x > 0 else None, split=split, bias=b)
+        acc, qx, sx = pipe.pipe_forward_conv2d_acc(g, dev(x), kh, kw, stride, pad, s_x=s_x)
+        assert np.array_equal(sx.cpu().numpy().view(np.uint32), np.array([ref["s_x"]], f32).view(np.uint32))
+        assert np.array_equal(qx.cpu().numpy(), ref["Qx"])
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        acc_l, qx_l, _ = pipe.pipe_forward_conv2d_acc(g, dev(xl), kh, kw, stride, pad, nhwc=True, s_x=s_x)
+        assert np.array_equal(acc_l.cpu().numpy(), ref["acc"])
+        assert np.array_equal(qx_l.cpu().numpy(), ref["Qx"].transpose(0, 2, 3, 1))
+        y = pipe.pipe_forward_conv2d(g, dev(x), kh, kw, stride, pad, s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        assert_close_fp32(y, ref["y"])
+        yl = pipe.pipe_forward_conv2d(g, dev(xl), kh, kw, stride, pad, nhwc=True, s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        ye = pipe.pipe_forward_conv2d(ge, dev(x), kh, kw, stride, pad, s_x=s_x, split=split, bias=dev(b)).cpu().numpy()
+        assert np.array_equal(y, yl) and np.array_equal(y, ye)
+        ym = pipe.pipe_forward_conv2d(g, dev(x), kh, kw, stride, pad, s_x=s_x, split=split, bias=dev(b), reduce_members=False).cpu().numpy()
+        refm = po.forward_conv2d(ora, x, kh, kw, stride, pad, s_x=s_x if s_x > 0 else None, split=split, bias=b, reduce_members=False)
+        assert_close_fp32(ym, refm["y"])
+    # a tap-major expansion is read by the convolution entry points only, with its own geometry
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_forward(g, dev(np.zeros((4, C * kh * kw), f32)))
+    if kh > 1:
+        with pytest.raises(pipe.PipeError):
+            pipe.pipe_forward_conv2d(g, dev(np.zeros((1, C * kh * kw, 4, 4), f32)), 1, 1, 1, 0)
+    g.free(); ge.free()
+
+
 def test_streaming_and_tiled_kernels_agree_bitwise(pipe):
     """Both kernels fold the orders in the same fixed order, so on a decode-sized batch (one to
     four 16-token blocks for the streaming kernel) their fp32 outputs are bit-identical."""
