@@ -467,8 +467,8 @@ int pipe_resident_status(void* stream, int* status_out);
  * words, workgroups = compute units of the chip) every later resident launch records, per workgroup and
  * layer, the time (100 MHz counter) at which 0 the exchange before the layer begins, 1 the scales are
  * known, 2 its codes are stored, 3 all workgroups' codes are visible, 4 its last unit's outputs are
- * written, 7 its first worker wave has multiplied its last round (5, 6 unused).  NULL switches it off
- * (default).  Process-wide.                                                                          */
+ * written, 5 the integer tiles of its first unit are complete, 6 that unit's outputs are computed, 7 its
+ * first worker wave has multiplied its last round.  NULL switches it off (default).  Process-wide.  */
 int pipe_resident_trace(unsigned long long* trace_dev);
 
 /* Kernel timing for benchmarks.  While enabled, every forward call brackets its

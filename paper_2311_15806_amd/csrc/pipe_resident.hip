@@ -122,6 +122,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
   __shared__ float s_wmax[RES_EPI][2];
   __shared__ float s_scale[2];   // scales of the codes entering the current layer
   __shared__ int s_fail;
+  __shared__ unsigned long long s_ts[PIPE_RES_MAX_LAYERS][8];
   __shared__ uint32_t s_seen;   // the last epoch one of the polling waves has seen every workgroup reach
   // this workgroup's unit descriptors of all layers, copied once (a cold scalar load per unit on the
   // workers' path costs more than the unit's arithmetic): per layer, per local unit, its sub-units
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
   const int wg = blockIdx.x, G = p.G;
   for (int i = threadIdx.x; i < 2 * (PIPE_RES_MAX_ITEMS + 2) * 256; i += RES_THREADS) (&tile[0][0][0])[i] = 0;
   if (threadIdx.x == 0) { s_fail = 0; s_scale[0] = 0.f; s_scale[1] = 0.f; }
+  if (threadIdx.x < PIPE_RES_MAX_LAYERS * 8) (&s_ts[0][0])[threadIdx.x] = 0ull;
   auto units_of = [&](int n_units) { return n_units > wg ? (n_units - wg + G - 1) / G : 0; };
   auto dstride_of = [&](int l) { return p.layer[l].nsub * 16 + 32; };
   {
@@ -153,8 +155,9 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
   auto dword = [&](int i) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(s_desc[i]); };
   // profiling: slot 0 exchange begins, 1 maxima known, 2 codes stored, 3 all flags seen, 4 last unit's epilogue done
   // (first epilogue wave); 7 worker wave 0 has multiplied its last round and passed the unit's barrier
+  // (kept in LDS and written out when the kernel ends: a store in the middle would be waited for by the next load)
   auto stamp = [&](int l, int slot) __attribute__((always_inline)) {
-    if (p.trace != nullptr && lane == 0) p.trace[((size_t)wg * p.L + l) * 8 + slot] = wall_clock64();
+    if (p.trace != nullptr && lane == 0) s_ts[l][slot] = wall_clock64();
   };
 
   if (wave < RES_WORKERS) {
@@ -188,39 +191,43 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
     int il = 0, iq = 0, iu = 0, ig = 0, ij = 0;       // layer, round in layer, local unit, sub-unit, tile step
     int ioff = 0;                                     // where layer il's descriptors begin in s_desc
     int ipos[4] = {0, 0, 0, 0};
+    // the cursor's layer, read from the kernel arguments once per layer (a scalar load per use sits on the issue path)
+    const uint8_t* i_codes = p.layer[0].codes;
+    int i_ntiles = 1, i_ru = 0, i_nsub = 1, i_nu = 0, i_stride = 48;
     auto issue_desc = [&]() __attribute__((always_inline)) {
-      const int at = ioff + iu * dstride_of(il) + ig * 16;
+      const int at = ioff + iu * i_stride + ig * 16;
 #pragma unroll
       for (int r = 0; r < 4; ++r) ipos[r] = dword(at + r);
     };
     auto issue_seek = [&]() __attribute__((always_inline)) {   // skip layers without rounds, fetch the descriptor
       while (il < p.L && rounds_of(il) == 0) { ioff += units_of(p.layer[il].n_units) * dstride_of(il); ++il; }
+      const int li = il < p.L ? il : p.L - 1;
+      i_codes = p.layer[li].codes; i_ntiles = p.layer[li].n_tiles; i_ru = ru_of(li); i_nsub = p.layer[li].nsub;
+      i_nu = units_of(p.layer[li].n_units); i_stride = dstride_of(li);
       if (il < p.L) issue_desc();
     };
     issue_seek();
     // Four code loads: the cursor's round if `real`, else a valid address whose data nobody uses.
     auto issue_codes = [&](uint4 (&w)[4], bool real) __attribute__((always_inline)) {
-      const int li = il < p.L ? il : p.L - 1;
-      const ResLayer& ly = p.layer[li];
-      const int ru = ru_of(li);
-      const bool has = real && ru > 0;
+      const bool has = real && i_ru > 0;
       const int tl = has ? wave + RES_WORKERS * ij : 0;
       // items a sub-unit does not have repeat its first one (a cache hit; the product is dropped)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        w[r] = reinterpret_cast<const uint4*>(ly.codes + ((size_t)(has ? ipos[r] : 0) * ly.n_tiles + tl) * 1024)[lane];
+        w[r] = reinterpret_cast<const uint4*>(i_codes + ((size_t)(has ? ipos[r] : 0) * i_ntiles + tl) * 1024)[lane];
       if (real) {
         ++iq;
-        if (++ij >= max(ru, 1)) {
+        if (++ij >= max(i_ru, 1)) {
           ij = 0;
-          if (++ig >= ly.nsub) { ig = 0; ++iu; }
-          if (iu >= units_of(ly.n_units)) { ioff += units_of(ly.n_units) * dstride_of(il); ++il; iq = 0; iu = 0; issue_seek(); }
+          if (++ig >= i_nsub) { ig = 0; ++iu; }
+          if (iu >= i_nu) { ioff += i_nu * i_stride; ++il; iq = 0; iu = 0; issue_seek(); }
           else issue_desc();
         }
       }
     };
 
     int buf = 0;
+    const int mof0 = p.member_of[0], mof1 = p.member_of[1], mof2 = p.member_of[2], mof3 = p.member_of[3];
     int coff = 0;   // where layer l's descriptors begin in s_desc
     for (int l = 0; l < p.L; coff += units_of(p.layer[l].n_units) * dstride_of(l), ++l) {
       const ResLayer& ly = p.layer[l];
@@ -239,6 +246,8 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       __syncthreads();
       __syncthreads();
       int xj = 0;   // tile step of the next round whose fragments have not been requested
+      const uint8_t* l_qin = ly.qin;
+      const int l_nks = ly.nks, l_xm = ly.xm, l_nsub = ly.nsub, l_stride = dstride_of(l);
       auto issue_x = [&](uint4 (&x)[NXL], bool real) __attribute__((always_inline)) {
         const bool has = real && ru > 0;
         const int tl = has ? wave + RES_WORKERS * xj : 0;
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         for (int m = 0; m < XM; ++m)
 #pragma unroll
           for (int j = 0; j < STEPS; ++j)
-            x[m * STEPS + j] = reinterpret_cast<const uint4*>(ly.qin + ((size_t)(m < ly.xm ? m : 0) * ly.nks + (size_t)tl * STEPS + j) * 1024)[xl];
+            x[m * STEPS + j] = reinterpret_cast<const uint4*>(l_qin + ((size_t)(m < l_xm ? m : 0) * l_nks + (size_t)tl * STEPS + j) * 1024)[xl];
         if (real && ++xj >= ru_eff) xj = 0;
       };
       if (rounds_pad > 0) {
@@ -256,12 +265,12 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       // ---- consume cursor
       int cu = 0, cg = 0, cj = 0, cn = 0, cslot0 = 0, clast = 0, citm[4] = {0, 0, 0, 0};
       auto cons_desc = [&]() __attribute__((always_inline)) {
-        const int at = coff + cu * dstride_of(l) + cg * 16;
+        const int at = coff + cu * l_stride + cg * 16;
         cn = dword(at + 8); cslot0 = dword(at + 9); clast = dword(at + 10);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int k = (XM == 1) ? 0 : dword(at + 4 + r);
-          citm[r] = (XM == 1 || ly.xm == 1) ? 0 : (k == 0 ? p.member_of[0] : (k == 1 ? p.member_of[1] : (k == 2 ? p.member_of[2] : p.member_of[3])));
+          citm[r] = (XM == 1 || l_xm == 1) ? 0 : (k == 0 ? mof0 : (k == 1 ? mof1 : (k == 2 ? mof2 : mof3)));
         }
       };
       if (rounds > 0) cons_desc();
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                 buf ^= 1;
               }
               cj = 0;
-              if (++cg >= ly.nsub) { cg = 0; ++cu; }
+              if (++cg >= l_nsub) { cg = 0; ++cu; }
               if (q + 1 < rounds) cons_desc();
               else if (wave == 0) stamp(l, 7);
             } else {
@@ -527,44 +536,53 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       const float sx0 = s_scale[0], sx1 = s_scale[1];
       const int nu = units_of(ly.n_units);
       const bool last = l == p.L - 1;
-      const bool fold_sx = ly.reduce && p.M > 1;
+      // the layer's description, read from the kernel arguments once (not once per use inside the units' epilogues)
+      const int e_reduce = ly.reduce, e_xm = ly.xm, e_act = ly.act, e_pre = ly.res_pre_act, e_gated = ly.gated, e_outw = ly.out_w;
+      const int e_resm = ly.res_members, e_resdev = ly.res_device, e_nsub = ly.nsub, e_stride = dstride_of(l), e_M = p.M, e_T = p.T;
+      const long long e_resms = ly.res_mstride;
+      const float* e_bias = ly.bias;
+      const float* e_res = ly.res;
+      const float* e_scales = ly.scales;
+      float* e_out = ly.out;
+      const int e_klo0 = p.member_lo[0], e_khi0 = p.member_hi[0], e_klo1 = p.member_lo[1], e_khi1 = p.member_hi[1];
+      const bool fold_sx = e_reduce && e_M > 1;
       mx_out[0] = 0.f; mx_out[1] = 0.f;
       for (int u = 0; u < nu; ++u) {
         int d[32];   // the unit's descriptor: scalar registers
 #pragma unroll
-        for (int i = 0; i < 32; ++i) d[i] = dword(eoff + u * dstride_of(l) + ly.nsub * 16 + i);
-        const int n_items = d[0], n_out = ly.gated ? 1 : d[1];
+        for (int i = 0; i < 32; ++i) d[i] = dword(eoff + u * e_stride + e_nsub * 16 + i);
+        const int n_items = d[0], n_out = e_gated ? 1 : d[1];
         // Every global load of the unit's epilogue is issued here, before the unit's barrier, and every
         // result is computed before the first store: a wait for a load also waits for the stores
         // before it, and a device-scope (write-through) store takes more than a microsecond to complete.
         float scv[PIPE_RES_MAX_ITEMS];
 #pragma unroll
-        for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) scv[i] = i < n_items ? ly.scales[(size_t)d[18 + i] * 16 + ch] : 0.f;
+        for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) scv[i] = i < n_items ? e_scales[(size_t)d[18 + i] * 16 + ch] : 0.f;
         float bsv[4] = {0.f, 0.f, 0.f, 0.f};   // plain: bias of output o; gated: bias of the gate and of the up channel
         float rsv[4][2];                         // skip tensor: what output o of member m (or the member sum) adds
 #pragma unroll
         for (int o = 0; o < 4; ++o) { rsv[o][0] = 0.f; rsv[o][1] = 0.f; }
-        if (ly.gated) {
-          if (ly.bias != nullptr) { bsv[0] = ly.bias[d[27] * 16 + ch]; bsv[1] = ly.bias[d[28] * 16 + ch]; }
+        if (e_gated) {
+          if (e_bias != nullptr) { bsv[0] = e_bias[d[27] * 16 + ch]; bsv[1] = e_bias[d[28] * 16 + ch]; }
         } else {
 #pragma unroll
           for (int o = 0; o < 4; ++o) {
             if (o >= n_out) continue;
             const int col = d[26 + o] * 16 + ch;
-            if (ly.bias != nullptr) bsv[o] = ly.bias[col];
-            if (ly.res != nullptr) {
+            if (e_bias != nullptr) bsv[o] = e_bias[col];
+            if (e_res != nullptr) {
 #pragma unroll
               for (int m = 0; m < 2; ++m) {
-                if (m >= p.M || (ly.reduce && m > 0)) continue;
+                if (m >= e_M || (e_reduce && m > 0)) continue;
                 // the members summed into this output each add their own skip tensor (members kept apart:
                 // member m adds its own if it has one)
-                const int n_res = ly.reduce ? ly.res_members : (m < ly.res_members ? 1 : 0);
-                const float* rp = ly.res + (size_t)(ly.reduce ? 0 : m) * ly.res_mstride + (size_t)min(t, p.T - 1) * ly.out_w + col;
+                const int n_res = e_reduce ? e_resm : (m < e_resm ? 1 : 0);
+                const float* rp = e_res + (size_t)(e_reduce ? 0 : m) * e_resms + (size_t)min(t, e_T - 1) * e_outw + col;
                 float rsum = 0.f;
                 for (int mm = 0; mm < n_res; ++mm) {
                   // a tensor an earlier layer of this launch produced is read with device scope
-                  const float* rq = rp + (size_t)mm * ly.res_mstride;
-                  rsum += ly.res_device ? __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(rq))) : *rq;
+                  const float* rq = rp + (size_t)mm * e_resms;
+                  rsum += e_resdev ? __uint_as_float(ld_dev_u32(reinterpret_cast<const uint32_t*>(rq))) : *rq;
                 }
                 rsv[o][m] = rsum;
               }
@@ -572,6 +590,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
           }
         }
         __syncthreads();   // the workers have added up this unit's tiles
+        if (wave == RES_WORKERS && u == 0) stamp(l, 5);
         int a_it[PIPE_RES_MAX_ITEMS];
 #pragma unroll
         for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
@@ -587,12 +606,12 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         float vout[4][2];   // output o of member m (the member sum in vout[o][0] when members are summed)
 #pragma unroll
         for (int o = 0; o < 4; ++o) { vout[o][0] = 0.f; vout[o][1] = 0.f; }
-        if (ly.gated) {
+        if (e_gated) {
           // items with slot 0 are the gate block's orders, slot 1 the up block's; h = SiLU(gate) * up per member
 #pragma unroll
           for (int m = 0; m < 2; ++m) {
-            if (m >= p.M) continue;
-            const int k_lo = p.member_lo[m], k_hi = p.member_hi[m];
+            if (m >= e_M) continue;
+            const int k_lo = m == 0 ? e_klo0 : e_klo1, k_hi = m == 0 ? e_khi0 : e_khi1;
             float gs = 0.f, us = 0.f;
 #pragma unroll
             for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
@@ -611,11 +630,11 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
             float yacc = 0.f;
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
-              if (m >= p.M) continue;
-              const int st_m = ly.xm == 1 ? 0 : m;
+              if (m >= e_M) continue;
+              const int st_m = e_xm == 1 ? 0 : m;
               const int rsm = st_m == 0 ? rs[0] : rs[1];
               const float sx = st_m == 0 ? sx0 : sx1;
-              const int k_lo = p.member_lo[m], k_hi = p.member_hi[m];
+              const int k_lo = m == 0 ? e_klo0 : e_klo1, k_hi = m == 0 ? e_khi0 : e_khi1;
 #pragma unroll
               for (int i = 0; i < PIPE_RES_MAX_ITEMS; ++i) {
                 const int kk = d[2 + i], sl = d[10 + i];
@@ -624,19 +643,20 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
                 const float sc = fold_sx ? scv[i] * sx : scv[i];
                 yacc = fmaf(sc, (float)a, yacc);
               }
-              if (fold_sx && m + 1 < p.M) continue;
+              if (fold_sx && m + 1 < e_M) continue;
               const float bm = (m == 0 || fold_sx) ? bsv[o] : 0.f;
               float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the per-layer kernels
               yacc = 0.f;
-              const float rsum = rsv[o][ly.reduce ? 0 : m];
-              if (ly.res_pre_act) v += rsum;
-              if (ly.act == PIPE_ACT_GELU) v = gelu_erf_r(v);
-              else if (ly.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
-              if (!ly.res_pre_act) v += rsum;
-              vout[o][ly.reduce ? 0 : m] = v;
+              const float rsum = rsv[o][e_reduce ? 0 : m];
+              if (e_pre) v += rsum;
+              if (e_act == PIPE_ACT_GELU) v = gelu_erf_r(v);
+              else if (e_act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
+              if (!e_pre) v += rsum;
+              vout[o][e_reduce ? 0 : m] = v;
             }
           }
         }
+        if (wave == RES_WORKERS && u == 0) stamp(l, 6);
         // ---- stores: the last layer's result plainly, a hidden tensor with device scope (other workgroups'
         // skips read it), into the stash (this thread quantizes it in the next exchange), and its max
         if (tok) {
@@ -646,9 +666,9 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
             const int col = d[26 + o] * 16 + ch;
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
-              if (m >= (ly.reduce ? 1 : p.M)) continue;
+              if (m >= (e_reduce ? 1 : e_M)) continue;
               const float v = vout[o][m];
-              float* dst = ly.out + ((size_t)m * p.T + t) * ly.out_w + col;
+              float* dst = e_out + ((size_t)m * e_T + t) * e_outw + col;
               if (last) {
                 *dst = v;
               } else {
@@ -664,6 +684,10 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       if (wave == RES_WORKERS) stamp(l, 4);
     }
     if (wg == 0 && e == 0 && epoch != epoch0) st_dev_u32(p.gen, epoch);
+  }
+  if (p.trace != nullptr) {
+    __syncthreads();
+    if ((int)threadIdx.x < p.L * 8) p.trace[(size_t)wg * p.L * 8 + threadIdx.x] = (&s_ts[0][0])[threadIdx.x];
   }
 }
 
@@ -716,7 +740,7 @@ int pipe_resident_tables(const pipe_expansion* ce, int kind, int G, ResidentTabl
     epi.insert(epi.end(), s, s + 32);
   };
   if (kind == 0) {
-    const bool by_bin = e->n_bins >= G;
+    const bool by_bin = e->n_bins >= G;   // (one unit per output row block whenever bins deal unevenly measured slower: the per-unit barrier and epilogue cost more than the imbalance)
     struct U { int n; int pos[4], k[4], slot[4], orb[4], n_out; };
     std::vector<U> us;
     for (int b = 0; b < e->n_bins; ++b) {
