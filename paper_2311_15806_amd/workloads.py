@@ -129,7 +129,8 @@ CHAIN = residual_stack(2048, 3, 1024, 2, 8, 0.5, 64, 4096, (4, 4))
 def decode_stack(layers: int = 8, tokens: int = 16) -> Workload:
     """A decode-time stack of layers of config 4's shape and distributions (11008 x 4096 and back,
     ternary, K = 4, a quarter of the groups kept), ReLU between them: what a resident decode step
-    streams layer after layer.  The expansions of the two shapes are shared by the layers."""
+    streams layer after layer.  Two fp32 weights (one per shape) serve all layers; every layer still has
+    its own expansion, so its codes are streamed from memory of their own."""
     up = LayerSpec(11008, 4096, 2, 4, 0.25, 64)
     down = LayerSpec(4096, 11008, 2, 4, 0.25, 64)
     specs = tuple(up if l % 2 == 0 else down for l in range(layers))
