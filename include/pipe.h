@@ -331,6 +331,20 @@ int pipe_chain_forward(const pipe_chain_layer* layers, int L, const float* x_dev
                        float s_x, const int* split, int M, float* const* acts_dev,
                        float* y_dev, void* stream);
 
+/* pipe_chain_forward with asymmetric activation codes (Sec. 4.3 makes its comparison under
+ * asymmetric quantization; the affine quantizer is the one of pipe_forward_asymmetric) in front
+ * of EVERY layer: the network input is quantized over its range [min(x,0), max(x,0)], and
+ * every member quantizes each of its own hidden tensors over that tensor's own range, with its
+ * own scale and integer zero point (after a ReLU the whole code range covers [0, max]: half the
+ * step of the symmetric codes).  Everything else -- members, biases, skips, the sum behind the
+ * last layer, acts_dev, y_dev -- as pipe_chain_forward; ranges are always dynamic (no s_x).
+ * Fully-connected layers only (kh = kw = 0, else PIPE_EINVAL).  The first call on an expansion
+ * builds the sums of its codes (allocates, synchronizes: not under capture, PIPE_ENOTREADY).
+ * Further errors: PIPE_ESHAPE when (2^a - 1) * q_max * in_features does not fit 31 bits.     */
+int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
+                                  const int* split, int M, float* const* acts_dev, float* y_dev,
+                                  void* stream);
+
 /* The same member chains over convolution layers (Fig. 2 draws the expansion of a
  * convolutional network; Sec. 4 evaluates ResNets and MobileNets).  Every tensor is
  * channels-last: tokens are the positions (n, h, w) of an N x H_l x W_l grid in that

@@ -663,13 +663,17 @@ def relu(v: np.ndarray) -> np.ndarray:
 
 
 def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: bool, skips,
-                        split=None, s_x: Optional[float] = None, act_bits: int = 8, grid=None) -> np.ndarray:
+                        split=None, s_x: Optional[float] = None, act_bits: int = 8, grid=None,
+                        asymmetric: bool = False) -> np.ndarray:
     """One layer for all members.  inputs: [T, I] when every member reads the same tensor
     (the network input; s_x is its static scale if given), else [M, T, I] and member m
     quantizes inputs[m] with its own dynamic scale.  Member m contracts with its own orders
     only; the bias goes to the first member.  skips: None, or a list of M entries (an array
     [T, O] or None) added before or after the activation.  grid = (N, H, W) of the tokens
     (needed by convolution layers; default: T tokens, no spatial extent).
+    asymmetric: every tensor entering the layer is quantized with the affine quantizer of
+    Sec. 4.3 (quantize_activations_asymmetric) over its own range, and the contraction runs on
+    the codes minus their zero point (a tap outside the image then contributes nothing).
     Returns [M, T', O] fp32."""
     exp = layer.exp
     rngs = member_ranges(exp.K, split)
@@ -677,7 +681,13 @@ def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: boo
     out = []
     for m in range(M):
         xin = inputs if shared_input else inputs[m]
-        Qa, sa = quantize_activations(xin, s_x if shared_input else None, act_bits)
+        if asymmetric:
+            if s_x is not None:
+                raise ValueError("asymmetric codes take their range from the tensor")
+            Qu, sa, zp = quantize_activations_asymmetric(xin, act_bits)
+            Qa = Qu.astype(np.int32) - int(zp)
+        else:
+            Qa, sa = quantize_activations(xin, s_x if shared_input else None, act_bits)
         acc, _ = chain_layer_acc(layer, Qa, grid if grid is not None else (Qa.shape[0], 1, 1))
         z = dequantize(exp, acc, sa, split, layer.bias, f32)[m]
         r = None if skips is None else skips[m]
@@ -723,7 +733,7 @@ def chain_grids(layers: Sequence[ChainLayer], grid):
 
 
 def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: Optional[float] = None,
-                  act_bits: int = 8, grid=None):
+                  act_bits: int = 8, grid=None, asymmetric: bool = False):
     """M member chains through L expanded layers, summed after the last one.
 
     Member m is the whole architecture with, in every layer, only the orders of its own
@@ -731,6 +741,8 @@ def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: 
     biases (and a skip from the network input) belong to the first member.  The last
     layer has no activation of its own (act must be "none").  x is [T, C]; with convolution
     layers its tokens form grid = (N, H, W), ordered (n, h, w) (a channels-last image).
+    asymmetric: the network input and every member's hidden tensors get asymmetric codes
+    (Sec. 4.3), each over its own range.
     Returns dict(y [T_L, O_L], members [M, T_L, O_L], acts: list of L-1 arrays [M, T_l, O_l])."""
     L = len(layers)
     if L < 1:
@@ -747,9 +759,9 @@ def chain_forward(layers: Sequence[ChainLayer], x: np.ndarray, split=None, s_x: 
     for l, ly in enumerate(layers):
         skips = chain_skips(layers, l, x, acts, M)
         if l == 0:
-            a = chain_layer_members(ly, x, True, skips, split, s_x, act_bits, grids[0])
+            a = chain_layer_members(ly, x, True, skips, split, s_x, act_bits, grids[0], asymmetric)
         else:
-            a = chain_layer_members(ly, acts[l - 1], False, skips, split, None, act_bits, grids[l])
+            a = chain_layer_members(ly, acts[l - 1], False, skips, split, None, act_bits, grids[l], asymmetric)
         acts.append(a)
     members = acts.pop()
     return dict(y=sum_members(members), members=members, acts=acts)

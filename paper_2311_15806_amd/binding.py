@@ -61,6 +61,7 @@ def _load():
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
+    lib.pipe_chain_forward_asymmetric.argtypes = [vp, ci, vp, ci, pi, ci, vp, vp, vp]
     lib.pipe_prepare.argtypes = [vp, pi, ci, ci, vp]
     lib.pipe_prepare_mlp.argtypes = [vp, vp, ci, pi, ci, ci, vp]
     lib.pipe_prepare_chain.argtypes = [vp, ci, ci, ci, ci, pi, ci, vp]
@@ -433,6 +434,25 @@ def pipe_chain_forward(layers, x: torch.Tensor, s_x: float = 0.0, split=None, re
     arr, m = _split(split)
     _check(_lib.pipe_chain_forward(arr_l, L, _ptr(x, torch.float32), T, float(s_x), arr, m, acts_arr, _ptr(y),
                                    _stream()), "pipe_chain_forward")
+    return (y, acts) if return_acts else y
+
+
+def pipe_chain_forward_asymmetric(layers, x: torch.Tensor, split=None, return_acts: bool = False,
+                                  out: Optional[torch.Tensor] = None):
+    """pipe_chain_forward with asymmetric activation codes in front of every layer (fully-connected layers)."""
+    T = x.shape[0]
+    L = len(layers)
+    M = 1 if split is None else len(split)
+    arr_l = _chain_layers(layers)
+    y = out if out is not None else torch.empty((T, layers[-1][0].out_features), dtype=torch.float32, device=x.device)
+    acts, acts_arr = None, None
+    if return_acts and L > 1:
+        acts = [torch.empty((M, T, layers[l][0].out_features), dtype=torch.float32, device=x.device)
+                for l in range(L - 1)]
+        acts_arr = (C.c_void_p * (L - 1))(*[_ptr(a) for a in acts])
+    arr, m = _split(split)
+    _check(_lib.pipe_chain_forward_asymmetric(arr_l, L, _ptr(x, torch.float32), T, arr, m, acts_arr, _ptr(y),
+                                              _stream()), "pipe_chain_forward_asymmetric")
     return (y, acts) if return_acts else y
 
 

@@ -45,6 +45,7 @@ extern "C" const char* pipe_strerror(int code) {
 struct WsSet {
   PipeWorkspace slot[WS_SLOTS];
   bool amax_h_dirty = false;   // the members' max|h| slots hold a value no kernel will clear
+  bool range_h_dirty = false;  // the same for the members' range slots of the asymmetric chain
 };
 static std::mutex g_ws_mu;
 static std::map<std::pair<int, hipStream_t>, WsSet*> g_ws_sets;
@@ -227,6 +228,7 @@ static void free_expansion(pipe_expansion* e) {
   if (e->asym_wsum_dev) (void)hipFree(e->asym_wsum_dev);
   if (e->asym_C_dev) (void)hipFree(e->asym_C_dev);
   if (e->asym_bias_dev) (void)hipFree(e->asym_bias_dev);
+  if (e->asym_P_dev) (void)hipFree(e->asym_P_dev);
   delete e;
 }
 
@@ -923,6 +925,7 @@ static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
   int32_t* wsum = nullptr;
   float* C = nullptr;
   float* be = nullptr;
+  float* P = nullptr;
   PIPE_HIP(hipMalloc(&wsum, (size_t)e->K * out * sizeof(int32_t)));
   hipError_t he = hipMemsetAsync(wsum, 0, (size_t)e->K * out * sizeof(int32_t), st);
   int rc = he == hipSuccess ? PIPE_OK : PIPE_EDEVICE;
@@ -937,7 +940,7 @@ static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
     if (rc == PIPE_OK) rc = launch_row_code_sums(tmp, rows, e->in, e->group, o.gids_dev, wsum + (size_t)k * out, st);
   }
   std::vector<int32_t> hw((size_t)e->K * out);
-  std::vector<float> all((size_t)e->n_bins * e->bin_cap * 16), hC(out, 0.f);
+  std::vector<float> all((size_t)e->n_bins * e->bin_cap * 16), hC(out, 0.f), hP((size_t)e->K * out, 0.f);
   if (rc == PIPE_OK && (hipStreamSynchronize(st) != hipSuccess ||
                         hipMemcpy(hw.data(), wsum, hw.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
                         hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess))
@@ -950,20 +953,25 @@ static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
         for (int j = 0; j < e->group; ++j) {
           const int r = slot * e->group + j;
           const size_t ch = (size_t)o.gids[slot] * e->group + j;
-          hC[ch] += all[(size_t)o.pos[r >> 4] * 16 + (r & 15)] * (float)hw[(size_t)k * out + ch];
+          const float pk = all[(size_t)o.pos[r >> 4] * 16 + (r & 15)] * (float)hw[(size_t)k * out + ch];
+          hP[(size_t)k * out + ch] = pk;
+          hC[ch] += pk;
         }
     }
     if (hipMalloc(&C, out * sizeof(float)) != hipSuccess || hipMalloc(&be, out * sizeof(float)) != hipSuccess ||
-        hipMemcpy(C, hC.data(), out * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+        hipMalloc(&P, hP.size() * sizeof(float)) != hipSuccess ||
+        hipMemcpy(C, hC.data(), out * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(P, hP.data(), hP.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
       rc = PIPE_EDEVICE;
   }
   if (rc != PIPE_OK) {
     if (wsum) (void)hipFree(wsum);
     if (C) (void)hipFree(C);
     if (be) (void)hipFree(be);
+    if (P) (void)hipFree(P);
     return rc;
   }
-  e->asym_wsum_dev = wsum; e->asym_C_dev = C; e->asym_bias_dev = be;
+  e->asym_wsum_dev = wsum; e->asym_C_dev = C; e->asym_bias_dev = be; e->asym_P_dev = P;
   return PIPE_OK;
 }
 
@@ -977,7 +985,7 @@ static int asym_quantize(const pipe_expansion* e, const float* x_dev, int T, con
   int32_t* dz = reinterpret_cast<int32_t*>(b.amax + 66);
   int rc = launch_minmax(x_dev, (int64_t)T * e->in, slots, st);
   if (rc) return rc;
-  rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, b.T_pad, slots, act_bits, b.qx, b.rowsum, qx_u8, b.scale, dz, st);
+  rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, b.T_pad, slots, slots + 1, act_bits, b.qx, b.rowsum, qx_u8, b.scale, dz, st);
   *slots_out = slots; *dz_out = dz;
   return rc;
 }
@@ -1483,6 +1491,41 @@ extern "C" int pipe_prepare_mlp(const pipe_expansion* l1, const pipe_expansion* 
 // ------------------------------------------------------------------ member chains
 // Tokens form an N x H x W grid (channels-last tensors); a fully-connected layer keeps the grid,
 // a convolution layer maps it to its output grid.
+// Tensors leaving layers 0..L-2 of a chain, [M, T_l, out_l] each.  Tensor l lives until its last
+// reader: layer l+1, or a later layer whose skip reads it.  Those the caller did not give a buffer
+// for share a pool of equal slabs.
+static int chain_tensors(const pipe_chain_layer* layers, int L, int Mm, const std::vector<int64_t>& Tin,
+                         float* const* acts_dev, std::vector<float*>* act_out) {
+  std::vector<float*>& act = *act_out;
+  act.assign(L > 1 ? L - 1 : 0, nullptr);
+  std::vector<int> last(L, 0), slab(L, -1);
+  size_t slab_floats = 0;
+  for (int l = 0; l + 1 < L; ++l) {
+    last[l] = l + 1;
+    for (int j = l + 1; j < L; ++j)
+      if (layers[j].skip_from == l + 1) last[l] = j;
+    if (!(acts_dev && acts_dev[l])) slab_floats = std::max(slab_floats, (size_t)Mm * Tin[l + 1] * layers[l].e->out);
+  }
+  slab_floats = (slab_floats + 63) & ~(size_t)63;
+  std::vector<int> busy_until;   // per slab: the last layer that reads its tensor
+  for (int l = 0; l + 1 < L; ++l) {
+    if (acts_dev && acts_dev[l]) continue;
+    int sl = -1;
+    for (size_t i = 0; i < busy_until.size(); ++i)
+      if (busy_until[i] < l) { sl = (int)i; break; }   // its last reader ran before layer l writes
+    if (sl < 0) { sl = (int)busy_until.size(); busy_until.push_back(0); }
+    busy_until[sl] = last[l];
+    slab[l] = sl;
+  }
+  float* pool = nullptr;
+  if (!busy_until.empty()) {
+    pool = (float*)pipe_ws_get(WS_CHAIN, busy_until.size() * slab_floats * sizeof(float));
+    if (!pool) return pipe_ws_error();
+  }
+  for (int l = 0; l + 1 < L; ++l) act[l] = (acts_dev && acts_dev[l]) ? acts_dev[l] : pool + (size_t)slab[l] * slab_floats;
+  return PIPE_OK;
+}
+
 static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float* x_dev, int N, int H0, int W0,
                               float s_x, const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
   if (!layers || L < 1 || N < 0 || H0 < 1 || W0 < 1) return PIPE_EINVAL;
@@ -1536,37 +1579,9 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
   rc = get_act_buffers((int)Tin[1], layers[0].e->in_pad, small[0], &b);
   if (rc) return rc;
 
-  // Tensors leaving layers 0..L-2, [M, T_l, out_l] each.  Tensor l lives until its last reader:
-  // layer l+1, or a later layer whose skip reads it.  Those the caller did not give a buffer
-  // for share a pool of equal slabs.
-  std::vector<float*> act(L > 1 ? L - 1 : 0, nullptr);
-  {
-    std::vector<int> last(L, 0), slab(L, -1);
-    size_t slab_floats = 0;
-    for (int l = 0; l + 1 < L; ++l) {
-      last[l] = l + 1;
-      for (int j = l + 1; j < L; ++j)
-        if (layers[j].skip_from == l + 1) last[l] = j;
-      if (!(acts_dev && acts_dev[l])) slab_floats = std::max(slab_floats, (size_t)Mm * Tin[l + 1] * layers[l].e->out);
-    }
-    slab_floats = (slab_floats + 63) & ~(size_t)63;
-    std::vector<int> busy_until;   // per slab: the last layer that reads its tensor
-    for (int l = 0; l + 1 < L; ++l) {
-      if (acts_dev && acts_dev[l]) continue;
-      int sl = -1;
-      for (size_t i = 0; i < busy_until.size(); ++i)
-        if (busy_until[i] < l) { sl = (int)i; break; }   // its last reader ran before layer l writes
-      if (sl < 0) { sl = (int)busy_until.size(); busy_until.push_back(0); }
-      busy_until[sl] = last[l];
-      slab[l] = sl;
-    }
-    float* pool = nullptr;
-    if (!busy_until.empty()) {
-      pool = (float*)pipe_ws_get(WS_CHAIN, busy_until.size() * slab_floats * sizeof(float));
-      if (!pool) return pipe_ws_error();
-    }
-    for (int l = 0; l + 1 < L; ++l) act[l] = (acts_dev && acts_dev[l]) ? acts_dev[l] : pool + (size_t)slab[l] * slab_floats;
-  }
+  std::vector<float*> act;
+  rc = chain_tensors(layers, L, Mm, Tin, acts_dev, &act);
+  if (rc) return rc;
   uint8_t* qh = nullptr;
   int32_t* rowsum_h = nullptr;
   int8_t* q8 = nullptr;
@@ -1706,6 +1721,139 @@ extern "C" int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, co
                                        float s_x, const int* split, int M, float* const* acts_dev, float* y_dev,
                                        void* stream) {
   return chain_forward_grid(layers, L, x_dev, N, H, W, s_x, split, M, acts_dev, y_dev, stream);
+}
+
+// Member chains with asymmetric activation codes (Sec. 4.3): the same driver as above for fully-connected
+// layers, with the affine quantizer in front of every layer.  A hidden tensor's range comes from the
+// epilogue that produced it (positive and negative part apart), every member quantizes its own tensor with
+// its own scale and zero point, and the token-free term of the zero point joins the member's bias vector.
+extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
+                                             const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
+  std::vector<int64_t> Tin(L + 1, (int64_t)T);
+  int out_max = 0;
+  for (int l = 0; l < L; ++l) {
+    const pipe_chain_layer& ly = layers[l];
+    if (!ly.e || ly.e->conv_C > 0 || ly.kh != 0 || ly.kw != 0) return PIPE_EINVAL;
+    if (ly.act != PIPE_ACT_NONE && ly.act != PIPE_ACT_RELU && ly.act != PIPE_ACT_GELU) return PIPE_EINVAL;
+    if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
+    if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;
+    if (l > 0 && ly.e->in != layers[l - 1].e->out) return PIPE_ESHAPE;
+    if (ly.skip_from >= 0 && layers[ly.skip_from].e->in != ly.e->out) return PIPE_ESHAPE;
+    out_max = std::max(out_max, ly.e->out);
+  }
+  if (layers[L - 1].act != PIPE_ACT_NONE) return PIPE_EINVAL;
+  const int K = layers[0].e->K;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
+  for (int l = 0; l < L; ++l)   // |Q - z| <= 2^a - 1: the exact accumulator must fit 32 bits
+    if ((int64_t)((1 << act_bits) - 1) * ((1 << (layers[l].e->qbits - 1)) - 1) * layers[l].e->in >= ((int64_t)1 << 31)) return PIPE_ESHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
+  for (int l = 0; l < L; ++l)
+    if ((rc = asym_prepare(layers[l].e, st)) != PIPE_OK) return rc;
+  std::vector<char> small(L);
+  int T_pad = 0;
+  size_t qh_bytes = 0;
+  for (int l = 0; l < L; ++l) {
+    small[l] = use_stream_kernel(layers[l].e, T);
+    // one padded token count for the whole chain: the members' code sums keep one stride
+    T_pad = std::max(T_pad, (int)round_up64(T, small[l] ? 16 : TOK_TILE));
+  }
+  for (int l = 1; l < L; ++l) qh_bytes = std::max(qh_bytes, (size_t)Mm * T_pad * layers[l].e->in_pad);
+  ActBuffers b;
+  rc = get_act_buffers(T_pad, layers[0].e->in_pad, false, &b);   // T_pad is a multiple of what either kernel needs
+  if (rc) return rc;
+  std::vector<float*> act;
+  rc = chain_tensors(layers, L, Mm, Tin, acts_dev, &act);
+  if (rc) return rc;
+  uint8_t* qh = nullptr;
+  int32_t* rowsum_h = nullptr;
+  if (L > 1) {
+    qh = (uint8_t*)pipe_ws_get(WS_QH, qh_bytes);
+    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+    if (!qh || !rowsum_h) return pipe_ws_error();
+  }
+  float* bias_m = (float*)pipe_ws_get(WS_ABIAS, (size_t)Mm * out_max * sizeof(float));
+  if (!bias_m) return pipe_ws_error();
+  for (int l = 0; l < L; ++l)
+    if (!small[l] && (rc = ensure_tables(layers[l].e, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  if (pipe_dry_run()) return PIPE_OK;
+  // the input's range slots and zero-point offset, then per member and set the hidden tensors' ranges
+  // (positive parts [0, 16), negative parts [16, 32) of a set; layer l's epilogue raises set l & 1, the
+  // quantizers of layer l+1 read it and layer l+1's contraction clears it), offsets and scales
+  uint32_t* slots_x = b.amax + 64;
+  int32_t* dz_x = reinterpret_cast<int32_t*>(b.amax + 66);
+  uint32_t* rng[2] = {b.amax + 128, b.amax + 128 + 2 * PIPE_MAX_K};
+  int32_t* dz_h = reinterpret_cast<int32_t*>(b.amax + 128 + 4 * PIPE_MAX_K);
+  float* scale_h = b.scale + 16;
+  if (t_ws->range_h_dirty) {
+    rc = launch_zero_u32(rng[0], 4 * PIPE_MAX_K, st);
+    if (rc) return rc;
+  }
+  t_ws->range_h_dirty = true;
+
+  for (int l = 0; l < L; ++l) {
+    const pipe_chain_layer& ly = layers[l];
+    const pipe_expansion* e = ly.e;
+    const bool last_layer = l == L - 1;
+    GemmArgs a{};
+    a.e = e; a.T = T; a.T_pad = T_pad;
+    if (l == 0) {
+      rc = launch_minmax(x_dev, (int64_t)T * e->in, slots_x, st);
+      if (rc) return rc;
+      rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, T_pad, slots_x, slots_x + 1, act_bits, b.qx, b.rowsum, nullptr,
+                                b.scale, dz_x, st);
+      if (rc == PIPE_OK)
+        rc = launch_asym_bias_members(ly.bias_dev, e->asym_P_dev, b.scale, 0, dz_x, 0, Mm, lo, hi, last_layer ? 1 : 0, bias_m,
+                                      e->out, slots_x, 2, st);
+      if (rc) {
+        (void)launch_zero_u32(slots_x, 2, st);   // the raised range slots: the kernel that clears them did not run
+        return rc;
+      }
+      a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
+      a.zero_after = nullptr; a.zero_n = 0;
+    } else {
+      const float* src = act[l - 1];
+      const uint32_t* r_in = rng[(l - 1) & 1];
+      const int64_t q_ms = (int64_t)T_pad * e->in_pad;
+      for (int m = 0; m < Mm; ++m) {
+        rc = launch_quantize_asym(src + (size_t)m * T * e->in, T, e->in, e->in_pad, T_pad, r_in + m, r_in + PIPE_MAX_K + m, act_bits,
+                                  qh + (size_t)m * q_ms, rowsum_h + (size_t)m * T_pad, nullptr, scale_h + m, dz_h + m, st);
+        if (rc) return rc;
+      }
+      rc = launch_asym_bias_members(ly.bias_dev, e->asym_P_dev, scale_h, 1, dz_h, 1, Mm, lo, hi, last_layer ? 1 : 0, bias_m, e->out,
+                                    nullptr, 0, st);
+      if (rc) return rc;
+      a.qx = qh; a.qx_mstride = q_ms;
+      a.rowsum = rowsum_h; a.rowsum_mstride = T_pad;
+      a.s_x = scale_h; a.sx_mstride = 1;
+      a.zero_after = rng[(l - 1) & 1]; a.zero_n = 2 * PIPE_MAX_K;
+    }
+    a.bias = bias_m;
+    a.bias_mstride = last_layer ? 0 : e->out;
+    a.act = ly.act;
+    if (ly.skip_from == 0) {
+      a.res = x_dev; a.res_mstride = 0; a.res_members = 1;
+    } else if (ly.skip_from > 0) {
+      a.res = act[ly.skip_from - 1]; a.res_mstride = (int64_t)T * e->out; a.res_members = Mm;
+    }
+    a.res_pre_act = ly.skip_pre_act ? 1 : 0;
+    if (last_layer) {
+      a.reduce = 1; a.y = y_dev;
+    } else {
+      a.reduce = 0; a.y = act[l]; a.amax_out = rng[l & 1]; a.amax_neg = rng[l & 1] + PIPE_MAX_K;
+    }
+    fill_members(a, Mm, lo, hi);
+    rc = run_gemm(a, small[l], st);
+    if (rc) return rc;
+  }
+  t_ws->range_h_dirty = false;
+  return PIPE_OK;
 }
 
 extern "C" int pipe_prepare_chain(const pipe_chain_layer* layers, int L, int N, int H, int W, const int* split, int M,

@@ -45,9 +45,11 @@ struct TiledParams {
   int n_sorted;                   // padded to a multiple of 64
   int p_max;
   const float* bias;
+  long long bias_mstride;         // 0: the first member's (or the sum's) vector; else one vector per member
   float* y;
   int32_t* acc_out;
   uint32_t* amax_out;
+  uint32_t* amax_neg;             // if set: positive and negative parts of the range apart
   uint32_t* zero_after;
   int zero_n;
   uint32_t* zero_big;
@@ -449,7 +451,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
     // The LDS accesses are issued by hand: left to the compiler, every read would first wait
     // for the previous global store to complete (it orders LDS accesses against all outstanding
     // vector-memory operations of a kernel that uses LDS-direct loads), serializing the stores.
-    float mx = 0.f;
+    float mx = 0.f, mn = 0.f;
+    const bool two_sided = p.amax_neg != nullptr;
     {
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));   // keeps the epilogue's address arithmetic out of the main loop's live range
@@ -467,9 +470,10 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
       // block of the hidden channel for both); the up waves finish h = SiLU(gate) * up
       const bool is_up = MODE == MODE_GATED && wave >= 2;
       float4 bv = make_float4(0.f, 0.f, 0.f, 0.f), bg = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (rb_l >= 0 && (m == 0 || fold_sx) && p.bias != nullptr) {
-        bv = *reinterpret_cast<const float4*>(p.bias + ch + (is_up ? p.hidden : 0));
-        if (is_up) bg = *reinterpret_cast<const float4*>(p.bias + ch);
+      if (rb_l >= 0 && (m == 0 || fold_sx || p.bias_mstride != 0) && p.bias != nullptr) {
+        const float* bm = p.bias + (size_t)m * p.bias_mstride;
+        bv = *reinterpret_cast<const float4*>(bm + ch + (is_up ? p.hidden : 0));
+        if (is_up) bg = *reinterpret_cast<const float4*>(bm + ch);
       }
       const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
       const float bgate[4] = {bg.x, bg.y, bg.z, bg.w};
@@ -547,7 +551,10 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
           }
           if (t < p.T && rb_l >= 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fabsf(v[i]));
+            for (int i = 0; i < 4; ++i) {
+              mx = fmaxf(mx, two_sided ? v[i] : fabsf(v[i]));
+              if (two_sided) mn = fmaxf(mn, -v[i]);
+            }
             *reinterpret_cast<float4*>(ycol + (size_t)t * p.out) = make_float4(v[0], v[1], v[2], v[3]);
           }
         }
@@ -558,6 +565,11 @@ __global__ __launch_bounds__(256, MINW) void gemm_tiled_kernel(const TiledParams
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
       if (lane == 0) amax_raise(&p.amax_out[m], mx);
+      if (two_sided) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mn = fmaxf(mn, __shfl_xor(mn, o, 64));
+        if (lane == 0) amax_raise(&p.amax_neg[m], mn);
+      }
     }
   }  // members
 }
@@ -611,7 +623,7 @@ int launch_gemm_tiled(const GemmArgs& a, hipStream_t st) {
   p.rowsum = a.rowsum; p.rowsum_mstride = a.rowsum_mstride;
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
+  p.bias = a.bias; p.bias_mstride = a.bias_mstride; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.amax_neg = a.amax_neg; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks;
   p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.hidden = 0;

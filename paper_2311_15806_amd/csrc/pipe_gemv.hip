@@ -38,9 +38,11 @@ struct StreamParams {
   const float* scales;     // 16 row scales per position
   const StreamBin* bins;
   const float* bias;
+  long long bias_mstride;  // 0: the first member's (or the sum's) vector; else one vector per member
   float* y;
   int32_t* acc_out;
   uint32_t* amax_out;
+  uint32_t* amax_neg;      // if set: positive and negative parts of the range apart
   const float* res;        // skip tensor [res_members, T, out] or nullptr
   long long res_mstride;
   int res_members, res_pre_act;
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
       }
       if (ACC_OUT) continue;
       if (fold_sx && m + 1 < p.M) continue;
-      const float bm = (m == 0 || fold_sx) ? bias : 0.f;
+      const float bm = (m == 0 || fold_sx) ? bias : (p.bias_mstride != 0 && p.bias != nullptr ? p.bias[(size_t)m * p.bias_mstride + col] : 0.f);
       float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);   // same rounding as the tiled kernel
       yacc = 0.f;
       float rsum = 0.f;
@@ -379,10 +381,17 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
       else if (p.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
       if (!p.res_pre_act) v += rsum;
       if (p.amax_out != nullptr) {
-        float mx = tg < p.T ? fabsf(v) : 0.f;
+        const bool two_sided = p.amax_neg != nullptr;
+        float mx = tg < p.T ? (two_sided ? fmaxf(v, 0.f) : fabsf(v)) : 0.f;
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
         if (lane == 0) amax_raise(&p.amax_out[m], mx);
+        if (two_sided) {
+          float mn = tg < p.T ? fmaxf(-v, 0.f) : 0.f;
+#pragma unroll
+          for (int s = 32; s > 0; s >>= 1) mn = fmaxf(mn, __shfl_xor(mn, s, 64));
+          if (lane == 0) amax_raise(&p.amax_neg[m], mn);
+        }
       }
       if (tg < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + tg) * p.out + col] = v;
     }
@@ -588,7 +597,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_multi_kernel(const Str
         yacc = fmaf(sc, (float)a, yacc);
       }
       if (fold_sx && m + 1 < p.M) continue;
-      const float bm = (m == 0 || fold_sx) ? bias : 0.f;
+      const float bm = (m == 0 || fold_sx) ? bias : (p.bias_mstride != 0 && p.bias != nullptr ? p.bias[(size_t)m * p.bias_mstride + col] : 0.f);
       float v = fold_sx ? yacc + bm : fmaf(sx, yacc, bm);
       yacc = 0.f;
       float rsum = 0.f;
@@ -602,10 +611,17 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_multi_kernel(const Str
       else if (p.act == PIPE_ACT_RELU) v = fmaxf(v, 0.f);
       if (!p.res_pre_act) v += rsum;
       if (p.amax_out != nullptr) {
-        float mx = tg < p.T ? fabsf(v) : 0.f;
+        const bool two_sided = p.amax_neg != nullptr;
+        float mx = tg < p.T ? (two_sided ? fmaxf(v, 0.f) : fabsf(v)) : 0.f;
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s, 64));
         if (lane == 0) amax_raise(&p.amax_out[m], mx);
+        if (two_sided) {
+          float mn = tg < p.T ? fmaxf(-v, 0.f) : 0.f;
+#pragma unroll
+          for (int s = 32; s > 0; s >>= 1) mn = fmaxf(mn, __shfl_xor(mn, s, 64));
+          if (lane == 0) amax_raise(&p.amax_neg[m], mn);
+        }
       }
       if (tg < p.T) p.y[((size_t)(p.reduce ? 0 : m) * p.T + tg) * p.out + col] = v;
     }
@@ -670,7 +686,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
   p.s_x = a.s_x; p.sx_mstride = a.sx_mstride;
   p.codes = e->codes_dev; p.scales = e->scales_all_dev;
   p.bins = e->bins_dev;
-  p.bias = a.bias; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
+  p.bias = a.bias; p.bias_mstride = a.bias_mstride; p.y = a.y; p.acc_out = a.acc_out; p.amax_out = a.amax_out; p.amax_neg = a.amax_neg; p.res = a.res; p.res_mstride = a.res_mstride; p.res_members = a.res_members; p.res_pre_act = a.res_pre_act; p.zero_after = a.zero_after; p.zero_n = a.zero_n; p.zero_big = a.zero_big; p.zero_big_n = a.zero_big_n;
   p.T = a.T; p.out = e->out; p.K = e->K; p.nks = e->nks; p.M = a.M; p.reduce = a.reduce; p.act = a.act;
   p.x_f32 = a.x_f32; p.s_static = a.s_static; p.act_qmax = g_act_qmax_host; p.in = e->in;
   if (a.x_f32 != nullptr && e->bin_cap != R) return PIPE_EINVAL;

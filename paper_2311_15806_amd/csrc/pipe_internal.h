@@ -143,6 +143,7 @@ struct pipe_expansion {
   int32_t* asym_wsum_dev = nullptr;
   float* asym_C_dev = nullptr;
   float* asym_bias_dev = nullptr;
+  float* asym_P_dev = nullptr;        // [K][out]: s_k[o] * wsum_k[o] (member chains sum their own orders' rows)
   // split bins of the weight-streaming kernel: partial tiles, and arrival counters (zero between launches)
   int32_t* split_sum_dev = nullptr;   // [n_bins][PIPE_MAX_SPLIT][bin_cap][256]
   uint32_t* split_cnt_dev = nullptr;  // [n_bins]
@@ -200,7 +201,7 @@ bool pipe_capturing();
   do {                                                      \
     if (!pipe_dry_run()) hipLaunchKernelGGL(__VA_ARGS__);   \
   } while (0)
-enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_RES, WS_RES_Q, WS_CSUM, WS_SLOTS };
+enum { WS_QX = 0, WS_ROWSUM, WS_SCAL, WS_Y1, WS_H, WS_QH, WS_ROWSUM_H, WS_RESID, WS_ENERGY, WS_MISC, WS_Q8X, WS_CHAIN, WS_DIAG, WS_DIAG_CODES, WS_DIAG_DENSE, WS_RES, WS_RES_Q, WS_CSUM, WS_ABIAS, WS_SLOTS };
 
 // ------------------------------------------------------------------ expand kernels (pipe_expand.hip)
 int launch_row_energy(const float* E, int out, int in, double* row_energy, hipStream_t st);
@@ -238,7 +239,7 @@ int launch_zero_u32(uint32_t* p, int n, hipStream_t st);
 // asymmetric activation codes: range slots {max(x,0), max(-x,0)}; unsigned a-bit codes stored minus 2^(a-1) in the
 // fragment layout with their token sums, scale and 2^(a-1) - z to device memory; the token-free correction as a bias
 int launch_minmax(const float* x, int64_t n, uint32_t* slots, hipStream_t st);
-int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
+int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* hi_slot, const uint32_t* nlo_slot, int act_bits,
                          uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
                          hipStream_t st);
 int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int kh, int kw, int stride, int pad, int nhwc,
@@ -248,6 +249,15 @@ int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int 
 int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
                      uint32_t* slots, hipStream_t st);
 int launch_asym_acc_fix(int32_t* acc, const int32_t* wsum, const int32_t* dz, int K, int T, int out, hipStream_t st);
+// member chains with asymmetric codes: per-member offset vectors [M][n] (reduce = 0; the bias joins member 0) or their
+// sum plus the bias [n] (reduce = 1) from P[k][o] = s_k[o] * sum_i q_k[o,i]; clears n_clear words at `clear`
+struct MemberRanges {
+  int M;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K];
+};
+int launch_asym_bias_members(const float* bias, const float* P, const float* scale, int scale_stride, const int32_t* dz,
+                             int dz_stride, int M, const int* lo, const int* hi, int reduce, float* outv, int n, uint32_t* clear,
+                             int n_clear, hipStream_t st);
 int launch_row_code_sums(const int8_t* codes, int rows, int in, int group, const int32_t* gids, int32_t* wsum, hipStream_t st);
 // launch_absmax also zeroes n_zero ints at zero_me (the code sums of the quantizer that follows).
 int launch_absmax(const float* x, int64_t n, uint32_t* amax_bits, int32_t* zero_me, int n_zero, hipStream_t st);
@@ -298,6 +308,8 @@ struct GemmArgs {
                          // itself (then qx, rowsum and s_x are not read), else nullptr
   float s_static;        // with x_f32: the given activation scale, or <= 0 for the dynamic one
   const float* bias;     // or nullptr
+  int64_t bias_mstride = 0;   // 0: one vector, added to the first member (or to the members' sum); else member m adds
+                              // bias + m * bias_mstride (members kept apart: the asymmetric codes' per-member offsets)
   int reduce;            // 1: y[T,out]; 0: y[M,T,out]
   int act;               // 0 none; PIPE_ACT_GELU fused in the epilogue; PIPE_ACT_SILU_GATED: the layer is gate||up and
                          // the tiled kernel writes h = SiLU(gate)*up, [M,T,out/2] (members kept apart)
@@ -309,6 +321,8 @@ struct GemmArgs {
   float* y;
   int32_t* acc_out;      // debug: [K,T,out] or nullptr (then y may be nullptr)
   uint32_t* amax_out;    // per member max|output| bit pattern (or nullptr)
+  uint32_t* amax_neg = nullptr;   // if set: amax_out[m] receives max(output, 0) and amax_neg[m] max(-output, 0), the
+                                  // range the asymmetric quantizer of the next layer needs
   uint32_t* zero_after;  // words the kernel clears (the max|x| slots this call consumed), or nullptr
   int zero_n = 1;        // how many (at most 64)
   uint32_t* zero_big = nullptr;   // a buffer the kernel clears as well (the code sums the next layer's quantizer

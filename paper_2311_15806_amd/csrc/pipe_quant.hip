@@ -442,11 +442,12 @@ __global__ __launch_bounds__(BLK) void minmax_kernel(const float* __restrict__ x
 // qa = 2^a - 1, shift = 2^(a-1).  Writes the fragment layout, adds the token code sums (zero on
 // entry), optionally the unsigned codes row-major, and (block 0,0) the scale and shift - z.
 __global__ __launch_bounds__(BLK) void quantize_asym_kernel(const float* __restrict__ x, int T, int in, int in_pad,
-                                                            const uint32_t* __restrict__ slots, float qa, int shift,
+                                                            const uint32_t* __restrict__ hi_slot,
+                                                            const uint32_t* __restrict__ nlo_slot, float qa, int shift,
                                                             uint8_t* __restrict__ qx_frag, int32_t* __restrict__ rowsum,
                                                             uint8_t* __restrict__ qx_rowmajor, float* __restrict__ scale_out,
                                                             int32_t* __restrict__ dz_out) {
-  const float hi = __uint_as_float(slots[0]), nlo = __uint_as_float(slots[1]);
+  const float hi = __uint_as_float(hi_slot[0]), nlo = __uint_as_float(nlo_slot[0]);
   const float s = __fdiv_rn(__fadd_rn(hi, nlo), qa);
   const bool live = s > 0.f;
   const float zf = live ? fminf(fmaxf(rintf(__fdiv_rn(nlo, s)), 0.f), qa) : 0.f;
@@ -526,6 +527,29 @@ __global__ void asym_bias_kernel(const float* __restrict__ bias, const float* __
   if (o >= n) return;
   const float f = scale[0] * (float)dz[0];
   out[o] = (bias != nullptr ? bias[o] : 0.f) + f * C[o];
+}
+
+// Members of a chain, each with its own scale and zero point: member m's offset vector is
+// (s_m * dz_m) * sum_{k in member m, ascending} P[k][o], P[k][o] = s_k[o] * (sum_i q_k[o,i]); the layer's
+// bias joins the first member.  reduce: one vector, the members' sum (ascending m) plus the bias.
+__global__ void asym_bias_members_kernel(const float* __restrict__ bias, const float* __restrict__ P, const float* __restrict__ scale,
+                                         int scale_stride, const int32_t* __restrict__ dz, int dz_stride, MemberRanges mr,
+                                         int reduce, float* __restrict__ outv, int n, uint32_t* __restrict__ clear, int n_clear) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o < n_clear) clear[o] = 0u;
+  if (o >= n) return;
+  float tot = bias != nullptr ? bias[o] : 0.f;
+  for (int m = 0; m < mr.M; ++m) {
+    float c = 0.f;
+    for (int k = mr.lo[m]; k <= mr.hi[m]; ++k) c += P[(size_t)k * n + o];
+    const float f = scale[m * scale_stride] * (float)dz[m * dz_stride];
+    if (reduce) {
+      tot = fmaf(f, c, tot);
+    } else {
+      outv[(size_t)m * n + o] = fmaf(f, c, m == 0 ? tot : 0.f);
+    }
+  }
+  if (reduce) outv[o] = tot;
 }
 
 // exact accumulators of the debug export: acc[k][t][o] += dz * wsum[k][o]
@@ -745,13 +769,13 @@ int launch_minmax(const float* x, int64_t n, uint32_t* slots, hipStream_t st) {
   return PIPE_OK;
 }
 
-int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
-                         uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
+int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, const uint32_t* hi_slot, const uint32_t* nlo_slot,
+                         int act_bits, uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
                          hipStream_t st) {
   int rc = launch_zero_u32(reinterpret_cast<uint32_t*>(rowsum), T_pad, st);
   if (rc) return rc;
   dim3 grid(T_pad / 16, ksplit_for(T_pad, in_pad));
-  PIPE_KLAUNCH(quantize_asym_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, slots, (float)((1 << act_bits) - 1),
+  PIPE_KLAUNCH(quantize_asym_kernel, grid, dim3(BLK), 0, st, x, T, in, in_pad, hi_slot, nlo_slot, (float)((1 << act_bits) - 1),
                      1 << (act_bits - 1), qx_frag, rowsum, qx_rowmajor, scale_out, dz_out);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
@@ -760,6 +784,18 @@ int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, c
 int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
                      uint32_t* slots, hipStream_t st) {
   PIPE_KLAUNCH(asym_bias_kernel, dim3((n + 255) / 256), dim3(256), 0, st, bias, C, scale, dz, out, n, slots);
+  PIPE_HIP(hipGetLastError());
+  return PIPE_OK;
+}
+
+int launch_asym_bias_members(const float* bias, const float* P, const float* scale, int scale_stride, const int32_t* dz,
+                             int dz_stride, int M, const int* lo, const int* hi, int reduce, float* outv, int n, uint32_t* clear,
+                             int n_clear, hipStream_t st) {
+  MemberRanges mr{};
+  mr.M = M;
+  for (int m = 0; m < M; ++m) { mr.lo[m] = lo[m]; mr.hi[m] = hi[m]; }
+  PIPE_KLAUNCH(asym_bias_members_kernel, dim3((std::max(n, n_clear) + 255) / 256), dim3(256), 0, st, bias, P, scale, scale_stride,
+               dz, dz_stride, mr, reduce, outv, n, clear, n_clear);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -111,6 +111,82 @@ def test_chain_of_one_and_two_layers_matches_the_other_entry_points(pipe):
     g1.free(); g2.free()
 
 
+def _check_chain_asymmetric(pipe, olayers, glayers, x, split, act_bits=8):
+    """Teacher-forced layer by layer, then free-running, as _check_chain, under asymmetric codes."""
+    L = len(olayers)
+    y, acts = pipe.pipe_chain_forward_asymmetric(glayers, dev(x), split=split, return_acts=True)
+    y = y.cpu().numpy()
+    acts = [a.cpu().numpy() for a in acts]
+    M = 1 if split is None else len(split)
+    for l in range(L):
+        skips = po.chain_skips(olayers, l, x, acts, M)
+        if l == 0:
+            ref = po.chain_layer_members(olayers[0], x, True, skips, split, None, act_bits, asymmetric=True)
+        else:
+            ref = po.chain_layer_members(olayers[l], acts[l - 1], False, skips, split, None, act_bits, asymmetric=True)
+        if l < L - 1:
+            for m in range(M):
+                assert_close_fp32(acts[l][m], ref[m], tol=2e-5)
+        else:
+            assert_close_fp32(y, po.sum_members(ref))
+    full = po.chain_forward(olayers, x, split=split, act_bits=act_bits, asymmetric=True)
+    assert_close_fp32(y, full["y"], tol=3e-2, elementwise=False)
+    return y
+
+
+@pytest.mark.parametrize("tokens", [150, 37, 9])
+@pytest.mark.parametrize("bits,K,split", [(4, 4, [2, 2]), (2, 4, [1, 1, 2]), (8, 2, None), (2, 8, [3, 3, 2])])
+def test_asymmetric_chain_parity(pipe, bits, K, split, tokens):
+    """Sec. 4.3's asymmetric codes in front of every layer of a residual stack: every member's hidden
+    tensor is quantized over its own range (taken in the producing kernel's epilogue) with its own
+    zero point; tiled and weight-streaming kernels, bins of more than 4 orders included."""
+    w = wl.residual_stack(128, 2, 64, bits, K, 0.5, 16, tokens, split or (K,))
+    olayers, glayers, gpu = _build(pipe, w)
+    x = wl.make_input(w)
+    y = _check_chain_asymmetric(pipe, olayers, glayers, x, split)
+    y_again = pipe.pipe_chain_forward_asymmetric(glayers, dev(x), split=split).cpu().numpy()   # every range slot was cleared
+    assert np.array_equal(y, y_again)
+    # the symmetric call on the same expansions and workspace is unchanged by the asymmetric one
+    _check_chain(pipe, w, olayers, glayers, x, split)
+    for g in gpu:
+        g.free()
+
+
+def test_asymmetric_chain_variants(pipe):
+    """GELU inside the chain (tensors with a negative part: a zero point between the ends), skips from
+    the input and from hidden tensors on both sides of the activation, a one-sided negative input,
+    4-bit activations, one layer, and both kernels forced."""
+    spec = lambda o, i: wl.LayerSpec(o, i, 4, 4, 0.5, 16)
+    layers = (spec(112, 112), spec(112, 112), spec(80, 112), spec(80, 80))
+    chain = (("relu", 0, False), ("gelu", 0, True), ("none", -1, True), ("none", 3, True))
+    w = wl.Workload(name="chain_variants", config=6, kind="chain", layers=layers, tokens=70, split=(2, 1, 1),
+                    w_dist=dict(kind=0, std=0.13), x_dist=dict(kind=0), chain=chain)
+    olayers, glayers, gpu = _build(pipe, w)
+    x = wl.make_input(w)
+    for kernel in (0, 1, 2):
+        pipe.pipe_set_kernel(kernel)
+        try:
+            _check_chain_asymmetric(pipe, olayers, glayers, x, [2, 1, 1])
+            _check_chain_asymmetric(pipe, olayers, glayers, -np.abs(x), None)
+        finally:
+            pipe.pipe_set_kernel(0)
+    pipe.pipe_set_activation_bits(4)
+    try:
+        _check_chain_asymmetric(pipe, olayers, glayers, x, [2, 2], act_bits=4)
+    finally:
+        pipe.pipe_set_activation_bits(8)
+    # one layer: the single-layer entry point
+    b0 = glayers[0][1]
+    y1 = pipe.pipe_chain_forward_asymmetric([(gpu[0], b0, 0, -1, True)], dev(x), split=[1, 3]).cpu().numpy()
+    assert_close_fp32(y1, pipe.pipe_forward_asymmetric(gpu[0], dev(x), split=[1, 3], bias=b0).cpu().numpy(), tol=1e-6)
+    assert_close_fp32(y1, po.forward_asymmetric(olayers[0].exp, x, split=[1, 3], bias=olayers[0].bias)["y"])
+    # an all-zero input: every layer sees its bias only
+    z = np.zeros_like(x)
+    _check_chain_asymmetric(pipe, olayers, glayers, z, [2, 1, 1])
+    for g in gpu:
+        g.free()
+
+
 def test_chain_argument_errors(pipe):
     w = wl.residual_stack(64, 1, 32, 4, 2, 1.0, 16, 8, (2,))
     _, glayers, gpu = _build(pipe, w, with_bias=False)

@@ -720,6 +720,62 @@ def test_chain_members_are_independent_networks():
     assert np.allclose(r["members"][0], one["y"], rtol=1e-5, atol=1e-7)
 
 
+def test_asymmetric_chain_is_the_pinned_asymmetric_layer_applied_member_wise():
+    """Asymmetric codes in front of every layer of a chain (Sec. 4.3).  One member: the pinned
+    single-layer routine applied L times with activation and skip between.  Two members: member 2
+    is the network of the order-2 terms alone on codes minus their zero point (written out with an
+    int64 einsum and the quantizer's own outputs), it carries no bias, and the sum is the members'."""
+    skips = [(-1, True), (1, True), (-1, True)]
+    acts = ["relu", "relu", "none"]
+    layers, _, bs = _chain_net(87, [24, 32, 32, 8], 2, 4, skips, acts)
+    x = np.random.default_rng(88).standard_normal((5, 24)).astype(f32)
+    r = po.chain_forward(layers, x, asymmetric=True)
+    a1 = np.maximum(po.forward_asymmetric(layers[0].exp, x, bias=bs[0])["y"], 0)
+    a2 = np.maximum((po.forward_asymmetric(layers[1].exp, a1, bias=bs[1])["y"] + a1).astype(f32), 0)
+    y = po.forward_asymmetric(layers[2].exp, a2, bias=bs[2])["y"]
+    assert np.array_equal(r["acts"][0][0], a1) and np.array_equal(r["acts"][1][0], a2)
+    assert np.array_equal(r["y"], y)
+    # after a ReLU the zero point is 0 and the codes span the whole range
+    Q2, s2, z2 = po.quantize_activations_asymmetric(a1)
+    assert z2 == 0 and Q2.max() == 255
+    assert not np.array_equal(r["y"], po.chain_forward(layers, x)["y"])
+
+    r2 = po.chain_forward(layers, x, split=[1, 1], asymmetric=True)
+
+    def order2(e, a):
+        Q, s, z = po.quantize_activations_asymmetric(a)
+        acc = np.einsum("ti,oi->to", Q.astype(np.int64) - z, e.dense_codes(2).astype(np.int64))
+        return f32(s) * (e.dense_scales(2)[None, :] * acc.astype(f32))
+
+    b1 = np.maximum(order2(layers[0].exp, x), 0)
+    b2 = np.maximum((order2(layers[1].exp, b1) + b1).astype(f32), 0)
+    y2 = order2(layers[2].exp, b2)
+    assert np.allclose(r2["acts"][1][1], b2, rtol=1e-6, atol=1e-9)
+    assert np.allclose(r2["members"][1], y2, rtol=1e-6, atol=1e-9)
+    assert np.array_equal(r2["y"], (r2["members"][0] + r2["members"][1]).astype(f32))
+    with pytest.raises(ValueError):
+        po.chain_forward(layers, x, s_x=0.1, asymmetric=True)
+
+
+@pytest.mark.parametrize("a", [4, 6])
+def test_asymmetric_chain_is_closer_to_the_float_network_after_relus(a):
+    """Why the comparison of Sec. 4.3 is made under asymmetric quantization: a tensor that left a
+    ReLU uses only half of a symmetric grid.  On a ReLU network with a-bit activations and an
+    expansion that is exact to 1e-7 the asymmetric chain must be clearly closer to the fp64 network."""
+    widths = [32, 48, 48, 16]
+    skips = [(-1, True)] * 3
+    acts = ["relu", "relu", "none"]
+    layers, Ws, bs = _chain_net(89, widths, 4, 8, skips, acts)
+    for ly in layers:
+        ly.bias = (ly.bias / 6.0).astype(f32)
+    bs = [ly.bias for ly in layers]
+    x = np.abs(np.random.default_rng(90).standard_normal((64, 32))).astype(f32)   # e.g. the output of an earlier ReLU
+    ref = _float_net(Ws, bs, skips, acts, x)[-1]
+    e_sym = np.abs(po.chain_forward(layers, x, split=[2, 2], act_bits=a)["y"] - ref).mean()
+    e_asym = np.abs(po.chain_forward(layers, x, split=[2, 2], act_bits=a, asymmetric=True)["y"] - ref).mean()
+    assert e_asym < 0.7 * e_sym, (e_asym, e_sym)
+
+
 def test_conv_chain_is_layer_by_layer_conv_and_converges_to_torch():
     """A residual conv stack as member chains: with one member it is the pinned conv forward
     applied layer by layer (ReLU, skip); with 8-bit orders it reproduces torch's fp64 ConvNet."""
