@@ -294,6 +294,18 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
                      const float* bias1_dev, const float* bias2_dev, float* h_dev,
                      float* y_dev, void* stream);
 
+/* pipe_mlp_forward with asymmetric activation codes (Sec. 4.3; the affine quantizer of
+ * pipe_forward_asymmetric) in front of both layers: the input is quantized over its own range
+ * [min(x,0), max(x,0)], every member's hidden activation over that tensor's own range with its
+ * own scale and integer zero point (GELU and SiLU(gate)*up take both signs).  Ranges are always
+ * dynamic.  Arguments, member semantics, h_dev and errors as pipe_mlp_forward; PIPE_ESHAPE when
+ * (2^a - 1) * q_max * in_features does not fit 31 bits.  The first call on an expansion builds
+ * the sums of its codes (allocates, synchronizes: PIPE_ENOTREADY under capture).            */
+int pipe_mlp_forward_asymmetric(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                                const float* x_dev, int T, const int* split, int M,
+                                const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                                float* y_dev, void* stream);
+
 /* One layer of a member chain (pipe_chain_forward, pipe_chain_forward_conv).     */
 typedef struct pipe_chain_layer {
   const pipe_expansion* e; /* [out_l, in_l]; in_l = width of the tensor entering it,

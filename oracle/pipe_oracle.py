@@ -563,7 +563,8 @@ def silu_mul(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
 
 
 def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, split=None,
-                bias1=None, bias2=None, s_x: Optional[float] = None, act_bits: int = 8):
+                bias1=None, bias2=None, s_x: Optional[float] = None, act_bits: int = 8,
+                asymmetric: bool = False):
     """Two expanded layers with an activation between, run as an ensemble.
 
     Member m uses only its own orders in BOTH layers, quantizes its own hidden
@@ -571,11 +572,20 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
     first member; the members' outputs are summed after the last layer.
     kind = "gelu": h = GELU(layer1(x));  kind = "gated": layer1 has 2H outputs
     (gate rows first, then up rows) and h = SiLU(gate) * up.
+    asymmetric: the input and every member's hidden activation get the affine codes of
+    Sec. 4.3 (quantize_activations_asymmetric), each over its own range; the contractions run
+    on the codes minus their zero point.
     Returns dict(y fp32 [T,O2], members [M,T,O2], h [M,T,H], s_h [M])."""
     if exp1.K != exp2.K:
         raise ValueError("both layers need the same expansion order")
     rngs = member_ranges(exp1.K, split)
-    Qx, sx = quantize_activations(x, s_x, act_bits)
+    if asymmetric:
+        if s_x is not None:
+            raise ValueError("asymmetric codes take their range from the tensor")
+        Qu, sx, zx = quantize_activations_asymmetric(x, act_bits)
+        Qx = Qu.astype(np.int32) - int(zx)
+    else:
+        Qx, sx = quantize_activations(x, s_x, act_bits)
     acc1 = forward_acc(exp1, Qx)
     y1 = dequantize(exp1, acc1, sx, split, bias1, f32)          # [M, T, O1]
     hs = []
@@ -589,12 +599,13 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
             raise ValueError("kind must be 'gelu' or 'gated'")
         hs.append(h)
     hs = np.stack(hs)
-    second = mlp_second_layer(exp2, hs, split, bias2, act_bits)
+    second = mlp_second_layer(exp2, hs, split, bias2, act_bits, asymmetric)
     second.update(h=hs, y1=y1, s_x=sx, Qx=Qx)
     return second
 
 
-def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, act_bits: int = 8):
+def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, act_bits: int = 8,
+                     asymmetric: bool = False):
     """Last layer of the ensemble on given hidden activations hs [M, T, H]: member m
     quantizes hs[m] with its own dynamic scale, uses its own orders of exp2 (bias in
     the first member only), and the members are summed in ascending order.
@@ -604,7 +615,11 @@ def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, ac
         raise ValueError("one hidden activation per member")
     outs, shs, Qhs = [], [], []
     for m in range(len(rngs)):
-        Qh, sh = quantize_activations(hs[m], None, act_bits)
+        if asymmetric:
+            Qu, sh, zh = quantize_activations_asymmetric(hs[m], act_bits)
+            Qh = Qu.astype(np.int32) - int(zh)
+        else:
+            Qh, sh = quantize_activations(hs[m], None, act_bits)
         acc2 = forward_acc(exp2, Qh)
         outs.append(dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m])
         shs.append(sh)

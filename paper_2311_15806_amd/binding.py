@@ -59,6 +59,7 @@ def _load():
     lib.pipe_forward_conv2d_acc.argtypes = [vp, vp] + [ci] * 9 + [cf, vp, vp, vp, vp]
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
+    lib.pipe_mlp_forward_asymmetric.argtypes = [vp, vp, ci, vp, ci, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_asymmetric.argtypes = [vp, ci, vp, ci, pi, ci, vp, vp, vp]
@@ -399,6 +400,20 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
     _check(_lib.pipe_mlp_forward(l1.handle, l2.handle, int(act), _ptr(x, torch.float32), T, float(s_x),
                                  arr, m, _ptr(bias1, torch.float32), _ptr(bias2, torch.float32),
                                  _ptr(h), _ptr(y), _stream()), "pipe_mlp_forward")
+    return (y, h) if return_hidden else y
+
+
+def pipe_mlp_forward_asymmetric(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, split=None, bias1=None,
+                                bias2=None, return_hidden: bool = False, out: Optional[torch.Tensor] = None):
+    """pipe_mlp_forward with asymmetric activation codes in front of both layers."""
+    T = x.shape[0]
+    M = 1 if split is None else len(split)
+    y = out if out is not None else torch.empty((T, l2.out_features), dtype=torch.float32, device=x.device)
+    h = torch.empty((M, T, l2.in_features), dtype=torch.float32, device=x.device) if return_hidden else None
+    arr, m = _split(split)
+    _check(_lib.pipe_mlp_forward_asymmetric(l1.handle, l2.handle, int(act), _ptr(x, torch.float32), T, arr, m,
+                                            _ptr(bias1, torch.float32), _ptr(bias2, torch.float32), _ptr(h), _ptr(y),
+                                            _stream()), "pipe_mlp_forward_asymmetric")
     return (y, h) if return_hidden else y
 
 

@@ -1448,7 +1448,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
     a.act = 0; a.y = y1; a.amax_out = nullptr;
     rc = run_gemm(a, small, st);
     if (rc) return rc;
-    rc = launch_mlp_act(y1, Mm, T, H, act, h, amax_h, st);
+    rc = launch_mlp_act(y1, Mm, T, H, act, h, amax_h, nullptr, st);
     if (rc) return rc;
   }
   // each member quantizes its own hidden activation with its own scale
@@ -1473,6 +1473,106 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   fill_members(a2, Mm, lo, hi);
   rc = run_gemm(a2, small, st);
   if (rc == PIPE_OK) t_ws->amax_h_dirty = false;
+  return rc;
+}
+
+// pipe_mlp_forward with asymmetric activation codes (Sec. 4.3) in front of both layers: the input over its own
+// range, every member's hidden activation over that tensor's range (taken where it is produced) with its own
+// zero point; the token-free terms of the zero points join the bias vectors.
+extern "C" int pipe_mlp_forward_asymmetric(const pipe_expansion* l1, const pipe_expansion* l2, int act, const float* x_dev, int T,
+                                           const int* split, int M, const float* bias1_dev, const float* bias2_dev,
+                                           float* h_dev, float* y_dev, void* stream) {
+  if (!l1 || !l2 || T < 0) return PIPE_EINVAL;
+  if (l1->conv_C > 0 || l2->conv_C > 0) return PIPE_EINVAL;
+  if (act != PIPE_ACT_GELU && act != PIPE_ACT_SILU_GATED) return PIPE_EINVAL;
+  if (l1->K != l2->K) return PIPE_ESPLIT;
+  const int H = l2->in;
+  if (l1->out != (act == PIPE_ACT_SILU_GATED ? 2 * H : H)) return PIPE_ESHAPE;
+  int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
+  int rc = parse_split(l1->K, split, M, lo, hi, &Mm);
+  if (rc) return rc;
+  if (T == 0) return PIPE_OK;
+  if (!x_dev || !y_dev) return PIPE_EINVAL;
+  const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
+  for (const pipe_expansion* e : {l1, l2})   // |Q - z| <= 2^a - 1: the exact accumulator must fit 32 bits
+    if ((int64_t)((1 << act_bits) - 1) * ((1 << (e->qbits - 1)) - 1) * e->in >= ((int64_t)1 << 31)) return PIPE_ESHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  CallScope scope(stream);
+  if ((rc = asym_prepare(l1, st)) != PIPE_OK || (rc = asym_prepare(l2, st)) != PIPE_OK) return rc;
+  const bool small = use_stream_kernel(l1, T);
+  ActBuffers b;
+  rc = get_act_buffers(T, l1->in_pad, small, &b);
+  if (rc) return rc;
+  const int T_pad = b.T_pad;
+  float* h = h_dev ? h_dev : (float*)pipe_ws_get(WS_H, (size_t)Mm * T * H * sizeof(float));
+  uint8_t* qh = (uint8_t*)pipe_ws_get(WS_QH, (size_t)Mm * T_pad * l2->in_pad);
+  int32_t* rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+  float* bias_m = (float*)pipe_ws_get(WS_ABIAS, (size_t)Mm * std::max(l1->out, l2->out) * sizeof(float));
+  if (!h || !qh || !rowsum_h || !bias_m) return pipe_ws_error();
+  const bool paired = act == PIPE_ACT_SILU_GATED && !small && l1->n_rb % 2 == 0;
+  float* y1 = nullptr;
+  if (act == PIPE_ACT_SILU_GATED && !paired) {
+    y1 = (float*)pipe_ws_get(WS_Y1, (size_t)Mm * T * l1->out * sizeof(float));
+    if (!y1) return pipe_ws_error();
+  }
+  if (!small) {
+    if ((rc = ensure_tables(l1, Mm, lo, hi, paired ? 1 : 0)) != PIPE_OK) return rc;
+    if ((rc = ensure_tables(l2, Mm, lo, hi, 0)) != PIPE_OK) return rc;
+  }
+  if (pipe_dry_run()) return PIPE_OK;
+  // slots as in pipe_chain_forward_asymmetric: the input's range and offset, the members' ranges (positive parts
+  // [0, 16), negative parts [16, 32)), offsets and scales
+  uint32_t* slots_x = b.amax + 64;
+  int32_t* dz_x = reinterpret_cast<int32_t*>(b.amax + 66);
+  uint32_t* rng = b.amax + 128;
+  int32_t* dz_h = reinterpret_cast<int32_t*>(b.amax + 128 + 4 * PIPE_MAX_K);
+  float* scale_h = b.scale + 16;
+  if (t_ws->range_h_dirty) {
+    rc = launch_zero_u32(rng, 4 * PIPE_MAX_K, st);
+    if (rc) return rc;
+  }
+  t_ws->range_h_dirty = true;
+
+  rc = launch_minmax(x_dev, (int64_t)T * l1->in, slots_x, st);
+  if (rc) return rc;
+  rc = launch_quantize_asym(x_dev, T, l1->in, l1->in_pad, T_pad, slots_x, slots_x + 1, act_bits, b.qx, b.rowsum, nullptr, b.scale, dz_x, st);
+  if (rc == PIPE_OK)
+    rc = launch_asym_bias_members(bias1_dev, l1->asym_P_dev, b.scale, 0, dz_x, 0, Mm, lo, hi, 0, bias_m, l1->out, slots_x, 2, st);
+  if (rc) {
+    (void)launch_zero_u32(slots_x, 2, st);
+    return rc;
+  }
+  // layer 1: every member reads the same codes; its own offset vector; outputs stay separate
+  GemmArgs a{};
+  a.e = l1; a.T = T; a.T_pad = T_pad; a.qx = b.qx; a.rowsum = b.rowsum; a.s_x = b.scale;
+  a.bias = bias_m; a.bias_mstride = l1->out; a.reduce = 0; a.zero_after = nullptr; a.zero_n = 0;
+  fill_members(a, Mm, lo, hi);
+  if (act == PIPE_ACT_GELU || paired) {
+    a.act = act; a.y = h; a.amax_out = rng; a.amax_neg = rng + PIPE_MAX_K;
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
+  } else {
+    a.act = 0; a.y = y1;
+    rc = run_gemm(a, small, st);
+    if (rc) return rc;
+    rc = launch_mlp_act(y1, Mm, T, H, act, h, rng, rng + PIPE_MAX_K, st);
+    if (rc) return rc;
+  }
+  for (int m = 0; m < Mm; ++m) {
+    rc = launch_quantize_asym(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, rng + m, rng + PIPE_MAX_K + m, act_bits,
+                              qh + (size_t)m * T_pad * l2->in_pad, rowsum_h + (size_t)m * T_pad, nullptr, scale_h + m, dz_h + m, st);
+    if (rc) return rc;
+  }
+  rc = launch_asym_bias_members(bias2_dev, l2->asym_P_dev, scale_h, 1, dz_h, 1, Mm, lo, hi, 1, bias_m, l2->out, nullptr, 0, st);
+  if (rc) return rc;
+  GemmArgs a2{};
+  a2.e = l2; a2.T = T; a2.T_pad = T_pad; a2.qx = qh; a2.qx_mstride = (int64_t)T_pad * l2->in_pad;
+  a2.rowsum = rowsum_h; a2.rowsum_mstride = T_pad; a2.s_x = scale_h; a2.sx_mstride = 1;
+  a2.bias = bias_m; a2.reduce = 1; a2.act = 0; a2.y = y_dev;
+  a2.zero_after = rng; a2.zero_n = 2 * PIPE_MAX_K;
+  fill_members(a2, Mm, lo, hi);
+  rc = run_gemm(a2, small, st);
+  if (rc == PIPE_OK) t_ws->range_h_dirty = false;
   return rc;
 }
 

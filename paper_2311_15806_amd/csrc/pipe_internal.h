@@ -286,8 +286,9 @@ int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, i
                            int pad, int nhwc, int Ho, int Wo, int in_pad, int T_pad,
                            float s_static, const uint32_t* amax_bits, int8_t* q8_scratch, uint8_t* qx_frag,
                            int32_t* rowsum, float* scale_out, hipStream_t st);
-// Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h|.
-int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
+// Hidden activation of the MLP call: h = act(y1) element-wise, plus per-member max|h| (or, with amax_neg, the
+// positive and negative parts of its range apart).
+int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits, uint32_t* amax_neg,
                    hipStream_t st);
 
 // ------------------------------------------------------------------ contraction kernels

@@ -387,15 +387,18 @@ __global__ __launch_bounds__(BLK) void im2col_codes_kernel(const int8_t* __restr
   if (tok && sum != 0) atomicAdd(&rowsum[t], sum);
 }
 
-// h = act(y1) for every member, and max|h| per member.
+// h = act(y1) for every member, and max|h| per member (amax_neg set: max(h, 0) and max(-h, 0) apart, the range
+// an asymmetric quantizer needs).
 __global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ y1, int T, int H, int act,
-                                                      float* __restrict__ h, uint32_t* __restrict__ amax_bits) {
+                                                      float* __restrict__ h, uint32_t* __restrict__ amax_bits,
+                                                      uint32_t* __restrict__ amax_neg) {
   const int m = blockIdx.y;
   const int64_t n = (int64_t)T * H;
   const int O1 = act == PIPE_ACT_SILU_GATED ? 2 * H : H;
   const float* src = y1 + (size_t)m * T * O1;
   float* dst = h + (size_t)m * n;
-  float mx = 0.f;
+  float mx = 0.f, mn = 0.f;
+  const bool two_sided = amax_neg != nullptr;
   for (int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x; i < n; i += (int64_t)gridDim.x * BLK) {
     float v;
     if (act == PIPE_ACT_SILU_GATED) {
@@ -408,10 +411,15 @@ __global__ __launch_bounds__(BLK) void mlp_act_kernel(const float* __restrict__ 
       v = 0.5f * a * (1.f + erff(a * 0.70710678118654752440f));
     }
     dst[i] = v;
-    mx = fmaxf(mx, fabsf(v));
+    mx = fmaxf(mx, two_sided ? v : fabsf(v));
+    mn = fmaxf(mn, -v);
   }
   mx = block_max(mx);
   if (threadIdx.x == 0) amax_raise(&amax_bits[m], mx);
+  if (two_sided) {
+    mn = block_max(mn);
+    if (threadIdx.x == 0) amax_raise(&amax_neg[m], mn);
+  }
 }
 
 
@@ -749,13 +757,13 @@ int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int 
   return PIPE_OK;
 }
 
-int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits,
+int launch_mlp_act(const float* y1, int M, int T, int H, int act, float* h, uint32_t* amax_bits, uint32_t* amax_neg,
                    hipStream_t st) {
   const int64_t n = (int64_t)T * H;
   if (n <= 0) return PIPE_OK;
   int64_t blocks = (n + BLK * 4 - 1) / (BLK * 4);
   if (blocks > 4096) blocks = 4096;
-  PIPE_KLAUNCH(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits);
+  PIPE_KLAUNCH(mlp_act_kernel, dim3((unsigned)blocks, M), dim3(BLK), 0, st, y1, T, H, act, h, amax_bits, amax_neg);
   PIPE_HIP(hipGetLastError());
   return PIPE_OK;
 }

@@ -397,6 +397,43 @@ def test_mlp_parity(pipe, kind, tokens):
     g1.free(); g2.free()
 
 
+@pytest.mark.parametrize("kind", ["gelu", "gated"])
+@pytest.mark.parametrize("tokens", [150, 40, 7])
+def test_mlp_asymmetric_parity(pipe, kind, tokens):
+    """Both layers of the ensemble MLP under asymmetric activation codes (Sec. 4.3): the tiled kernel (gate and
+    up blocks paired in a workgroup) and the weight-streaming one (separate activation pass), every member with
+    its own zero point; teacher-forced per layer, then end to end, as test_mlp_parity."""
+    base = wl.C3 if kind == "gelu" else wl.C5
+    w = wl.scaled(base, out_div=8, in_div=8, tokens=tokens)
+    l1, l2 = w.layers
+    W1, W2, x = wl.make_weight(w, 0), wl.make_weight(w, 1), wl.make_input(w)
+    b1, b2 = wl.make_bias(w, 0), wl.make_bias(w, 1)
+    o1, o2 = oracle_expand(W1, l1), oracle_expand(W2, l2)
+    g1 = pipe.pipe_expand(dev(W1), l1.bits, l1.K, l1.gamma, l1.group)
+    g2 = pipe.pipe_expand(dev(W2), l2.bits, l2.K, l2.gamma, l2.group)
+    act = pipe.PIPE_ACT_GELU if kind == "gelu" else pipe.PIPE_ACT_SILU_GATED
+    for split in (list(w.split), None, [1] * l1.K):
+        ref = po.mlp_forward(o1, o2, kind, x, split=split, bias1=b1, bias2=b2, asymmetric=True)
+        y, h = pipe.pipe_mlp_forward_asymmetric(g1, g2, act, dev(x), split=split, bias1=dev(b1), bias2=dev(b2),
+                                                return_hidden=True)
+        hg = h.cpu().numpy()
+        # the kernels add the zero point's term as a bias (s * sum_k s_k acc' + [b + s dz C]): two large terms that
+        # cancel, so an element's error scales with them, not with the element; the product SiLU(gate) * up then
+        # carries a large gate's factor onto a small up.  2e-5 of the tensor's maximum, 1e-3 element-wise.
+        assert_close_fp32(hg, ref["h"], tol=2e-5, elementwise=False)
+        assert_close_fp32(hg, ref["h"], tol=1e-3)
+        ref2 = po.mlp_second_layer(o2, hg, split=split, bias2=b2, asymmetric=True)
+        assert_close_fp32(y.cpu().numpy(), ref2["y"])
+        assert_close_fp32(y.cpu().numpy(), ref["y"], tol=3e-2, elementwise=False)
+        y_again = pipe.pipe_mlp_forward_asymmetric(g1, g2, act, dev(x), split=split, bias1=dev(b1), bias2=dev(b2))
+        assert np.array_equal(y.cpu().numpy(), y_again.cpu().numpy())   # every range slot was cleared
+    # the symmetric call on the same expansions and scratch still holds its bar
+    ref = po.mlp_forward(o1, o2, kind, x, split=list(w.split))
+    ys, hs = pipe.pipe_mlp_forward(g1, g2, act, dev(x), split=list(w.split), return_hidden=True)
+    assert_close_fp32(ys.cpu().numpy(), po.mlp_second_layer(o2, hs.cpu().numpy(), split=list(w.split))["y"])
+    g1.free(); g2.free()
+
+
 @pytest.mark.parametrize("bits,K", [(3, 3), (5, 2), (6, 2), (7, 2)])
 def test_intermediate_weight_widths(pipe, bits, K):
     """3-bit codes travel in 4-bit fields, 5..7-bit codes in bytes: expansion bit-exact, forward

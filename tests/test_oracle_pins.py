@@ -757,6 +757,40 @@ def test_asymmetric_chain_is_the_pinned_asymmetric_layer_applied_member_wise():
         po.chain_forward(layers, x, s_x=0.1, asymmetric=True)
 
 
+def test_asymmetric_mlp_is_the_pinned_layers_and_activation():
+    """The two-layer ensemble under asymmetric codes: with GELU it is the asymmetric chain of two layers
+    (pinned above); gated, member m is the pinned asymmetric layer (its own orders, bias in the first
+    member), torch's SiLU times up, and the pinned asymmetric layer again on its own hidden tensor."""
+    rng = np.random.default_rng(91)
+    I, H, O, T = 24, 32, 16, 6
+    W1 = (rng.standard_normal((2 * H, I)) / math.sqrt(I)).astype(f32)
+    W2 = (rng.standard_normal((O, H)) / math.sqrt(H)).astype(f32)
+    b1 = rng.standard_normal(2 * H).astype(f32)
+    b2 = rng.standard_normal(O).astype(f32)
+    x = (rng.standard_normal((T, I)) + 0.4).astype(f32)
+    e1, e2 = po.expand(W1, 4, 2, 1.0, 8), po.expand(W2, 4, 2, 1.0, 8)
+    r = po.mlp_forward(e1, e2, "gated", x, split=[1, 1], bias1=b1, bias2=b2, asymmetric=True)
+    ys = []
+    for m, sp in enumerate(([1], [1])):
+        one1 = po.expand((e1.dense_scales(m + 1)[:, None] * e1.dense_codes(m + 1)).astype(f32), 4, 1, 1.0, 8)
+        one2 = po.expand((e2.dense_scales(m + 1)[:, None] * e2.dense_codes(m + 1)).astype(f32), 4, 1, 1.0, 8)
+        y1 = po.forward_asymmetric(one1, x, bias=b1 if m == 0 else None)["y"]
+        g, u = torch.from_numpy(y1[:, :H].astype(np.float64)), torch.from_numpy(y1[:, H:].astype(np.float64))
+        h = (torch.nn.functional.silu(g) * u).numpy().astype(f32)
+        assert np.allclose(r["h"][m], h, rtol=2e-6, atol=1e-7)
+        ys.append(po.forward_asymmetric(one2, r["h"][m], bias=b2 if m == 0 else None)["y"])
+        assert np.allclose(r["members"][m], ys[m], rtol=1e-5, atol=1e-6)
+    assert np.array_equal(r["y"], (r["members"][0] + r["members"][1]).astype(f32))
+    # GELU: the chain of two layers
+    W1g = W1[:H]
+    e1g = po.expand(W1g, 4, 2, 1.0, 8)
+    m2 = po.mlp_forward(e1g, e2, "gelu", x, split=[1, 1], bias1=b1[:H], bias2=b2, asymmetric=True)
+    c2 = po.chain_forward([po.ChainLayer(e1g, b1[:H], "gelu"), po.ChainLayer(e2, b2, "none")], x, split=[1, 1], asymmetric=True)
+    assert np.array_equal(m2["y"], c2["y"]) and np.array_equal(m2["h"], c2["acts"][0])
+    with pytest.raises(ValueError):
+        po.mlp_forward(e1, e2, "gated", x, s_x=0.1, asymmetric=True)
+
+
 @pytest.mark.parametrize("a", [4, 6])
 def test_asymmetric_chain_is_closer_to_the_float_network_after_relus(a):
     """Why the comparison of Sec. 4.3 is made under asymmetric quantization: a tensor that left a
