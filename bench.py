@@ -141,6 +141,7 @@ def main():
             self.xd_full = torch.from_numpy(self.x_full).to(dev)
             self.split = list(cfg.split) if len(cfg.split) > 1 else None
             self.static_sx = 0.0   # > 0: the activation scale is given (the paper's static ranges) instead of max|x| / 127
+            self.given = None      # chain: per layer the given scales of the tensors entering it (static ranges), or None
 
         def build(self):
             cfg = self.cfg
@@ -161,6 +162,9 @@ def main():
             if cfg.kind == "linear" and self.static_sx > 0:
                 return pipe.pipe_forward(e[0], xd, s_x=self.static_sx, split=split, out=out)
             if cfg.kind == "chain":
+                if self.given is not None:
+                    layers = [(e[i], None, chain_act[c[0]], c[1], c[2], 0, 0, 1, 0, self.given[i]) for i, c in enumerate(cfg.chain)]
+                    return pipe.pipe_chain_forward(layers, xd, s_x=self.static_sx, split=split, out=out)
                 layers = [(e[i], None, chain_act[c[0]], c[1], c[2]) for i, c in enumerate(cfg.chain)]
                 return pipe.pipe_chain_forward(layers, xd, split=split, out=out)
             if cfg.kind == "linear":
@@ -169,6 +173,8 @@ def main():
                 c = cfg.conv
                 return pipe.pipe_forward_conv2d(e[0], xd, c["kh"], c["kw"], c["stride"], c["pad"], split=split, out=out)
             act = pipe.PIPE_ACT_GELU if cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
+            if self.given is not None:
+                return pipe.pipe_mlp_forward_given_scales(e[0], e[1], act, xd, self.static_sx, self.given, split=split, out=out)
             return pipe.pipe_mlp_forward(e[0], e[1], act, xd, split=split, out=out)
 
         def io_bytes(self, T):
@@ -337,6 +343,28 @@ def main():
                 r = other.measure(T, max(10, args.steps // 2), 3, rotate=(T <= 128))
                 r["workload"] = other.cfg.name
                 r["traffic"] = traffic.get((name, T))
+                if other.cfg.kind == "chain":
+                    # the same step with the paper's static activation ranges: every layer's input scale is given
+                    # (here: the scales the dynamic run found), so no maxima are exchanged between the layers
+                    xd = other.xd_full[:T].contiguous()
+                    layers = [(other.exps[0][i], None, chain_act[c[0]], c[1], c[2]) for i, c in enumerate(other.cfg.chain)]
+                    _, acts = pipe.pipe_chain_forward(layers, xd, split=other.split, return_acts=True)
+                    other.given = [None] + [[float(a[m].abs().max().item()) / 127.0 for m in range(a.shape[0])] for a in acts]
+                    other.static_sx = float(xd.abs().max().item()) / 127.0
+                    rs = other.measure(T, max(10, args.steps // 2), 3, rotate=True)
+                    other.given, other.static_sx = None, 0.0
+                    r["static_ranges"] = {"ms_per_step": rs["ms_per_step"], "kernel_ms_per_step": rs["kernel_ms_per_step"],
+                                          "step_gbs": rs.get("step_gbs"), "hbm_frac": (rs.get("step_gbs") or 0.0) / HBM_PEAK_GBS}
+                elif other.cfg.kind in ("mlp_gelu", "mlp_gated") and T <= 128:
+                    xd = other.xd_full[:T].contiguous()
+                    act = pipe.PIPE_ACT_GELU if other.cfg.kind == "mlp_gelu" else pipe.PIPE_ACT_SILU_GATED
+                    _, hh = pipe.pipe_mlp_forward(other.exps[0][0], other.exps[0][1], act, xd, split=other.split, return_hidden=True)
+                    other.given = [float(hh[m].abs().max().item()) / 127.0 for m in range(hh.shape[0])]
+                    other.static_sx = float(xd.abs().max().item()) / 127.0
+                    rs = other.measure(T, max(10, args.steps // 2), 3, rotate=True)
+                    other.given, other.static_sx = None, 0.0
+                    r["static_ranges"] = {"ms_per_step": rs["ms_per_step"], "kernel_ms_per_step": rs["kernel_ms_per_step"],
+                                          "step_gbs": rs.get("step_gbs"), "hbm_frac": (rs.get("step_gbs") or 0.0) / HBM_PEAK_GBS}
                 extra.append(fractions(r))
             other.free()
             del other

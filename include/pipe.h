@@ -294,6 +294,17 @@ int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act
                      const float* bias1_dev, const float* bias2_dev, float* h_dev,
                      float* y_dev, void* stream);
 
+/* pipe_mlp_forward with static activation ranges throughout (Sec. 4: activations quantized with
+ * ranges fixed ahead of time, as in DFQ): s_x > 0 is the given scale of the input and s_h_host
+ * (HOST, [M], positive, read during the call) the given scales of the members' hidden
+ * activations, used instead of max|h_m| / q_max.  No maximum is reduced or exchanged anywhere
+ * in the call.  Everything else as pipe_mlp_forward; PIPE_EINVAL if a scale is missing or not
+ * positive.                                                                               */
+int pipe_mlp_forward_given_scales(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                                  const float* x_dev, int T, float s_x, const float* s_h_host,
+                                  const int* split, int M, const float* bias1_dev,
+                                  const float* bias2_dev, float* h_dev, float* y_dev, void* stream);
+
 /* pipe_mlp_forward with asymmetric activation codes (Sec. 4.3; the affine quantizer of
  * pipe_forward_asymmetric) in front of both layers: the input is quantized over its own range
  * [min(x,0), max(x,0)], every member's hidden activation over that tensor's own range with its
@@ -320,6 +331,11 @@ typedef struct pipe_chain_layer {
                               else the kernel size of a convolution over the grid    */
   int stride, pad;         /* of the convolution (stride >= 1, pad >= 0); ignored when
                               kh = kw = 0                                            */
+  const float* s_in;       /* HOST, NULL or [M] positive: given (static) scales of the
+                              members' tensors that ENTER this layer (Sec. 4: activation
+                              ranges fixed ahead of time, as in DFQ), read during the call;
+                              NULL: each member's max|tensor| / q_max.  Ignored for layer 0,
+                              whose shared input takes the call's s_x                    */
 } pipe_chain_layer;
 
 /* An L-layer feed-forward network run as M independent member chains that are

@@ -564,7 +564,7 @@ def silu_mul(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
 
 def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, split=None,
                 bias1=None, bias2=None, s_x: Optional[float] = None, act_bits: int = 8,
-                asymmetric: bool = False):
+                asymmetric: bool = False, s_h: Optional[Sequence[float]] = None):
     """Two expanded layers with an activation between, run as an ensemble.
 
     Member m uses only its own orders in BOTH layers, quantizes its own hidden
@@ -572,6 +572,7 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
     first member; the members' outputs are summed after the last layer.
     kind = "gelu": h = GELU(layer1(x));  kind = "gated": layer1 has 2H outputs
     (gate rows first, then up rows) and h = SiLU(gate) * up.
+    s_h: given (static) scales of the members' hidden activations instead of their dynamic ones.
     asymmetric: the input and every member's hidden activation get the affine codes of
     Sec. 4.3 (quantize_activations_asymmetric), each over its own range; the contractions run
     on the codes minus their zero point.
@@ -599,13 +600,13 @@ def mlp_forward(exp1: Expansion, exp2: Expansion, kind: str, x: np.ndarray, spli
             raise ValueError("kind must be 'gelu' or 'gated'")
         hs.append(h)
     hs = np.stack(hs)
-    second = mlp_second_layer(exp2, hs, split, bias2, act_bits, asymmetric)
+    second = mlp_second_layer(exp2, hs, split, bias2, act_bits, asymmetric, s_h)
     second.update(h=hs, y1=y1, s_x=sx, Qx=Qx)
     return second
 
 
 def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, act_bits: int = 8,
-                     asymmetric: bool = False):
+                     asymmetric: bool = False, s_h: Optional[Sequence[float]] = None):
     """Last layer of the ensemble on given hidden activations hs [M, T, H]: member m
     quantizes hs[m] with its own dynamic scale, uses its own orders of exp2 (bias in
     the first member only), and the members are summed in ascending order.
@@ -619,7 +620,7 @@ def mlp_second_layer(exp2: Expansion, hs: np.ndarray, split=None, bias2=None, ac
             Qu, sh, zh = quantize_activations_asymmetric(hs[m], act_bits)
             Qh = Qu.astype(np.int32) - int(zh)
         else:
-            Qh, sh = quantize_activations(hs[m], None, act_bits)
+            Qh, sh = quantize_activations(hs[m], None if s_h is None else float(s_h[m]), act_bits)
         acc2 = forward_acc(exp2, Qh)
         outs.append(dequantize(exp2, acc2, sh, split, bias2 if m == 0 else None, f32)[m])
         shs.append(sh)
@@ -644,7 +645,10 @@ class ChainLayer:
     skip_pre_act True: a = act(z + r) (ResNet block); False: a = act(z) + r
     kh, kw, stride, pad   kh = 0: a fully-connected layer applied to every token; kh > 0: a
                  convolution over the [N, H, W] grid the tokens form (tensors are channels
-                 last, tokens ordered (n, h, w)), exp built from W [O, C*kh*kw]"""
+                 last, tokens ordered (n, h, w)), exp built from W [O, C*kh*kw]
+    s_in         None, or one given (static) activation scale per member for the tensors that
+                 enter this layer (Sec. 4: ranges fixed ahead of time); not used by the first
+                 layer, whose shared input takes chain_forward's s_x"""
     exp: Expansion
     bias: Optional[np.ndarray] = None
     act: str = "none"
@@ -654,6 +658,7 @@ class ChainLayer:
     kw: int = 0
     stride: int = 1
     pad: int = 0
+    s_in: Optional[Sequence[float]] = None
 
 
 def chain_layer_acc(layer: ChainLayer, Qa: np.ndarray, grid):
@@ -702,7 +707,8 @@ def chain_layer_members(layer: ChainLayer, inputs: np.ndarray, shared_input: boo
             Qu, sa, zp = quantize_activations_asymmetric(xin, act_bits)
             Qa = Qu.astype(np.int32) - int(zp)
         else:
-            Qa, sa = quantize_activations(xin, s_x if shared_input else None, act_bits)
+            given = s_x if shared_input else (None if layer.s_in is None else float(layer.s_in[m]))
+            Qa, sa = quantize_activations(xin, given, act_bits)
         acc, _ = chain_layer_acc(layer, Qa, grid if grid is not None else (Qa.shape[0], 1, 1))
         z = dequantize(exp, acc, sa, split, layer.bias, f32)[m]
         r = None if skips is None else skips[m]

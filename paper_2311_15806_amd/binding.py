@@ -60,6 +60,7 @@ def _load():
     lib.pipe_forward_depthwise2d.argtypes = [vp, vp] + [ci] * 9 + [cf, pi, ci, vp, ci, vp, vp]
     lib.pipe_mlp_forward.argtypes = [vp, vp, ci, vp, ci, cf, pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_mlp_forward_asymmetric.argtypes = [vp, vp, ci, vp, ci, pi, ci, vp, vp, vp, vp, vp]
+    lib.pipe_mlp_forward_given_scales.argtypes = [vp, vp, ci, vp, ci, cf, C.POINTER(C.c_float), pi, ci, vp, vp, vp, vp, vp]
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_asymmetric.argtypes = [vp, ci, vp, ci, pi, ci, vp, vp, vp]
@@ -403,6 +404,21 @@ def pipe_mlp_forward(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_
     return (y, h) if return_hidden else y
 
 
+def pipe_mlp_forward_given_scales(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, s_x: float, s_h, split=None,
+                                  bias1=None, bias2=None, return_hidden: bool = False, out: Optional[torch.Tensor] = None):
+    """pipe_mlp_forward with given (static) scales: s_x for the input, s_h[m] for member m's hidden activation."""
+    T = x.shape[0]
+    M = 1 if split is None else len(split)
+    y = out if out is not None else torch.empty((T, l2.out_features), dtype=torch.float32, device=x.device)
+    h = torch.empty((M, T, l2.in_features), dtype=torch.float32, device=x.device) if return_hidden else None
+    arr, m = _split(split)
+    sh = (C.c_float * len(s_h))(*[float(v) for v in s_h])
+    _check(_lib.pipe_mlp_forward_given_scales(l1.handle, l2.handle, int(act), _ptr(x, torch.float32), T, float(s_x), sh, arr, m,
+                                              _ptr(bias1, torch.float32), _ptr(bias2, torch.float32), _ptr(h), _ptr(y),
+                                              _stream()), "pipe_mlp_forward_given_scales")
+    return (y, h) if return_hidden else y
+
+
 def pipe_mlp_forward_asymmetric(l1: Expansion, l2: Expansion, act: int, x: torch.Tensor, split=None, bias1=None,
                                 bias2=None, return_hidden: bool = False, out: Optional[torch.Tensor] = None):
     """pipe_mlp_forward with asymmetric activation codes in front of both layers."""
@@ -419,17 +435,27 @@ def pipe_mlp_forward_asymmetric(l1: Expansion, l2: Expansion, act: int, x: torch
 
 class _ChainLayer(C.Structure):
     _fields_ = [("e", C.c_void_p), ("bias_dev", C.c_void_p), ("act", C.c_int), ("skip_from", C.c_int),
-                ("skip_pre_act", C.c_int), ("kh", C.c_int), ("kw", C.c_int), ("stride", C.c_int), ("pad", C.c_int)]
+                ("skip_pre_act", C.c_int), ("kh", C.c_int), ("kw", C.c_int), ("stride", C.c_int), ("pad", C.c_int),
+                ("s_in", C.c_void_p)]
 
 
 def _chain_layers(layers):
-    """(Expansion, bias or None, act, skip_from, skip_pre_act[, kh, kw, stride, pad]) -> C array."""
+    """(Expansion, bias or None, act, skip_from, skip_pre_act[, kh, kw, stride, pad[, s_in]]) -> C array;
+    s_in: None or the given scales (one per member) of the tensors entering the layer."""
     arr = (_ChainLayer * len(layers))()
+    keep = []
     for l, ly in enumerate(layers):
         e, bias, act, skip_from, pre = ly[:5]
         kh, kw, stride, pad = ly[5:9] if len(ly) >= 9 else (0, 0, 1, 0)
+        s_in = ly[9] if len(ly) >= 10 else None
+        s_ptr = None
+        if s_in is not None:
+            buf = (C.c_float * len(s_in))(*[float(v) for v in s_in])
+            keep.append(buf)
+            s_ptr = C.cast(buf, C.c_void_p)
         arr[l] = _ChainLayer(e.handle, _ptr(bias, torch.float32), int(act), int(skip_from), 1 if pre else 0,
-                             int(kh), int(kw), int(stride), int(pad))
+                             int(kh), int(kw), int(stride), int(pad), s_ptr)
+    arr._keep = keep   # the host arrays live as long as the layer array
     return arr
 
 

@@ -1285,6 +1285,7 @@ struct ResidentLayerSpec {
   const float* res;
   long long res_mstride;
   int res_members, res_pre_act, res_device, act, gated;
+  const float* s_in;   // HOST: given scales of the members' tensors entering the layer, or nullptr (layers after the first)
 };
 
 static bool resident_eligible(const pipe_expansion* const* es, int L, int T, int M, const float* x_dev) {
@@ -1328,6 +1329,9 @@ static int run_resident(const ResidentLayerSpec* ls, int L, const float* x_dev, 
     la.bias = ls[l].bias; la.out = ls[l].out; la.res = ls[l].res; la.res_mstride = ls[l].res_mstride;
     la.res_members = ls[l].res_members; la.res_pre_act = ls[l].res_pre_act; la.res_device = ls[l].res_device;
     la.act = ls[l].act; la.gated = ls[l].gated;
+    la.s_in[0] = la.s_in[1] = 0.f;
+    if (l > 0 && ls[l].s_in != nullptr)
+      for (int m = 0; m < M && m < PIPE_RES_MAX_M; ++m) la.s_in[m] = ls[l].s_in[m];
     la.qin = qbuf + q_off[l];
   }
   // the busiest workgroup's unit descriptors have to fit the kernel's LDS copy; else the caller
@@ -1359,10 +1363,11 @@ extern "C" int pipe_resident_status(void* stream, int* status_out) {
   return PIPE_OK;
 }
 
-extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,
-                                const float* x_dev, int T, float s_x, const int* split, int M,
-                                const float* bias1_dev, const float* bias2_dev, float* h_dev,
-                                float* y_dev, void* stream) {
+// s_h_host: nullptr, or the given scales of the members' hidden activations (HOST, one per member)
+static int mlp_forward_impl(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                            const float* x_dev, int T, float s_x, const float* s_h_host, const int* split, int M,
+                            const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                            float* y_dev, void* stream) {
   if (!l1 || !l2 || T < 0) return PIPE_EINVAL;
   if (l1->conv_C > 0 || l2->conv_C > 0) return PIPE_EINVAL;
   if (act != PIPE_ACT_GELU && act != PIPE_ACT_SILU_GATED) return PIPE_EINVAL;
@@ -1372,6 +1377,9 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(l1->K, split, M, lo, hi, &Mm);
   if (rc) return rc;
+  if (s_h_host != nullptr)
+    for (int m = 0; m < Mm; ++m)
+      if (!(s_h_host[m] > 0.f)) return PIPE_EINVAL;
   if (T == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   hipStream_t st = (hipStream_t)stream;
@@ -1397,6 +1405,7 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
       ls[0].e = l1; ls[0].bias = bias1_dev; ls[0].out = h; ls[0].act = gated ? PIPE_ACT_NONE : PIPE_ACT_GELU; ls[0].gated = gated ? 1 : 0;
       ls[0].res_pre_act = 1;
       ls[1].e = l2; ls[1].bias = bias2_dev; ls[1].out = y_dev; ls[1].act = PIPE_ACT_NONE; ls[1].res_pre_act = 1;
+      ls[1].s_in = s_h_host;
       rc = run_resident(ls, 2, x_dev, T, s_x, Mm, lo, hi, st);
       if (rc != 1) return rc;   // 1: does not fit the resident kernel, per-layer launches below
     }
@@ -1453,12 +1462,23 @@ extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* 
   }
   // each member quantizes its own hidden activation with its own scale
   const bool one_launch = small && T <= PIPE_QUANT1_MAX_T;
-  if (one_launch) {
+  if (s_h_host != nullptr) {
+    // given scales: one launch per member (the maxima taken above are not read; layer 2 clears them)
+    for (int m = 0; m < Mm; ++m) {
+      if (one_launch)
+        rc = launch_quantize_small(h + (size_t)m * T * H, 0, 1, T, H, l2->in_pad, s_h_host[m], nullptr, qh + (size_t)m * T_pad * l2->in_pad, 0,
+                                   rowsum_h + (size_t)m * T_pad, nullptr, scale_h + m, st);
+      else
+        rc = launch_quantize_act(h + (size_t)m * T * H, T, H, l2->in_pad, T_pad, s_h_host[m], nullptr, qh + (size_t)m * T_pad * l2->in_pad,
+                                 rowsum_h + (size_t)m * T_pad, true, nullptr, scale_h + m, st);
+      if (rc) return rc;
+    }
+  } else if (one_launch) {
     rc = launch_quantize_small(h, (int64_t)T * H, Mm, T, H, l2->in_pad, 0.f, amax_h, qh, (int64_t)T_pad * l2->in_pad,
                                rowsum_h, nullptr, scale_h, st);
     if (rc) return rc;
   }
-  if (!one_launch) {
+  if (s_h_host == nullptr && !one_launch) {
     // the gated path's separate activation pass ran after layer 1: its code sums were cleared there too
     rc = launch_quantize_members(h, (int64_t)T * H, Mm, T, H, l2->in_pad, T_pad, amax_h, qh, (int64_t)T_pad * l2->in_pad,
                                  rowsum_h, true, scale_h, st);
@@ -1576,6 +1596,21 @@ extern "C" int pipe_mlp_forward_asymmetric(const pipe_expansion* l1, const pipe_
   return rc;
 }
 
+extern "C" int pipe_mlp_forward(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                                const float* x_dev, int T, float s_x, const int* split, int M,
+                                const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                                float* y_dev, void* stream) {
+  return mlp_forward_impl(l1, l2, act, x_dev, T, s_x, nullptr, split, M, bias1_dev, bias2_dev, h_dev, y_dev, stream);
+}
+
+extern "C" int pipe_mlp_forward_given_scales(const pipe_expansion* l1, const pipe_expansion* l2, int act,
+                                             const float* x_dev, int T, float s_x, const float* s_h_host, const int* split,
+                                             int M, const float* bias1_dev, const float* bias2_dev, float* h_dev,
+                                             float* y_dev, void* stream) {
+  if (!(s_x > 0.f) || s_h_host == nullptr) return PIPE_EINVAL;
+  return mlp_forward_impl(l1, l2, act, x_dev, T, s_x, s_h_host, split, M, bias1_dev, bias2_dev, h_dev, y_dev, stream);
+}
+
 extern "C" int pipe_prepare_mlp(const pipe_expansion* l1, const pipe_expansion* l2, int act, const int* split, int M,
                                 int T_max, void* stream) {
   if (!l1 || !l2 || T_max < 1) return PIPE_EINVAL;
@@ -1639,6 +1674,9 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
     if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
     if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;
     if (ly.kh < 0 || ly.kw < 0 || (ly.kh == 0) != (ly.kw == 0)) return PIPE_EINVAL;
+    if (l > 0 && ly.s_in != nullptr)
+      for (int m = 0; m < (split ? M : 1); ++m)
+        if (!(ly.s_in[m] > 0.f)) return PIPE_EINVAL;   // given scales are positive
     if (ly.kh == 0) {
       Cin[l] = ly.e->in; Hin[l + 1] = Hin[l]; Win[l + 1] = Win[l];
     } else {
@@ -1714,6 +1752,7 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
         ls[l] = ResidentLayerSpec{};
         ls[l].e = ly.e; ls[l].bias = ly.bias_dev; ls[l].out = l == L - 1 ? y_dev : act[l]; ls[l].act = ly.act;
         ls[l].res_pre_act = ly.skip_pre_act ? 1 : 0;
+        ls[l].s_in = ly.s_in;
         if (ly.skip_from == 0) {
           ls[l].res = x_dev; ls[l].res_mstride = 0; ls[l].res_members = 1; ls[l].res_device = 0;
         } else if (ly.skip_from > 0) {
@@ -1761,11 +1800,23 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
       uint32_t* amax_in = amax_set[(l - 1) & 1];
       int32_t* rs_in = rs_buf[l & 1];
       const int64_t q_ms = (int64_t)T_pad * e->in_pad;
+      const float* s_given = ly.s_in;   // given scales: no maximum was taken (the producing layer was told so)
       if (conv) {
         for (int m = 0; m < Mm; ++m) {
           rc = launch_quantize_im2col(src + (size_t)m * Tin[l] * Cin[l], N, Cin[l], Hin[l], Win[l], ly.kh, ly.kw, ly.stride,
-                                      ly.pad, 1, Hin[l + 1], Win[l + 1], e->in_pad, T_pad, 0.f, amax_in + m, q8,
+                                      ly.pad, 1, Hin[l + 1], Win[l + 1], e->in_pad, T_pad, s_given ? s_given[m] : 0.f, amax_in + m, q8,
                                       qh + (size_t)m * q_ms, rs_in + (size_t)m * T_pad_max, scale_h + m, st);
+          if (rc) return rc;
+        }
+      } else if (s_given != nullptr) {
+        // one launch per member, each with its own given scale
+        for (int m = 0; m < Mm; ++m) {
+          if (small[l] && T <= PIPE_QUANT1_MAX_T && T_pad == T_pad_max)
+            rc = launch_quantize_small(src + (size_t)m * T * in, 0, 1, T, in, e->in_pad, s_given[m], nullptr, qh + (size_t)m * q_ms, 0,
+                                       rs_in + (size_t)m * T_pad_max, nullptr, scale_h + m, st);
+          else
+            rc = launch_quantize_act(src + (size_t)m * T * in, T, in, e->in_pad, T_pad, s_given[m], nullptr, qh + (size_t)m * q_ms,
+                                     rs_in + (size_t)m * T_pad_max, true, nullptr, scale_h + m, st);
           if (rc) return rc;
         }
       } else if (small[l] && T <= PIPE_QUANT1_MAX_T && T_pad == T_pad_max) {
@@ -1798,7 +1849,8 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
     if (last_layer) {
       a.reduce = 1; a.y = y_dev;
     } else {
-      a.reduce = 0; a.y = act[l]; a.amax_out = amax_set[l & 1];
+      a.reduce = 0; a.y = act[l];
+      a.amax_out = layers[l + 1].s_in != nullptr ? nullptr : amax_set[l & 1];   // nobody asks for the maximum of a tensor whose scale is given
     }
     fill_members(a, Mm, lo, hi);
     rc = run_gemm(a, small[l], st);

@@ -365,6 +365,7 @@ struct ResidentLayerArgs {
   long long res_mstride;
   int res_members, res_pre_act, res_device;   // res_device: the skip tensor is produced inside the launch
   int act, gated;
+  float s_in[PIPE_RES_MAX_M];   // > 0: given scale of member m's tensor entering the layer (layers after the first)
   uint8_t* qin;           // scratch for the codes entering the layer: M * 16 * in_pad bytes (first layer: 16 * in_pad)
 };
 struct ResidentArgs {

@@ -59,6 +59,7 @@ struct ResLayer {
   int in, in_pad;
   int xm;                   // distinct activation tensors entering the layer: 1 (first layer) or M
   int act, res_members, res_pre_act, gated, reduce, res_device;
+  float s_in[2];            // > 0: given scales of the tensors entering the layer (no exchange of maxima then)
 };
 
 struct ResParams {
@@ -399,7 +400,8 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
       const int n_in = ly.xm;   // tensors to quantize for this layer
       const ResLayer& lp = p.layer[l > 0 ? l - 1 : 0];
       const int nu_prev = l > 0 ? units_of(lp.n_units) : 0;
-      const bool dynamic = l > 0 || !(p.s_static > 0.f);
+      const float st0 = l == 0 ? p.s_static : ly.s_in[0], st1 = l == 0 ? p.s_static : ly.s_in[1];
+      const bool dynamic = !(st0 > 0.f);
       // ---------------- exchange, step A: max|.| of the tensor(s) entering layer l
       if (wave == RES_WORKERS) stamp(l, 0);
       float mx[2] = {0.f, 0.f};
@@ -460,7 +462,7 @@ __global__ __launch_bounds__(RES_THREADS, 1) void chain_resident_kernel(const Re
         }
         if (!ok && lane == 0) { s_fail = 1; s_scale[0] = 0.f; s_scale[1] = 0.f; st_dev_u32(p.status, 2u); }
       } else if (e == 0) {
-        s_scale[0] = p.s_static; s_scale[1] = p.s_static;
+        s_scale[0] = st0; s_scale[1] = st1;
       }
       __syncthreads();   // P2
       if (wave == RES_WORKERS) stamp(l, 1);
@@ -865,6 +867,7 @@ int launch_resident_chain(const ResidentArgs& a, hipStream_t st) {
     ly.act = la.act; ly.res_members = la.res_members; ly.res_pre_act = la.res_pre_act; ly.gated = la.gated;
     ly.reduce = l == a.L - 1 ? 1 : 0;
     ly.res_device = la.res_device;
+    ly.s_in[0] = la.s_in[0]; ly.s_in[1] = la.s_in[1];
   }
   // the descriptors of the busiest workgroup (the first) have to fit their LDS copy
   int desc_ints = 0;

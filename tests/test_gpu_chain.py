@@ -187,6 +187,51 @@ def test_asymmetric_chain_variants(pipe):
         g.free()
 
 
+@pytest.mark.parametrize("tokens", [150, 37, 9])
+@pytest.mark.parametrize("bits,K,split", [(4, 4, [2, 2]), (2, 4, None), (2, 8, [3, 3, 2])])
+def test_chain_with_given_scales(pipe, bits, K, split, tokens):
+    """Static activation ranges inside a chain (Sec. 4: ranges fixed ahead of time): every member quantizes the
+    tensor entering layer l with the given s_in[m].  With the scales a dynamic run found, the result is that
+    run's, bit for bit; with other scales (some too small: codes clip) every layer matches the checker fed the
+    same tensors.  Tiled, streaming and, for the small batch, the resident kernel."""
+    w = wl.residual_stack(128, 2, 64, bits, K, 0.5, 16, tokens, split or (K,))
+    olayers, glayers, gpu = _build(pipe, w)
+    x = wl.make_input(w)
+    M = 1 if split is None else len(split)
+    L = len(glayers)
+    y_dyn, acts = pipe.pipe_chain_forward(glayers, dev(x), split=split, return_acts=True)
+    found = [None] + [[float(np.float32(np.float32(np.abs(acts[l - 1][m].cpu().numpy()).max()) / np.float32(127))) for m in range(M)]
+                      for l in range(1, L)]
+    given = [g + (0, 0, 1, 0, found[l]) for l, g in enumerate(glayers)]
+    for resident in (True, False):
+        pipe.pipe_set_decode_resident(resident)
+        try:
+            y_same = pipe.pipe_chain_forward(given, dev(x), split=split)
+            assert pipe.pipe_resident_status() == 0
+            assert torch.equal(y_same, y_dyn)
+            other = [None] + [[f * (0.5 if (l + m) % 2 else 1.7) for m, f in enumerate(found[l])] for l in range(1, L)]
+            g2 = [g + (0, 0, 1, 0, other[l]) for l, g in enumerate(glayers)]
+            y2, a2 = pipe.pipe_chain_forward(g2, dev(x), s_x=0.05, split=split, return_acts=True)
+        finally:
+            pipe.pipe_set_decode_resident(1)
+        a2 = [a.cpu().numpy() for a in a2]
+        for l in range(L):
+            ol = po.ChainLayer(olayers[l].exp, olayers[l].bias, olayers[l].act, olayers[l].skip_from, olayers[l].skip_pre_act,
+                               s_in=other[l])
+            skips = po.chain_skips(olayers, l, x, a2, M)
+            ref = po.chain_layer_members(ol, x, True, skips, split, 0.05) if l == 0 else po.chain_layer_members(ol, a2[l - 1], False, skips, split)
+            if l < L - 1:
+                for m in range(M):
+                    assert_close_fp32(a2[l][m], ref[m], tol=2e-5)
+            else:
+                assert_close_fp32(y2.cpu().numpy(), po.sum_members(ref))
+    with pytest.raises(pipe.PipeError):
+        bad = [g + (0, 0, 1, 0, None if l == 0 else [0.0] * M) for l, g in enumerate(glayers)]
+        pipe.pipe_chain_forward(bad, dev(x), split=split)
+    for g in gpu:
+        g.free()
+
+
 def test_chain_argument_errors(pipe):
     w = wl.residual_stack(64, 1, 32, 4, 2, 1.0, 16, 8, (2,))
     _, glayers, gpu = _build(pipe, w, with_bias=False)

@@ -399,6 +399,42 @@ def test_mlp_parity(pipe, kind, tokens):
 
 @pytest.mark.parametrize("kind", ["gelu", "gated"])
 @pytest.mark.parametrize("tokens", [150, 40, 7])
+def test_mlp_given_scales(pipe, kind, tokens):
+    """Static activation ranges through the two-layer call (Sec. 4): with the scales a dynamic run found the result
+    is that run's, bit for bit (tiled, streaming and resident kernels); with other scales the last layer matches
+    the checker fed the GPU's hidden activations."""
+    base = wl.C3 if kind == "gelu" else wl.C5
+    w = wl.scaled(base, out_div=8, in_div=8, tokens=tokens)
+    l1, l2 = w.layers
+    W1, W2, x = wl.make_weight(w, 0), wl.make_weight(w, 1), wl.make_input(w)
+    o2 = oracle_expand(W2, l2)
+    g1 = pipe.pipe_expand(dev(W1), l1.bits, l1.K, l1.gamma, l1.group)
+    g2 = pipe.pipe_expand(dev(W2), l2.bits, l2.K, l2.gamma, l2.group)
+    act = pipe.PIPE_ACT_GELU if kind == "gelu" else pipe.PIPE_ACT_SILU_GATED
+    split = list(w.split) if len(w.split) > 1 else None
+    M = len(w.split)
+    sx = float(np.float32(np.float32(np.abs(x).max()) / np.float32(127)))
+    for resident in (True, False):
+        pipe.pipe_set_decode_resident(resident)
+        try:
+            y_dyn, h_dyn = pipe.pipe_mlp_forward(g1, g2, act, dev(x), split=split, return_hidden=True)
+            sh = [float(np.float32(np.float32(np.abs(h_dyn[m].cpu().numpy()).max()) / np.float32(127))) for m in range(M)]
+            y_same = pipe.pipe_mlp_forward_given_scales(g1, g2, act, dev(x), sx, sh, split=split)
+            assert torch.equal(y_same, y_dyn)
+            other = [v * (0.6 if m % 2 else 1.5) for m, v in enumerate(sh)]
+            y2, h2 = pipe.pipe_mlp_forward_given_scales(g1, g2, act, dev(x), sx, other, split=split, return_hidden=True)
+            assert pipe.pipe_resident_status() == 0
+        finally:
+            pipe.pipe_set_decode_resident(1)
+        ref2 = po.mlp_second_layer(o2, h2.cpu().numpy(), split=split, s_h=other)
+        assert_close_fp32(y2.cpu().numpy(), ref2["y"])
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_mlp_forward_given_scales(g1, g2, act, dev(x), 0.0, sh, split=split)
+    g1.free(); g2.free()
+
+
+@pytest.mark.parametrize("kind", ["gelu", "gated"])
+@pytest.mark.parametrize("tokens", [150, 40, 7])
 def test_mlp_asymmetric_parity(pipe, kind, tokens):
     """Both layers of the ensemble MLP under asymmetric activation codes (Sec. 4.3): the tiled kernel (gate and
     up blocks paired in a workgroup) and the weight-streaming one (separate activation pass), every member with

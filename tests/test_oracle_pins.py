@@ -695,6 +695,49 @@ def test_chain_single_member_is_layer_by_layer_forward():
     assert np.array_equal(c["y"], m["y"]) and np.array_equal(c["acts"][0], m["h"])
 
 
+def test_chain_with_given_scales_is_the_pinned_layer_with_its_static_scale():
+    """Static activation ranges inside a chain: layer l quantizes member m's tensor with the given scale
+    s_in[m] instead of max|tensor|/127 -- written out with the pinned single-layer routine and its s_x."""
+    skips = [(-1, True), (1, True), (-1, True)]
+    acts = ["relu", "relu", "none"]
+    layers, _, bs = _chain_net(92, [24, 32, 32, 8], 2, 4, skips, acts)
+    x = np.random.default_rng(93).standard_normal((5, 24)).astype(f32)
+    layers[1].s_in = [0.05]
+    layers[2].s_in = [0.11]
+    r = po.chain_forward(layers, x, s_x=0.03)
+    a1 = np.maximum(po.forward(layers[0].exp, x, s_x=0.03, bias=bs[0])["y"], 0)
+    a2 = np.maximum((po.forward(layers[1].exp, a1, s_x=0.05, bias=bs[1])["y"] + a1).astype(f32), 0)
+    y = po.forward(layers[2].exp, a2, s_x=0.11, bias=bs[2])["y"]
+    assert np.array_equal(r["acts"][0][0], a1) and np.array_equal(r["acts"][1][0], a2) and np.array_equal(r["y"], y)
+    # a scale too small clips at +-127: the result differs from the dynamic one
+    assert not np.array_equal(r["y"], po.chain_forward([po.ChainLayer(l.exp, l.bias, l.act, l.skip_from, l.skip_pre_act) for l in layers], x, s_x=0.03)["y"])
+    # two members: each with its own given scale; with the scales the dynamic run found, nothing changes
+    dyn = po.chain_forward([po.ChainLayer(l.exp, l.bias, l.act, l.skip_from, l.skip_pre_act) for l in layers], x, split=[1, 1])
+    found = [[float(np.abs(dyn["acts"][l][m]).max()) / 127.0 for m in range(2)] for l in range(2)]
+    given = [po.ChainLayer(l.exp, l.bias, l.act, l.skip_from, l.skip_pre_act, s_in=None if i == 0 else [f32(f32(np.abs(dyn["acts"][i - 1][m]).max()) / f32(127)) for m in range(2)])
+             for i, l in enumerate(layers)]
+    same = po.chain_forward(given, x, split=[1, 1])
+    assert np.array_equal(same["y"], dyn["y"]) and found[0][1] < found[0][0]
+
+
+def test_mlp_with_given_hidden_scales_is_the_chain_with_given_scales():
+    """pipe_mlp_forward's static form: with GELU it is the two-layer chain whose second layer has s_in (pinned
+    above); gated, member m's last layer is the pinned single layer with s_x = s_h[m]."""
+    rng = np.random.default_rng(94)
+    I, H, O, T = 24, 32, 16, 6
+    W1 = (rng.standard_normal((2 * H, I)) / math.sqrt(I)).astype(f32)
+    W2 = (rng.standard_normal((O, H)) / math.sqrt(H)).astype(f32)
+    x = rng.standard_normal((T, I)).astype(f32)
+    e1, e2, e1g = po.expand(W1, 4, 2, 1.0, 8), po.expand(W2, 4, 2, 1.0, 8), po.expand(W1[:H], 4, 2, 1.0, 8)
+    m2 = po.mlp_forward(e1g, e2, "gelu", x, split=[1, 1], s_x=0.03, s_h=[0.02, 0.004])
+    c2 = po.chain_forward([po.ChainLayer(e1g, None, "gelu"), po.ChainLayer(e2, None, "none", s_in=[0.02, 0.004])], x, split=[1, 1], s_x=0.03)
+    assert np.array_equal(m2["y"], c2["y"])
+    r = po.mlp_forward(e1, e2, "gated", x, split=[1, 1], s_x=0.03, s_h=[0.05, 0.01])
+    for m in range(2):
+        one2 = po.expand((e2.dense_scales(m + 1)[:, None] * e2.dense_codes(m + 1)).astype(f32), 4, 1, 1.0, 8)
+        assert np.allclose(r["members"][m], po.forward(one2, r["h"][m], s_x=[0.05, 0.01][m])["y"], rtol=1e-5, atol=1e-7)
+
+
 def test_chain_members_are_independent_networks():
     """Member 2 of split [1,1] equals a network built from the order-2 terms alone, with no
     bias anywhere, fed the same input; member 1 does not change when order 2 is altered."""
