@@ -1288,9 +1288,11 @@ struct ResidentLayerSpec {
   const float* s_in;   // HOST: given scales of the members' tensors entering the layer, or nullptr (layers after the first)
 };
 
-static bool resident_eligible(const pipe_expansion* const* es, int L, int T, int M, const float* x_dev) {
+// given_scales: every tensor's scale is given, so the launch exchanges no maxima
+static bool resident_eligible(const pipe_expansion* const* es, int L, int T, int M, const float* x_dev, bool given_scales = false) {
   if (!g_decode_resident || g_kernel_choice == 1) return false;
-  if (g_decode_resident == 1 && L < 3 && T < 8) return false;   // automatic: where it measured faster
+  // automatic: where it measured faster (short chains of few tokens only when no maxima are exchanged)
+  if (g_decode_resident == 1 && L < 3 && T < 8 && !given_scales) return false;
   if (T < 1 || T > 16 || M > PIPE_RES_MAX_M || L > PIPE_RES_MAX_LAYERS) return false;
   if (es[0]->in % 4 != 0 || (reinterpret_cast<uintptr_t>(x_dev) & 15) != 0) return false;
   for (int l = 0; l < L; ++l)
@@ -1400,7 +1402,7 @@ static int mlp_forward_impl(const pipe_expansion* l1, const pipe_expansion* l2, 
     // decode-sized batches: both layers in one resident launch
     const pipe_expansion* es[2] = {l1, l2};
     const bool gated = act == PIPE_ACT_SILU_GATED;
-    if (small && resident_eligible(es, 2, T, Mm, x_dev) && (!gated || l1->n_rb % 2 == 0)) {
+    if (small && resident_eligible(es, 2, T, Mm, x_dev, s_h_host != nullptr && s_x > 0.f) && (!gated || l1->n_rb % 2 == 0)) {
       ResidentLayerSpec ls[2] = {};
       ls[0].e = l1; ls[0].bias = bias1_dev; ls[0].out = h; ls[0].act = gated ? PIPE_ACT_NONE : PIPE_ACT_GELU; ls[0].gated = gated ? 1 : 0;
       ls[0].res_pre_act = 1;
@@ -1743,8 +1745,9 @@ static int chain_forward_grid(const pipe_chain_layer* layers, int L, const float
     // decode-sized batches of fully-connected layers: the whole chain in one resident launch
     std::vector<const pipe_expansion*> es(L);
     bool fc = H0 == 1 && W0 == 1;
-    for (int l = 0; l < L; ++l) { es[l] = layers[l].e; fc = fc && layers[l].kh == 0 && small[l]; }
-    if (fc && resident_eligible(es.data(), L, (int)Tin[0], Mm, x_dev)) {
+    bool given = s_x > 0.f;
+    for (int l = 0; l < L; ++l) { es[l] = layers[l].e; fc = fc && layers[l].kh == 0 && small[l]; given = given && (l == 0 || layers[l].s_in != nullptr); }
+    if (fc && resident_eligible(es.data(), L, (int)Tin[0], Mm, x_dev, given)) {
       const int T = (int)Tin[0];
       std::vector<ResidentLayerSpec> ls(L);
       for (int l = 0; l < L; ++l) {
