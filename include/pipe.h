@@ -373,6 +373,16 @@ int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int L, const f
                                   const int* split, int M, float* const* acts_dev, float* y_dev,
                                   void* stream);
 
+/* pipe_chain_forward_conv (below) with the asymmetric codes of pipe_chain_forward_asymmetric in
+ * front of every layer, convolutions included: a member quantizes every element of its
+ * channels-last input once, over that tensor's range, and a tap outside the image holds the code
+ * of the real value 0 (the zero point), so the padding contributes nothing, as in
+ * pipe_forward_conv2d_asymmetric.  Arguments, layouts and errors as pipe_chain_forward_conv
+ * (no s_x: ranges are dynamic) and pipe_chain_forward_asymmetric.                            */
+int pipe_chain_forward_conv_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev,
+                                       int N, int H, int W, const int* split, int M,
+                                       float* const* acts_dev, float* y_dev, void* stream);
+
 /* The same member chains over convolution layers (Fig. 2 draws the expansion of a
  * convolutional network; Sec. 4 evaluates ResNets and MobileNets).  Every tensor is
  * channels-last: tokens are the positions (n, h, w) of an N x H_l x W_l grid in that

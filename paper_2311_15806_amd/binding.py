@@ -64,6 +64,7 @@ def _load():
     lib.pipe_chain_forward.argtypes = [vp, ci, vp, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_conv.argtypes = [vp, ci, vp, ci, ci, ci, cf, pi, ci, vp, vp, vp]
     lib.pipe_chain_forward_asymmetric.argtypes = [vp, ci, vp, ci, pi, ci, vp, vp, vp]
+    lib.pipe_chain_forward_conv_asymmetric.argtypes = [vp, ci, vp, ci, ci, ci, pi, ci, vp, vp, vp]
     lib.pipe_prepare.argtypes = [vp, pi, ci, ci, vp]
     lib.pipe_prepare_mlp.argtypes = [vp, vp, ci, pi, ci, ci, vp]
     lib.pipe_prepare_chain.argtypes = [vp, ci, ci, ci, ci, pi, ci, vp]
@@ -523,6 +524,33 @@ def pipe_chain_forward_conv(layers, x: torch.Tensor, s_x: float = 0.0, split=Non
     arr, m = _split(split)
     _check(_lib.pipe_chain_forward_conv(arr_l, L, _ptr(x, torch.float32), N, H, W, float(s_x), arr, m, acts_arr,
                                         _ptr(y), _stream()), "pipe_chain_forward_conv")
+    return (y, acts) if return_acts else y
+
+
+def pipe_chain_forward_conv_asymmetric(layers, x: torch.Tensor, split=None, return_acts: bool = False,
+                                       out: Optional[torch.Tensor] = None):
+    """pipe_chain_forward_conv with asymmetric activation codes in front of every layer; x [N, H, W, C] channels-last."""
+    N, H, W, _ = x.shape
+    L = len(layers)
+    M = 1 if split is None else len(split)
+    arr_l = _chain_layers(layers)
+    grids = []
+    h, w = H, W
+    for l in range(L):
+        if arr_l[l].kh > 0 and arr_l[l].kw > 0 and arr_l[l].stride > 0:
+            h = (h + 2 * arr_l[l].pad - arr_l[l].kh) // arr_l[l].stride + 1
+            w = (w + 2 * arr_l[l].pad - arr_l[l].kw) // arr_l[l].stride + 1
+        grids.append((max(h, 0), max(w, 0)))
+    y = out if out is not None else torch.empty((N,) + grids[-1] + (layers[-1][0].out_features,), dtype=torch.float32,
+                                               device=x.device)
+    acts, acts_arr = None, None
+    if return_acts and L > 1:
+        acts = [torch.empty((M, N) + grids[l] + (layers[l][0].out_features,), dtype=torch.float32, device=x.device)
+                for l in range(L - 1)]
+        acts_arr = (C.c_void_p * (L - 1))(*[_ptr(a) for a in acts])
+    arr, m = _split(split)
+    _check(_lib.pipe_chain_forward_conv_asymmetric(arr_l, L, _ptr(x, torch.float32), N, H, W, arr, m, acts_arr, _ptr(y),
+                                                   _stream()), "pipe_chain_forward_conv_asymmetric")
     return (y, acts) if return_acts else y
 
 

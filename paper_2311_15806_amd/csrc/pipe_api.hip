@@ -1056,7 +1056,7 @@ extern "C" int pipe_forward_conv2d_asymmetric(const pipe_expansion* e, const flo
   int32_t* dz = reinterpret_cast<int32_t*>(b.amax + 66);
   rc = launch_minmax(x_dev, (int64_t)N * C * H * W, slots, st);
   if (rc) return rc;
-  rc = launch_quantize_im2col_asym(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, slots,
+  rc = launch_quantize_im2col_asym(x_dev, N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo, e->in_pad, b.T_pad, slots, slots + 1,
                                    act_bits, q8, b.qx, b.rowsum, b.scale, dz, st);
   if (rc) return rc;
   rc = launch_asym_bias(bias_dev, e->asym_C_dev, b.scale, dz, e->asym_bias_dev, e->out, slots, st);
@@ -1882,19 +1882,36 @@ extern "C" int pipe_chain_forward_conv(const pipe_chain_layer* layers, int L, co
 // layers, with the affine quantizer in front of every layer.  A hidden tensor's range comes from the
 // epilogue that produced it (positive and negative part apart), every member quantizes its own tensor with
 // its own scale and zero point, and the token-free term of the zero point joins the member's bias vector.
-extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
-                                             const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
-  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
-  std::vector<int64_t> Tin(L + 1, (int64_t)T);
+// Member chains under asymmetric activation codes, on a grid of tokens (fully-connected chains: T x 1 x 1).
+// A convolution layer quantizes every element of its input once (per member, with the member's scale and zero
+// point) and gathers the patches from those codes; a tap outside the image holds the code of the real value 0.
+static int chain_forward_asym_grid(const pipe_chain_layer* layers, int L, const float* x_dev, int N, int H0, int W0,
+                                   const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || N < 0 || H0 < 1 || W0 < 1) return PIPE_EINVAL;
+  std::vector<int> Hin(L + 1), Win(L + 1), Cin(L);
+  std::vector<int64_t> Tin(L + 1);
+  Hin[0] = H0; Win[0] = W0; Tin[0] = (int64_t)N * H0 * W0;
   int out_max = 0;
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
-    if (!ly.e || ly.e->conv_C > 0 || ly.kh != 0 || ly.kw != 0) return PIPE_EINVAL;
+    if (!ly.e || ly.e->conv_C > 0) return PIPE_EINVAL;
     if (ly.act != PIPE_ACT_NONE && ly.act != PIPE_ACT_RELU && ly.act != PIPE_ACT_GELU) return PIPE_EINVAL;
     if (ly.skip_from < -1 || ly.skip_from > l) return PIPE_EINVAL;
     if (ly.e->K != layers[0].e->K) return PIPE_ESPLIT;
-    if (l > 0 && ly.e->in != layers[l - 1].e->out) return PIPE_ESHAPE;
-    if (ly.skip_from >= 0 && layers[ly.skip_from].e->in != ly.e->out) return PIPE_ESHAPE;
+    if (ly.kh < 0 || ly.kw < 0 || (ly.kh == 0) != (ly.kw == 0)) return PIPE_EINVAL;
+    if (ly.kh == 0) {
+      Cin[l] = ly.e->in; Hin[l + 1] = Hin[l]; Win[l + 1] = Win[l];
+    } else {
+      if (ly.stride < 1 || ly.pad < 0 || ly.e->in % (ly.kh * ly.kw) != 0) return PIPE_ESHAPE;
+      if (Hin[l] + 2 * ly.pad < ly.kh || Win[l] + 2 * ly.pad < ly.kw) return PIPE_ESHAPE;
+      Cin[l] = ly.e->in / (ly.kh * ly.kw);
+      Hin[l + 1] = (Hin[l] + 2 * ly.pad - ly.kh) / ly.stride + 1;
+      Win[l + 1] = (Win[l] + 2 * ly.pad - ly.kw) / ly.stride + 1;
+    }
+    Tin[l + 1] = (int64_t)N * Hin[l + 1] * Win[l + 1];
+    if (Tin[l + 1] > (int64_t)1 << 30) return PIPE_ESHAPE;
+    if (l > 0 && Cin[l] != layers[l - 1].e->out) return PIPE_ESHAPE;
+    if (ly.skip_from >= 0 && (Cin[ly.skip_from] != ly.e->out || Tin[ly.skip_from] != Tin[l + 1])) return PIPE_ESHAPE;
     out_max = std::max(out_max, ly.e->out);
   }
   if (layers[L - 1].act != PIPE_ACT_NONE) return PIPE_EINVAL;
@@ -1902,7 +1919,7 @@ extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int
   int lo[PIPE_MAX_K], hi[PIPE_MAX_K], Mm = 1;
   int rc = parse_split(K, split, M, lo, hi, &Mm);
   if (rc) return rc;
-  if (T == 0) return PIPE_OK;
+  if (N == 0) return PIPE_OK;
   if (!x_dev || !y_dev) return PIPE_EINVAL;
   const int act_bits = (int)std::lround(std::log2((double)g_act_qmax_host + 1.0)) + 1;
   for (int l = 0; l < L; ++l)   // |Q - z| <= 2^a - 1: the exact accumulator must fit 32 bits
@@ -1911,27 +1928,35 @@ extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int
   CallScope scope(stream);
   for (int l = 0; l < L; ++l)
     if ((rc = asym_prepare(layers[l].e, st)) != PIPE_OK) return rc;
+  // per layer: the contraction's token count is the layer's output grid; the members' code sums keep one stride
   std::vector<char> small(L);
-  int T_pad = 0;
-  size_t qh_bytes = 0;
+  std::vector<int> Tpad(L);
+  int T_pad_max = 0;
+  size_t qh_bytes = 0, q8_bytes = 0;
   for (int l = 0; l < L; ++l) {
-    small[l] = use_stream_kernel(layers[l].e, T);
-    // one padded token count for the whole chain: the members' code sums keep one stride
-    T_pad = std::max(T_pad, (int)round_up64(T, small[l] ? 16 : TOK_TILE));
+    small[l] = use_stream_kernel(layers[l].e, (int)Tin[l + 1]);
+    Tpad[l] = (int)round_up64(Tin[l + 1], small[l] ? 16 : TOK_TILE);
+    T_pad_max = std::max(T_pad_max, Tpad[l]);
+    if (l > 0) qh_bytes = std::max(qh_bytes, (size_t)Mm * Tpad[l] * layers[l].e->in_pad);
+    if (layers[l].kh > 0) q8_bytes = std::max(q8_bytes, (size_t)Tin[l] * Cin[l]);
   }
-  for (int l = 1; l < L; ++l) qh_bytes = std::max(qh_bytes, (size_t)Mm * T_pad * layers[l].e->in_pad);
   ActBuffers b;
-  rc = get_act_buffers(T_pad, layers[0].e->in_pad, false, &b);   // T_pad is a multiple of what either kernel needs
+  rc = get_act_buffers(Tpad[0], layers[0].e->in_pad, false, &b);   // Tpad[0] is a multiple of what its kernel needs
   if (rc) return rc;
   std::vector<float*> act;
   rc = chain_tensors(layers, L, Mm, Tin, acts_dev, &act);
   if (rc) return rc;
   uint8_t* qh = nullptr;
   int32_t* rowsum_h = nullptr;
+  int8_t* q8 = nullptr;
   if (L > 1) {
     qh = (uint8_t*)pipe_ws_get(WS_QH, qh_bytes);
-    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad * 4);
+    rowsum_h = (int32_t*)pipe_ws_get(WS_ROWSUM_H, (size_t)Mm * T_pad_max * 4);
     if (!qh || !rowsum_h) return pipe_ws_error();
+  }
+  if (q8_bytes) {
+    q8 = (int8_t*)pipe_ws_get(WS_Q8X, q8_bytes);
+    if (!q8) return pipe_ws_error();
   }
   float* bias_m = (float*)pipe_ws_get(WS_ABIAS, (size_t)Mm * out_max * sizeof(float));
   if (!bias_m) return pipe_ws_error();
@@ -1955,14 +1980,19 @@ extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int
   for (int l = 0; l < L; ++l) {
     const pipe_chain_layer& ly = layers[l];
     const pipe_expansion* e = ly.e;
-    const bool last_layer = l == L - 1;
+    const bool last_layer = l == L - 1, conv = ly.kh > 0;
+    const int T = (int)Tin[l + 1], T_pad = Tpad[l];
     GemmArgs a{};
     a.e = e; a.T = T; a.T_pad = T_pad;
     if (l == 0) {
-      rc = launch_minmax(x_dev, (int64_t)T * e->in, slots_x, st);
+      rc = launch_minmax(x_dev, Tin[0] * Cin[0], slots_x, st);
       if (rc) return rc;
-      rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, T_pad, slots_x, slots_x + 1, act_bits, b.qx, b.rowsum, nullptr,
-                                b.scale, dz_x, st);
+      if (conv)
+        rc = launch_quantize_im2col_asym(x_dev, N, Cin[0], Hin[0], Win[0], ly.kh, ly.kw, ly.stride, ly.pad, 1, Hin[1], Win[1], e->in_pad,
+                                         T_pad, slots_x, slots_x + 1, act_bits, q8, b.qx, b.rowsum, b.scale, dz_x, st);
+      else
+        rc = launch_quantize_asym(x_dev, T, e->in, e->in_pad, T_pad, slots_x, slots_x + 1, act_bits, b.qx, b.rowsum, nullptr,
+                                  b.scale, dz_x, st);
       if (rc == PIPE_OK)
         rc = launch_asym_bias_members(ly.bias_dev, e->asym_P_dev, b.scale, 0, dz_x, 0, Mm, lo, hi, last_layer ? 1 : 0, bias_m,
                                       e->out, slots_x, 2, st);
@@ -1977,15 +2007,21 @@ extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int
       const uint32_t* r_in = rng[(l - 1) & 1];
       const int64_t q_ms = (int64_t)T_pad * e->in_pad;
       for (int m = 0; m < Mm; ++m) {
-        rc = launch_quantize_asym(src + (size_t)m * T * e->in, T, e->in, e->in_pad, T_pad, r_in + m, r_in + PIPE_MAX_K + m, act_bits,
-                                  qh + (size_t)m * q_ms, rowsum_h + (size_t)m * T_pad, nullptr, scale_h + m, dz_h + m, st);
+        const float* src_m = src + (size_t)m * Tin[l] * Cin[l];
+        if (conv)
+          rc = launch_quantize_im2col_asym(src_m, N, Cin[l], Hin[l], Win[l], ly.kh, ly.kw, ly.stride, ly.pad, 1, Hin[l + 1], Win[l + 1],
+                                           e->in_pad, T_pad, r_in + m, r_in + PIPE_MAX_K + m, act_bits, q8, qh + (size_t)m * q_ms,
+                                           rowsum_h + (size_t)m * T_pad_max, scale_h + m, dz_h + m, st);
+        else
+          rc = launch_quantize_asym(src_m, T, e->in, e->in_pad, T_pad, r_in + m, r_in + PIPE_MAX_K + m, act_bits,
+                                    qh + (size_t)m * q_ms, rowsum_h + (size_t)m * T_pad_max, nullptr, scale_h + m, dz_h + m, st);
         if (rc) return rc;
       }
       rc = launch_asym_bias_members(ly.bias_dev, e->asym_P_dev, scale_h, 1, dz_h, 1, Mm, lo, hi, last_layer ? 1 : 0, bias_m, e->out,
                                     nullptr, 0, st);
       if (rc) return rc;
       a.qx = qh; a.qx_mstride = q_ms;
-      a.rowsum = rowsum_h; a.rowsum_mstride = T_pad;
+      a.rowsum = rowsum_h; a.rowsum_mstride = T_pad_max;
       a.s_x = scale_h; a.sx_mstride = 1;
       a.zero_after = rng[(l - 1) & 1]; a.zero_n = 2 * PIPE_MAX_K;
     }
@@ -2009,6 +2045,19 @@ extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int
   }
   t_ws->range_h_dirty = false;
   return PIPE_OK;
+}
+
+extern "C" int pipe_chain_forward_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev, int T,
+                                             const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  if (!layers || L < 1 || T < 0) return PIPE_EINVAL;
+  for (int l = 0; l < L; ++l)
+    if (layers[l].kh != 0 || layers[l].kw != 0) return PIPE_EINVAL;
+  return chain_forward_asym_grid(layers, L, x_dev, T, 1, 1, split, M, acts_dev, y_dev, stream);
+}
+
+extern "C" int pipe_chain_forward_conv_asymmetric(const pipe_chain_layer* layers, int L, const float* x_dev, int N, int H, int W,
+                                                  const int* split, int M, float* const* acts_dev, float* y_dev, void* stream) {
+  return chain_forward_asym_grid(layers, L, x_dev, N, H, W, split, M, acts_dev, y_dev, stream);
 }
 
 extern "C" int pipe_prepare_chain(const pipe_chain_layer* layers, int L, int N, int H, int W, const int* split, int M,

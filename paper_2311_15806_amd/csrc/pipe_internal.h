@@ -243,9 +243,9 @@ int launch_quantize_asym(const float* x, int T, int in, int in_pad, int T_pad, c
                          uint8_t* qx_frag, int32_t* rowsum, uint8_t* qx_rowmajor, float* scale_out, int32_t* dz_out,
                          hipStream_t st);
 int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int kh, int kw, int stride, int pad, int nhwc,
-                                int Ho, int Wo, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
-                                int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out, int32_t* dz_out,
-                                hipStream_t st);
+                                int Ho, int Wo, int in_pad, int T_pad, const uint32_t* hi_slot, const uint32_t* nlo_slot,
+                                int act_bits, int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out,
+                                int32_t* dz_out, hipStream_t st);
 int launch_asym_bias(const float* bias, const float* C, const float* scale, const int32_t* dz, float* out, int n,
                      uint32_t* slots, hipStream_t st);
 int launch_asym_acc_fix(int32_t* acc, const int32_t* wsum, const int32_t* dz, int K, int T, int out, hipStream_t st);

@@ -506,12 +506,13 @@ __global__ __launch_bounds__(BLK) void quantize_asym_kernel(const float* __restr
 
 // every element of a tensor once, in its own layout (the convolution's first step): code minus shift
 __global__ __launch_bounds__(BLK) void quantize_elem_asym_kernel(const float* __restrict__ x, int64_t n,
-                                                                 const uint32_t* __restrict__ slots, float qa, int shift,
+                                                                 const uint32_t* __restrict__ hi_slot,
+                                                                 const uint32_t* __restrict__ nlo_slot, float qa, int shift,
                                                                  int8_t* __restrict__ q8, float* __restrict__ scale_out,
                                                                  int32_t* __restrict__ dz_out, int32_t* __restrict__ zero_me,
                                                                  int n_zero) {
   for (int i = blockIdx.x * BLK + threadIdx.x; i < n_zero; i += gridDim.x * BLK) zero_me[i] = 0;
-  const float hi = __uint_as_float(slots[0]), nlo = __uint_as_float(slots[1]);
+  const float hi = __uint_as_float(hi_slot[0]), nlo = __uint_as_float(nlo_slot[0]);
   const float s = __fdiv_rn(__fadd_rn(hi, nlo), qa);
   const bool live = s > 0.f;
   const float zf = live ? fminf(fmaxf(rintf(__fdiv_rn(nlo, s)), 0.f), qa) : 0.f;
@@ -739,14 +740,15 @@ int launch_quantize_im2col(const float* x, int N, int C, int H, int W, int kh, i
 // the same with asymmetric codes: every element once (code minus 2^(a-1), scale and 2^(a-1) - z to device
 // memory), then the patches, whose taps outside the image hold the code of the real value 0
 int launch_quantize_im2col_asym(const float* x, int N, int C, int H, int W, int kh, int kw, int stride, int pad, int nhwc,
-                                int Ho, int Wo, int in_pad, int T_pad, const uint32_t* slots, int act_bits,
-                                int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out, int32_t* dz_out,
-                                hipStream_t st) {
+                                int Ho, int Wo, int in_pad, int T_pad, const uint32_t* hi_slot, const uint32_t* nlo_slot,
+                                int act_bits, int8_t* q8_scratch, uint8_t* qx_frag, int32_t* rowsum, float* scale_out,
+                                int32_t* dz_out, hipStream_t st) {
   const int64_t n = (int64_t)N * C * H * W;
   if (n >= ((int64_t)1 << 31)) return PIPE_ESHAPE;   // the gather steps 32-bit element offsets
   int64_t blocks = (n + BLK - 1) / BLK;
   if (blocks > 2048) blocks = 2048;
-  PIPE_KLAUNCH(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, slots,
+  if (blocks < 1) blocks = 1;
+  PIPE_KLAUNCH(quantize_elem_asym_kernel, dim3((unsigned)blocks), dim3(BLK), 0, st, x, n, hi_slot, nlo_slot,
                      (float)((1 << act_bits) - 1), 1 << (act_bits - 1), q8_scratch, scale_out, dz_out, rowsum, T_pad);
   ConvGeom g{N, C, H, W, kh, kw, stride, pad, nhwc, Ho, Wo};
   const int T = N * Ho * Wo, in = C * kh * kw;

@@ -60,6 +60,7 @@ def test_argument_errors_return_codes(lib):
     assert lib.pipe_chain_forward(fake, 0, None, 4, C.c_float(0), None, 0, None, None, None) == EINVAL
     assert lib.pipe_chain_forward_conv(None, 1, None, 1, 4, 4, C.c_float(0), None, 0, None, None, None) == EINVAL
     assert lib.pipe_chain_forward_asymmetric(None, 1, None, 1, None, 0, None, None, None) == EINVAL
+    assert lib.pipe_chain_forward_conv_asymmetric(None, 1, None, 1, 4, 4, None, 0, None, None, None) == EINVAL
     assert lib.pipe_mlp_forward_asymmetric(None, None, 1, None, 1, None, 0, None, None, None, None, None) == EINVAL
     assert lib.pipe_mlp_forward_given_scales(None, None, 1, None, 1, C.c_float(1), None, None, 0, None, None, None, None, None) == EINVAL
     assert lib.pipe_spectral_norm(None, 4, 4, 3, None, None) == EINVAL

@@ -333,6 +333,57 @@ def test_conv_residual_stack_parity(pipe, bits, K, split, N, H, W):
         g.free()
 
 
+@pytest.mark.parametrize("N,H,W", [(2, 12, 12), (1, 5, 7)])
+@pytest.mark.parametrize("bits,K,split", [(4, 4, [2, 2]), (2, 4, [1, 3]), (8, 2, None)])
+def test_asymmetric_conv_chain_parity(pipe, bits, K, split, N, H, W):
+    """The ResNet-like stack of test_conv_residual_stack_parity under asymmetric activation codes (Sec. 4.3):
+    every member quantizes every element of its own hidden tensor over that tensor's range, and the taps of a
+    3x3 window outside the image hold the zero point.  Teacher-forced layer by layer, then free-running; a
+    second call (all range slots cleared) and the symmetric call on the same scratch are unchanged."""
+    C0 = 16
+    geo = [(32, C0, 3, 1, 1), (32, 32, 3, 1, 1), (32, 32, 3, 1, 1), (48, 32, 3, 2, 1), (32, 48, 1, 1, 0), (16, 32, 0, 1, 0)]
+    acts = ["relu", "relu", "relu", "relu", "gelu", "none"]
+    skips = [-1, -1, 1, -1, -1, -1]
+    olayers, glayers, gpu = _conv_stack(pipe, geo, acts, skips, bits, K, 0.5, 16, seed=400 + bits)
+    rng = np.random.default_rng(19)
+    x = (rng.standard_normal((N, H, W, C0)) + 0.5).astype(np.float32)   # a range with both signs, off centre
+    xt = x.reshape(N * H * W, C0)
+    y, acts_g = pipe.pipe_chain_forward_conv_asymmetric(glayers, dev(x), split=split, return_acts=True)
+    grids = po.chain_grids(olayers, (N, H, W))
+    assert tuple(y.shape) == (N, grids[-1][1], grids[-1][2], 16)
+    y = y.cpu().numpy().reshape(-1, 16)
+    acts_g = [a.cpu().numpy().reshape(a.shape[0], -1, a.shape[-1]) for a in acts_g]
+    M = 1 if split is None else len(split)
+    L = len(olayers)
+    for l in range(L):
+        sk = po.chain_skips(olayers, l, xt, acts_g, M)
+        if l == 0:
+            ref = po.chain_layer_members(olayers[0], xt, True, sk, split, None, 8, grids[0], asymmetric=True)
+        else:
+            ref = po.chain_layer_members(olayers[l], acts_g[l - 1], False, sk, split, None, 8, grids[l], asymmetric=True)
+        if l < L - 1:
+            assert acts_g[l].shape == ref.shape, (l, acts_g[l].shape, ref.shape)
+            for m in range(M):
+                # two large terms cancel in the kernels' evaluation: the error follows the tensor's scale
+                d = np.abs(acts_g[l][m].astype(np.float64) - ref[m])
+                assert d.max() <= 2e-5 * np.abs(ref[m]).max() + 1e-30
+                assert_close_fp32(acts_g[l][m], ref[m])
+        else:
+            assert_close_fp32(y, po.sum_members(ref))
+    full = po.chain_forward(olayers, xt, split=split, grid=(N, H, W), asymmetric=True)
+    assert_close_fp32(y, full["y"], tol=3e-2, elementwise=False)
+    y2 = pipe.pipe_chain_forward_conv_asymmetric(glayers, dev(x), split=split).cpu().numpy().reshape(-1, 16)
+    assert np.array_equal(y, y2)
+    ys = pipe.pipe_chain_forward_conv(glayers, dev(x), split=split).cpu().numpy().reshape(-1, 16)
+    fs = po.chain_forward(olayers, xt, split=split, grid=(N, H, W))
+    assert_close_fp32(ys, fs["y"], tol=3e-2, elementwise=False)
+    # the flat entry point has no grid: it refuses convolution layers
+    with pytest.raises(pipe.PipeError):
+        pipe.pipe_chain_forward_asymmetric(glayers, dev(xt), split=split)
+    for g in gpu:
+        g.free()
+
+
 def test_conv_chain_argument_errors(pipe):
     geo = [(32, 16, 3, 1, 1), (32, 32, 3, 2, 1), (16, 32, 0, 1, 0)]
     olayers, glayers, gpu = _conv_stack(pipe, geo, ["relu", "relu", "none"], [-1, -1, -1], 4, 2, 1.0, 16, seed=5)

@@ -895,6 +895,56 @@ def test_conv_chain_is_layer_by_layer_conv_and_converges_to_torch():
     assert np.abs(r8["y"] - ref).max() < 0.03 * np.abs(ref).max()
 
 
+def test_asymmetric_conv_chain_is_the_pinned_asymmetric_conv_layer_by_layer():
+    """Asymmetric codes (Sec. 4.3) in front of the convolutions of a member chain: with one member it is the
+    pinned single-layer routine (whose padding is the real value 0) applied layer by layer with ReLU and a
+    skip; with two members the sum is the members'; and after ReLUs, at 4-bit activations, it is closer
+    to torch's fp64 ConvNet than the symmetric chain."""
+    rng = np.random.default_rng(187)
+    N, H, W, C = 2, 7, 6, 8
+    geo = [(16, C, 3, 1, 1), (16, 16, 3, 1, 1), (16, 16, 3, 1, 1), (24, 16, 3, 2, 1), (8, 24, 0, 1, 0)]   # O, Cin, k, stride, pad
+    Ws = [(rng.standard_normal((o, c * max(k, 1) ** 2)) * math.sqrt(2.0 / (c * max(k, 1) ** 2))).astype(f32) for o, c, k, _, _ in geo]
+    bs = [(0.2 * rng.standard_normal(o)).astype(f32) for o, *_ in geo]
+    acts = ["relu", "relu", "relu", "relu", "none"]
+    skip = [-1, -1, 1, -1, -1]
+    x = np.abs(rng.standard_normal((N, C, H, W))).astype(f32)
+    xt = np.ascontiguousarray(x.transpose(0, 2, 3, 1)).reshape(N * H * W, C)
+
+    def layers(bits, K):
+        return [po.ChainLayer(po.expand(Wl, bits, K, 1.0, 8), b, a, sk, True, k, k, st, pd)
+                for Wl, b, a, sk, (o, c, k, st, pd) in zip(Ws, bs, acts, skip, geo)]
+
+    L4 = layers(4, 2)
+    grids = po.chain_grids(L4, (N, H, W))
+    to_nchw = lambda a, g: a.reshape(g[0], g[1], g[2], -1).transpose(0, 3, 1, 2)
+    r = po.chain_forward(L4, xt, grid=(N, H, W), asymmetric=True)
+    a0 = np.maximum(po.forward_conv2d_asymmetric(L4[0].exp, x, 3, 3, 1, 1, bias=bs[0])["y"], 0)
+    a1 = np.maximum(po.forward_conv2d_asymmetric(L4[1].exp, to_nchw(a0, grids[1]), 3, 3, 1, 1, bias=bs[1])["y"], 0)
+    a2 = np.maximum((po.forward_conv2d_asymmetric(L4[2].exp, to_nchw(a1, grids[2]), 3, 3, 1, 1, bias=bs[2])["y"] + a0).astype(f32), 0)
+    a3 = np.maximum(po.forward_conv2d_asymmetric(L4[3].exp, to_nchw(a2, grids[3]), 3, 3, 2, 1, bias=bs[3])["y"], 0)
+    y = po.forward_asymmetric(L4[4].exp, a3, bias=bs[4])["y"]
+    assert all(np.array_equal(r["acts"][i][0], a) for i, a in enumerate([a0, a1, a2, a3]))
+    assert np.array_equal(r["y"], y)
+    assert not np.array_equal(r["y"], po.chain_forward(L4, xt, grid=(N, H, W))["y"])
+    r2 = po.chain_forward(L4, xt, split=[1, 1], grid=(N, H, W), asymmetric=True)
+    assert np.array_equal(r2["y"], (r2["members"][0] + r2["members"][1]).astype(f32))
+    # against torch's fp64 ConvNet, 8-bit weights (K = 4), 4-bit activations
+    t = lambda a: torch.from_numpy(np.asarray(a)).double()
+    h, saved = t(x), {}
+    for l, (Wl, b, (o, c, k, st, pd)) in enumerate(zip(Ws, bs, geo)):
+        saved[l] = h
+        kk = max(k, 1)
+        z = torch.nn.functional.conv2d(h, t(Wl).reshape(o, c, kk, kk), t(b), stride=st, padding=pd)
+        if skip[l] >= 0:
+            z = z + saved[skip[l]]
+        h = torch.relu(z) if acts[l] == "relu" else z
+    ref = h.permute(0, 2, 3, 1).reshape(-1, 8).numpy()
+    L8 = layers(8, 4)
+    e_sym = np.abs(po.chain_forward(L8, xt, split=[2, 2], grid=(N, H, W), act_bits=4)["y"] - ref).mean()
+    e_asym = np.abs(po.chain_forward(L8, xt, split=[2, 2], grid=(N, H, W), act_bits=4, asymmetric=True)["y"] - ref).mean()
+    assert e_asym < 0.8 * e_sym, (e_asym, e_sym)
+
+
 # ---------------------------------------------------------------- App. C: diagnostics
 def test_spectral_norm_against_svd_and_closed_forms():
     rng = np.random.default_rng(90)
