@@ -253,19 +253,22 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
     if (a.mask != b.mask) return a.mask < b.mask;
     return a.rb < b.rb;
   });
-  // Bins of the weight-streaming kernel: output row blocks, most orders first, packed first-fit
-  // into bins of `cap` stored row blocks.  A stored row block's position in the schedule-ordered
-  // buffers is bin * cap + index inside the bin.
+  // Bins of the weight-streaming kernel: output row blocks, most orders first, packed best-fit
+  // into bins of `cap` stored row blocks (the bin with the least room that still takes the block: a bin's
+  // unused positions are zeros in memory that the kernel streams like codes, so a 3-order block should meet
+  // a 1-order block).  A stored row block's position in the schedule-ordered buffers is
+  // bin * cap + index inside the bin.
   const int cap = std::min(STREAM_BIN_CAP, (std::max(4, K) + 3) / 4 * 4);   // 4, 8, 12 or 16: the kernel streams 4 items at a time
   std::vector<StreamBin> bins;
   std::vector<int> room;
+  std::vector<std::vector<int>> with_room(cap + 1);   // open bins by the room they have left (most recent last)
   for (int k = 0; k < K; ++k) e->orders[k].pos.assign((size_t)e->orders[k].n_kept * rbpg, -1);
   for (int i = 0; i < n_rb; ++i) {
     const int rb = items[i].rb, pop = items[i].pop;
     const int g = rb / rbpg, b = rb % rbpg;
     int which = -1;
-    for (int j = (int)bins.size() - 1; j >= 0 && j >= (int)bins.size() - 64; --j)
-      if (room[j] >= pop) { which = j; break; }
+    for (int r = pop; r <= cap && which < 0; ++r)
+      if (!with_room[r].empty()) { which = with_room[r].back(); with_room[r].pop_back(); }
     if (which < 0) {
       StreamBin nb;
       std::memset(&nb, 0, sizeof(nb));
@@ -273,6 +276,7 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
       room.push_back(cap);
       which = (int)bins.size() - 1;
     }
+    if (room[which] - pop > 0) with_room[room[which] - pop].push_back(which);
     StreamBin& bn = bins[which];
     const int slot = bn.n_out++;
     bn.out_rb[slot] = rb;
