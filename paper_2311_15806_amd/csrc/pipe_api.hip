@@ -254,43 +254,61 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
     return a.rb < b.rb;
   });
   // Bins of the weight-streaming kernel: output row blocks, most orders first, packed best-fit
-  // into bins of `cap` stored row blocks (the bin with the least room that still takes the block: a bin's
-  // unused positions are zeros in memory that the kernel streams like codes, so a 3-order block should meet
-  // a 1-order block).  A stored row block's position in the schedule-ordered buffers is
-  // bin * cap + index inside the bin.
+  // into bins of `cap` stored row blocks (the bin with the least room that still takes the block).
   const int cap = std::min(STREAM_BIN_CAP, (std::max(4, K) + 3) / 4 * 4);   // 4, 8, 12 or 16: the kernel streams 4 items at a time
-  std::vector<StreamBin> bins;
-  std::vector<int> room;
+  struct BinRbs { std::vector<int> rbs; int n_items = 0; };
+  std::vector<BinRbs> packed;
   std::vector<std::vector<int>> with_room(cap + 1);   // open bins by the room they have left (most recent last)
-  for (int k = 0; k < K; ++k) e->orders[k].pos.assign((size_t)e->orders[k].n_kept * rbpg, -1);
   for (int i = 0; i < n_rb; ++i) {
-    const int rb = items[i].rb, pop = items[i].pop;
-    const int g = rb / rbpg, b = rb % rbpg;
+    const int pop = items[i].pop;
     int which = -1;
     for (int r = pop; r <= cap && which < 0; ++r)
       if (!with_room[r].empty()) { which = with_room[r].back(); with_room[r].pop_back(); }
     if (which < 0) {
-      StreamBin nb;
-      std::memset(&nb, 0, sizeof(nb));
-      bins.push_back(nb);
-      room.push_back(cap);
-      which = (int)bins.size() - 1;
+      packed.push_back(BinRbs{});
+      which = (int)packed.size() - 1;
     }
-    if (room[which] - pop > 0) with_room[room[which] - pop].push_back(which);
-    StreamBin& bn = bins[which];
-    const int slot = bn.n_out++;
-    bn.out_rb[slot] = rb;
-    for (int k = 0; k < K; ++k) {
-      if (slot_of[k][g] < 0) continue;
-      const int it = bn.n_items++;
-      bn.k[it] = k;
-      bn.slot[it] = slot;
-      e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b] = which * cap + it;
+    packed[which].rbs.push_back(items[i].rb);
+    packed[which].n_items += pop;
+    if (cap - packed[which].n_items > 0) with_room[cap - packed[which].n_items].push_back(which);
+  }
+  // Positions in the schedule-ordered buffers.  Bins of 4: fullest bins first and the stored row blocks
+  // packed without gaps, so a bin's first position and item count follow from its index and the number of
+  // bins with 4, 3 and 2 items (bin_thr): the kernel still addresses its codes from its block index alone,
+  // and the items a bin does not have are read from one all-zero position behind the last (zero_pos), which
+  // stays in cache, instead of from zeros of the bin's own in memory.  Wider bins (more than 4 orders):
+  // position = bin * cap + index, unused positions are zeros.
+  if (cap == 4)
+    std::stable_sort(packed.begin(), packed.end(), [](const BinRbs& a, const BinRbs& b) { return a.n_items > b.n_items; });
+  std::vector<StreamBin> bins(packed.size());
+  for (int k = 0; k < K; ++k) e->orders[k].pos.assign((size_t)e->orders[k].n_kept * rbpg, -1);
+  e->bin_thr[0] = e->bin_thr[1] = e->bin_thr[2] = 0;
+  int next_pos = 0;
+  for (size_t bi = 0; bi < packed.size(); ++bi) {
+    StreamBin& bn = bins[bi];
+    std::memset(&bn, 0, sizeof(bn));
+    const int first = cap == 4 ? next_pos : (int)bi * cap;
+    for (int rb : packed[bi].rbs) {
+      const int g = rb / rbpg, b = rb % rbpg;
+      const int slot = bn.n_out++;
+      bn.out_rb[slot] = rb;
+      for (int k = 0; k < K; ++k) {
+        if (slot_of[k][g] < 0) continue;
+        const int it = bn.n_items++;
+        bn.k[it] = k;
+        bn.slot[it] = slot;
+        e->orders[k].pos[(size_t)slot_of[k][g] * rbpg + b] = first + it;
+      }
     }
-    room[which] -= pop;
+    next_pos = first + (cap == 4 ? bn.n_items : cap);
+    if (cap == 4)
+      for (int n = 4; n >= 2; --n)
+        if (bn.n_items >= n) e->bin_thr[4 - n] = (int)bi + 1;   // bins 0 .. bin_thr[4-n]-1 hold at least n items
   }
   e->n_bins = (int)bins.size();
   e->bin_cap = cap;
+  e->n_pos = next_pos;
+  e->zero_pos = next_pos;
   PIPE_HIP(hipMalloc(&e->bins_dev, bins.size() * sizeof(StreamBin)));
   PIPE_HIP(hipMemcpy(e->bins_dev, bins.data(), bins.size() * sizeof(StreamBin), hipMemcpyHostToDevice));
 
@@ -304,12 +322,12 @@ static int build_schedule(pipe_expansion* e, hipStream_t st) {
 
   // Move the stored row blocks to their positions and drop the per-order buffers.
   const int64_t rb_bytes = (int64_t)(e->in_pad / (512 / e->bits)) * 1024;
-  const size_t n_pos = (size_t)e->n_bins * cap;
+  const size_t n_pos = (size_t)e->n_pos + 1;   // and the all-zero position
   PIPE_HIP(hipMalloc(&e->codes_dev, n_pos * (size_t)rb_bytes));
   PIPE_HIP(hipMalloc(&e->scales_all_dev, n_pos * 16 * sizeof(float)));
   PIPE_HIP(hipMemsetAsync(e->codes_dev, 0, n_pos * (size_t)rb_bytes, st));
   PIPE_HIP(hipMemsetAsync(e->scales_all_dev, 0, n_pos * 16 * sizeof(float), st));
-  PIPE_HIP(hipMalloc(&e->split_sum_dev, n_pos * PIPE_MAX_SPLIT * 256 * sizeof(int32_t)));
+  PIPE_HIP(hipMalloc(&e->split_sum_dev, (size_t)e->n_bins * cap * PIPE_MAX_SPLIT * 256 * sizeof(int32_t)));
   PIPE_HIP(hipMalloc(&e->split_cnt_dev, (size_t)e->n_bins * sizeof(uint32_t)));
   PIPE_HIP(hipMemsetAsync(e->split_cnt_dev, 0, (size_t)e->n_bins * sizeof(uint32_t), st));
   for (int k = 0; k < K; ++k) {
@@ -514,7 +532,7 @@ extern "C" int pipe_expansion_order(const pipe_expansion* e, int k, int* n_group
   PIPE_HIP(hipDeviceSynchronize());
   if (scales && rows) {
     // row scales sit at the row blocks' schedule positions
-    const size_t n_pos = (size_t)e->n_bins * e->bin_cap;
+    const size_t n_pos = (size_t)e->n_pos;
     std::vector<float> all(n_pos * 16);
     PIPE_HIP(hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost));
     for (size_t c = 0; c < o.pos.size(); ++c) std::memcpy(scales + c * 16, &all[(size_t)o.pos[c] * 16], 16 * sizeof(float));
@@ -944,7 +962,7 @@ static int asym_prepare(const pipe_expansion* ce, hipStream_t st) {
     if (rc == PIPE_OK) rc = launch_row_code_sums(tmp, rows, e->in, e->group, o.gids_dev, wsum + (size_t)k * out, st);
   }
   std::vector<int32_t> hw((size_t)e->K * out);
-  std::vector<float> all((size_t)e->n_bins * e->bin_cap * 16), hC(out, 0.f), hP((size_t)e->K * out, 0.f);
+  std::vector<float> all((size_t)e->n_pos * 16), hC(out, 0.f), hP((size_t)e->K * out, 0.f);
   if (rc == PIPE_OK && (hipStreamSynchronize(st) != hipSuccess ||
                         hipMemcpy(hw.data(), wsum, hw.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
                         hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess))

@@ -230,7 +230,7 @@ extern "C" int pipe_expansion_error_bound(const pipe_expansion* e, double* u_lem
   if (!e) return PIPE_EINVAL;
   if (e->unstructured) return PIPE_EINVAL;   // a pruned entry keeps an earlier order's residual: the row scales do not bound it
   PIPE_HIP(hipDeviceSynchronize());
-  const size_t n_pos = (size_t)e->n_bins * e->bin_cap;
+  const size_t n_pos = (size_t)e->n_pos;
   std::vector<float> all(n_pos * 16);
   PIPE_HIP(hipMemcpy(all.data(), e->scales_all_dev, all.size() * sizeof(float), hipMemcpyDeviceToHost));
   std::vector<double> last((size_t)e->out, 0.0);

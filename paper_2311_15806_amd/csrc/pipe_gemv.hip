@@ -54,6 +54,8 @@ struct StreamParams {
   int ksplit;              // workgroups per bin: each takes a contiguous share of the k tiles
   int n_tb;                // 16-token blocks: one workgroup per (bin, k share, token block)
   int n_bins;
+  int thr0, thr1, thr2;    // bins of 4, fullest first: how many hold 4, at least 3, at least 2 items
+  int zero_pos;            // an all-zero position (codes and scales): read for the items a bin does not have
   const float* x_f32;      // QFUSE: the fp32 input [T, in] (T <= 4), quantized by every workgroup itself
   float s_static;          // QFUSE: given activation scale, or <= 0 for max|x| / act_qmax
   float act_qmax;          // QFUSE: largest activation code
@@ -146,10 +148,16 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   // tiles w, w+NW, ...; two tiles per item are in flight.
   // this workgroup's share of the k tiles
   const int tile_lo = (int)((long long)n_tiles * ksp / p.ksplit), tile_hi = (int)((long long)n_tiles * (ksp + 1) / p.ksplit);
-  const size_t pos0 = (size_t)bin * R;
+  // the bin's first position and item count, from its index: the bins lie without gaps, fullest first
+  const int b3 = max(bin - p.thr0, 0), b2 = max(bin - p.thr1, 0), b1 = max(bin - p.thr2, 0);
+  const int n_here = bin < p.thr0 ? 4 : (bin < p.thr1 ? 3 : (bin < p.thr2 ? 2 : 1));
+  const int pos0 = 4 * bin - b3 - b2 - b1;
+  size_t posr[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) posr[r] = (size_t)(r < n_here ? pos0 + r : p.zero_pos);
   const uint8_t* wb[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) wb[r] = p.codes + (pos0 + r) * (size_t)n_tiles * 1024;
+  for (int r = 0; r < R; ++r) wb[r] = p.codes + posr[r] * (size_t)n_tiles * 1024;
   const int d0 = lane < BIN_WORDS ? reinterpret_cast<const int32_t*>(p.bins + bin)[lane] : 0;
   uint4 w0[R], w1[R], x0[NX], x1[NX];
   auto load_w = [&](int tl, uint4 (&w)[R]) __attribute__((always_inline)) {
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   // activation scale and this thread's token code sum
   float scv[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) scv[r] = p.scales[(pos0 + r) * 16 + ch];
+  for (int r = 0; r < R; ++r) scv[r] = p.scales[posr[r] * 16 + ch];
   float sxm[R];
   int rsm[R];
   if constexpr (!QFUSE) {
@@ -708,6 +716,7 @@ int launch_gemm_stream(const GemmArgs& a, hipStream_t st) {
     else ks = std::min(256 / (e->n_bins > 0 ? e->n_bins : 1), std::min(PIPE_MAX_SPLIT, n_tiles / 16));
     p.n_tb = a.T_pad / 16;
     p.n_bins = e->n_bins;
+    p.thr0 = e->bin_thr[0]; p.thr1 = e->bin_thr[1]; p.thr2 = e->bin_thr[2]; p.zero_pos = e->zero_pos;
     if (p.n_tb > 1) ks = 1;   // several token blocks already multiply the workgroups
     p.ksplit = std::max(ks, 1);
     p.ws_sum = e->split_sum_dev; p.ws_cnt = e->split_cnt_dev;

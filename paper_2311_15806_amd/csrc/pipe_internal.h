@@ -131,12 +131,15 @@ struct pipe_expansion {
   // (in = kh*kw), built on first use of pipe_forward_depthwise2d
   int8_t* dw_codes_dev = nullptr;
   float* dw_scales_dev = nullptr;
-  // Stored row blocks of all orders in schedule order: bin b of the weight-streaming kernel owns
-  // positions [b*bin_cap, (b+1)*bin_cap), so that kernel addresses its codes from its block index
-  // alone; the tiled kernel reaches them through its pass tables.  Unused positions are zero.
-  uint8_t* codes_dev = nullptr;       // [n_bins*bin_cap][in_pad/KSUP][1 KiB]
-  float* scales_all_dev = nullptr;    // [n_bins*bin_cap][16]
+  // Stored row blocks of all orders in schedule order, bin after bin of the weight-streaming kernel, which
+  // addresses its codes from its block index alone: bins of 4 lie without gaps, fullest first (a bin's first
+  // position follows from bin_thr), wider bins own positions [b*bin_cap, (b+1)*bin_cap) with zeros in the unused
+  // ones.  The tiled and resident kernels reach the row blocks through their tables (pos_of).
+  uint8_t* codes_dev = nullptr;       // [n_pos + 1][in_pad/KSUP][1 KiB]
+  float* scales_all_dev = nullptr;    // [n_pos + 1][16]
   int n_bins = 0, bin_cap = 0;
+  int n_pos = 0, zero_pos = 0;        // stored positions; the all-zero position behind them
+  int bin_thr[3] = {0, 0, 0};         // bins of 4 (fullest first): how many hold 4, at least 3, at least 2 items
   StreamBin* bins_dev = nullptr;
   // asymmetric activations (built on first use of pipe_forward_asymmetric): per order and output channel the sum of
   // the row's codes [K][out] (pruned rows 0), C[o] = sum_k s_k[o] * wsum_k[o], and the effective bias of the last call
