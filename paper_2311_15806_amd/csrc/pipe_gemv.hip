@@ -142,8 +142,8 @@ __global__ __launch_bounds__(NW * 64, (XM * (BITS == 2 ? 4 : (BITS == 4 ? 2 : 1)
   constexpr int O_STEP = (NW * 64) / 256;
   const bool fold_sx = p.reduce && p.M > 1;
 
-  // ---- everything that does not depend on the bin descriptor is requested first: the bin's R
-  // stored row blocks sit at positions blockIdx.x * R + r of the schedule-ordered buffers, so
+  // ---- everything that does not depend on the bin descriptor is requested first: where the bin's
+  // stored row blocks sit in the schedule-ordered buffers follows from the bin's index (below), so
   // the code stream (the HBM traffic that bounds this kernel) starts at once.  Wave w streams
   // tiles w, w+NW, ...; two tiles per item are in flight.
   // this workgroup's share of the k tiles
