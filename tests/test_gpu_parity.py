@@ -832,12 +832,14 @@ def test_decode_with_the_quantizer_inside_the_streaming_kernel(pipe, T):
         es = [pipe.pipe_expand(dev(wl.make_weight(w, l)), s.bits, s.K, s.gamma, s.group) for l, s in enumerate(w.layers)]
         xm = dev(wl.make_input(w))
         try:
-            ya = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split).cpu().numpy()
+            ya, ha = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split, return_hidden=True)
+            ya, ha = ya.cpu().numpy(), ha.cpu().numpy()
             pipe.pipe_set_decode_fusion(False)
-            yb = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split).cpu().numpy()
+            yb, hb = pipe.pipe_mlp_forward(es[0], es[1], act, xm, split=split, return_hidden=True)
+            yb, hb = yb.cpu().numpy(), hb.cpu().numpy()
         finally:
             pipe.pipe_set_decode_fusion(True)
-        assert np.array_equal(ya, yb)
+        assert np.array_equal(ya, yb) and np.array_equal(ha, hb)
         for e in es:
             e.free()
     # an output buffer that IS the input (square layer): the two-launch path, whose quantizer has
