@@ -502,7 +502,7 @@ int pipe_set_decode_fusion(int on);
  * 16 layers, in_features of the first layer a multiple of 4 and a 16-byte aligned input; otherwise
  * the calls take the per-layer launches.  `on`: 0 never, 2 whenever the conditions hold, 1 (default)
  * where it measured faster: chains of three or more layers at any batch, shorter chains and the MLP
- * call from 8 tokens on, or at any batch when every activation scale is given (the exchange between
+ * call above 8 tokens, or at any batch when every activation scale is given (the exchange between
  * workgroups costs about 8 us per layer, half of it for the maxima that given scales make
  * unnecessary; two launches per layer cost about 10-17 us).  Results do not depend on the setting (the fp32 arithmetic and its
  * order are those of the per-layer kernels).  Returns PIPE_EINVAL for other values.
