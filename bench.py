@@ -226,6 +226,9 @@ def main():
             k_ms, k_n = pipe.pipe_timing_read()
             step_ms = (t_b - t_a) * 1e3 / steps
             mode = "eager"
+            # a resident launch whose wait for other workgroups ran out ends with wrong results: no figure from such a run
+            if pipe.pipe_resident_status() != 0:
+                raise RuntimeError("a resident launch ran into its wait limit: the timings of this run are void")
             # ---- the same K steps as ONE HIP graph: decode-sized steps are launch bound, and the small
             # layers' five launches leave gaps as long as their kernels when launched eagerly --------
             if graph and not args.no_graph:
@@ -251,6 +254,9 @@ def main():
                     g.replay()
                     torch.cuda.synchronize()
                     t_b = time.perf_counter()
+                    with torch.cuda.stream(side):
+                        if pipe.pipe_resident_status() != 0:
+                            raise RuntimeError("a resident launch of the graph ran into its wait limit")
                     step_ms = (t_b - t_a) * 1e3 / steps
                     mode = "hipgraph"
                 except Exception as ex:      # keep the eager number
