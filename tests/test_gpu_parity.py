@@ -858,3 +858,45 @@ def test_decode_with_the_quantizer_inside_the_streaming_kernel(pipe, T):
     y = pipe.pipe_forward(g, dev(np.zeros((T, 256), np.float32)), bias=dev(b)).cpu().numpy()
     assert np.array_equal(y, np.tile(b, (T, 1)))
     g.free()
+
+
+def _off_by_one_float(x):
+    """The same values at an address that is 4-byte but not 16-byte aligned."""
+    buf = torch.empty(x.numel() + 8, dtype=x.dtype, device=x.device)
+    off = 1 if (buf.data_ptr() + 4) % 16 != 0 else 2
+    v = buf[off:off + x.numel()].view(x.shape)
+    v.copy_(x)
+    assert v.data_ptr() % 16 != 0
+    return v
+
+
+@pytest.mark.parametrize("O,I,bits,K,gamma,group", [(320, 700, 4, 3, 0.5, 32), (512, 1024, 2, 4, 0.25, 64)])
+def test_inputs_that_are_not_16_byte_aligned(pipe, O, I, bits, K, gamma, group):
+    """Every kernel that reads 16 bytes at a time has a path for pointers that do not allow it: input and
+    bias at odd float offsets give the aligned call's result bit for bit (decode, streaming and tiled sizes;
+    the gated two-layer call per layer and as one resident launch)."""
+    torch.manual_seed(O + I)
+    e = pipe.pipe_expand(torch.randn(O, I, device="cuda:0") * 0.02, bits, K, gamma, group)
+    bias = torch.randn(O, device="cuda:0")
+    for T in (1, 3, 16, 17, 130, 300):
+        x = torch.randn(T, I, device="cuda:0")
+        for split in (None, [1, K - 1]):
+            y0 = pipe.pipe_forward(e, x, split=split, bias=bias).clone()
+            y1 = pipe.pipe_forward(e, _off_by_one_float(x), split=split, bias=_off_by_one_float(bias))
+            assert torch.equal(y0, y1), "T=%d split=%s" % (T, split)
+    e.free()
+    H = 384
+    e1 = pipe.pipe_expand(torch.randn(2 * H, I, device="cuda:0") * 0.02, bits, 4, 0.5, group)
+    e2 = pipe.pipe_expand(torch.randn(O, H, device="cuda:0") * 0.02, bits, 4, 0.5, group)
+    try:
+        for T in (1, 5, 16, 200):
+            x = torch.randn(T, I, device="cuda:0")
+            for mode in (0, 2):
+                pipe.pipe_set_decode_resident(mode)
+                y0 = pipe.pipe_mlp_forward(e1, e2, pipe.PIPE_ACT_SILU_GATED, x, split=[2, 2]).clone()
+                y1 = pipe.pipe_mlp_forward(e1, e2, pipe.PIPE_ACT_SILU_GATED, _off_by_one_float(x), split=[2, 2])
+                assert torch.equal(y0, y1), "gated MLP, T=%d, resident mode %d" % (T, mode)
+        assert pipe.pipe_resident_status() == 0
+    finally:
+        pipe.pipe_set_decode_resident(1)
+    e1.free(); e2.free()
