@@ -900,3 +900,22 @@ def test_inputs_that_are_not_16_byte_aligned(pipe, O, I, bits, K, gamma, group):
     finally:
         pipe.pipe_set_decode_resident(1)
     e1.free(); e2.free()
+
+
+@pytest.mark.parametrize("O,I,bits,K,T", [(11008, 4096, 2, 4, 20000), (768, 3072, 4, 3, 70001)])
+def test_token_counts_far_beyond_the_bench_sizes(pipe, O, I, bits, K, T):
+    """A property that holds at any size: with a given activation scale a token's output does not depend on
+    the batch it is in, so one call over T tokens equals, bit for bit, calls over chunks of 4096 tokens (whose
+    tiles the whole-tensor comparisons against the checker cover); and the dynamic scale is max|x|/127."""
+    torch.manual_seed(T)
+    e = pipe.pipe_expand(torch.randn(O, I, device="cuda:0") * 0.02, bits, K, 0.25, 64)
+    x = torch.randn(T, I, device="cuda:0")
+    s_x = float(np.float32(float(x.abs().max())) / np.float32(127.0))
+    for split in (None, [2, K - 2]):
+        y = pipe.pipe_forward(e, x, s_x=s_x, split=split)
+        for t0 in range(0, T, 4096):
+            t1 = min(T, t0 + 4096)
+            yc = pipe.pipe_forward(e, x[t0:t1].contiguous(), s_x=s_x, split=split)
+            assert torch.equal(yc, y[t0:t1]), "tokens %d..%d, split %s" % (t0, t1, split)
+        assert torch.equal(pipe.pipe_forward(e, x, split=split), y)
+    e.free()
