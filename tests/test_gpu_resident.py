@@ -171,3 +171,62 @@ def test_resident_chain_graph_replays(pipe):
         assert torch.equal(out, eager[i]), "replay %d differs" % rep
     for g in gs:
         g.free()
+
+
+def _launches(pipe, fn):
+    """(result of fn(), number of contraction launches it made)."""
+    pipe.pipe_timing_read()
+    pipe.pipe_timing_enable(True)
+    try:
+        out = fn()
+        torch.cuda.synchronize()
+    finally:
+        pipe.pipe_timing_enable(False)
+    return out, pipe.pipe_timing_read()[1]
+
+
+def test_resident_limits_layers_and_descriptor_space(pipe):
+    """At the limits of the resident launch: 16 layers run as one launch, 17 as per-layer launches; a
+    chain whose unit descriptors fill most of a workgroup's table runs resident, one that overflows
+    it falls back.  Same results either way."""
+    torch.manual_seed(3)
+    mk = lambda o, i: pipe.pipe_expand(torch.randn(o, i, device="cuda:0") * (1.5 / i ** 0.5), 4, 2, 1.0, 16)
+    x = torch.randn(4, 96, device="cuda:0")
+    es = [mk(96, 96) for _ in range(17)]
+    for L, want in ((16, 1), (17, 17)):
+        layers = [(e, None, ACT["relu"] if l + 1 < L else ACT["none"], -1, True) for l, e in enumerate(es[:L])]
+        pipe.pipe_set_decode_resident(True)
+        y1, n1 = _launches(pipe, lambda: pipe.pipe_chain_forward(layers, x))
+        assert pipe.pipe_resident_status() == 0 and n1 == want, (L, n1)
+        pipe.pipe_set_decode_resident(False)
+        try:
+            y2, n2 = _launches(pipe, lambda: pipe.pipe_chain_forward(layers, x))
+        finally:
+            pipe.pipe_set_decode_resident(True)
+        assert n2 == L and torch.equal(y1, y2)
+    for e in es:
+        e.free()
+    # 122880 output channels in 4 dense orders: 7680 units, 30 per workgroup on 256 compute units
+    wide, narrow = 122880, 64
+    up = [pipe.pipe_expand(torch.randn(wide, narrow, device="cuda:0") * 0.2, 2, 4, 1.0, 16) for _ in range(3)]
+    down = [pipe.pipe_expand(torch.randn(narrow, wide, device="cuda:0") * 0.004, 2, 4, 1.0, 16) for _ in range(3)]
+    x = torch.randn(2, narrow, device="cuda:0")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for pairs in (2, 3):
+        L = 2 * pairs
+        layers = []
+        for j in range(pairs):
+            layers += [(up[j], None, ACT["relu"], -1, True), (down[j], None, ACT["relu"] if j + 1 < pairs else ACT["none"], -1, True)]
+        ints = pairs * (-(-7680 // cus) * 48 + -(-4 // cus) * 48)
+        pipe.pipe_set_decode_resident(True)
+        y1, n1 = _launches(pipe, lambda: pipe.pipe_chain_forward(layers, x))
+        assert pipe.pipe_resident_status() == 0
+        assert n1 == (1 if ints <= 4096 else L), (pairs, ints, n1)
+        pipe.pipe_set_decode_resident(False)
+        try:
+            y2, n2 = _launches(pipe, lambda: pipe.pipe_chain_forward(layers, x))
+        finally:
+            pipe.pipe_set_decode_resident(True)
+        assert torch.equal(y1, y2)
+    for e in up + down:
+        e.free()
