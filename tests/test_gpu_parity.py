@@ -919,3 +919,30 @@ def test_token_counts_far_beyond_the_bench_sizes(pipe, O, I, bits, K, T):
             assert torch.equal(yc, y[t0:t1]), "tokens %d..%d, split %s" % (t0, t1, split)
         assert torch.equal(pipe.pipe_forward(e, x, split=split), y)
     e.free()
+
+
+def test_empty_batches_through_every_forward_call(pipe):
+    """No tokens: every forward entry point returns empty outputs without an error, and the next call
+    with tokens is unaffected."""
+    d = "cuda:0"
+    torch.manual_seed(1)
+    e1 = pipe.pipe_expand(torch.randn(256, 128, device=d) * 0.1, 4, 3, 0.5, 16)
+    e2 = pipe.pipe_expand(torch.randn(64, 128, device=d) * 0.1, 4, 3, 0.5, 16)
+    eg = pipe.pipe_expand(torch.randn(128, 256, device=d) * 0.1, 4, 3, 0.5, 16)
+    x3 = torch.randn(3, 128, device=d)
+    before = pipe.pipe_forward(e1, x3).clone()
+    x0 = torch.empty((0, 128), device=d)
+    assert pipe.pipe_forward(e1, x0).shape == (0, 256)
+    assert pipe.pipe_forward(e1, x0, split=[1, 2], reduce_members=False).shape == (2, 0, 256)
+    assert pipe.pipe_forward_acc(e1, x0)[0].shape == (3, 0, 256)
+    assert pipe.pipe_forward_asymmetric(e1, x0).shape == (0, 256)
+    y, h = pipe.pipe_mlp_forward(e1, e2, pipe.PIPE_ACT_SILU_GATED, x0, split=[2, 1], return_hidden=True)
+    assert y.shape == (0, 64) and h.shape == (2, 0, 128)
+    assert pipe.pipe_mlp_forward(eg, e2, pipe.PIPE_ACT_GELU, torch.empty((0, 256), device=d)).shape == (0, 64)
+    chain = [(e1, None, 3, -1, True), (eg, None, 0, -1, True)]
+    assert pipe.pipe_chain_forward(chain, x0).shape == (0, 128)
+    assert pipe.pipe_chain_forward_asymmetric(chain, x0).shape == (0, 128)
+    torch.cuda.synchronize()
+    assert torch.equal(pipe.pipe_forward(e1, x3), before)
+    for e in (e1, e2, eg):
+        e.free()
